@@ -1,0 +1,186 @@
+#!/usr/bin/env python3
+"""Benchmark of the LAVa prefill-end eviction path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4|cfg2|cfg1]
+
+One step = the whole hot path for one layer of one sequence, inputs resident in HBM:
+lava_window_scores (value norms, window softmax statistics, window scores, pooling + layer
+statistic) -> lava_layer_budgets (on device) -> lava_select_topk (budget read on device) ->
+lava_compact_kv.  Steps rotate over several distinct K/V buffer sets so that no step can be
+served from the 256 MB Infinity Cache by the previous one.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
+
+
+def parse():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="cfg4", choices=["cfg1", "cfg2", "cfg4"])
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--sets", type=int, default=0, help="distinct K/V buffer sets (0 = enough for >= 1.5 GiB)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-check", action="store_true")
+    return ap.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              f"--gpus {args.gpus} is not supported. Re-run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+
+    from paper_2509_09754_amd import lava, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(2)
+    torch.cuda.set_device(0)
+    dev = torch.device("cuda:0")
+
+    cfg_idx = {"cfg1": 1, "cfg2": 2, "cfg4": 4}[args.workload]
+    sh = synth.config(cfg_idx)
+    esize = synth.itemsize(sh.dtype)
+    inp = synth.gen_layer(sh, args.seed)
+    desc = lava.LayerDesc.make(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.window, sh.dtype, pool_kernel=sh.pool_kernel)
+    kv_bytes = sh.n_kv_heads * sh.n * sh.head_dim * esize           # one of K or V
+    n_sets = args.sets if args.sets > 0 else max(2, int(np.ceil(1.5 * 2**30 / (2 * kv_bytes))))
+    n_sets = min(n_sets, 64)
+
+    q0, k0, v0 = (lava.to_device(a, sh.dtype, dev) for a in (inp.q_win, inp.k, inp.v))
+    sets = [(q0, k0, v0)] + [(q0.clone(), k0.clone(), v0.clone()) for _ in range(n_sets - 1)]
+
+    total_entries = sh.n_kv_heads * sh.n
+    B = sh.budget
+    ws_scores = torch.empty(lava.lava_window_scores_workspace_bytes(desc, 1, sh.n), dtype=torch.uint8, device=dev)
+    ws_sel = torch.empty(lava.lava_select_workspace_bytes(total_entries), dtype=torch.uint8, device=dev)
+    scores = torch.empty(total_entries, dtype=torch.float32, device=dev)
+    vbar = torch.empty(1, sh.n_kv_heads, dtype=torch.float32, device=dev)
+    stat = torch.empty(1, dtype=torch.float32, device=dev)
+    budgets = torch.empty(1, 1, dtype=torch.int64, device=dev)
+    total_b = torch.tensor([B], dtype=torch.int64, device=dev)
+    lo = torch.tensor([[sh.n_kv_heads * sh.window]], dtype=torch.int64, device=dev)
+    hi = torch.tensor([[total_entries]], dtype=torch.int64, device=dev)
+    counts = torch.empty(sh.n_kv_heads, dtype=torch.int32, device=dev)
+    offs = torch.empty(sh.n_kv_heads + 1, dtype=torch.int64, device=dev)
+    idx = torch.empty(B, dtype=torch.int32, device=dev)
+    kept_s = torch.empty(B, dtype=torch.float32, device=dev)
+    k_hat = torch.empty(B, sh.head_dim, dtype=desc.torch_dtype, device=dev)
+    v_hat = torch.empty(B, sh.head_dim, dtype=desc.torch_dtype, device=dev)
+    lens = [sh.n]
+
+    def step(i):
+        q, k, v = sets[i % n_sets]
+        lava.lava_window_scores(desc, lens, q, k, v, scores=scores, vbar=vbar, layer_stat=stat, workspace=ws_scores)
+        lava.lava_layer_budgets(stat.view(1, 1), total_b, lo, hi, budgets=budgets)
+        lava.lava_select_topk(sh.n_kv_heads, scores, B, budget_dev=budgets.view(-1), head_counts=counts,
+                              head_offsets=offs, kept_idx=idx, kept_scores=kept_s, workspace=ws_sel)
+        lava.lava_compact_kv(desc, sh.n, k, v, offs, idx, B, k_out=k_hat, v_out=v_hat)
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    ms_per_step = 1e3 * elapsed / args.steps
+    tokens_per_s = sh.n / (elapsed / args.steps)
+
+    # ---- per-kernel durations over an identical loop, HIP events on the launch stream
+    lava.prof_enable(True)
+    lava.prof_reset()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    prof = lava.prof_read()
+    lava.prof_enable(False)
+    per_kernel_us = {name: 1e3 * ms / max(cnt, 1) for name, (ms, cnt) in prof.items() if cnt}
+
+    # algorithmic bytes of each sweep kernel per launch (bytes it must move given its inputs/outputs)
+    q_bytes = sh.n_q_heads * sh.window * sh.head_dim * esize
+    sraw_bytes = 4 * sh.n_kv_heads * sh.n_prefix
+    alg_bytes = {
+        "vnorm": kv_bytes,
+        "stats": kv_bytes + q_bytes,
+        "scores": kv_bytes + q_bytes + sraw_bytes,
+        "poolstat": sraw_bytes + 4 * total_entries,
+        "compact": 4 * B * sh.head_dim * esize,
+    }
+    dominant = max(per_kernel_us, key=per_kernel_us.get)
+    dom_bytes = alg_bytes.get(dominant, 0)
+    achieved = dom_bytes / (per_kernel_us[dominant] * 1e-6) / 1e9 if dom_bytes else 0.0
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "kernel_us": round(per_kernel_us[dominant], 2), "algorithmic_bytes": dom_bytes}
+    # whole-path view: K once + V once + scores + kept rows, over the whole step
+    path_bytes = 2 * kv_bytes + q_bytes + 5 * 4 * total_entries + 4 * B * sh.head_dim * esize
+    path_gbs = path_bytes / (elapsed / args.steps) / 1e9
+
+    out = {
+        "metric": "cached tokens evicted-and-compacted/sec per layer; achieved HBM GB/s vs peak",
+        "value": round(tokens_per_s, 1), "unit": "tokens/s/layer", "n_gpus": 1, "steps": args.steps,
+        "warmup": args.warmup, "ms_per_step": round(ms_per_step, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": sh.dtype, "data": "synthetic",
+        "config": {"workload": f"{args.workload}: one layer, {sh.n_q_heads}q/{sh.n_kv_heads}kv heads, d_h {sh.head_dim}, "
+                               f"N={sh.n}, w={sh.window}, B_l={B}, {sh.dtype}, batch 1",
+                   "kv_buffer_sets": n_sets},
+        "roofline": roofline,
+        "path": {"algorithmic_bytes": path_bytes, "achieved_GBs": round(path_gbs, 1),
+                 "frac_of_hbm_peak": round(path_gbs / HBM_PEAK_GBS, 4)},
+        "kernels_us": {k: round(v, 2) for k, v in per_kernel_us.items()},
+    }
+
+    if not args.no_check or not args.no_cpu_baseline:
+        from oracle import lava_oracle as O
+        try:
+            from threadpoolctl import threadpool_limits
+        except Exception:                                       # pragma: no cover
+            threadpool_limits = None
+        q, k, v = inp.f64()
+        t0 = time.perf_counter()
+        if threadpool_limits is not None:
+            with threadpool_limits(limits=1):
+                ref = O.layer_evict(q, k, v, sh.window, B, sh.pool_kernel, k_store=inp.k, v_store=inp.v)
+        else:
+            ref = O.layer_evict(q, k, v, sh.window, B, sh.pool_kernel, k_store=inp.k, v_store=inp.v)
+        cpu_s = time.perf_counter() - t0
+        out["cpu_baseline"] = {"value": round(sh.n / cpu_s, 1), "unit": "tokens/s/layer",
+                               "cores": 1 if threadpool_limits is not None else os.cpu_count(),
+                               "kind": "oracle",
+                               "sample": f"one full layer of the workload (N={sh.n}), one run, {cpu_s:.2f} s",
+                               "host_cores_available": os.cpu_count()}
+        # parity of the timed configuration against the oracle (outside the timed region)
+        step(0)
+        torch.cuda.synchronize()
+        c, o, ii = counts.cpu().numpy(), offs.cpu().numpy(), idx.cpu().numpy()
+        mine = {(g, int(p)) for g in range(sh.n_kv_heads) for p in ii[o[g]:o[g + 1]]}
+        theirs = {(g, int(p)) for g in range(sh.n_kv_heads)
+                  for p in ref["kept_idx"][ref["head_offsets"][g]:ref["head_offsets"][g + 1]]}
+        got = scores.cpu().numpy().reshape(sh.n_kv_heads, sh.n)[:, : sh.n_prefix].astype(np.float64)
+        want = ref["scores"][:, : sh.n_prefix]
+        mask = want > 1e-30 * want.max()
+        out["parity"] = {"kept_overlap": round(len(mine & theirs) / B, 6),
+                         "score_max_rel_err": float(np.max(np.abs(got[mask] - want[mask]) / want[mask]))}
+
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,175 @@
+/*
+ * lava.h — C ABI of the MI355X (gfx950) implementation of LAVa's prefill-end KV-cache
+ * eviction path (arXiv 2509.09754).
+ *
+ * For one transformer layer the path is, in order:
+ *   lava_window_scores   attention of the last w queries against every cached key, reduced to
+ *                        the pooled, head-comparable LAVa score of every cache entry, plus the
+ *                        layer's normalised-entropy statistic          (Def. 1 / Eq. 3, Sec. 4.3,
+ *                                                                       Sec. 5.1 pooling, Eq. 4-5)
+ *   lava_layer_budgets   dynamic layer budgets from the statistics of the layers seen so far
+ *                                                                      (Alg. 2, inner loop)
+ *   lava_select_topk     one top-B selection over the flattened heads of the layer; the number
+ *                        of survivors per head is the dynamic head budget   (Alg. 1, Sec. 4.1)
+ *   lava_compact_kv      packs the surviving K/V rows per head              (Alg. 1, last loop)
+ *
+ * Conventions common to all calls
+ *   - "device" pointers are HIP device memory of the current device, "host" pointers are
+ *     ordinary host memory.  The library never allocates, frees or keeps any buffer; the
+ *     caller owns everything, including the workspace.  Outputs must not alias inputs.
+ *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = default stream)
+ *     and the call returns without synchronising, unless stated otherwise.
+ *   - All argument checks happen on the host before anything is launched; a call that returns
+ *     an error has launched nothing.  Errors are reported by return code only.
+ *   - Layouts are row-major with the last index fastest.  K and V are head-major per layer as
+ *     in the paper's layer-wise view (App. A): [H_kv][N][d_h].
+ *   - Notation: H query heads, H_kv KV heads, G = H / H_kv (query head h reads KV head
+ *     h / G), d_h head dimension, N cached tokens, w window, N' = N - w prefix length.
+ */
+#ifndef LAVA_H
+#define LAVA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+  LAVA_OK = 0,
+  LAVA_ERR_INVALID_ARG = 1, /* null pointer, negative count, unknown enum value            */
+  LAVA_ERR_SHAPE = 2,       /* a shape the kernels are not built for (see lava_layer_desc) */
+  LAVA_ERR_BUDGET = 3,      /* budget outside its feasible range                           */
+  LAVA_ERR_WORKSPACE = 4,   /* workspace missing, misaligned (256 B) or too small          */
+  LAVA_ERR_HIP = 5          /* a HIP runtime call or kernel launch failed                  */
+} lava_status;
+
+typedef enum { LAVA_F32 = 0, LAVA_BF16 = 1 } lava_dtype;
+
+/* One layer of one model.  Plain data, read during the call only. */
+typedef struct lava_layer_desc {
+  int32_t n_q_heads;    /* H                                                                  */
+  int32_t n_kv_heads;   /* H_kv; H % H_kv == 0 and G = H / H_kv <= 8                          */
+  int32_t head_dim;     /* d_h: 64 or 128                                                     */
+  int32_t window;       /* w, 1 <= w <= 32: number of observation-window query rows           */
+  int32_t pool_kernel;  /* odd, 1..15; the paper uses 7 (Sec. 5.1); 1 disables pooling        */
+  int32_t dtype;        /* lava_dtype of q_win, k, v, k_out, v_out                            */
+  float softmax_scale;  /* logits are scale * <q, k>; 0 selects 1 / sqrt(d_h) (Sec. 2)        */
+} lava_layer_desc;
+
+const char* lava_status_string(int32_t status);
+
+/* Bytes of device workspace lava_window_scores needs for `batch` sequences holding
+ * `total_tokens` cached tokens in all.  Returns 0 for an invalid descriptor. */
+size_t lava_window_scores_workspace_bytes(const lava_layer_desc* desc, int32_t batch,
+                                          int64_t total_tokens);
+
+/*
+ * Scores of every cache entry of one layer (Def. 1 / Eq. 3; GQA group-max, Sec. 4.3; max-pool,
+ * Sec. 5.1) and the layer statistic e_l (Eq. 4-5).
+ *
+ *   seq_lens   host  [batch]            N_b > w for every sequence
+ *   q_win      device [batch][H][w][d_h]      queries of the last w positions, row r is the
+ *                                             query at position N_b - w + r
+ *   k, v       device, sequences packed back to back; sequence b starts at element
+ *              H_kv * d_h * sum_{b' < b} N_b' and is laid out [H_kv][N_b][d_h]
+ *   lse        device [batch][H][w] or NULL   natural-log log-sum-exp of each window row's
+ *                                             logits over keys 0..N_b-w+r, if the prefill
+ *                                             attention kept it; skips the statistics pass
+ *   scores     device, float, packed like k without the d_h axis: [H_kv][N_b] per sequence.
+ *              Prefix entries hold the pooled group score; the w window entries of each head
+ *              hold +inf (they are always retained, Eq. 1)
+ *   vbar       device [batch][H_kv] float     max_k ||V[k]||_1 over all N_b rows (Thm. 1)
+ *   layer_stat device [batch] float           e_l of Eq. 5 over the H_kv * N' prefix scores
+ *
+ * Each window row is normalised over all keys up to and including its own position.
+ * Results are deterministic (no floating-point atomics).  Scores carry fp32 accumulation
+ * error only (inputs are used exactly as stored).
+ */
+int32_t lava_window_scores(const lava_layer_desc* desc, int32_t batch, const int64_t* seq_lens,
+                           const void* q_win, const void* k, const void* v, const float* lse,
+                           float* scores, float* vbar, float* layer_stat, void* workspace,
+                           size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Layer budgets B_l = e_l / sum_l e_l * total (Alg. 2, inner loop) as integers.
+ *
+ *   e          [batch][n_layers] float   statistics of the layers prefilled so far
+ *   total      [batch] int64             total budget of each sequence
+ *   lo, hi     [batch][n_layers] int64   bounds of each layer's budget (H_kv * w and the
+ *                                        number of entries the layer still holds)
+ *   budgets    [batch][n_layers] int64   out; sums to total[b], lo <= B <= hi
+ *
+ * Rounding: real quotas are floored and the leftover units go to the largest fractional parts
+ * (lower layer first on ties); layers that violate a bound are pinned to it and the remainder
+ * is split again among the others.  All-zero statistics give a uniform split.
+ *
+ * on_device == 0: every pointer is host memory; pure host arithmetic, synchronous, the stream
+ * is ignored; infeasible bounds (sum lo > total or sum hi < total) return LAVA_ERR_BUDGET.
+ * on_device != 0: every pointer is device memory; one small kernel on the stream; a sequence
+ * with infeasible bounds gets all budgets = -1.  n_layers <= 1024.
+ * Calling it with n_layers = 1, 2, ... reproduces the cascade of Alg. 2.
+ */
+int32_t lava_layer_budgets(int32_t batch, int32_t n_layers, const float* e, const int64_t* total,
+                           const int64_t* lo, const int64_t* hi, int64_t* budgets,
+                           int32_t on_device, void* hip_stream);
+
+/* Bytes of device workspace lava_select_topk needs for `total_entries` scores. */
+size_t lava_select_workspace_bytes(int64_t total_entries);
+
+/*
+ * Top-`budget` selection over the concatenated per-head score segments of a layer (Alg. 1,
+ * "B_l largest entries based on s_l").  An entry precedes another if its score is larger, or
+ * the scores are equal and its flat index is smaller; the first `budget` entries survive.
+ *
+ *   scores        device float [total_entries], heads concatenated.  No NaN; -0 == +0.
+ *   seg_offsets   device int64 [n_heads + 1] segment starts (seg_offsets[n_heads] ==
+ *                 total_entries), or NULL for equal segments of total_entries / n_heads
+ *   budget        entries to keep, 0 <= budget <= total_entries; when budget_dev != NULL the
+ *                 value is read on the device from *budget_dev instead (clamped to
+ *                 [0, min(budget, total_entries)]) and `budget` is the capacity of the outputs
+ *   head_counts   device int32 [n_heads]      survivors per head (the dynamic head budget)
+ *   head_offsets  device int64 [n_heads + 1]  exclusive prefix sums of head_counts
+ *   kept_idx      device int32 [budget]       position of each survivor inside its head,
+ *                                             ascending per head, heads concatenated
+ *   kept_scores   device float [budget] or NULL   the survivors' scores, same order (what a
+ *                                             later re-selection with a smaller budget needs)
+ * Integer-exact and deterministic.  n_heads <= 64, total_entries < 2^31.
+ */
+int32_t lava_select_topk(int32_t n_heads, const float* scores, const int64_t* seg_offsets,
+                         int64_t total_entries, int64_t budget, const int64_t* budget_dev,
+                         int32_t* head_counts, int64_t* head_offsets, int32_t* kept_idx,
+                         float* kept_scores, void* workspace, size_t workspace_bytes,
+                         void* hip_stream);
+
+/*
+ * Packed surviving rows (Alg. 1: K^ = K (.) I, V^ = V (.) I, stored without the evicted rows):
+ *   k_out[head_offsets[g] + t][:] = k[g][kept_idx[head_offsets[g] + t]][:], same for v.
+ *
+ *   k, v          device [H_kv][n][d_h]   one sequence's layer cache
+ *   head_offsets  device int64 [H_kv + 1], kept_idx device int32 [>= head_offsets[H_kv]]
+ *   capacity      rows available in k_out / v_out; rows beyond head_offsets[H_kv] are left
+ *                 untouched, and no more than `capacity` rows are ever written
+ *   k_out, v_out  device [capacity][d_h], dtype of the descriptor; bit copies of the rows
+ */
+int32_t lava_compact_kv(const lava_layer_desc* desc, int64_t n, const void* k, const void* v,
+                        const int64_t* head_offsets, const int32_t* kept_idx, int64_t capacity,
+                        void* k_out, void* v_out, void* hip_stream);
+
+/*
+ * Per-kernel timing for benchmarks.  When enabled, every kernel the library launches is
+ * bracketed by HIP events on the stream it is launched on.  lava_prof_read synchronises the
+ * device and returns the accumulated time of kernel `id` since the last reset.  Kernel ids run
+ * from 0 to lava_prof_kernel_count() - 1.  Not thread-safe; leave disabled in production.
+ */
+int32_t lava_prof_kernel_count(void);
+const char* lava_prof_kernel_name(int32_t id);
+int32_t lava_prof_enable(int32_t on);
+int32_t lava_prof_reset(void);
+int32_t lava_prof_read(int32_t id, double* total_ms, int64_t* launches);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* LAVA_H */

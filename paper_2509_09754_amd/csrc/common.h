@@ -1,0 +1,109 @@
+// Shared declarations of the HIP library: kernel launchers, the per-kernel timing hook and a
+// few device helpers.  gfx950 only.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "../../include/lava.h"
+
+namespace lava {
+
+// ---------------------------------------------------------------- kernel ids (timing hook)
+enum KernelId : int {
+  KID_VNORM = 0,      // value-row L1 norms, per-block maxima
+  KID_STATS,          // window softmax statistics (row max, row sum) per block
+  KID_SCORES,         // window scores: group-max of window-mean attention
+  KID_POOLSTAT,       // max-pool, value factor, +inf window entries, entropy statistic
+  KID_SEL_INIT,       // selection: clear histograms and counters
+  KID_SEL_HIST,       // selection: radix histogram pass + digit pick
+  KID_SEL_COUNT,      // selection: per-block survivor counts + scan
+  KID_SEL_WRITE,      // selection: ordered write of survivors
+  KID_COMPACT,        // K/V row gather
+  KID_BUDGETS,        // layer budgets on the device
+  KID_COUNT
+};
+
+// Brackets a launch with events when timing is enabled (no-ops otherwise).
+void prof_begin(int kid, hipStream_t s);
+void prof_end(int kid, hipStream_t s);
+
+struct ProfScope {
+  int kid;
+  hipStream_t s;
+  ProfScope(int k, hipStream_t st) : kid(k), s(st) { prof_begin(kid, s); }
+  ~ProfScope() { prof_end(kid, s); }
+};
+
+inline int32_t hip_ok(hipError_t e) { return e == hipSuccess ? LAVA_OK : LAVA_ERR_HIP; }
+inline int32_t launch_status() { return hip_ok(hipGetLastError()); }
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
+
+// ---------------------------------------------------------------- sweep (K, V) kernels
+constexpr int kTileKeys = 32;        // keys per MFMA tile
+constexpr int kSweepThreads = 256;   // 4 wavefronts per workgroup
+constexpr int kMaxChunkHeads = 4;    // query heads a wavefront keeps in registers
+
+struct SweepPlan {
+  int chunk_heads;     // GT: heads per chunk (<= kMaxChunkHeads; <= 2 for f32 with d_h 128)
+  int n_chunks;        // ceil(G / GT)
+  int blocks_x;        // workgroups along the key axis per (KV head, chunk)
+  int tiles_per_block; // key tiles per workgroup
+  int vnorm_blocks;    // workgroups per KV head of the value-norm kernel
+};
+SweepPlan make_sweep_plan(const lava_layer_desc& d, int64_t n);
+
+// Workspace of lava_window_scores for one sequence (all offsets 256-byte aligned).
+struct ScoreWorkspace {
+  size_t off_stat_part;   // float2 [H_kv*n_chunks][blocks_x][GT*32]  (row max, row sum)
+  size_t off_vnorm_part;  // float  [H_kv][vnorm_blocks]
+  size_t off_sraw;        // float  [H_kv][N']  group-max of window-mean attention
+  size_t off_ent_part;    // double2[pool blocks]  partial (S, T)
+  size_t off_counter;     // uint32 [8]
+  size_t bytes;
+};
+ScoreWorkspace make_score_workspace(const lava_layer_desc& d, int64_t n);
+int pool_blocks(const lava_layer_desc& d, int64_t n);
+
+int32_t launch_vnorm(const lava_layer_desc& d, int64_t n, const void* v, float* vnorm_part,
+                     uint32_t* counters, const SweepPlan& p, hipStream_t s);
+int32_t launch_stats(const lava_layer_desc& d, int64_t n, const void* q_win, const void* k,
+                     float2* stat_part, const SweepPlan& p, hipStream_t s);
+int32_t launch_scores(const lava_layer_desc& d, int64_t n, const void* q_win, const void* k,
+                      const float2* stat_part, const float* lse, float* s_raw, const SweepPlan& p,
+                      hipStream_t s);
+int32_t launch_poolstat(const lava_layer_desc& d, int64_t n, const float* s_raw,
+                        const float* vnorm_part, int vnorm_blocks, float* scores, float* vbar,
+                        float* layer_stat, double2* ent_part, uint32_t* counters, hipStream_t s);
+
+// ---------------------------------------------------------------- selection / compaction
+struct SelectWorkspace {
+  size_t off_hist;      // uint32 [3][2048]
+  size_t off_state;     // SelectState
+  size_t off_blk;       // uint32 [4][n_blocks]: gt, eq, out_off, eq_prefix
+  int n_blocks;
+  size_t bytes;
+};
+SelectWorkspace make_select_workspace(int64_t total);
+
+int32_t launch_select(int n_heads, const float* scores, const int64_t* seg_offsets, int64_t total,
+                      int64_t budget, const int64_t* budget_dev, int32_t* head_counts,
+                      int64_t* head_offsets, int32_t* kept_idx, float* kept_scores, void* ws,
+                      hipStream_t s);
+
+int32_t launch_compact(const lava_layer_desc& d, int64_t n, const void* k, const void* v,
+                       const int64_t* head_offsets, const int32_t* kept_idx, int64_t capacity,
+                       void* k_out, void* v_out, hipStream_t s);
+
+// ---------------------------------------------------------------- layer budgets
+// Sequential allocation shared by the host path and the device kernel (one thread per
+// sequence) so both give bit-identical integers.  scratch: 3 * n_layers doubles.
+int32_t budgets_host(int32_t batch, int32_t n_layers, const float* e, const int64_t* total,
+                     const int64_t* lo, const int64_t* hi, int64_t* out);
+int32_t launch_budgets(int32_t batch, int32_t n_layers, const float* e, const int64_t* total,
+                       const int64_t* lo, const int64_t* hi, int64_t* out, hipStream_t s);
+
+}  // namespace lava

@@ -1,0 +1,620 @@
+// The three sweeps over a layer's cache (Def. 1 / Eq. 3 with the attention rows of Sec. 2):
+//
+//   vnorm   V once:  per-row L1 norms, per-workgroup maxima                 -> Vbar (Thm. 1)
+//   stats   K once:  logits of the w window rows against every key on the matrix cores, online
+//                    row max / row sum per workgroup                        -> softmax normaliser
+//   scores  K again: the same logits, exp2 against the merged normaliser, mean over the window
+//                    rows, max over the query heads of the KV group (Sec. 4.3)
+//
+// The window product is the one dense contraction of the path: per KV head a
+// [G*w] x d_h x N GEMM.  Each wavefront owns 32-key tiles: the tile is read from HBM with fully
+// coalesced 128-bit loads, staged through a wavefront-private, XOR-swizzled LDS buffer into MFMA
+// operand layout, and multiplied against the group's query rows, which stay in registers for the
+// whole sweep.  No workgroup barrier is needed inside the sweep.
+//
+// MFMA 32x32 layouts used below (wave64): operand lane l supplies row/column l%32 and k-slice
+// l/32; result register v of lane l is element (8*(v/4) + 4*(l/32) + v%4, l%32).
+//   stats  : D = K_tile * Q^T  -> a lane holds 16 keys of ONE query row: row reductions stay in-lane
+//   scores : D = Q * K_tile^T  -> a lane holds 16 query rows of ONE key: the window mean stays in-lane
+#include <math.h>
+
+#include "common.h"
+
+namespace lava {
+
+typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
+typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // 16 bytes held in registers
+
+constexpr float kLog2e = 1.4426950408889634f;
+
+template <int DT> struct Elem;
+template <> struct Elem<LAVA_BF16> { static constexpr int kBytes = 2; };
+template <> struct Elem<LAVA_F32> { static constexpr int kBytes = 4; };
+
+// acc += A(16 bytes of k) x B(16 bytes of k).  Both operands use the same lane -> k mapping, so
+// any fixed assignment of a row's elements to (step, lane half) gives the full dot product.
+template <int DT>
+__device__ __forceinline__ f32x16 mfma_chunk(const u32x4& a, const u32x4& b, f32x16 acc) {
+  if constexpr (DT == LAVA_BF16) {
+    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
+                                                   __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
+  } else {
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
+    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
+    return acc;
+  }
+}
+
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+
+// Ordering point between LDS writes and reads of one wavefront (its LDS traffic is in order;
+// this only stops the compiler from moving accesses across it).
+__device__ __forceinline__ void wave_lds_sync() {
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+  __builtin_amdgcn_wave_barrier();
+  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// (m1, z1) (+) (m2, z2) for sums of exp2((x - m) * c2); empty sets are (-inf, 0).
+__device__ __forceinline__ void merge_stat(float& m, float& z, float m2, float z2, float c2) {
+  const float mn = fmaxf(m, m2);
+  const float f1 = (m == mn) ? 1.0f : fast_exp2((m - mn) * c2);
+  const float f2 = (m2 == mn) ? 1.0f : fast_exp2((m2 - mn) * c2);
+  z = z * f1 + z2 * f2;
+  m = mn;
+}
+
+template <int DT, int D>
+struct Tile {
+  static constexpr int kRowBytes = D * Elem<DT>::kBytes;
+  static constexpr int kCpr = kRowBytes / 16;          // 16-byte chunks per row
+  static constexpr int kSteps = kCpr / 2;              // chunk steps (two lane halves per step)
+  static constexpr int kLoads = kTileKeys * kCpr / 64; // 128-bit loads per lane per tile
+  static constexpr int kTileChunks = kTileKeys * kCpr;
+};
+
+// Coalesced read of one 32-key tile (rows beyond n are clamped to the last row; callers mask).
+template <int DT, int D>
+__device__ __forceinline__ void load_tile(const u32x4* __restrict__ kg, long long tile, long long n,
+                                          int lane, u32x4 (&stage)[Tile<DT, D>::kLoads]) {
+  using T = Tile<DT, D>;
+#pragma unroll
+  for (int i = 0; i < T::kLoads; ++i) {
+    const int q = i * 64 + lane;
+    long long key = tile * kTileKeys + q / T::kCpr;
+    key = key < n ? key : n - 1;
+    stage[i] = kg[key * T::kCpr + (q % T::kCpr)];
+  }
+}
+
+template <int DT, int D>
+__device__ __forceinline__ void stage_to_lds(u32x4* __restrict__ buf, int lane,
+                                             const u32x4 (&stage)[Tile<DT, D>::kLoads]) {
+  using T = Tile<DT, D>;
+#pragma unroll
+  for (int i = 0; i < T::kLoads; ++i) {
+    const int q = i * 64 + lane;
+    const int row = q / T::kCpr, c = q % T::kCpr;
+    buf[row * T::kCpr + (c ^ (row & 7))] = stage[i];
+  }
+}
+
+template <int DT, int D>
+__device__ __forceinline__ void lds_to_frag(const u32x4* __restrict__ buf, int lane,
+                                            u32x4 (&frag)[Tile<DT, D>::kSteps]) {
+  using T = Tile<DT, D>;
+  const int row = lane & 31, half = lane >> 5;
+#pragma unroll
+  for (int j = 0; j < T::kSteps; ++j) {
+    const int c = 2 * j + half;
+    frag[j] = buf[row * T::kCpr + (c ^ (row & 7))];
+  }
+}
+
+// Query fragments of the chunk's heads: row r = lane % 32 (zero beyond the window or the chunk).
+template <int DT, int D, int GT>
+__device__ __forceinline__ void load_q(const u32x4* __restrict__ qg, int h0, int nh, int w, int lane,
+                                       u32x4 (&qf)[GT][Tile<DT, D>::kSteps]) {
+  using T = Tile<DT, D>;
+  const int r = lane & 31, half = lane >> 5;
+#pragma unroll
+  for (int t = 0; t < GT; ++t) {
+#pragma unroll
+    for (int j = 0; j < T::kSteps; ++j) {
+      u32x4 x = u32x4{0u, 0u, 0u, 0u};
+      if (t < nh && r < w) x = qg[((long long)(h0 + t) * w + r) * T::kCpr + 2 * j + half];
+      qf[t][j] = x;
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// stats: per workgroup and per (head of the chunk, window row) the running maximum of the raw
+// dot products and sum of exp2((dot - max) * c2) over the workgroup's keys, c2 = scale * log2 e.
+// Row r may see keys 0 .. n - w + r only (each window row is normalised over the keys up to
+// and including its own position).
+// ------------------------------------------------------------------------------------------
+template <int DT, int D, int GT>
+__global__ void __launch_bounds__(kSweepThreads)
+stats_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long long n, int w, int G,
+             int n_chunks, float c2, int tiles_per_block, float2* __restrict__ stat_part) {
+  using T = Tile<DT, D>;
+  __shared__ u32x4 s_tile[kSweepThreads / 64][T::kTileChunks];
+  __shared__ float2 s_red[kSweepThreads / 64][GT * 32];
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int g = blockIdx.y / n_chunks, chunk = blockIdx.y % n_chunks;
+  const int h0 = g * G + chunk * GT;
+  const int nh = (G - chunk * GT) < GT ? (G - chunk * GT) : GT;
+  const u32x4* kg = k + (long long)g * n * T::kCpr;
+
+  u32x4 qf[GT][T::kSteps];
+  load_q<DT, D, GT>(q_win, h0, nh, w, lane, qf);
+
+  const long long n_tiles = (n + kTileKeys - 1) / kTileKeys;
+  const long long t_begin = (long long)blockIdx.x * tiles_per_block;
+  long long t_end = t_begin + tiles_per_block;
+  if (t_end > n_tiles) t_end = n_tiles;
+
+  float m_run[GT], z_run[GT];
+#pragma unroll
+  for (int t = 0; t < GT; ++t) { m_run[t] = -INFINITY; z_run[t] = 0.0f; }
+
+  const int r = lane & 31, half = lane >> 5;
+  long long last_visible = n - w + r;           // last key row r may see
+  if (last_visible > n - 1) last_visible = n - 1;
+
+  u32x4 stage[T::kLoads];
+  long long tile = t_begin + wave;
+  if (tile < t_end) load_tile<DT, D>(kg, tile, n, lane, stage);
+  u32x4* buf = s_tile[wave];
+  for (; tile < t_end; tile += kSweepThreads / 64) {
+    stage_to_lds<DT, D>(buf, lane, stage);
+    const long long next = tile + kSweepThreads / 64;
+    if (next < t_end) load_tile<DT, D>(kg, next, n, lane, stage);
+    wave_lds_sync();
+    u32x4 kf[T::kSteps];
+    lds_to_frag<DT, D>(buf, lane, kf);
+    wave_lds_sync();
+
+    const long long key0 = tile * kTileKeys;
+    const bool late = key0 + kTileKeys - 1 > n - w;   // some row cannot see some key of this tile
+#pragma unroll
+    for (int t = 0; t < GT; ++t) {
+      f32x16 acc = {0};
+#pragma unroll
+      for (int j = 0; j < T::kSteps; ++j) acc = mfma_chunk<DT>(kf[j], qf[t][j], acc);
+      if (late) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const long long key = key0 + 8 * (v / 4) + 4 * half + (v % 4);
+          if (key > last_visible) acc[v] = -INFINITY;
+        }
+      }
+      float tmax = acc[0];
+#pragma unroll
+      for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, acc[v]);
+      if (tmax > -INFINITY) {
+        const float mn = fmaxf(m_run[t], tmax);
+        const float mc = mn * c2;
+        float zs = 0.0f;
+#pragma unroll
+        for (int v = 0; v < 16; ++v) zs += fast_exp2(fmaf(acc[v], c2, -mc));
+        const float f = (m_run[t] == mn) ? 1.0f : fast_exp2((m_run[t] - mn) * c2);
+        z_run[t] = z_run[t] * f + zs;
+        m_run[t] = mn;
+      }
+    }
+  }
+
+  // merge the two lane halves (same row, different keys), then the four wavefronts
+#pragma unroll
+  for (int t = 0; t < GT; ++t) {
+    const float m2 = __shfl_xor(m_run[t], 32);
+    const float z2 = __shfl_xor(z_run[t], 32);
+    merge_stat(m_run[t], z_run[t], m2, z2, c2);
+    if (half == 0) s_red[wave][t * 32 + r] = make_float2(m_run[t], z_run[t]);
+  }
+  __syncthreads();
+  if (threadIdx.x < GT * 32) {
+    float m = -INFINITY, z = 0.0f;
+#pragma unroll
+    for (int wv = 0; wv < kSweepThreads / 64; ++wv) {
+      const float2 p = s_red[wv][threadIdx.x];
+      merge_stat(m, z, p.x, p.y, c2);
+    }
+    stat_part[((long long)blockIdx.y * gridDim.x + blockIdx.x) * (GT * 32) + threadIdx.x] =
+        make_float2(m, z);
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// scores: s_raw[g, i] = max over the heads h of group g of (1/w) sum_r softmax_r[h, i], i < n'.
+// The normaliser of each (head, row) is merged from the stats partials by every workgroup in the
+// same fixed order (deterministic), or taken from a caller-supplied log-sum-exp.
+// ------------------------------------------------------------------------------------------
+template <int DT, int D, int GT>
+__global__ void __launch_bounds__(kSweepThreads)
+scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long long n, int w, int G,
+              int n_chunks, float c2, int tiles_per_block, const float2* __restrict__ stat_part,
+              int stat_blocks, const float* __restrict__ lse, float* __restrict__ s_raw) {
+  using T = Tile<DT, D>;
+  __shared__ u32x4 s_tile[kSweepThreads / 64][T::kTileChunks];
+  __shared__ float s_bias[GT * 32];
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int g = blockIdx.y / n_chunks, chunk = blockIdx.y % n_chunks;
+  const int h0 = g * G + chunk * GT;
+  const int nh = (G - chunk * GT) < GT ? (G - chunk * GT) : GT;
+  const u32x4* kg = k + (long long)g * n * T::kCpr;
+  const long long n_prefix = n - w;
+
+  // exponent bias of every (head, row): log2 of (row normaliser * w), +inf for padding rows
+  if (threadIdx.x < GT * 32) {
+    const int t = threadIdx.x >> 5, rr = threadIdx.x & 31;
+    float bias = INFINITY;
+    if (t < nh && rr < w) {
+      if (lse != nullptr) {
+        bias = lse[(long long)(h0 + t) * w + rr] * kLog2e;
+      } else {
+        float m = -INFINITY, z = 0.0f;
+        const float2* p = stat_part + (long long)blockIdx.y * stat_blocks * (GT * 32) + threadIdx.x;
+        for (int b = 0; b < stat_blocks; ++b) {
+          const float2 x = p[(long long)b * (GT * 32)];
+          merge_stat(m, z, x.x, x.y, c2);
+        }
+        bias = m * c2 + log2f(z);
+      }
+      bias += log2f((float)w);
+    }
+    s_bias[threadIdx.x] = bias;
+  }
+
+  u32x4 qf[GT][T::kSteps];
+  load_q<DT, D, GT>(q_win, h0, nh, w, lane, qf);
+  __syncthreads();
+
+  const int half = lane >> 5;
+  float bias[GT][16];
+#pragma unroll
+  for (int t = 0; t < GT; ++t)
+#pragma unroll
+    for (int v = 0; v < 16; ++v) bias[t][v] = s_bias[t * 32 + 8 * (v / 4) + 4 * half + (v % 4)];
+
+  const long long n_tiles = (n_prefix + kTileKeys - 1) / kTileKeys;
+  const long long t_begin = (long long)blockIdx.x * tiles_per_block;
+  long long t_end = t_begin + tiles_per_block;
+  if (t_end > n_tiles) t_end = n_tiles;
+
+  u32x4 stage[T::kLoads];
+  long long tile = t_begin + wave;
+  if (tile < t_end) load_tile<DT, D>(kg, tile, n, lane, stage);
+  u32x4* buf = s_tile[wave];
+  for (; tile < t_end; tile += kSweepThreads / 64) {
+    stage_to_lds<DT, D>(buf, lane, stage);
+    const long long next = tile + kSweepThreads / 64;
+    if (next < t_end) load_tile<DT, D>(kg, next, n, lane, stage);
+    wave_lds_sync();
+    u32x4 kf[T::kSteps];
+    lds_to_frag<DT, D>(buf, lane, kf);
+    wave_lds_sync();
+
+    float best = 0.0f;
+#pragma unroll
+    for (int t = 0; t < GT; ++t) {
+      f32x16 acc = {0};
+#pragma unroll
+      for (int j = 0; j < T::kSteps; ++j) acc = mfma_chunk<DT>(qf[t][j], kf[j], acc);
+      float ps = 0.0f;
+#pragma unroll
+      for (int v = 0; v < 16; ++v) ps += fast_exp2(fmaf(acc[v], c2, -bias[t][v]));
+      ps += __shfl_xor(ps, 32);
+      best = fmaxf(best, ps);
+    }
+    const long long key = tile * kTileKeys + (lane & 31);
+    if (half == 0 && key < n_prefix) {
+      float* dst = s_raw + (long long)g * n_prefix + key;
+      if (n_chunks == 1) {
+        *dst = best;
+      } else {   // heads of the group are split over workgroups: non-negative floats order as integers
+        atomicMax(reinterpret_cast<unsigned int*>(dst), __float_as_uint(best));
+      }
+    }
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// vnorm: per-workgroup maximum over rows of sum_c |V[g, k, c]|, all n rows.
+// ------------------------------------------------------------------------------------------
+template <int DT>
+__device__ __forceinline__ float abs_sum16(const u32x4& x) {
+  if constexpr (DT == LAVA_BF16) {
+    float s = 0.0f;
+    const unsigned int u[4] = {x.x, x.y, x.z, x.w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      s += fabsf(__uint_as_float(u[i] << 16));
+      s += fabsf(__uint_as_float(u[i] & 0xffff0000u));
+    }
+    return s;
+  } else {
+    return fabsf(__uint_as_float(x.x)) + fabsf(__uint_as_float(x.y)) + fabsf(__uint_as_float(x.z)) +
+           fabsf(__uint_as_float(x.w));
+  }
+}
+
+constexpr int kVnormThreads = 256;
+constexpr int kVnormUnroll = 4;
+
+template <int DT, int LPR>   // LPR lanes (16 bytes each) per row
+__global__ void __launch_bounds__(kVnormThreads)
+vnorm_kernel(const u32x4* __restrict__ v, long long n, long long rows_per_block,
+             float* __restrict__ vnorm_part, uint32_t* __restrict__ counters) {
+  __shared__ float s_max[kVnormThreads / 64];
+  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 8) counters[threadIdx.x] = 0u;
+  const int g = blockIdx.y;
+  const u32x4* vg = v + (long long)g * n * LPR;
+  const long long row_begin = (long long)blockIdx.x * rows_per_block;
+  long long row_end = row_begin + rows_per_block;
+  if (row_end > n) row_end = n;
+  constexpr int kRowsPerIter = kVnormThreads / LPR;
+  const int sub = threadIdx.x / LPR, c = threadIdx.x % LPR;
+  float best = 0.0f;
+  for (long long row = row_begin; row < row_end; row += kRowsPerIter * kVnormUnroll) {
+    u32x4 x[kVnormUnroll];
+#pragma unroll
+    for (int u = 0; u < kVnormUnroll; ++u) {
+      const long long rr = row + u * kRowsPerIter + sub;
+      x[u] = rr < row_end ? vg[rr * LPR + c] : u32x4{0u, 0u, 0u, 0u};
+    }
+#pragma unroll
+    for (int u = 0; u < kVnormUnroll; ++u) {
+      float s = abs_sum16<DT>(x[u]);
+#pragma unroll
+      for (int off = 1; off < LPR; off <<= 1) s += __shfl_xor(s, off);
+      best = fmaxf(best, s);
+    }
+  }
+  for (int off = 32; off > 0; off >>= 1) best = fmaxf(best, __shfl_xor(best, off));
+  if ((threadIdx.x & 63) == 0) s_max[threadIdx.x >> 6] = best;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float m = s_max[0];
+    for (int i = 1; i < kVnormThreads / 64; ++i) m = fmaxf(m, s_max[i]);
+    vnorm_part[(long long)g * gridDim.x + blockIdx.x] = m;
+  }
+}
+
+// ------------------------------------------------------------------------------------------
+// poolstat: scores[g, i] = Vbar[g] * max_{|i'-i| <= half, i' in prefix} s_raw[g, i'] for the
+// prefix, +inf for the window entries; S = sum s, T = sum s ln s in double with a fixed
+// reduction order; the last workgroup to finish forms e = (ln S - T / S) / (H_kv * n')  (Eq. 4-5).
+// ------------------------------------------------------------------------------------------
+constexpr int kPoolThreads = 256;
+constexpr int kPoolPerThread = 8;
+constexpr int kPoolChunk = kPoolThreads * kPoolPerThread;
+constexpr int kPoolMaxHalf = 7;
+
+__global__ void __launch_bounds__(kPoolThreads)
+poolstat_kernel(const float* __restrict__ s_raw, long long n, int w, int pool_half,
+                const float* __restrict__ vnorm_part, int vnorm_blocks, float* __restrict__ scores,
+                float* __restrict__ vbar, float* __restrict__ layer_stat,
+                double2* __restrict__ ent_part, uint32_t* __restrict__ counters) {
+  __shared__ float s_in[kPoolChunk + 2 * kPoolMaxHalf];
+  __shared__ float s_vmax[kPoolThreads / 64];
+  __shared__ double s_s[kPoolThreads / 64], s_t[kPoolThreads / 64];
+  __shared__ unsigned int s_last;
+  const int g = blockIdx.y;
+  const long long n_prefix = n - w;
+  const long long i0 = (long long)blockIdx.x * kPoolChunk;
+
+  // Vbar of this head from the value-norm partials
+  float vb = 0.0f;
+  for (int i = threadIdx.x; i < vnorm_blocks; i += kPoolThreads)
+    vb = fmaxf(vb, vnorm_part[(long long)g * vnorm_blocks + i]);
+  for (int off = 32; off > 0; off >>= 1) vb = fmaxf(vb, __shfl_xor(vb, off));
+  if ((threadIdx.x & 63) == 0) s_vmax[threadIdx.x >> 6] = vb;
+
+  for (int i = threadIdx.x; i < kPoolChunk + 2 * pool_half; i += kPoolThreads) {
+    const long long p = i0 + i - pool_half;
+    s_in[i] = (p >= 0 && p < n_prefix) ? s_raw[(long long)g * n_prefix + p] : -INFINITY;
+  }
+  __syncthreads();
+  vb = s_vmax[0];
+  for (int i = 1; i < kPoolThreads / 64; ++i) vb = fmaxf(vb, s_vmax[i]);
+  if (blockIdx.x == 0 && threadIdx.x == 0) vbar[g] = vb;
+
+  double acc_s = 0.0, acc_t = 0.0;
+#pragma unroll
+  for (int j = 0; j < kPoolPerThread; ++j) {
+    const int i = j * kPoolThreads + threadIdx.x;
+    const long long p = i0 + i;
+    if (p < n_prefix) {
+      float m = s_in[i + pool_half];
+      for (int d = 1; d <= pool_half; ++d) m = fmaxf(m, fmaxf(s_in[i + pool_half - d], s_in[i + pool_half + d]));
+      const float s = vb * m;
+      scores[(long long)g * n + p] = s;
+      acc_s += (double)s;
+      if (s > 0.0f) acc_t += (double)s * (double)logf(s);
+    } else if (p < n) {
+      scores[(long long)g * n + p] = INFINITY;
+    }
+  }
+  // fixed-order reduction: lanes (xor tree), wavefronts, then workgroups in index order
+  for (int off = 32; off > 0; off >>= 1) {
+    acc_s += __shfl_xor(acc_s, off);
+    acc_t += __shfl_xor(acc_t, off);
+  }
+  if ((threadIdx.x & 63) == 0) { s_s[threadIdx.x >> 6] = acc_s; s_t[threadIdx.x >> 6] = acc_t; }
+  __syncthreads();
+  const unsigned int n_blocks = gridDim.x * gridDim.y;
+  if (threadIdx.x == 0) {
+    double S = 0.0, Tt = 0.0;
+    for (int i = 0; i < kPoolThreads / 64; ++i) { S += s_s[i]; Tt += s_t[i]; }
+    ent_part[blockIdx.y * gridDim.x + blockIdx.x] = make_double2(S, Tt);
+    __threadfence();
+    const unsigned int ticket = atomicAdd(&counters[0], 1u);
+    s_last = (ticket == n_blocks - 1) ? 1u : 0u;
+  }
+  __syncthreads();
+  if (s_last == 0u || threadIdx.x != 0) return;
+  __threadfence();
+  double S = 0.0, Tt = 0.0;
+  for (unsigned int i = 0; i < n_blocks; ++i) {
+    S += __hip_atomic_load(&ent_part[i].x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    Tt += __hip_atomic_load(&ent_part[i].y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+  double e = 0.0;
+  if (S > 0.0) e = (log(S) - Tt / S) / ((double)gridDim.y * (double)n_prefix);
+  layer_stat[0] = (float)e;
+}
+
+__global__ void __launch_bounds__(256) fill_zero_kernel(float* __restrict__ p, long long count) {
+  const long long i0 = ((long long)blockIdx.x * 256 + threadIdx.x) * 4;
+  for (int j = 0; j < 4; ++j)
+    if (i0 + j < count) p[i0 + j] = 0.0f;
+}
+
+// ------------------------------------------------------------------------------------------ host
+SweepPlan make_sweep_plan(const lava_layer_desc& d, int64_t n) {
+  SweepPlan p;
+  const int G = d.n_q_heads / d.n_kv_heads;
+  int gt = kMaxChunkHeads;
+  if (d.dtype == LAVA_F32 && d.head_dim == 128) gt = 2;
+  p.chunk_heads = G < gt ? G : gt;
+  if (p.chunk_heads == 3) p.chunk_heads = 4;   // kernels are built for 1, 2 and 4 heads per chunk
+  p.n_chunks = (G + p.chunk_heads - 1) / p.chunk_heads;
+  const int64_t n_tiles = (n + kTileKeys - 1) / kTileKeys;
+  int64_t max_bx = 1024 / ((int64_t)d.n_kv_heads * p.n_chunks);
+  if (max_bx < 1) max_bx = 1;
+  int64_t tpb = (n_tiles + max_bx - 1) / max_bx;
+  if (tpb < 16) tpb = 16;
+  p.tiles_per_block = (int)tpb;
+  p.blocks_x = (int)((n_tiles + tpb - 1) / tpb);
+  int64_t vb = (n + 1023) / 1024;      // at least 1024 rows per workgroup
+  if (vb > 256) vb = 256;
+  if (vb < 1) vb = 1;
+  p.vnorm_blocks = (int)vb;
+  return p;
+}
+
+int pool_blocks(const lava_layer_desc& d, int64_t n) {
+  (void)d;
+  return (int)((n + kPoolChunk - 1) / kPoolChunk);
+}
+
+ScoreWorkspace make_score_workspace(const lava_layer_desc& d, int64_t n) {
+  const SweepPlan p = make_sweep_plan(d, n);
+  ScoreWorkspace w;
+  size_t off = 0;
+  w.off_stat_part = off;
+  off += align_up(sizeof(float2) * (size_t)d.n_kv_heads * p.n_chunks * p.blocks_x * p.chunk_heads * 32);
+  w.off_vnorm_part = off;
+  off += align_up(sizeof(float) * (size_t)d.n_kv_heads * p.vnorm_blocks);
+  w.off_sraw = off;
+  off += align_up(sizeof(float) * (size_t)d.n_kv_heads * (size_t)(n - d.window));
+  w.off_ent_part = off;
+  off += align_up(sizeof(double2) * (size_t)d.n_kv_heads * pool_blocks(d, n));
+  w.off_counter = off;
+  off += align_up(sizeof(uint32_t) * 8);
+  w.bytes = off;
+  return w;
+}
+
+int32_t launch_vnorm(const lava_layer_desc& d, int64_t n, const void* v, float* vnorm_part,
+                     uint32_t* counters, const SweepPlan& p, hipStream_t s) {
+  const int lpr = d.head_dim * (d.dtype == LAVA_BF16 ? 2 : 4) / 16;
+  const long long rows_per_block = (n + p.vnorm_blocks - 1) / p.vnorm_blocks;
+  const dim3 grid(p.vnorm_blocks, d.n_kv_heads), block(kVnormThreads);
+  ProfScope ps(KID_VNORM, s);
+#define LAVA_VNORM(DTV, L)                                                                    \
+  hipLaunchKernelGGL((vnorm_kernel<DTV, L>), grid, block, 0, s, static_cast<const u32x4*>(v), \
+                     (long long)n, rows_per_block, vnorm_part, counters)
+  if (d.dtype == LAVA_BF16 && lpr == 8) LAVA_VNORM(LAVA_BF16, 8);
+  else if (d.dtype == LAVA_BF16 && lpr == 16) LAVA_VNORM(LAVA_BF16, 16);
+  else if (d.dtype == LAVA_F32 && lpr == 16) LAVA_VNORM(LAVA_F32, 16);
+  else if (d.dtype == LAVA_F32 && lpr == 32) LAVA_VNORM(LAVA_F32, 32);
+  else return LAVA_ERR_SHAPE;
+#undef LAVA_VNORM
+  return launch_status();
+}
+
+static float exp2_scale(const lava_layer_desc& d) {
+  const float scale = d.softmax_scale > 0.0f ? d.softmax_scale : 1.0f / sqrtf((float)d.head_dim);
+  return scale * kLog2e;
+}
+
+// Dispatch over (dtype, head_dim, heads per chunk).
+#define LAVA_SWEEP_DISPATCH(CALL)                                                   \
+  do {                                                                              \
+    const int gt = p.chunk_heads;                                                   \
+    if (d.dtype == LAVA_BF16 && d.head_dim == 128) {                                \
+      if (gt == 4) CALL(LAVA_BF16, 128, 4); else if (gt == 2) CALL(LAVA_BF16, 128, 2); \
+      else CALL(LAVA_BF16, 128, 1);                                                 \
+    } else if (d.dtype == LAVA_BF16 && d.head_dim == 64) {                          \
+      if (gt == 4) CALL(LAVA_BF16, 64, 4); else if (gt == 2) CALL(LAVA_BF16, 64, 2); \
+      else CALL(LAVA_BF16, 64, 1);                                                  \
+    } else if (d.dtype == LAVA_F32 && d.head_dim == 64) {                           \
+      if (gt == 4) CALL(LAVA_F32, 64, 4); else if (gt == 2) CALL(LAVA_F32, 64, 2);  \
+      else CALL(LAVA_F32, 64, 1);                                                   \
+    } else if (d.dtype == LAVA_F32 && d.head_dim == 128) {                          \
+      if (gt == 2) CALL(LAVA_F32, 128, 2); else CALL(LAVA_F32, 128, 1);             \
+    } else {                                                                        \
+      return LAVA_ERR_SHAPE;                                                        \
+    }                                                                               \
+  } while (0)
+
+int32_t launch_stats(const lava_layer_desc& d, int64_t n, const void* q_win, const void* k,
+                     float2* stat_part, const SweepPlan& p, hipStream_t s) {
+  const int G = d.n_q_heads / d.n_kv_heads;
+  const dim3 grid(p.blocks_x, d.n_kv_heads * p.n_chunks), block(kSweepThreads);
+  const float c2 = exp2_scale(d);
+  ProfScope ps(KID_STATS, s);
+#define LAVA_STATS(DTV, DV, GTV)                                                              \
+  hipLaunchKernelGGL((stats_kernel<DTV, DV, GTV>), grid, block, 0, s,                         \
+                     static_cast<const u32x4*>(q_win), static_cast<const u32x4*>(k),          \
+                     (long long)n, d.window, G, p.n_chunks, c2, p.tiles_per_block, stat_part)
+  LAVA_SWEEP_DISPATCH(LAVA_STATS);
+#undef LAVA_STATS
+  return launch_status();
+}
+
+int32_t launch_scores(const lava_layer_desc& d, int64_t n, const void* q_win, const void* k,
+                      const float2* stat_part, const float* lse, float* s_raw, const SweepPlan& p,
+                      hipStream_t s) {
+  const int G = d.n_q_heads / d.n_kv_heads;
+  const dim3 grid(p.blocks_x, d.n_kv_heads * p.n_chunks), block(kSweepThreads);
+  const float c2 = exp2_scale(d);
+  ProfScope ps(KID_SCORES, s);
+  if (p.n_chunks > 1) {
+    // partial group maxima are combined with integer atomicMax; start from +0 (a fill kernel,
+    // not a memset node, so the call sequence can be captured in a HIP graph)
+    const long long count = (long long)d.n_kv_heads * (long long)(n - d.window);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((count + 1023) / 1024)), dim3(256), 0, s,
+                       s_raw, count);
+  }
+#define LAVA_SCORES(DTV, DV, GTV)                                                             \
+  hipLaunchKernelGGL((scores_kernel<DTV, DV, GTV>), grid, block, 0, s,                        \
+                     static_cast<const u32x4*>(q_win), static_cast<const u32x4*>(k),          \
+                     (long long)n, d.window, G, p.n_chunks, c2, p.tiles_per_block, stat_part, \
+                     p.blocks_x, lse, s_raw)
+  LAVA_SWEEP_DISPATCH(LAVA_SCORES);
+#undef LAVA_SCORES
+  return launch_status();
+}
+
+int32_t launch_poolstat(const lava_layer_desc& d, int64_t n, const float* s_raw,
+                        const float* vnorm_part, int vnorm_blocks, float* scores, float* vbar,
+                        float* layer_stat, double2* ent_part, uint32_t* counters, hipStream_t s) {
+  const dim3 grid(pool_blocks(d, n), d.n_kv_heads), block(kPoolThreads);
+  ProfScope ps(KID_POOLSTAT, s);
+  hipLaunchKernelGGL(poolstat_kernel, grid, block, 0, s, s_raw, (long long)n, d.window,
+                     d.pool_kernel / 2, vnorm_part, vnorm_blocks, scores, vbar, layer_stat, ent_part,
+                     counters);
+  return launch_status();
+}
+
+}  // namespace lava

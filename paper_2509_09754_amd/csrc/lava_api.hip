@@ -1,0 +1,245 @@
+// C ABI of the library: argument checks on the host, then kernel launches on the caller's
+// stream.  Nothing here allocates device memory.
+#include <string.h>
+
+#include <vector>
+
+#include "common.h"
+
+namespace lava {
+
+// ------------------------------------------------------------------ per-kernel timing hook
+namespace {
+struct ProfState {
+  bool enabled = false;
+  std::vector<hipEvent_t> start[KID_COUNT], stop[KID_COUNT];
+  size_t used[KID_COUNT] = {};
+  double total_ms[KID_COUNT] = {};
+  int64_t launches[KID_COUNT] = {};
+} g_prof;
+
+const char* const kKernelNames[KID_COUNT] = {
+    "vnorm", "stats", "scores", "poolstat", "sel_init", "sel_hist", "sel_count", "sel_write",
+    "compact", "budgets"};
+
+void prof_collect() {
+  (void)hipDeviceSynchronize();
+  for (int k = 0; k < KID_COUNT; ++k) {
+    for (size_t i = 0; i < g_prof.used[k]; ++i) {
+      float ms = 0.0f;
+      if (hipEventElapsedTime(&ms, g_prof.start[k][i], g_prof.stop[k][i]) == hipSuccess) {
+        g_prof.total_ms[k] += ms;
+        g_prof.launches[k] += 1;
+      }
+    }
+    g_prof.used[k] = 0;
+  }
+}
+}  // namespace
+
+void prof_begin(int kid, hipStream_t s) {
+  if (!g_prof.enabled) return;
+  if (g_prof.used[kid] == g_prof.start[kid].size()) {
+    hipEvent_t a, b;
+    if (hipEventCreate(&a) != hipSuccess || hipEventCreate(&b) != hipSuccess) return;
+    g_prof.start[kid].push_back(a);
+    g_prof.stop[kid].push_back(b);
+  }
+  (void)hipEventRecord(g_prof.start[kid][g_prof.used[kid]], s);
+}
+
+void prof_end(int kid, hipStream_t s) {
+  if (!g_prof.enabled) return;
+  if (g_prof.used[kid] >= g_prof.start[kid].size()) return;
+  (void)hipEventRecord(g_prof.stop[kid][g_prof.used[kid]], s);
+  g_prof.used[kid] += 1;
+  if (g_prof.used[kid] >= 4096) prof_collect();   // bound the number of live events
+}
+
+// ------------------------------------------------------------------ descriptor checks
+static int32_t check_desc(const lava_layer_desc* d) {
+  if (d == nullptr) return LAVA_ERR_INVALID_ARG;
+  if (d->dtype != LAVA_F32 && d->dtype != LAVA_BF16) return LAVA_ERR_INVALID_ARG;
+  if (d->n_q_heads < 1 || d->n_kv_heads < 1 || d->window < 1 || d->pool_kernel < 1)
+    return LAVA_ERR_INVALID_ARG;
+  if (!(d->softmax_scale >= 0.0f) || d->softmax_scale > 1e30f) return LAVA_ERR_INVALID_ARG;
+  if (d->n_q_heads % d->n_kv_heads != 0) return LAVA_ERR_SHAPE;
+  if (d->n_q_heads / d->n_kv_heads > 8 || d->n_kv_heads > 64) return LAVA_ERR_SHAPE;
+  if (d->head_dim != 64 && d->head_dim != 128) return LAVA_ERR_SHAPE;
+  if (d->window > 32) return LAVA_ERR_SHAPE;
+  if (d->pool_kernel % 2 == 0 || d->pool_kernel > 15) return LAVA_ERR_SHAPE;
+  return LAVA_OK;
+}
+
+static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace lava
+
+using namespace lava;
+
+extern "C" {
+
+const char* lava_status_string(int32_t status) {
+  switch (status) {
+    case LAVA_OK: return "ok";
+    case LAVA_ERR_INVALID_ARG: return "invalid argument";
+    case LAVA_ERR_SHAPE: return "unsupported shape";
+    case LAVA_ERR_BUDGET: return "budget out of range";
+    case LAVA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case LAVA_ERR_HIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+size_t lava_window_scores_workspace_bytes(const lava_layer_desc* desc, int32_t batch,
+                                          int64_t total_tokens) {
+  if (check_desc(desc) != LAVA_OK || batch < 1 || total_tokens <= desc->window) return 0;
+  // sequences are processed one after another on the stream and share the workspace, so the
+  // largest possible single sequence bounds it
+  const int64_t max_n = total_tokens - (int64_t)(batch - 1) * (desc->window + 1);
+  if (max_n <= desc->window) return 0;
+  return make_score_workspace(*desc, max_n).bytes;
+}
+
+int32_t lava_window_scores(const lava_layer_desc* desc, int32_t batch, const int64_t* seq_lens,
+                           const void* q_win, const void* k, const void* v, const float* lse,
+                           float* scores, float* vbar, float* layer_stat, void* workspace,
+                           size_t workspace_bytes, void* hip_stream) {
+  int32_t st = check_desc(desc);
+  if (st != LAVA_OK) return st;
+  if (batch < 1 || seq_lens == nullptr || q_win == nullptr || k == nullptr || v == nullptr ||
+      scores == nullptr || vbar == nullptr || layer_stat == nullptr)
+    return LAVA_ERR_INVALID_ARG;
+  if (!aligned16(q_win) || !aligned16(k) || !aligned16(v)) return LAVA_ERR_INVALID_ARG;
+  int64_t max_n = 0;
+  for (int b = 0; b < batch; ++b) {
+    if (seq_lens[b] <= desc->window) return LAVA_ERR_SHAPE;
+    if (seq_lens[b] >= (int64_t)1 << 31) return LAVA_ERR_SHAPE;
+    if (seq_lens[b] > max_n) max_n = seq_lens[b];
+  }
+  const size_t need = make_score_workspace(*desc, max_n).bytes;
+  if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 ||
+      workspace_bytes < need)
+    return LAVA_ERR_WORKSPACE;
+
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const lava_layer_desc& d = *desc;
+  const size_t esize = d.dtype == LAVA_BF16 ? 2 : 4;
+  const size_t row = (size_t)d.head_dim * esize;
+  char* ws = static_cast<char*>(workspace);
+  int64_t tok = 0;
+  for (int b = 0; b < batch; ++b) {
+    const int64_t n = seq_lens[b];
+    const SweepPlan plan = make_sweep_plan(d, n);
+    const ScoreWorkspace w = make_score_workspace(d, n);
+    const char* kb = static_cast<const char*>(k) + (size_t)d.n_kv_heads * tok * row;
+    const char* vb = static_cast<const char*>(v) + (size_t)d.n_kv_heads * tok * row;
+    const char* qb = static_cast<const char*>(q_win) + (size_t)b * d.n_q_heads * d.window * row;
+    const float* lse_b = lse ? lse + (size_t)b * d.n_q_heads * d.window : nullptr;
+    float* sc = scores + (size_t)d.n_kv_heads * tok;
+    float2* stat_part = reinterpret_cast<float2*>(ws + w.off_stat_part);
+    float* vnorm_part = reinterpret_cast<float*>(ws + w.off_vnorm_part);
+    float* s_raw = reinterpret_cast<float*>(ws + w.off_sraw);
+    double2* ent_part = reinterpret_cast<double2*>(ws + w.off_ent_part);
+    uint32_t* counters = reinterpret_cast<uint32_t*>(ws + w.off_counter);
+
+    st = launch_vnorm(d, n, vb, vnorm_part, counters, plan, s);
+    if (st != LAVA_OK) return st;
+    if (lse_b == nullptr) {
+      st = launch_stats(d, n, qb, kb, stat_part, plan, s);
+      if (st != LAVA_OK) return st;
+    }
+    st = launch_scores(d, n, qb, kb, stat_part, lse_b, s_raw, plan, s);
+    if (st != LAVA_OK) return st;
+    st = launch_poolstat(d, n, s_raw, vnorm_part, plan.vnorm_blocks, sc, vbar + (size_t)b * d.n_kv_heads,
+                         layer_stat + b, ent_part, counters, s);
+    if (st != LAVA_OK) return st;
+    tok += n;
+  }
+  return LAVA_OK;
+}
+
+int32_t lava_layer_budgets(int32_t batch, int32_t n_layers, const float* e, const int64_t* total,
+                           const int64_t* lo, const int64_t* hi, int64_t* budgets,
+                           int32_t on_device, void* hip_stream) {
+  if (batch < 1 || n_layers < 1 || e == nullptr || total == nullptr || lo == nullptr ||
+      hi == nullptr || budgets == nullptr)
+    return LAVA_ERR_INVALID_ARG;
+  if (n_layers > 1024) return LAVA_ERR_SHAPE;
+  if (on_device)
+    return launch_budgets(batch, n_layers, e, total, lo, hi, budgets,
+                          static_cast<hipStream_t>(hip_stream));
+  return budgets_host(batch, n_layers, e, total, lo, hi, budgets);
+}
+
+size_t lava_select_workspace_bytes(int64_t total_entries) {
+  if (total_entries < 1 || total_entries >= (int64_t)1 << 31) return 0;
+  return make_select_workspace(total_entries).bytes;
+}
+
+int32_t lava_select_topk(int32_t n_heads, const float* scores, const int64_t* seg_offsets,
+                         int64_t total_entries, int64_t budget, const int64_t* budget_dev,
+                         int32_t* head_counts, int64_t* head_offsets, int32_t* kept_idx,
+                         float* kept_scores, void* workspace, size_t workspace_bytes,
+                         void* hip_stream) {
+  if (n_heads < 1 || scores == nullptr || head_counts == nullptr || head_offsets == nullptr ||
+      kept_idx == nullptr || total_entries < 1)
+    return LAVA_ERR_INVALID_ARG;
+  if (n_heads > 64 || total_entries >= (int64_t)1 << 31) return LAVA_ERR_SHAPE;
+  if (seg_offsets == nullptr && total_entries % n_heads != 0) return LAVA_ERR_SHAPE;
+  if (budget < 0 || budget > total_entries) return LAVA_ERR_BUDGET;
+  const size_t need = make_select_workspace(total_entries).bytes;
+  if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 ||
+      workspace_bytes < need)
+    return LAVA_ERR_WORKSPACE;
+  return launch_select(n_heads, scores, seg_offsets, total_entries, budget, budget_dev, head_counts,
+                       head_offsets, kept_idx, kept_scores, workspace,
+                       static_cast<hipStream_t>(hip_stream));
+}
+
+int32_t lava_compact_kv(const lava_layer_desc* desc, int64_t n, const void* k, const void* v,
+                        const int64_t* head_offsets, const int32_t* kept_idx, int64_t capacity,
+                        void* k_out, void* v_out, void* hip_stream) {
+  int32_t st = check_desc(desc);
+  if (st != LAVA_OK) return st;
+  if (k == nullptr || v == nullptr || head_offsets == nullptr || kept_idx == nullptr ||
+      k_out == nullptr || v_out == nullptr || n < 1 || capacity < 0)
+    return LAVA_ERR_INVALID_ARG;
+  if (!aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out))
+    return LAVA_ERR_INVALID_ARG;
+  if (capacity > (int64_t)desc->n_kv_heads * n) return LAVA_ERR_BUDGET;
+  return launch_compact(*desc, n, k, v, head_offsets, kept_idx, capacity, k_out, v_out,
+                        static_cast<hipStream_t>(hip_stream));
+}
+
+int32_t lava_prof_kernel_count(void) { return KID_COUNT; }
+
+const char* lava_prof_kernel_name(int32_t id) {
+  return (id >= 0 && id < KID_COUNT) ? kKernelNames[id] : "";
+}
+
+int32_t lava_prof_enable(int32_t on) {
+  if (!on && g_prof.enabled) prof_collect();
+  g_prof.enabled = on != 0;
+  return LAVA_OK;
+}
+
+int32_t lava_prof_reset(void) {
+  prof_collect();
+  for (int k = 0; k < KID_COUNT; ++k) {
+    g_prof.total_ms[k] = 0.0;
+    g_prof.launches[k] = 0;
+  }
+  return LAVA_OK;
+}
+
+int32_t lava_prof_read(int32_t id, double* total_ms, int64_t* launches) {
+  if (id < 0 || id >= KID_COUNT || total_ms == nullptr || launches == nullptr)
+    return LAVA_ERR_INVALID_ARG;
+  prof_collect();
+  *total_ms = g_prof.total_ms[id];
+  *launches = g_prof.launches[id];
+  return LAVA_OK;
+}
+
+}  // extern "C"

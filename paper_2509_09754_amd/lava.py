@@ -1,0 +1,269 @@
+"""ctypes binding over liblava.so: the same entry points as include/lava.h, taking torch tensors.
+
+Argument marshalling only — every step of the path runs in the HIP kernels.  PyTorch supplies
+device memory and the current stream.  If the library has not been built the import fails
+loudly; there is no fallback implementation.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "liblava.so")
+
+LAVA_OK, LAVA_ERR_INVALID_ARG, LAVA_ERR_SHAPE, LAVA_ERR_BUDGET, LAVA_ERR_WORKSPACE, LAVA_ERR_HIP = range(6)
+LAVA_F32, LAVA_BF16 = 0, 1
+
+EXPORTS = [
+    "lava_status_string", "lava_window_scores_workspace_bytes", "lava_window_scores",
+    "lava_layer_budgets", "lava_select_workspace_bytes", "lava_select_topk", "lava_compact_kv",
+    "lava_prof_kernel_count", "lava_prof_kernel_name", "lava_prof_enable", "lava_prof_reset",
+    "lava_prof_read",
+]
+
+
+class LayerDesc(ctypes.Structure):
+    """Mirror of lava_layer_desc."""
+    _fields_ = [
+        ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
+        ("window", ctypes.c_int32), ("pool_kernel", ctypes.c_int32), ("dtype", ctypes.c_int32),
+        ("softmax_scale", ctypes.c_float),
+    ]
+
+    @classmethod
+    def make(cls, n_q_heads, n_kv_heads, head_dim, window, dtype, pool_kernel=7, softmax_scale=0.0):
+        code = {"f32": LAVA_F32, "bf16": LAVA_BF16, LAVA_F32: LAVA_F32, LAVA_BF16: LAVA_BF16}[dtype]
+        return cls(n_q_heads, n_kv_heads, head_dim, window, pool_kernel, code, softmax_scale)
+
+    @property
+    def torch_dtype(self):
+        return torch.bfloat16 if self.dtype == LAVA_BF16 else torch.float32
+
+
+class LavaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {status_string(status)} (status {status})")
+
+
+def _load() -> ctypes.CDLL:
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2509_09754_amd.build` "
+            "(there is no CPU fallback)")
+    lib = ctypes.CDLL(LIB_PATH)
+    vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+    dp = ctypes.POINTER(LayerDesc)
+    lib.lava_status_string.restype = ctypes.c_char_p
+    lib.lava_status_string.argtypes = [i32]
+    lib.lava_window_scores_workspace_bytes.restype = sz
+    lib.lava_window_scores_workspace_bytes.argtypes = [dp, i32, i64]
+    lib.lava_window_scores.restype = i32
+    lib.lava_window_scores.argtypes = [dp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.lava_layer_budgets.restype = i32
+    lib.lava_layer_budgets.argtypes = [i32, i32, vp, vp, vp, vp, vp, i32, vp]
+    lib.lava_select_workspace_bytes.restype = sz
+    lib.lava_select_workspace_bytes.argtypes = [i64]
+    lib.lava_select_topk.restype = i32
+    lib.lava_select_topk.argtypes = [i32, vp, vp, i64, i64, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.lava_compact_kv.restype = i32
+    lib.lava_compact_kv.argtypes = [dp, i64, vp, vp, vp, vp, i64, vp, vp, vp]
+    lib.lava_prof_kernel_count.restype = i32
+    lib.lava_prof_kernel_name.restype = ctypes.c_char_p
+    lib.lava_prof_kernel_name.argtypes = [i32]
+    lib.lava_prof_enable.restype = i32
+    lib.lava_prof_enable.argtypes = [i32]
+    lib.lava_prof_reset.restype = i32
+    lib.lava_prof_read.restype = i32
+    lib.lava_prof_read.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+    return lib
+
+
+lib = _load()
+
+
+def status_string(status: int) -> str:
+    return lib.lava_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str) -> None:
+    if status != LAVA_OK:
+        raise LavaError(status, where)
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream) -> ctypes.c_void_p:
+    if stream is None:
+        stream = torch.cuda.current_stream()
+    return ctypes.c_void_p(stream.cuda_stream)
+
+
+def _dev(t: torch.Tensor, name: str, dtype=None) -> torch.Tensor:
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError(f"{name} must be a contiguous device tensor")
+    if dtype is not None and t.dtype != dtype:
+        raise ValueError(f"{name} must have dtype {dtype}")
+    return t
+
+
+def to_device(arr: np.ndarray, dtype: str, device="cuda") -> torch.Tensor:
+    """Upload a stored array from the generator (float32, or uint16 bf16 bit patterns)."""
+    if dtype in ("bf16", LAVA_BF16):
+        return torch.from_numpy(np.ascontiguousarray(arr).view(np.int16)).to(device).view(torch.bfloat16)
+    return torch.from_numpy(np.ascontiguousarray(arr, dtype=np.float32)).to(device)
+
+
+def to_host_bits(t: torch.Tensor) -> np.ndarray:
+    """Download rows bit for bit (bf16 as uint16 patterns, f32 as float32)."""
+    if t.dtype == torch.bfloat16:
+        return t.view(torch.int16).cpu().numpy().view(np.uint16)
+    return t.cpu().numpy()
+
+
+# ------------------------------------------------------------------------------ entry points
+def lava_window_scores_workspace_bytes(desc: LayerDesc, batch: int, total_tokens: int) -> int:
+    return int(lib.lava_window_scores_workspace_bytes(ctypes.byref(desc), batch, total_tokens))
+
+
+def lava_window_scores(desc: LayerDesc, seq_lens: Sequence[int], q_win: torch.Tensor, k: torch.Tensor,
+                       v: torch.Tensor, lse: Optional[torch.Tensor] = None, scores=None, vbar=None,
+                       layer_stat=None, workspace=None, stream=None):
+    """Scores [sum_b H_kv * N_b] (per sequence [H_kv][N_b]), vbar [batch, H_kv], layer_stat [batch]."""
+    lens = np.ascontiguousarray(np.asarray(seq_lens, dtype=np.int64))
+    batch, total = int(lens.shape[0]), int(lens.sum())
+    dev = k.device
+    _dev(q_win, "q_win", desc.torch_dtype), _dev(k, "k", desc.torch_dtype), _dev(v, "v", desc.torch_dtype)
+    row = desc.n_kv_heads * desc.head_dim
+    if k.numel() != total * row or v.numel() != total * row:
+        raise ValueError("k / v hold a different number of tokens than seq_lens")
+    if q_win.numel() != batch * desc.n_q_heads * desc.window * desc.head_dim:
+        raise ValueError("q_win must be [batch, H, w, d_h]")
+    if lse is not None:
+        _dev(lse, "lse", torch.float32)
+        if lse.numel() != batch * desc.n_q_heads * desc.window:
+            raise ValueError("lse must be [batch, H, w]")
+    if scores is None:
+        scores = torch.empty(total * desc.n_kv_heads, dtype=torch.float32, device=dev)
+    if vbar is None:
+        vbar = torch.empty(batch, desc.n_kv_heads, dtype=torch.float32, device=dev)
+    if layer_stat is None:
+        layer_stat = torch.empty(batch, dtype=torch.float32, device=dev)
+    if workspace is None:
+        nbytes = lava_window_scores_workspace_bytes(desc, batch, total)
+        workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
+    st = lib.lava_window_scores(ctypes.byref(desc), batch, lens.ctypes.data_as(ctypes.c_void_p), _ptr(q_win),
+                                _ptr(k), _ptr(v), _ptr(lse), _ptr(scores), _ptr(vbar), _ptr(layer_stat),
+                                _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(st, "lava_window_scores")
+    return scores, vbar, layer_stat
+
+
+def lava_layer_budgets(e, total, lo, hi, budgets=None, stream=None):
+    """e [batch, L] float32; total [batch], lo / hi [batch, L] int64.  All numpy (host path) or all
+    device tensors (device path)."""
+    on_device = isinstance(e, torch.Tensor) and e.is_cuda
+    if on_device:
+        batch, L = e.shape
+        for name, t, dt in (("e", e, torch.float32), ("total", total, torch.int64), ("lo", lo, torch.int64),
+                            ("hi", hi, torch.int64)):
+            _dev(t, name, dt)
+        if budgets is None:
+            budgets = torch.empty(batch, L, dtype=torch.int64, device=e.device)
+        st = lib.lava_layer_budgets(batch, L, _ptr(e), _ptr(total), _ptr(lo), _ptr(hi), _ptr(budgets), 1,
+                                    _stream(stream))
+        _check(st, "lava_layer_budgets")
+        return budgets
+    e = np.ascontiguousarray(np.asarray(e, dtype=np.float32))
+    if e.ndim == 1:
+        e = e[None, :]
+    batch, L = e.shape
+    total = np.ascontiguousarray(np.asarray(total, dtype=np.int64).reshape(batch))
+    lo = np.ascontiguousarray(np.broadcast_to(np.asarray(lo, dtype=np.int64), (batch, L)))
+    hi = np.ascontiguousarray(np.broadcast_to(np.asarray(hi, dtype=np.int64), (batch, L)))
+    out = np.zeros((batch, L), dtype=np.int64)
+    as_vp = lambda a: a.ctypes.data_as(ctypes.c_void_p)
+    st = lib.lava_layer_budgets(batch, L, as_vp(e), as_vp(total), as_vp(lo), as_vp(hi), as_vp(out), 0, None)
+    _check(st, "lava_layer_budgets")
+    return out
+
+
+def lava_select_workspace_bytes(total_entries: int) -> int:
+    return int(lib.lava_select_workspace_bytes(total_entries))
+
+
+def lava_select_topk(n_heads: int, scores: torch.Tensor, budget: int, seg_offsets: Optional[torch.Tensor] = None,
+                     budget_dev: Optional[torch.Tensor] = None, total_entries: Optional[int] = None,
+                     head_counts=None, head_offsets=None, kept_idx=None, kept_scores=None,
+                     want_scores: bool = True, workspace=None, stream=None):
+    _dev(scores, "scores", torch.float32)
+    total = scores.numel() if total_entries is None else int(total_entries)
+    dev = scores.device
+    if seg_offsets is not None:
+        _dev(seg_offsets, "seg_offsets", torch.int64)
+    if budget_dev is not None:
+        _dev(budget_dev, "budget_dev", torch.int64)
+    if head_counts is None:
+        head_counts = torch.empty(n_heads, dtype=torch.int32, device=dev)
+    if head_offsets is None:
+        head_offsets = torch.empty(n_heads + 1, dtype=torch.int64, device=dev)
+    if kept_idx is None:
+        kept_idx = torch.empty(max(int(budget), 1), dtype=torch.int32, device=dev)
+    if kept_scores is None and want_scores:
+        kept_scores = torch.empty(max(int(budget), 1), dtype=torch.float32, device=dev)
+    if workspace is None:
+        workspace = torch.empty(max(lava_select_workspace_bytes(total), 256), dtype=torch.uint8, device=dev)
+    st = lib.lava_select_topk(n_heads, _ptr(scores), _ptr(seg_offsets), total, int(budget), _ptr(budget_dev),
+                              _ptr(head_counts), _ptr(head_offsets), _ptr(kept_idx), _ptr(kept_scores),
+                              _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(st, "lava_select_topk")
+    return head_counts, head_offsets, kept_idx, kept_scores
+
+
+def lava_compact_kv(desc: LayerDesc, n: int, k: torch.Tensor, v: torch.Tensor, head_offsets: torch.Tensor,
+                    kept_idx: torch.Tensor, capacity: int, k_out=None, v_out=None, stream=None):
+    _dev(k, "k", desc.torch_dtype), _dev(v, "v", desc.torch_dtype)
+    _dev(head_offsets, "head_offsets", torch.int64), _dev(kept_idx, "kept_idx", torch.int32)
+    if k_out is None:
+        k_out = torch.empty(max(int(capacity), 1), desc.head_dim, dtype=desc.torch_dtype, device=k.device)
+    if v_out is None:
+        v_out = torch.empty(max(int(capacity), 1), desc.head_dim, dtype=desc.torch_dtype, device=k.device)
+    st = lib.lava_compact_kv(ctypes.byref(desc), int(n), _ptr(k), _ptr(v), _ptr(head_offsets), _ptr(kept_idx),
+                             int(capacity), _ptr(k_out), _ptr(v_out), _stream(stream))
+    _check(st, "lava_compact_kv")
+    return k_out, v_out
+
+
+# ------------------------------------------------------------------------------ timing hook
+def prof_enable(on: bool = True) -> None:
+    lib.lava_prof_enable(1 if on else 0)
+
+
+def prof_reset() -> None:
+    lib.lava_prof_reset()
+
+
+def prof_read() -> dict:
+    """{kernel name: (total milliseconds, launches)} since the last reset."""
+    out = {}
+    for i in range(lib.lava_prof_kernel_count()):
+        ms, cnt = ctypes.c_double(0.0), ctypes.c_int64(0)
+        lib.lava_prof_read(i, ctypes.byref(ms), ctypes.byref(cnt))
+        out[lib.lava_prof_kernel_name(i).decode()] = (ms.value, cnt.value)
+    return out
+
+
+def evict_layer(desc: LayerDesc, n: int, q_win, k, v, budget: int, lse=None, stream=None):
+    """The four calls in order for one sequence of one layer (fixed budget)."""
+    scores, vbar, stat = lava_window_scores(desc, [n], q_win, k, v, lse=lse, stream=stream)
+    counts, offs, idx, kept_s = lava_select_topk(desc.n_kv_heads, scores, budget, stream=stream)
+    k_hat, v_hat = lava_compact_kv(desc, n, k, v, offs, idx, budget, stream=stream)
+    return dict(scores=scores, vbar=vbar, layer_stat=stat, head_counts=counts, head_offsets=offs,
+                kept_idx=idx, kept_scores=kept_s, k_hat=k_hat, v_hat=v_hat)
