@@ -144,6 +144,14 @@ int32_t lava_select_topk(int32_t n_heads, const float* scores, const int64_t* se
                          void* hip_stream);
 
 /*
+ * Synchronises the stream and reports whether the last lava_select_topk that used `workspace`
+ * (with the same total_entries) completed normally.  The selection meets at grid-wide barriers
+ * whose waits are bounded; LAVA_ERR_HIP means a wait gave up (the device could not keep the
+ * kernel's workgroups resident together) and the outputs of that call must not be used.
+ */
+int32_t lava_select_status(const void* workspace, int64_t total_entries, void* hip_stream);
+
+/*
  * Packed surviving rows (Alg. 1: K^ = K (.) I, V^ = V (.) I, stored without the evicted rows):
  *   k_out[head_offsets[g] + t][:] = k[g][kept_idx[head_offsets[g] + t]][:], same for v.
  *
@@ -168,6 +176,15 @@ const char* lava_prof_kernel_name(int32_t id);
 int32_t lava_prof_enable(int32_t on);
 int32_t lava_prof_reset(void);
 int32_t lava_prof_read(int32_t id, double* total_ms, int64_t* launches);
+
+/*
+ * Measurement aid: a plain streaming kernel over `bytes` (multiple of 16) of device memory, used
+ * to calibrate the profiler's HBM byte counters and to measure the streaming ceiling the sweep
+ * kernels are compared with.  mode 0: copy src -> dst (both `bytes` long); mode 1: read src only
+ * (dst: at least 4 bytes, effectively never written).  `blocks` workgroups of 256 lanes.
+ */
+int32_t lava_probe_stream(const void* src, void* dst, int64_t bytes, int32_t mode, int32_t blocks,
+                          void* hip_stream);
 
 #ifdef __cplusplus
 }

@@ -17,9 +17,8 @@ enum KernelId : int {
   KID_SCORES,         // window scores: group-max of window-mean attention
   KID_POOLSTAT,       // max-pool, value factor, +inf window entries, entropy statistic
   KID_SEL_INIT,       // selection: clear histograms and counters
-  KID_SEL_HIST,       // selection: radix histogram pass + digit pick
-  KID_SEL_COUNT,      // selection: per-block survivor counts + scan
-  KID_SEL_WRITE,      // selection: ordered write of survivors
+  KID_SEL_FUSED,      // selection: radix select + ordered write in one launch
+  KID_SEL_STEPS,      // selection: the same phases as separate launches (very large inputs)
   KID_COMPACT,        // K/V row gather
   KID_BUDGETS,        // layer budgets on the device
   KID_COUNT
@@ -62,7 +61,8 @@ struct ScoreWorkspace {
   size_t off_vnorm_part;  // float  [H_kv][vnorm_blocks]
   size_t off_sraw;        // float  [H_kv][N']  group-max of window-mean attention
   size_t off_ent_part;    // double2[pool blocks]  partial (S, T)
-  size_t off_counter;     // uint32 [8]
+  size_t off_row_bias;    // float  [H_kv*n_chunks][GT*32]  log2 of each row's softmax normaliser
+  size_t off_counter;     // uint32 "last workgroup done" tickets
   size_t bytes;
 };
 ScoreWorkspace make_score_workspace(const lava_layer_desc& d, int64_t n);
@@ -71,9 +71,10 @@ int pool_blocks(const lava_layer_desc& d, int64_t n);
 int32_t launch_vnorm(const lava_layer_desc& d, int64_t n, const void* v, float* vnorm_part,
                      uint32_t* counters, const SweepPlan& p, hipStream_t s);
 int32_t launch_stats(const lava_layer_desc& d, int64_t n, const void* q_win, const void* k,
-                     float2* stat_part, const SweepPlan& p, hipStream_t s);
+                     float2* stat_part, float* row_bias, uint32_t* counters, const SweepPlan& p,
+                     hipStream_t s);
 int32_t launch_scores(const lava_layer_desc& d, int64_t n, const void* q_win, const void* k,
-                      const float2* stat_part, const float* lse, float* s_raw, const SweepPlan& p,
+                      const float* row_bias, const float* lse, float* s_raw, const SweepPlan& p,
                       hipStream_t s);
 int32_t launch_poolstat(const lava_layer_desc& d, int64_t n, const float* s_raw,
                         const float* vnorm_part, int vnorm_blocks, float* scores, float* vbar,
@@ -83,7 +84,7 @@ int32_t launch_poolstat(const lava_layer_desc& d, int64_t n, const float* s_raw,
 struct SelectWorkspace {
   size_t off_hist;      // uint32 [3][2048]
   size_t off_state;     // SelectState
-  size_t off_blk;       // uint32 [4][n_blocks]: gt, eq, out_off, eq_prefix
+  size_t off_blk;       // uint32 [2][n_blocks]: keys above / equal to the threshold per workgroup
   int n_blocks;
   size_t bytes;
 };
@@ -93,6 +94,8 @@ int32_t launch_select(int n_heads, const float* scores, const int64_t* seg_offse
                       int64_t budget, const int64_t* budget_dev, int32_t* head_counts,
                       int64_t* head_offsets, int32_t* kept_idx, float* kept_scores, void* ws,
                       hipStream_t s);
+
+int32_t select_error_flag(const void* ws, int64_t total, hipStream_t s, int* flag);
 
 int32_t launch_compact(const lava_layer_desc& d, int64_t n, const void* k, const void* v,
                        const int64_t* head_offsets, const int32_t* kept_idx, int64_t capacity,

@@ -8,7 +8,14 @@
 // an ordered scan, so the survivor set is unique and the output needs no floating-point
 // comparison at all.  Survivors are written in flat order, which is exactly "heads
 // concatenated, ascending position inside each head".
+//
+// The whole selection is latency-bound (a few MiB of scores), so it runs as ONE kernel whose
+// workgroups keep their 4096 scores in registers and meet at five grid-wide barriers; every
+// workgroup derives the digit picks and its output offset redundantly from the shared
+// histograms / per-workgroup counts, so no workgroup waits for a "leader".  Inputs too large for
+// all workgroups to be resident at once fall back to the same phases as separate kernels.
 #include "common.h"
+#include "xblock.h"
 
 namespace lava {
 
@@ -17,13 +24,12 @@ constexpr int kSelPerThread = 16;
 constexpr int kSelChunk = kSelThreads * kSelPerThread;  // entries per workgroup
 constexpr int kBins = 2048;
 constexpr int kMaxHeads = 64;
+constexpr unsigned int kSpinLimit = 1u << 18;           // polls of a grid barrier before giving up
 
 struct SelectState {
-  unsigned int prefix;       // digits of the threshold key decided so far
-  unsigned int reserved;
-  long long need;            // survivors still to take among keys that match `prefix`
-  long long budget_eff;      // number of survivors
-  unsigned int ticket[8];    // "last workgroup done" counters: 0-2 histogram passes, 3 count, 4 write
+  unsigned int barrier;      // arrivals at the grid barriers of the fused kernel (monotonic)
+  unsigned int error;        // set when a barrier wait gave up (results are then invalid)
+  unsigned int reserved[6];
 };
 
 SelectWorkspace make_select_workspace(int64_t total) {
@@ -33,7 +39,7 @@ SelectWorkspace make_select_workspace(int64_t total) {
   size_t off = 0;
   w.off_hist = off;  off += align_up(sizeof(unsigned int) * 3 * kBins);
   w.off_state = off; off += align_up(sizeof(SelectState));
-  w.off_blk = off;   off += align_up(sizeof(unsigned int) * 4 * (size_t)w.n_blocks);
+  w.off_blk = off;   off += align_up(sizeof(unsigned int) * 2 * (size_t)w.n_blocks);
   w.bytes = off;
   return w;
 }
@@ -45,294 +51,384 @@ __device__ __forceinline__ unsigned int score_key(float f) {
   return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
 }
 
-__device__ __forceinline__ unsigned int ld_agent(const unsigned int* p) {
-  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
+struct SelShared {
+  union {
+    float val[kSelChunk + 64];        // staging of the chunk (one pad word per 64 entries)
+    unsigned int hist[kBins];         // per-workgroup digit histogram
+  };
+  long long off[kMaxHeads + 1];       // segment starts
+  unsigned int cnt[kMaxHeads];        // survivors per head in this workgroup
+  unsigned int wave[kSelThreads / 64];
+  unsigned long long wave64[kSelThreads / 64];
+  unsigned int pick_digit;
+  long long pick_need;
+};
 
-// Returns true in every thread of the workgroup that finishes last.
-__device__ __forceinline__ bool last_block_done(unsigned int* ticket, unsigned int n_blocks) {
-  __shared__ unsigned int s_last;
-  __threadfence();
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    const unsigned int t = atomicAdd(ticket, 1u);
-    s_last = (t == n_blocks - 1) ? 1u : 0u;
+// Where the selection stands: digits of the threshold key found so far and how many survivors
+// must still come from the keys that match them.
+struct Pick {
+  unsigned int prefix;
+  long long need;
+};
+
+__device__ __forceinline__ long long effective_budget(long long budget, const int64_t* budget_dev,
+                                                      long long total) {
+  long long b = budget;
+  if (budget_dev != nullptr) {
+    const long long d = (long long)*budget_dev;
+    b = d < b ? d : b;
   }
-  __syncthreads();
-  const bool last = s_last != 0u;
-  if (last) __threadfence();
-  return last;
+  if (b > total) b = total;
+  if (b < 0) b = 0;
+  return b;
 }
 
-__global__ void __launch_bounds__(kSelThreads)
-sel_init_kernel(unsigned int* __restrict__ hist, SelectState* __restrict__ st,
-                int32_t* __restrict__ head_counts, int n_heads, long long total, long long budget,
-                const int64_t* __restrict__ budget_dev) {
-  for (int i = threadIdx.x; i < 3 * kBins; i += kSelThreads) hist[i] = 0u;
-  if (threadIdx.x < n_heads) head_counts[threadIdx.x] = 0;
-  if (threadIdx.x == 0) {
-    long long b = budget;
-    if (budget_dev != nullptr) {
-      const long long d = (long long)*budget_dev;
-      b = d < b ? d : b;
-    }
-    if (b > total) b = total;
-    if (b < 0) b = 0;
-    st->prefix = 0u;
-    st->reserved = 0u;
-    st->need = b;
-    st->budget_eff = b;
-    for (int i = 0; i < 8; ++i) st->ticket[i] = 0u;
-  }
-}
-
-// One radix pass: histogram of digit PASS among the keys whose higher digits equal the prefix
-// found so far; the last workgroup to finish then picks the digit that holds the need-th
-// largest key and updates (prefix, need).
-template <int PASS>
-__global__ void __launch_bounds__(kSelThreads)
-sel_hist_kernel(const float* __restrict__ scores, long long total, unsigned int* __restrict__ hist,
-                SelectState* __restrict__ st) {
-  constexpr int kShift = PASS == 0 ? 21 : (PASS == 1 ? 10 : 0);
-  constexpr int kDigitBits = PASS == 2 ? 10 : 11;
-  constexpr int kNumBins = 1 << kDigitBits;
-  constexpr int kHiShift = kShift + kDigitBits;   // bits above this digit
-  __shared__ unsigned int s_hist[kBins];
-  __shared__ unsigned int s_sum[kSelThreads];
-  unsigned int* ghist = hist + PASS * kBins;
-
-  for (int i = threadIdx.x; i < kNumBins; i += kSelThreads) s_hist[i] = 0u;
-  const unsigned int prefix = PASS == 0 ? 0u : st->prefix;
-  __syncthreads();
-
+// Chunk -> registers: coalesced reads through shared memory, then 16 consecutive entries per lane
+// (flat order inside the workgroup = lane order, which the ordered write needs).
+__device__ __forceinline__ void load_chunk(const float* __restrict__ scores, long long total,
+                                           SelShared& sh, float (&val)[kSelPerThread]) {
   const long long base = (long long)blockIdx.x * kSelChunk;
 #pragma unroll 4
   for (int j = 0; j < kSelPerThread; ++j) {
-    const long long p = base + j * kSelThreads + threadIdx.x;
-    if (p < total) {
-      const unsigned int key = score_key(scores[p]);
-      const bool match = PASS == 0 ? true : ((key >> kHiShift) == prefix);
-      if (match) atomicAdd(&s_hist[(key >> kShift) & (kNumBins - 1)], 1u);
+    const int i = j * kSelThreads + threadIdx.x;
+    const long long p = base + i;
+    sh.val[i + (i >> 6)] = p < total ? scores[p] : 0.0f;
+  }
+  __syncthreads();
+  const int first = threadIdx.x * kSelPerThread;
+#pragma unroll
+  for (int j = 0; j < kSelPerThread; ++j) val[j] = sh.val[first + j + ((first + j) >> 6)];
+  __syncthreads();
+}
+
+template <int PASS> struct Digit {
+  static constexpr int kShift = PASS == 0 ? 21 : (PASS == 1 ? 10 : 0);
+  static constexpr int kBits = PASS == 2 ? 10 : 11;
+  static constexpr int kNum = 1 << kBits;
+  static constexpr int kHiShift = kShift + kBits;
+};
+
+// Histogram of digit PASS over this workgroup's keys that match the prefix; merged into the
+// global histogram with integer atomics.
+template <int PASS>
+__device__ __forceinline__ void hist_phase(const float (&val)[kSelPerThread], long long total,
+                                           unsigned int prefix, SelShared& sh,
+                                           unsigned int* __restrict__ ghist) {
+  using Dg = Digit<PASS>;
+  for (int i = threadIdx.x; i < Dg::kNum; i += kSelThreads) sh.hist[i] = 0u;
+  __syncthreads();
+  const long long p0 = (long long)blockIdx.x * kSelChunk + threadIdx.x * kSelPerThread;
+#pragma unroll
+  for (int j = 0; j < kSelPerThread; ++j) {
+    if (p0 + j < total) {
+      const unsigned int key = score_key(val[j]);
+      const bool match = PASS == 0 ? true : ((key >> Dg::kHiShift) == prefix);
+      if (match) atomicAdd(&sh.hist[(key >> Dg::kShift) & (Dg::kNum - 1)], 1u);
     }
   }
   __syncthreads();
-  for (int i = threadIdx.x; i < kNumBins; i += kSelThreads) {
-    const unsigned int c = s_hist[i];
-    if (c) atomicAdd(&ghist[i], c);
+  for (int i = threadIdx.x; i < Dg::kNum; i += kSelThreads) {
+    const unsigned int c = sh.hist[i];
+    if (c) __hip_atomic_fetch_add(&ghist[i], c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
+}
 
-  if (!last_block_done(&st->ticket[PASS], gridDim.x)) return;
-
-  // ---- digit pick (one workgroup): thread t owns bins [t*per, (t+1)*per), scanned from the top
-  constexpr int kPer = kNumBins / kSelThreads;
+// Digit of the threshold key: the bin, counted from the top, in which the cumulative count
+// reaches `need`.  Every workgroup computes it for itself from the complete global histogram.
+template <int PASS>
+__device__ __forceinline__ Pick pick_phase(const unsigned int* __restrict__ ghist, Pick in,
+                                           SelShared& sh) {
+  using Dg = Digit<PASS>;
+  constexpr int kPer = Dg::kNum / kSelThreads;
+  // thread t owns the bins kNum-1 - t*kPer - j (descending), so a prefix scan over t runs from the top
   unsigned int cnt[kPer];
   unsigned int mine = 0u;
 #pragma unroll
   for (int j = 0; j < kPer; ++j) {
-    cnt[j] = ld_agent(&ghist[threadIdx.x * kPer + j]);
+    cnt[j] = ld_dev(&ghist[Dg::kNum - 1 - (threadIdx.x * kPer + j)]);
     mine += cnt[j];
   }
-  // inclusive suffix sums over threads (Hillis-Steele in LDS)
-  s_sum[threadIdx.x] = mine;
-  __syncthreads();
-  for (int off = 1; off < kSelThreads; off <<= 1) {
-    unsigned int add = (threadIdx.x + off < kSelThreads) ? s_sum[threadIdx.x + off] : 0u;
-    __syncthreads();
-    s_sum[threadIdx.x] += add;
-    __syncthreads();
+  unsigned int incl = mine;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const unsigned int up = __shfl_up(incl, off);
+    if (lane >= off) incl += up;
   }
-  const long long need = st->need;
-  const long long above_me = (long long)s_sum[threadIdx.x] - mine;  // keys in bins owned by higher threads
-  __syncthreads();
-  if (need <= 0) {
-    if (threadIdx.x == 0) st->prefix = (prefix << kDigitBits) | (unsigned int)(kNumBins - 1);
-    return;
+  if (lane == 63) sh.wave[wave] = incl;
+  if (threadIdx.x == 0) {
+    sh.pick_digit = (unsigned int)(Dg::kNum - 1);     // taken when need == 0: nothing matches below
+    sh.pick_need = 0;
   }
-  if (above_me < need && need <= above_me + (long long)mine) {
-    long long above = above_me;
-    for (int j = kPer - 1; j >= 0; --j) {
-      if (need <= above + (long long)cnt[j]) {
-        st->prefix = (prefix << kDigitBits) | (unsigned int)(threadIdx.x * kPer + j);
-        st->need = need - above;
+  __syncthreads();
+  long long above = 0;
+  for (int i = 0; i < wave; ++i) above += sh.wave[i];
+  above += (long long)incl - mine;                     // keys in bins above this thread's bins
+  if (in.need > 0 && above < in.need && in.need <= above + (long long)mine) {
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+      if (in.need <= above + (long long)cnt[j]) {
+        sh.pick_digit = (unsigned int)(Dg::kNum - 1 - (threadIdx.x * kPer + j));
+        sh.pick_need = in.need - above;
         break;
       }
       above += cnt[j];
     }
   }
+  __syncthreads();
+  Pick out;
+  out.prefix = (in.prefix << Dg::kBits) | sh.pick_digit;
+  out.need = sh.pick_need;
+  __syncthreads();
+  return out;
 }
 
-// Per-workgroup counts of keys above / equal to the threshold; the last workgroup turns them
-// into output offsets and the number of threshold-equal entries each workgroup may keep.
-__global__ void __launch_bounds__(kSelThreads)
-sel_count_kernel(const float* __restrict__ scores, long long total, SelectState* __restrict__ st,
-                 unsigned int* __restrict__ blk, int n_blocks) {
-  __shared__ unsigned int s_gt[kSelThreads / 64], s_eq[kSelThreads / 64];
-  __shared__ unsigned long long s_scan[kSelThreads];
-  const unsigned int T = st->prefix;
-  const long long base = (long long)blockIdx.x * kSelChunk;
-  unsigned int gt = 0u, eq = 0u;
-#pragma unroll 4
-  for (int j = 0; j < kSelPerThread; ++j) {
-    const long long p = base + j * kSelThreads + threadIdx.x;
-    if (p < total) {
-      const unsigned int key = score_key(scores[p]);
-      gt += key > T;
-      eq += key == T;
-    }
-  }
-  for (int off = 32; off > 0; off >>= 1) {
-    gt += __shfl_down(gt, off);
-    eq += __shfl_down(eq, off);
-  }
-  const int wave = threadIdx.x >> 6;
-  if ((threadIdx.x & 63) == 0) { s_gt[wave] = gt; s_eq[wave] = eq; }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    unsigned int g = 0u, e = 0u;
-    for (int i = 0; i < kSelThreads / 64; ++i) { g += s_gt[i]; e += s_eq[i]; }
-    blk[blockIdx.x] = g;
-    blk[n_blocks + blockIdx.x] = e;
-  }
-
-  if (!last_block_done(&st->ticket[3], gridDim.x)) return;
-
-  // ---- scan over workgroups (one workgroup): thread t owns a contiguous run of workgroups
-  const long long need = st->need;
-  const int per = (n_blocks + kSelThreads - 1) / kSelThreads;
-  const int b0 = threadIdx.x * per;
-  const int b1 = b0 + per < n_blocks ? b0 + per : n_blocks;
-  unsigned long long sum_gt = 0ull, sum_eq = 0ull;
-  for (int b = b0; b < b1; ++b) {
-    sum_gt += ld_agent(&blk[b]);
-    sum_eq += ld_agent(&blk[n_blocks + b]);
-  }
-  // exclusive prefix of (gt, eq) over threads; both fit 32 bits, packed in one 64-bit word
-  s_scan[threadIdx.x] = (sum_gt << 32) | sum_eq;
-  __syncthreads();
-  for (int off = 1; off < kSelThreads; off <<= 1) {
-    unsigned long long add = (threadIdx.x >= (unsigned)off) ? s_scan[threadIdx.x - off] : 0ull;
-    __syncthreads();
-    s_scan[threadIdx.x] += add;
-    __syncthreads();
-  }
-  const unsigned long long incl = s_scan[threadIdx.x];
-  long long gt_before = (long long)(incl >> 32) - (long long)sum_gt;
-  long long eq_before = (long long)(incl & 0xffffffffull) - (long long)sum_eq;
-  for (int b = b0; b < b1; ++b) {
-    const long long g = ld_agent(&blk[b]);
-    const long long e = ld_agent(&blk[n_blocks + b]);
-    const long long taken_before = eq_before < need ? eq_before : need;
-    blk[2 * n_blocks + b] = (unsigned int)(gt_before + taken_before);   // first output slot
-    blk[3 * n_blocks + b] = (unsigned int)(eq_before < 0xffffffffll ? eq_before : 0xffffffffll);
-    gt_before += g;
-    eq_before += e;
-  }
-}
-
-// Ordered write of the survivors of one chunk.
-__global__ void __launch_bounds__(kSelThreads)
-sel_write_kernel(const float* __restrict__ scores, long long total, int n_heads,
-                 const int64_t* __restrict__ seg_offsets, SelectState* __restrict__ st,
-                 const unsigned int* __restrict__ blk, int n_blocks,
-                 int32_t* __restrict__ head_counts, int64_t* __restrict__ head_offsets,
-                 int32_t* __restrict__ kept_idx, float* __restrict__ kept_scores) {
-  __shared__ float s_val[kSelChunk + 64];
-  __shared__ long long s_off[kMaxHeads + 1];
-  __shared__ unsigned int s_cnt[kMaxHeads];
-  __shared__ unsigned int s_wave[kSelThreads / 64];
-
-  const long long base = (long long)blockIdx.x * kSelChunk;
-  for (int j = 0; j < kSelPerThread; ++j) {
-    const int i = j * kSelThreads + threadIdx.x;
-    const long long p = base + i;
-    s_val[i + (i >> 6)] = p < total ? scores[p] : 0.0f;   // one pad word per 64 against bank clashes
-  }
-  if (threadIdx.x <= n_heads) {
-    const long long seg = total / n_heads;
-    s_off[threadIdx.x] = seg_offsets ? (long long)seg_offsets[threadIdx.x]
-                                     : (threadIdx.x == n_heads ? total : seg * threadIdx.x);
-  }
-  if (threadIdx.x < kMaxHeads) s_cnt[threadIdx.x] = 0u;
-  const unsigned int T = st->prefix;
-  const long long need = st->need;
-  const unsigned int out0 = blk[2 * n_blocks + blockIdx.x];
-  const long long eq0 = (long long)blk[3 * n_blocks + blockIdx.x];
-  __syncthreads();
-
-  // this thread's 16 consecutive entries
-  float val[kSelPerThread];
-  unsigned int gt_mask = 0u, eq_mask = 0u;
-  const int first = threadIdx.x * kSelPerThread;
+// Keys above / equal to the threshold in this workgroup, published for the other workgroups.
+__device__ __forceinline__ void count_phase(const float (&val)[kSelPerThread], long long total,
+                                            unsigned int T, SelShared& sh, unsigned int* __restrict__ blk,
+                                            int n_blocks, unsigned int& gt_mask, unsigned int& eq_mask) {
+  const long long p0 = (long long)blockIdx.x * kSelChunk + threadIdx.x * kSelPerThread;
+  gt_mask = 0u;
+  eq_mask = 0u;
 #pragma unroll
   for (int j = 0; j < kSelPerThread; ++j) {
-    const int i = first + j;
-    val[j] = s_val[i + (i >> 6)];
-    if (base + i < total) {
+    if (p0 + j < total) {
       const unsigned int key = score_key(val[j]);
       gt_mask |= (key > T ? 1u : 0u) << j;
       eq_mask |= (key == T ? 1u : 0u) << j;
     }
   }
+  unsigned int packed = ((unsigned int)__popc(gt_mask) << 16) | (unsigned int)__popc(eq_mask);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) packed += __shfl_xor(packed, off);
+  if ((threadIdx.x & 63) == 0) sh.wave[threadIdx.x >> 6] = packed;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    unsigned int tot = 0u;
+    for (int i = 0; i < kSelThreads / 64; ++i) tot += sh.wave[i];
+    st_dev(&blk[blockIdx.x], tot >> 16);
+    st_dev(&blk[n_blocks + blockIdx.x], tot & 0xffffu);
+  }
+  __syncthreads();
+}
+
+// Sums of (gt, eq) over the workgroups before this one.
+__device__ __forceinline__ void prefix_phase(const unsigned int* __restrict__ blk, int n_blocks,
+                                             SelShared& sh, long long& gt_before, long long& eq_before) {
+  unsigned long long acc = 0ull;   // gt in the high word, eq in the low word (each < 2^31)
+  for (int b = threadIdx.x; b < (int)blockIdx.x; b += kSelThreads)
+    acc += ((unsigned long long)ld_dev(&blk[b]) << 32) | (unsigned long long)ld_dev(&blk[n_blocks + b]);
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+  if ((threadIdx.x & 63) == 0) sh.wave64[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  unsigned long long tot = 0ull;
+  for (int i = 0; i < kSelThreads / 64; ++i) tot += sh.wave64[i];
+  gt_before = (long long)(tot >> 32);
+  eq_before = (long long)(tot & 0xffffffffull);
+  __syncthreads();
+}
+
+// Ordered write of this workgroup's survivors; survivors per head are added to head_counts.
+__device__ __forceinline__ void write_phase(const float (&val)[kSelPerThread], long long total, int n_heads,
+                                            const int64_t* __restrict__ seg_offsets, unsigned int gt_mask,
+                                            unsigned int eq_mask, long long need, long long capacity,
+                                            long long gt_blocks_before, long long eq_blocks_before,
+                                            SelShared& sh, int32_t* __restrict__ head_counts,
+                                            int32_t* __restrict__ kept_idx, float* __restrict__ kept_scores) {
+  if (threadIdx.x <= n_heads) {
+    const long long seg = total / n_heads;
+    sh.off[threadIdx.x] = seg_offsets ? (long long)seg_offsets[threadIdx.x]
+                                      : (threadIdx.x == n_heads ? total : seg * threadIdx.x);
+  }
+  if (threadIdx.x < kMaxHeads) sh.cnt[threadIdx.x] = 0u;
   // exclusive scan of packed (gt << 16 | eq) over the workgroup
   const unsigned int mine = ((unsigned int)__popc(gt_mask) << 16) | (unsigned int)__popc(eq_mask);
   unsigned int incl = mine;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
   for (int off = 1; off < 64; off <<= 1) {
     const unsigned int up = __shfl_up(incl, off);
     if (lane >= off) incl += up;
   }
-  if (lane == 63) s_wave[wave] = incl;
+  if (lane == 63) sh.wave[wave] = incl;
   __syncthreads();
   unsigned int wave_base = 0u;
-  for (int i = 0; i < wave; ++i) wave_base += s_wave[i];
+  for (int i = 0; i < wave; ++i) wave_base += sh.wave[i];
   const unsigned int excl = wave_base + incl - mine;
-  long long gt_before = (long long)(excl >> 16);
-  long long eq_before = eq0 + (long long)(excl & 0xffffu);
+  long long gt_before = gt_blocks_before + (long long)(excl >> 16);
+  long long eq_before = eq_blocks_before + (long long)(excl & 0xffffu);
 
-  // walk the entries in flat order
+  const long long first = (long long)blockIdx.x * kSelChunk + threadIdx.x * kSelPerThread;
   int g = 0;
-  {
-    const long long p0 = base + first;
-    while (g + 1 < n_heads && p0 >= s_off[g + 1]) ++g;
-  }
+  while (g + 1 < n_heads && first >= sh.off[g + 1]) ++g;
   unsigned int local_cnt = 0u;
 #pragma unroll
   for (int j = 0; j < kSelPerThread; ++j) {
-    const long long p = base + first + j;
-    while (g + 1 < n_heads && p >= s_off[g + 1]) {
-      if (local_cnt) atomicAdd(&s_cnt[g], local_cnt);
+    const long long p = first + j;
+    while (g + 1 < n_heads && p >= sh.off[g + 1]) {
+      if (local_cnt) atomicAdd(&sh.cnt[g], local_cnt);
       local_cnt = 0u;
       ++g;
     }
     const bool is_gt = (gt_mask >> j) & 1u;
     const bool is_eq = (eq_mask >> j) & 1u;
-    const bool keep = is_gt || (is_eq && eq_before < need);
-    if (keep) {
-      const long long taken_before = eq_before < need ? eq_before : need;
-      const long long slot = (long long)out0 + gt_before + (taken_before - (eq0 < need ? eq0 : need));
-      kept_idx[slot] = (int32_t)(p - s_off[g]);
-      if (kept_scores) kept_scores[slot] = val[j];
+    if (is_gt || (is_eq && eq_before < need)) {
+      // survivors before this entry in flat order: all larger keys plus the threshold-equal ones taken
+      const long long slot = gt_before + (eq_before < need ? eq_before : need);
+      if (slot < capacity) {
+        kept_idx[slot] = (int32_t)(p - sh.off[g]);
+        if (kept_scores) kept_scores[slot] = val[j];
+      }
       ++local_cnt;
     }
     gt_before += is_gt;
     eq_before += is_eq;
   }
-  if (local_cnt) atomicAdd(&s_cnt[g], local_cnt);
+  if (local_cnt) atomicAdd(&sh.cnt[g], local_cnt);
   __syncthreads();
   if (threadIdx.x < n_heads) {
-    const unsigned int c = s_cnt[threadIdx.x];
-    if (c) atomicAdd(reinterpret_cast<unsigned int*>(&head_counts[threadIdx.x]), c);
+    const unsigned int c = sh.cnt[threadIdx.x];
+    if (c) __hip_atomic_fetch_add(reinterpret_cast<unsigned int*>(&head_counts[threadIdx.x]), c,
+                                  __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
   }
+}
 
-  if (!last_block_done(&st->ticket[4], gridDim.x)) return;
+__device__ __forceinline__ void offsets_phase(int n_heads, const int32_t* __restrict__ head_counts,
+                                              int64_t* __restrict__ head_offsets) {
   if (threadIdx.x == 0) {
     long long acc = 0;
     for (int h = 0; h < n_heads; ++h) {
       head_offsets[h] = acc;
-      acc += (long long)ld_agent(reinterpret_cast<const unsigned int*>(&head_counts[h]));
+      acc += (long long)ld_dev(reinterpret_cast<const unsigned int*>(&head_counts[h]));
     }
     head_offsets[n_heads] = acc;
   }
+}
+
+// Grid-wide barrier of the fused kernel: all of its workgroups are resident (the host checks the
+// grid against the device's capacity), arrivals are counted monotonically, and the wait is
+// bounded: if it ever gives up, the error word is set and the kernel still runs to completion.
+__device__ __forceinline__ void grid_sync(SelectState* __restrict__ st, unsigned int target) {
+  drain_vmem();
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    __hip_atomic_fetch_add(&st->barrier, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    unsigned int spins = 0u;
+    while (ld_dev(&st->barrier) < target) {
+      __builtin_amdgcn_s_sleep(2);
+      if (++spins > kSpinLimit) {
+        st_dev(&st->error, 1u);
+        break;
+      }
+    }
+  }
+  __syncthreads();
+}
+
+__global__ void __launch_bounds__(kSelThreads)
+sel_init_kernel(unsigned int* __restrict__ hist, SelectState* __restrict__ st,
+                int32_t* __restrict__ head_counts, int n_heads) {
+  for (int i = threadIdx.x; i < 3 * kBins; i += kSelThreads) hist[i] = 0u;
+  if (threadIdx.x < n_heads) head_counts[threadIdx.x] = 0;
+  if (threadIdx.x == 0) {
+    st->barrier = 0u;
+    st->error = 0u;
+  }
+}
+
+// The whole selection in one launch.
+__global__ void __launch_bounds__(kSelThreads)
+sel_fused_kernel(const float* __restrict__ scores, long long total, int n_heads,
+                 const int64_t* __restrict__ seg_offsets, long long budget,
+                 const int64_t* __restrict__ budget_dev, unsigned int* __restrict__ hist,
+                 SelectState* __restrict__ st, unsigned int* __restrict__ blk,
+                 int32_t* __restrict__ head_counts, int64_t* __restrict__ head_offsets,
+                 int32_t* __restrict__ kept_idx, float* __restrict__ kept_scores) {
+  __shared__ SelShared sh;
+  const unsigned int nb = gridDim.x;
+  float val[kSelPerThread];
+  load_chunk(scores, total, sh, val);
+  Pick pk;
+  pk.prefix = 0u;
+  pk.need = effective_budget(budget, budget_dev, total);
+
+  hist_phase<0>(val, total, pk.prefix, sh, hist);
+  grid_sync(st, nb);
+  pk = pick_phase<0>(hist, pk, sh);
+  hist_phase<1>(val, total, pk.prefix, sh, hist + kBins);
+  grid_sync(st, 2 * nb);
+  pk = pick_phase<1>(hist + kBins, pk, sh);
+  hist_phase<2>(val, total, pk.prefix, sh, hist + 2 * kBins);
+  grid_sync(st, 3 * nb);
+  pk = pick_phase<2>(hist + 2 * kBins, pk, sh);
+
+  unsigned int gt_mask, eq_mask;
+  count_phase(val, total, pk.prefix, sh, blk, (int)nb, gt_mask, eq_mask);
+  grid_sync(st, 4 * nb);
+  long long gt_before, eq_before;
+  prefix_phase(blk, (int)nb, sh, gt_before, eq_before);
+  write_phase(val, total, n_heads, seg_offsets, gt_mask, eq_mask, pk.need, budget, gt_before, eq_before, sh,
+              head_counts, kept_idx, kept_scores);
+  grid_sync(st, 5 * nb);
+  if (blockIdx.x == 0) offsets_phase(n_heads, head_counts, head_offsets);
+}
+
+// The same phases as separate launches (kernel boundaries take the place of the grid barriers).
+// STEP 0..2: histogram pass STEP; 3: counts; 4: write; 5: head offsets.
+template <int STEP>
+__global__ void __launch_bounds__(kSelThreads)
+sel_step_kernel(const float* __restrict__ scores, long long total, int n_heads,
+                const int64_t* __restrict__ seg_offsets, long long budget,
+                const int64_t* __restrict__ budget_dev, unsigned int* __restrict__ hist,
+                unsigned int* __restrict__ blk, int32_t* __restrict__ head_counts,
+                int64_t* __restrict__ head_offsets, int32_t* __restrict__ kept_idx,
+                float* __restrict__ kept_scores) {
+  __shared__ SelShared sh;
+  if constexpr (STEP == 5) {
+    offsets_phase(n_heads, head_counts, head_offsets);
+    return;
+  } else {
+    const int nb = (int)gridDim.x;
+    float val[kSelPerThread];
+    load_chunk(scores, total, sh, val);
+    Pick pk;
+    pk.prefix = 0u;
+    pk.need = effective_budget(budget, budget_dev, total);
+    if constexpr (STEP >= 1) pk = pick_phase<0>(hist, pk, sh);
+    if constexpr (STEP >= 2) pk = pick_phase<1>(hist + kBins, pk, sh);
+    if constexpr (STEP >= 3) pk = pick_phase<2>(hist + 2 * kBins, pk, sh);
+    if constexpr (STEP <= 2) {
+      hist_phase<STEP>(val, total, pk.prefix, sh, hist + STEP * kBins);
+    } else {
+      unsigned int gt_mask, eq_mask;
+      // counts are recomputed in the write step (cheap) so that both steps share count_phase
+      count_phase(val, total, pk.prefix, sh, blk, nb, gt_mask, eq_mask);
+      if constexpr (STEP == 4) {
+        long long gt_before, eq_before;
+        prefix_phase(blk, nb, sh, gt_before, eq_before);
+        write_phase(val, total, n_heads, seg_offsets, gt_mask, eq_mask, pk.need, budget, gt_before, eq_before,
+                    sh, head_counts, kept_idx, kept_scores);
+      }
+    }
+  }
+}
+
+// Workgroups of the fused kernel that can be resident at once on the current device.
+static int fused_capacity() {
+  static int cached[64];
+  static bool known[64];
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+  if (!known[dev]) {
+    int per_cu = 0, cus = 0;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, sel_fused_kernel, kSelThreads, 0) != hipSuccess ||
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
+      return 0;
+    cached[dev] = per_cu * cus;
+    known[dev] = true;
+  }
+  return cached[dev];
 }
 
 int32_t launch_select(int n_heads, const float* scores, const int64_t* seg_offsets, int64_t total,
@@ -347,27 +443,40 @@ int32_t launch_select(int n_heads, const float* scores, const int64_t* seg_offse
   const dim3 grid(w.n_blocks), block(kSelThreads);
   {
     ProfScope ps(KID_SEL_INIT, s);
-    hipLaunchKernelGGL(sel_init_kernel, dim3(1), block, 0, s, hist, st, head_counts, n_heads,
-                       (long long)total, (long long)budget, budget_dev);
+    hipLaunchKernelGGL(sel_init_kernel, dim3(1), block, 0, s, hist, st, head_counts, n_heads);
   }
-  {
-    ProfScope ps(KID_SEL_HIST, s);
-    hipLaunchKernelGGL(sel_hist_kernel<0>, grid, block, 0, s, scores, (long long)total, hist, st);
-    hipLaunchKernelGGL(sel_hist_kernel<1>, grid, block, 0, s, scores, (long long)total, hist, st);
-    hipLaunchKernelGGL(sel_hist_kernel<2>, grid, block, 0, s, scores, (long long)total, hist, st);
-  }
-  {
-    ProfScope ps(KID_SEL_COUNT, s);
-    hipLaunchKernelGGL(sel_count_kernel, grid, block, 0, s, scores, (long long)total, st, blk,
-                       w.n_blocks);
-  }
-  {
-    ProfScope ps(KID_SEL_WRITE, s);
-    hipLaunchKernelGGL(sel_write_kernel, grid, block, 0, s, scores, (long long)total, n_heads,
-                       seg_offsets, st, blk, w.n_blocks, head_counts, head_offsets, kept_idx,
+  // The fused kernel needs its whole grid resident; a quarter of the device's capacity leaves room
+  // for other work (and another selection) running beside it.
+  if (w.n_blocks <= fused_capacity() / 4) {
+    ProfScope ps(KID_SEL_FUSED, s);
+    hipLaunchKernelGGL(sel_fused_kernel, grid, block, 0, s, scores, (long long)total, n_heads, seg_offsets,
+                       (long long)budget, budget_dev, hist, st, blk, head_counts, head_offsets, kept_idx,
                        kept_scores);
+    return launch_status();
   }
+  ProfScope ps(KID_SEL_STEPS, s);
+#define LAVA_SEL_STEP(STEP, GRID)                                                                       \
+  hipLaunchKernelGGL(sel_step_kernel<STEP>, GRID, block, 0, s, scores, (long long)total, n_heads,       \
+                     seg_offsets, (long long)budget, budget_dev, hist, blk, head_counts, head_offsets,  \
+                     kept_idx, kept_scores)
+  LAVA_SEL_STEP(0, grid);
+  LAVA_SEL_STEP(1, grid);
+  LAVA_SEL_STEP(2, grid);
+  LAVA_SEL_STEP(3, grid);
+  LAVA_SEL_STEP(4, grid);
+  LAVA_SEL_STEP(5, dim3(1));
+#undef LAVA_SEL_STEP
   return launch_status();
+}
+
+int32_t select_error_flag(const void* ws, int64_t total, hipStream_t s, int* flag) {
+  const SelectWorkspace w = make_select_workspace(total);
+  const SelectState* st = reinterpret_cast<const SelectState*>(static_cast<const char*>(ws) + w.off_state);
+  unsigned int host = 0u;
+  if (hipMemcpyAsync(&host, &st->error, sizeof(host), hipMemcpyDeviceToHost, s) != hipSuccess) return LAVA_ERR_HIP;
+  if (hipStreamSynchronize(s) != hipSuccess) return LAVA_ERR_HIP;
+  *flag = (int)host;
+  return LAVA_OK;
 }
 
 }  // namespace lava

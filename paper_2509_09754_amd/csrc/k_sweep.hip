@@ -7,10 +7,12 @@
 //                    rows, max over the query heads of the KV group (Sec. 4.3)
 //
 // The window product is the one dense contraction of the path: per KV head a
-// [G*w] x d_h x N GEMM.  Each wavefront owns 32-key tiles: the tile is read from HBM with fully
-// coalesced 128-bit loads, staged through a wavefront-private, XOR-swizzled LDS buffer into MFMA
-// operand layout, and multiplied against the group's query rows, which stay in registers for the
-// whole sweep.  No workgroup barrier is needed inside the sweep.
+// [G*w] x d_h x N GEMM.  Each wavefront owns 32-key tiles.  A tile travels HBM -> LDS with
+// coalesced 128-bit direct-to-LDS loads (no staging registers) into a wavefront-private ring of
+// XOR-swizzled buffers, several tiles ahead of the one being multiplied; it is then read in MFMA
+// operand layout and multiplied against the group's query rows, which stay in registers for the
+// whole sweep.  The ring is private to the wavefront, so the sweep needs no workgroup barrier:
+// arrival of a tile is a vmcnt wait that leaves the younger tiles in flight.
 //
 // MFMA 32x32 layouts used below (wave64): operand lane l supplies row/column l%32 and k-slice
 // l/32; result register v of lane l is element (8*(v/4) + 4*(l/32) + v%4, l%32).
@@ -19,6 +21,7 @@
 #include <math.h>
 
 #include "common.h"
+#include "xblock.h"
 
 namespace lava {
 
@@ -27,6 +30,11 @@ typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // 16 bytes held in registers
 
 constexpr float kLog2e = 1.4426950408889634f;
+
+// "last workgroup done" tickets in the workspace (zeroed by the first kernel of every call)
+constexpr int kCounterPool = 0;          // poolstat: one ticket
+constexpr int kCounterStats = 8;         // stats: one ticket per (KV head, chunk)
+constexpr int kNumCounters = 8 + 512;
 
 template <int DT> struct Elem;
 template <> struct Elem<LAVA_BF16> { static constexpr int kBytes = 2; };
@@ -50,12 +58,17 @@ __device__ __forceinline__ f32x16 mfma_chunk(const u32x4& a, const u32x4& b, f32
 
 __device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
 
-// Ordering point between LDS writes and reads of one wavefront (its LDS traffic is in order;
-// this only stops the compiler from moving accesses across it).
-__device__ __forceinline__ void wave_lds_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#define LAVA_GLOBAL_AS __attribute__((address_space(1)))
+#define LAVA_LDS_AS __attribute__((address_space(3)))
+
+// Wait until at most N vector-memory operations of this wavefront are still outstanding.  Loads
+// complete in issue order, so this guarantees every load older than the N youngest has landed.
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+  asm volatile("" ::: "memory");
+  __builtin_amdgcn_s_waitcnt((N & 0xF) | (0x7 << 4) | (0xF << 8) | ((N >> 4) << 14));
+  asm volatile("" ::: "memory");
 }
 
 // (m1, z1) (+) (m2, z2) for sums of exp2((x - m) * c2); empty sets are (-inf, 0).
@@ -74,31 +87,40 @@ struct Tile {
   static constexpr int kSteps = kCpr / 2;              // chunk steps (two lane halves per step)
   static constexpr int kLoads = kTileKeys * kCpr / 64; // 128-bit loads per lane per tile
   static constexpr int kTileChunks = kTileKeys * kCpr;
+  static constexpr int kTileBytes = kTileKeys * kRowBytes;
+  static constexpr int kStages = kTileBytes <= 8192 ? 4 : 2;   // ring depth: 32 KiB of LDS per wavefront
 };
 
-// Coalesced read of one 32-key tile (rows beyond n are clamped to the last row; callers mask).
+// Direct-to-LDS read of one 32-key tile into a ring stage (rows beyond n are clamped to the last
+// row; callers mask them).  Instruction i moves 1 KiB: lane l lands at chunk slot i*64 + l of the
+// stage, i.e. row (i*64+l)/kCpr, slot s = (i*64+l)%kCpr, and fetches the row's chunk
+// s ^ (row & 7): the swizzle is applied on the global side because the LDS side is linear.
 template <int DT, int D>
-__device__ __forceinline__ void load_tile(const u32x4* __restrict__ kg, long long tile, long long n,
-                                          int lane, u32x4 (&stage)[Tile<DT, D>::kLoads]) {
+__device__ __forceinline__ void dma_tile(const u32x4* __restrict__ kg, long long tile, long long n,
+                                         int lane, u32x4* stage) {
   using T = Tile<DT, D>;
 #pragma unroll
   for (int i = 0; i < T::kLoads; ++i) {
     const int q = i * 64 + lane;
-    long long key = tile * kTileKeys + q / T::kCpr;
+    const int row = q / T::kCpr, slot = q % T::kCpr;
+    long long key = tile * kTileKeys + row;
     key = key < n ? key : n - 1;
-    stage[i] = kg[key * T::kCpr + (q % T::kCpr)];
+    const u32x4* src = kg + key * T::kCpr + (slot ^ (row & 7));
+    __builtin_amdgcn_global_load_lds((const LAVA_GLOBAL_AS void*)src, (LAVA_LDS_AS void*)(stage + i * 64),
+                                     16, 0, 0);
   }
 }
 
+// Wait for the oldest tile of the ring while `younger` (0 .. kStages-1) tiles stay in flight.
 template <int DT, int D>
-__device__ __forceinline__ void stage_to_lds(u32x4* __restrict__ buf, int lane,
-                                             const u32x4 (&stage)[Tile<DT, D>::kLoads]) {
+__device__ __forceinline__ void wait_tile(int younger) {
   using T = Tile<DT, D>;
-#pragma unroll
-  for (int i = 0; i < T::kLoads; ++i) {
-    const int q = i * 64 + lane;
-    const int row = q / T::kCpr, c = q % T::kCpr;
-    buf[row * T::kCpr + (c ^ (row & 7))] = stage[i];
+  static_assert(T::kStages <= 4, "ring depth");
+  switch (younger) {
+    case 0: wait_vmcnt<0>(); break;
+    case 1: wait_vmcnt<T::kLoads>(); break;
+    case 2: wait_vmcnt<2 * T::kLoads>(); break;
+    default: wait_vmcnt<3 * T::kLoads>(); break;
   }
 }
 
@@ -140,10 +162,12 @@ __device__ __forceinline__ void load_q(const u32x4* __restrict__ qg, int h0, int
 template <int DT, int D, int GT>
 __global__ void __launch_bounds__(kSweepThreads)
 stats_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long long n, int w, int G,
-             int n_chunks, float c2, int tiles_per_block, float2* __restrict__ stat_part) {
+             int n_chunks, float c2, int tiles_per_block, float2* __restrict__ stat_part,
+             float* __restrict__ row_bias, uint32_t* __restrict__ counters) {
   using T = Tile<DT, D>;
-  __shared__ u32x4 s_tile[kSweepThreads / 64][T::kTileChunks];
-  __shared__ float2 s_red[kSweepThreads / 64][GT * 32];
+  __shared__ u32x4 s_tile[kSweepThreads / 64][T::kStages][T::kTileChunks];
+  __shared__ float2 s_red[kSweepThreads / 64][kMaxChunkHeads * 32];   // [wave][head*32+row]; reused as [slice][row] at the end
+  __shared__ unsigned int s_last;
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int g = blockIdx.y / n_chunks, chunk = blockIdx.y % n_chunks;
@@ -167,18 +191,25 @@ stats_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long 
   long long last_visible = n - w + r;           // last key row r may see
   if (last_visible > n - 1) last_visible = n - 1;
 
-  u32x4 stage[T::kLoads];
-  long long tile = t_begin + wave;
-  if (tile < t_end) load_tile<DT, D>(kg, tile, n, lane, stage);
-  u32x4* buf = s_tile[wave];
-  for (; tile < t_end; tile += kSweepThreads / 64) {
-    stage_to_lds<DT, D>(buf, lane, stage);
-    const long long next = tile + kSweepThreads / 64;
-    if (next < t_end) load_tile<DT, D>(kg, next, n, lane, stage);
-    wave_lds_sync();
+  // this wavefront's tiles: t_begin + wave, + 4, ...; ring of kStages buffers, kStages-1 tiles ahead
+  constexpr int kWaves = kSweepThreads / 64;
+  const long long first = t_begin + wave;
+  const int cnt = first < t_end ? (int)((t_end - first + kWaves - 1) / kWaves) : 0;
+  u32x4* ring = s_tile[wave][0];
+#pragma unroll
+  for (int p = 0; p < T::kStages - 1; ++p)
+    if (p < cnt) dma_tile<DT, D>(kg, first + (long long)p * kWaves, n, lane, ring + p * T::kTileChunks);
+  for (int it = 0; it < cnt; ++it) {
+    const long long tile = first + (long long)it * kWaves;
+    const int ahead = it + T::kStages - 1;
+    if (ahead < cnt)
+      dma_tile<DT, D>(kg, first + (long long)ahead * kWaves, n, lane,
+                      ring + (ahead % T::kStages) * T::kTileChunks);
+    const int younger = cnt - 1 - it < T::kStages - 1 ? cnt - 1 - it : T::kStages - 1;
+    wait_tile<DT, D>(younger);
     u32x4 kf[T::kSteps];
-    lds_to_frag<DT, D>(buf, lane, kf);
-    wave_lds_sync();
+    lds_to_frag<DT, D>(ring + (it % T::kStages) * T::kTileChunks, lane, kf);
+    asm volatile("" ::: "memory");   // the next iteration's loads into this ring stay below these reads
 
     const long long key0 = tile * kTileKeys;
     const bool late = key0 + kTileKeys - 1 > n - w;   // some row cannot see some key of this tile
@@ -226,23 +257,58 @@ stats_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long 
       const float2 p = s_red[wv][threadIdx.x];
       merge_stat(m, z, p.x, p.y, c2);
     }
-    stat_part[((long long)blockIdx.y * gridDim.x + blockIdx.x) * (GT * 32) + threadIdx.x] =
-        make_float2(m, z);
+    st_dev_f2(&stat_part[((long long)blockIdx.y * gridDim.x + blockIdx.x) * (GT * 32) + threadIdx.x], m, z);
+  }
+
+  // The last workgroup of this (KV head, chunk) to finish merges all partials, always in
+  // workgroup-index order (deterministic), into the exponent bias of every (head, row):
+  // log2 of the row's softmax normaliser in the exp2 domain.
+  if (!arrive_last(&counters[kCounterStats + blockIdx.y], gridDim.x, &s_last)) return;
+  // 256 threads: thread (row, slice) merges its slice of the partials in workgroup order with
+  // independent loads, then the slices are merged in slice order.
+  constexpr int kRows = GT * 32;
+  constexpr int kSlices = kSweepThreads / kRows;
+  const int row = threadIdx.x % kRows, slice = threadIdx.x / kRows;
+  const int nb = gridDim.x;
+  const int per = (nb + kSlices - 1) / kSlices;
+  const int b_begin = slice * per, b_end = (b_begin + per < nb) ? b_begin + per : nb;
+  const float2* part = stat_part + (long long)blockIdx.y * nb * kRows + row;
+  float m = -INFINITY, z = 0.0f;
+  for (int b0 = b_begin; b0 < b_end; b0 += 16) {
+    float2 x[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u)
+      x[u] = (b0 + u < b_end) ? ld_dev_f2(&part[(long long)(b0 + u) * kRows]) : make_float2(-INFINITY, 0.0f);
+#pragma unroll
+    for (int u = 0; u < 16; ++u) merge_stat(m, z, x[u].x, x[u].y, c2);
+  }
+  __syncthreads();                       // s_red is free again: every slice result goes there
+  float2* fin = &s_red[0][0];            // [kSlices][kRows], kSlices * kRows == 256 entries
+  fin[slice * kRows + row] = make_float2(m, z);
+  __syncthreads();
+  if (threadIdx.x < kRows) {
+    m = -INFINITY; z = 0.0f;
+#pragma unroll
+    for (int sl = 0; sl < kSlices; ++sl) {
+      const float2 x = fin[sl * kRows + threadIdx.x];
+      merge_stat(m, z, x.x, x.y, c2);
+    }
+    row_bias[(long long)blockIdx.y * kRows + threadIdx.x] = m * c2 + log2f(z);
   }
 }
 
 // ------------------------------------------------------------------------------------------
 // scores: s_raw[g, i] = max over the heads h of group g of (1/w) sum_r softmax_r[h, i], i < n'.
-// The normaliser of each (head, row) is merged from the stats partials by every workgroup in the
-// same fixed order (deterministic), or taken from a caller-supplied log-sum-exp.
+// The normaliser of each (head, row) comes from the stats kernel's merged exponent bias, or from a
+// caller-supplied log-sum-exp.
 // ------------------------------------------------------------------------------------------
 template <int DT, int D, int GT>
 __global__ void __launch_bounds__(kSweepThreads)
 scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long long n, int w, int G,
-              int n_chunks, float c2, int tiles_per_block, const float2* __restrict__ stat_part,
-              int stat_blocks, const float* __restrict__ lse, float* __restrict__ s_raw) {
+              int n_chunks, float c2, int tiles_per_block, const float* __restrict__ row_bias,
+              const float* __restrict__ lse, float* __restrict__ s_raw) {
   using T = Tile<DT, D>;
-  __shared__ u32x4 s_tile[kSweepThreads / 64][T::kTileChunks];
+  __shared__ u32x4 s_tile[kSweepThreads / 64][T::kStages][T::kTileChunks];
   __shared__ float s_bias[GT * 32];
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
@@ -257,17 +323,8 @@ scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long
     const int t = threadIdx.x >> 5, rr = threadIdx.x & 31;
     float bias = INFINITY;
     if (t < nh && rr < w) {
-      if (lse != nullptr) {
-        bias = lse[(long long)(h0 + t) * w + rr] * kLog2e;
-      } else {
-        float m = -INFINITY, z = 0.0f;
-        const float2* p = stat_part + (long long)blockIdx.y * stat_blocks * (GT * 32) + threadIdx.x;
-        for (int b = 0; b < stat_blocks; ++b) {
-          const float2 x = p[(long long)b * (GT * 32)];
-          merge_stat(m, z, x.x, x.y, c2);
-        }
-        bias = m * c2 + log2f(z);
-      }
+      bias = (lse != nullptr) ? lse[(long long)(h0 + t) * w + rr] * kLog2e
+                              : row_bias[(long long)blockIdx.y * (GT * 32) + threadIdx.x];
       bias += log2f((float)w);
     }
     s_bias[threadIdx.x] = bias;
@@ -289,18 +346,25 @@ scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long
   long long t_end = t_begin + tiles_per_block;
   if (t_end > n_tiles) t_end = n_tiles;
 
-  u32x4 stage[T::kLoads];
-  long long tile = t_begin + wave;
-  if (tile < t_end) load_tile<DT, D>(kg, tile, n, lane, stage);
-  u32x4* buf = s_tile[wave];
-  for (; tile < t_end; tile += kSweepThreads / 64) {
-    stage_to_lds<DT, D>(buf, lane, stage);
-    const long long next = tile + kSweepThreads / 64;
-    if (next < t_end) load_tile<DT, D>(kg, next, n, lane, stage);
-    wave_lds_sync();
+  // this wavefront's tiles: t_begin + wave, + 4, ...; ring of kStages buffers, kStages-1 tiles ahead
+  constexpr int kWaves = kSweepThreads / 64;
+  const long long first = t_begin + wave;
+  const int cnt = first < t_end ? (int)((t_end - first + kWaves - 1) / kWaves) : 0;
+  u32x4* ring = s_tile[wave][0];
+#pragma unroll
+  for (int p = 0; p < T::kStages - 1; ++p)
+    if (p < cnt) dma_tile<DT, D>(kg, first + (long long)p * kWaves, n, lane, ring + p * T::kTileChunks);
+  for (int it = 0; it < cnt; ++it) {
+    const long long tile = first + (long long)it * kWaves;
+    const int ahead = it + T::kStages - 1;
+    if (ahead < cnt)
+      dma_tile<DT, D>(kg, first + (long long)ahead * kWaves, n, lane,
+                      ring + (ahead % T::kStages) * T::kTileChunks);
+    const int younger = cnt - 1 - it < T::kStages - 1 ? cnt - 1 - it : T::kStages - 1;
+    wait_tile<DT, D>(younger);
     u32x4 kf[T::kSteps];
-    lds_to_frag<DT, D>(buf, lane, kf);
-    wave_lds_sync();
+    lds_to_frag<DT, D>(ring + (it % T::kStages) * T::kTileChunks, lane, kf);
+    asm volatile("" ::: "memory");   // the next iteration's loads into this ring stay below these reads
 
     float best = 0.0f;
 #pragma unroll
@@ -354,7 +418,8 @@ __global__ void __launch_bounds__(kVnormThreads)
 vnorm_kernel(const u32x4* __restrict__ v, long long n, long long rows_per_block,
              float* __restrict__ vnorm_part, uint32_t* __restrict__ counters) {
   __shared__ float s_max[kVnormThreads / 64];
-  if (blockIdx.x == 0 && blockIdx.y == 0 && threadIdx.x < 8) counters[threadIdx.x] = 0u;
+  if (blockIdx.x == 0 && blockIdx.y == 0)
+    for (int i = threadIdx.x; i < kNumCounters; i += kVnormThreads) counters[i] = 0u;
   const int g = blockIdx.y;
   const u32x4* vg = v + (long long)g * n * LPR;
   const long long row_begin = (long long)blockIdx.x * rows_per_block;
@@ -454,19 +519,27 @@ poolstat_kernel(const float* __restrict__ s_raw, long long n, int w, int pool_ha
   if (threadIdx.x == 0) {
     double S = 0.0, Tt = 0.0;
     for (int i = 0; i < kPoolThreads / 64; ++i) { S += s_s[i]; Tt += s_t[i]; }
-    ent_part[blockIdx.y * gridDim.x + blockIdx.x] = make_double2(S, Tt);
-    __threadfence();
-    const unsigned int ticket = atomicAdd(&counters[0], 1u);
-    s_last = (ticket == n_blocks - 1) ? 1u : 0u;
+    double2* mine = &ent_part[blockIdx.y * gridDim.x + blockIdx.x];
+    st_dev_f64(&mine->x, S);
+    st_dev_f64(&mine->y, Tt);
+  }
+  if (!arrive_last(&counters[kCounterPool], n_blocks, &s_last)) return;
+  // last workgroup: thread t sums partials t, t + 256, ... then the same fixed tree as above
+  double S = 0.0, Tt = 0.0;
+  for (unsigned int i = threadIdx.x; i < n_blocks; i += kPoolThreads) {
+    S += ld_dev_f64(&ent_part[i].x);
+    Tt += ld_dev_f64(&ent_part[i].y);
+  }
+  for (int off = 32; off > 0; off >>= 1) {
+    S += __shfl_xor(S, off);
+    Tt += __shfl_xor(Tt, off);
   }
   __syncthreads();
-  if (s_last == 0u || threadIdx.x != 0) return;
-  __threadfence();
-  double S = 0.0, Tt = 0.0;
-  for (unsigned int i = 0; i < n_blocks; ++i) {
-    S += __hip_atomic_load(&ent_part[i].x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    Tt += __hip_atomic_load(&ent_part[i].y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
+  if ((threadIdx.x & 63) == 0) { s_s[threadIdx.x >> 6] = S; s_t[threadIdx.x >> 6] = Tt; }
+  __syncthreads();
+  if (threadIdx.x != 0) return;
+  S = 0.0; Tt = 0.0;
+  for (int i = 0; i < kPoolThreads / 64; ++i) { S += s_s[i]; Tt += s_t[i]; }
   double e = 0.0;
   if (S > 0.0) e = (log(S) - Tt / S) / ((double)gridDim.y * (double)n_prefix);
   layer_stat[0] = (float)e;
@@ -518,8 +591,10 @@ ScoreWorkspace make_score_workspace(const lava_layer_desc& d, int64_t n) {
   off += align_up(sizeof(float) * (size_t)d.n_kv_heads * (size_t)(n - d.window));
   w.off_ent_part = off;
   off += align_up(sizeof(double2) * (size_t)d.n_kv_heads * pool_blocks(d, n));
+  w.off_row_bias = off;
+  off += align_up(sizeof(float) * (size_t)d.n_kv_heads * p.n_chunks * p.chunk_heads * 32);
   w.off_counter = off;
-  off += align_up(sizeof(uint32_t) * 8);
+  off += align_up(sizeof(uint32_t) * kNumCounters);
   w.bytes = off;
   return w;
 }
@@ -568,7 +643,9 @@ static float exp2_scale(const lava_layer_desc& d) {
   } while (0)
 
 int32_t launch_stats(const lava_layer_desc& d, int64_t n, const void* q_win, const void* k,
-                     float2* stat_part, const SweepPlan& p, hipStream_t s) {
+                     float2* stat_part, float* row_bias, uint32_t* counters, const SweepPlan& p,
+                     hipStream_t s) {
+  if (d.n_kv_heads * p.n_chunks > kNumCounters - kCounterStats) return LAVA_ERR_SHAPE;
   const int G = d.n_q_heads / d.n_kv_heads;
   const dim3 grid(p.blocks_x, d.n_kv_heads * p.n_chunks), block(kSweepThreads);
   const float c2 = exp2_scale(d);
@@ -576,14 +653,15 @@ int32_t launch_stats(const lava_layer_desc& d, int64_t n, const void* q_win, con
 #define LAVA_STATS(DTV, DV, GTV)                                                              \
   hipLaunchKernelGGL((stats_kernel<DTV, DV, GTV>), grid, block, 0, s,                         \
                      static_cast<const u32x4*>(q_win), static_cast<const u32x4*>(k),          \
-                     (long long)n, d.window, G, p.n_chunks, c2, p.tiles_per_block, stat_part)
+                     (long long)n, d.window, G, p.n_chunks, c2, p.tiles_per_block, stat_part,    \
+                     row_bias, counters)
   LAVA_SWEEP_DISPATCH(LAVA_STATS);
 #undef LAVA_STATS
   return launch_status();
 }
 
 int32_t launch_scores(const lava_layer_desc& d, int64_t n, const void* q_win, const void* k,
-                      const float2* stat_part, const float* lse, float* s_raw, const SweepPlan& p,
+                      const float* row_bias, const float* lse, float* s_raw, const SweepPlan& p,
                       hipStream_t s) {
   const int G = d.n_q_heads / d.n_kv_heads;
   const dim3 grid(p.blocks_x, d.n_kv_heads * p.n_chunks), block(kSweepThreads);
@@ -599,8 +677,8 @@ int32_t launch_scores(const lava_layer_desc& d, int64_t n, const void* q_win, co
 #define LAVA_SCORES(DTV, DV, GTV)                                                             \
   hipLaunchKernelGGL((scores_kernel<DTV, DV, GTV>), grid, block, 0, s,                        \
                      static_cast<const u32x4*>(q_win), static_cast<const u32x4*>(k),          \
-                     (long long)n, d.window, G, p.n_chunks, c2, p.tiles_per_block, stat_part, \
-                     p.blocks_x, lse, s_raw)
+                     (long long)n, d.window, G, p.n_chunks, c2, p.tiles_per_block, row_bias,  \
+                     lse, s_raw)
   LAVA_SWEEP_DISPATCH(LAVA_SCORES);
 #undef LAVA_SCORES
   return launch_status();

@@ -19,8 +19,7 @@ struct ProfState {
 } g_prof;
 
 const char* const kKernelNames[KID_COUNT] = {
-    "vnorm", "stats", "scores", "poolstat", "sel_init", "sel_hist", "sel_count", "sel_write",
-    "compact", "budgets"};
+    "vnorm", "stats", "scores", "poolstat", "sel_init", "sel_fused", "sel_steps", "compact", "budgets"};
 
 void prof_collect() {
   (void)hipDeviceSynchronize();
@@ -142,14 +141,15 @@ int32_t lava_window_scores(const lava_layer_desc* desc, int32_t batch, const int
     float* s_raw = reinterpret_cast<float*>(ws + w.off_sraw);
     double2* ent_part = reinterpret_cast<double2*>(ws + w.off_ent_part);
     uint32_t* counters = reinterpret_cast<uint32_t*>(ws + w.off_counter);
+    float* row_bias = reinterpret_cast<float*>(ws + w.off_row_bias);
 
     st = launch_vnorm(d, n, vb, vnorm_part, counters, plan, s);
     if (st != LAVA_OK) return st;
     if (lse_b == nullptr) {
-      st = launch_stats(d, n, qb, kb, stat_part, plan, s);
+      st = launch_stats(d, n, qb, kb, stat_part, row_bias, counters, plan, s);
       if (st != LAVA_OK) return st;
     }
-    st = launch_scores(d, n, qb, kb, stat_part, lse_b, s_raw, plan, s);
+    st = launch_scores(d, n, qb, kb, row_bias, lse_b, s_raw, plan, s);
     if (st != LAVA_OK) return st;
     st = launch_poolstat(d, n, s_raw, vnorm_part, plan.vnorm_blocks, sc, vbar + (size_t)b * d.n_kv_heads,
                          layer_stat + b, ent_part, counters, s);
@@ -195,6 +195,15 @@ int32_t lava_select_topk(int32_t n_heads, const float* scores, const int64_t* se
   return launch_select(n_heads, scores, seg_offsets, total_entries, budget, budget_dev, head_counts,
                        head_offsets, kept_idx, kept_scores, workspace,
                        static_cast<hipStream_t>(hip_stream));
+}
+
+int32_t lava_select_status(const void* workspace, int64_t total_entries, void* hip_stream) {
+  if (workspace == nullptr || total_entries < 1 || total_entries >= (int64_t)1 << 31)
+    return LAVA_ERR_INVALID_ARG;
+  int flag = 0;
+  const int32_t st = select_error_flag(workspace, total_entries, static_cast<hipStream_t>(hip_stream), &flag);
+  if (st != LAVA_OK) return st;
+  return flag ? LAVA_ERR_HIP : LAVA_OK;
 }
 
 int32_t lava_compact_kv(const lava_layer_desc* desc, int64_t n, const void* k, const void* v,

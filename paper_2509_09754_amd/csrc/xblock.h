@@ -1,0 +1,58 @@
+// Exchange of small results between workgroups of one kernel without cache-wide fences.
+//
+// A device-scope release fence writes back the whole L2 of the issuing XCD; issued by every
+// workgroup of a large grid those write-backs serialise and dominate a bandwidth kernel.  The
+// helpers below avoid that: values meant for other workgroups are written with device-scope
+// atomic stores (write-through), the writer waits until its own stores have completed
+// (vmcnt == 0) before it takes a ticket, and readers use device-scope atomic loads, which do not
+// hit in caches that are not coherent across XCDs.  Nothing else is exchanged this way.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+namespace lava {
+
+__device__ __forceinline__ void st_dev(unsigned int* p, unsigned int v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_dev(unsigned long long* p, unsigned long long v) {
+  __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned int ld_dev(const unsigned int* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ unsigned long long ld_dev(const unsigned long long* p) {
+  return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st_dev_f2(float2* p, float a, float b) {
+  st_dev(reinterpret_cast<unsigned long long*>(p),
+         (unsigned long long)__float_as_uint(a) | ((unsigned long long)__float_as_uint(b) << 32));
+}
+__device__ __forceinline__ float2 ld_dev_f2(const float2* p) {
+  const unsigned long long r = ld_dev(reinterpret_cast<const unsigned long long*>(p));
+  return make_float2(__uint_as_float((unsigned int)(r & 0xffffffffull)), __uint_as_float((unsigned int)(r >> 32)));
+}
+__device__ __forceinline__ void st_dev_f64(double* p, double v) {
+  st_dev(reinterpret_cast<unsigned long long*>(p), (unsigned long long)__double_as_longlong(v));
+}
+__device__ __forceinline__ double ld_dev_f64(const double* p) {
+  return __longlong_as_double((long long)ld_dev(reinterpret_cast<const unsigned long long*>(p)));
+}
+
+// Every vector-memory operation this lane has issued is complete once this returns.
+__device__ __forceinline__ void drain_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
+// Ticket of a workgroup that has published its results with st_dev.  Returns true, in every
+// thread, for the workgroup that arrives last.  `s_flag` is a word of shared memory.
+__device__ __forceinline__ bool arrive_last(unsigned int* ticket, unsigned int n_groups, unsigned int* s_flag) {
+  drain_vmem();
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const unsigned int t = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    *s_flag = (t == n_groups - 1) ? 1u : 0u;
+  }
+  __syncthreads();
+  return *s_flag != 0u;
+}
+
+}  // namespace lava

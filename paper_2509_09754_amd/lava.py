@@ -21,9 +21,10 @@ LAVA_F32, LAVA_BF16 = 0, 1
 
 EXPORTS = [
     "lava_status_string", "lava_window_scores_workspace_bytes", "lava_window_scores",
-    "lava_layer_budgets", "lava_select_workspace_bytes", "lava_select_topk", "lava_compact_kv",
+    "lava_layer_budgets", "lava_select_workspace_bytes", "lava_select_topk", "lava_select_status",
+    "lava_compact_kv",
     "lava_prof_kernel_count", "lava_prof_kernel_name", "lava_prof_enable", "lava_prof_reset",
-    "lava_prof_read",
+    "lava_prof_read", "lava_probe_stream",
 ]
 
 
@@ -71,6 +72,8 @@ def _load() -> ctypes.CDLL:
     lib.lava_select_workspace_bytes.argtypes = [i64]
     lib.lava_select_topk.restype = i32
     lib.lava_select_topk.argtypes = [i32, vp, vp, i64, i64, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.lava_select_status.restype = i32
+    lib.lava_select_status.argtypes = [vp, i64, vp]
     lib.lava_compact_kv.restype = i32
     lib.lava_compact_kv.argtypes = [dp, i64, vp, vp, vp, vp, i64, vp, vp, vp]
     lib.lava_prof_kernel_count.restype = i32
@@ -81,6 +84,8 @@ def _load() -> ctypes.CDLL:
     lib.lava_prof_reset.restype = i32
     lib.lava_prof_read.restype = i32
     lib.lava_prof_read.argtypes = [i32, ctypes.POINTER(ctypes.c_double), ctypes.POINTER(ctypes.c_int64)]
+    lib.lava_probe_stream.restype = i32
+    lib.lava_probe_stream.argtypes = [vp, vp, i64, i32, i32, vp]
     return lib
 
 
@@ -227,6 +232,11 @@ def lava_select_topk(n_heads: int, scores: torch.Tensor, budget: int, seg_offset
     return head_counts, head_offsets, kept_idx, kept_scores
 
 
+def lava_select_status(workspace: torch.Tensor, total_entries: int, stream=None) -> int:
+    """Synchronises; LAVA_OK, or LAVA_ERR_HIP if the selection's bounded barrier wait gave up."""
+    return int(lib.lava_select_status(_ptr(workspace), int(total_entries), _stream(stream)))
+
+
 def lava_compact_kv(desc: LayerDesc, n: int, k: torch.Tensor, v: torch.Tensor, head_offsets: torch.Tensor,
                     kept_idx: torch.Tensor, capacity: int, k_out=None, v_out=None, stream=None):
     _dev(k, "k", desc.torch_dtype), _dev(v, "v", desc.torch_dtype)
@@ -258,6 +268,12 @@ def prof_read() -> dict:
         lib.lava_prof_read(i, ctypes.byref(ms), ctypes.byref(cnt))
         out[lib.lava_prof_kernel_name(i).decode()] = (ms.value, cnt.value)
     return out
+
+
+def probe_stream(src: torch.Tensor, dst: torch.Tensor, nbytes: int, mode: int, blocks: int = 2048, stream=None):
+    """mode 0: copy nbytes from src to dst; mode 1: read nbytes of src."""
+    _check(lib.lava_probe_stream(_ptr(src), _ptr(dst), int(nbytes), int(mode), int(blocks), _stream(stream)),
+           "lava_probe_stream")
 
 
 def evict_layer(desc: LayerDesc, n: int, q_win, k, v, budget: int, lse=None, stream=None):

@@ -89,6 +89,8 @@ def test_select_and_compact_argument_errors():
     assert call(8, 1024, 10, wsb=8) == lava.LAVA_ERR_WORKSPACE
     assert lava.lava_select_workspace_bytes(1 << 20) >= 3 * 2048 * 4
     assert lava.lava_select_workspace_bytes(0) == 0
+    assert L.lava_select_status(None, 1024, None) == lava.LAVA_ERR_INVALID_ARG
+    assert L.lava_select_status(FAKE, 0, None) == lava.LAVA_ERR_INVALID_ARG
     d = _desc()
     cc = lambda n, cap, k=FAKE: L.lava_compact_kv(ctypes.byref(d), n, k, FAKE, FAKE, FAKE, cap, FAKE, FAKE, None)
     assert cc(1024, 8 * 1024 + 1) == lava.LAVA_ERR_BUDGET

@@ -121,6 +121,25 @@ def test_select_large_flat_array(lava):
     check_select(lava, full, 8, 8 * 131072 - 5)
 
 
+def test_select_beyond_resident_grid_uses_separate_launches(lava):
+    # 2.4 M entries need more workgroups than the single-launch selection may keep resident, so
+    # the same phases run as separate kernels; the result must not change.
+    say("select 8 x 300000 (multi-launch path)")
+    n = 300000
+    s = synth.random_scores(8, n - 32, 22)
+    full = O.flat_layer_scores(s.astype(np.float64), n).astype(np.float32)
+    check_select(lava, full, 8, 8 * 1024)
+    check_select(lava, full, 8, 1_000_003)
+
+
+def test_select_status_reports_ok(lava):
+    say("select status")
+    sc = torch.from_numpy(synth.random_scores(4, 5000, 23).ravel()).cuda()
+    ws = torch.empty(lava.lava_select_workspace_bytes(sc.numel()), dtype=torch.uint8, device="cuda")
+    lava.lava_select_topk(4, sc, 777, workspace=ws)
+    assert lava.lava_select_status(ws, sc.numel()) == lava.LAVA_OK
+
+
 # ------------------------------------------------------------------------------ compaction
 @pytest.mark.parametrize("dtype,d", [("bf16", 128), ("f32", 64), ("bf16", 64), ("f32", 128)])
 def test_compact_bit_exact(lava, dtype, d):
