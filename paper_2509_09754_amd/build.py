@@ -25,6 +25,8 @@ COMMON_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
     # packed-FP32 VALU forms are kept out of the generated code on the test machines
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+    # MFMA results go straight to VGPRs (no v_accvgpr_read per accumulator element in the epilogues)
+    "-mllvm", "-amdgpu-mfma-vgpr-form",
 ]
 
 

@@ -10,7 +10,7 @@
 // concatenated, ascending position inside each head".
 //
 // The whole selection is latency-bound (a few MiB of scores), so it runs as ONE kernel whose
-// workgroups keep their 4096 scores in registers and meet at five grid-wide barriers; every
+// workgroups (1024 lanes, 16 scores per lane in registers) meet at five grid-wide barriers; every
 // workgroup derives the digit picks and its output offset redundantly from the shared
 // histograms / per-workgroup counts, so no workgroup waits for a "leader".  Inputs too large for
 // all workgroups to be resident at once fall back to the same phases as separate kernels.
@@ -19,7 +19,7 @@
 
 namespace lava {
 
-constexpr int kSelThreads = 256;
+constexpr int kSelThreads = 1024;   // few, large workgroups: grid-wide barriers and histogram merges cost per workgroup
 constexpr int kSelPerThread = 16;
 constexpr int kSelChunk = kSelThreads * kSelPerThread;  // entries per workgroup
 constexpr int kBins = 2048;
@@ -88,11 +88,16 @@ __device__ __forceinline__ long long effective_budget(long long budget, const in
 __device__ __forceinline__ void load_chunk(const float* __restrict__ scores, long long total,
                                            SelShared& sh, float (&val)[kSelPerThread]) {
   const long long base = (long long)blockIdx.x * kSelChunk;
-#pragma unroll 4
+  float tmp[kSelPerThread];
+#pragma unroll
+  for (int j = 0; j < kSelPerThread; ++j) {        // all loads in flight before the first use
+    const long long p = base + j * kSelThreads + threadIdx.x;
+    tmp[j] = p < total ? scores[p] : 0.0f;
+  }
+#pragma unroll
   for (int j = 0; j < kSelPerThread; ++j) {
     const int i = j * kSelThreads + threadIdx.x;
-    const long long p = base + i;
-    sh.val[i + (i >> 6)] = p < total ? scores[p] : 0.0f;
+    sh.val[i + (i >> 6)] = tmp[j];
   }
   __syncthreads();
   const int first = threadIdx.x * kSelPerThread;
@@ -118,14 +123,25 @@ __device__ __forceinline__ void hist_phase(const float (&val)[kSelPerThread], lo
   for (int i = threadIdx.x; i < Dg::kNum; i += kSelThreads) sh.hist[i] = 0u;
   __syncthreads();
   const long long p0 = (long long)blockIdx.x * kSelChunk + threadIdx.x * kSelPerThread;
+  // neighbouring entries mostly share a digit (pooling makes plateaus, magnitudes vary slowly), so a
+  // lane adds one count per run of equal digits instead of one per entry
+  unsigned int run_digit = 0xffffffffu, run_len = 0u;
 #pragma unroll
   for (int j = 0; j < kSelPerThread; ++j) {
+    unsigned int digit = 0xffffffffu;
     if (p0 + j < total) {
       const unsigned int key = score_key(val[j]);
       const bool match = PASS == 0 ? true : ((key >> Dg::kHiShift) == prefix);
-      if (match) atomicAdd(&sh.hist[(key >> Dg::kShift) & (Dg::kNum - 1)], 1u);
+      if (match) digit = (key >> Dg::kShift) & (Dg::kNum - 1);
     }
+    if (digit != run_digit) {
+      if (run_len != 0u && run_digit != 0xffffffffu) atomicAdd(&sh.hist[run_digit], run_len);
+      run_digit = digit;
+      run_len = 0u;
+    }
+    ++run_len;
   }
+  if (run_digit != 0xffffffffu) atomicAdd(&sh.hist[run_digit], run_len);
   __syncthreads();
   for (int i = threadIdx.x; i < Dg::kNum; i += kSelThreads) {
     const unsigned int c = sh.hist[i];
@@ -309,11 +325,12 @@ __device__ __forceinline__ void offsets_phase(int n_heads, const int32_t* __rest
 // Grid-wide barrier of the fused kernel: all of its workgroups are resident (the host checks the
 // grid against the device's capacity), arrivals are counted monotonically, and the wait is
 // bounded: if it ever gives up, the error word is set and the kernel still runs to completion.
-__device__ __forceinline__ void grid_sync(SelectState* __restrict__ st, unsigned int target) {
+__device__ __forceinline__ void grid_sync(SelectState* __restrict__ st, unsigned int round) {
   drain_vmem();
   __syncthreads();
   if (threadIdx.x == 0) {
     __hip_atomic_fetch_add(&st->barrier, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned int target = round * gridDim.x;
     unsigned int spins = 0u;
     while (ld_dev(&st->barrier) < target) {
       __builtin_amdgcn_s_sleep(2);
@@ -354,23 +371,23 @@ sel_fused_kernel(const float* __restrict__ scores, long long total, int n_heads,
   pk.need = effective_budget(budget, budget_dev, total);
 
   hist_phase<0>(val, total, pk.prefix, sh, hist);
-  grid_sync(st, nb);
+  grid_sync(st, 1u);
   pk = pick_phase<0>(hist, pk, sh);
   hist_phase<1>(val, total, pk.prefix, sh, hist + kBins);
-  grid_sync(st, 2 * nb);
+  grid_sync(st, 2u);
   pk = pick_phase<1>(hist + kBins, pk, sh);
   hist_phase<2>(val, total, pk.prefix, sh, hist + 2 * kBins);
-  grid_sync(st, 3 * nb);
+  grid_sync(st, 3u);
   pk = pick_phase<2>(hist + 2 * kBins, pk, sh);
 
   unsigned int gt_mask, eq_mask;
   count_phase(val, total, pk.prefix, sh, blk, (int)nb, gt_mask, eq_mask);
-  grid_sync(st, 4 * nb);
+  grid_sync(st, 4u);
   long long gt_before, eq_before;
   prefix_phase(blk, (int)nb, sh, gt_before, eq_before);
   write_phase(val, total, n_heads, seg_offsets, gt_mask, eq_mask, pk.need, budget, gt_before, eq_before, sh,
               head_counts, kept_idx, kept_scores);
-  grid_sync(st, 5 * nb);
+  grid_sync(st, 5u);
   if (blockIdx.x == 0) offsets_phase(n_heads, head_counts, head_offsets);
 }
 
@@ -445,9 +462,9 @@ int32_t launch_select(int n_heads, const float* scores, const int64_t* seg_offse
     ProfScope ps(KID_SEL_INIT, s);
     hipLaunchKernelGGL(sel_init_kernel, dim3(1), block, 0, s, hist, st, head_counts, n_heads);
   }
-  // The fused kernel needs its whole grid resident; a quarter of the device's capacity leaves room
+  // The fused kernel needs its whole grid resident; half of the device's capacity leaves room
   // for other work (and another selection) running beside it.
-  if (w.n_blocks <= fused_capacity() / 4) {
+  if (w.n_blocks <= fused_capacity() / 2) {
     ProfScope ps(KID_SEL_FUSED, s);
     hipLaunchKernelGGL(sel_fused_kernel, grid, block, 0, s, scores, (long long)total, n_heads, seg_offsets,
                        (long long)budget, budget_dev, hist, st, blk, head_counts, head_offsets, kept_idx,

@@ -19,6 +19,7 @@
 //   stats  : D = K_tile * Q^T  -> a lane holds 16 keys of ONE query row: row reductions stay in-lane
 //   scores : D = Q * K_tile^T  -> a lane holds 16 query rows of ONE key: the window mean stays in-lane
 #include <math.h>
+#include <stdlib.h>
 
 #include "common.h"
 #include "xblock.h"
@@ -32,9 +33,9 @@ typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // 16 bytes he
 constexpr float kLog2e = 1.4426950408889634f;
 
 // "last workgroup done" tickets in the workspace (zeroed by the first kernel of every call)
-constexpr int kCounterPool = 0;          // poolstat: one ticket
-constexpr int kCounterStats = 8;         // stats: one ticket per (KV head, chunk)
-constexpr int kNumCounters = 8 + 512;
+constexpr int kCounterPool = 0;                         // poolstat: one two-level ticket
+constexpr int kCounterStats = kArriveWords;             // stats: one two-level ticket per (KV head, chunk)
+constexpr int kMaxStatTickets = 512;
 
 template <int DT> struct Elem;
 template <> struct Elem<LAVA_BF16> { static constexpr int kBytes = 2; };
@@ -91,25 +92,57 @@ struct Tile {
   static constexpr int kStages = kTileBytes <= 8192 ? 4 : 2;   // ring depth: 32 KiB of LDS per wavefront
 };
 
-// Direct-to-LDS read of one 32-key tile into a ring stage (rows beyond n are clamped to the last
-// row; callers mask them).  Instruction i moves 1 KiB: lane l lands at chunk slot i*64 + l of the
-// stage, i.e. row (i*64+l)/kCpr, slot s = (i*64+l)%kCpr, and fetches the row's chunk
-// s ^ (row & 7): the swizzle is applied on the global side because the LDS side is linear.
+// Direct-to-LDS reads of 32-key tiles into a ring stage.  Instruction i moves 1 KiB: lane l lands
+// at chunk slot i*64 + l of the stage, i.e. row (i*64+l)/kCpr, slot s = (i*64+l)%kCpr, and fetches
+// the row's chunk s ^ (row & 7): the swizzle is applied on the global side because the LDS side
+// of such a load is linear.  The per-lane byte offsets inside a tile are computed once; a full tile
+// is then (wave-uniform tile address) + (per-lane offset), which needs no vector arithmetic.
 template <int DT, int D>
-__device__ __forceinline__ void dma_tile(const u32x4* __restrict__ kg, long long tile, long long n,
-                                         int lane, u32x4* stage) {
+struct TileDma {
   using T = Tile<DT, D>;
+  unsigned int loff[T::kLoads];
+
+  __device__ __forceinline__ void init(int lane) {
 #pragma unroll
-  for (int i = 0; i < T::kLoads; ++i) {
-    const int q = i * 64 + lane;
-    const int row = q / T::kCpr, slot = q % T::kCpr;
-    long long key = tile * kTileKeys + row;
-    key = key < n ? key : n - 1;
-    const u32x4* src = kg + key * T::kCpr + (slot ^ (row & 7));
-    __builtin_amdgcn_global_load_lds((const LAVA_GLOBAL_AS void*)src, (LAVA_LDS_AS void*)(stage + i * 64),
-                                     16, 0, 0);
+    for (int i = 0; i < T::kLoads; ++i) {
+      const int q = i * 64 + lane;
+      const int row = q / T::kCpr, slot = q % T::kCpr;
+      loff[i] = (unsigned int)(row * T::kRowBytes + ((slot ^ (row & 7)) << 4));
+    }
   }
-}
+
+  // every row of the tile exists
+  __device__ __forceinline__ void issue_full(const char* __restrict__ tile_base, u32x4* stage) const {
+#pragma unroll
+    for (int i = 0; i < T::kLoads; ++i)
+      __builtin_amdgcn_global_load_lds((const LAVA_GLOBAL_AS void*)(tile_base + loff[i]),
+                                       (LAVA_LDS_AS void*)(stage + i * 64), 16, 0, 0);
+  }
+
+  // rows at or beyond n are read from row n - 1 (callers mask or drop them)
+  __device__ __forceinline__ void issue_clamped(const char* __restrict__ head_base, long long tile,
+                                                long long n, int lane, u32x4* stage) const {
+#pragma unroll
+    for (int i = 0; i < T::kLoads; ++i) {
+      const int q = i * 64 + lane;
+      const int row = q / T::kCpr, slot = q % T::kCpr;
+      long long key = tile * kTileKeys + row;
+      key = key < n ? key : n - 1;
+      const char* src = head_base + key * T::kRowBytes + ((slot ^ (row & 7)) << 4);
+      __builtin_amdgcn_global_load_lds((const LAVA_GLOBAL_AS void*)src, (LAVA_LDS_AS void*)(stage + i * 64), 16,
+                                       0, 0);
+    }
+  }
+
+  __device__ __forceinline__ void issue(const char* __restrict__ head_base, long long tile, long long n,
+                                        int lane, u32x4* stage) const {
+    if ((tile + 1) * kTileKeys <= n) {
+      issue_full(head_base + tile * T::kTileBytes, stage);
+    } else {
+      issue_clamped(head_base, tile, n, lane, stage);
+    }
+  }
+};
 
 // Wait for the oldest tile of the ring while `younger` (0 .. kStages-1) tiles stay in flight.
 template <int DT, int D>
@@ -153,6 +186,21 @@ __device__ __forceinline__ void load_q(const u32x4* __restrict__ qg, int h0, int
   }
 }
 
+// One head's 32 x 32 block of raw dot products: keys x rows (KEYS_AS_ROWS) or rows x keys.
+template <int DT, int D, bool KEYS_AS_ROWS>
+__device__ __forceinline__ f32x16 dot_tile(const u32x4 (&kf)[Tile<DT, D>::kSteps],
+                                           const u32x4 (&qh)[Tile<DT, D>::kSteps]) {
+  f32x16 acc = {0};
+#pragma unroll
+  for (int j = 0; j < Tile<DT, D>::kSteps; ++j)
+    acc = KEYS_AS_ROWS ? mfma_chunk<DT>(kf[j], qh[j], acc) : mfma_chunk<DT>(qh[j], kf[j], acc);
+  return acc;
+}
+
+// Index of the wavefront inside its workgroup as a scalar, so that everything derived from it
+// (tile numbers, ring stages, loop bounds) stays in scalar registers and scalar branches.
+__device__ __forceinline__ int wave_index() { return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
+
 // ------------------------------------------------------------------------------------------
 // stats: per workgroup and per (head of the chunk, window row) the running maximum of the raw
 // dot products and sum of exp2((dot - max) * c2) over the workgroup's keys, c2 = scale * log2 e.
@@ -165,18 +213,21 @@ stats_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long 
              int n_chunks, float c2, int tiles_per_block, float2* __restrict__ stat_part,
              float* __restrict__ row_bias, uint32_t* __restrict__ counters) {
   using T = Tile<DT, D>;
-  __shared__ u32x4 s_tile[kSweepThreads / 64][T::kStages][T::kTileChunks];
-  __shared__ float2 s_red[kSweepThreads / 64][kMaxChunkHeads * 32];   // [wave][head*32+row]; reused as [slice][row] at the end
+  constexpr int kWaves = kSweepThreads / 64;
+  __shared__ u32x4 s_tile[kWaves][T::kStages][T::kTileChunks];
+  __shared__ float2 s_red[kWaves][kMaxChunkHeads * 32];   // [wave][head*32+row]; reused as [slice][row] at the end
   __shared__ unsigned int s_last;
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = wave_index();
   const int g = blockIdx.y / n_chunks, chunk = blockIdx.y % n_chunks;
   const int h0 = g * G + chunk * GT;
   const int nh = (G - chunk * GT) < GT ? (G - chunk * GT) : GT;
-  const u32x4* kg = k + (long long)g * n * T::kCpr;
+  const char* kg = reinterpret_cast<const char*>(k) + (long long)g * n * T::kRowBytes;
 
   u32x4 qf[GT][T::kSteps];
   load_q<DT, D, GT>(q_win, h0, nh, w, lane, qf);
+  TileDma<DT, D> dma;
+  dma.init(lane);
 
   const long long n_tiles = (n + kTileKeys - 1) / kTileKeys;
   const long long t_begin = (long long)blockIdx.x * tiles_per_block;
@@ -188,55 +239,69 @@ stats_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long 
   for (int t = 0; t < GT; ++t) { m_run[t] = -INFINITY; z_run[t] = 0.0f; }
 
   const int r = lane & 31, half = lane >> 5;
-  long long last_visible = n - w + r;           // last key row r may see
-  if (last_visible > n - 1) last_visible = n - 1;
 
-  // this wavefront's tiles: t_begin + wave, + 4, ...; ring of kStages buffers, kStages-1 tiles ahead
-  constexpr int kWaves = kSweepThreads / 64;
+  // this wavefront's tiles: t_begin + wave, + kWaves, ...; ring of kStages buffers, kStages-1 tiles ahead
   const long long first = t_begin + wave;
   const int cnt = first < t_end ? (int)((t_end - first + kWaves - 1) / kWaves) : 0;
   u32x4* ring = s_tile[wave][0];
 #pragma unroll
   for (int p = 0; p < T::kStages - 1; ++p)
-    if (p < cnt) dma_tile<DT, D>(kg, first + (long long)p * kWaves, n, lane, ring + p * T::kTileChunks);
+    if (p < cnt) dma.issue(kg, first + (long long)p * kWaves, n, lane, ring + p * T::kTileChunks);
   for (int it = 0; it < cnt; ++it) {
     const long long tile = first + (long long)it * kWaves;
     const int ahead = it + T::kStages - 1;
     if (ahead < cnt)
-      dma_tile<DT, D>(kg, first + (long long)ahead * kWaves, n, lane,
-                      ring + (ahead % T::kStages) * T::kTileChunks);
+      dma.issue(kg, first + (long long)ahead * kWaves, n, lane, ring + (ahead % T::kStages) * T::kTileChunks);
     const int younger = cnt - 1 - it < T::kStages - 1 ? cnt - 1 - it : T::kStages - 1;
     wait_tile<DT, D>(younger);
     u32x4 kf[T::kSteps];
     lds_to_frag<DT, D>(ring + (it % T::kStages) * T::kTileChunks, lane, kf);
-    asm volatile("" ::: "memory");   // the next iteration's loads into this ring stay below these reads
+    asm volatile("" ::: "memory");   // later loads into this ring stage stay below these reads
 
     const long long key0 = tile * kTileKeys;
-    const bool late = key0 + kTileKeys - 1 > n - w;   // some row cannot see some key of this tile
+    if (key0 + kTileKeys - 1 <= n - w) {
+      // every row sees every key of the tile: straight-line code, the next head's MFMAs are
+      // independent of this head's exponentials
+      f32x16 acc = dot_tile<DT, D, true>(kf, qf[0]);
 #pragma unroll
-    for (int t = 0; t < GT; ++t) {
-      f32x16 acc = {0};
+      for (int t = 0; t < GT; ++t) {
+        f32x16 nxt = acc;
+        if (t + 1 < GT) nxt = dot_tile<DT, D, true>(kf, qf[t + 1]);
+        float tmax = fmaxf(acc[0], acc[1]);
 #pragma unroll
-      for (int j = 0; j < T::kSteps; ++j) acc = mfma_chunk<DT>(kf[j], qf[t][j], acc);
-      if (late) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
-          const long long key = key0 + 8 * (v / 4) + 4 * half + (v % 4);
-          if (key > last_visible) acc[v] = -INFINITY;
-        }
-      }
-      float tmax = acc[0];
-#pragma unroll
-      for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, acc[v]);
-      if (tmax > -INFINITY) {
+        for (int v = 2; v < 16; ++v) tmax = fmaxf(tmax, acc[v]);
         const float mn = fmaxf(m_run[t], tmax);
         const float mc = mn * c2;
         float zs = 0.0f;
 #pragma unroll
         for (int v = 0; v < 16; ++v) zs += fast_exp2(fmaf(acc[v], c2, -mc));
-        const float f = (m_run[t] == mn) ? 1.0f : fast_exp2((m_run[t] - mn) * c2);
-        z_run[t] = z_run[t] * f + zs;
+        z_run[t] = z_run[t] * fast_exp2((m_run[t] - mn) * c2) + zs;   // exp2(-inf) = 0 on the first tile
         m_run[t] = mn;
+        acc = nxt;
+      }
+    } else {
+      // tile touches the window or the end of the sequence: mask what a row may not see
+      const int rel0 = (int)(key0 - (n - w));                // position of the tile's first key relative to N - w
+      const int row_limit = r < w - 1 ? r : w - 1;            // row r sees relative positions <= min(r, w - 1)
+#pragma unroll
+      for (int t = 0; t < GT; ++t) {
+        f32x16 acc = dot_tile<DT, D, true>(kf, qf[t]);
+#pragma unroll
+        for (int v = 0; v < 16; ++v)
+          if (rel0 + 8 * (v / 4) + 4 * half + (v % 4) > row_limit) acc[v] = -INFINITY;
+        float tmax = acc[0];
+#pragma unroll
+        for (int v = 1; v < 16; ++v) tmax = fmaxf(tmax, acc[v]);
+        if (tmax > -INFINITY) {
+          const float mn = fmaxf(m_run[t], tmax);
+          const float mc = mn * c2;
+          float zs = 0.0f;
+#pragma unroll
+          for (int v = 0; v < 16; ++v) zs += fast_exp2(fmaf(acc[v], c2, -mc));
+          const float f = (m_run[t] == mn) ? 1.0f : fast_exp2((m_run[t] - mn) * c2);
+          z_run[t] = z_run[t] * f + zs;
+          m_run[t] = mn;
+        }
       }
     }
   }
@@ -253,7 +318,7 @@ stats_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long 
   if (threadIdx.x < GT * 32) {
     float m = -INFINITY, z = 0.0f;
 #pragma unroll
-    for (int wv = 0; wv < kSweepThreads / 64; ++wv) {
+    for (int wv = 0; wv < kWaves; ++wv) {
       const float2 p = s_red[wv][threadIdx.x];
       merge_stat(m, z, p.x, p.y, c2);
     }
@@ -263,7 +328,7 @@ stats_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long 
   // The last workgroup of this (KV head, chunk) to finish merges all partials, always in
   // workgroup-index order (deterministic), into the exponent bias of every (head, row):
   // log2 of the row's softmax normaliser in the exp2 domain.
-  if (!arrive_last(&counters[kCounterStats + blockIdx.y], gridDim.x, &s_last)) return;
+  if (!arrive_last(&counters[kCounterStats + kArriveWords * blockIdx.y], gridDim.x, blockIdx.x, &s_last)) return;
   // 256 threads: thread (row, slice) merges its slice of the partials in workgroup order with
   // independent loads, then the slices are merged in slice order.
   constexpr int kRows = GT * 32;
@@ -308,14 +373,15 @@ scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long
               int n_chunks, float c2, int tiles_per_block, const float* __restrict__ row_bias,
               const float* __restrict__ lse, float* __restrict__ s_raw) {
   using T = Tile<DT, D>;
-  __shared__ u32x4 s_tile[kSweepThreads / 64][T::kStages][T::kTileChunks];
-  __shared__ float s_bias[GT * 32];
+  constexpr int kWaves = kSweepThreads / 64;
+  __shared__ u32x4 s_tile[kWaves][T::kStages][T::kTileChunks];
+  __shared__ __attribute__((aligned(16))) float s_bias[GT * 32];
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = wave_index();
   const int g = blockIdx.y / n_chunks, chunk = blockIdx.y % n_chunks;
   const int h0 = g * G + chunk * GT;
   const int nh = (G - chunk * GT) < GT ? (G - chunk * GT) : GT;
-  const u32x4* kg = k + (long long)g * n * T::kCpr;
+  const char* kg = reinterpret_cast<const char*>(k) + (long long)g * n * T::kRowBytes;
   const long long n_prefix = n - w;
 
   // exponent bias of every (head, row): log2 of (row normaliser * w), +inf for padding rows
@@ -332,51 +398,54 @@ scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long
 
   u32x4 qf[GT][T::kSteps];
   load_q<DT, D, GT>(q_win, h0, nh, w, lane, qf);
+  TileDma<DT, D> dma;
+  dma.init(lane);
   __syncthreads();
 
   const int half = lane >> 5;
-  float bias[GT][16];
-#pragma unroll
-  for (int t = 0; t < GT; ++t)
-#pragma unroll
-    for (int v = 0; v < 16; ++v) bias[t][v] = s_bias[t * 32 + 8 * (v / 4) + 4 * half + (v % 4)];
+  // rows held by this lane in result register v: 8 * (v / 4) + 4 * half + v % 4 -> four float4 per head
+  const float4* bias4 = reinterpret_cast<const float4*>(s_bias) + half;
 
   const long long n_tiles = (n_prefix + kTileKeys - 1) / kTileKeys;
   const long long t_begin = (long long)blockIdx.x * tiles_per_block;
   long long t_end = t_begin + tiles_per_block;
   if (t_end > n_tiles) t_end = n_tiles;
 
-  // this wavefront's tiles: t_begin + wave, + 4, ...; ring of kStages buffers, kStages-1 tiles ahead
-  constexpr int kWaves = kSweepThreads / 64;
   const long long first = t_begin + wave;
   const int cnt = first < t_end ? (int)((t_end - first + kWaves - 1) / kWaves) : 0;
   u32x4* ring = s_tile[wave][0];
 #pragma unroll
   for (int p = 0; p < T::kStages - 1; ++p)
-    if (p < cnt) dma_tile<DT, D>(kg, first + (long long)p * kWaves, n, lane, ring + p * T::kTileChunks);
+    if (p < cnt) dma.issue(kg, first + (long long)p * kWaves, n, lane, ring + p * T::kTileChunks);
   for (int it = 0; it < cnt; ++it) {
     const long long tile = first + (long long)it * kWaves;
     const int ahead = it + T::kStages - 1;
     if (ahead < cnt)
-      dma_tile<DT, D>(kg, first + (long long)ahead * kWaves, n, lane,
-                      ring + (ahead % T::kStages) * T::kTileChunks);
+      dma.issue(kg, first + (long long)ahead * kWaves, n, lane, ring + (ahead % T::kStages) * T::kTileChunks);
     const int younger = cnt - 1 - it < T::kStages - 1 ? cnt - 1 - it : T::kStages - 1;
     wait_tile<DT, D>(younger);
     u32x4 kf[T::kSteps];
     lds_to_frag<DT, D>(ring + (it % T::kStages) * T::kTileChunks, lane, kf);
-    asm volatile("" ::: "memory");   // the next iteration's loads into this ring stay below these reads
+    asm volatile("" ::: "memory");   // later loads into this ring stage stay below these reads
 
     float best = 0.0f;
+    f32x16 acc = dot_tile<DT, D, false>(kf, qf[0]);
 #pragma unroll
     for (int t = 0; t < GT; ++t) {
-      f32x16 acc = {0};
-#pragma unroll
-      for (int j = 0; j < T::kSteps; ++j) acc = mfma_chunk<DT>(qf[t][j], kf[j], acc);
+      f32x16 nxt = acc;
+      if (t + 1 < GT) nxt = dot_tile<DT, D, false>(kf, qf[t + 1]);
       float ps = 0.0f;
 #pragma unroll
-      for (int v = 0; v < 16; ++v) ps += fast_exp2(fmaf(acc[v], c2, -bias[t][v]));
+      for (int jj = 0; jj < 4; ++jj) {
+        const float4 b = bias4[t * 8 + 2 * jj];
+        ps += fast_exp2(fmaf(acc[4 * jj + 0], c2, -b.x));
+        ps += fast_exp2(fmaf(acc[4 * jj + 1], c2, -b.y));
+        ps += fast_exp2(fmaf(acc[4 * jj + 2], c2, -b.z));
+        ps += fast_exp2(fmaf(acc[4 * jj + 3], c2, -b.w));
+      }
       ps += __shfl_xor(ps, 32);
       best = fmaxf(best, ps);
+      acc = nxt;
     }
     const long long key = tile * kTileKeys + (lane & 31);
     if (half == 0 && key < n_prefix) {
@@ -416,10 +485,10 @@ constexpr int kVnormUnroll = 4;
 template <int DT, int LPR>   // LPR lanes (16 bytes each) per row
 __global__ void __launch_bounds__(kVnormThreads)
 vnorm_kernel(const u32x4* __restrict__ v, long long n, long long rows_per_block,
-             float* __restrict__ vnorm_part, uint32_t* __restrict__ counters) {
+             float* __restrict__ vnorm_part, uint32_t* __restrict__ counters, int n_counter_words) {
   __shared__ float s_max[kVnormThreads / 64];
   if (blockIdx.x == 0 && blockIdx.y == 0)
-    for (int i = threadIdx.x; i < kNumCounters; i += kVnormThreads) counters[i] = 0u;
+    for (int i = threadIdx.x; i < n_counter_words; i += kVnormThreads) counters[i] = 0u;
   const int g = blockIdx.y;
   const u32x4* vg = v + (long long)g * n * LPR;
   const long long row_begin = (long long)blockIdx.x * rows_per_block;
@@ -523,7 +592,7 @@ poolstat_kernel(const float* __restrict__ s_raw, long long n, int w, int pool_ha
     st_dev_f64(&mine->x, S);
     st_dev_f64(&mine->y, Tt);
   }
-  if (!arrive_last(&counters[kCounterPool], n_blocks, &s_last)) return;
+  if (!arrive_last(&counters[kCounterPool], n_blocks, blockIdx.y * gridDim.x + blockIdx.x, &s_last)) return;
   // last workgroup: thread t sums partials t, t + 256, ... then the same fixed tree as above
   double S = 0.0, Tt = 0.0;
   for (unsigned int i = threadIdx.x; i < n_blocks; i += kPoolThreads) {
@@ -552,6 +621,19 @@ __global__ void __launch_bounds__(256) fill_zero_kernel(float* __restrict__ p, l
 }
 
 // ------------------------------------------------------------------------------------------ host
+static int compute_units() {
+  static int cached = 0;
+  if (cached == 0) {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) == hipSuccess &&
+        hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && cus > 0)
+      cached = cus;
+    else
+      cached = 256;   // MI355X
+  }
+  return cached;
+}
+
 SweepPlan make_sweep_plan(const lava_layer_desc& d, int64_t n) {
   SweepPlan p;
   const int G = d.n_q_heads / d.n_kv_heads;
@@ -561,7 +643,15 @@ SweepPlan make_sweep_plan(const lava_layer_desc& d, int64_t n) {
   if (p.chunk_heads == 3) p.chunk_heads = 4;   // kernels are built for 1, 2 and 4 heads per chunk
   p.n_chunks = (G + p.chunk_heads - 1) / p.chunk_heads;
   const int64_t n_tiles = (n + kTileKeys - 1) / kTileKeys;
-  int64_t max_bx = 1024 / ((int64_t)d.n_kv_heads * p.n_chunks);
+  // One workgroup per compute unit: the sweeps keep the group's query rows in registers and a
+  // 128 KiB tile ring in LDS, so a CU holds exactly one workgroup, and per-workgroup set-up (query
+  // load, partial results) is amortised over as many tiles as possible.
+  int64_t target_wgs = compute_units();
+  if (const char* env = getenv("LAVA_SWEEP_WGS")) {      // tuning knob: workgroups per sweep launch
+    const long v = atol(env);
+    if (v >= 1 && v <= 65536) target_wgs = v;
+  }
+  int64_t max_bx = target_wgs / ((int64_t)d.n_kv_heads * p.n_chunks);
   if (max_bx < 1) max_bx = 1;
   int64_t tpb = (n_tiles + max_bx - 1) / max_bx;
   if (tpb < 16) tpb = 16;
@@ -594,7 +684,7 @@ ScoreWorkspace make_score_workspace(const lava_layer_desc& d, int64_t n) {
   w.off_row_bias = off;
   off += align_up(sizeof(float) * (size_t)d.n_kv_heads * p.n_chunks * p.chunk_heads * 32);
   w.off_counter = off;
-  off += align_up(sizeof(uint32_t) * kNumCounters);
+  off += align_up(sizeof(uint32_t) * kArriveWords * (1 + (size_t)d.n_kv_heads * p.n_chunks));
   w.bytes = off;
   return w;
 }
@@ -607,7 +697,8 @@ int32_t launch_vnorm(const lava_layer_desc& d, int64_t n, const void* v, float* 
   ProfScope ps(KID_VNORM, s);
 #define LAVA_VNORM(DTV, L)                                                                    \
   hipLaunchKernelGGL((vnorm_kernel<DTV, L>), grid, block, 0, s, static_cast<const u32x4*>(v), \
-                     (long long)n, rows_per_block, vnorm_part, counters)
+                     (long long)n, rows_per_block, vnorm_part, counters,                      \
+                     kArriveWords * (1 + d.n_kv_heads * p.n_chunks))
   if (d.dtype == LAVA_BF16 && lpr == 8) LAVA_VNORM(LAVA_BF16, 8);
   else if (d.dtype == LAVA_BF16 && lpr == 16) LAVA_VNORM(LAVA_BF16, 16);
   else if (d.dtype == LAVA_F32 && lpr == 16) LAVA_VNORM(LAVA_F32, 16);
@@ -645,7 +736,7 @@ static float exp2_scale(const lava_layer_desc& d) {
 int32_t launch_stats(const lava_layer_desc& d, int64_t n, const void* q_win, const void* k,
                      float2* stat_part, float* row_bias, uint32_t* counters, const SweepPlan& p,
                      hipStream_t s) {
-  if (d.n_kv_heads * p.n_chunks > kNumCounters - kCounterStats) return LAVA_ERR_SHAPE;
+  if (d.n_kv_heads * p.n_chunks > kMaxStatTickets) return LAVA_ERR_SHAPE;
   const int G = d.n_q_heads / d.n_kv_heads;
   const dim3 grid(p.blocks_x, d.n_kv_heads * p.n_chunks), block(kSweepThreads);
   const float c2 = exp2_scale(d);

@@ -42,14 +42,42 @@ __device__ __forceinline__ double ld_dev_f64(const double* p) {
 // Every vector-memory operation this lane has issued is complete once this returns.
 __device__ __forceinline__ void drain_vmem() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
 
+// Arrivals are counted in two levels because device-scope atomics on ONE address serialise at
+// a few tens of nanoseconds each: workgroup `id` of `n` bumps the counter of its group (at most
+// 64 groups of at least 16 workgroups), and the workgroup that completes a group bumps the top
+// counter.  Counters are monotonic: `round` is 1 for the first use after they were zeroed.
+__device__ __forceinline__ unsigned int arrive_group_size(unsigned int n) {
+  const unsigned int g = (n + 63u) / 64u;
+  return g < 16u ? 16u : g;
+}
+__device__ __forceinline__ unsigned int arrive_groups(unsigned int n) {
+  const unsigned int gs = arrive_group_size(n);
+  return (n + gs - 1u) / gs;
+}
+constexpr int kArriveWords = 1 + 64;   // top counter + group counters
+
+// Called by one lane.  Returns the value the top counter had before this arrival's increment if this
+// workgroup completed its group in this round, or 0xffffffff otherwise.
+__device__ __forceinline__ unsigned int arrive_two_level(unsigned int* ctr, unsigned int n, unsigned int id,
+                                                         unsigned int round) {
+  const unsigned int gs = arrive_group_size(n);
+  const unsigned int grp = id / gs;
+  const unsigned int members = (grp + 1u) * gs <= n ? gs : n - grp * gs;
+  const unsigned int t = __hip_atomic_fetch_add(&ctr[1 + grp], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  if (t + 1u != round * members) return 0xffffffffu;
+  return __hip_atomic_fetch_add(&ctr[0], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // Ticket of a workgroup that has published its results with st_dev.  Returns true, in every
-// thread, for the workgroup that arrives last.  `s_flag` is a word of shared memory.
-__device__ __forceinline__ bool arrive_last(unsigned int* ticket, unsigned int n_groups, unsigned int* s_flag) {
+// thread, for the workgroup that arrives last.  `ctr` holds kArriveWords zeroed words, `s_flag`
+// is a word of shared memory.
+__device__ __forceinline__ bool arrive_last(unsigned int* ctr, unsigned int n, unsigned int id,
+                                            unsigned int* s_flag) {
   drain_vmem();
   __syncthreads();
   if (threadIdx.x == 0) {
-    const unsigned int t = __hip_atomic_fetch_add(ticket, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    *s_flag = (t == n_groups - 1) ? 1u : 0u;
+    const unsigned int t = arrive_two_level(ctr, n, id, 1u);
+    *s_flag = (t != 0xffffffffu && t + 1u == arrive_groups(n)) ? 1u : 0u;
   }
   __syncthreads();
   return *s_flag != 0u;
