@@ -84,6 +84,27 @@ def main():
     v_hat = torch.empty(B, sh.head_dim, dtype=desc.torch_dtype, device=dev)
     lens = [sh.n]
 
+    # ---- streaming probe: plain read / copy of 1 GiB (also calibrates the profiler's byte counters)
+    probe_bytes = 1 << 30
+    probe_src = torch.empty(probe_bytes, dtype=torch.uint8, device=dev).fill_(1)
+    probe_dst = torch.empty(probe_bytes, dtype=torch.uint8, device=dev)
+    probe_sink = torch.zeros(64, dtype=torch.int32, device=dev)
+
+    def timed_probe(mode):
+        best = float("inf")
+        for _ in range(5):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            lava.probe_stream(probe_src, probe_dst if mode == 0 else probe_sink, probe_bytes, mode, 8192)
+            b.record()
+            torch.cuda.synchronize()
+            best = min(best, a.elapsed_time(b) * 1e-3)
+        return best
+
+    probe = {"read_GBs": round(probe_bytes / timed_probe(1) / 1e9, 1),
+             "copy_GBs_read_plus_write": round(2 * probe_bytes / timed_probe(0) / 1e9, 1), "bytes": probe_bytes}
+    del probe_src, probe_dst
+
     def step(i):
         q, k, v = sets[i % n_sets]
         lava.lava_window_scores(desc, lens, q, k, v, scores=scores, vbar=vbar, layer_stat=stat, workspace=ws_scores)
@@ -145,6 +166,7 @@ def main():
         "path": {"algorithmic_bytes": path_bytes, "achieved_GBs": round(path_gbs, 1),
                  "frac_of_hbm_peak": round(path_gbs / HBM_PEAK_GBS, 4)},
         "kernels_us": {k: round(v, 2) for k, v in per_kernel_us.items()},
+        "stream_probe": probe,
     }
 
     if not args.no_check or not args.no_cpu_baseline:
