@@ -61,7 +61,6 @@ struct ScoreWorkspace {
   size_t off_vnorm_part;  // float  [H_kv][vnorm_blocks]
   size_t off_sraw;        // float  [H_kv][N']  group-max of window-mean attention
   size_t off_ent_part;    // double2[pool blocks]  partial (S, T)
-  size_t off_row_bias;    // float  [H_kv*n_chunks][GT*32]  log2 of each row's softmax normaliser
   size_t off_counter;     // uint32 "last workgroup done" tickets
   size_t bytes;
 };
@@ -71,10 +70,9 @@ int pool_blocks(const lava_layer_desc& d, int64_t n);
 int32_t launch_vnorm(const lava_layer_desc& d, int64_t n, const void* v, float* vnorm_part,
                      uint32_t* counters, const SweepPlan& p, hipStream_t s);
 int32_t launch_stats(const lava_layer_desc& d, int64_t n, const void* q_win, const void* k,
-                     float2* stat_part, float* row_bias, uint32_t* counters, const SweepPlan& p,
-                     hipStream_t s);
+                     float2* stat_part, const SweepPlan& p, hipStream_t s);
 int32_t launch_scores(const lava_layer_desc& d, int64_t n, const void* q_win, const void* k,
-                      const float* row_bias, const float* lse, float* s_raw, const SweepPlan& p,
+                      const float2* stat_part, const float* lse, float* s_raw, const SweepPlan& p,
                       hipStream_t s);
 int32_t launch_poolstat(const lava_layer_desc& d, int64_t n, const float* s_raw,
                         const float* vnorm_part, int vnorm_blocks, float* scores, float* vbar,

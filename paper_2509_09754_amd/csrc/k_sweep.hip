@@ -34,8 +34,6 @@ constexpr float kLog2e = 1.4426950408889634f;
 
 // "last workgroup done" tickets in the workspace (zeroed by the first kernel of every call)
 constexpr int kCounterPool = 0;                         // poolstat: one two-level ticket
-constexpr int kCounterStats = kArriveWords;             // stats: one two-level ticket per (KV head, chunk)
-constexpr int kMaxStatTickets = 512;
 
 template <int DT> struct Elem;
 template <> struct Elem<LAVA_BF16> { static constexpr int kBytes = 2; };
@@ -89,7 +87,19 @@ struct Tile {
   static constexpr int kLoads = kTileKeys * kCpr / 64; // 128-bit loads per lane per tile
   static constexpr int kTileChunks = kTileKeys * kCpr;
   static constexpr int kTileBytes = kTileKeys * kRowBytes;
-  static constexpr int kStages = kTileBytes <= 8192 ? 4 : 2;   // ring depth: 32 KiB of LDS per wavefront
+};
+
+// Wavefronts per workgroup and ring depth.  The ring takes 128 KiB of LDS in all.  Kernels whose
+// registers fit twice into a SIMD run 8 wavefronts (2 per SIMD: one wavefront's exponentials
+// overlap the other's MFMAs and waits) with a shallower ring; the f32 / d_h 128 kernels need more
+// than 256 registers and stay at 4 wavefronts.
+template <int DT, int D>
+struct Shape {
+  static constexpr int kWaves = (DT == LAVA_F32 && D == 128) ? 4 : 8;
+  static constexpr int kThreads = kWaves * 64;
+  static constexpr int kStagesRaw = (128 * 1024) / (kWaves * Tile<DT, D>::kTileBytes);
+  static constexpr int kStages = kStagesRaw > 4 ? 4 : kStagesRaw;
+  static_assert(kStages >= 2, "ring needs at least two stages");
 };
 
 // Direct-to-LDS reads of 32-key tiles into a ring stage.  Instruction i moves 1 KiB: lane l lands
@@ -100,23 +110,34 @@ struct Tile {
 template <int DT, int D>
 struct TileDma {
   using T = Tile<DT, D>;
-  unsigned int loff[T::kLoads];
+  static constexpr int kRowsPerLoad = 64 / T::kCpr;                                // rows one instruction covers
+  static constexpr int kVariants = kRowsPerLoad >= 8 ? 1 : 8 / kRowsPerLoad;        // distinct (row & 7) patterns
+  unsigned int loff[kVariants];   // per-lane byte offset inside the 1 KiB slice of load i, variant i % kVariants
 
   __device__ __forceinline__ void init(int lane) {
 #pragma unroll
-    for (int i = 0; i < T::kLoads; ++i) {
+    for (int i = 0; i < kVariants; ++i) {
       const int q = i * 64 + lane;
       const int row = q / T::kCpr, slot = q % T::kCpr;
-      loff[i] = (unsigned int)(row * T::kRowBytes + ((slot ^ (row & 7)) << 4));
+      loff[i] = (unsigned int)((row - i * kRowsPerLoad) * T::kRowBytes + ((slot ^ (row & 7)) << 4));
     }
   }
 
-  // every row of the tile exists
+  // Every row of the tile exists.  Load i covers bytes [i KiB, (i+1) KiB) of the tile on both sides;
+  // the common part of the offset is an instruction immediate (< 4 KiB) applied to the global and
+  // the LDS address alike, plus a scalar 4 KiB step, so a load costs no vector arithmetic.
   __device__ __forceinline__ void issue_full(const char* __restrict__ tile_base, u32x4* stage) const {
 #pragma unroll
-    for (int i = 0; i < T::kLoads; ++i)
-      __builtin_amdgcn_global_load_lds((const LAVA_GLOBAL_AS void*)(tile_base + loff[i]),
-                                       (LAVA_LDS_AS void*)(stage + i * 64), 16, 0, 0);
+    for (int i = 0; i < T::kLoads; ++i) {
+      const char* src = tile_base + (i / 4) * 4096 + loff[i % kVariants];
+      u32x4* dst = stage + (i / 4) * 256;
+      switch (i % 4) {
+        case 0: __builtin_amdgcn_global_load_lds((const LAVA_GLOBAL_AS void*)src, (LAVA_LDS_AS void*)dst, 16, 0, 0); break;
+        case 1: __builtin_amdgcn_global_load_lds((const LAVA_GLOBAL_AS void*)src, (LAVA_LDS_AS void*)dst, 16, 1024, 0); break;
+        case 2: __builtin_amdgcn_global_load_lds((const LAVA_GLOBAL_AS void*)src, (LAVA_LDS_AS void*)dst, 16, 2048, 0); break;
+        default: __builtin_amdgcn_global_load_lds((const LAVA_GLOBAL_AS void*)src, (LAVA_LDS_AS void*)dst, 16, 3072, 0); break;
+      }
+    }
   }
 
   // rows at or beyond n are read from row n - 1 (callers mask or drop them)
@@ -148,7 +169,7 @@ struct TileDma {
 template <int DT, int D>
 __device__ __forceinline__ void wait_tile(int younger) {
   using T = Tile<DT, D>;
-  static_assert(T::kStages <= 4, "ring depth");
+  static_assert(Shape<DT, D>::kStages <= 4, "ring depth");
   switch (younger) {
     case 0: wait_vmcnt<0>(); break;
     case 1: wait_vmcnt<T::kLoads>(); break;
@@ -208,15 +229,14 @@ __device__ __forceinline__ int wave_index() { return __builtin_amdgcn_readfirstl
 // and including its own position).
 // ------------------------------------------------------------------------------------------
 template <int DT, int D, int GT>
-__global__ void __launch_bounds__(kSweepThreads)
+__global__ void __launch_bounds__((Shape<DT, D>::kThreads))
 stats_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long long n, int w, int G,
-             int n_chunks, float c2, int tiles_per_block, float2* __restrict__ stat_part,
-             float* __restrict__ row_bias, uint32_t* __restrict__ counters) {
+             int n_chunks, float c2, int tiles_per_block, float2* __restrict__ stat_part) {
   using T = Tile<DT, D>;
-  constexpr int kWaves = kSweepThreads / 64;
-  __shared__ u32x4 s_tile[kWaves][T::kStages][T::kTileChunks];
-  __shared__ float2 s_red[kWaves][kMaxChunkHeads * 32];   // [wave][head*32+row]; reused as [slice][row] at the end
-  __shared__ unsigned int s_last;
+  constexpr int kWaves = Shape<DT, D>::kWaves;
+  constexpr int kStages = Shape<DT, D>::kStages;
+  __shared__ u32x4 s_tile[kWaves][kStages][T::kTileChunks];
+  __shared__ float2 s_red[kWaves][kMaxChunkHeads * 32];   // [wave][head*32+row]
 
   const int lane = threadIdx.x & 63, wave = wave_index();
   const int g = blockIdx.y / n_chunks, chunk = blockIdx.y % n_chunks;
@@ -245,17 +265,17 @@ stats_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long 
   const int cnt = first < t_end ? (int)((t_end - first + kWaves - 1) / kWaves) : 0;
   u32x4* ring = s_tile[wave][0];
 #pragma unroll
-  for (int p = 0; p < T::kStages - 1; ++p)
+  for (int p = 0; p < kStages - 1; ++p)
     if (p < cnt) dma.issue(kg, first + (long long)p * kWaves, n, lane, ring + p * T::kTileChunks);
   for (int it = 0; it < cnt; ++it) {
     const long long tile = first + (long long)it * kWaves;
-    const int ahead = it + T::kStages - 1;
+    const int ahead = it + kStages - 1;
     if (ahead < cnt)
-      dma.issue(kg, first + (long long)ahead * kWaves, n, lane, ring + (ahead % T::kStages) * T::kTileChunks);
-    const int younger = cnt - 1 - it < T::kStages - 1 ? cnt - 1 - it : T::kStages - 1;
+      dma.issue(kg, first + (long long)ahead * kWaves, n, lane, ring + (ahead % kStages) * T::kTileChunks);
+    const int younger = cnt - 1 - it < kStages - 1 ? cnt - 1 - it : kStages - 1;
     wait_tile<DT, D>(younger);
     u32x4 kf[T::kSteps];
-    lds_to_frag<DT, D>(ring + (it % T::kStages) * T::kTileChunks, lane, kf);
+    lds_to_frag<DT, D>(ring + (it % kStages) * T::kTileChunks, lane, kf);
     asm volatile("" ::: "memory");   // later loads into this ring stage stay below these reads
 
     const long long key0 = tile * kTileKeys;
@@ -322,59 +342,25 @@ stats_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long 
       const float2 p = s_red[wv][threadIdx.x];
       merge_stat(m, z, p.x, p.y, c2);
     }
-    st_dev_f2(&stat_part[((long long)blockIdx.y * gridDim.x + blockIdx.x) * (GT * 32) + threadIdx.x], m, z);
-  }
-
-  // The last workgroup of this (KV head, chunk) to finish merges all partials, always in
-  // workgroup-index order (deterministic), into the exponent bias of every (head, row):
-  // log2 of the row's softmax normaliser in the exp2 domain.
-  if (!arrive_last(&counters[kCounterStats + kArriveWords * blockIdx.y], gridDim.x, blockIdx.x, &s_last)) return;
-  // 256 threads: thread (row, slice) merges its slice of the partials in workgroup order with
-  // independent loads, then the slices are merged in slice order.
-  constexpr int kRows = GT * 32;
-  constexpr int kSlices = kSweepThreads / kRows;
-  const int row = threadIdx.x % kRows, slice = threadIdx.x / kRows;
-  const int nb = gridDim.x;
-  const int per = (nb + kSlices - 1) / kSlices;
-  const int b_begin = slice * per, b_end = (b_begin + per < nb) ? b_begin + per : nb;
-  const float2* part = stat_part + (long long)blockIdx.y * nb * kRows + row;
-  float m = -INFINITY, z = 0.0f;
-  for (int b0 = b_begin; b0 < b_end; b0 += 16) {
-    float2 x[16];
-#pragma unroll
-    for (int u = 0; u < 16; ++u)
-      x[u] = (b0 + u < b_end) ? ld_dev_f2(&part[(long long)(b0 + u) * kRows]) : make_float2(-INFINITY, 0.0f);
-#pragma unroll
-    for (int u = 0; u < 16; ++u) merge_stat(m, z, x[u].x, x[u].y, c2);
-  }
-  __syncthreads();                       // s_red is free again: every slice result goes there
-  float2* fin = &s_red[0][0];            // [kSlices][kRows], kSlices * kRows == 256 entries
-  fin[slice * kRows + row] = make_float2(m, z);
-  __syncthreads();
-  if (threadIdx.x < kRows) {
-    m = -INFINITY; z = 0.0f;
-#pragma unroll
-    for (int sl = 0; sl < kSlices; ++sl) {
-      const float2 x = fin[sl * kRows + threadIdx.x];
-      merge_stat(m, z, x.x, x.y, c2);
-    }
-    row_bias[(long long)blockIdx.y * kRows + threadIdx.x] = m * c2 + log2f(z);
+    stat_part[((long long)blockIdx.y * gridDim.x + blockIdx.x) * (GT * 32) + threadIdx.x] = make_float2(m, z);
   }
 }
 
 // ------------------------------------------------------------------------------------------
 // scores: s_raw[g, i] = max over the heads h of group g of (1/w) sum_r softmax_r[h, i], i < n'.
-// The normaliser of each (head, row) comes from the stats kernel's merged exponent bias, or from a
+// The normaliser of each (head, row) is merged from the stats partials by every workgroup, always
+// in the same fixed order (deterministic) and with independent loads, or taken from a
 // caller-supplied log-sum-exp.
 // ------------------------------------------------------------------------------------------
 template <int DT, int D, int GT>
-__global__ void __launch_bounds__(kSweepThreads)
+__global__ void __launch_bounds__((Shape<DT, D>::kThreads))
 scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long long n, int w, int G,
-              int n_chunks, float c2, int tiles_per_block, const float* __restrict__ row_bias,
-              const float* __restrict__ lse, float* __restrict__ s_raw) {
+              int n_chunks, float c2, int tiles_per_block, const float2* __restrict__ stat_part,
+              int stat_blocks, const float* __restrict__ lse, float* __restrict__ s_raw) {
   using T = Tile<DT, D>;
-  constexpr int kWaves = kSweepThreads / 64;
-  __shared__ u32x4 s_tile[kWaves][T::kStages][T::kTileChunks];
+  constexpr int kWaves = Shape<DT, D>::kWaves;
+  constexpr int kStages = Shape<DT, D>::kStages;
+  __shared__ u32x4 s_tile[kWaves][kStages][T::kTileChunks];
   __shared__ __attribute__((aligned(16))) float s_bias[GT * 32];
 
   const int lane = threadIdx.x & 63, wave = wave_index();
@@ -384,13 +370,62 @@ scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long
   const char* kg = reinterpret_cast<const char*>(k) + (long long)g * n * T::kRowBytes;
   const long long n_prefix = n - w;
 
-  // exponent bias of every (head, row): log2 of (row normaliser * w), +inf for padding rows
-  if (threadIdx.x < GT * 32) {
+  constexpr int kThreads = Shape<DT, D>::kThreads;
+  constexpr int kRows = GT * 32;
+  constexpr int kSlices = kThreads / kRows;
+  __shared__ float2 s_merge[kThreads];
+
+  // start the ring first: these loads only need the key pointer
+  TileDma<DT, D> dma;
+  dma.init(lane);
+  const long long n_tiles = (n_prefix + kTileKeys - 1) / kTileKeys;
+  const long long t_begin = (long long)blockIdx.x * tiles_per_block;
+  long long t_end = t_begin + tiles_per_block;
+  if (t_end > n_tiles) t_end = n_tiles;
+  const long long first = t_begin + wave;
+  const int cnt = first < t_end ? (int)((t_end - first + kWaves - 1) / kWaves) : 0;
+  u32x4* ring = s_tile[wave][0];
+#pragma unroll
+  for (int p = 0; p < kStages - 1; ++p)
+    if (p < cnt) dma.issue(kg, first + (long long)p * kWaves, n, lane, ring + p * T::kTileChunks);
+
+  // exponent bias of every (head, row): log2 of (row normaliser * w), +inf for padding rows.
+  // Thread (row, slice) merges its slice of the workgroup partials in workgroup order, then the
+  // slices are merged in slice order.
+  {
+    const int row = threadIdx.x % kRows, slice = threadIdx.x / kRows;
+    float m = -INFINITY, z = 0.0f;
+    if (lse == nullptr) {
+      const int per = (stat_blocks + kSlices - 1) / kSlices;
+      const int b_begin = slice * per, b_end = (b_begin + per < stat_blocks) ? b_begin + per : stat_blocks;
+      const float2* part = stat_part + (long long)blockIdx.y * stat_blocks * kRows + row;
+      for (int b0 = b_begin; b0 < b_end; b0 += 16) {
+        float2 x[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u)
+          x[u] = (b0 + u < b_end) ? part[(long long)(b0 + u) * kRows] : make_float2(-INFINITY, 0.0f);
+#pragma unroll
+        for (int u = 0; u < 16; ++u) merge_stat(m, z, x[u].x, x[u].y, c2);
+      }
+    }
+    s_merge[slice * kRows + row] = make_float2(m, z);
+  }
+  __syncthreads();
+  if (threadIdx.x < kRows) {
     const int t = threadIdx.x >> 5, rr = threadIdx.x & 31;
     float bias = INFINITY;
     if (t < nh && rr < w) {
-      bias = (lse != nullptr) ? lse[(long long)(h0 + t) * w + rr] * kLog2e
-                              : row_bias[(long long)blockIdx.y * (GT * 32) + threadIdx.x];
+      if (lse != nullptr) {
+        bias = lse[(long long)(h0 + t) * w + rr] * kLog2e;
+      } else {
+        float m = -INFINITY, z = 0.0f;
+#pragma unroll
+        for (int sl = 0; sl < kSlices; ++sl) {
+          const float2 x = s_merge[sl * kRows + threadIdx.x];
+          merge_stat(m, z, x.x, x.y, c2);
+        }
+        bias = m * c2 + log2f(z);
+      }
       bias += log2f((float)w);
     }
     s_bias[threadIdx.x] = bias;
@@ -398,34 +433,37 @@ scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long
 
   u32x4 qf[GT][T::kSteps];
   load_q<DT, D, GT>(q_win, h0, nh, w, lane, qf);
-  TileDma<DT, D> dma;
-  dma.init(lane);
   __syncthreads();
 
   const int half = lane >> 5;
   // rows held by this lane in result register v: 8 * (v / 4) + 4 * half + v % 4 -> four float4 per head
   const float4* bias4 = reinterpret_cast<const float4*>(s_bias) + half;
 
-  const long long n_tiles = (n_prefix + kTileKeys - 1) / kTileKeys;
-  const long long t_begin = (long long)blockIdx.x * tiles_per_block;
-  long long t_end = t_begin + tiles_per_block;
-  if (t_end > n_tiles) t_end = n_tiles;
-
-  const long long first = t_begin + wave;
-  const int cnt = first < t_end ? (int)((t_end - first + kWaves - 1) / kWaves) : 0;
-  u32x4* ring = s_tile[wave][0];
-#pragma unroll
-  for (int p = 0; p < T::kStages - 1; ++p)
-    if (p < cnt) dma.issue(kg, first + (long long)p * kWaves, n, lane, ring + p * T::kTileChunks);
+  // The result of a tile is stored one iteration later, right after the next tile's arrival wait:
+  // the store then has a whole iteration to complete before a wait counts it among the older
+  // operations, instead of stalling every iteration on its acknowledgement.
+  float pend = 0.0f;
+  int pend_key = -1;                 // n < 2^31
+  auto store_result = [&](int key, float value) {
+    if (half == 0 && key >= 0 && key < n_prefix) {
+      float* dst = s_raw + (long long)g * n_prefix + key;
+      if (n_chunks == 1) {
+        *dst = value;
+      } else {   // heads of the group are split over workgroups: non-negative floats order as integers
+        atomicMax(reinterpret_cast<unsigned int*>(dst), __float_as_uint(value));
+      }
+    }
+  };
   for (int it = 0; it < cnt; ++it) {
     const long long tile = first + (long long)it * kWaves;
-    const int ahead = it + T::kStages - 1;
+    const int ahead = it + kStages - 1;
     if (ahead < cnt)
-      dma.issue(kg, first + (long long)ahead * kWaves, n, lane, ring + (ahead % T::kStages) * T::kTileChunks);
-    const int younger = cnt - 1 - it < T::kStages - 1 ? cnt - 1 - it : T::kStages - 1;
+      dma.issue(kg, first + (long long)ahead * kWaves, n, lane, ring + (ahead % kStages) * T::kTileChunks);
+    const int younger = cnt - 1 - it < kStages - 1 ? cnt - 1 - it : kStages - 1;
     wait_tile<DT, D>(younger);
+    store_result(pend_key, pend);
     u32x4 kf[T::kSteps];
-    lds_to_frag<DT, D>(ring + (it % T::kStages) * T::kTileChunks, lane, kf);
+    lds_to_frag<DT, D>(ring + (it % kStages) * T::kTileChunks, lane, kf);
     asm volatile("" ::: "memory");   // later loads into this ring stage stay below these reads
 
     float best = 0.0f;
@@ -447,16 +485,10 @@ scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long
       best = fmaxf(best, ps);
       acc = nxt;
     }
-    const long long key = tile * kTileKeys + (lane & 31);
-    if (half == 0 && key < n_prefix) {
-      float* dst = s_raw + (long long)g * n_prefix + key;
-      if (n_chunks == 1) {
-        *dst = best;
-      } else {   // heads of the group are split over workgroups: non-negative floats order as integers
-        atomicMax(reinterpret_cast<unsigned int*>(dst), __float_as_uint(best));
-      }
-    }
+    pend = best;
+    pend_key = (int)(tile * kTileKeys) + (lane & 31);
   }
+  store_result(pend_key, pend);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -681,10 +713,8 @@ ScoreWorkspace make_score_workspace(const lava_layer_desc& d, int64_t n) {
   off += align_up(sizeof(float) * (size_t)d.n_kv_heads * (size_t)(n - d.window));
   w.off_ent_part = off;
   off += align_up(sizeof(double2) * (size_t)d.n_kv_heads * pool_blocks(d, n));
-  w.off_row_bias = off;
-  off += align_up(sizeof(float) * (size_t)d.n_kv_heads * p.n_chunks * p.chunk_heads * 32);
   w.off_counter = off;
-  off += align_up(sizeof(uint32_t) * kArriveWords * (1 + (size_t)d.n_kv_heads * p.n_chunks));
+  off += align_up(sizeof(uint32_t) * kArriveWords);
   w.bytes = off;
   return w;
 }
@@ -697,8 +727,7 @@ int32_t launch_vnorm(const lava_layer_desc& d, int64_t n, const void* v, float* 
   ProfScope ps(KID_VNORM, s);
 #define LAVA_VNORM(DTV, L)                                                                    \
   hipLaunchKernelGGL((vnorm_kernel<DTV, L>), grid, block, 0, s, static_cast<const u32x4*>(v), \
-                     (long long)n, rows_per_block, vnorm_part, counters,                      \
-                     kArriveWords * (1 + d.n_kv_heads * p.n_chunks))
+                     (long long)n, rows_per_block, vnorm_part, counters, kArriveWords)
   if (d.dtype == LAVA_BF16 && lpr == 8) LAVA_VNORM(LAVA_BF16, 8);
   else if (d.dtype == LAVA_BF16 && lpr == 16) LAVA_VNORM(LAVA_BF16, 16);
   else if (d.dtype == LAVA_F32 && lpr == 16) LAVA_VNORM(LAVA_F32, 16);
@@ -734,28 +763,25 @@ static float exp2_scale(const lava_layer_desc& d) {
   } while (0)
 
 int32_t launch_stats(const lava_layer_desc& d, int64_t n, const void* q_win, const void* k,
-                     float2* stat_part, float* row_bias, uint32_t* counters, const SweepPlan& p,
-                     hipStream_t s) {
-  if (d.n_kv_heads * p.n_chunks > kMaxStatTickets) return LAVA_ERR_SHAPE;
+                     float2* stat_part, const SweepPlan& p, hipStream_t s) {
   const int G = d.n_q_heads / d.n_kv_heads;
-  const dim3 grid(p.blocks_x, d.n_kv_heads * p.n_chunks), block(kSweepThreads);
+  const dim3 grid(p.blocks_x, d.n_kv_heads * p.n_chunks);
   const float c2 = exp2_scale(d);
   ProfScope ps(KID_STATS, s);
 #define LAVA_STATS(DTV, DV, GTV)                                                              \
-  hipLaunchKernelGGL((stats_kernel<DTV, DV, GTV>), grid, block, 0, s,                         \
+  hipLaunchKernelGGL((stats_kernel<DTV, DV, GTV>), grid, dim3(Shape<DTV, DV>::kThreads), 0, s,                         \
                      static_cast<const u32x4*>(q_win), static_cast<const u32x4*>(k),          \
-                     (long long)n, d.window, G, p.n_chunks, c2, p.tiles_per_block, stat_part,    \
-                     row_bias, counters)
+                     (long long)n, d.window, G, p.n_chunks, c2, p.tiles_per_block, stat_part)
   LAVA_SWEEP_DISPATCH(LAVA_STATS);
 #undef LAVA_STATS
   return launch_status();
 }
 
 int32_t launch_scores(const lava_layer_desc& d, int64_t n, const void* q_win, const void* k,
-                      const float* row_bias, const float* lse, float* s_raw, const SweepPlan& p,
+                      const float2* stat_part, const float* lse, float* s_raw, const SweepPlan& p,
                       hipStream_t s) {
   const int G = d.n_q_heads / d.n_kv_heads;
-  const dim3 grid(p.blocks_x, d.n_kv_heads * p.n_chunks), block(kSweepThreads);
+  const dim3 grid(p.blocks_x, d.n_kv_heads * p.n_chunks);
   const float c2 = exp2_scale(d);
   ProfScope ps(KID_SCORES, s);
   if (p.n_chunks > 1) {
@@ -766,10 +792,10 @@ int32_t launch_scores(const lava_layer_desc& d, int64_t n, const void* q_win, co
                        s_raw, count);
   }
 #define LAVA_SCORES(DTV, DV, GTV)                                                             \
-  hipLaunchKernelGGL((scores_kernel<DTV, DV, GTV>), grid, block, 0, s,                        \
+  hipLaunchKernelGGL((scores_kernel<DTV, DV, GTV>), grid, dim3(Shape<DTV, DV>::kThreads), 0, s,                        \
                      static_cast<const u32x4*>(q_win), static_cast<const u32x4*>(k),          \
-                     (long long)n, d.window, G, p.n_chunks, c2, p.tiles_per_block, row_bias,  \
-                     lse, s_raw)
+                     (long long)n, d.window, G, p.n_chunks, c2, p.tiles_per_block, stat_part, \
+                     p.blocks_x, lse, s_raw)
   LAVA_SWEEP_DISPATCH(LAVA_SCORES);
 #undef LAVA_SCORES
   return launch_status();

@@ -141,15 +141,14 @@ int32_t lava_window_scores(const lava_layer_desc* desc, int32_t batch, const int
     float* s_raw = reinterpret_cast<float*>(ws + w.off_sraw);
     double2* ent_part = reinterpret_cast<double2*>(ws + w.off_ent_part);
     uint32_t* counters = reinterpret_cast<uint32_t*>(ws + w.off_counter);
-    float* row_bias = reinterpret_cast<float*>(ws + w.off_row_bias);
 
     st = launch_vnorm(d, n, vb, vnorm_part, counters, plan, s);
     if (st != LAVA_OK) return st;
     if (lse_b == nullptr) {
-      st = launch_stats(d, n, qb, kb, stat_part, row_bias, counters, plan, s);
+      st = launch_stats(d, n, qb, kb, stat_part, plan, s);
       if (st != LAVA_OK) return st;
     }
-    st = launch_scores(d, n, qb, kb, row_bias, lse_b, s_raw, plan, s);
+    st = launch_scores(d, n, qb, kb, stat_part, lse_b, s_raw, plan, s);
     if (st != LAVA_OK) return st;
     st = launch_poolstat(d, n, s_raw, vnorm_part, plan.vnorm_blocks, sc, vbar + (size_t)b * d.n_kv_heads,
                          layer_stat + b, ent_part, counters, s);
