@@ -52,6 +52,8 @@ struct SweepPlan {
   int blocks_x;        // workgroups along the key axis per (KV head, chunk)
   int tiles_per_block; // key tiles per workgroup
   int vnorm_blocks;    // workgroups per KV head of the value-norm kernel
+  int vnorm_tiles_per_block;
+  bool fused_pool;     // the scores kernel also pools, scales and forms the layer statistic
 };
 SweepPlan make_sweep_plan(const lava_layer_desc& d, int64_t n);
 
@@ -72,8 +74,9 @@ int32_t launch_vnorm(const lava_layer_desc& d, int64_t n, const void* v, float* 
 int32_t launch_stats(const lava_layer_desc& d, int64_t n, const void* q_win, const void* k,
                      float2* stat_part, const SweepPlan& p, hipStream_t s);
 int32_t launch_scores(const lava_layer_desc& d, int64_t n, const void* q_win, const void* k,
-                      const float2* stat_part, const float* lse, float* s_raw, const SweepPlan& p,
-                      hipStream_t s);
+                      const float2* stat_part, const float* lse, float* s_raw, const float* vnorm_part,
+                      float* scores, float* vbar, float* layer_stat, double2* ent_part, uint32_t* counters,
+                      const SweepPlan& p, hipStream_t s);
 int32_t launch_poolstat(const lava_layer_desc& d, int64_t n, const float* s_raw,
                         const float* vnorm_part, int vnorm_blocks, float* scores, float* vbar,
                         float* layer_stat, double2* ent_part, uint32_t* counters, hipStream_t s);

@@ -222,6 +222,51 @@ __device__ __forceinline__ f32x16 dot_tile(const u32x4 (&kf)[Tile<DT, D>::kSteps
 // (tile numbers, ring stages, loop bounds) stays in scalar registers and scalar branches.
 __device__ __forceinline__ int wave_index() { return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
 
+// Layer statistic from per-lane partial sums S = sum s, T = sum s ln s (fp64): fixed-order reduction
+// over lanes (xor tree), wavefronts and, by the last workgroup to arrive, workgroups; then
+// e = (ln S - T / S) / n_entries  (Eq. 4-5 in closed form).  Contains workgroup barriers.
+template <int THREADS>
+__device__ __forceinline__ void entropy_finish(double acc_s, double acc_t, double2* __restrict__ ent_part,
+                                               uint32_t* __restrict__ counters, unsigned int n_blocks,
+                                               unsigned int block_id, double n_entries,
+                                               float* __restrict__ layer_stat, double* s_s, double* s_t,
+                                               unsigned int* s_last) {
+  constexpr int kW = THREADS / 64;
+  for (int off = 32; off > 0; off >>= 1) {
+    acc_s += __shfl_xor(acc_s, off);
+    acc_t += __shfl_xor(acc_t, off);
+  }
+  if ((threadIdx.x & 63) == 0) { s_s[threadIdx.x >> 6] = acc_s; s_t[threadIdx.x >> 6] = acc_t; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    double S = 0.0, Tt = 0.0;
+    for (int i = 0; i < kW; ++i) { S += s_s[i]; Tt += s_t[i]; }
+    double2* mine = &ent_part[block_id];
+    st_dev_f64(&mine->x, S);
+    st_dev_f64(&mine->y, Tt);
+  }
+  if (!arrive_last(&counters[kCounterPool], n_blocks, block_id, s_last)) return;
+  // last workgroup: thread t sums partials t, t + THREADS, ... then the same fixed tree as above
+  double S = 0.0, Tt = 0.0;
+  for (unsigned int i = threadIdx.x; i < n_blocks; i += THREADS) {
+    S += ld_dev_f64(&ent_part[i].x);
+    Tt += ld_dev_f64(&ent_part[i].y);
+  }
+  for (int off = 32; off > 0; off >>= 1) {
+    S += __shfl_xor(S, off);
+    Tt += __shfl_xor(Tt, off);
+  }
+  __syncthreads();
+  if ((threadIdx.x & 63) == 0) { s_s[threadIdx.x >> 6] = S; s_t[threadIdx.x >> 6] = Tt; }
+  __syncthreads();
+  if (threadIdx.x != 0) return;
+  S = 0.0; Tt = 0.0;
+  for (int i = 0; i < kW; ++i) { S += s_s[i]; Tt += s_t[i]; }
+  double e = 0.0;
+  if (S > 0.0) e = (log(S) - Tt / S) / n_entries;
+  layer_stat[0] = (float)e;
+}
+
 // ------------------------------------------------------------------------------------------
 // stats: per workgroup and per (head of the chunk, window row) the running maximum of the raw
 // dot products and sum of exp2((dot - max) * c2) over the workgroup's keys, c2 = scale * log2 e.
@@ -352,16 +397,36 @@ stats_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long 
 // in the same fixed order (deterministic) and with independent loads, or taken from a
 // caller-supplied log-sum-exp.
 // ------------------------------------------------------------------------------------------
-template <int DT, int D, int GT>
+//
+// FUSED (all heads of the group in one workgroup, at most kFusedTiles tiles per workgroup): the
+// workgroup keeps the raw scores of its key span in LDS, recomputes one tile on either side of
+// the span (the pooling halo; 2 extra tiles per workgroup instead of a trip through HBM and
+// another launch), and finishes the scores itself: max-pool, value factor, +inf for the window
+// entries, and the layer statistic.  Otherwise the raw scores go to s_raw for poolstat_kernel.
+constexpr int kFusedTiles = 128;
+
+struct PoolArgs {
+  const float* vnorm_part;   // [H_kv][vnorm_blocks] value-norm partials
+  int vnorm_blocks;
+  int pool_half;
+  float* scores;             // [H_kv][n]
+  float* vbar;               // [H_kv]
+  float* layer_stat;         // [1]
+  double2* ent_part;         // [workgroups]
+  uint32_t* counters;
+};
+
+template <int DT, int D, int GT, bool FUSED>
 __global__ void __launch_bounds__((Shape<DT, D>::kThreads))
 scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long long n, int w, int G,
               int n_chunks, float c2, int tiles_per_block, const float2* __restrict__ stat_part,
-              int stat_blocks, const float* __restrict__ lse, float* __restrict__ s_raw) {
+              int stat_blocks, const float* __restrict__ lse, float* __restrict__ s_raw, PoolArgs pa) {
   using T = Tile<DT, D>;
   constexpr int kWaves = Shape<DT, D>::kWaves;
   constexpr int kStages = Shape<DT, D>::kStages;
   __shared__ u32x4 s_tile[kWaves][kStages][T::kTileChunks];
   __shared__ __attribute__((aligned(16))) float s_bias[GT * 32];
+  __shared__ float s_span[FUSED ? (kFusedTiles + 2) * kTileKeys : 1];   // raw scores of the span + halo tiles
 
   const int lane = threadIdx.x & 63, wave = wave_index();
   const int g = blockIdx.y / n_chunks, chunk = blockIdx.y % n_chunks;
@@ -369,6 +434,12 @@ scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long
   const int nh = (G - chunk * GT) < GT ? (G - chunk * GT) : GT;
   const char* kg = reinterpret_cast<const char*>(k) + (long long)g * n * T::kRowBytes;
   const long long n_prefix = n - w;
+
+  float vb = 0.0f;   // this thread's share of the head's value-norm partials (reduced after the sweep)
+  if constexpr (FUSED) {
+    for (int i = threadIdx.x; i < pa.vnorm_blocks; i += Shape<DT, D>::kThreads)
+      vb = fmaxf(vb, pa.vnorm_part[(long long)g * pa.vnorm_blocks + i]);
+  }
 
   constexpr int kThreads = Shape<DT, D>::kThreads;
   constexpr int kRows = GT * 32;
@@ -383,11 +454,21 @@ scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long
   long long t_end = t_begin + tiles_per_block;
   if (t_end > n_tiles) t_end = n_tiles;
   const long long first = t_begin + wave;
-  const int cnt = first < t_end ? (int)((t_end - first + kWaves - 1) / kWaves) : 0;
+  const int cnt_own = first < t_end ? (int)((t_end - first + kWaves - 1) / kWaves) : 0;
+  // pooling halo: the last two wavefronts also take the tile before / after the workgroup's span
+  long long halo_tile = -1;
+  if constexpr (FUSED) {
+    if (t_begin < t_end) {
+      if (wave == kWaves - 1 && t_begin > 0) halo_tile = t_begin - 1;
+      if (wave == kWaves - 2 && t_end < n_tiles) halo_tile = t_end;
+    }
+  }
+  const int cnt = cnt_own + (halo_tile >= 0 ? 1 : 0);
+  auto tile_at = [&](int j) -> long long { return j < cnt_own ? first + (long long)j * kWaves : halo_tile; };
   u32x4* ring = s_tile[wave][0];
 #pragma unroll
   for (int p = 0; p < kStages - 1; ++p)
-    if (p < cnt) dma.issue(kg, first + (long long)p * kWaves, n, lane, ring + p * T::kTileChunks);
+    if (p < cnt) dma.issue(kg, tile_at(p), n, lane, ring + p * T::kTileChunks);
 
   // exponent bias of every (head, row): log2 of (row normaliser * w), +inf for padding rows.
   // Thread (row, slice) merges its slice of the workgroup partials in workgroup order, then the
@@ -455,13 +536,12 @@ scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long
     }
   };
   for (int it = 0; it < cnt; ++it) {
-    const long long tile = first + (long long)it * kWaves;
+    const long long tile = tile_at(it);
     const int ahead = it + kStages - 1;
-    if (ahead < cnt)
-      dma.issue(kg, first + (long long)ahead * kWaves, n, lane, ring + (ahead % kStages) * T::kTileChunks);
+    if (ahead < cnt) dma.issue(kg, tile_at(ahead), n, lane, ring + (ahead % kStages) * T::kTileChunks);
     const int younger = cnt - 1 - it < kStages - 1 ? cnt - 1 - it : kStages - 1;
     wait_tile<DT, D>(younger);
-    store_result(pend_key, pend);
+    if constexpr (!FUSED) store_result(pend_key, pend);
     u32x4 kf[T::kSteps];
     lds_to_frag<DT, D>(ring + (it % kStages) * T::kTileChunks, lane, kf);
     asm volatile("" ::: "memory");   // later loads into this ring stage stay below these reads
@@ -485,71 +565,146 @@ scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long
       best = fmaxf(best, ps);
       acc = nxt;
     }
-    pend = best;
-    pend_key = (int)(tile * kTileKeys) + (lane & 31);
-  }
-  store_result(pend_key, pend);
-}
-
-// ------------------------------------------------------------------------------------------
-// vnorm: per-workgroup maximum over rows of sum_c |V[g, k, c]|, all n rows.
-// ------------------------------------------------------------------------------------------
-template <int DT>
-__device__ __forceinline__ float abs_sum16(const u32x4& x) {
-  if constexpr (DT == LAVA_BF16) {
-    float s = 0.0f;
-    const unsigned int u[4] = {x.x, x.y, x.z, x.w};
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      s += fabsf(__uint_as_float(u[i] << 16));
-      s += fabsf(__uint_as_float(u[i] & 0xffff0000u));
+    if constexpr (FUSED) {
+      if (half == 0) s_span[(int)(tile - t_begin + 1) * kTileKeys + lane] = best;
+    } else {
+      pend = best;
+      pend_key = (int)(tile * kTileKeys) + (lane & 31);
     }
-    return s;
+  }
+  if constexpr (!FUSED) {
+    store_result(pend_key, pend);
   } else {
-    return fabsf(__uint_as_float(x.x)) + fabsf(__uint_as_float(x.y)) + fabsf(__uint_as_float(x.z)) +
-           fabsf(__uint_as_float(x.w));
+    // ---- finish the scores of this span: Vbar, max-pool, +inf window entries, layer statistic
+    __shared__ float s_vb[kWaves];
+    __shared__ double s_s[kWaves], s_t[kWaves];
+    __shared__ unsigned int s_last;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) vb = fmaxf(vb, __shfl_xor(vb, off));
+    if ((threadIdx.x & 63) == 0) s_vb[wave] = vb;
+    __syncthreads();                       // s_span complete, s_vb visible
+    vb = s_vb[0];
+#pragma unroll
+    for (int i = 1; i < kWaves; ++i) vb = fmaxf(vb, s_vb[i]);
+    if (blockIdx.x == 0 && threadIdx.x == 0) pa.vbar[g] = vb;
+
+    const long long p_begin = t_begin * kTileKeys;
+    long long p_end = t_end * kTileKeys;
+    if (p_end > n_prefix) p_end = n_prefix;
+    const long long span0 = (t_begin - 1) * kTileKeys;      // position held by s_span[0]
+    double acc_s = 0.0, acc_t = 0.0;
+    for (long long p = p_begin + threadIdx.x; p < p_end; p += Shape<DT, D>::kThreads) {
+      float m = s_span[(int)(p - span0)];
+      for (int dd = 1; dd <= pa.pool_half; ++dd) {
+        if (p - dd >= 0) m = fmaxf(m, s_span[(int)(p - dd - span0)]);
+        if (p + dd < n_prefix) m = fmaxf(m, s_span[(int)(p + dd - span0)]);
+      }
+      const float sc = vb * m;
+      pa.scores[(long long)g * n + p] = sc;
+      acc_s += (double)sc;
+      if (sc > 0.0f) acc_t += (double)sc * (double)logf(sc);
+    }
+    // the workgroup that owns the head's last prefix tile also writes the window entries
+    if (t_begin < t_end && t_end == n_tiles && threadIdx.x < (unsigned)w)
+      pa.scores[(long long)g * n + n_prefix + threadIdx.x] = INFINITY;
+    entropy_finish<Shape<DT, D>::kThreads>(acc_s, acc_t, pa.ent_part, pa.counters, gridDim.x * gridDim.y,
+                                           blockIdx.y * gridDim.x + blockIdx.x,
+                                           (double)gridDim.y * (double)n_prefix, pa.layer_stat, s_s, s_t,
+                                           &s_last);
   }
 }
 
-constexpr int kVnormThreads = 256;
-constexpr int kVnormUnroll = 4;
+// ------------------------------------------------------------------------------------------
+// vnorm: per-workgroup maximum over rows of sum_c |V[g, k, c]|, all n rows.  Pure streaming: the
+// same direct-to-LDS tile ring as the key sweeps (it sustains more bandwidth than loads into
+// registers), 32-row tiles, no matrix work.
+// ------------------------------------------------------------------------------------------
 
-template <int DT, int LPR>   // LPR lanes (16 bytes each) per row
-__global__ void __launch_bounds__(kVnormThreads)
-vnorm_kernel(const u32x4* __restrict__ v, long long n, long long rows_per_block,
-             float* __restrict__ vnorm_part, uint32_t* __restrict__ counters, int n_counter_words) {
-  __shared__ float s_max[kVnormThreads / 64];
-  if (blockIdx.x == 0 && blockIdx.y == 0)
-    for (int i = threadIdx.x; i < n_counter_words; i += kVnormThreads) counters[i] = 0u;
-  const int g = blockIdx.y;
-  const u32x4* vg = v + (long long)g * n * LPR;
-  const long long row_begin = (long long)blockIdx.x * rows_per_block;
-  long long row_end = row_begin + rows_per_block;
-  if (row_end > n) row_end = n;
-  constexpr int kRowsPerIter = kVnormThreads / LPR;
-  const int sub = threadIdx.x / LPR, c = threadIdx.x % LPR;
-  float best = 0.0f;
-  for (long long row = row_begin; row < row_end; row += kRowsPerIter * kVnormUnroll) {
-    u32x4 x[kVnormUnroll];
+// sum of |x| over 16 bytes, added to s
+template <int DT>
+__device__ __forceinline__ float abs_sum16(const u32x4& x, float s) {
+  const unsigned int u[4] = {x.x, x.y, x.z, x.w};
+  if constexpr (DT == LAVA_BF16) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
-    for (int u = 0; u < kVnormUnroll; ++u) {
-      const long long rr = row + u * kRowsPerIter + sub;
-      x[u] = rr < row_end ? vg[rr * LPR + c] : u32x4{0u, 0u, 0u, 0u};
-    }
+    for (int i = 0; i < 4; ++i)   // clear both sign bits, then a.x * 1 + a.y * 1 + s in one instruction
+      s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, u[i] & 0x7fff7fffu), ones, s, false);
+  } else {
 #pragma unroll
-    for (int u = 0; u < kVnormUnroll; ++u) {
-      float s = abs_sum16<DT>(x[u]);
-#pragma unroll
-      for (int off = 1; off < LPR; off <<= 1) s += __shfl_xor(s, off);
-      best = fmaxf(best, s);
-    }
+    for (int i = 0; i < 4; ++i) s += fabsf(__uint_as_float(u[i]));
   }
+  return s;
+}
+
+template <int DT, int D>
+struct VShape {
+  static constexpr int kWaves = Tile<DT, D>::kTileBytes > 8192 ? 4 : 8;
+  static constexpr int kThreads = kWaves * 64;
+  static constexpr int kStagesRaw = (128 * 1024) / (kWaves * Tile<DT, D>::kTileBytes);
+  static constexpr int kStages = kStagesRaw > 4 ? 4 : kStagesRaw;
+  static_assert(kStages >= 1, "tile too large for the ring");
+};
+
+template <int DT, int D>
+__global__ void __launch_bounds__((VShape<DT, D>::kThreads))
+vnorm_kernel(const u32x4* __restrict__ v, long long n, int tiles_per_block, float* __restrict__ vnorm_part,
+             uint32_t* __restrict__ counters, int n_counter_words) {
+  using T = Tile<DT, D>;
+  constexpr int kWaves = VShape<DT, D>::kWaves;
+  constexpr int kStages = VShape<DT, D>::kStages < 2 ? 2 : VShape<DT, D>::kStages;
+  __shared__ u32x4 s_tile[kWaves][kStages][T::kTileChunks];
+  __shared__ float s_max[kWaves];
+  if (blockIdx.x == 0 && blockIdx.y == 0)
+    for (int i = threadIdx.x; i < n_counter_words; i += VShape<DT, D>::kThreads) counters[i] = 0u;
+
+  const int lane = threadIdx.x & 63, wave = wave_index();
+  const int g = blockIdx.y;
+  const char* vg = reinterpret_cast<const char*>(v) + (long long)g * n * T::kRowBytes;
+  TileDma<DT, D> dma;
+  dma.init(lane);
+
+  const long long n_tiles = (n + kTileKeys - 1) / kTileKeys;
+  const long long t_begin = (long long)blockIdx.x * tiles_per_block;
+  long long t_end = t_begin + tiles_per_block;
+  if (t_end > n_tiles) t_end = n_tiles;
+  const long long first = t_begin + wave;
+  const int cnt = first < t_end ? (int)((t_end - first + kWaves - 1) / kWaves) : 0;
+  u32x4* ring = s_tile[wave][0];
+#pragma unroll
+  for (int p = 0; p < kStages - 1; ++p)
+    if (p < cnt) dma.issue(vg, first + (long long)p * kWaves, n, lane, ring + p * T::kTileChunks);
+  float best = 0.0f;
+  for (int it = 0; it < cnt; ++it) {
+    const int ahead = it + kStages - 1;
+    if (ahead < cnt)
+      dma.issue(vg, first + (long long)ahead * kWaves, n, lane, ring + (ahead % kStages) * T::kTileChunks);
+    const int younger = cnt - 1 - it < kStages - 1 ? cnt - 1 - it : kStages - 1;
+    switch (younger) {
+      case 0: wait_vmcnt<0>(); break;
+      case 1: wait_vmcnt<T::kLoads>(); break;
+      case 2: wait_vmcnt<2 * T::kLoads>(); break;
+      default: wait_vmcnt<3 * T::kLoads>(); break;
+    }
+    // each lane sums the half row it holds (row lane % 32; rows past n repeat row n - 1), the two
+    // halves are added across lanes
+    u32x4 f[T::kSteps];
+    lds_to_frag<DT, D>(ring + (it % kStages) * T::kTileChunks, lane, f);
+    asm volatile("" ::: "memory");   // later loads into this ring stage stay below these reads
+    float s = 0.0f;
+#pragma unroll
+    for (int j = 0; j < T::kSteps; ++j) s = abs_sum16<DT>(f[j], s);
+    s += __shfl_xor(s, 32);
+    best = fmaxf(best, s);
+  }
+#pragma unroll
   for (int off = 32; off > 0; off >>= 1) best = fmaxf(best, __shfl_xor(best, off));
-  if ((threadIdx.x & 63) == 0) s_max[threadIdx.x >> 6] = best;
+  if ((threadIdx.x & 63) == 0) s_max[wave] = best;
   __syncthreads();
   if (threadIdx.x == 0) {
     float m = s_max[0];
-    for (int i = 1; i < kVnormThreads / 64; ++i) m = fmaxf(m, s_max[i]);
+#pragma unroll
+    for (int i = 1; i < kWaves; ++i) m = fmaxf(m, s_max[i]);
     vnorm_part[(long long)g * gridDim.x + blockIdx.x] = m;
   }
 }
@@ -609,41 +764,9 @@ poolstat_kernel(const float* __restrict__ s_raw, long long n, int w, int pool_ha
       scores[(long long)g * n + p] = INFINITY;
     }
   }
-  // fixed-order reduction: lanes (xor tree), wavefronts, then workgroups in index order
-  for (int off = 32; off > 0; off >>= 1) {
-    acc_s += __shfl_xor(acc_s, off);
-    acc_t += __shfl_xor(acc_t, off);
-  }
-  if ((threadIdx.x & 63) == 0) { s_s[threadIdx.x >> 6] = acc_s; s_t[threadIdx.x >> 6] = acc_t; }
-  __syncthreads();
-  const unsigned int n_blocks = gridDim.x * gridDim.y;
-  if (threadIdx.x == 0) {
-    double S = 0.0, Tt = 0.0;
-    for (int i = 0; i < kPoolThreads / 64; ++i) { S += s_s[i]; Tt += s_t[i]; }
-    double2* mine = &ent_part[blockIdx.y * gridDim.x + blockIdx.x];
-    st_dev_f64(&mine->x, S);
-    st_dev_f64(&mine->y, Tt);
-  }
-  if (!arrive_last(&counters[kCounterPool], n_blocks, blockIdx.y * gridDim.x + blockIdx.x, &s_last)) return;
-  // last workgroup: thread t sums partials t, t + 256, ... then the same fixed tree as above
-  double S = 0.0, Tt = 0.0;
-  for (unsigned int i = threadIdx.x; i < n_blocks; i += kPoolThreads) {
-    S += ld_dev_f64(&ent_part[i].x);
-    Tt += ld_dev_f64(&ent_part[i].y);
-  }
-  for (int off = 32; off > 0; off >>= 1) {
-    S += __shfl_xor(S, off);
-    Tt += __shfl_xor(Tt, off);
-  }
-  __syncthreads();
-  if ((threadIdx.x & 63) == 0) { s_s[threadIdx.x >> 6] = S; s_t[threadIdx.x >> 6] = Tt; }
-  __syncthreads();
-  if (threadIdx.x != 0) return;
-  S = 0.0; Tt = 0.0;
-  for (int i = 0; i < kPoolThreads / 64; ++i) { S += s_s[i]; Tt += s_t[i]; }
-  double e = 0.0;
-  if (S > 0.0) e = (log(S) - Tt / S) / ((double)gridDim.y * (double)n_prefix);
-  layer_stat[0] = (float)e;
+  entropy_finish<kPoolThreads>(acc_s, acc_t, ent_part, counters, gridDim.x * gridDim.y,
+                               blockIdx.y * gridDim.x + blockIdx.x, (double)gridDim.y * (double)n_prefix,
+                               layer_stat, s_s, s_t, &s_last);
 }
 
 __global__ void __launch_bounds__(256) fill_zero_kernel(float* __restrict__ p, long long count) {
@@ -687,12 +810,19 @@ SweepPlan make_sweep_plan(const lava_layer_desc& d, int64_t n) {
   if (max_bx < 1) max_bx = 1;
   int64_t tpb = (n_tiles + max_bx - 1) / max_bx;
   if (tpb < 16) tpb = 16;
+  // all heads of a group in one workgroup -> the scores kernel can finish the scores itself, which
+  // needs the workgroup's span of raw scores in LDS: at most kFusedTiles tiles per workgroup
+  p.fused_pool = p.n_chunks == 1;
+  if (p.fused_pool && tpb > kFusedTiles) tpb = kFusedTiles;
   p.tiles_per_block = (int)tpb;
   p.blocks_x = (int)((n_tiles + tpb - 1) / tpb);
-  int64_t vb = (n + 1023) / 1024;      // at least 1024 rows per workgroup
-  if (vb > 256) vb = 256;
+  // value norms: one workgroup per CU as well, at least 8 tiles (one per wavefront) each
+  int64_t vb = target_wgs / d.n_kv_heads;
   if (vb < 1) vb = 1;
-  p.vnorm_blocks = (int)vb;
+  int64_t vtpb = (n_tiles + vb - 1) / vb;
+  if (vtpb < 8) vtpb = 8;
+  p.vnorm_tiles_per_block = (int)vtpb;
+  p.vnorm_blocks = (int)((n_tiles + vtpb - 1) / vtpb);
   return p;
 }
 
@@ -712,7 +842,9 @@ ScoreWorkspace make_score_workspace(const lava_layer_desc& d, int64_t n) {
   w.off_sraw = off;
   off += align_up(sizeof(float) * (size_t)d.n_kv_heads * (size_t)(n - d.window));
   w.off_ent_part = off;
-  off += align_up(sizeof(double2) * (size_t)d.n_kv_heads * pool_blocks(d, n));
+  const size_t ent_blocks = (size_t)pool_blocks(d, n) > (size_t)p.blocks_x * p.n_chunks
+                                ? (size_t)pool_blocks(d, n) : (size_t)p.blocks_x * p.n_chunks;
+  off += align_up(sizeof(double2) * (size_t)d.n_kv_heads * ent_blocks);
   w.off_counter = off;
   off += align_up(sizeof(uint32_t) * kArriveWords);
   w.bytes = off;
@@ -721,17 +853,16 @@ ScoreWorkspace make_score_workspace(const lava_layer_desc& d, int64_t n) {
 
 int32_t launch_vnorm(const lava_layer_desc& d, int64_t n, const void* v, float* vnorm_part,
                      uint32_t* counters, const SweepPlan& p, hipStream_t s) {
-  const int lpr = d.head_dim * (d.dtype == LAVA_BF16 ? 2 : 4) / 16;
-  const long long rows_per_block = (n + p.vnorm_blocks - 1) / p.vnorm_blocks;
-  const dim3 grid(p.vnorm_blocks, d.n_kv_heads), block(kVnormThreads);
+  const dim3 grid(p.vnorm_blocks, d.n_kv_heads);
   ProfScope ps(KID_VNORM, s);
-#define LAVA_VNORM(DTV, L)                                                                    \
-  hipLaunchKernelGGL((vnorm_kernel<DTV, L>), grid, block, 0, s, static_cast<const u32x4*>(v), \
-                     (long long)n, rows_per_block, vnorm_part, counters, kArriveWords)
-  if (d.dtype == LAVA_BF16 && lpr == 8) LAVA_VNORM(LAVA_BF16, 8);
-  else if (d.dtype == LAVA_BF16 && lpr == 16) LAVA_VNORM(LAVA_BF16, 16);
-  else if (d.dtype == LAVA_F32 && lpr == 16) LAVA_VNORM(LAVA_F32, 16);
-  else if (d.dtype == LAVA_F32 && lpr == 32) LAVA_VNORM(LAVA_F32, 32);
+#define LAVA_VNORM(DTV, DV)                                                                          \
+  hipLaunchKernelGGL((vnorm_kernel<DTV, DV>), grid, dim3(VShape<DTV, DV>::kThreads), 0, s,           \
+                     static_cast<const u32x4*>(v), (long long)n, p.vnorm_tiles_per_block, vnorm_part, \
+                     counters, kArriveWords)
+  if (d.dtype == LAVA_BF16 && d.head_dim == 128) LAVA_VNORM(LAVA_BF16, 128);
+  else if (d.dtype == LAVA_BF16 && d.head_dim == 64) LAVA_VNORM(LAVA_BF16, 64);
+  else if (d.dtype == LAVA_F32 && d.head_dim == 64) LAVA_VNORM(LAVA_F32, 64);
+  else if (d.dtype == LAVA_F32 && d.head_dim == 128) LAVA_VNORM(LAVA_F32, 128);
   else return LAVA_ERR_SHAPE;
 #undef LAVA_VNORM
   return launch_status();
@@ -778,8 +909,18 @@ int32_t launch_stats(const lava_layer_desc& d, int64_t n, const void* q_win, con
 }
 
 int32_t launch_scores(const lava_layer_desc& d, int64_t n, const void* q_win, const void* k,
-                      const float2* stat_part, const float* lse, float* s_raw, const SweepPlan& p,
-                      hipStream_t s) {
+                      const float2* stat_part, const float* lse, float* s_raw, const float* vnorm_part,
+                      float* scores, float* vbar, float* layer_stat, double2* ent_part, uint32_t* counters,
+                      const SweepPlan& p, hipStream_t s) {
+  PoolArgs pa;
+  pa.vnorm_part = vnorm_part;
+  pa.vnorm_blocks = p.vnorm_blocks;
+  pa.pool_half = d.pool_kernel / 2;
+  pa.scores = scores;
+  pa.vbar = vbar;
+  pa.layer_stat = layer_stat;
+  pa.ent_part = ent_part;
+  pa.counters = counters;
   const int G = d.n_q_heads / d.n_kv_heads;
   const dim3 grid(p.blocks_x, d.n_kv_heads * p.n_chunks);
   const float c2 = exp2_scale(d);
@@ -791,13 +932,21 @@ int32_t launch_scores(const lava_layer_desc& d, int64_t n, const void* q_win, co
     hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((count + 1023) / 1024)), dim3(256), 0, s,
                        s_raw, count);
   }
-#define LAVA_SCORES(DTV, DV, GTV)                                                             \
-  hipLaunchKernelGGL((scores_kernel<DTV, DV, GTV>), grid, dim3(Shape<DTV, DV>::kThreads), 0, s,                        \
-                     static_cast<const u32x4*>(q_win), static_cast<const u32x4*>(k),          \
-                     (long long)n, d.window, G, p.n_chunks, c2, p.tiles_per_block, stat_part, \
-                     p.blocks_x, lse, s_raw)
+#define LAVA_SCORES_ARGS                                                                                 \
+  static_cast<const u32x4*>(q_win), static_cast<const u32x4*>(k), (long long)n, d.window, G, p.n_chunks, \
+      c2, p.tiles_per_block, stat_part, p.blocks_x, lse, s_raw, pa
+#define LAVA_SCORES(DTV, DV, GTV)                                                                        \
+  do {                                                                                                   \
+    if (p.fused_pool)                                                                                    \
+      hipLaunchKernelGGL((scores_kernel<DTV, DV, GTV, true>), grid, dim3(Shape<DTV, DV>::kThreads), 0,   \
+                         s, LAVA_SCORES_ARGS);                                                           \
+    else                                                                                                 \
+      hipLaunchKernelGGL((scores_kernel<DTV, DV, GTV, false>), grid, dim3(Shape<DTV, DV>::kThreads), 0,  \
+                         s, LAVA_SCORES_ARGS);                                                           \
+  } while (0)
   LAVA_SWEEP_DISPATCH(LAVA_SCORES);
 #undef LAVA_SCORES
+#undef LAVA_SCORES_ARGS
   return launch_status();
 }
 

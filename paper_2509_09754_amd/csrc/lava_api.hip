@@ -148,9 +148,10 @@ int32_t lava_window_scores(const lava_layer_desc* desc, int32_t batch, const int
       st = launch_stats(d, n, qb, kb, stat_part, plan, s);
       if (st != LAVA_OK) return st;
     }
-    st = launch_scores(d, n, qb, kb, stat_part, lse_b, s_raw, plan, s);
+    st = launch_scores(d, n, qb, kb, stat_part, lse_b, s_raw, vnorm_part, sc, vbar + (size_t)b * d.n_kv_heads,
+                       layer_stat + b, ent_part, counters, plan, s);
     if (st != LAVA_OK) return st;
-    st = launch_poolstat(d, n, s_raw, vnorm_part, plan.vnorm_blocks, sc, vbar + (size_t)b * d.n_kv_heads,
+    if (!plan.fused_pool) st = launch_poolstat(d, n, s_raw, vnorm_part, plan.vnorm_blocks, sc, vbar + (size_t)b * d.n_kv_heads,
                          layer_stat + b, ent_part, counters, s);
     if (st != LAVA_OK) return st;
     tok += n;
