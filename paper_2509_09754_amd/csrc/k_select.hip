@@ -10,7 +10,7 @@
 // concatenated, ascending position inside each head".
 //
 // The whole selection is latency-bound (a few MiB of scores), so it runs as ONE kernel whose
-// workgroups (1024 lanes, 16 scores per lane in registers) meet at five grid-wide barriers; every
+// workgroups (1024 lanes, 16 scores per lane in registers) meet at four grid-wide barriers; every
 // workgroup derives the digit picks and its output offset redundantly from the shared
 // histograms / per-workgroup counts, so no workgroup waits for a "leader".  Inputs too large for
 // all workgroups to be resident at once fall back to the same phases as separate kernels.
@@ -245,12 +245,14 @@ __device__ __forceinline__ void prefix_phase(const unsigned int* __restrict__ bl
   __syncthreads();
 }
 
-// Ordered write of this workgroup's survivors; survivors per head are added to head_counts.
+// Ordered write of this workgroup's survivors; survivors per head are added to head_counts and the
+// head offsets are written by the lanes that own the first entry of each head.
 __device__ __forceinline__ void write_phase(const float (&val)[kSelPerThread], long long total, int n_heads,
                                             const int64_t* __restrict__ seg_offsets, unsigned int gt_mask,
                                             unsigned int eq_mask, long long need, long long capacity,
                                             long long gt_blocks_before, long long eq_blocks_before,
-                                            SelShared& sh, int32_t* __restrict__ head_counts,
+                                            long long need_total, SelShared& sh,
+                                            int32_t* __restrict__ head_counts, int64_t* __restrict__ head_offsets,
                                             int32_t* __restrict__ kept_idx, float* __restrict__ kept_scores) {
   if (threadIdx.x <= n_heads) {
     const long long seg = total / n_heads;
@@ -276,8 +278,17 @@ __device__ __forceinline__ void write_phase(const float (&val)[kSelPerThread], l
   long long eq_before = eq_blocks_before + (long long)(excl & 0xffffu);
 
   const long long first = (long long)blockIdx.x * kSelChunk + threadIdx.x * kSelPerThread;
+  // head_offsets[h] = survivors before the first entry of head h: written by the lane that owns that
+  // entry; segments starting at or beyond the end (empty trailing heads) and the two ends by lane 0
+  if (blockIdx.x == 0 && threadIdx.x == 0) {
+    const long long kept = need_total;
+    head_offsets[0] = 0;
+    head_offsets[n_heads] = kept;
+    for (int h = 1; h < n_heads; ++h)
+      if (sh.off[h] >= total) head_offsets[h] = kept;
+  }
   int g = 0;
-  while (g + 1 < n_heads && first >= sh.off[g + 1]) ++g;
+  while (g + 1 < n_heads && sh.off[g + 1] < first) ++g;     // segment starts equal to `first` are crossed below
   unsigned int local_cnt = 0u;
 #pragma unroll
   for (int j = 0; j < kSelPerThread; ++j) {
@@ -286,6 +297,7 @@ __device__ __forceinline__ void write_phase(const float (&val)[kSelPerThread], l
       if (local_cnt) atomicAdd(&sh.cnt[g], local_cnt);
       local_cnt = 0u;
       ++g;
+      if (p == sh.off[g] && p < total) head_offsets[g] = gt_before + (eq_before < need ? eq_before : need);
     }
     const bool is_gt = (gt_mask >> j) & 1u;
     const bool is_eq = (eq_mask >> j) & 1u;
@@ -307,18 +319,6 @@ __device__ __forceinline__ void write_phase(const float (&val)[kSelPerThread], l
     const unsigned int c = sh.cnt[threadIdx.x];
     if (c) __hip_atomic_fetch_add(reinterpret_cast<unsigned int*>(&head_counts[threadIdx.x]), c,
                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-  }
-}
-
-__device__ __forceinline__ void offsets_phase(int n_heads, const int32_t* __restrict__ head_counts,
-                                              int64_t* __restrict__ head_offsets) {
-  if (threadIdx.x == 0) {
-    long long acc = 0;
-    for (int h = 0; h < n_heads; ++h) {
-      head_offsets[h] = acc;
-      acc += (long long)ld_dev(reinterpret_cast<const unsigned int*>(&head_counts[h]));
-    }
-    head_offsets[n_heads] = acc;
   }
 }
 
@@ -369,6 +369,7 @@ sel_fused_kernel(const float* __restrict__ scores, long long total, int n_heads,
   Pick pk;
   pk.prefix = 0u;
   pk.need = effective_budget(budget, budget_dev, total);
+  const long long kept_total = pk.need;
 
   hist_phase<0>(val, total, pk.prefix, sh, hist);
   grid_sync(st, 1u);
@@ -385,14 +386,12 @@ sel_fused_kernel(const float* __restrict__ scores, long long total, int n_heads,
   grid_sync(st, 4u);
   long long gt_before, eq_before;
   prefix_phase(blk, (int)nb, sh, gt_before, eq_before);
-  write_phase(val, total, n_heads, seg_offsets, gt_mask, eq_mask, pk.need, budget, gt_before, eq_before, sh,
-              head_counts, kept_idx, kept_scores);
-  grid_sync(st, 5u);
-  if (blockIdx.x == 0) offsets_phase(n_heads, head_counts, head_offsets);
+  write_phase(val, total, n_heads, seg_offsets, gt_mask, eq_mask, pk.need, budget, gt_before, eq_before,
+              kept_total, sh, head_counts, head_offsets, kept_idx, kept_scores);
 }
 
 // The same phases as separate launches (kernel boundaries take the place of the grid barriers).
-// STEP 0..2: histogram pass STEP; 3: counts; 4: write; 5: head offsets.
+// STEP 0..2: histogram pass STEP; 3: counts; 4: write.
 template <int STEP>
 __global__ void __launch_bounds__(kSelThreads)
 sel_step_kernel(const float* __restrict__ scores, long long total, int n_heads,
@@ -402,16 +401,14 @@ sel_step_kernel(const float* __restrict__ scores, long long total, int n_heads,
                 int64_t* __restrict__ head_offsets, int32_t* __restrict__ kept_idx,
                 float* __restrict__ kept_scores) {
   __shared__ SelShared sh;
-  if constexpr (STEP == 5) {
-    offsets_phase(n_heads, head_counts, head_offsets);
-    return;
-  } else {
+  {
     const int nb = (int)gridDim.x;
     float val[kSelPerThread];
     load_chunk(scores, total, sh, val);
     Pick pk;
     pk.prefix = 0u;
     pk.need = effective_budget(budget, budget_dev, total);
+    const long long kept_total = pk.need;
     if constexpr (STEP >= 1) pk = pick_phase<0>(hist, pk, sh);
     if constexpr (STEP >= 2) pk = pick_phase<1>(hist + kBins, pk, sh);
     if constexpr (STEP >= 3) pk = pick_phase<2>(hist + 2 * kBins, pk, sh);
@@ -425,7 +422,7 @@ sel_step_kernel(const float* __restrict__ scores, long long total, int n_heads,
         long long gt_before, eq_before;
         prefix_phase(blk, nb, sh, gt_before, eq_before);
         write_phase(val, total, n_heads, seg_offsets, gt_mask, eq_mask, pk.need, budget, gt_before, eq_before,
-                    sh, head_counts, kept_idx, kept_scores);
+                    kept_total, sh, head_counts, head_offsets, kept_idx, kept_scores);
       }
     }
   }
@@ -481,7 +478,6 @@ int32_t launch_select(int n_heads, const float* scores, const int64_t* seg_offse
   LAVA_SEL_STEP(2, grid);
   LAVA_SEL_STEP(3, grid);
   LAVA_SEL_STEP(4, grid);
-  LAVA_SEL_STEP(5, dim3(1));
 #undef LAVA_SEL_STEP
   return launch_status();
 }
