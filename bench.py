@@ -105,9 +105,12 @@ def main():
              "copy_GBs_read_plus_write": round(2 * probe_bytes / timed_probe(0) / 1e9, 1), "bytes": probe_bytes}
     del probe_src, probe_dst
 
+    lse_dev = [None]
+
     def step(i):
         q, k, v = sets[i % n_sets]
-        lava.lava_window_scores(desc, lens, q, k, v, scores=scores, vbar=vbar, layer_stat=stat, workspace=ws_scores)
+        lava.lava_window_scores(desc, lens, q, k, v, lse=lse_dev[0], scores=scores, vbar=vbar, layer_stat=stat,
+                                workspace=ws_scores)
         lava.lava_layer_budgets(stat.view(1, 1), total_b, lo, hi, budgets=budgets)
         lava.lava_select_topk(sh.n_kv_heads, scores, B, budget_dev=budgets.view(-1), head_counts=counts,
                               head_offsets=offs, kept_idx=idx, kept_scores=kept_s, workspace=ws_sel)
@@ -134,14 +137,36 @@ def main():
     lava.prof_enable(False)
     per_kernel_us = {name: 1e3 * ms / max(cnt, 1) for name, (ms, cnt) in prof.items() if cnt}
 
+    # ---- variant: the prefill attention hands over the window rows' log-sum-exp, so the statistics
+    # pass is skipped (the LSE itself is prepared here with torch, outside any timed region)
+    G = sh.n_q_heads // sh.n_kv_heads
+    with torch.no_grad():
+        qf = q0.float().view(sh.n_kv_heads, G * sh.window, sh.head_dim)
+        logits = torch.bmm(qf, k0.float().view(sh.n_kv_heads, sh.n, sh.head_dim).transpose(1, 2))
+        logits = logits.view(sh.n_q_heads, sh.window, sh.n) / (sh.head_dim ** 0.5)
+        pos = torch.arange(sh.n, device=dev)[None, None, :]
+        last = (sh.n - sh.window + torch.arange(sh.window, device=dev))[None, :, None]
+        logits = logits.masked_fill(pos > last, float("-inf"))
+        lse_dev[0] = torch.logsumexp(logits, dim=2).contiguous()
+        del logits, qf
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(i)
+    torch.cuda.synchronize()
+    lse_elapsed = time.perf_counter() - t0
+    lse_dev[0] = None
+
     # algorithmic bytes of each sweep kernel per launch (bytes it must move given its inputs/outputs)
     q_bytes = sh.n_q_heads * sh.window * sh.head_dim * esize
-    sraw_bytes = 4 * sh.n_kv_heads * sh.n_prefix
+    score_bytes = 4 * total_entries
     alg_bytes = {
         "vnorm": kv_bytes,
         "stats": kv_bytes + q_bytes,
-        "scores": kv_bytes + q_bytes + sraw_bytes,
-        "poolstat": sraw_bytes + 4 * total_entries,
+        "scores": kv_bytes + q_bytes + score_bytes,
+        "sel_fused": score_bytes,
         "compact": 4 * B * sh.head_dim * esize,
     }
     dominant = max(per_kernel_us, key=per_kernel_us.get)
@@ -151,7 +176,7 @@ def main():
                 "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
                 "kernel_us": round(per_kernel_us[dominant], 2), "algorithmic_bytes": dom_bytes}
     # whole-path view: K once + V once + scores + kept rows, over the whole step
-    path_bytes = 2 * kv_bytes + q_bytes + 5 * 4 * total_entries + 4 * B * sh.head_dim * esize
+    path_bytes = 2 * kv_bytes + q_bytes + 2 * score_bytes + 4 * B * sh.head_dim * esize
     path_gbs = path_bytes / (elapsed / args.steps) / 1e9
 
     out = {
@@ -167,6 +192,10 @@ def main():
                  "frac_of_hbm_peak": round(path_gbs / HBM_PEAK_GBS, 4)},
         "kernels_us": {k: round(v, 2) for k, v in per_kernel_us.items()},
         "stream_probe": probe,
+        "with_lse": {"note": "window-row log-sum-exp supplied by the caller: statistics pass skipped",
+                     "ms_per_step": round(1e3 * lse_elapsed / args.steps, 5),
+                     "value": round(sh.n / (lse_elapsed / args.steps), 1),
+                     "path_frac_of_hbm_peak": round(path_bytes / (lse_elapsed / args.steps) / 1e9 / HBM_PEAK_GBS, 4)},
     }
 
     if not args.no_check or not args.no_cpu_baseline:

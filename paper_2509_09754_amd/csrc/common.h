@@ -53,6 +53,7 @@ struct SweepPlan {
   int tiles_per_block; // key tiles per workgroup
   int vnorm_blocks;    // workgroups per KV head of the value-norm kernel
   int vnorm_tiles_per_block;
+  int blocks_x_bound, vnorm_blocks_bound;   // upper bounds of blocks_x / vnorm_blocks for any shorter sequence
   bool fused_pool;     // the scores kernel also pools, scales and forms the layer statistic
 };
 SweepPlan make_sweep_plan(const lava_layer_desc& d, int64_t n);

@@ -816,6 +816,10 @@ SweepPlan make_sweep_plan(const lava_layer_desc& d, int64_t n) {
   if (p.fused_pool && tpb > kFusedTiles) tpb = kFusedTiles;
   p.tiles_per_block = (int)tpb;
   p.blocks_x = (int)((n_tiles + tpb - 1) / tpb);
+  // bounds that never shrink when n grows: a workspace sized for the longest sequence of a batch
+  // must also hold the (slightly differently split) partials of every shorter one
+  const int64_t capped = (n_tiles + kFusedTiles - 1) / kFusedTiles;
+  p.blocks_x_bound = (int)(max_bx > capped ? max_bx : capped);
   // value norms: one workgroup per CU as well, at least 8 tiles (one per wavefront) each
   int64_t vb = target_wgs / d.n_kv_heads;
   if (vb < 1) vb = 1;
@@ -823,6 +827,7 @@ SweepPlan make_sweep_plan(const lava_layer_desc& d, int64_t n) {
   if (vtpb < 8) vtpb = 8;
   p.vnorm_tiles_per_block = (int)vtpb;
   p.vnorm_blocks = (int)((n_tiles + vtpb - 1) / vtpb);
+  p.vnorm_blocks_bound = (int)vb;
   return p;
 }
 
@@ -836,14 +841,14 @@ ScoreWorkspace make_score_workspace(const lava_layer_desc& d, int64_t n) {
   ScoreWorkspace w;
   size_t off = 0;
   w.off_stat_part = off;
-  off += align_up(sizeof(float2) * (size_t)d.n_kv_heads * p.n_chunks * p.blocks_x * p.chunk_heads * 32);
+  off += align_up(sizeof(float2) * (size_t)d.n_kv_heads * p.n_chunks * p.blocks_x_bound * p.chunk_heads * 32);
   w.off_vnorm_part = off;
-  off += align_up(sizeof(float) * (size_t)d.n_kv_heads * p.vnorm_blocks);
+  off += align_up(sizeof(float) * (size_t)d.n_kv_heads * p.vnorm_blocks_bound);
   w.off_sraw = off;
   off += align_up(sizeof(float) * (size_t)d.n_kv_heads * (size_t)(n - d.window));
   w.off_ent_part = off;
-  const size_t ent_blocks = (size_t)pool_blocks(d, n) > (size_t)p.blocks_x * p.n_chunks
-                                ? (size_t)pool_blocks(d, n) : (size_t)p.blocks_x * p.n_chunks;
+  const size_t ent_blocks = (size_t)pool_blocks(d, n) > (size_t)p.blocks_x_bound * p.n_chunks
+                                ? (size_t)pool_blocks(d, n) : (size_t)p.blocks_x_bound * p.n_chunks;
   off += align_up(sizeof(double2) * (size_t)d.n_kv_heads * ent_blocks);
   w.off_counter = off;
   off += align_up(sizeof(uint32_t) * kArriveWords);

@@ -74,6 +74,17 @@ def test_window_scores_argument_errors():
     assert lava.lava_window_scores_workspace_bytes(_desc(head_dim=100), 1, 4096) == 0
 
 
+def test_workspace_size_never_shrinks_with_length():
+    # a batch shares one workspace sized for its longest sequence; every shorter one must fit
+    for d in (_desc(), _desc(n_q_heads=8, n_kv_heads=2, head_dim=64, window=8, dtype="f32"),
+              _desc(n_q_heads=16, n_kv_heads=2)):
+        prev = 0
+        for n in list(range(40, 20000, 13)) + list(range(20000, 700000, 4999)):
+            b = lava.lava_window_scores_workspace_bytes(d, 1, n)
+            assert b >= prev > -1 and b % 256 == 0
+            prev = b
+
+
 def test_select_and_compact_argument_errors():
     L = lava.lib
     big = 1 << 40

@@ -240,7 +240,8 @@ def test_window_scores_pool_kernels_and_lse(lava):
 
 def test_window_scores_deterministic_and_batched(lava):
     say("scores determinism + ragged batch")
-    shapes = [synth.config(2, n=n, budget=8 * 64) for n in (1500, 4096, 33 + 32, 2777)]
+    # 16416 and 16384 tokens split into a different number of workgroups (513 vs 512 tiles)
+    shapes = [synth.config(2, n=n, budget=8 * 64) for n in (1500, 16416, 33 + 32, 16384, 2777)]
     inps = [synth.gen_layer(s, 40 + i) for i, s in enumerate(shapes)]
     sh0 = shapes[0]
     desc = lava.LayerDesc.make(sh0.n_q_heads, sh0.n_kv_heads, sh0.head_dim, sh0.window, sh0.dtype)
