@@ -21,6 +21,16 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 
+# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs), each scaled by
+# what the same counter reads for the 1 GiB probe kernels below (FETCH_SIZE KiB x 2.000, WRITE_SIZE
+# KiB x 1.000); source tables: profiles/<workload>_hbm_counters.md.  (read_bytes, write_bytes)
+MEASURED_TRAFFIC = {
+    ("cfg4", "vnorm"): (268_501_402, 8_499), ("cfg4", "stats"): (270_678_835, 262_144),
+    ("cfg4", "scores"): (276_137_165, 4_219_494),
+    ("cfg2", "vnorm"): (67_174_810, 8_499), ("cfg2", "stats"): (69_352_038, 262_144),
+    ("cfg2", "scores"): (74_809_549, 1_073_766),
+}
+
 
 def parse():
     ap = argparse.ArgumentParser()
@@ -173,7 +183,9 @@ def main():
     dom_bytes = alg_bytes.get(dominant, 0)
     achieved = dom_bytes / (per_kernel_us[dominant] * 1e-6) / 1e9 if dom_bytes else 0.0
     roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                "traffic": sum(MEASURED_TRAFFIC[(args.workload, dominant)])
+                if (args.workload, dominant) in MEASURED_TRAFFIC else None,
                 "kernel_us": round(per_kernel_us[dominant], 2), "algorithmic_bytes": dom_bytes}
     # whole-path view: K once + V once + scores + kept rows, over the whole step
     path_bytes = 2 * kv_bytes + q_bytes + 2 * score_bytes + 4 * B * sh.head_dim * esize
