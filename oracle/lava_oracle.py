@@ -20,6 +20,8 @@ algorithm step by step in the paper's order.  Steps and the passage each follows
   selection           the B_l largest entries over all heads of the layer  (Alg. 1)
   head budgets        number of survivors that fall in each head           (Sec. 4.1)
   compaction          K^, V^ = the surviving rows                          (Alg. 1)
+  decode attention    one new token attends to the retained entries only:
+                      A = Softmax(q K^T / sqrt(d_h)) over them, y = A V    (Sec. 2; Sec. 3 mask)
 
 Readings taken where the paper is silent or inconsistent (each is listed with its reason in
 the design notes): exactly w window rows (the paper's sum has w+1 terms but divides by w);
@@ -267,6 +269,43 @@ def compact(x: np.ndarray, head_offsets, kept_idx) -> np.ndarray:
     if not rows:
         return np.zeros((0,) + x.shape[2:], dtype=x.dtype)
     return np.stack(rows)
+
+
+# ------------------------------------------------------------------ decode step (Sec. 2, Sec. 3)
+def decode_attention(q, k_hat, v_hat, head_offsets, k_tail=None, v_tail=None, scale=None):
+    """Attention of ONE new token over a compressed layer cache.
+
+    Sec. 2: A_h = Softmax(q_h K_h^T / sqrt(d_h)), output A_h V_h.  Sec. 3: eviction is a mask,
+    i.e. the softmax runs over the retained entries only.  Query head h reads KV head
+    g = h // (H / H_kv), whose retained rows are k_hat / v_hat[head_offsets[g] : head_offsets[g+1]]
+    followed by the rows appended since the eviction, k_tail / v_tail[g] (Cat[K, K^N] of Sec. 2).
+
+    q [H, d]; k_hat, v_hat [R, d]; head_offsets [H_kv + 1]; k_tail, v_tail [H_kv, T, d] or None.
+    Returns (out [H, d], lse [H]); a head with no entries gives zeros and -inf.
+    """
+    H, d = q.shape
+    Hkv = len(head_offsets) - 1
+    G = H // Hkv
+    if scale is None:
+        scale = 1.0 / math.sqrt(d)
+    out = np.zeros((H, d), dtype=np.float64)
+    lse = np.full(H, -np.inf, dtype=np.float64)
+    for h in range(H):
+        g = h // G
+        lo, hi = int(head_offsets[g]), int(head_offsets[g + 1])
+        keys, vals = k_hat[lo:hi], v_hat[lo:hi]
+        if k_tail is not None and k_tail.shape[1] > 0:
+            keys = np.concatenate([keys, k_tail[g]], axis=0)
+            vals = np.concatenate([vals, v_tail[g]], axis=0)
+        if keys.shape[0] == 0:
+            continue
+        logits = (keys @ q[h]) * scale
+        m = logits.max()
+        p = np.exp(logits - m)
+        z = p.sum()
+        out[h] = (p / z) @ vals
+        lse[h] = m + math.log(z)
+    return out, lse
 
 
 def layer_evict(q_win, k, v, window: int, budget: int, pool_kernel: int = 7, scale=None,

@@ -440,3 +440,101 @@ def test_generator_structure_and_determinism():
     assert np.array_equal(torch.from_numpy(x).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16), bits)
     big = synth.gen_layer(synth.config(2, n=2048, budget=8 * 64), 0)
     assert big.k.dtype == np.uint16 and big.k.shape == (8, 2048, 128)
+
+
+# ----------------------------------------------------------------- decode attention (Sec. 2 / Sec. 3)
+def _full_and_kept(seed, Hkv=2, G=3, N=40, d=8, keep=0.4):
+    r = rng(seed)
+    q = r.standard_normal((Hkv * G, d))
+    k = r.standard_normal((Hkv, N, d))
+    v = r.standard_normal((Hkv, N, d)) * np.exp(0.5 * r.standard_normal((Hkv, N, 1)))
+    mask = r.random((Hkv, N)) < keep
+    mask[:, -3:] = True
+    offs = np.concatenate([[0], np.cumsum(mask.sum(1))])
+    k_hat = np.concatenate([k[g][mask[g]] for g in range(Hkv)])
+    v_hat = np.concatenate([v[g][mask[g]] for g in range(Hkv)])
+    return q, k, v, mask, offs, k_hat, v_hat
+
+
+def test_decode_is_masked_renormalised_full_attention():
+    # Sec. 3: eviction = masking; the compressed cache gives A*I / ||A*I||_1 applied to V
+    for seed in range(4):
+        q, k, v, mask, offs, k_hat, v_hat = _full_and_kept(seed)
+        out, lse = O.decode_attention(q, k_hat, v_hat, offs)
+        G = q.shape[0] // k.shape[0]
+        for h in range(q.shape[0]):
+            g = h // G
+            A = scipy.special.softmax(k[g] @ q[h] / math.sqrt(q.shape[1]))
+            Am = A * mask[g]
+            want = (Am / Am.sum()) @ v[g]
+            np.testing.assert_allclose(out[h], want, rtol=1e-12, atol=1e-14)
+            logits = (k[g] @ q[h] / math.sqrt(q.shape[1]))[mask[g]]
+            assert abs(lse[h] - scipy.special.logsumexp(logits)) < 1e-12
+
+
+def test_decode_brute_force_tiny():
+    q, k, v, mask, offs, k_hat, v_hat = _full_and_kept(11, Hkv=2, G=2, N=9, d=3, keep=0.5)
+    out, _ = O.decode_attention(q, k_hat, v_hat, offs, scale=0.7)
+    for h in range(4):
+        g = h // 2
+        rows = range(int(offs[g]), int(offs[g + 1]))
+        ws = [math.exp(0.7 * sum(q[h][c] * k_hat[i][c] for c in range(3))) for i in rows]
+        for c in range(3):
+            want = sum(wt * v_hat[i][c] for wt, i in zip(ws, rows)) / sum(ws)
+            assert abs(out[h][c] - want) < 1e-12
+
+
+def test_decode_closed_forms():
+    r = rng(5)
+    # identical keys -> uniform attention -> the mean of the value rows
+    k_hat = np.tile(r.standard_normal((1, 6)), (10, 1))
+    v_hat = r.standard_normal((10, 6))
+    q = r.standard_normal((2, 6))
+    out, lse = O.decode_attention(q, k_hat, v_hat, [0, 4, 10])
+    np.testing.assert_allclose(out[0], v_hat[:4].mean(0), rtol=1e-12)
+    np.testing.assert_allclose(out[1], v_hat[4:].mean(0), rtol=1e-12)
+    assert abs(lse[0] - (k_hat[0] @ q[0] / math.sqrt(6) + math.log(4))) < 1e-12
+    # one overwhelming key -> its value row; an empty head -> zeros and -inf
+    k2 = np.zeros((5, 6)); k2[3] = 500 * q[0]
+    out, lse = O.decode_attention(q[:1], k2, v_hat[:5], [0, 5])
+    np.testing.assert_allclose(out[0], v_hat[3], atol=1e-9)
+    out, lse = O.decode_attention(q, k_hat, v_hat, [0, 0, 10])
+    assert np.all(out[0] == 0) and lse[0] == -np.inf and np.isfinite(lse[1])
+    # the order of the retained rows inside a head does not matter
+    perm = np.concatenate([r.permutation(4), 4 + r.permutation(6)])
+    kk = r.standard_normal((10, 6))
+    o2, _ = O.decode_attention(q, kk, v_hat, [0, 4, 10])
+    o3, _ = O.decode_attention(q, kk[perm], v_hat[perm], [0, 4, 10])
+    np.testing.assert_allclose(o2, o3, rtol=1e-11, atol=1e-13)
+
+
+def test_decode_tail_equals_appended_rows():
+    # Sec. 2: the cache grows by Cat[K, K^N]; a dense tail must act like rows appended to each head
+    q, k, v, mask, offs, k_hat, v_hat = _full_and_kept(7)
+    r = rng(8)
+    Hkv = k.shape[0]
+    kt, vt = r.standard_normal((Hkv, 5, 8)), r.standard_normal((Hkv, 5, 8))
+    out, lse = O.decode_attention(q, k_hat, v_hat, offs, kt, vt)
+    k_app = np.concatenate([np.concatenate([k_hat[offs[g]:offs[g + 1]], kt[g]]) for g in range(Hkv)])
+    v_app = np.concatenate([np.concatenate([v_hat[offs[g]:offs[g + 1]], vt[g]]) for g in range(Hkv)])
+    offs2 = [int(offs[g]) + 5 * g for g in range(Hkv + 1)]
+    out2, lse2 = O.decode_attention(q, k_app, v_app, offs2)
+    np.testing.assert_allclose(out, out2, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(lse, lse2, rtol=1e-12)
+
+
+def test_decode_loss_obeys_theorem_bound():
+    # Thm. 1 per head: || (A - A') V ||_1 <= 2 * Vbar * (evicted attention mass)
+    for seed in range(6):
+        q, k, v, mask, offs, k_hat, v_hat = _full_and_kept(20 + seed, keep=0.6)
+        Hkv, N, d = k.shape
+        full_offs = [g * N for g in range(Hkv + 1)]
+        o_full, _ = O.decode_attention(q, k.reshape(-1, d), v.reshape(-1, d), full_offs)
+        o_kept, _ = O.decode_attention(q, k_hat, v_hat, offs)
+        G = q.shape[0] // Hkv
+        for h in range(q.shape[0]):
+            g = h // G
+            A = scipy.special.softmax(k[g] @ q[h] / math.sqrt(d))
+            eps = A[~mask[g]].sum()
+            vbar = np.abs(v[g]).sum(1).max()
+            assert np.abs(o_full[h] - o_kept[h]).sum() <= 2 * vbar * eps * (1 + 1e-9) + 1e-14
