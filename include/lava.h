@@ -12,6 +12,7 @@
  *   lava_select_topk     one top-B selection over the flattened heads of the layer; the number
  *                        of survivors per head is the dynamic head budget   (Alg. 1, Sec. 4.1)
  *   lava_compact_kv      packs the surviving K/V rows per head              (Alg. 1, last loop)
+ * and, after the path, lava_decode_attention reads the packed cache (Sec. 2 decoding step).
  *
  * Conventions common to all calls
  *   - "device" pointers are HIP device memory of the current device, "host" pointers are
@@ -164,6 +165,41 @@ int32_t lava_select_status(const void* workspace, int64_t total_entries, void* h
 int32_t lava_compact_kv(const lava_layer_desc* desc, int64_t n, const void* k, const void* v,
                         const int64_t* head_offsets, const int32_t* kept_idx, int64_t capacity,
                         void* k_out, void* v_out, void* hip_stream);
+
+/* Bytes of device workspace lava_decode_attention needs.  Returns 0 for invalid arguments. */
+size_t lava_decode_workspace_bytes(const lava_layer_desc* desc, int32_t batch, int64_t rows_capacity,
+                                   int64_t tail_len);
+
+/*
+ * The step after the path: attention of ONE new token per sequence over the compressed layer
+ * cache (decoding step of Sec. 2, restricted to the retained entries, i.e. under the mask of
+ * Sec. 3):  out[h] = Softmax(scale * q[h] K_g^T) V_g,  g = h / G, where K_g, V_g are the rows
+ * head g retained, followed by the rows appended since the eviction (Cat[K, K^N] of Sec. 2).
+ * It consumes the packed variable-length layout lava_select_topk / lava_compact_kv produce.
+ *
+ *   q             device [batch][H][d_h], dtype of the descriptor
+ *   k_hat, v_hat  device, packed rows [..][d_h], dtype of the descriptor
+ *   head_offsets  device int64 [batch][H_kv + 1]; head g of sequence b owns packed rows
+ *                 base_b + head_offsets[b][g] .. base_b + head_offsets[b][g+1] - 1
+ *   seq_base      device int64 [batch] first packed row of each sequence, or NULL for
+ *                 base_b = b * rows_capacity
+ *   rows_capacity upper bound of head_offsets[b][H_kv] for every b (>= 0)
+ *   k_tail,v_tail device [batch][H_kv][tail_capacity][d_h] rows appended after the eviction, the
+ *                 first tail_len of them valid; NULL when tail_len == 0
+ *   out           device float [batch][H][d_h]
+ *   lse           device float [batch][H] natural-log log-sum-exp of the scaled logits, or NULL
+ *
+ * A head without any row gives zeros (lse = -inf).  If a sequence's offsets exceed rows_capacity
+ * its outputs are NaN.  fp32 accumulation, deterministic (fixed merge order).  Uses n_q_heads,
+ * n_kv_heads (G <= 8), head_dim, dtype and softmax_scale of the descriptor; window and
+ * pool_kernel are ignored.
+ */
+int32_t lava_decode_attention(const lava_layer_desc* desc, int32_t batch, const void* q,
+                              const void* k_hat, const void* v_hat, const int64_t* head_offsets,
+                              const int64_t* seq_base, int64_t rows_capacity, const void* k_tail,
+                              const void* v_tail, int64_t tail_len, int64_t tail_capacity,
+                              float* out, float* lse, void* workspace, size_t workspace_bytes,
+                              void* hip_stream);
 
 /*
  * Per-kernel timing for benchmarks.  When enabled, every kernel the library launches is

@@ -18,7 +18,7 @@ CSRC = os.path.join(HERE, "csrc")
 BUILD_DIR = os.path.join(ROOT, "_build")
 LIB_PATH = os.path.join(HERE, "liblava.so")
 
-SOURCES = ["lava_api.hip", "k_sweep.hip", "k_select.hip", "k_compact.hip", "k_budgets.hip", "k_probe.hip"]
+SOURCES = ["lava_api.hip", "k_sweep.hip", "k_select.hip", "k_compact.hip", "k_budgets.hip", "k_decode.hip", "k_probe.hip"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 COMMON_FLAGS = [

@@ -21,6 +21,8 @@ enum KernelId : int {
   KID_SEL_STEPS,      // selection: the same phases as separate launches (very large inputs)
   KID_COMPACT,        // K/V row gather
   KID_BUDGETS,        // layer budgets on the device
+  KID_DECODE,         // decode attention over the packed cache: per-unit partials
+  KID_DECODE_MERGE,   // decode attention: merge of the units of each head
   KID_COUNT
 };
 
@@ -102,6 +104,20 @@ int32_t select_error_flag(const void* ws, int64_t total, hipStream_t s, int* fla
 int32_t launch_compact(const lava_layer_desc& d, int64_t n, const void* k, const void* v,
                        const int64_t* head_offsets, const int32_t* kept_idx, int64_t capacity,
                        void* k_out, void* v_out, hipStream_t s);
+
+// ---------------------------------------------------------------- decode attention
+struct DecodePlan {
+  int rows_per_unit;     // rows of one head a workgroup handles
+  int group_pad;         // G rounded up to 1, 2, 4 or 8
+  int64_t units_bound;   // units a sequence can have at most (grid.x)
+  size_t off_ml, off_acc, bytes;
+};
+DecodePlan make_decode_plan(const lava_layer_desc& d, int32_t batch, int64_t rows_capacity, int64_t tail_len);
+int32_t launch_decode(const lava_layer_desc& d, int32_t batch, const void* q, const void* k_hat,
+                      const void* v_hat, const int64_t* head_offsets, const int64_t* seq_base,
+                      int64_t rows_capacity, const void* k_tail, const void* v_tail, int64_t tail_len,
+                      int64_t tail_capacity, float* out, float* lse, void* ws, const DecodePlan& p,
+                      hipStream_t s);
 
 // ---------------------------------------------------------------- layer budgets
 // Sequential allocation shared by the host path and the device kernel (one thread per

@@ -22,72 +22,13 @@
 #include <stdlib.h>
 
 #include "common.h"
+#include "tile_ring.h"
 #include "xblock.h"
 
 namespace lava {
 
-typedef __attribute__((__vector_size__(8 * sizeof(__bf16)))) __bf16 bf16x8;
-typedef __attribute__((__vector_size__(16 * sizeof(float)))) float f32x16;
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));   // 16 bytes held in registers
-
-constexpr float kLog2e = 1.4426950408889634f;
-
 // "last workgroup done" tickets in the workspace (zeroed by the first kernel of every call)
 constexpr int kCounterPool = 0;                         // poolstat: one two-level ticket
-
-template <int DT> struct Elem;
-template <> struct Elem<LAVA_BF16> { static constexpr int kBytes = 2; };
-template <> struct Elem<LAVA_F32> { static constexpr int kBytes = 4; };
-
-// acc += A(16 bytes of k) x B(16 bytes of k).  Both operands use the same lane -> k mapping, so
-// any fixed assignment of a row's elements to (step, lane half) gives the full dot product.
-template <int DT>
-__device__ __forceinline__ f32x16 mfma_chunk(const u32x4& a, const u32x4& b, f32x16 acc) {
-  if constexpr (DT == LAVA_BF16) {
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a),
-                                                   __builtin_bit_cast(bf16x8, b), acc, 0, 0, 0);
-  } else {
-    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.x), __uint_as_float(b.x), acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.y), __uint_as_float(b.y), acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.z), __uint_as_float(b.z), acc, 0, 0, 0);
-    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(__uint_as_float(a.w), __uint_as_float(b.w), acc, 0, 0, 0);
-    return acc;
-  }
-}
-
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
-
-#define LAVA_GLOBAL_AS __attribute__((address_space(1)))
-#define LAVA_LDS_AS __attribute__((address_space(3)))
-
-// Wait until at most N vector-memory operations of this wavefront are still outstanding.  Loads
-// complete in issue order, so this guarantees every load older than the N youngest has landed.
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-  static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-  asm volatile("" ::: "memory");
-  __builtin_amdgcn_s_waitcnt((N & 0xF) | (0x7 << 4) | (0xF << 8) | ((N >> 4) << 14));
-  asm volatile("" ::: "memory");
-}
-
-// (m1, z1) (+) (m2, z2) for sums of exp2((x - m) * c2); empty sets are (-inf, 0).
-__device__ __forceinline__ void merge_stat(float& m, float& z, float m2, float z2, float c2) {
-  const float mn = fmaxf(m, m2);
-  const float f1 = (m == mn) ? 1.0f : fast_exp2((m - mn) * c2);
-  const float f2 = (m2 == mn) ? 1.0f : fast_exp2((m2 - mn) * c2);
-  z = z * f1 + z2 * f2;
-  m = mn;
-}
-
-template <int DT, int D>
-struct Tile {
-  static constexpr int kRowBytes = D * Elem<DT>::kBytes;
-  static constexpr int kCpr = kRowBytes / 16;          // 16-byte chunks per row
-  static constexpr int kSteps = kCpr / 2;              // chunk steps (two lane halves per step)
-  static constexpr int kLoads = kTileKeys * kCpr / 64; // 128-bit loads per lane per tile
-  static constexpr int kTileChunks = kTileKeys * kCpr;
-  static constexpr int kTileBytes = kTileKeys * kRowBytes;
-};
 
 // Wavefronts per workgroup and ring depth.  The ring takes 128 KiB of LDS in all.  Kernels whose
 // registers fit twice into a SIMD run 8 wavefronts (2 per SIMD: one wavefront's exponentials
@@ -99,128 +40,8 @@ struct Shape {
   static constexpr int kThreads = kWaves * 64;
   static constexpr int kStagesRaw = (128 * 1024) / (kWaves * Tile<DT, D>::kTileBytes);
   static constexpr int kStages = kStagesRaw > 4 ? 4 : kStagesRaw;
-  static_assert(kStages >= 2, "ring needs at least two stages");
+  static_assert(kStages >= 2 && kStages <= kMaxRingStages, "ring depth");
 };
-
-// Direct-to-LDS reads of 32-key tiles into a ring stage.  Instruction i moves 1 KiB: lane l lands
-// at chunk slot i*64 + l of the stage, i.e. row (i*64+l)/kCpr, slot s = (i*64+l)%kCpr, and fetches
-// the row's chunk s ^ (row & 7): the swizzle is applied on the global side because the LDS side
-// of such a load is linear.  The per-lane byte offsets inside a tile are computed once; a full tile
-// is then (wave-uniform tile address) + (per-lane offset), which needs no vector arithmetic.
-template <int DT, int D>
-struct TileDma {
-  using T = Tile<DT, D>;
-  static constexpr int kRowsPerLoad = 64 / T::kCpr;                                // rows one instruction covers
-  static constexpr int kVariants = kRowsPerLoad >= 8 ? 1 : 8 / kRowsPerLoad;        // distinct (row & 7) patterns
-  unsigned int loff[kVariants];   // per-lane byte offset inside the 1 KiB slice of load i, variant i % kVariants
-
-  __device__ __forceinline__ void init(int lane) {
-#pragma unroll
-    for (int i = 0; i < kVariants; ++i) {
-      const int q = i * 64 + lane;
-      const int row = q / T::kCpr, slot = q % T::kCpr;
-      loff[i] = (unsigned int)((row - i * kRowsPerLoad) * T::kRowBytes + ((slot ^ (row & 7)) << 4));
-    }
-  }
-
-  // Every row of the tile exists.  Load i covers bytes [i KiB, (i+1) KiB) of the tile on both sides;
-  // the common part of the offset is an instruction immediate (< 4 KiB) applied to the global and
-  // the LDS address alike, plus a scalar 4 KiB step, so a load costs no vector arithmetic.
-  __device__ __forceinline__ void issue_full(const char* __restrict__ tile_base, u32x4* stage) const {
-#pragma unroll
-    for (int i = 0; i < T::kLoads; ++i) {
-      const char* src = tile_base + (i / 4) * 4096 + loff[i % kVariants];
-      u32x4* dst = stage + (i / 4) * 256;
-      switch (i % 4) {
-        case 0: __builtin_amdgcn_global_load_lds((const LAVA_GLOBAL_AS void*)src, (LAVA_LDS_AS void*)dst, 16, 0, 0); break;
-        case 1: __builtin_amdgcn_global_load_lds((const LAVA_GLOBAL_AS void*)src, (LAVA_LDS_AS void*)dst, 16, 1024, 0); break;
-        case 2: __builtin_amdgcn_global_load_lds((const LAVA_GLOBAL_AS void*)src, (LAVA_LDS_AS void*)dst, 16, 2048, 0); break;
-        default: __builtin_amdgcn_global_load_lds((const LAVA_GLOBAL_AS void*)src, (LAVA_LDS_AS void*)dst, 16, 3072, 0); break;
-      }
-    }
-  }
-
-  // rows at or beyond n are read from row n - 1 (callers mask or drop them)
-  __device__ __forceinline__ void issue_clamped(const char* __restrict__ head_base, long long tile,
-                                                long long n, int lane, u32x4* stage) const {
-#pragma unroll
-    for (int i = 0; i < T::kLoads; ++i) {
-      const int q = i * 64 + lane;
-      const int row = q / T::kCpr, slot = q % T::kCpr;
-      long long key = tile * kTileKeys + row;
-      key = key < n ? key : n - 1;
-      const char* src = head_base + key * T::kRowBytes + ((slot ^ (row & 7)) << 4);
-      __builtin_amdgcn_global_load_lds((const LAVA_GLOBAL_AS void*)src, (LAVA_LDS_AS void*)(stage + i * 64), 16,
-                                       0, 0);
-    }
-  }
-
-  __device__ __forceinline__ void issue(const char* __restrict__ head_base, long long tile, long long n,
-                                        int lane, u32x4* stage) const {
-    if ((tile + 1) * kTileKeys <= n) {
-      issue_full(head_base + tile * T::kTileBytes, stage);
-    } else {
-      issue_clamped(head_base, tile, n, lane, stage);
-    }
-  }
-};
-
-// Wait for the oldest tile of the ring while `younger` (0 .. kStages-1) tiles stay in flight.
-template <int DT, int D>
-__device__ __forceinline__ void wait_tile(int younger) {
-  using T = Tile<DT, D>;
-  static_assert(Shape<DT, D>::kStages <= 4, "ring depth");
-  switch (younger) {
-    case 0: wait_vmcnt<0>(); break;
-    case 1: wait_vmcnt<T::kLoads>(); break;
-    case 2: wait_vmcnt<2 * T::kLoads>(); break;
-    default: wait_vmcnt<3 * T::kLoads>(); break;
-  }
-}
-
-template <int DT, int D>
-__device__ __forceinline__ void lds_to_frag(const u32x4* __restrict__ buf, int lane,
-                                            u32x4 (&frag)[Tile<DT, D>::kSteps]) {
-  using T = Tile<DT, D>;
-  const int row = lane & 31, half = lane >> 5;
-#pragma unroll
-  for (int j = 0; j < T::kSteps; ++j) {
-    const int c = 2 * j + half;
-    frag[j] = buf[row * T::kCpr + (c ^ (row & 7))];
-  }
-}
-
-// Query fragments of the chunk's heads: row r = lane % 32 (zero beyond the window or the chunk).
-template <int DT, int D, int GT>
-__device__ __forceinline__ void load_q(const u32x4* __restrict__ qg, int h0, int nh, int w, int lane,
-                                       u32x4 (&qf)[GT][Tile<DT, D>::kSteps]) {
-  using T = Tile<DT, D>;
-  const int r = lane & 31, half = lane >> 5;
-#pragma unroll
-  for (int t = 0; t < GT; ++t) {
-#pragma unroll
-    for (int j = 0; j < T::kSteps; ++j) {
-      u32x4 x = u32x4{0u, 0u, 0u, 0u};
-      if (t < nh && r < w) x = qg[((long long)(h0 + t) * w + r) * T::kCpr + 2 * j + half];
-      qf[t][j] = x;
-    }
-  }
-}
-
-// One head's 32 x 32 block of raw dot products: keys x rows (KEYS_AS_ROWS) or rows x keys.
-template <int DT, int D, bool KEYS_AS_ROWS>
-__device__ __forceinline__ f32x16 dot_tile(const u32x4 (&kf)[Tile<DT, D>::kSteps],
-                                           const u32x4 (&qh)[Tile<DT, D>::kSteps]) {
-  f32x16 acc = {0};
-#pragma unroll
-  for (int j = 0; j < Tile<DT, D>::kSteps; ++j)
-    acc = KEYS_AS_ROWS ? mfma_chunk<DT>(kf[j], qh[j], acc) : mfma_chunk<DT>(qh[j], kf[j], acc);
-  return acc;
-}
-
-// Index of the wavefront inside its workgroup as a scalar, so that everything derived from it
-// (tile numbers, ring stages, loop bounds) stays in scalar registers and scalar branches.
-__device__ __forceinline__ int wave_index() { return __builtin_amdgcn_readfirstlane((int)(threadIdx.x >> 6)); }
 
 // Layer statistic from per-lane partial sums S = sum s, T = sum s ln s (fp64): fixed-order reduction
 // over lanes (xor tree), wavefronts and, by the last workgroup to arrive, workgroups; then

@@ -19,7 +19,8 @@ struct ProfState {
 } g_prof;
 
 const char* const kKernelNames[KID_COUNT] = {
-    "vnorm", "stats", "scores", "poolstat", "sel_init", "sel_fused", "sel_steps", "compact", "budgets"};
+    "vnorm", "stats", "scores", "poolstat", "sel_init", "sel_fused", "sel_steps", "compact", "budgets",
+    "decode", "decode_merge"};
 
 void prof_collect() {
   (void)hipDeviceSynchronize();
@@ -219,6 +220,49 @@ int32_t lava_compact_kv(const lava_layer_desc* desc, int64_t n, const void* k, c
   if (capacity > (int64_t)desc->n_kv_heads * n) return LAVA_ERR_BUDGET;
   return launch_compact(*desc, n, k, v, head_offsets, kept_idx, capacity, k_out, v_out,
                         static_cast<hipStream_t>(hip_stream));
+}
+
+// Descriptor checks for the decode step: window and pool_kernel play no role there.
+static int32_t check_desc_decode(const lava_layer_desc* desc, lava_layer_desc* out) {
+  if (desc == nullptr) return LAVA_ERR_INVALID_ARG;
+  *out = *desc;
+  out->window = 1;
+  out->pool_kernel = 1;
+  return check_desc(out);
+}
+
+size_t lava_decode_workspace_bytes(const lava_layer_desc* desc, int32_t batch, int64_t rows_capacity,
+                                   int64_t tail_len) {
+  lava_layer_desc d;
+  if (check_desc_decode(desc, &d) != LAVA_OK || batch < 1 || rows_capacity < 0 || tail_len < 0) return 0;
+  if (rows_capacity >= (int64_t)1 << 31 || tail_len >= (int64_t)1 << 31) return 0;
+  return make_decode_plan(d, batch, rows_capacity, tail_len).bytes;
+}
+
+int32_t lava_decode_attention(const lava_layer_desc* desc, int32_t batch, const void* q,
+                              const void* k_hat, const void* v_hat, const int64_t* head_offsets,
+                              const int64_t* seq_base, int64_t rows_capacity, const void* k_tail,
+                              const void* v_tail, int64_t tail_len, int64_t tail_capacity,
+                              float* out, float* lse, void* workspace, size_t workspace_bytes,
+                              void* hip_stream) {
+  lava_layer_desc d;
+  int32_t st = check_desc_decode(desc, &d);
+  if (st != LAVA_OK) return st;
+  if (batch < 1 || q == nullptr || head_offsets == nullptr || out == nullptr || rows_capacity < 0 ||
+      tail_len < 0 || tail_capacity < tail_len)
+    return LAVA_ERR_INVALID_ARG;
+  if (batch > 65535) return LAVA_ERR_SHAPE;
+  if (rows_capacity >= (int64_t)1 << 31 || tail_len >= (int64_t)1 << 31) return LAVA_ERR_SHAPE;
+  if (rows_capacity > 0 && (k_hat == nullptr || v_hat == nullptr)) return LAVA_ERR_INVALID_ARG;
+  if (tail_len > 0 && (k_tail == nullptr || v_tail == nullptr)) return LAVA_ERR_INVALID_ARG;
+  if (!aligned16(q) || !aligned16(k_hat) || !aligned16(v_hat) || !aligned16(k_tail) || !aligned16(v_tail))
+    return LAVA_ERR_INVALID_ARG;
+  const DecodePlan p = make_decode_plan(d, batch, rows_capacity, tail_len);
+  if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 ||
+      workspace_bytes < p.bytes)
+    return LAVA_ERR_WORKSPACE;
+  return launch_decode(d, batch, q, k_hat, v_hat, head_offsets, seq_base, rows_capacity, k_tail, v_tail,
+                       tail_len, tail_capacity, out, lse, workspace, p, static_cast<hipStream_t>(hip_stream));
 }
 
 int32_t lava_prof_kernel_count(void) { return KID_COUNT; }

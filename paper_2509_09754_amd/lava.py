@@ -22,7 +22,7 @@ LAVA_F32, LAVA_BF16 = 0, 1
 EXPORTS = [
     "lava_status_string", "lava_window_scores_workspace_bytes", "lava_window_scores",
     "lava_layer_budgets", "lava_select_workspace_bytes", "lava_select_topk", "lava_select_status",
-    "lava_compact_kv",
+    "lava_compact_kv", "lava_decode_workspace_bytes", "lava_decode_attention",
     "lava_prof_kernel_count", "lava_prof_kernel_name", "lava_prof_enable", "lava_prof_reset",
     "lava_prof_read", "lava_probe_stream",
 ]
@@ -76,6 +76,10 @@ def _load() -> ctypes.CDLL:
     lib.lava_select_status.argtypes = [vp, i64, vp]
     lib.lava_compact_kv.restype = i32
     lib.lava_compact_kv.argtypes = [dp, i64, vp, vp, vp, vp, i64, vp, vp, vp]
+    lib.lava_decode_workspace_bytes.restype = sz
+    lib.lava_decode_workspace_bytes.argtypes = [dp, i32, i64, i64]
+    lib.lava_decode_attention.restype = i32
+    lib.lava_decode_attention.argtypes = [dp, i32, vp, vp, vp, vp, vp, i64, vp, vp, i64, i64, vp, vp, vp, sz, vp]
     lib.lava_prof_kernel_count.restype = i32
     lib.lava_prof_kernel_name.restype = ctypes.c_char_p
     lib.lava_prof_kernel_name.argtypes = [i32]
@@ -249,6 +253,35 @@ def lava_compact_kv(desc: LayerDesc, n: int, k: torch.Tensor, v: torch.Tensor, h
                              int(capacity), _ptr(k_out), _ptr(v_out), _stream(stream))
     _check(st, "lava_compact_kv")
     return k_out, v_out
+
+
+def lava_decode_workspace_bytes(desc: LayerDesc, batch: int, rows_capacity: int, tail_len: int = 0) -> int:
+    return int(lib.lava_decode_workspace_bytes(ctypes.byref(desc), int(batch), int(rows_capacity), int(tail_len)))
+
+
+def lava_decode_attention(desc: LayerDesc, batch: int, q: torch.Tensor, k_hat, v_hat, head_offsets: torch.Tensor,
+                          rows_capacity: int, seq_base=None, k_tail=None, v_tail=None, tail_len: int = 0,
+                          tail_capacity: int = 0, out=None, lse=None, workspace=None, stream=None):
+    """One new token per sequence attends to the packed cache (+ dense tail).  Returns (out, lse)."""
+    _dev(q, "q", desc.torch_dtype), _dev(head_offsets, "head_offsets", torch.int64)
+    for name, t in (("k_hat", k_hat), ("v_hat", v_hat), ("k_tail", k_tail), ("v_tail", v_tail)):
+        if t is not None:
+            _dev(t, name, desc.torch_dtype)
+    if seq_base is not None:
+        _dev(seq_base, "seq_base", torch.int64)
+    if out is None:
+        out = torch.empty(batch, desc.n_q_heads, desc.head_dim, dtype=torch.float32, device=q.device)
+    if lse is None:
+        lse = torch.empty(batch, desc.n_q_heads, dtype=torch.float32, device=q.device)
+    if workspace is None:
+        need = lava_decode_workspace_bytes(desc, batch, rows_capacity, tail_len)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=q.device)
+    st = lib.lava_decode_attention(ctypes.byref(desc), int(batch), _ptr(q), _ptr(k_hat), _ptr(v_hat),
+                                   _ptr(head_offsets), _ptr(seq_base), int(rows_capacity), _ptr(k_tail),
+                                   _ptr(v_tail), int(tail_len), int(tail_capacity), _ptr(out), _ptr(lse),
+                                   _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(st, "lava_decode_attention")
+    return out, lse
 
 
 # ------------------------------------------------------------------------------ timing hook

@@ -194,3 +194,75 @@ def random_scores(n_heads: int, n: int, seed: int, plateau: int = 7, zero_frac: 
     base[rng.random(base.shape) < zero_frac] = 0.0
     s = np.repeat(base, plateau, axis=1)[:, :n]
     return np.ascontiguousarray(s, dtype=np.float32)
+
+
+# --------------------------------------------------------------------------- decode-step inputs
+@dataclasses.dataclass
+class DecodeInputs:
+    dtype: str
+    q: np.ndarray             # [batch, H, d]                 storage dtype
+    k_hat: np.ndarray         # [batch * rows_capacity, d]    packed rows, sequence b at b * rows_capacity
+    v_hat: np.ndarray
+    head_offsets: np.ndarray  # [batch, H_kv + 1] int64
+    rows_capacity: int
+    k_tail: np.ndarray        # [batch, H_kv, tail_capacity, d]
+    v_tail: np.ndarray
+    tail_len: int
+
+
+def head_split(rows: int, n_heads: int, rng, kind: str = "skewed") -> np.ndarray:
+    """Offsets [n_heads + 1] that split `rows` packed rows among heads: 'uniform', or 'skewed'
+    (the uneven head budgets a layer-wide selection produces: a few heads take most rows, some
+    may get none)."""
+    if kind == "uniform":
+        cnt = np.full(n_heads, rows // n_heads, dtype=np.int64)
+        cnt[: rows - cnt.sum()] += 1
+    else:
+        wgt = np.exp(1.5 * rng.standard_normal(n_heads))
+        wgt[rng.random(n_heads) < 0.15] = 0.0
+        if wgt.sum() == 0.0:
+            wgt[0] = 1.0
+        cnt = np.floor(wgt / wgt.sum() * rows).astype(np.int64)
+        cnt[int(np.argmax(wgt))] += rows - cnt.sum()
+    return np.concatenate([[0], np.cumsum(cnt)]).astype(np.int64)
+
+
+def gen_decode(n_q_heads: int, n_kv_heads: int, head_dim: int, dtype: str, rows, seed: int,
+               rows_capacity: int | None = None, tail_len: int = 0, tail_capacity: int | None = None,
+               split: str = "skewed", heavy_frac: float = 0.01) -> DecodeInputs:
+    """A compressed layer cache as the eviction leaves it, plus one new query token per sequence.
+
+    rows[b] packed rows for sequence b, split among the KV heads by `head_split`; q, K ~ N(0,1),
+    V ~ N(0,1) * log-normal row scale (sigma 0.5) as in gen_layer; a fraction `heavy_frac` of the
+    rows are turned towards the query of a random head of their group (cosine 0.8), which is what
+    retained entries look like: they were kept because recent queries attend to them."""
+    rng = np.random.Generator(np.random.PCG64(seed + 7919))
+    rows = np.asarray(rows, dtype=np.int64)
+    batch = rows.shape[0]
+    cap = int(rows.max()) if rows_capacity is None else int(rows_capacity)
+    tcap = tail_len if tail_capacity is None else int(tail_capacity)
+    G, d = n_q_heads // n_kv_heads, head_dim
+    q = rng.standard_normal((batch, n_q_heads, d), dtype=np.float32)
+    k = rng.standard_normal((batch * cap, d), dtype=np.float32)
+    v = rng.standard_normal((batch * cap, d), dtype=np.float32)
+    v *= np.exp(np.float32(0.5) * rng.standard_normal((batch * cap, 1), dtype=np.float32))
+    kt = rng.standard_normal((batch, n_kv_heads, max(tcap, 1), d), dtype=np.float32)
+    vt = rng.standard_normal((batch, n_kv_heads, max(tcap, 1), d), dtype=np.float32)
+    offs = np.zeros((batch, n_kv_heads + 1), dtype=np.int64)
+    for b in range(batch):
+        offs[b] = head_split(int(rows[b]), n_kv_heads, rng, split)
+        n_heavy = int(round(heavy_frac * rows[b]))
+        if n_heavy == 0:
+            continue
+        r = rng.integers(0, int(rows[b]), size=n_heavy)
+        r = np.unique(r)
+        g = np.searchsorted(offs[b], r, side="right") - 1
+        h = g * G + rng.integers(0, G, size=r.shape[0])
+        qhat = _unit(q[b, h])
+        u = rng.standard_normal((r.shape[0], d), dtype=np.float32)
+        u = u - np.sum(u * qhat, axis=-1, keepdims=True) * qhat
+        rr = b * cap + r
+        nrm = np.sqrt(np.sum(k[rr].astype(np.float64) ** 2, axis=-1, keepdims=True)).astype(np.float32)
+        k[rr] = nrm * (np.float32(0.8) * qhat + np.float32(0.6) * _unit(u))
+    return DecodeInputs(dtype, store(q, dtype), store(k, dtype), store(v, dtype), offs, cap,
+                        store(kt, dtype), store(vt, dtype), int(tail_len))

@@ -138,3 +138,37 @@ def test_host_budgets_errors():
     assert ei.value.status == lava.LAVA_ERR_BUDGET
     with pytest.raises(lava.LavaError):
         lava.lava_layer_budgets(np.ones(2, np.float32), [50], [3, 3], [9, 9])
+
+
+def test_decode_argument_errors():
+    L = lava.lib
+    d = _desc()
+    big = 1 << 40
+
+    def call(desc=d, batch=1, q=FAKE, kh=FAKE, vh=FAKE, offs=FAKE, cap=1024, kt=None, vt=None, tail=0, tcap=0,
+             out=FAKE, ws=FAKE, wsb=big):
+        return L.lava_decode_attention(ctypes.byref(desc), batch, q, kh, vh, offs, None, cap, kt, vt, tail, tcap,
+                                       out, None, ws, wsb, None)
+
+    assert call(q=None) == lava.LAVA_ERR_INVALID_ARG
+    assert call(offs=None) == lava.LAVA_ERR_INVALID_ARG
+    assert call(out=None) == lava.LAVA_ERR_INVALID_ARG
+    assert call(kh=None) == lava.LAVA_ERR_INVALID_ARG                    # rows but no packed cache
+    assert call(cap=-1) == lava.LAVA_ERR_INVALID_ARG
+    assert call(tail=4, tcap=4) == lava.LAVA_ERR_INVALID_ARG             # tail rows but no tail buffers
+    assert call(kt=FAKE, vt=FAKE, tail=5, tcap=4) == lava.LAVA_ERR_INVALID_ARG
+    assert call(kh=ctypes.c_void_p(0x10004)) == lava.LAVA_ERR_INVALID_ARG
+    assert call(batch=0) == lava.LAVA_ERR_INVALID_ARG
+    assert call(desc=_desc(head_dim=96)) == lava.LAVA_ERR_SHAPE
+    assert call(desc=_desc(n_q_heads=72, n_kv_heads=8)) == lava.LAVA_ERR_SHAPE   # G = 9
+    assert call(ws=None) == lava.LAVA_ERR_WORKSPACE
+    assert call(wsb=64) == lava.LAVA_ERR_WORKSPACE
+    # window and pool_kernel of the descriptor are ignored by the decode step
+    odd = _desc(window=32)
+    odd.window, odd.pool_kernel = 999, 4
+    assert lava.lava_decode_workspace_bytes(odd, 2, 8192, 16) > 0
+    assert lava.lava_decode_workspace_bytes(d, 0, 8192, 0) == 0
+    prev = 0
+    for cap in range(0, 200000, 777):        # enough for every smaller capacity of the same batch
+        b = lava.lava_decode_workspace_bytes(d, 4, cap, 0)
+        assert b % 256 == 0 and b > 0
