@@ -42,7 +42,84 @@ def parse():
     ap.add_argument("--sets", type=int, default=0, help="distinct K/V buffer sets (0 = enough for >= 1.5 GiB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
+    ap.add_argument("--no-decode", action="store_true", help="skip the decode-attention leg")
     return ap.parse_args()
+
+
+def decode_leg(lava, synth, torch, np, sh, desc, dev, sets, k_hat, v_hat, offs, B, args):
+    """The step after the path: one new token attends to the compressed cache.  Three timings:
+    the layer just evicted (batch 1), the same token over the unevicted cache (what the eviction
+    saves), and a batch of 64 compressed caches rotating over >= 1 GiB (the bandwidth case)."""
+    esize = synth.itemsize(sh.dtype)
+    row_bytes = sh.head_dim * esize
+    iters = max(20, args.steps // 2)
+
+    def timed(fn, n):
+        for i in range(3):
+            fn(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n):
+            fn(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n
+
+    rng = np.random.Generator(np.random.PCG64(args.seed + 99))
+    q1 = lava.to_device(synth.store(rng.standard_normal((1, sh.n_q_heads, sh.head_dim), dtype=np.float32), sh.dtype),
+                        sh.dtype, dev)
+    offs1 = offs.view(1, -1).contiguous()
+    out1 = torch.empty(1, sh.n_q_heads, sh.head_dim, dtype=torch.float32, device=dev)
+    lse1 = torch.empty(1, sh.n_q_heads, dtype=torch.float32, device=dev)
+    ws1 = torch.empty(lava.lava_decode_workspace_bytes(desc, 1, B), dtype=torch.uint8, device=dev)
+    t_small = timed(lambda i: lava.lava_decode_attention(desc, 1, q1, k_hat, v_hat, offs1, B, out=out1, lse=lse1,
+                                                         workspace=ws1), 4 * iters)
+
+    # the same token over the whole, unevicted layer cache
+    full_rows = sh.n_kv_heads * sh.n
+    offs_full = torch.arange(sh.n_kv_heads + 1, dtype=torch.int64, device=dev).mul_(sh.n).view(1, -1).contiguous()
+    ws_full = torch.empty(lava.lava_decode_workspace_bytes(desc, 1, full_rows), dtype=torch.uint8, device=dev)
+
+    def full(i):
+        _, k, v = sets[i % len(sets)]
+        lava.lava_decode_attention(desc, 1, q1, k.view(-1, sh.head_dim), v.view(-1, sh.head_dim), offs_full, full_rows,
+                                   out=out1, lse=lse1, workspace=ws_full)
+    t_full = timed(full, iters)
+
+    # batch of compressed caches: `batch` sequences x B rows with skewed head budgets
+    batch = 64
+    n_pools = max(2, int(np.ceil(2**30 / (2 * batch * B * row_bytes))))
+    di = synth.gen_decode(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.dtype, [B] * batch, args.seed)
+    qb = lava.to_device(di.q, sh.dtype, dev)
+    offs_b = torch.from_numpy(di.head_offsets).to(dev)
+    kb0, vb0 = lava.to_device(di.k_hat, sh.dtype, dev), lava.to_device(di.v_hat, sh.dtype, dev)
+    pools = [(kb0, vb0)] + [(kb0.clone(), vb0.clone()) for _ in range(n_pools - 1)]
+    out_b = torch.empty(batch, sh.n_q_heads, sh.head_dim, dtype=torch.float32, device=dev)
+    lse_b = torch.empty(batch, sh.n_q_heads, dtype=torch.float32, device=dev)
+    ws_b = torch.empty(lava.lava_decode_workspace_bytes(desc, batch, B), dtype=torch.uint8, device=dev)
+
+    def batched(i):
+        kb, vb = pools[i % n_pools]
+        lava.lava_decode_attention(desc, batch, qb, kb, vb, offs_b, B, out=out_b, lse=lse_b, workspace=ws_b)
+    t_batch = timed(batched, iters)
+    lava.prof_enable(True)
+    lava.prof_reset()
+    for i in range(iters):
+        batched(i)
+    torch.cuda.synchronize()
+    prof = lava.prof_read()
+    lava.prof_enable(False)
+    k_us = {n: 1e3 * prof[n][0] / max(prof[n][1], 1) for n in ("decode", "decode_merge")}
+    bytes_b = 2 * batch * B * row_bytes
+    return {
+        "note": "one new token per sequence over the packed variable-length cache (Sec. 2 step on the retained entries)",
+        "evicted_layer_us": round(1e6 * t_small, 2), "evicted_rows": B,
+        "full_cache_us": round(1e6 * t_full, 2), "full_rows": full_rows,
+        "attention_speedup_from_eviction": round(t_full / t_small, 1),
+        "batched": {"batch": batch, "rows_per_seq": B, "us": round(1e6 * t_batch, 2), "pools": n_pools,
+                    "algorithmic_bytes": bytes_b, "kernel_us": {n: round(v, 2) for n, v in k_us.items()},
+                    "achieved_GBs": round(bytes_b / (k_us["decode"] * 1e-6) / 1e9, 1),
+                    "frac_of_hbm_peak": round(bytes_b / (k_us["decode"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)},
+    }
 
 
 def main():
@@ -209,6 +286,9 @@ def main():
                      "value": round(sh.n / (lse_elapsed / args.steps), 1),
                      "path_frac_of_hbm_peak": round(path_bytes / (lse_elapsed / args.steps) / 1e9 / HBM_PEAK_GBS, 4)},
     }
+
+    if not args.no_decode:
+        out["decode"] = decode_leg(lava, synth, torch, np, sh, desc, dev, sets, k_hat, v_hat, offs, B, args)
 
     if not args.no_check or not args.no_cpu_baseline:
         from oracle import lava_oracle as O

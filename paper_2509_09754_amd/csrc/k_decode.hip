@@ -4,7 +4,11 @@
 //
 //   decode_kernel   one workgroup per "unit" = up to C consecutive rows of one head (packed rows
 //                   first, then the rows appended since the eviction).  Each wavefront streams
-//                   32-row K and V tiles alternately through its private tile ring:
+//                   32-row tiles: K through its private LDS ring (two tiles ahead), V straight
+//                   into registers (one tile ahead; a lane owns the same columns of every row, so
+//                   a row is one coalesced load and needs no LDS).  The step is latency-bound
+//                   unless enough bytes are in flight per compute unit, and registers are the
+//                   larger buffer:
 //                     logits   K_tile x Q^T on the matrix cores (the G heads are G columns of the
 //                              32-wide operand; the product is exact, accumulation fp32)
 //                     softmax  online, in the exp2 domain, per head, kept in the column's lanes
@@ -17,6 +21,7 @@
 //
 // The step is bound by HBM: 2 * d_h * elem bytes per retained row against 4 * G * d_h flop.
 #include <math.h>
+#include <stdlib.h>
 
 #include "common.h"
 #include "tile_ring.h"
@@ -28,45 +33,39 @@ namespace {
 constexpr int kDecWaves = 4;
 constexpr int kDecThreads = kDecWaves * 64;
 
+// Two ring stages per wavefront (the K and the V tile of the moment): a workgroup then takes
+// well under half of a compute unit's LDS, so two workgroups share a unit and the set-up of one
+// overlaps the streaming of the other.
 template <int DT, int D>
 struct DecShape {
   using T = Tile<DT, D>;
-  static constexpr int kStagesRaw = (128 * 1024) / (kDecWaves * T::kTileBytes);
-  static constexpr int kStages = kStagesRaw > kMaxRingStages ? kMaxRingStages : kStagesRaw;
-  static_assert(kStages >= 2, "ring needs a K and a V stage");
+  static constexpr int kStages = 2;
   static constexpr int kBpl = T::kRowBytes / 64;              // bytes of a row one lane owns
   static constexpr int kDpl = kBpl / Elem<DT>::kBytes;        // elements of a row one lane owns
   static_assert(kDpl == 1 || kDpl == 2, "one or two output columns per lane");
+  static_assert(kDecWaves * kStages * T::kTileBytes >= kDecWaves * 8 * D * 4, "the ring doubles as the merge buffer");
 };
 
-__device__ __forceinline__ void wait_lds() { __builtin_amdgcn_s_waitcnt(0xc07f); }   // lgkmcnt(0)
+template <int BYTES> struct RawBits;
+template <> struct RawBits<2> { using type = unsigned short; };
+template <> struct RawBits<4> { using type = unsigned int; };
+template <> struct RawBits<8> { using type = uint2; };
 
-// What the lanes of one wavefront wrote to LDS is visible to its other lanes after this.
-__device__ __forceinline__ void wave_lds_sync() {
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-  __builtin_amdgcn_wave_barrier();
-  __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-}
-
-// The kDpl elements of row `row` this lane owns, as floats.  voff[j] is the lane's byte offset
-// inside a row whose (row & 7) == j (the tile is XOR-swizzled in 16-byte chunks).
+// The kDpl elements of a row this lane owns, from their raw bits to floats.
 template <int DT, int D>
-__device__ __forceinline__ void read_v(const char* __restrict__ stage, int row, const unsigned int (&voff)[8],
-                                       float (&x)[DecShape<DT, D>::kDpl]) {
+__device__ __forceinline__ void unpack_v(const typename RawBits<DecShape<DT, D>::kBpl>::type& raw,
+                                         float (&x)[DecShape<DT, D>::kDpl]) {
   using S = DecShape<DT, D>;
-  const char* p = stage + row * S::T::kRowBytes + voff[row & 7];
   if constexpr (DT == LAVA_BF16 && S::kDpl == 1) {
-    x[0] = __uint_as_float((unsigned int)(*reinterpret_cast<const unsigned short*>(p)) << 16);
+    x[0] = __uint_as_float((unsigned int)raw << 16);
   } else if constexpr (DT == LAVA_BF16) {
-    const unsigned int b = *reinterpret_cast<const unsigned int*>(p);
-    x[0] = __uint_as_float(b << 16);
-    x[1] = __uint_as_float(b & 0xffff0000u);
+    x[0] = __uint_as_float(raw << 16);
+    x[1] = __uint_as_float(raw & 0xffff0000u);
   } else if constexpr (S::kDpl == 1) {
-    x[0] = *reinterpret_cast<const float*>(p);
+    x[0] = __uint_as_float(raw);
   } else {
-    const float2 f = *reinterpret_cast<const float2*>(p);
-    x[0] = f.x;
-    x[1] = f.y;
+    x[0] = __uint_as_float(raw.x);
+    x[1] = __uint_as_float(raw.y);
   }
 }
 
@@ -90,17 +89,47 @@ struct DecodeArgs {
 
 __device__ __forceinline__ long long ceil_div(long long a, long long b) { return (a + b - 1) / b; }
 
-// Units of head g: packed chunks, then tail chunks.
-__device__ __forceinline__ long long head_len(const long long* __restrict__ off, int g) {
-  const long long len = off[g + 1] - off[g];
-  return len > 0 ? len : 0;
+__device__ __forceinline__ long long uniform64(long long x) {
+  const unsigned int lo = __builtin_amdgcn_readfirstlane((unsigned int)((unsigned long long)x & 0xffffffffull));
+  const unsigned int hi = __builtin_amdgcn_readfirstlane((unsigned int)((unsigned long long)x >> 32));
+  return (long long)(((unsigned long long)hi << 32) | lo);
 }
 
-// Offsets a kernel may follow: start at >= 0, never decrease, end within the stated capacity.
-__device__ __forceinline__ bool offsets_usable(const long long* __restrict__ off, int n_heads, long long capacity) {
-  bool ok = off[0] >= 0 && off[n_heads] <= capacity;
-  for (int g = 0; g < n_heads; ++g) ok = ok && off[g + 1] >= off[g];
-  return ok;
+// The units of one sequence, found by every wavefront on its own with one coalesced load of the
+// head offsets: lane g holds head g.  Units are numbered head by head, each head's packed chunks
+// first, then its tail chunks.  Offsets a kernel may follow start at >= 0, never decrease and end
+// within the stated capacity; anything else makes `usable` false and nothing is read.
+struct UnitMap {
+  bool usable;
+  unsigned int total;        // units of the sequence
+  unsigned int incl;         // lane g: units of heads 0..g
+  unsigned int cnt;          // lane g: units of head g
+  unsigned int packed;       // lane g: packed units of head g
+  long long off, len;        // lane g: first packed row and number of packed rows of head g
+};
+
+__device__ __forceinline__ UnitMap map_units(const long long* __restrict__ offs, int n_heads, long long capacity,
+                                             int rows_per_unit, long long tail_len, int lane) {
+  UnitMap m;
+  const long long o = lane <= n_heads ? offs[lane] : 0;
+  const long long o_next = __shfl_down(o, 1);
+  const bool head = lane < n_heads;
+  const bool bad = (head && o_next < o) || (lane == 0 && o < 0) || (lane == n_heads && o > capacity);
+  m.usable = __ballot(bad) == 0ull;
+  m.off = o;
+  m.len = head && m.usable ? o_next - o : 0;
+  const unsigned int tail_units = tail_len > 0 ? (unsigned int)ceil_div(tail_len, rows_per_unit) : 0u;
+  m.packed = (unsigned int)ceil_div(m.len, rows_per_unit);
+  m.cnt = head && m.usable ? m.packed + tail_units : 0u;
+  unsigned int incl = m.cnt;
+#pragma unroll
+  for (int d = 1; d < 64; d <<= 1) {
+    const unsigned int up = __shfl_up(incl, d);
+    if (lane >= d) incl += up;
+  }
+  m.incl = incl;
+  m.total = __shfl(incl, 63);
+  return m;
 }
 
 template <int DT, int D, int GP>
@@ -109,35 +138,29 @@ __global__ void __launch_bounds__(kDecThreads) decode_kernel(DecodeArgs a) {
   using T = Tile<DT, D>;
   constexpr int kStages = S::kStages;
   constexpr int kDpl = S::kDpl;
-  __shared__ u32x4 s_tile[kDecWaves][kStages][T::kTileChunks];
-  __shared__ float s_p[kDecWaves][kTileKeys + 1][GP];      // probabilities of the tile; row 32: rescale factors
-  __shared__ float s_acc[kDecWaves][GP][D];
+  __shared__ u32x4 s_tile[kDecWaves][kStages][T::kTileChunks];   // after the sweep: float [kDecWaves][GP][D]
+  constexpr int kPs = GP < 4 ? 4 : GP;                      // floats per key in s_p (one or two 128-bit reads)
+  __shared__ __attribute__((aligned(16))) float s_p[kDecWaves][kTileKeys + 1][kPs];   // probabilities; row 32: rescale factors
   __shared__ float s_m[kDecWaves][GP], s_l[kDecWaves][GP];
 
   const int lane = threadIdx.x & 63, wave = wave_index();
   const int b = blockIdx.y;
-  const long long* off = a.head_offsets + (long long)b * (a.H_kv + 1);
-  const long long tail_units = a.tail_len > 0 ? ceil_div(a.tail_len, a.rows_per_unit) : 0;
-  if (!offsets_usable(off, a.H_kv, a.rows_capacity)) return;   // the merge reports it
-
-  // which head and chunk this unit is (wave-uniform scalar loop over at most 64 heads)
-  long long u = blockIdx.x;
-  int g = 0;
-  long long packed_units = 0;
-  for (; g < a.H_kv; ++g) {
-    packed_units = ceil_div(head_len(off, g), a.rows_per_unit);
-    if (u < packed_units + tail_units) break;
-    u -= packed_units + tail_units;
-  }
-  if (g >= a.H_kv) return;                                  // beyond the sequence's last unit
+  const UnitMap um = map_units(a.head_offsets + (long long)b * (a.H_kv + 1), a.H_kv, a.rows_capacity,
+                               a.rows_per_unit, a.tail_len, lane);
+  if (!um.usable || blockIdx.x >= um.total) return;         // bad offsets (the merge reports them) or no such unit
+  const int g = __builtin_ctzll(__ballot(um.incl > blockIdx.x));
+  const long long u = (long long)blockIdx.x - (__builtin_amdgcn_readfirstlane(__shfl(um.incl, g)) -
+                                                __builtin_amdgcn_readfirstlane(__shfl(um.cnt, g)));
+  const long long packed_units = __builtin_amdgcn_readfirstlane(__shfl(um.packed, g));
+  const long long off_g = uniform64(__shfl(um.off, g)), len_g = uniform64(__shfl(um.len, g));
 
   const char* kb;
   const char* vb;
   long long n_rows;
   if (u < packed_units) {
-    const long long base = (a.seq_base ? a.seq_base[b] : (long long)b * a.rows_capacity) + off[g] +
+    const long long base = (a.seq_base ? a.seq_base[b] : (long long)b * a.rows_capacity) + off_g +
                            u * a.rows_per_unit;
-    n_rows = head_len(off, g) - u * a.rows_per_unit;
+    n_rows = len_g - u * a.rows_per_unit;
     kb = a.k_hat + base * T::kRowBytes;
     vb = a.v_hat + base * T::kRowBytes;
   } else {
@@ -149,6 +172,39 @@ __global__ void __launch_bounds__(kDecThreads) decode_kernel(DecodeArgs a) {
   }
   if (n_rows > a.rows_per_unit) n_rows = a.rows_per_unit;
 
+  // This wavefront's tiles: wave, wave + kDecWaves, ...  Vector-memory operations complete in issue
+  // order and the K ring is awaited by count, so the order below is part of the protocol:
+  //   K_0, K_1 | query rows, V_0 | then per tile i:  K_{i+2} ... V_{i+1}
+  using VRaw = typename RawBits<S::kBpl>::type;
+  TileDma<DT, D> dma;
+  dma.init(lane);
+  const long long n_tiles = ceil_div(n_rows, kTileKeys);
+  const int cnt = wave < n_tiles ? (int)((n_tiles - wave + kDecWaves - 1) / kDecWaves) : 0;
+  u32x4* ring = s_tile[wave][0];
+  FragReader<DT, D> frags;
+  frags.init_at(lane, lds_addr(ring));
+  const unsigned int p_addr = lds_addr(&s_p[wave][0][0]);
+  auto issue_k = [&](int i) {
+    dma.issue(kb, wave + (long long)i * kDecWaves, n_rows, lane, ring + (i % kStages) * T::kTileChunks);
+  };
+  const unsigned int v_lane = (unsigned int)lane * S::kBpl;   // a row is a uniform address plus this
+  auto load_v = [&](VRaw (&dst)[kTileKeys], int i) {
+    const long long row0 = (wave + (long long)i * kDecWaves) * kTileKeys;
+    const char* p = vb + row0 * T::kRowBytes;
+    if (row0 + kTileKeys <= n_rows) {
+#pragma unroll
+      for (int kk = 0; kk < kTileKeys; ++kk) dst[kk] = *reinterpret_cast<const VRaw*>(p + kk * T::kRowBytes + v_lane);
+    } else {                                                // rows beyond the unit repeat its last row
+      const int last = (int)(n_rows - 1 - row0);            // 0 .. 30, uniform
+#pragma unroll
+      for (int kk = 0; kk < kTileKeys; ++kk)
+        dst[kk] = *reinterpret_cast<const VRaw*>(p + (kk < last ? kk : last) * T::kRowBytes + v_lane);
+    }
+  };
+  if (cnt > 0) issue_k(0);
+  if (cnt > 1) issue_k(1);
+  asm volatile("" ::: "memory");
+
   // the group's query rows as the 32-column operand: column t < G is head g*G + t
   const int col = lane & 31, half = lane >> 5;
   u32x4 qf[T::kSteps];
@@ -158,15 +214,10 @@ __global__ void __launch_bounds__(kDecThreads) decode_kernel(DecodeArgs a) {
     if (col < a.G) x = a.q[((long long)b * a.H + (long long)g * a.G + col) * T::kCpr + 2 * j + half];
     qf[j] = x;
   }
-  TileDma<DT, D> dma;
-  dma.init(lane);
-  unsigned int voff[8];
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const unsigned int byte = (unsigned int)lane * S::kBpl;
-    voff[j] = (((byte >> 4) ^ (unsigned int)j) << 4) | (byte & 15u);
-  }
-  wait_vmcnt<0>();                                          // the ring counts its own loads only
+  const unsigned int p_col = p_addr + (unsigned int)(col * 4);                  // row 0 of s_p, this head's column
+  const unsigned int p_mine = p_col + (unsigned int)(4 * half * kPs * 4);       // first key this lane's results cover
+  VRaw v0[kTileKeys], v1[kTileKeys];
+  if (cnt > 0) load_v(v0, 0);
 
   float m_run = -INFINITY, l_run = 0.0f;                    // of head `col` (lanes col < G)
   float acc[GP][kDpl];
@@ -175,88 +226,109 @@ __global__ void __launch_bounds__(kDecThreads) decode_kernel(DecodeArgs a) {
 #pragma unroll
     for (int e = 0; e < kDpl; ++e) acc[t][e] = 0.0f;
 
-  // ring items of this wavefront: K tile j0, V tile j0, K tile j0 + kDecWaves, ...
-  const long long n_tiles = ceil_div(n_rows, kTileKeys);
-  const int cnt = wave < n_tiles ? (int)((n_tiles - wave + kDecWaves - 1) / kDecWaves) : 0;
-  const int n_items = 2 * cnt;
-  u32x4* ring = s_tile[wave][0];
-  auto issue_item = [&](int item) {
-    const long long tile = wave + (long long)(item >> 1) * kDecWaves;
-    dma.issue((item & 1) ? vb : kb, tile, n_rows, lane, ring + (item % kStages) * T::kTileChunks);
-  };
-#pragma unroll
-  for (int p = 0; p < kStages - 1; ++p)
-    if (p < n_items) issue_item(p);
-
-  for (int it = 0; it < cnt; ++it) {
+  // PAR = it % 2 is the ring stage of K_it
+  auto step = [&](auto par, int it, VRaw (&v_cur)[kTileKeys], VRaw (&v_next)[kTileKeys]) {
+    constexpr int PAR = decltype(par)::value;
     const long long tile = wave + (long long)it * kDecWaves;
     // ---------------- K tile: logits, online softmax, probabilities to LDS
     {
-      const int item = 2 * it;
-      wait_lds();                                           // reads of the stage about to be refilled are done
-      if (item + kStages - 1 < n_items) issue_item(item + kStages - 1);
-      const int younger = n_items - 1 - item < kStages - 1 ? n_items - 1 - item : kStages - 1;
-      wait_tile<DT, D>(younger);
+      // everything older than V_it (32 loads) and, if it was requested, K_{it+1} has landed
+      if (it + 1 < cnt) wait_vmcnt<T::kLoads + kTileKeys>(); else wait_vmcnt<kTileKeys>();
       u32x4 kf[T::kSteps];
-      lds_to_frag<DT, D>(ring + (item % kStages) * T::kTileChunks, lane, kf);
+      frags.template read_at<PAR * T::kTileBytes>(kf);      // in registers on return: the stage is free
+      if (it + 2 < cnt) issue_k(it + 2);
       asm volatile("" ::: "memory");
-      f32x16 x = dot_tile<DT, D, true>(kf, qf);             // x[v]: key 8*(v/4) + 4*half + v%4, head col
-      const long long key0 = tile * kTileKeys;
-      const bool ragged = key0 + kTileKeys > n_rows;
-      float mt = -INFINITY;
+      // two independent accumulation chains halve the latency of the dependent MFMAs
+      f32x16 x = {0}, x2 = {0};
 #pragma unroll
-      for (int v = 0; v < 16; ++v) {
-        float s = x[v] * a.c2;
-        if (ragged && key0 + 8 * (v / 4) + 4 * half + (v % 4) >= n_rows) s = -INFINITY;
-        x[v] = s;
-        mt = fmaxf(mt, s);
+      for (int j = 0; j < T::kSteps; j += 2) {
+        x = mfma_chunk<DT>(kf[j], qf[j], x);
+        x2 = mfma_chunk<DT>(kf[j + 1], qf[j + 1], x2);
+      }
+      x += x2;                                              // x[v]: key 8*(v/4) + 4*half + v%4, head col
+      const long long left = n_rows - tile * kTileKeys;     // rows of the unit from this tile on (uniform)
+      float mt = -INFINITY;
+      if (left >= kTileKeys) {
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          x[v] *= a.c2;
+          mt = fmaxf(mt, x[v]);
+        }
+      } else {                                              // the unit's last, partial tile
+        int h4 = 4 * half;
+        asm volatile("" : "+v"(h4));                        // keeps this path's temporaries out of the hot loop
+#pragma unroll
+        for (int v = 0; v < 16; ++v) {
+          const float s = (h4 + 8 * (v / 4) + (v % 4) < (int)left) ? x[v] * a.c2 : -INFINITY;
+          x[v] = s;
+          mt = fmaxf(mt, s);
+        }
       }
       mt = fmaxf(mt, __shfl_xor(mt, 32));
       const float m_new = fmaxf(m_run, mt);                 // finite: a tile holds at least one row
       const float alpha = fast_exp2(m_run - m_new);
       float ls = 0.0f;
       if (col < GP) {
-#pragma unroll
-        for (int v = 0; v < 16; ++v) {
+        static_for<16>([&](auto vc) {
+          constexpr int v = decltype(vc)::value;
           const float p = fast_exp2(x[v] - m_new);
           ls += p;
-          s_p[wave][8 * (v / 4) + 4 * half + (v % 4)][col] = p;
-        }
-        if (half == 0) s_p[wave][kTileKeys][col] = alpha;
+          lds_write32_at<(8 * (v / 4) + (v % 4)) * kPs * 4>(p_mine, p);
+        });
+        if (half == 0) lds_write32_at<kTileKeys * kPs * 4>(p_col, alpha);
       }
       l_run = l_run * alpha + ls;
       m_run = m_new;
     }
-    wave_lds_sync();
-    // ---------------- V tile: rescale, accumulate
+    lds_reads_done();                                       // LDS operations of a wavefront execute in order
+    // ---------------- V tile (already requested): request the next one, rescale, accumulate
     {
-      const int item = 2 * it + 1;
-      wait_lds();
-      if (item + kStages - 1 < n_items) issue_item(item + kStages - 1);
-      const int younger = n_items - 1 - item < kStages - 1 ? n_items - 1 - item : kStages - 1;
-      wait_tile<DT, D>(younger);
-      const char* stage = reinterpret_cast<const char*>(ring + (item % kStages) * T::kTileChunks);
-#pragma unroll
-      for (int t = 0; t < GP; ++t) {
-        const float al = s_p[wave][kTileKeys][t];
-#pragma unroll
-        for (int e = 0; e < kDpl; ++e) acc[t][e] *= al;
-      }
-#pragma unroll
-      for (int kk = 0; kk < kTileKeys; ++kk) {
-        float vx[kDpl];
-        read_v<DT, D>(stage, kk, voff, vx);
-#pragma unroll
-        for (int t = 0; t < GP; ++t) {
-          const float p = s_p[wave][kk][t];
-#pragma unroll
-          for (int e = 0; e < kDpl; ++e) acc[t][e] = fmaf(p, vx[e], acc[t][e]);
-        }
-      }
+      if (it + 1 < cnt) load_v(v_next, it + 1);
       asm volatile("" ::: "memory");
+      u32x4 al[kPs / 4];
+      static_for<kPs / 4>([&](auto cc) {
+        constexpr int c = decltype(cc)::value;
+        lds_read128_at<(kTileKeys * kPs + 4 * c) * 4>(p_addr, al[c]);
+      });
+#pragma unroll
+      for (int t = 0; t < GP; ++t)
+#pragma unroll
+        for (int e = 0; e < kDpl; ++e) acc[t][e] *= __uint_as_float(al[t / 4][t % 4]);
+      // probabilities of four keys per read batch
+      static_for<kTileKeys / 4>([&](auto kc) {
+        constexpr int k4 = 4 * decltype(kc)::value;
+        u32x4 pr[kPs / 4][4];
+        static_for<kPs / 4>([&](auto cc) {
+          constexpr int c = decltype(cc)::value;
+          lds_read128x4_strided<kPs * 4, (k4 * kPs + 4 * c) * 4>(p_addr, pr[c][0], pr[c][1], pr[c][2], pr[c][3]);
+        });
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk) {
+          float vx[kDpl];
+          unpack_v<DT, D>(v_cur[k4 + kk], vx);
+#pragma unroll
+          for (int t = 0; t < GP; ++t) {
+            const float p = __uint_as_float(pr[t / 4][kk][t % 4]);
+#pragma unroll
+            for (int e = 0; e < kDpl; ++e) acc[t][e] = fmaf(p, vx[e], acc[t][e]);
+          }
+        }
+        // pin the accumulators here: otherwise the multiply-adds of all batches sink below the reads
+        // of all batches, which then have to stay in registers together
+#pragma unroll
+        for (int t = 0; t < GP; ++t)
+#pragma unroll
+          for (int e = 0; e < kDpl; ++e) asm volatile("" : "+v"(acc[t][e]));
+      });
     }
-    wave_lds_sync();                                        // next tile's probabilities overwrite s_p
+  };
+  int it = 0;
+  for (; it + 1 < cnt; it += 2) {
+    step(std::integral_constant<int, 0>{}, it, v0, v1);
+    step(std::integral_constant<int, 1>{}, it + 1, v1, v0);
   }
+  if (it < cnt) step(std::integral_constant<int, 0>{}, it, v0, v1);
+  wait_vmcnt<0>();
 
   // ---------------- merge the wavefronts of the unit
   l_run += __shfl_xor(l_run, 32);
@@ -264,6 +336,8 @@ __global__ void __launch_bounds__(kDecThreads) decode_kernel(DecodeArgs a) {
     s_m[wave][lane] = m_run;
     s_l[wave][lane] = l_run;
   }
+  __syncthreads();                                          // every wavefront is done with its ring
+  float (*s_acc)[GP][D] = reinterpret_cast<float (*)[GP][D]>(&s_tile[0][0][0]);
 #pragma unroll
   for (int t = 0; t < GP; ++t)
 #pragma unroll
@@ -293,16 +367,11 @@ template <int D, int GP>
 __global__ void __launch_bounds__(256) decode_merge_kernel(DecodeArgs a, float* __restrict__ out,
                                                            float* __restrict__ lse) {
   const int b = blockIdx.y, g = blockIdx.x;
-  const long long* off = a.head_offsets + (long long)b * (a.H_kv + 1);
-  const long long tail_units = a.tail_len > 0 ? ceil_div(a.tail_len, a.rows_per_unit) : 0;
-  long long first = 0, total = 0, mine = 0;
-  for (int gg = 0; gg < a.H_kv; ++gg) {
-    const long long c = ceil_div(head_len(off, gg), a.rows_per_unit) + tail_units;
-    if (gg < g) first += c;
-    if (gg == g) mine = c;
-    total += c;
-  }
-  const bool overflow = total > a.units_bound || !offsets_usable(off, a.H_kv, a.rows_capacity);
+  const UnitMap um = map_units(a.head_offsets + (long long)b * (a.H_kv + 1), a.H_kv, a.rows_capacity,
+                               a.rows_per_unit, a.tail_len, (int)(threadIdx.x & 63));
+  const long long mine = __builtin_amdgcn_readfirstlane(__shfl(um.cnt, g));
+  const long long first = __builtin_amdgcn_readfirstlane(__shfl(um.incl, g)) - mine;
+  const bool overflow = !um.usable || um.total > (unsigned int)a.units_bound;
   const float2* ml = a.part_ml + ((long long)b * a.units_bound + first) * GP;
   const float* pa = a.part_acc + ((long long)b * a.units_bound + first) * GP * D;
   for (int idx = threadIdx.x; idx < a.G * D; idx += 256) {
@@ -311,14 +380,31 @@ __global__ void __launch_bounds__(256) decode_merge_kernel(DecodeArgs a, float* 
     if (overflow) {
       result = lse_v = NAN;
     } else if (mine > 0) {
+      // eight units per round trip: the loads of a batch are independent of each other
       float M = -INFINITY;
-      for (long long i = 0; i < mine; ++i) M = fmaxf(M, ml[i * GP + t].x);
+      for (long long i0 = 0; i0 < mine; i0 += 8) {
+        float mx[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) mx[u] = i0 + u < mine ? ml[(i0 + u) * GP + t].x : -INFINITY;
+#pragma unroll
+        for (int u = 0; u < 8; ++u) M = fmaxf(M, mx[u]);
+      }
       float L = 0.0f, sum = 0.0f;
-      for (long long i = 0; i < mine; ++i) {
-        const float2 s = ml[i * GP + t];
-        const float wgt = fast_exp2(s.x - M);
-        L += wgt * s.y;
-        sum += wgt * pa[(i * GP + t) * D + e];
+      for (long long i0 = 0; i0 < mine; i0 += 8) {
+        float2 st[8];
+        float pv[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {
+          const bool in = i0 + u < mine;
+          st[u] = in ? ml[(i0 + u) * GP + t] : make_float2(-INFINITY, 0.0f);
+          pv[u] = in ? pa[((i0 + u) * GP + t) * D + e] : 0.0f;
+        }
+#pragma unroll
+        for (int u = 0; u < 8; ++u) {                       // unit order: the result does not depend on timing
+          const float wgt = fast_exp2(st[u].x - M);
+          L += wgt * st[u].y;
+          sum += wgt * pv[u];
+        }
       }
       result = sum / L;
       lse_v = (M + log2f(L)) * 0.6931471805599453f;
@@ -367,6 +453,10 @@ DecodePlan make_decode_plan(const lava_layer_desc& d, int32_t batch, int64_t row
   int64_t c = (total / (4 * (int64_t)device_cus()) + step - 1) / step * step;
   if (c < step) c = step;
   if (c > 8 * step) c = 8 * step;
+  if (const char* env = getenv("LAVA_DECODE_ROWS")) {      // tuning knob: rows per unit
+    const long v = atol(env);
+    if (v >= step && v <= 64 * step) c = v / step * step;
+  }
   p.rows_per_unit = (int)c;
   p.group_pad = padded_group(d.n_q_heads / d.n_kv_heads);
   const int64_t tail_units = tail_len > 0 ? (tail_len + c - 1) / c : 0;

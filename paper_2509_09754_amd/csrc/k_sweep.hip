@@ -114,6 +114,8 @@ stats_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long 
   load_q<DT, D, GT>(q_win, h0, nh, w, lane, qf);
   TileDma<DT, D> dma;
   dma.init(lane);
+  FragReader<DT, D> frags;
+  frags.init(lane);
 
   const long long n_tiles = (n + kTileKeys - 1) / kTileKeys;
   const long long t_begin = (long long)blockIdx.x * tiles_per_block;
@@ -130,9 +132,13 @@ stats_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long 
   const long long first = t_begin + wave;
   const int cnt = first < t_end ? (int)((t_end - first + kWaves - 1) / kWaves) : 0;
   u32x4* ring = s_tile[wave][0];
+  const unsigned int ring_addr = lds_addr(ring);
 #pragma unroll
   for (int p = 0; p < kStages - 1; ++p)
     if (p < cnt) dma.issue(kg, first + (long long)p * kWaves, n, lane, ring + p * T::kTileChunks);
+  // the query rows (and the first tiles) are in before the loop: otherwise the compiler, which cannot
+  // count the ring's loads across iterations, waits for everything in flight before each tile's products
+  wait_vmcnt<0>();
   for (int it = 0; it < cnt; ++it) {
     const long long tile = first + (long long)it * kWaves;
     const int ahead = it + kStages - 1;
@@ -141,8 +147,7 @@ stats_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long 
     const int younger = cnt - 1 - it < kStages - 1 ? cnt - 1 - it : kStages - 1;
     wait_tile<DT, D>(younger);
     u32x4 kf[T::kSteps];
-    lds_to_frag<DT, D>(ring + (it % kStages) * T::kTileChunks, lane, kf);
-    asm volatile("" ::: "memory");   // later loads into this ring stage stay below these reads
+    frags.read(ring_addr + (it % kStages) * T::kTileBytes, kf);
 
     const long long key0 = tile * kTileKeys;
     if (key0 + kTileKeys - 1 <= n - w) {
@@ -270,6 +275,8 @@ scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long
   // start the ring first: these loads only need the key pointer
   TileDma<DT, D> dma;
   dma.init(lane);
+  FragReader<DT, D> frags;
+  frags.init(lane);
   const long long n_tiles = (n_prefix + kTileKeys - 1) / kTileKeys;
   const long long t_begin = (long long)blockIdx.x * tiles_per_block;
   long long t_end = t_begin + tiles_per_block;
@@ -287,6 +294,7 @@ scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long
   const int cnt = cnt_own + (halo_tile >= 0 ? 1 : 0);
   auto tile_at = [&](int j) -> long long { return j < cnt_own ? first + (long long)j * kWaves : halo_tile; };
   u32x4* ring = s_tile[wave][0];
+  const unsigned int ring_addr = lds_addr(ring);
 #pragma unroll
   for (int p = 0; p < kStages - 1; ++p)
     if (p < cnt) dma.issue(kg, tile_at(p), n, lane, ring + p * T::kTileChunks);
@@ -339,7 +347,8 @@ scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long
 
   const int half = lane >> 5;
   // rows held by this lane in result register v: 8 * (v / 4) + 4 * half + v % 4 -> four float4 per head
-  const float4* bias4 = reinterpret_cast<const float4*>(s_bias) + half;
+  const unsigned int bias_addr = lds_addr(s_bias) + half * 16;
+  const unsigned int span_addr = lds_addr(s_span) + lane * 4;
 
   // The result of a tile is stored one iteration later, right after the next tile's arrival wait:
   // the store then has a whole iteration to complete before a wait counts it among the older
@@ -364,8 +373,7 @@ scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long
     wait_tile<DT, D>(younger);
     if constexpr (!FUSED) store_result(pend_key, pend);
     u32x4 kf[T::kSteps];
-    lds_to_frag<DT, D>(ring + (it % kStages) * T::kTileChunks, lane, kf);
-    asm volatile("" ::: "memory");   // later loads into this ring stage stay below these reads
+    frags.read(ring_addr + (it % kStages) * T::kTileBytes, kf);
 
     float best = 0.0f;
     f32x16 acc = dot_tile<DT, D, false>(kf, qf[0]);
@@ -374,20 +382,21 @@ scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long
       f32x16 nxt = acc;
       if (t + 1 < GT) nxt = dot_tile<DT, D, false>(kf, qf[t + 1]);
       float ps = 0.0f;
+      u32x4 bb[4];                       // biases of rows 8*jj + 4*half + 0..3 of head t
+      lds_read128x4_strided<32>(bias_addr + t * 128, bb[0], bb[1], bb[2], bb[3]);
 #pragma unroll
       for (int jj = 0; jj < 4; ++jj) {
-        const float4 b = bias4[t * 8 + 2 * jj];
-        ps += fast_exp2(fmaf(acc[4 * jj + 0], c2, -b.x));
-        ps += fast_exp2(fmaf(acc[4 * jj + 1], c2, -b.y));
-        ps += fast_exp2(fmaf(acc[4 * jj + 2], c2, -b.z));
-        ps += fast_exp2(fmaf(acc[4 * jj + 3], c2, -b.w));
+        ps += fast_exp2(fmaf(acc[4 * jj + 0], c2, -__uint_as_float(bb[jj].x)));
+        ps += fast_exp2(fmaf(acc[4 * jj + 1], c2, -__uint_as_float(bb[jj].y)));
+        ps += fast_exp2(fmaf(acc[4 * jj + 2], c2, -__uint_as_float(bb[jj].z)));
+        ps += fast_exp2(fmaf(acc[4 * jj + 3], c2, -__uint_as_float(bb[jj].w)));
       }
       ps += __shfl_xor(ps, 32);
       best = fmaxf(best, ps);
       acc = nxt;
     }
     if constexpr (FUSED) {
-      if (half == 0) s_span[(int)(tile - t_begin + 1) * kTileKeys + lane] = best;
+      if (half == 0) lds_write32(span_addr + (unsigned int)(tile - t_begin + 1) * (kTileKeys * 4), best);
     } else {
       pend = best;
       pend_key = (int)(tile * kTileKeys) + (lane & 31);
@@ -403,6 +412,7 @@ scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) vb = fmaxf(vb, __shfl_xor(vb, off));
     if ((threadIdx.x & 63) == 0) s_vb[wave] = vb;
+    lds_reads_done();                      // this wavefront's span entries are written
     __syncthreads();                       // s_span complete, s_vb visible
     vb = s_vb[0];
 #pragma unroll
@@ -484,6 +494,8 @@ vnorm_kernel(const u32x4* __restrict__ v, long long n, int tiles_per_block, floa
   const char* vg = reinterpret_cast<const char*>(v) + (long long)g * n * T::kRowBytes;
   TileDma<DT, D> dma;
   dma.init(lane);
+  FragReader<DT, D> frags;
+  frags.init(lane);
 
   const long long n_tiles = (n + kTileKeys - 1) / kTileKeys;
   const long long t_begin = (long long)blockIdx.x * tiles_per_block;
@@ -492,6 +504,7 @@ vnorm_kernel(const u32x4* __restrict__ v, long long n, int tiles_per_block, floa
   const long long first = t_begin + wave;
   const int cnt = first < t_end ? (int)((t_end - first + kWaves - 1) / kWaves) : 0;
   u32x4* ring = s_tile[wave][0];
+  const unsigned int ring_addr = lds_addr(ring);
 #pragma unroll
   for (int p = 0; p < kStages - 1; ++p)
     if (p < cnt) dma.issue(vg, first + (long long)p * kWaves, n, lane, ring + p * T::kTileChunks);
@@ -510,8 +523,7 @@ vnorm_kernel(const u32x4* __restrict__ v, long long n, int tiles_per_block, floa
     // each lane sums the half row it holds (row lane % 32; rows past n repeat row n - 1), the two
     // halves are added across lanes
     u32x4 f[T::kSteps];
-    lds_to_frag<DT, D>(ring + (it % kStages) * T::kTileChunks, lane, f);
-    asm volatile("" ::: "memory");   // later loads into this ring stage stay below these reads
+    frags.read(ring_addr + (it % kStages) * T::kTileBytes, f);
     float s = 0.0f;
 #pragma unroll
     for (int j = 0; j < T::kSteps; ++j) s = abs_sum16<DT>(f[j], s);

@@ -12,6 +12,8 @@
 
 #include <hip/hip_runtime.h>
 
+#include <utility>
+
 #include "common.h"
 
 namespace lava {
@@ -117,13 +119,17 @@ struct TileDma {
   // rows at or beyond n are read from row n - 1 (callers mask or drop them)
   __device__ __forceinline__ void issue_clamped(const char* __restrict__ head_base, long long tile,
                                                 long long n, int lane, u32x4* stage) const {
+    // This path runs once per sweep.  The lane index goes through an opaque move so that nothing
+    // derived from it is computed ahead of the hot loop and kept in registers across it.
+    asm volatile("" : "+v"(lane));
+    const char* tile_base = head_base + tile * T::kTileBytes;
+    const int last = (int)(n - 1 - tile * kTileKeys);      // last existing row of the tile, 0 .. 30
 #pragma unroll
     for (int i = 0; i < T::kLoads; ++i) {
       const int q = i * 64 + lane;
       const int row = q / T::kCpr, slot = q % T::kCpr;
-      long long key = tile * kTileKeys + row;
-      key = key < n ? key : n - 1;
-      const char* src = head_base + key * T::kRowBytes + ((slot ^ (row & 7)) << 4);
+      const int src_row = row < last ? row : last;
+      const char* src = tile_base + (unsigned int)(src_row * T::kRowBytes + ((slot ^ (row & 7)) << 4));
       __builtin_amdgcn_global_load_lds((const LAVA_GLOBAL_AS void*)src, (LAVA_LDS_AS void*)(stage + i * 64), 16,
                                        0, 0);
     }
@@ -152,17 +158,138 @@ __device__ __forceinline__ void wait_tile(int younger) {
   }
 }
 
-template <int DT, int D>
-__device__ __forceinline__ void lds_to_frag(const u32x4* __restrict__ buf, int lane,
-                                            u32x4 (&frag)[Tile<DT, D>::kSteps]) {
-  using T = Tile<DT, D>;
-  const int row = lane & 31, half = lane >> 5;
-#pragma unroll
-  for (int j = 0; j < T::kSteps; ++j) {
-    const int c = 2 * j + half;
-    frag[j] = buf[row * T::kCpr + (c ^ (row & 7))];
-  }
+// ------------------------------------------------------------------------------------------
+// LDS accesses written as instructions.
+//
+// While direct-to-LDS loads are in flight the compiler cannot tell which LDS bytes they will
+// write, so before EVERY ordinary LDS access it waits for all of them (vmcnt(0)), which turns the
+// ring into one tile in flight per wavefront.  The ring protocol already guarantees that a stage
+// is only read after its own loads have landed (wait_tile) and only refilled after its reads have
+// returned (lds_reads_done), so the LDS accesses inside a sweep are issued as instructions the
+// compiler does not reason about.  Each read helper ends with its own wait: its results are valid
+// on return.  Addresses are LDS byte offsets (lds_addr).
+// ------------------------------------------------------------------------------------------
+__device__ __forceinline__ unsigned int lds_addr(const void* p) {
+  return (unsigned int)(unsigned long long)(LAVA_LDS_AS const char*)p;
 }
+
+// every LDS operation this wavefront has issued is complete
+__device__ __forceinline__ void lds_reads_done() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+
+__device__ __forceinline__ void lds_read128x4(unsigned int a0, unsigned int a1, unsigned int a2, unsigned int a3,
+                                              u32x4& o0, u32x4& o1, u32x4& o2, u32x4& o3) {
+  asm volatile(
+      "ds_read_b128 %0, %4\n\t"
+      "ds_read_b128 %1, %5\n\t"
+      "ds_read_b128 %2, %6\n\t"
+      "ds_read_b128 %3, %7\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(o0), "=&v"(o1), "=&v"(o2), "=&v"(o3)
+      : "v"(a0), "v"(a1), "v"(a2), "v"(a3)
+      : "memory");
+}
+
+// Offsets known at compile time travel in the instruction (16-bit field), so that one address
+// register serves every access of a loop instead of one hoisted register per access.
+// four reads at byte offsets OFF, OFF + STRIDE, OFF + 2*STRIDE, OFF + 3*STRIDE from one address
+template <int STRIDE, int OFF = 0>
+__device__ __forceinline__ void lds_read128x4_strided(unsigned int a, u32x4& o0, u32x4& o1, u32x4& o2, u32x4& o3) {
+  static_assert(OFF >= 0 && OFF + 3 * STRIDE < 65536, "LDS instruction offset field");
+  asm volatile(
+      "ds_read_b128 %0, %4 offset:%5\n\t"
+      "ds_read_b128 %1, %4 offset:%6\n\t"
+      "ds_read_b128 %2, %4 offset:%7\n\t"
+      "ds_read_b128 %3, %4 offset:%8\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(o0), "=&v"(o1), "=&v"(o2), "=&v"(o3)
+      : "v"(a), "n"(OFF), "n"(OFF + STRIDE), "n"(OFF + 2 * STRIDE), "n"(OFF + 3 * STRIDE)
+      : "memory");
+}
+
+// four reads at one compile-time offset from four addresses
+template <int OFF>
+__device__ __forceinline__ void lds_read128x4_at(unsigned int a0, unsigned int a1, unsigned int a2, unsigned int a3,
+                                                 u32x4& o0, u32x4& o1, u32x4& o2, u32x4& o3) {
+  static_assert(OFF >= 0 && OFF < 65536, "LDS instruction offset field");
+  asm volatile(
+      "ds_read_b128 %0, %4 offset:%8\n\t"
+      "ds_read_b128 %1, %5 offset:%8\n\t"
+      "ds_read_b128 %2, %6 offset:%8\n\t"
+      "ds_read_b128 %3, %7 offset:%8\n\t"
+      "s_waitcnt lgkmcnt(0)"
+      : "=&v"(o0), "=&v"(o1), "=&v"(o2), "=&v"(o3)
+      : "v"(a0), "v"(a1), "v"(a2), "v"(a3), "n"(OFF)
+      : "memory");
+}
+
+template <int OFF>
+__device__ __forceinline__ void lds_read128_at(unsigned int a, u32x4& o) {
+  static_assert(OFF >= 0 && OFF < 65536, "LDS instruction offset field");
+  asm volatile("ds_read_b128 %0, %1 offset:%2\n\ts_waitcnt lgkmcnt(0)" : "=&v"(o) : "v"(a), "n"(OFF) : "memory");
+}
+
+template <int OFF>
+__device__ __forceinline__ void lds_write32_at(unsigned int a, float x) {
+  static_assert(OFF >= 0 && OFF < 65536, "LDS instruction offset field");
+  asm volatile("ds_write_b32 %0, %1 offset:%2" : : "v"(a), "v"(x), "n"(OFF) : "memory");
+}
+
+// f(std::integral_constant<int, 0>{}), ..., f(std::integral_constant<int, N - 1>{}): a loop whose
+// index is a constant expression inside the body
+template <int... I, class F>
+__device__ __forceinline__ void static_for_impl(std::integer_sequence<int, I...>, F&& f) {
+  (f(std::integral_constant<int, I>{}), ...);
+}
+template <int N, class F>
+__device__ __forceinline__ void static_for(F&& f) {
+  static_for_impl(std::make_integer_sequence<int, N>{}, f);
+}
+
+__device__ __forceinline__ void lds_read128(unsigned int a, u32x4& o) {
+  asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(o) : "v"(a) : "memory");
+}
+
+__device__ __forceinline__ void lds_write32(unsigned int a, float x) {
+  asm volatile("ds_write_b32 %0, %1" : : "v"(a), "v"(x) : "memory");
+}
+
+// Per-lane addresses of a tile's MFMA operand fragments: lane l holds row l % 32 and, at step j,
+// the row's 16-byte chunk 2j + l/32 (stored at slot chunk ^ (row & 7)).
+template <int DT, int D>
+struct FragReader {
+  using T = Tile<DT, D>;
+  unsigned int foff[T::kSteps];
+
+  __device__ __forceinline__ void init(int lane) {
+    const int row = lane & 31, half = lane >> 5;
+#pragma unroll
+    for (int j = 0; j < T::kSteps; ++j) foff[j] = (unsigned int)((row * T::kCpr + ((2 * j + half) ^ (row & 7))) << 4);
+  }
+
+  // Variant for a ring whose stage is known at compile time: init_at folds the ring's address into
+  // the per-lane offsets once, read_at<OFF> then needs no address arithmetic at all.
+  __device__ __forceinline__ void init_at(int lane, unsigned int ring) {
+    init(lane);
+#pragma unroll
+    for (int j = 0; j < T::kSteps; ++j) foff[j] += ring;
+  }
+  template <int OFF>
+  __device__ __forceinline__ void read_at(u32x4 (&frag)[T::kSteps]) const {
+#pragma unroll
+    for (int j = 0; j < T::kSteps; j += 4)
+      lds_read128x4_at<OFF>(foff[j], foff[j + 1], foff[j + 2], foff[j + 3], frag[j], frag[j + 1], frag[j + 2],
+                            frag[j + 3]);
+  }
+
+  // `stage`: LDS byte address of the ring stage.  The fragments are in registers on return.
+  __device__ __forceinline__ void read(unsigned int stage, u32x4 (&frag)[T::kSteps]) const {
+    static_assert(T::kSteps % 4 == 0, "fragments are read four at a time");
+#pragma unroll
+    for (int j = 0; j < T::kSteps; j += 4)
+      lds_read128x4(stage + foff[j], stage + foff[j + 1], stage + foff[j + 2], stage + foff[j + 3], frag[j],
+                    frag[j + 1], frag[j + 2], frag[j + 3]);
+  }
+};
 
 // Query fragments of the chunk's heads: row r = lane % 32 (zero beyond the window or the chunk).
 template <int DT, int D, int GT>
