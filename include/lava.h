@@ -125,8 +125,11 @@ size_t lava_select_workspace_bytes(int64_t total_entries);
  * the scores are equal and its flat index is smaller; the first `budget` entries survive.
  *
  *   scores        device float [total_entries], heads concatenated.  No NaN; -0 == +0.
- *   seg_offsets   device int64 [n_heads + 1] segment starts (seg_offsets[n_heads] ==
- *                 total_entries), or NULL for equal segments of total_entries / n_heads
+ *   seg_offsets   device int64 [n_heads + 1] segment starts, or NULL for equal segments of
+ *                 total_entries / n_heads.  With explicit segments the number of entries is
+ *                 seg_offsets[n_heads] as read on the device (clamped to total_entries, which is
+ *                 then an upper bound: it sizes the launch and the workspace), so that selections
+ *                 can be chained without a host round trip
  *   budget        entries to keep, 0 <= budget <= total_entries; when budget_dev != NULL the
  *                 value is read on the device from *budget_dev instead (clamped to
  *                 [0, min(budget, total_entries)]) and `budget` is the capacity of the outputs
@@ -165,6 +168,68 @@ int32_t lava_select_status(const void* workspace, int64_t total_entries, void* h
 int32_t lava_compact_kv(const lava_layer_desc* desc, int64_t n, const void* k, const void* v,
                         const int64_t* head_offsets, const int32_t* kept_idx, int64_t capacity,
                         void* k_out, void* v_out, void* hip_stream);
+
+/*
+ * The same gather from an already packed source: what a re-eviction of a compressed layer does
+ * (Alg. 2, inner loop: layers below the one just prefilled are evicted again, from what they still
+ * hold, with a smaller budget).
+ *
+ *   src_offsets   device int64 [H_kv + 1]: head g owns source rows src_offsets[g] .. src_offsets[g+1]-1
+ *   src_rows      rows in the source pool; offsets beyond it are never followed
+ *   k_src, v_src  device [src_rows][d_h];  pos_src device int32 [src_rows] or NULL
+ *   head_offsets, kept_idx   as written by lava_select_topk run on the source's segments
+ *                 (kept_idx counts from the start of the head's source segment)
+ *   k_out, v_out  device [capacity][d_h]; pos_out device int32 [capacity] or NULL: the token
+ *                 position of every surviving row (pos_src of its source row)
+ * Out of place: outputs must not overlap the source.
+ */
+int32_t lava_compact_packed(const lava_layer_desc* desc, const int64_t* src_offsets, int64_t src_rows,
+                            const void* k_src, const void* v_src, const int32_t* pos_src,
+                            const int64_t* head_offsets, const int32_t* kept_idx, int64_t capacity,
+                            void* k_out, void* v_out, int32_t* pos_out, void* hip_stream);
+
+/*
+ * Algorithm 2 as a driver: state of one layer between cascade steps.  Every pointer is device
+ * memory owned by the caller; buffers come in pairs because a re-eviction is out of place, and
+ * `cur` (host) says which of the pair holds the layer's current state.  capacity: rows of each
+ * pool, at least min(total budget, H_kv * N).
+ */
+typedef struct lava_cascade_layer {
+  void* k[2];               /* [capacity][d_h] packed keys                                     */
+  void* v[2];               /* [capacity][d_h] packed values                                   */
+  int32_t* pos[2];          /* [capacity] token position of each retained row                  */
+  float* scores[2];         /* [capacity] retained LAVa scores (what the next re-eviction ranks)*/
+  int64_t* head_offsets[2]; /* [H_kv + 1]                                                      */
+  int32_t* head_counts;     /* [H_kv] dynamic head budgets after the latest step               */
+  int32_t* kept_idx;        /* [capacity] scratch                                              */
+  int64_t capacity;
+  int32_t cur;              /* updated by lava_cascade_step                                    */
+  int32_t reserved;
+} lava_cascade_layer;
+
+/* Bytes of device workspace lava_cascade_step needs for layers of H_kv * n entries. */
+size_t lava_cascade_workspace_bytes(const lava_layer_desc* desc, int64_t n);
+
+/*
+ * One outer iteration of Algorithm 2, after layer `layer` (0-based) has been prefilled and scored:
+ *   budgets  B_t = e_t / sum_{t' <= layer} e_t' * total_budget for t = 0..layer (device, bounds
+ *            H_kv * w and H_kv * n, rounding as lava_layer_budgets)
+ *   layer    first eviction of the new layer from its dense cache k_new, v_new [H_kv][n][d_h] by
+ *            its scores [H_kv][n] (as written by lava_window_scores) into layers[layer], pool 0
+ *   t<layer  re-eviction of every earlier layer from its current pool into the other one with the
+ *            scores it retained; the budget actually applied is min(B_t, entries still held)
+ *
+ *   e        device float [>= layer + 1]: statistics of layers 0..layer (point layer_stat of
+ *            lava_window_scores at e + layer)
+ *   layers   host array [layer + 1]
+ *   budgets  device int64 [>= layer + 1] out
+ * Everything is enqueued on the stream; nothing is read back.  Selection is integer-exact, rows
+ * are bit copies, so the state after every step equals the literal algorithm's.
+ */
+int32_t lava_cascade_step(const lava_layer_desc* desc, int32_t layer, int64_t n, const void* k_new,
+                          const void* v_new, const float* scores_new, const float* e,
+                          int64_t total_budget, lava_cascade_layer* layers, int64_t* budgets,
+                          void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Bytes of device workspace lava_decode_attention needs.  Returns 0 for invalid arguments. */
 size_t lava_decode_workspace_bytes(const lava_layer_desc* desc, int32_t batch, int64_t rows_capacity,

@@ -324,17 +324,19 @@ def layer_evict(q_win, k, v, window: int, budget: int, pool_kernel: int = 7, sca
 
 
 # ------------------------------------------------------------------ Algorithm 2, literally
-def cascade(layer_scores, n: int, total_budget: int, window: int):
+def cascade(layer_scores, n: int, total_budget: int, window: int, entropies=None):
     """Run Algorithm 2 on precomputed per-layer flat score arrays [H_kv, N] (window = +inf):
     after layer l arrives every layer <= l is re-evicted from what it still retains, with the
     budget e_l / sum(e so far) * total.  Returns per layer (head_offsets, kept positions,
-    retained scores) and the list of budget vectors used at each step."""
+    retained scores) and the list of budget vectors used at each step.  `entropies`, if given,
+    replaces the statistics computed here (so that a caller can allocate from the exact values
+    another implementation saw); the algorithm is unchanged."""
     L = len(layer_scores)
     Hkv = layer_scores[0].shape[0]
     lo, hi = Hkv * window, Hkv * n
     ent, state, history = [], [], []
     for l in range(L):
-        ent.append(layer_entropy(layer_scores[l][:, : n - window]))
+        ent.append(layer_entropy(layer_scores[l][:, : n - window]) if entropies is None else float(entropies[l]))
         offs = np.array([g * n for g in range(Hkv + 1)], dtype=np.int64)
         pos = np.concatenate([np.arange(n, dtype=np.int64)] * Hkv)
         state.append((offs, pos, layer_scores[l].ravel().copy()))

@@ -101,9 +101,11 @@ int32_t launch_select(int n_heads, const float* scores, const int64_t* seg_offse
 
 int32_t select_error_flag(const void* ws, int64_t total, hipStream_t s, int* flag);
 
-int32_t launch_compact(const lava_layer_desc& d, int64_t n, const void* k, const void* v,
-                       const int64_t* head_offsets, const int32_t* kept_idx, int64_t capacity,
-                       void* k_out, void* v_out, hipStream_t s);
+// src_offsets null: dense source [H_kv][n]; otherwise a packed source inside a pool of n rows.
+int32_t launch_compact(const lava_layer_desc& d, int64_t n, const int64_t* src_offsets, const void* k,
+                       const void* v, const int32_t* pos_src, const int64_t* head_offsets,
+                       const int32_t* kept_idx, int64_t capacity, void* k_out, void* v_out, int32_t* pos_out,
+                       hipStream_t s);
 
 // ---------------------------------------------------------------- decode attention
 struct DecodePlan {
@@ -126,5 +128,8 @@ int32_t budgets_host(int32_t batch, int32_t n_layers, const float* e, const int6
                      const int64_t* lo, const int64_t* hi, int64_t* out);
 int32_t launch_budgets(int32_t batch, int32_t n_layers, const float* e, const int64_t* total,
                        const int64_t* lo, const int64_t* hi, int64_t* out, hipStream_t s);
+// one sequence, the same bounds for every layer, all scalars passed by value
+int32_t launch_budgets_uniform_bounds(int32_t n_layers, const float* e, int64_t total, int64_t lo, int64_t hi,
+                                      int64_t* out, hipStream_t s);
 
 }  // namespace lava

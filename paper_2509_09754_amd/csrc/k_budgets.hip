@@ -145,6 +145,30 @@ __global__ void __launch_bounds__(64) budgets_kernel(int n_layers, const float* 
     for (int i = 0; i < n_layers; ++i) out_b[i] = -1;
 }
 
+__global__ void __launch_bounds__(64) budgets_uniform_kernel(int n_layers, const float* __restrict__ e,
+                                                             long long total, long long lo, long long hi,
+                                                             int64_t* __restrict__ out) {
+  __shared__ double quota[kMaxLayers];
+  __shared__ double frac[kMaxLayers];
+  __shared__ long long base[kMaxLayers], lo_l[kMaxLayers], hi_l[kMaxLayers];
+  __shared__ int freel[kMaxLayers];
+  if (threadIdx.x != 0) return;
+  for (int i = 0; i < n_layers; ++i) { lo_l[i] = lo; hi_l[i] = hi; }
+  long long* out_b = reinterpret_cast<long long*>(out);
+  const int bad = allocate_budgets(n_layers, e, total, lo_l, hi_l, out_b, quota, base, freel, frac);
+  if (bad)
+    for (int i = 0; i < n_layers; ++i) out_b[i] = -1;
+}
+
+int32_t launch_budgets_uniform_bounds(int32_t n_layers, const float* e, int64_t total, int64_t lo, int64_t hi,
+                                      int64_t* out, hipStream_t s) {
+  if (n_layers > kMaxLayers) return LAVA_ERR_SHAPE;
+  ProfScope ps(KID_BUDGETS, s);
+  hipLaunchKernelGGL(budgets_uniform_kernel, dim3(1), dim3(64), 0, s, n_layers, e, (long long)total,
+                     (long long)lo, (long long)hi, out);
+  return launch_status();
+}
+
 int32_t launch_budgets(int32_t batch, int32_t n_layers, const float* e, const int64_t* total,
                        const int64_t* lo, const int64_t* hi, int64_t* out, hipStream_t s) {
   if (n_layers > kMaxLayers) return LAVA_ERR_SHAPE;

@@ -354,6 +354,17 @@ sel_init_kernel(unsigned int* __restrict__ hist, SelectState* __restrict__ st,
   }
 }
 
+// With explicit segments the number of entries is whatever the last offset says (read on the
+// device, so that a caller can chain selections without a host round trip); the host value is then
+// an upper bound that sized the grid and the workspace.
+__device__ __forceinline__ long long device_total(long long bound, const int64_t* __restrict__ seg_offsets,
+                                                  int n_heads) {
+  if (seg_offsets == nullptr) return bound;
+  long long t = (long long)seg_offsets[n_heads];
+  t = t < 0 ? 0 : t;
+  return t < bound ? t : bound;
+}
+
 // The whole selection in one launch.
 __global__ void __launch_bounds__(kSelThreads)
 sel_fused_kernel(const float* __restrict__ scores, long long total, int n_heads,
@@ -364,6 +375,7 @@ sel_fused_kernel(const float* __restrict__ scores, long long total, int n_heads,
                  int32_t* __restrict__ kept_idx, float* __restrict__ kept_scores) {
   __shared__ SelShared sh;
   const unsigned int nb = gridDim.x;
+  total = device_total(total, seg_offsets, n_heads);
   float val[kSelPerThread];
   load_chunk(scores, total, sh, val);
   Pick pk;
@@ -403,6 +415,7 @@ sel_step_kernel(const float* __restrict__ scores, long long total, int n_heads,
   __shared__ SelShared sh;
   {
     const int nb = (int)gridDim.x;
+    total = device_total(total, seg_offsets, n_heads);
     float val[kSelPerThread];
     load_chunk(scores, total, sh, val);
     Pick pk;

@@ -218,8 +218,89 @@ int32_t lava_compact_kv(const lava_layer_desc* desc, int64_t n, const void* k, c
   if (!aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out))
     return LAVA_ERR_INVALID_ARG;
   if (capacity > (int64_t)desc->n_kv_heads * n) return LAVA_ERR_BUDGET;
-  return launch_compact(*desc, n, k, v, head_offsets, kept_idx, capacity, k_out, v_out,
-                        static_cast<hipStream_t>(hip_stream));
+  return launch_compact(*desc, n, nullptr, k, v, nullptr, head_offsets, kept_idx, capacity, k_out, v_out,
+                        nullptr, static_cast<hipStream_t>(hip_stream));
+}
+
+int32_t lava_compact_packed(const lava_layer_desc* desc, const int64_t* src_offsets, int64_t src_rows,
+                            const void* k_src, const void* v_src, const int32_t* pos_src,
+                            const int64_t* head_offsets, const int32_t* kept_idx, int64_t capacity,
+                            void* k_out, void* v_out, int32_t* pos_out, void* hip_stream) {
+  int32_t st = check_desc(desc);
+  if (st != LAVA_OK) return st;
+  if (src_offsets == nullptr || k_src == nullptr || v_src == nullptr || head_offsets == nullptr ||
+      kept_idx == nullptr || k_out == nullptr || v_out == nullptr || src_rows < 1 || capacity < 0)
+    return LAVA_ERR_INVALID_ARG;
+  if (!aligned16(k_src) || !aligned16(v_src) || !aligned16(k_out) || !aligned16(v_out)) return LAVA_ERR_INVALID_ARG;
+  if (capacity > src_rows) return LAVA_ERR_BUDGET;
+  return launch_compact(*desc, src_rows, src_offsets, k_src, v_src, pos_src, head_offsets, kept_idx, capacity,
+                        k_out, v_out, pos_out, static_cast<hipStream_t>(hip_stream));
+}
+
+size_t lava_cascade_workspace_bytes(const lava_layer_desc* desc, int64_t n) {
+  if (check_desc(desc) != LAVA_OK || n <= desc->window) return 0;
+  const int64_t total = (int64_t)desc->n_kv_heads * n;
+  if (total >= (int64_t)1 << 31) return 0;
+  return make_select_workspace(total).bytes;
+}
+
+int32_t lava_cascade_step(const lava_layer_desc* desc, int32_t layer, int64_t n, const void* k_new,
+                          const void* v_new, const float* scores_new, const float* e,
+                          int64_t total_budget, lava_cascade_layer* layers, int64_t* budgets,
+                          void* workspace, size_t workspace_bytes, void* hip_stream) {
+  int32_t st = check_desc(desc);
+  if (st != LAVA_OK) return st;
+  if (layer < 0 || k_new == nullptr || v_new == nullptr || scores_new == nullptr || e == nullptr ||
+      layers == nullptr || budgets == nullptr)
+    return LAVA_ERR_INVALID_ARG;
+  if (n <= desc->window || layer >= 1024) return LAVA_ERR_SHAPE;
+  const int64_t dense = (int64_t)desc->n_kv_heads * n;
+  if (dense >= (int64_t)1 << 31) return LAVA_ERR_SHAPE;
+  const int64_t lo = (int64_t)desc->n_kv_heads * desc->window;
+  if (total_budget < lo * (layer + 1) || total_budget > dense * (layer + 1)) return LAVA_ERR_BUDGET;
+  if (!aligned16(k_new) || !aligned16(v_new)) return LAVA_ERR_INVALID_ARG;
+  const int64_t first_cap = total_budget < dense ? total_budget : dense;
+  for (int t = 0; t <= layer; ++t) {
+    const lava_cascade_layer& L = layers[t];
+    for (int i = 0; i < 2; ++i)
+      if (L.k[i] == nullptr || L.v[i] == nullptr || L.pos[i] == nullptr || L.scores[i] == nullptr ||
+          L.head_offsets[i] == nullptr || !aligned16(L.k[i]) || !aligned16(L.v[i]))
+        return LAVA_ERR_INVALID_ARG;
+    if (L.head_counts == nullptr || L.kept_idx == nullptr || (L.cur != 0 && L.cur != 1)) return LAVA_ERR_INVALID_ARG;
+    if (L.capacity < first_cap || L.capacity >= (int64_t)1 << 31) return LAVA_ERR_BUDGET;
+  }
+  if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 ||
+      workspace_bytes < make_select_workspace(dense).bytes)
+    return LAVA_ERR_WORKSPACE;
+  hipStream_t s = static_cast<hipStream_t>(hip_stream);
+
+  st = launch_budgets_uniform_bounds(layer + 1, e, total_budget, lo, dense, budgets, s);
+  if (st != LAVA_OK) return st;
+
+  // the new layer: dense scores, equal segments; its state starts in pool 0
+  {
+    lava_cascade_layer& L = layers[layer];
+    st = launch_select(desc->n_kv_heads, scores_new, nullptr, dense, first_cap, budgets + layer, L.head_counts,
+                       L.head_offsets[0], L.kept_idx, L.scores[0], workspace, s);
+    if (st != LAVA_OK) return st;
+    st = launch_compact(*desc, n, nullptr, k_new, v_new, nullptr, L.head_offsets[0], L.kept_idx, first_cap,
+                        L.k[0], L.v[0], L.pos[0], s);
+    if (st != LAVA_OK) return st;
+    L.cur = 0;
+  }
+  // every earlier layer again, from what it still holds (the workspace is reused: same stream)
+  for (int t = 0; t < layer; ++t) {
+    lava_cascade_layer& L = layers[t];
+    const int a = L.cur, b = 1 - L.cur;
+    st = launch_select(desc->n_kv_heads, L.scores[a], L.head_offsets[a], L.capacity, L.capacity, budgets + t,
+                       L.head_counts, L.head_offsets[b], L.kept_idx, L.scores[b], workspace, s);
+    if (st != LAVA_OK) return st;
+    st = launch_compact(*desc, L.capacity, L.head_offsets[a], L.k[a], L.v[a], L.pos[a], L.head_offsets[b],
+                        L.kept_idx, L.capacity, L.k[b], L.v[b], L.pos[b], s);
+    if (st != LAVA_OK) return st;
+    L.cur = b;
+  }
+  return LAVA_OK;
 }
 
 // Descriptor checks for the decode step: window and pool_kernel play no role there.

@@ -22,7 +22,8 @@ LAVA_F32, LAVA_BF16 = 0, 1
 EXPORTS = [
     "lava_status_string", "lava_window_scores_workspace_bytes", "lava_window_scores",
     "lava_layer_budgets", "lava_select_workspace_bytes", "lava_select_topk", "lava_select_status",
-    "lava_compact_kv", "lava_decode_workspace_bytes", "lava_decode_attention",
+    "lava_compact_kv", "lava_compact_packed", "lava_cascade_workspace_bytes", "lava_cascade_step",
+    "lava_decode_workspace_bytes", "lava_decode_attention",
     "lava_prof_kernel_count", "lava_prof_kernel_name", "lava_prof_enable", "lava_prof_reset",
     "lava_prof_read", "lava_probe_stream",
 ]
@@ -76,6 +77,12 @@ def _load() -> ctypes.CDLL:
     lib.lava_select_status.argtypes = [vp, i64, vp]
     lib.lava_compact_kv.restype = i32
     lib.lava_compact_kv.argtypes = [dp, i64, vp, vp, vp, vp, i64, vp, vp, vp]
+    lib.lava_compact_packed.restype = i32
+    lib.lava_compact_packed.argtypes = [dp, vp, i64, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp]
+    lib.lava_cascade_workspace_bytes.restype = sz
+    lib.lava_cascade_workspace_bytes.argtypes = [dp, i64]
+    lib.lava_cascade_step.restype = i32
+    lib.lava_cascade_step.argtypes = [dp, i32, i64, vp, vp, vp, vp, i64, vp, vp, vp, sz, vp]
     lib.lava_decode_workspace_bytes.restype = sz
     lib.lava_decode_workspace_bytes.argtypes = [dp, i32, i64, i64]
     lib.lava_decode_attention.restype = i32
@@ -253,6 +260,94 @@ def lava_compact_kv(desc: LayerDesc, n: int, k: torch.Tensor, v: torch.Tensor, h
                              int(capacity), _ptr(k_out), _ptr(v_out), _stream(stream))
     _check(st, "lava_compact_kv")
     return k_out, v_out
+
+
+def lava_compact_packed(desc: LayerDesc, src_offsets: torch.Tensor, k_src: torch.Tensor, v_src: torch.Tensor,
+                        head_offsets: torch.Tensor, kept_idx: torch.Tensor, capacity: int, pos_src=None,
+                        k_out=None, v_out=None, pos_out=None, stream=None):
+    """Gather from an already packed cache (re-eviction).  Returns (k_out, v_out, pos_out)."""
+    _dev(k_src, "k_src", desc.torch_dtype), _dev(v_src, "v_src", desc.torch_dtype)
+    _dev(src_offsets, "src_offsets", torch.int64), _dev(head_offsets, "head_offsets", torch.int64)
+    _dev(kept_idx, "kept_idx", torch.int32)
+    if pos_src is not None:
+        _dev(pos_src, "pos_src", torch.int32)
+    rows = max(int(capacity), 1)
+    if k_out is None:
+        k_out = torch.empty(rows, desc.head_dim, dtype=desc.torch_dtype, device=k_src.device)
+    if v_out is None:
+        v_out = torch.empty(rows, desc.head_dim, dtype=desc.torch_dtype, device=k_src.device)
+    if pos_out is None:
+        pos_out = torch.empty(rows, dtype=torch.int32, device=k_src.device)
+    st = lib.lava_compact_packed(ctypes.byref(desc), _ptr(src_offsets), k_src.shape[0], _ptr(k_src), _ptr(v_src),
+                                 _ptr(pos_src), _ptr(head_offsets), _ptr(kept_idx), int(capacity), _ptr(k_out),
+                                 _ptr(v_out), _ptr(pos_out), _stream(stream))
+    _check(st, "lava_compact_packed")
+    return k_out, v_out, pos_out
+
+
+class CascadeLayer(ctypes.Structure):
+    """Mirror of lava_cascade_layer."""
+    _fields_ = [
+        ("k", ctypes.c_void_p * 2), ("v", ctypes.c_void_p * 2), ("pos", ctypes.c_void_p * 2),
+        ("scores", ctypes.c_void_p * 2), ("head_offsets", ctypes.c_void_p * 2),
+        ("head_counts", ctypes.c_void_p), ("kept_idx", ctypes.c_void_p),
+        ("capacity", ctypes.c_int64), ("cur", ctypes.c_int32), ("reserved", ctypes.c_int32),
+    ]
+
+
+class CascadeState:
+    """Device buffers of a stack of layers for lava_cascade_step (allocation and views only)."""
+
+    def __init__(self, desc: LayerDesc, n_layers: int, capacity: int, device="cuda"):
+        self.desc, self.n_layers, self.capacity = desc, n_layers, int(capacity)
+        self.layers = (CascadeLayer * n_layers)()
+        self.tensors = []
+        for t in range(n_layers):
+            bufs = {}
+            for i in range(2):
+                bufs[f"k{i}"] = torch.empty(capacity, desc.head_dim, dtype=desc.torch_dtype, device=device)
+                bufs[f"v{i}"] = torch.empty(capacity, desc.head_dim, dtype=desc.torch_dtype, device=device)
+                bufs[f"pos{i}"] = torch.empty(capacity, dtype=torch.int32, device=device)
+                bufs[f"scores{i}"] = torch.empty(capacity, dtype=torch.float32, device=device)
+                bufs[f"offs{i}"] = torch.zeros(desc.n_kv_heads + 1, dtype=torch.int64, device=device)
+                self.layers[t].k[i] = bufs[f"k{i}"].data_ptr()
+                self.layers[t].v[i] = bufs[f"v{i}"].data_ptr()
+                self.layers[t].pos[i] = bufs[f"pos{i}"].data_ptr()
+                self.layers[t].scores[i] = bufs[f"scores{i}"].data_ptr()
+                self.layers[t].head_offsets[i] = bufs[f"offs{i}"].data_ptr()
+            bufs["counts"] = torch.zeros(desc.n_kv_heads, dtype=torch.int32, device=device)
+            bufs["idx"] = torch.empty(capacity, dtype=torch.int32, device=device)
+            self.layers[t].head_counts = bufs["counts"].data_ptr()
+            self.layers[t].kept_idx = bufs["idx"].data_ptr()
+            self.layers[t].capacity = capacity
+            self.layers[t].cur = 0
+            self.tensors.append(bufs)
+        self.e = torch.zeros(n_layers, dtype=torch.float32, device=device)
+        self.budgets = torch.zeros(n_layers, dtype=torch.int64, device=device)
+
+    def current(self, t: int) -> dict:
+        """Views of layer t's current state."""
+        c, b = self.layers[t].cur, self.tensors[t]
+        return dict(k_hat=b[f"k{c}"], v_hat=b[f"v{c}"], pos=b[f"pos{c}"], scores=b[f"scores{c}"],
+                    head_offsets=b[f"offs{c}"], head_counts=b["counts"])
+
+
+def lava_cascade_workspace_bytes(desc: LayerDesc, n: int) -> int:
+    return int(lib.lava_cascade_workspace_bytes(ctypes.byref(desc), int(n)))
+
+
+def lava_cascade_step(desc: LayerDesc, layer: int, n: int, k_new: torch.Tensor, v_new: torch.Tensor,
+                      scores_new: torch.Tensor, state: CascadeState, total_budget: int, workspace=None, stream=None):
+    """Alg. 2, one outer iteration; state.e[: layer + 1] must hold the layers' statistics."""
+    _dev(k_new, "k_new", desc.torch_dtype), _dev(v_new, "v_new", desc.torch_dtype)
+    _dev(scores_new, "scores_new", torch.float32)
+    if workspace is None:
+        workspace = torch.empty(max(lava_cascade_workspace_bytes(desc, n), 256), dtype=torch.uint8, device=k_new.device)
+    st = lib.lava_cascade_step(ctypes.byref(desc), int(layer), int(n), _ptr(k_new), _ptr(v_new), _ptr(scores_new),
+                               _ptr(state.e), int(total_budget), ctypes.cast(state.layers, ctypes.c_void_p),
+                               _ptr(state.budgets), _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(st, "lava_cascade_step")
+    return workspace
 
 
 def lava_decode_workspace_bytes(desc: LayerDesc, batch: int, rows_capacity: int, tail_len: int = 0) -> int:

@@ -172,3 +172,37 @@ def test_decode_argument_errors():
     for cap in range(0, 200000, 777):        # enough for every smaller capacity of the same batch
         b = lava.lava_decode_workspace_bytes(d, 4, cap, 0)
         assert b % 256 == 0 and b > 0
+
+
+def test_cascade_and_packed_compaction_argument_errors():
+    L = lava.lib
+    d = _desc()
+    cp = lambda src=FAKE, rows=1000, cap=10, k=FAKE: L.lava_compact_packed(
+        ctypes.byref(d), src, rows, k, FAKE, None, FAKE, FAKE, cap, FAKE, FAKE, None, None)
+    assert cp(src=None) == lava.LAVA_ERR_INVALID_ARG
+    assert cp(k=None) == lava.LAVA_ERR_INVALID_ARG
+    assert cp(rows=0) == lava.LAVA_ERR_INVALID_ARG
+    assert cp(cap=1001) == lava.LAVA_ERR_BUDGET
+    assert cp(cap=0) == lava.LAVA_OK                              # nothing to move, nothing launched
+
+    layer = lava.CascadeLayer()
+    for i in range(2):
+        layer.k[i] = layer.v[i] = layer.pos[i] = layer.scores[i] = layer.head_offsets[i] = 0x10000
+    layer.head_counts = layer.kept_idx = 0x10000
+    layer.capacity, layer.cur = 8192, 0
+    n = 4096
+    step = lambda lay=layer, layer_idx=0, total=8192, ws=FAKE, wsb=1 << 40, nn=n: L.lava_cascade_step(
+        ctypes.byref(d), layer_idx, nn, FAKE, FAKE, FAKE, FAKE, total, ctypes.byref(lay), FAKE, ws, wsb, None)
+    assert step(total=8 * 32 - 1) == lava.LAVA_ERR_BUDGET         # below H_kv * w per layer
+    assert step(total=8 * n + 1) == lava.LAVA_ERR_BUDGET          # more than the layers seen so far hold
+    assert step(nn=32) == lava.LAVA_ERR_SHAPE
+    assert step(ws=None) == lava.LAVA_ERR_WORKSPACE
+    assert step(wsb=16) == lava.LAVA_ERR_WORKSPACE
+    small = lava.CascadeLayer.from_buffer_copy(layer)
+    small.capacity = 100
+    assert step(lay=small) == lava.LAVA_ERR_BUDGET                # pools smaller than the first budget
+    broken = lava.CascadeLayer.from_buffer_copy(layer)
+    broken.pos[1] = None
+    assert step(lay=broken) == lava.LAVA_ERR_INVALID_ARG
+    assert lava.lava_cascade_workspace_bytes(d, n) == lava.lava_select_workspace_bytes(8 * n)
+    assert lava.lava_cascade_workspace_bytes(d, 16) == 0
