@@ -43,7 +43,45 @@ def parse():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode-attention leg")
+    ap.add_argument("--no-cascade", action="store_true", help="skip the Algorithm-2 cascade leg")
     return ap.parse_args()
+
+
+def cascade_leg(lava, torch, np, sh, desc, dev, sets, scores, args):
+    """Algorithm 2's outer loop for a stack of layers: after each layer arrives, device budgets plus one
+    (re-)eviction per layer seen so far.  Timing only: every layer reuses the benchmark layer's K, V and
+    scores (the selection and the copies do the same work whatever the values are), the statistics are
+    drawn at random so the budgets differ per layer.  Parity of the driver is a test, not this leg."""
+    n_layers = 8
+    per_layer = sh.budget
+    total = n_layers * per_layer
+    cap = min(total, sh.n_kv_heads * sh.n)
+    state = lava.CascadeState(desc, n_layers, cap, device=dev)
+    rng = np.random.Generator(np.random.PCG64(args.seed + 5))
+    state.e.copy_(torch.from_numpy((1e-6 * (0.5 + rng.random(n_layers))).astype(np.float32)))
+    ws = torch.empty(lava.lava_cascade_workspace_bytes(desc, sh.n), dtype=torch.uint8, device=dev)
+    _, k, v = sets[0]
+
+    def run():
+        for t in range(n_layers):
+            state.layers[t].cur = 0
+        times = []
+        for l in range(n_layers):
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record()
+            lava.lava_cascade_step(desc, l, sh.n, k, v, scores, state, total, workspace=ws)
+            b.record()
+            times.append((a, b))
+        torch.cuda.synchronize()
+        return [1e3 * a.elapsed_time(b) for a, b in times]
+
+    run()
+    reps = [run() for _ in range(5)]
+    best = [min(r[l] for r in reps) for l in range(n_layers)]
+    budgets = state.budgets.cpu().numpy().tolist()
+    return {"note": "Alg. 2 outer loop, one step per arriving layer: budgets + one (re-)eviction per layer so far",
+            "layers": n_layers, "total_budget": total, "us_per_step": [round(x, 1) for x in best],
+            "us_all_steps": round(sum(best), 1), "final_budgets": budgets}
 
 
 def decode_leg(lava, synth, torch, np, sh, desc, dev, sets, k_hat, v_hat, offs, B, args):
@@ -289,6 +327,9 @@ def main():
 
     if not args.no_decode:
         out["decode"] = decode_leg(lava, synth, torch, np, sh, desc, dev, sets, k_hat, v_hat, offs, B, args)
+
+    if not args.no_cascade:
+        out["cascade"] = cascade_leg(lava, torch, np, sh, desc, dev, sets, scores, args)
 
     if not args.no_check or not args.no_cpu_baseline:
         from oracle import lava_oracle as O

@@ -48,6 +48,14 @@ typedef enum {
 
 typedef enum { LAVA_F32 = 0, LAVA_BF16 = 1 } lava_dtype;
 
+/* Which score lava_window_scores writes.
+ *   LAVA_SCORE_LAVA       window-mean attention times max_k ||V[k]||_1 (Def. 1 / Eq. 3)
+ *   LAVA_SCORE_ATTENTION  window-mean attention alone: the value factor is 1 and V is not read
+ *                         (the recent-window attention score of the SnapKV / Ada-KV rows of
+ *                         Table 4, and the paper's ablation without the value norm); vbar = 1
+ * Group-max, pooling and the layer statistic are the same for both. */
+typedef enum { LAVA_SCORE_LAVA = 0, LAVA_SCORE_ATTENTION = 1 } lava_score_kind;
+
 /* One layer of one model.  Plain data, read during the call only. */
 typedef struct lava_layer_desc {
   int32_t n_q_heads;    /* H                                                                  */
@@ -57,6 +65,7 @@ typedef struct lava_layer_desc {
   int32_t pool_kernel;  /* odd, 1..15; the paper uses 7 (Sec. 5.1); 1 disables pooling        */
   int32_t dtype;        /* lava_dtype of q_win, k, v, k_out, v_out                            */
   float softmax_scale;  /* logits are scale * <q, k>; 0 selects 1 / sqrt(d_h) (Sec. 2)        */
+  int32_t score_kind;   /* lava_score_kind; 0 = the LAVa score                                */
 } lava_layer_desc;
 
 const char* lava_status_string(int32_t status);

@@ -74,6 +74,9 @@ int pool_blocks(const lava_layer_desc& d, int64_t n);
 
 int32_t launch_vnorm(const lava_layer_desc& d, int64_t n, const void* v, float* vnorm_part,
                      uint32_t* counters, const SweepPlan& p, hipStream_t s);
+// value factor 1 for every head (scores without the value norm): fills the partials, clears the counters
+int32_t launch_unit_vnorm(const lava_layer_desc& d, float* vnorm_part, uint32_t* counters, const SweepPlan& p,
+                          hipStream_t s);
 int32_t launch_stats(const lava_layer_desc& d, int64_t n, const void* q_win, const void* k,
                      float2* stat_part, const SweepPlan& p, hipStream_t s);
 int32_t launch_scores(const lava_layer_desc& d, int64_t n, const void* q_win, const void* k,

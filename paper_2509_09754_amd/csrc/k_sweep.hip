@@ -706,6 +706,23 @@ int32_t launch_vnorm(const lava_layer_desc& d, int64_t n, const void* v, float* 
   return launch_status();
 }
 
+__global__ void __launch_bounds__(256) unit_vnorm_kernel(float* __restrict__ vnorm_part, int n_part,
+                                                         uint32_t* __restrict__ counters, int n_counter_words) {
+  const int i = blockIdx.x * 256 + threadIdx.x;
+  if (i < n_part) vnorm_part[i] = 1.0f;
+  if (i < n_counter_words) counters[i] = 0u;
+}
+
+int32_t launch_unit_vnorm(const lava_layer_desc& d, float* vnorm_part, uint32_t* counters, const SweepPlan& p,
+                          hipStream_t s) {
+  const int n_part = d.n_kv_heads * p.vnorm_blocks;
+  const int n = n_part > kArriveWords ? n_part : kArriveWords;
+  ProfScope ps(KID_VNORM, s);
+  hipLaunchKernelGGL(unit_vnorm_kernel, dim3((n + 255) / 256), dim3(256), 0, s, vnorm_part, n_part, counters,
+                     kArriveWords);
+  return launch_status();
+}
+
 static float exp2_scale(const lava_layer_desc& d) {
   const float scale = d.softmax_scale > 0.0f ? d.softmax_scale : 1.0f / sqrtf((float)d.head_dim);
   return scale * kLog2e;

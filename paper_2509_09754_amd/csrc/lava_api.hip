@@ -63,6 +63,7 @@ static int32_t check_desc(const lava_layer_desc* d) {
   if (d->n_q_heads < 1 || d->n_kv_heads < 1 || d->window < 1 || d->pool_kernel < 1)
     return LAVA_ERR_INVALID_ARG;
   if (!(d->softmax_scale >= 0.0f) || d->softmax_scale > 1e30f) return LAVA_ERR_INVALID_ARG;
+  if (d->score_kind != LAVA_SCORE_LAVA && d->score_kind != LAVA_SCORE_ATTENTION) return LAVA_ERR_INVALID_ARG;
   if (d->n_q_heads % d->n_kv_heads != 0) return LAVA_ERR_SHAPE;
   if (d->n_q_heads / d->n_kv_heads > 8 || d->n_kv_heads > 64) return LAVA_ERR_SHAPE;
   if (d->head_dim != 64 && d->head_dim != 128) return LAVA_ERR_SHAPE;
@@ -143,7 +144,8 @@ int32_t lava_window_scores(const lava_layer_desc* desc, int32_t batch, const int
     double2* ent_part = reinterpret_cast<double2*>(ws + w.off_ent_part);
     uint32_t* counters = reinterpret_cast<uint32_t*>(ws + w.off_counter);
 
-    st = launch_vnorm(d, n, vb, vnorm_part, counters, plan, s);
+    st = d.score_kind == LAVA_SCORE_ATTENTION ? launch_unit_vnorm(d, vnorm_part, counters, plan, s)
+                                              : launch_vnorm(d, n, vb, vnorm_part, counters, plan, s);
     if (st != LAVA_OK) return st;
     if (lse_b == nullptr) {
       st = launch_stats(d, n, qb, kb, stat_part, plan, s);

@@ -18,6 +18,7 @@ LIB_PATH = os.path.join(_HERE, "liblava.so")
 
 LAVA_OK, LAVA_ERR_INVALID_ARG, LAVA_ERR_SHAPE, LAVA_ERR_BUDGET, LAVA_ERR_WORKSPACE, LAVA_ERR_HIP = range(6)
 LAVA_F32, LAVA_BF16 = 0, 1
+LAVA_SCORE_LAVA, LAVA_SCORE_ATTENTION = 0, 1
 
 EXPORTS = [
     "lava_status_string", "lava_window_scores_workspace_bytes", "lava_window_scores",
@@ -34,13 +35,14 @@ class LayerDesc(ctypes.Structure):
     _fields_ = [
         ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32), ("head_dim", ctypes.c_int32),
         ("window", ctypes.c_int32), ("pool_kernel", ctypes.c_int32), ("dtype", ctypes.c_int32),
-        ("softmax_scale", ctypes.c_float),
+        ("softmax_scale", ctypes.c_float), ("score_kind", ctypes.c_int32),
     ]
 
     @classmethod
-    def make(cls, n_q_heads, n_kv_heads, head_dim, window, dtype, pool_kernel=7, softmax_scale=0.0):
+    def make(cls, n_q_heads, n_kv_heads, head_dim, window, dtype, pool_kernel=7, softmax_scale=0.0,
+             score_kind=LAVA_SCORE_LAVA):
         code = {"f32": LAVA_F32, "bf16": LAVA_BF16, LAVA_F32: LAVA_F32, LAVA_BF16: LAVA_BF16}[dtype]
-        return cls(n_q_heads, n_kv_heads, head_dim, window, pool_kernel, code, softmax_scale)
+        return cls(n_q_heads, n_kv_heads, head_dim, window, pool_kernel, code, softmax_scale, score_kind)
 
     @property
     def torch_dtype(self):
