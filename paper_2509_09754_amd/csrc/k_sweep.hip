@@ -110,8 +110,6 @@ stats_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long 
   const int nh = (G - chunk * GT) < GT ? (G - chunk * GT) : GT;
   const char* kg = reinterpret_cast<const char*>(k) + (long long)g * n * T::kRowBytes;
 
-  u32x4 qf[GT][T::kSteps];
-  load_q<DT, D, GT>(q_win, h0, nh, w, lane, qf);
   TileDma<DT, D> dma;
   dma.init(lane);
   FragReader<DT, D> frags;
@@ -136,8 +134,11 @@ stats_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long 
 #pragma unroll
   for (int p = 0; p < kStages - 1; ++p)
     if (p < cnt) dma.issue(kg, first + (long long)p * kWaves, n, lane, ring + p * T::kTileChunks);
-  // the query rows (and the first tiles) are in before the loop: otherwise the compiler, which cannot
-  // count the ring's loads across iterations, waits for everything in flight before each tile's products
+  // The query rows are requested after the first tiles, so that the two latencies overlap, and both
+  // are in before the loop: otherwise the compiler, which cannot count the ring's loads across
+  // iterations, waits for everything in flight before each tile's products.
+  u32x4 qf[GT][T::kSteps];
+  load_q<DT, D, GT>(q_win, h0, nh, w, lane, qf);
   wait_vmcnt<0>();
   for (int it = 0; it < cnt; ++it) {
     const long long tile = first + (long long)it * kWaves;
@@ -299,6 +300,10 @@ scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long
   for (int p = 0; p < kStages - 1; ++p)
     if (p < cnt) dma.issue(kg, tile_at(p), n, lane, ring + p * T::kTileChunks);
 
+  // the query rows are requested before the normalisers are merged: the latencies overlap
+  u32x4 qf[GT][T::kSteps];
+  load_q<DT, D, GT>(q_win, h0, nh, w, lane, qf);
+
   // exponent bias of every (head, row): log2 of (row normaliser * w), +inf for padding rows.
   // Thread (row, slice) merges its slice of the workgroup partials in workgroup order, then the
   // slices are merged in slice order.
@@ -341,8 +346,6 @@ scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long
     s_bias[threadIdx.x] = bias;
   }
 
-  u32x4 qf[GT][T::kSteps];
-  load_q<DT, D, GT>(q_win, h0, nh, w, lane, qf);
   __syncthreads();
 
   const int half = lane >> 5;
