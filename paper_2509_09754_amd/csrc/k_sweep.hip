@@ -134,9 +134,11 @@ stats_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long 
 #pragma unroll
   for (int p = 0; p < kStages - 1; ++p)
     if (p < cnt) dma.issue(kg, first + (long long)p * kWaves, n, lane, ring + p * T::kTileChunks);
-  // The query rows are requested after the first tiles, so that the two latencies overlap, and both
-  // are in before the loop: otherwise the compiler, which cannot count the ring's loads across
-  // iterations, waits for everything in flight before each tile's products.
+  // Every wavefront fetches its own copy of the query rows, after its first tiles so that the two
+  // latencies overlap.  (Staging them once per workgroup through LDS, as the scores kernel does, was
+  // measured slower here: the wavefronts then leave the barrier in step and the sweep loses more
+  // than the set-up gains.)  Both are in before the loop: otherwise the compiler, which cannot count
+  // the ring's loads across iterations, waits for everything in flight before each tile's products.
   u32x4 qf[GT][T::kSteps];
   load_q<DT, D, GT>(q_win, h0, nh, w, lane, qf);
   wait_vmcnt<0>();
@@ -282,27 +284,38 @@ scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long
   const long long t_begin = (long long)blockIdx.x * tiles_per_block;
   long long t_end = t_begin + tiles_per_block;
   if (t_end > n_tiles) t_end = n_tiles;
-  const long long first = t_begin + wave;
-  const int cnt_own = first < t_end ? (int)((t_end - first + kWaves - 1) / kWaves) : 0;
-  // pooling halo: the last two wavefronts also take the tile before / after the workgroup's span
-  long long halo_tile = -1;
-  if constexpr (FUSED) {
-    if (t_begin < t_end) {
-      if (wave == kWaves - 1 && t_begin > 0) halo_tile = t_begin - 1;
-      if (wave == kWaves - 2 && t_end < n_tiles) halo_tile = t_end;
-    }
+  // Jobs of the workgroup: its own tiles, then (FUSED) the pooling halo, i.e. the tile before and the
+  // tile after the span.  The first kStages - 1 jobs of every wavefront are fixed; the rest are taken
+  // from a shared counter as wavefronts become free, because the wavefronts of a workgroup do not
+  // run at the same speed (two share each SIMD and the older one wins the arbitration).  Which
+  // wavefront computes a tile does not change its result, so the scores stay deterministic.
+  const int n_own = t_begin < t_end ? (int)(t_end - t_begin) : 0;
+  const bool halo_left = FUSED && n_own > 0 && t_begin > 0;
+  const bool halo_right = FUSED && n_own > 0 && t_end < n_tiles;
+  const int n_jobs = n_own + (halo_left ? 1 : 0) + (halo_right ? 1 : 0);
+  auto job_tile = [&](int j) -> long long {
+    if (j < n_own) return t_begin + j;
+    return (j == n_own && halo_left) ? t_begin - 1 : t_end;
+  };
+  __shared__ unsigned int s_next_job;
+  if (threadIdx.x == 0) s_next_job = kWaves * (kStages - 1);   // published by the barriers below
+  const unsigned int next_job_addr = lds_addr(&s_next_job);
+  int fifo[kStages];                                            // jobs requested and not yet computed; -1: none
+#pragma unroll
+  for (int p = 0; p < kStages; ++p) {
+    const int j = wave + p * kWaves;
+    fifo[p] = (p < kStages - 1 && j < n_jobs) ? j : -1;
   }
-  const int cnt = cnt_own + (halo_tile >= 0 ? 1 : 0);
-  auto tile_at = [&](int j) -> long long { return j < cnt_own ? first + (long long)j * kWaves : halo_tile; };
   u32x4* ring = s_tile[wave][0];
   const unsigned int ring_addr = lds_addr(ring);
 #pragma unroll
   for (int p = 0; p < kStages - 1; ++p)
-    if (p < cnt) dma.issue(kg, tile_at(p), n, lane, ring + p * T::kTileChunks);
+    if (fifo[p] >= 0) dma.issue(kg, job_tile(fifo[p]), n, lane, ring + p * T::kTileChunks);
 
-  // the query rows are requested before the normalisers are merged: the latencies overlap
-  u32x4 qf[GT][T::kSteps];
-  load_q<DT, D, GT>(q_win, h0, nh, w, lane, qf);
+  // the query rows go through the last stage of the first GT wavefronts' rings (idle until the loop
+  // starts); their loads are in flight together with the normaliser partials below
+  static_assert(kWaves >= GT, "one staging buffer per head");
+  stage_q<DT, D, GT, kThreads>(q_win, h0, nh, w, [&](int t) { return &s_tile[t][kStages - 1][0]; });
 
   // exponent bias of every (head, row): log2 of (row normaliser * w), +inf for padding rows.
   // Thread (row, slice) merges its slice of the workgroup partials in workgroup order, then the
@@ -345,7 +358,9 @@ scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long
     }
     s_bias[threadIdx.x] = bias;
   }
-
+  u32x4 qf[GT][T::kSteps];
+#pragma unroll
+  for (int t = 0; t < GT; ++t) frags.read(lds_addr(&s_tile[t][kStages - 1][0]), qf[t]);
   __syncthreads();
 
   const int half = lane >> 5;
@@ -368,12 +383,26 @@ scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long
       }
     }
   };
-  for (int it = 0; it < cnt; ++it) {
-    const long long tile = tile_at(it);
-    const int ahead = it + kStages - 1;
-    if (ahead < cnt) dma.issue(kg, tile_at(ahead), n, lane, ring + (ahead % kStages) * T::kTileChunks);
-    const int younger = cnt - 1 - it < kStages - 1 ? cnt - 1 - it : kStages - 1;
+  bool more = true;                                             // the counter has not run out yet
+  for (int it = 0; fifo[0] >= 0; ++it) {
+    const long long tile = job_tile(fifo[0]);
+    if (more) {
+      unsigned int j = 0;
+      if (lane == 0) j = lds_fetch_inc(next_job_addr);
+      j = __builtin_amdgcn_readfirstlane(j);
+      more = j < (unsigned int)n_jobs;
+      if (more) {
+        fifo[kStages - 1] = (int)j;
+        dma.issue(kg, job_tile((int)j), n, lane, ring + ((it + kStages - 1) % kStages) * T::kTileChunks);
+      }
+    }
+    int younger = 0;
+#pragma unroll
+    for (int p = 1; p < kStages; ++p) younger += fifo[p] >= 0 ? 1 : 0;
     wait_tile<DT, D>(younger);
+#pragma unroll
+    for (int p = 0; p + 1 < kStages; ++p) fifo[p] = fifo[p + 1];
+    fifo[kStages - 1] = -1;
     if constexpr (!FUSED) store_result(pend_key, pend);
     u32x4 kf[T::kSteps];
     frags.read(ring_addr + (it % kStages) * T::kTileBytes, kf);

@@ -249,6 +249,14 @@ __device__ __forceinline__ void lds_read128(unsigned int a, u32x4& o) {
   asm volatile("ds_read_b128 %0, %1\n\ts_waitcnt lgkmcnt(0)" : "=&v"(o) : "v"(a) : "memory");
 }
 
+// *a += 1 in LDS, returns the value before.  Call from ONE lane.
+__device__ __forceinline__ unsigned int lds_fetch_inc(unsigned int a) {
+  unsigned int v;
+  const unsigned int one = 1u;
+  asm volatile("ds_add_rtn_u32 %0, %1, %2\n\ts_waitcnt lgkmcnt(0)" : "=&v"(v) : "v"(a), "v"(one) : "memory");
+  return v;
+}
+
 __device__ __forceinline__ void lds_write32(unsigned int a, float x) {
   asm volatile("ds_write_b32 %0, %1" : : "v"(a), "v"(x) : "memory");
 }
@@ -291,7 +299,8 @@ struct FragReader {
   }
 };
 
-// Query fragments of the chunk's heads: row r = lane % 32 (zero beyond the window or the chunk).
+// Query fragments of the chunk's heads, one copy per wavefront straight from global memory:
+// row r = lane % 32 (zero beyond the window or the chunk).
 template <int DT, int D, int GT>
 __device__ __forceinline__ void load_q(const u32x4* __restrict__ qg, int h0, int nh, int w, int lane,
                                        u32x4 (&qf)[GT][Tile<DT, D>::kSteps]) {
@@ -305,6 +314,28 @@ __device__ __forceinline__ void load_q(const u32x4* __restrict__ qg, int h0, int
       if (t < nh && r < w) x = qg[((long long)(h0 + t) * w + r) * T::kCpr + 2 * j + half];
       qf[t][j] = x;
     }
+  }
+}
+
+// Query rows of the chunk's heads, copied once per workgroup into tile-shaped LDS buffers (one per
+// head: row r of head t at row r, 16-byte chunks swizzled like a key tile, zero beyond the window
+// or the chunk), from where every wavefront reads them as fragments with FragReader.  Letting each
+// wavefront fetch its own copy from global memory costs kWaves times the traffic on a handful of
+// cache lines that every workgroup of the grid wants at the same moment.
+// bufs(t) returns the buffer of head t.  The caller synchronises the workgroup afterwards.
+template <int DT, int D, int GT, int THREADS, class BUFS>
+__device__ __forceinline__ void stage_q(const u32x4* __restrict__ qg, int h0, int nh, int w, BUFS&& bufs) {
+  using T = Tile<DT, D>;
+  constexpr int kPerHead = kTileKeys * T::kCpr;
+  constexpr int kTotal = GT * kPerHead;
+#pragma unroll
+  for (int i = 0; i < (kTotal + THREADS - 1) / THREADS; ++i) {
+    const int c = i * THREADS + (int)threadIdx.x;
+    if (kTotal % THREADS != 0 && c >= kTotal) break;
+    const int t = c / kPerHead, rr = (c / T::kCpr) % kTileKeys, ch = c % T::kCpr;
+    u32x4 x = u32x4{0u, 0u, 0u, 0u};
+    if (t < nh && rr < w) x = qg[((long long)(h0 + t) * w + rr) * T::kCpr + ch];
+    bufs(t)[rr * T::kCpr + (ch ^ (rr & 7))] = x;
   }
 }
 
