@@ -44,6 +44,8 @@ def parse():
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode-attention leg")
     ap.add_argument("--no-cascade", action="store_true", help="skip the Algorithm-2 cascade leg")
+    ap.add_argument("--decode-only", action="store_true",
+                    help="run only the batched decode-attention case (for profiling that kernel) and print its object")
     return ap.parse_args()
 
 
@@ -123,7 +125,31 @@ def decode_leg(lava, synth, torch, np, sh, desc, dev, sets, k_hat, v_hat, offs, 
                                    out=out1, lse=lse1, workspace=ws_full)
     t_full = timed(full, iters)
 
-    # batch of compressed caches: `batch` sequences x B rows with skewed head budgets
+    out = {
+        "note": "one new token per sequence over the packed variable-length cache (Sec. 2 step on the retained entries)",
+        "evicted_layer_us": round(1e6 * t_small, 2), "evicted_rows": B,
+        "full_cache_us": round(1e6 * t_full, 2), "full_rows": full_rows,
+        "attention_speedup_from_eviction": round(t_full / t_small, 1),
+    }
+    out["batched"] = decode_batched(lava, synth, torch, np, sh, desc, dev, B, args, iters)
+    return out
+
+
+def decode_batched(lava, synth, torch, np, sh, desc, dev, B, args, iters):
+    """64 compressed caches of B rows each, skewed head budgets, rotating over >= 1 GiB of pools."""
+    esize = synth.itemsize(sh.dtype)
+    row_bytes = sh.head_dim * esize
+
+    def timed(fn, n):
+        for i in range(3):
+            fn(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(n):
+            fn(i)
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / n
+
     batch = 64
     n_pools = max(2, int(np.ceil(2**30 / (2 * batch * B * row_bytes))))
     di = synth.gen_decode(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.dtype, [B] * batch, args.seed)
@@ -148,16 +174,10 @@ def decode_leg(lava, synth, torch, np, sh, desc, dev, sets, k_hat, v_hat, offs, 
     lava.prof_enable(False)
     k_us = {n: 1e3 * prof[n][0] / max(prof[n][1], 1) for n in ("decode", "decode_merge")}
     bytes_b = 2 * batch * B * row_bytes
-    return {
-        "note": "one new token per sequence over the packed variable-length cache (Sec. 2 step on the retained entries)",
-        "evicted_layer_us": round(1e6 * t_small, 2), "evicted_rows": B,
-        "full_cache_us": round(1e6 * t_full, 2), "full_rows": full_rows,
-        "attention_speedup_from_eviction": round(t_full / t_small, 1),
-        "batched": {"batch": batch, "rows_per_seq": B, "us": round(1e6 * t_batch, 2), "pools": n_pools,
-                    "algorithmic_bytes": bytes_b, "kernel_us": {n: round(v, 2) for n, v in k_us.items()},
-                    "achieved_GBs": round(bytes_b / (k_us["decode"] * 1e-6) / 1e9, 1),
-                    "frac_of_hbm_peak": round(bytes_b / (k_us["decode"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)},
-    }
+    return {"batch": batch, "rows_per_seq": B, "us": round(1e6 * t_batch, 2), "pools": n_pools,
+            "algorithmic_bytes": bytes_b, "kernel_us": {n: round(v, 2) for n, v in k_us.items()},
+            "achieved_GBs": round(bytes_b / (k_us["decode"] * 1e-6) / 1e9, 1),
+            "frac_of_hbm_peak": round(bytes_b / (k_us["decode"] * 1e-6) / 1e9 / HBM_PEAK_GBS, 4)}
 
 
 def main():
@@ -181,8 +201,12 @@ def main():
     cfg_idx = {"cfg1": 1, "cfg2": 2, "cfg4": 4}[args.workload]
     sh = synth.config(cfg_idx)
     esize = synth.itemsize(sh.dtype)
-    inp = synth.gen_layer(sh, args.seed)
     desc = lava.LayerDesc.make(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.window, sh.dtype, pool_kernel=sh.pool_kernel)
+    if args.decode_only:
+        res = decode_batched(lava, synth, torch, np, sh, desc, dev, sh.budget, args, max(20, args.steps // 2))
+        print(json.dumps({"decode_only": res, "workload": args.workload}), flush=True)
+        return
+    inp = synth.gen_layer(sh, args.seed)
     kv_bytes = sh.n_kv_heads * sh.n * sh.head_dim * esize           # one of K or V
     n_sets = args.sets if args.sets > 0 else max(2, int(np.ceil(1.5 * 2**30 / (2 * kv_bytes))))
     n_sets = min(n_sets, 64)
