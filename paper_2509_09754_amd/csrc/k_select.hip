@@ -289,15 +289,21 @@ __device__ __forceinline__ void write_phase(const float (&val)[kSelPerThread], l
   }
   int g = 0;
   while (g + 1 < n_heads && sh.off[g + 1] < first) ++g;     // segment starts equal to `first` are crossed below
+  // most lanes never cross a segment start: the next start and this head's start stay in registers
+  constexpr long long kNever = 0x7fffffffffffffffll;
+  long long next_start = g + 1 < n_heads ? sh.off[g + 1] : kNever;
+  long long head_start = sh.off[g];
   unsigned int local_cnt = 0u;
 #pragma unroll
   for (int j = 0; j < kSelPerThread; ++j) {
     const long long p = first + j;
-    while (g + 1 < n_heads && p >= sh.off[g + 1]) {
+    while (p >= next_start) {
       if (local_cnt) atomicAdd(&sh.cnt[g], local_cnt);
       local_cnt = 0u;
       ++g;
-      if (p == sh.off[g] && p < total) head_offsets[g] = gt_before + (eq_before < need ? eq_before : need);
+      head_start = next_start;
+      if (p == head_start && p < total) head_offsets[g] = gt_before + (eq_before < need ? eq_before : need);
+      next_start = g + 1 < n_heads ? sh.off[g + 1] : kNever;
     }
     const bool is_gt = (gt_mask >> j) & 1u;
     const bool is_eq = (eq_mask >> j) & 1u;
@@ -305,7 +311,7 @@ __device__ __forceinline__ void write_phase(const float (&val)[kSelPerThread], l
       // survivors before this entry in flat order: all larger keys plus the threshold-equal ones taken
       const long long slot = gt_before + (eq_before < need ? eq_before : need);
       if (slot < capacity) {
-        kept_idx[slot] = (int32_t)(p - sh.off[g]);
+        kept_idx[slot] = (int32_t)(p - head_start);
         if (kept_scores) kept_scores[slot] = val[j];
       }
       ++local_cnt;
