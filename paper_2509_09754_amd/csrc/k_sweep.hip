@@ -233,6 +233,7 @@ stats_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long 
 // another launch), and finishes the scores itself: max-pool, value factor, +inf for the window
 // entries, and the layer statistic.  Otherwise the raw scores go to s_raw for poolstat_kernel.
 constexpr int kFusedTiles = 128;
+constexpr int kPoolMaxHalf = 7;   // pooling kernels up to 15
 
 struct PoolArgs {
   const float* vnorm_part;   // [H_kv][vnorm_blocks] value-norm partials
@@ -255,7 +256,7 @@ scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long
   constexpr int kStages = Shape<DT, D>::kStages;
   __shared__ u32x4 s_tile[kWaves][kStages][T::kTileChunks];
   __shared__ __attribute__((aligned(16))) float s_bias[GT * 32];
-  __shared__ float s_span[FUSED ? (kFusedTiles + 2) * kTileKeys : 1];   // raw scores of the span + halo tiles
+  __shared__ __attribute__((aligned(16))) float s_span[FUSED ? (kFusedTiles + 2) * kTileKeys : 4];   // raw scores of the span + halo tiles
 
   const int lane = threadIdx.x & 63, wave = wave_index();
   const int g = blockIdx.y / n_chunks, chunk = blockIdx.y % n_chunks;
@@ -455,17 +456,54 @@ scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long
     long long p_end = t_end * kTileKeys;
     if (p_end > n_prefix) p_end = n_prefix;
     const long long span0 = (t_begin - 1) * kTileKeys;      // position held by s_span[0]
+    // Eight consecutive positions per thread: 24 raw scores (positions base-8 .. base+15, six
+    // 128-bit reads) cover every tap of a pooling window of up to 15; positions outside the prefix
+    // do not take part in the maximum (the window is clipped, not padded).
     double acc_s = 0.0, acc_t = 0.0;
-    for (long long p = p_begin + threadIdx.x; p < p_end; p += Shape<DT, D>::kThreads) {
-      float m = s_span[(int)(p - span0)];
-      for (int dd = 1; dd <= pa.pool_half; ++dd) {
-        if (p - dd >= 0) m = fmaxf(m, s_span[(int)(p - dd - span0)]);
-        if (p + dd < n_prefix) m = fmaxf(m, s_span[(int)(p + dd - span0)]);
+    constexpr int kPer = 8;
+    static_assert(kPoolMaxHalf <= kPer - 1, "taps must stay inside the 24 values read");
+    const float* out_head = pa.scores + (long long)g * n;
+    for (long long base = p_begin + (long long)threadIdx.x * kPer; base < p_end;
+         base += (long long)Shape<DT, D>::kThreads * kPer) {
+      float raw[3 * kPer];
+      const float4* src = reinterpret_cast<const float4*>(&s_span[(int)(base - kPer - span0)]);
+#pragma unroll
+      for (int i = 0; i < 3 * kPer / 4; ++i) {
+        const float4 x = src[i];
+        raw[4 * i + 0] = x.x; raw[4 * i + 1] = x.y; raw[4 * i + 2] = x.z; raw[4 * i + 3] = x.w;
       }
-      const float sc = vb * m;
-      pa.scores[(long long)g * n + p] = sc;
-      acc_s += (double)sc;
-      if (sc > 0.0f) acc_t += (double)sc * (double)logf(sc);
+#pragma unroll
+      for (int i = 0; i < 3 * kPer; ++i) {
+        const long long pos = base - kPer + i;
+        if (pos < 0 || pos >= n_prefix) raw[i] = -INFINITY;
+      }
+      float sc[kPer];
+#pragma unroll
+      for (int j = 0; j < kPer; ++j) sc[j] = raw[kPer + j];
+#pragma unroll
+      for (int dd = 1; dd <= kPoolMaxHalf; ++dd) {
+        if (dd <= pa.pool_half) {                              // uniform
+#pragma unroll
+          for (int j = 0; j < kPer; ++j) sc[j] = fmaxf(sc[j], fmaxf(raw[kPer + j - dd], raw[kPer + j + dd]));
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < kPer; ++j) {
+        sc[j] *= vb;
+        if (base + j < p_end) {
+          acc_s += (double)sc[j];
+          if (sc[j] > 0.0f) acc_t += (double)sc[j] * (double)logf(sc[j]);
+        }
+      }
+      if (base + kPer <= p_end && (reinterpret_cast<uintptr_t>(out_head + base) & 15) == 0) {
+        float4* dst = reinterpret_cast<float4*>(const_cast<float*>(out_head) + base);
+        dst[0] = make_float4(sc[0], sc[1], sc[2], sc[3]);
+        dst[1] = make_float4(sc[4], sc[5], sc[6], sc[7]);
+      } else {
+#pragma unroll
+        for (int j = 0; j < kPer; ++j)
+          if (base + j < p_end) pa.scores[(long long)g * n + base + j] = sc[j];
+      }
     }
     // the workgroup that owns the head's last prefix tile also writes the window entries
     if (t_begin < t_end && t_end == n_tiles && threadIdx.x < (unsigned)w)
@@ -582,7 +620,6 @@ vnorm_kernel(const u32x4* __restrict__ v, long long n, int tiles_per_block, floa
 constexpr int kPoolThreads = 256;
 constexpr int kPoolPerThread = 8;
 constexpr int kPoolChunk = kPoolThreads * kPoolPerThread;
-constexpr int kPoolMaxHalf = 7;
 
 __global__ void __launch_bounds__(kPoolThreads)
 poolstat_kernel(const float* __restrict__ s_raw, long long n, int w, int pool_half,
