@@ -362,17 +362,22 @@ def main():
         except Exception:                                       # pragma: no cover
             threadpool_limits = None
         q, k, v = inp.f64()
-        t0 = time.perf_counter()
-        if threadpool_limits is not None:
-            with threadpool_limits(limits=1):
+        # the oracle on full layers of the workload until about ten seconds have gone by (at most 12 runs)
+        runs, cpu_s = 0, 0.0
+        while runs < 12 and (runs == 0 or cpu_s < 10.0):
+            t0 = time.perf_counter()
+            if threadpool_limits is not None:
+                with threadpool_limits(limits=1):
+                    ref = O.layer_evict(q, k, v, sh.window, B, sh.pool_kernel, k_store=inp.k, v_store=inp.v)
+            else:
                 ref = O.layer_evict(q, k, v, sh.window, B, sh.pool_kernel, k_store=inp.k, v_store=inp.v)
-        else:
-            ref = O.layer_evict(q, k, v, sh.window, B, sh.pool_kernel, k_store=inp.k, v_store=inp.v)
-        cpu_s = time.perf_counter() - t0
-        out["cpu_baseline"] = {"value": round(sh.n / cpu_s, 1), "unit": "tokens/s/layer",
+            cpu_s += time.perf_counter() - t0
+            runs += 1
+        out["cpu_baseline"] = {"value": round(runs * sh.n / cpu_s, 1), "unit": "tokens/s/layer",
                                "cores": 1 if threadpool_limits is not None else os.cpu_count(),
                                "kind": "oracle",
-                               "sample": f"one full layer of the workload (N={sh.n}), one run, {cpu_s:.2f} s",
+                               "sample": f"{runs} full layers of the workload (N={sh.n}) one after another, "
+                                         f"{cpu_s:.1f} s in all",
                                "host_cores_available": os.cpu_count()}
         # parity of the timed configuration against the oracle (outside the timed region)
         step(0)

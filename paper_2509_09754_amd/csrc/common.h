@@ -45,7 +45,6 @@ inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a
 
 // ---------------------------------------------------------------- sweep (K, V) kernels
 constexpr int kTileKeys = 32;        // keys per MFMA tile
-constexpr int kSweepThreads = 256;   // 4 wavefronts per workgroup
 constexpr int kMaxChunkHeads = 4;    // query heads a wavefront keeps in registers
 
 struct SweepPlan {

@@ -200,7 +200,7 @@ stats_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long 
     }
   }
 
-  // merge the two lane halves (same row, different keys), then the four wavefronts
+  // merge the two lane halves (same row, different keys), then the wavefronts
 #pragma unroll
   for (int t = 0; t < GT; ++t) {
     const float m2 = __shfl_xor(m_run[t], 32);
