@@ -73,15 +73,49 @@ int pool_blocks(const lava_layer_desc& d, int64_t n);
 
 int32_t launch_vnorm(const lava_layer_desc& d, int64_t n, const void* v, float* vnorm_part,
                      uint32_t* counters, const SweepPlan& p, hipStream_t s);
-// value factor 1 for every head (scores without the value norm): fills the partials, clears the counters
-int32_t launch_unit_vnorm(const lava_layer_desc& d, float* vnorm_part, uint32_t* counters, const SweepPlan& p,
-                          hipStream_t s);
-int32_t launch_stats(const lava_layer_desc& d, int64_t n, const void* q_win, const void* k,
-                     float2* stat_part, const SweepPlan& p, hipStream_t s);
-int32_t launch_scores(const lava_layer_desc& d, int64_t n, const void* q_win, const void* k,
-                      const float2* stat_part, const float* lse, float* s_raw, const float* vnorm_part,
-                      float* scores, float* vbar, float* layer_stat, double2* ent_part, uint32_t* counters,
-                      const SweepPlan& p, hipStream_t s);
+// Arguments of a sweep launch.  One launch covers up to kMaxSeqPerLaunch sequences of a batch
+// (blockIdx.z picks the sequence): the whole table travels in the kernel arguments, so nothing is
+// copied to the device and the call stays capturable.  Workgroups beyond a sequence's own count
+// (the grid is sized for the longest sequence) return at once.
+constexpr int kMaxSeqPerLaunch = 32;
+
+struct SweepSeq {
+  long long n;               // cached tokens of the sequence
+  long long tok;             // tokens of the batch before it (K, V and the scores are packed)
+  long long ws_off;          // byte offset of the sequence's region in the workspace
+  int blocks_x;              // stats / scores workgroups along the key axis
+  int tiles_per_block;
+  int vnorm_blocks;          // value-norm partials per KV head the scores kernel finds
+  int vnorm_tiles_per_block;
+};
+
+struct SweepArgs {
+  const void* q_win;         // [batch][H][w][d_h]
+  const void* k;             // packed, [H_kv][n][d_h] per sequence
+  const void* v;
+  const float* lse;          // [batch][H][w] or null
+  float* scores;             // packed, [H_kv][n] per sequence
+  float* vbar;               // [batch][H_kv]
+  float* layer_stat;         // [batch]
+  char* ws;
+  size_t off_stat_part, off_vnorm_part, off_sraw, off_ent_part, off_counter;   // inside a sequence's region
+  int H, H_kv, w, G, n_chunks, pool_half;
+  float c2;
+  int first_seq;             // index in the batch of s[0]
+  int n_seq;
+  SweepSeq s[kMaxSeqPerLaunch];
+};
+
+// grid.x of the launches below: the largest blocks_x / vnorm_blocks in the table
+int32_t launch_vnorm(const lava_layer_desc& d, const SweepArgs& a, int max_vnorm_blocks, hipStream_t s);
+// value factor 1 for every head (scores without the value norm): fills the partials, clears the tickets
+int32_t launch_unit_vnorm(const lava_layer_desc& d, const SweepArgs& a, int max_vnorm_blocks, hipStream_t s);
+int32_t launch_stats(const lava_layer_desc& d, const SweepArgs& a, int max_blocks_x, const SweepPlan& p,
+                     hipStream_t s);
+// not fused (a group split into chunks): one sequence per launch, raw scores to the region's s_raw
+int32_t launch_scores(const lava_layer_desc& d, const SweepArgs& a, int max_blocks_x, const SweepPlan& p,
+                      hipStream_t s);
+float sweep_exp2_scale(const lava_layer_desc& d);
 int32_t launch_poolstat(const lava_layer_desc& d, int64_t n, const float* s_raw,
                         const float* vnorm_part, int vnorm_blocks, float* scores, float* vbar,
                         float* layer_stat, double2* ent_part, uint32_t* counters, hipStream_t s);

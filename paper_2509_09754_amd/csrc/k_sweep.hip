@@ -96,9 +96,17 @@ __device__ __forceinline__ void entropy_finish(double acc_s, double acc_t, doubl
 // ------------------------------------------------------------------------------------------
 template <int DT, int D, int GT>
 __global__ void __launch_bounds__((Shape<DT, D>::kThreads))
-stats_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long long n, int w, int G,
-             int n_chunks, float c2, int tiles_per_block, float2* __restrict__ stat_part) {
+stats_kernel(const SweepArgs a) {
   using T = Tile<DT, D>;
+  const SweepSeq sq = a.s[blockIdx.z];
+  if (blockIdx.x >= (unsigned int)sq.blocks_x) return;
+  const long long n = sq.n;
+  const int w = a.w, G = a.G, n_chunks = a.n_chunks, tiles_per_block = sq.tiles_per_block;
+  const float c2 = a.c2;
+  const u32x4* __restrict__ q_win =
+      static_cast<const u32x4*>(a.q_win) + (long long)(a.first_seq + blockIdx.z) * a.H * w * T::kCpr;
+  const u32x4* __restrict__ k = static_cast<const u32x4*>(a.k) + (long long)a.H_kv * sq.tok * T::kCpr;
+  float2* __restrict__ stat_part = reinterpret_cast<float2*>(a.ws + sq.ws_off + a.off_stat_part);
   constexpr int kWaves = Shape<DT, D>::kWaves;
   constexpr int kStages = Shape<DT, D>::kStages;
   __shared__ u32x4 s_tile[kWaves][kStages][T::kTileChunks];
@@ -216,7 +224,7 @@ stats_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long 
       const float2 p = s_red[wv][threadIdx.x];
       merge_stat(m, z, p.x, p.y, c2);
     }
-    stat_part[((long long)blockIdx.y * gridDim.x + blockIdx.x) * (GT * 32) + threadIdx.x] = make_float2(m, z);
+    stat_part[((long long)blockIdx.y * sq.blocks_x + blockIdx.x) * (GT * 32) + threadIdx.x] = make_float2(m, z);
   }
 }
 
@@ -248,10 +256,30 @@ struct PoolArgs {
 
 template <int DT, int D, int GT, bool FUSED>
 __global__ void __launch_bounds__((Shape<DT, D>::kThreads))
-scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long long n, int w, int G,
-              int n_chunks, float c2, int tiles_per_block, const float2* __restrict__ stat_part,
-              int stat_blocks, const float* __restrict__ lse, float* __restrict__ s_raw, PoolArgs pa) {
+scores_kernel(const SweepArgs a) {
   using T = Tile<DT, D>;
+  const SweepSeq sq = a.s[blockIdx.z];
+  if (blockIdx.x >= (unsigned int)sq.blocks_x) return;
+  const int seq = a.first_seq + (int)blockIdx.z;
+  const long long n = sq.n;
+  const int w = a.w, G = a.G, n_chunks = a.n_chunks, tiles_per_block = sq.tiles_per_block;
+  const int stat_blocks = sq.blocks_x;
+  const float c2 = a.c2;
+  const u32x4* __restrict__ q_win = static_cast<const u32x4*>(a.q_win) + (long long)seq * a.H * w * T::kCpr;
+  const u32x4* __restrict__ k = static_cast<const u32x4*>(a.k) + (long long)a.H_kv * sq.tok * T::kCpr;
+  char* region = a.ws + sq.ws_off;
+  const float2* __restrict__ stat_part = reinterpret_cast<const float2*>(region + a.off_stat_part);
+  const float* __restrict__ lse = a.lse ? a.lse + (long long)seq * a.H * w : nullptr;
+  float* __restrict__ s_raw = reinterpret_cast<float*>(region + a.off_sraw);
+  PoolArgs pa;
+  pa.vnorm_part = reinterpret_cast<const float*>(region + a.off_vnorm_part);
+  pa.vnorm_blocks = sq.vnorm_blocks;
+  pa.pool_half = a.pool_half;
+  pa.scores = a.scores + (long long)a.H_kv * sq.tok;
+  pa.vbar = a.vbar + (long long)seq * a.H_kv;
+  pa.layer_stat = a.layer_stat + seq;
+  pa.ent_part = reinterpret_cast<double2*>(region + a.off_ent_part);
+  pa.counters = reinterpret_cast<uint32_t*>(region + a.off_counter);
   constexpr int kWaves = Shape<DT, D>::kWaves;
   constexpr int kStages = Shape<DT, D>::kStages;
   __shared__ u32x4 s_tile[kWaves][kStages][T::kTileChunks];
@@ -508,8 +536,8 @@ scores_kernel(const u32x4* __restrict__ q_win, const u32x4* __restrict__ k, long
     // the workgroup that owns the head's last prefix tile also writes the window entries
     if (t_begin < t_end && t_end == n_tiles && threadIdx.x < (unsigned)w)
       pa.scores[(long long)g * n + n_prefix + threadIdx.x] = INFINITY;
-    entropy_finish<Shape<DT, D>::kThreads>(acc_s, acc_t, pa.ent_part, pa.counters, gridDim.x * gridDim.y,
-                                           blockIdx.y * gridDim.x + blockIdx.x,
+    entropy_finish<Shape<DT, D>::kThreads>(acc_s, acc_t, pa.ent_part, pa.counters, sq.blocks_x * gridDim.y,
+                                           blockIdx.y * sq.blocks_x + blockIdx.x,
                                            (double)gridDim.y * (double)n_prefix, pa.layer_stat, s_s, s_t,
                                            &s_last);
   }
@@ -549,9 +577,16 @@ struct VShape {
 
 template <int DT, int D>
 __global__ void __launch_bounds__((VShape<DT, D>::kThreads))
-vnorm_kernel(const u32x4* __restrict__ v, long long n, int tiles_per_block, float* __restrict__ vnorm_part,
-             uint32_t* __restrict__ counters, int n_counter_words) {
+vnorm_kernel(const SweepArgs a) {
   using T = Tile<DT, D>;
+  const SweepSeq sq = a.s[blockIdx.z];
+  if (blockIdx.x >= (unsigned int)sq.vnorm_blocks) return;
+  const long long n = sq.n;
+  const int tiles_per_block = sq.vnorm_tiles_per_block;
+  const u32x4* __restrict__ v = static_cast<const u32x4*>(a.v) + (long long)a.H_kv * sq.tok * T::kCpr;
+  float* __restrict__ vnorm_part = reinterpret_cast<float*>(a.ws + sq.ws_off + a.off_vnorm_part);
+  uint32_t* __restrict__ counters = reinterpret_cast<uint32_t*>(a.ws + sq.ws_off + a.off_counter);
+  constexpr int n_counter_words = kArriveWords;
   constexpr int kWaves = VShape<DT, D>::kWaves;
   constexpr int kStages = VShape<DT, D>::kStages < 2 ? 2 : VShape<DT, D>::kStages;
   __shared__ u32x4 s_tile[kWaves][kStages][T::kTileChunks];
@@ -608,7 +643,7 @@ vnorm_kernel(const u32x4* __restrict__ v, long long n, int tiles_per_block, floa
     float m = s_max[0];
 #pragma unroll
     for (int i = 1; i < kWaves; ++i) m = fmaxf(m, s_max[i]);
-    vnorm_part[(long long)g * gridDim.x + blockIdx.x] = m;
+    vnorm_part[(long long)g * sq.vnorm_blocks + blockIdx.x] = m;
   }
 }
 
@@ -746,8 +781,8 @@ ScoreWorkspace make_score_workspace(const lava_layer_desc& d, int64_t n) {
   off += align_up(sizeof(float2) * (size_t)d.n_kv_heads * p.n_chunks * p.blocks_x_bound * p.chunk_heads * 32);
   w.off_vnorm_part = off;
   off += align_up(sizeof(float) * (size_t)d.n_kv_heads * p.vnorm_blocks_bound);
-  w.off_sraw = off;
-  off += align_up(sizeof(float) * (size_t)d.n_kv_heads * (size_t)(n - d.window));
+  w.off_sraw = off;          // only a group split into chunks goes through raw scores in memory
+  if (!p.fused_pool) off += align_up(sizeof(float) * (size_t)d.n_kv_heads * (size_t)(n - d.window));
   w.off_ent_part = off;
   const size_t ent_blocks = (size_t)pool_blocks(d, n) > (size_t)p.blocks_x_bound * p.n_chunks
                                 ? (size_t)pool_blocks(d, n) : (size_t)p.blocks_x_bound * p.n_chunks;
@@ -758,14 +793,11 @@ ScoreWorkspace make_score_workspace(const lava_layer_desc& d, int64_t n) {
   return w;
 }
 
-int32_t launch_vnorm(const lava_layer_desc& d, int64_t n, const void* v, float* vnorm_part,
-                     uint32_t* counters, const SweepPlan& p, hipStream_t s) {
-  const dim3 grid(p.vnorm_blocks, d.n_kv_heads);
+int32_t launch_vnorm(const lava_layer_desc& d, const SweepArgs& a, int max_vnorm_blocks, hipStream_t s) {
+  const dim3 grid(max_vnorm_blocks, d.n_kv_heads, a.n_seq);
   ProfScope ps(KID_VNORM, s);
-#define LAVA_VNORM(DTV, DV)                                                                          \
-  hipLaunchKernelGGL((vnorm_kernel<DTV, DV>), grid, dim3(VShape<DTV, DV>::kThreads), 0, s,           \
-                     static_cast<const u32x4*>(v), (long long)n, p.vnorm_tiles_per_block, vnorm_part, \
-                     counters, kArriveWords)
+#define LAVA_VNORM(DTV, DV) \
+  hipLaunchKernelGGL((vnorm_kernel<DTV, DV>), grid, dim3(VShape<DTV, DV>::kThreads), 0, s, a)
   if (d.dtype == LAVA_BF16 && d.head_dim == 128) LAVA_VNORM(LAVA_BF16, 128);
   else if (d.dtype == LAVA_BF16 && d.head_dim == 64) LAVA_VNORM(LAVA_BF16, 64);
   else if (d.dtype == LAVA_F32 && d.head_dim == 64) LAVA_VNORM(LAVA_F32, 64);
@@ -775,24 +807,24 @@ int32_t launch_vnorm(const lava_layer_desc& d, int64_t n, const void* v, float* 
   return launch_status();
 }
 
-__global__ void __launch_bounds__(256) unit_vnorm_kernel(float* __restrict__ vnorm_part, int n_part,
-                                                         uint32_t* __restrict__ counters, int n_counter_words) {
+__global__ void __launch_bounds__(256) unit_vnorm_kernel(const SweepArgs a) {
+  const SweepSeq sq = a.s[blockIdx.z];
+  float* vnorm_part = reinterpret_cast<float*>(a.ws + sq.ws_off + a.off_vnorm_part);
+  uint32_t* counters = reinterpret_cast<uint32_t*>(a.ws + sq.ws_off + a.off_counter);
   const int i = blockIdx.x * 256 + threadIdx.x;
-  if (i < n_part) vnorm_part[i] = 1.0f;
-  if (i < n_counter_words) counters[i] = 0u;
+  if (i < a.H_kv * sq.vnorm_blocks) vnorm_part[i] = 1.0f;
+  if (i < kArriveWords) counters[i] = 0u;
 }
 
-int32_t launch_unit_vnorm(const lava_layer_desc& d, float* vnorm_part, uint32_t* counters, const SweepPlan& p,
-                          hipStream_t s) {
-  const int n_part = d.n_kv_heads * p.vnorm_blocks;
+int32_t launch_unit_vnorm(const lava_layer_desc& d, const SweepArgs& a, int max_vnorm_blocks, hipStream_t s) {
+  const int n_part = d.n_kv_heads * max_vnorm_blocks;
   const int n = n_part > kArriveWords ? n_part : kArriveWords;
   ProfScope ps(KID_VNORM, s);
-  hipLaunchKernelGGL(unit_vnorm_kernel, dim3((n + 255) / 256), dim3(256), 0, s, vnorm_part, n_part, counters,
-                     kArriveWords);
+  hipLaunchKernelGGL(unit_vnorm_kernel, dim3((n + 255) / 256, 1, a.n_seq), dim3(256), 0, s, a);
   return launch_status();
 }
 
-static float exp2_scale(const lava_layer_desc& d) {
+float sweep_exp2_scale(const lava_layer_desc& d) {
   const float scale = d.softmax_scale > 0.0f ? d.softmax_scale : 1.0f / sqrtf((float)d.head_dim);
   return scale * kLog2e;
 }
@@ -817,60 +849,39 @@ static float exp2_scale(const lava_layer_desc& d) {
     }                                                                               \
   } while (0)
 
-int32_t launch_stats(const lava_layer_desc& d, int64_t n, const void* q_win, const void* k,
-                     float2* stat_part, const SweepPlan& p, hipStream_t s) {
-  const int G = d.n_q_heads / d.n_kv_heads;
-  const dim3 grid(p.blocks_x, d.n_kv_heads * p.n_chunks);
-  const float c2 = exp2_scale(d);
+int32_t launch_stats(const lava_layer_desc& d, const SweepArgs& a, int max_blocks_x, const SweepPlan& p,
+                     hipStream_t s) {
+  const dim3 grid(max_blocks_x, d.n_kv_heads * p.n_chunks, a.n_seq);
   ProfScope ps(KID_STATS, s);
-#define LAVA_STATS(DTV, DV, GTV)                                                              \
-  hipLaunchKernelGGL((stats_kernel<DTV, DV, GTV>), grid, dim3(Shape<DTV, DV>::kThreads), 0, s,                         \
-                     static_cast<const u32x4*>(q_win), static_cast<const u32x4*>(k),          \
-                     (long long)n, d.window, G, p.n_chunks, c2, p.tiles_per_block, stat_part)
+#define LAVA_STATS(DTV, DV, GTV) \
+  hipLaunchKernelGGL((stats_kernel<DTV, DV, GTV>), grid, dim3(Shape<DTV, DV>::kThreads), 0, s, a)
   LAVA_SWEEP_DISPATCH(LAVA_STATS);
 #undef LAVA_STATS
   return launch_status();
 }
 
-int32_t launch_scores(const lava_layer_desc& d, int64_t n, const void* q_win, const void* k,
-                      const float2* stat_part, const float* lse, float* s_raw, const float* vnorm_part,
-                      float* scores, float* vbar, float* layer_stat, double2* ent_part, uint32_t* counters,
-                      const SweepPlan& p, hipStream_t s) {
-  PoolArgs pa;
-  pa.vnorm_part = vnorm_part;
-  pa.vnorm_blocks = p.vnorm_blocks;
-  pa.pool_half = d.pool_kernel / 2;
-  pa.scores = scores;
-  pa.vbar = vbar;
-  pa.layer_stat = layer_stat;
-  pa.ent_part = ent_part;
-  pa.counters = counters;
-  const int G = d.n_q_heads / d.n_kv_heads;
-  const dim3 grid(p.blocks_x, d.n_kv_heads * p.n_chunks);
-  const float c2 = exp2_scale(d);
+int32_t launch_scores(const lava_layer_desc& d, const SweepArgs& a, int max_blocks_x, const SweepPlan& p,
+                      hipStream_t s) {
+  const dim3 grid(max_blocks_x, d.n_kv_heads * p.n_chunks, a.n_seq);
   ProfScope ps(KID_SCORES, s);
   if (p.n_chunks > 1) {
     // partial group maxima are combined with integer atomicMax; start from +0 (a fill kernel,
-    // not a memset node, so the call sequence can be captured in a HIP graph)
-    const long long count = (long long)d.n_kv_heads * (long long)(n - d.window);
+    // not a memset node, so the call sequence can be captured in a HIP graph).  One sequence per launch here.
+    const long long count = (long long)d.n_kv_heads * (a.s[0].n - d.window);
     hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((count + 1023) / 1024)), dim3(256), 0, s,
-                       s_raw, count);
+                       reinterpret_cast<float*>(a.ws + a.s[0].ws_off + a.off_sraw), count);
   }
-#define LAVA_SCORES_ARGS                                                                                 \
-  static_cast<const u32x4*>(q_win), static_cast<const u32x4*>(k), (long long)n, d.window, G, p.n_chunks, \
-      c2, p.tiles_per_block, stat_part, p.blocks_x, lse, s_raw, pa
-#define LAVA_SCORES(DTV, DV, GTV)                                                                        \
-  do {                                                                                                   \
-    if (p.fused_pool)                                                                                    \
-      hipLaunchKernelGGL((scores_kernel<DTV, DV, GTV, true>), grid, dim3(Shape<DTV, DV>::kThreads), 0,   \
-                         s, LAVA_SCORES_ARGS);                                                           \
-    else                                                                                                 \
-      hipLaunchKernelGGL((scores_kernel<DTV, DV, GTV, false>), grid, dim3(Shape<DTV, DV>::kThreads), 0,  \
-                         s, LAVA_SCORES_ARGS);                                                           \
+#define LAVA_SCORES(DTV, DV, GTV)                                                                       \
+  do {                                                                                                  \
+    if (p.fused_pool)                                                                                   \
+      hipLaunchKernelGGL((scores_kernel<DTV, DV, GTV, true>), grid, dim3(Shape<DTV, DV>::kThreads), 0,  \
+                         s, a);                                                                         \
+    else                                                                                                \
+      hipLaunchKernelGGL((scores_kernel<DTV, DV, GTV, false>), grid, dim3(Shape<DTV, DV>::kThreads), 0, \
+                         s, a);                                                                         \
   } while (0)
   LAVA_SWEEP_DISPATCH(LAVA_SCORES);
 #undef LAVA_SCORES
-#undef LAVA_SCORES_ARGS
   return launch_status();
 }
 

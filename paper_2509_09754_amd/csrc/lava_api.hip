@@ -95,11 +95,14 @@ const char* lava_status_string(int32_t status) {
 size_t lava_window_scores_workspace_bytes(const lava_layer_desc* desc, int32_t batch,
                                           int64_t total_tokens) {
   if (check_desc(desc) != LAVA_OK || batch < 1 || total_tokens <= desc->window) return 0;
-  // sequences are processed one after another on the stream and share the workspace, so the
-  // largest possible single sequence bounds it
+  // the longest sequence the batch can contain bounds every sequence's region (the size of a region
+  // never shrinks with the length)
   const int64_t max_n = total_tokens - (int64_t)(batch - 1) * (desc->window + 1);
   if (max_n <= desc->window) return 0;
-  return make_score_workspace(*desc, max_n).bytes;
+  const size_t region = make_score_workspace(*desc, max_n).bytes;
+  // sequences of a batch are swept together, each in its own region; when a KV group has to be
+  // split into chunks they are processed one after another and share one region
+  return make_sweep_plan(*desc, max_n).fused_pool ? region * (size_t)batch : region;
 }
 
 int32_t lava_window_scores(const lava_layer_desc* desc, int32_t batch, const int64_t* seq_lens,
@@ -118,46 +121,78 @@ int32_t lava_window_scores(const lava_layer_desc* desc, int32_t batch, const int
     if (seq_lens[b] >= (int64_t)1 << 31) return LAVA_ERR_SHAPE;
     if (seq_lens[b] > max_n) max_n = seq_lens[b];
   }
-  const size_t need = make_score_workspace(*desc, max_n).bytes;
+  const lava_layer_desc& d = *desc;
+  const SweepPlan plan_max = make_sweep_plan(d, max_n);
+  const ScoreWorkspace region = make_score_workspace(d, max_n);
+  const bool together = plan_max.fused_pool;                 // property of the descriptor, not of the length
+  const size_t need = together ? region.bytes * (size_t)batch : region.bytes;
   if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 ||
       workspace_bytes < need)
     return LAVA_ERR_WORKSPACE;
 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
-  const lava_layer_desc& d = *desc;
-  const size_t esize = d.dtype == LAVA_BF16 ? 2 : 4;
-  const size_t row = (size_t)d.head_dim * esize;
-  char* ws = static_cast<char*>(workspace);
-  int64_t tok = 0;
-  for (int b = 0; b < batch; ++b) {
-    const int64_t n = seq_lens[b];
-    const SweepPlan plan = make_sweep_plan(d, n);
-    const ScoreWorkspace w = make_score_workspace(d, n);
-    const char* kb = static_cast<const char*>(k) + (size_t)d.n_kv_heads * tok * row;
-    const char* vb = static_cast<const char*>(v) + (size_t)d.n_kv_heads * tok * row;
-    const char* qb = static_cast<const char*>(q_win) + (size_t)b * d.n_q_heads * d.window * row;
-    const float* lse_b = lse ? lse + (size_t)b * d.n_q_heads * d.window : nullptr;
-    float* sc = scores + (size_t)d.n_kv_heads * tok;
-    float2* stat_part = reinterpret_cast<float2*>(ws + w.off_stat_part);
-    float* vnorm_part = reinterpret_cast<float*>(ws + w.off_vnorm_part);
-    float* s_raw = reinterpret_cast<float*>(ws + w.off_sraw);
-    double2* ent_part = reinterpret_cast<double2*>(ws + w.off_ent_part);
-    uint32_t* counters = reinterpret_cast<uint32_t*>(ws + w.off_counter);
+  SweepArgs a;
+  a.q_win = q_win;
+  a.k = k;
+  a.v = v;
+  a.lse = lse;
+  a.scores = scores;
+  a.vbar = vbar;
+  a.layer_stat = layer_stat;
+  a.ws = static_cast<char*>(workspace);
+  a.off_stat_part = region.off_stat_part;
+  a.off_vnorm_part = region.off_vnorm_part;
+  a.off_sraw = region.off_sraw;
+  a.off_ent_part = region.off_ent_part;
+  a.off_counter = region.off_counter;
+  a.H = d.n_q_heads;
+  a.H_kv = d.n_kv_heads;
+  a.w = d.window;
+  a.G = d.n_q_heads / d.n_kv_heads;
+  a.n_chunks = plan_max.n_chunks;
+  a.pool_half = d.pool_kernel / 2;
+  a.c2 = sweep_exp2_scale(d);
 
-    st = d.score_kind == LAVA_SCORE_ATTENTION ? launch_unit_vnorm(d, vnorm_part, counters, plan, s)
-                                              : launch_vnorm(d, n, vb, vnorm_part, counters, plan, s);
+  const int per_launch = together ? kMaxSeqPerLaunch : 1;
+  int64_t tok = 0;
+  for (int b0 = 0; b0 < batch; b0 += per_launch) {
+    a.first_seq = b0;
+    a.n_seq = batch - b0 < per_launch ? batch - b0 : per_launch;
+    int max_bx = 0, max_vb = 0;
+    SweepPlan plan = plan_max;
+    for (int i = 0; i < a.n_seq; ++i) {
+      const int64_t n = seq_lens[b0 + i];
+      plan = make_sweep_plan(d, n);
+      SweepSeq& sq = a.s[i];
+      sq.n = n;
+      sq.tok = tok;
+      sq.ws_off = together ? (long long)(region.bytes * (size_t)(b0 + i)) : 0;
+      sq.blocks_x = plan.blocks_x;
+      sq.tiles_per_block = plan.tiles_per_block;
+      sq.vnorm_blocks = plan.vnorm_blocks;
+      sq.vnorm_tiles_per_block = plan.vnorm_tiles_per_block;
+      if (plan.blocks_x > max_bx) max_bx = plan.blocks_x;
+      if (plan.vnorm_blocks > max_vb) max_vb = plan.vnorm_blocks;
+      tok += n;
+    }
+    st = d.score_kind == LAVA_SCORE_ATTENTION ? launch_unit_vnorm(d, a, max_vb, s) : launch_vnorm(d, a, max_vb, s);
     if (st != LAVA_OK) return st;
-    if (lse_b == nullptr) {
-      st = launch_stats(d, n, qb, kb, stat_part, plan, s);
+    if (lse == nullptr) {
+      st = launch_stats(d, a, max_bx, plan_max, s);
       if (st != LAVA_OK) return st;
     }
-    st = launch_scores(d, n, qb, kb, stat_part, lse_b, s_raw, vnorm_part, sc, vbar + (size_t)b * d.n_kv_heads,
-                       layer_stat + b, ent_part, counters, plan, s);
+    st = launch_scores(d, a, max_bx, plan_max, s);
     if (st != LAVA_OK) return st;
-    if (!plan.fused_pool) st = launch_poolstat(d, n, s_raw, vnorm_part, plan.vnorm_blocks, sc, vbar + (size_t)b * d.n_kv_heads,
-                         layer_stat + b, ent_part, counters, s);
-    if (st != LAVA_OK) return st;
-    tok += n;
+    if (!together) {                                         // one sequence: `plan` is its plan
+      const SweepSeq& sq = a.s[0];
+      char* reg = a.ws + sq.ws_off;
+      st = launch_poolstat(d, sq.n, reinterpret_cast<const float*>(reg + a.off_sraw),
+                           reinterpret_cast<const float*>(reg + a.off_vnorm_part), sq.vnorm_blocks,
+                           scores + (size_t)d.n_kv_heads * sq.tok, vbar + (size_t)b0 * d.n_kv_heads,
+                           layer_stat + b0, reinterpret_cast<double2*>(reg + a.off_ent_part),
+                           reinterpret_cast<uint32_t*>(reg + a.off_counter), s);
+      if (st != LAVA_OK) return st;
+    }
   }
   return LAVA_OK;
 }
