@@ -61,7 +61,7 @@ def cascade_leg(lava, torch, np, sh, desc, dev, sets, scores, args):
     state = lava.CascadeState(desc, n_layers, cap, device=dev)
     rng = np.random.Generator(np.random.PCG64(args.seed + 5))
     state.e.copy_(torch.from_numpy((1e-6 * (0.5 + rng.random(n_layers))).astype(np.float32)))
-    ws = torch.empty(lava.lava_cascade_workspace_bytes(desc, sh.n), dtype=torch.uint8, device=dev)
+    ws = torch.empty(lava.lava_cascade_workspace_bytes(desc, sh.n, n_layers, cap), dtype=torch.uint8, device=dev)
     _, k, v = sets[0]
 
     def run():
@@ -184,8 +184,8 @@ def ragged_batch(lava, synth, torch, np, dev, args):
     """Config 5, one layer: 16 sequences of ragged length (4096 .. 65536 tokens) evicted in one batch.
     Throughput only, so K / V / Q are drawn on the device (same distributions as the generator, without
     the planted structure); every sequence gets the same per-sequence budget.  The sweeps of the whole
-    batch are three launches; budgets, selection and compaction are per sequence.  For comparison the
-    same work is also timed with one lava_window_scores call per sequence."""
+    batch are three launches, the budgets one, the selections and the compactions one table each.  For
+    comparison the same work is also timed with one call per sequence for every step."""
     sh = synth.config(2)
     H, Hkv, d, w = sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.window
     desc = lava.LayerDesc.make(H, Hkv, d, w, sh.dtype)
@@ -217,6 +217,19 @@ def ragged_batch(lava, synth, torch, np, dev, args):
     v_hat = torch.empty(len(lens), B, d, dtype=torch.bfloat16, device=dev)
     starts = np.concatenate([[0], np.cumsum(lens)])
 
+    ws_batch = torch.empty(lava.lava_select_batch_workspace_bytes(len(lens), Hkv * max(lens)), dtype=torch.uint8,
+                           device=dev)
+
+    def tail_batched(q, k, v):
+        lava.lava_layer_budgets(stat.view(-1, 1), total_b, lo, hi, budgets=budgets)
+        sel, cmp = [], []
+        for b, n in enumerate(lens):
+            a0, a1 = int(starts[b]) * Hkv, int(starts[b + 1]) * Hkv
+            sel.append(lava.select_problem(scores[a0:a1], B, counts[b], offs[b], idx[b], kept[b], budget_dev=budgets[b]))
+            cmp.append(lava.compact_problem(desc, n, k[a0:a1], v[a0:a1], offs[b], idx[b], B, k_hat[b], v_hat[b]))
+        lava.lava_select_topk_batch(Hkv, sel, Hkv * max(lens), workspace=ws_batch)
+        lava.lava_compact_batch(desc, cmp)
+
     def tail(q, k, v):
         lava.lava_layer_budgets(stat.view(-1, 1), total_b, lo, hi, budgets=budgets)
         for b, n in enumerate(lens):
@@ -228,7 +241,7 @@ def ragged_batch(lava, synth, torch, np, dev, args):
     def step_batched(i):
         q, k, v = sets[i % n_sets]
         lava.lava_window_scores(desc, lens, q, k, v, scores=scores, vbar=vbar, layer_stat=stat, workspace=ws)
-        tail(q, k, v)
+        tail_batched(q, k, v)
 
     def step_one_by_one(i):
         q, k, v = sets[i % n_sets]
@@ -262,7 +275,7 @@ def ragged_batch(lava, synth, torch, np, dev, args):
                                f"w=32, budget {B} per sequence, bf16", "total_tokens": total, "kv_buffer_sets": n_sets},
         "path": {"algorithmic_bytes": path_bytes, "achieved_GBs": round(path_bytes / t_batch / 1e9, 1),
                  "frac_of_hbm_peak": round(path_bytes / t_batch / 1e9 / HBM_PEAK_GBS, 4)},
-        "one_window_scores_call_per_sequence": {"ms_per_step": round(1e3 * t_seq, 5), "value": round(total / t_seq, 1)},
+        "one_call_per_sequence": {"ms_per_step": round(1e3 * t_seq, 5), "value": round(total / t_seq, 1)},
     }
 
 

@@ -198,6 +198,60 @@ int32_t lava_compact_packed(const lava_layer_desc* desc, const int64_t* src_offs
                             void* k_out, void* v_out, int32_t* pos_out, void* hip_stream);
 
 /*
+ * Several independent selections / compactions in as few launches as the device allows: the layers
+ * an outer iteration of Alg. 2 evicts again, or the sequences of a ragged batch (Alg. 1 per
+ * sequence).  Each problem is exactly one lava_select_topk / lava_compact_packed call (same
+ * meaning, layout and limits of every field); results are identical to calling them one by one.
+ * The tables are host arrays, read during the call.
+ */
+typedef struct lava_select_problem {
+  const float* scores;
+  const int64_t* seg_offsets;   /* or NULL: equal segments                                     */
+  int64_t total_entries;
+  int64_t budget;
+  const int64_t* budget_dev;    /* or NULL                                                     */
+  int32_t* head_counts;
+  int64_t* head_offsets;
+  int32_t* kept_idx;
+  float* kept_scores;           /* or NULL                                                     */
+} lava_select_problem;
+
+typedef struct lava_compact_problem {
+  int64_t src_rows;             /* src_offsets != NULL: rows of the packed source pool;
+                                   src_offsets == NULL: rows per head of a dense [H_kv][n] source */
+  const int64_t* src_offsets;
+  const void* k_src;
+  const void* v_src;
+  const int32_t* pos_src;       /* or NULL (dense source: the position is the index itself)    */
+  const int64_t* head_offsets;
+  const int32_t* kept_idx;
+  int64_t capacity;
+  void* k_out;
+  void* v_out;
+  int32_t* pos_out;             /* or NULL                                                     */
+} lava_compact_problem;
+
+/* Workspace of a batch: n_problems regions, each sized for max_total_entries.  0 if invalid. */
+size_t lava_select_batch_workspace_bytes(int32_t n_problems, int64_t max_total_entries);
+
+/*
+ * n_problems >= 1 selections with n_heads heads each.  max_total_entries >= every problem's
+ * total_entries fixes the region size (problem p uses region p of the workspace).  Problems are
+ * packed into one launch while their workgroups can be resident together, otherwise into several.
+ */
+int32_t lava_select_topk_batch(int32_t n_heads, int32_t n_problems, const lava_select_problem* problems,
+                               int64_t max_total_entries, void* workspace, size_t workspace_bytes,
+                               void* hip_stream);
+
+/* lava_select_status over the regions of a batch: LAVA_ERR_HIP if any selection gave up. */
+int32_t lava_select_batch_status(const void* workspace, int32_t n_problems, int64_t max_total_entries,
+                                 void* hip_stream);
+
+/* n_problems >= 1 compactions of layers of the descriptor's shape, one launch per 32 problems. */
+int32_t lava_compact_batch(const lava_layer_desc* desc, int32_t n_problems,
+                           const lava_compact_problem* problems, void* hip_stream);
+
+/*
  * Algorithm 2 as a driver: state of one layer between cascade steps.  Every pointer is device
  * memory owned by the caller; buffers come in pairs because a re-eviction is out of place, and
  * `cur` (host) says which of the pair holds the layer's current state.  capacity: rows of each
@@ -216,8 +270,13 @@ typedef struct lava_cascade_layer {
   int32_t reserved;
 } lava_cascade_layer;
 
-/* Bytes of device workspace lava_cascade_step needs for layers of H_kv * n entries. */
-size_t lava_cascade_workspace_bytes(const lava_layer_desc* desc, int64_t n);
+/*
+ * Bytes of device workspace lava_cascade_step needs for up to n_layers layers of H_kv * n entries
+ * whose pools hold `capacity` rows (all layers of a step are evicted by one batched selection, one
+ * workspace region per layer).  Returns 0 for invalid arguments.
+ */
+size_t lava_cascade_workspace_bytes(const lava_layer_desc* desc, int64_t n, int32_t n_layers,
+                                    int64_t capacity);
 
 /*
  * One outer iteration of Algorithm 2, after layer `layer` (0-based) has been prefilled and scored:

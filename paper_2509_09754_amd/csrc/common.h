@@ -134,14 +134,21 @@ int32_t launch_select(int n_heads, const float* scores, const int64_t* seg_offse
                       int64_t budget, const int64_t* budget_dev, int32_t* head_counts,
                       int64_t* head_offsets, int32_t* kept_idx, float* kept_scores, void* ws,
                       hipStream_t s);
+// independent selections in as few launches as the device's capacity allows; problem p uses the
+// p-th region of the workspace, regions laid out for max_total entries
+constexpr int kMaxSelProblems = 32;
+int32_t launch_select_batch(int n_heads, int n_problems, const lava_select_problem* problems, int64_t max_total,
+                            void* ws, hipStream_t s);
 
-int32_t select_error_flag(const void* ws, int64_t total, hipStream_t s, int* flag);
+int32_t select_error_flag(const void* ws, int64_t max_total, int n_problems, hipStream_t s, int* flag);
 
 // src_offsets null: dense source [H_kv][n]; otherwise a packed source inside a pool of n rows.
 int32_t launch_compact(const lava_layer_desc& d, int64_t n, const int64_t* src_offsets, const void* k,
                        const void* v, const int32_t* pos_src, const int64_t* head_offsets,
                        const int32_t* kept_idx, int64_t capacity, void* k_out, void* v_out, int32_t* pos_out,
                        hipStream_t s);
+int32_t launch_compact_batch(const lava_layer_desc& d, int n_problems, const lava_compact_problem* problems,
+                             hipStream_t s);
 
 // ---------------------------------------------------------------- decode attention
 struct DecodePlan {

@@ -8,30 +8,44 @@ namespace lava {
 constexpr int kCompactThreads = 256;
 constexpr int kCompactMaxHeads = 64;
 
+struct CompactBatch {
+  int n_heads;
+  int n_problems;
+  lava_compact_problem p[kMaxSelProblems];
+};
+
 // LPR = lanes per row = row bytes / 16.  The source is either dense ([n_heads][n] rows, src_offsets
 // null) or itself packed (head g owns source rows src_offsets[g] .. src_offsets[g+1]-1), which is
 // what a re-eviction of an already compressed layer reads (Alg. 2, inner loop).  pos_out, if
 // given, receives the token position of every surviving row: pos_src[source row] for a packed
 // source, the index itself for a dense one.
+// blockIdx.y = problem of the table; the grid is as wide as the largest capacity asks for.
 template <int LPR>
-__global__ void __launch_bounds__(kCompactThreads)
-compact_kernel(int n_heads, long long n, const int64_t* __restrict__ src_offsets, const uint4* __restrict__ k,
-               const uint4* __restrict__ v, const int32_t* __restrict__ pos_src,
-               const int64_t* __restrict__ head_offsets, const int32_t* __restrict__ kept_idx,
-               long long capacity, uint4* __restrict__ k_out, uint4* __restrict__ v_out,
-               int32_t* __restrict__ pos_out) {
+__global__ void __launch_bounds__(kCompactThreads) compact_kernel(const CompactBatch a) {
+  const lava_compact_problem pr = a.p[blockIdx.y];
+  const int n_heads = a.n_heads;
+  const long long n = pr.src_rows;
+  const int64_t* __restrict__ src_offsets = pr.src_offsets;
+  const int32_t* __restrict__ pos_src = pr.pos_src;
+  const int32_t* __restrict__ kept_idx = pr.kept_idx;
+  const uint4* __restrict__ k = static_cast<const uint4*>(pr.k_src);
+  const uint4* __restrict__ v = static_cast<const uint4*>(pr.v_src);
+  uint4* __restrict__ k_out = static_cast<uint4*>(pr.k_out);
+  uint4* __restrict__ v_out = static_cast<uint4*>(pr.v_out);
+  int32_t* __restrict__ pos_out = pr.pos_out;
+  constexpr int kRowsPerBlock = kCompactThreads / LPR;
+  if ((long long)blockIdx.x * kRowsPerBlock >= pr.capacity) return;
   __shared__ long long s_off[kCompactMaxHeads + 1];
   __shared__ long long s_src[kCompactMaxHeads + 1];
   if (threadIdx.x <= n_heads) {
-    s_off[threadIdx.x] = (long long)head_offsets[threadIdx.x];
+    s_off[threadIdx.x] = (long long)pr.head_offsets[threadIdx.x];
     s_src[threadIdx.x] = src_offsets ? (long long)src_offsets[threadIdx.x] : (long long)threadIdx.x * n;
   }
   __syncthreads();
-  constexpr int kRowsPerBlock = kCompactThreads / LPR;
   const long long t = (long long)blockIdx.x * kRowsPerBlock + threadIdx.x / LPR;
   const int c = threadIdx.x % LPR;
   long long kept = s_off[n_heads];
-  if (kept > capacity) kept = capacity;
+  if (kept > pr.capacity) kept = pr.capacity;
   if (t >= kept) return;
   int g = 0;
   while (g + 1 < n_heads && t >= s_off[g + 1]) ++g;
@@ -49,29 +63,53 @@ compact_kernel(int n_heads, long long n, const int64_t* __restrict__ src_offsets
   if (pos_out != nullptr && c == 0) pos_out[t] = pos_src ? pos_src[row] : (int32_t)src;
 }
 
+int32_t launch_compact_batch(const lava_layer_desc& d, int n_problems, const lava_compact_problem* problems,
+                             hipStream_t s) {
+  const int row_bytes = d.head_dim * (d.dtype == LAVA_BF16 ? 2 : 4);
+  const int lpr = row_bytes / 16;
+  const int rows_per_block = kCompactThreads / lpr;
+  CompactBatch a;
+  a.n_heads = d.n_kv_heads;
+  for (int first = 0; first < n_problems; first += kMaxSelProblems) {
+    const int count = n_problems - first < kMaxSelProblems ? n_problems - first : kMaxSelProblems;
+    int64_t widest = 0;
+    for (int i = 0; i < count; ++i) {
+      a.p[i] = problems[first + i];
+      if (a.p[i].capacity > widest) widest = a.p[i].capacity;
+    }
+    if (widest == 0) continue;
+    a.n_problems = count;
+    const dim3 grid((unsigned)((widest + rows_per_block - 1) / rows_per_block), count), block(kCompactThreads);
+    ProfScope ps(KID_COMPACT, s);
+    switch (lpr) {
+      case 8: hipLaunchKernelGGL(compact_kernel<8>, grid, block, 0, s, a); break;
+      case 16: hipLaunchKernelGGL(compact_kernel<16>, grid, block, 0, s, a); break;
+      case 32: hipLaunchKernelGGL(compact_kernel<32>, grid, block, 0, s, a); break;
+      default: return LAVA_ERR_SHAPE;
+    }
+    const int32_t st = launch_status();
+    if (st != LAVA_OK) return st;
+  }
+  return LAVA_OK;
+}
+
 int32_t launch_compact(const lava_layer_desc& d, int64_t n, const int64_t* src_offsets, const void* k,
                        const void* v, const int32_t* pos_src, const int64_t* head_offsets,
                        const int32_t* kept_idx, int64_t capacity, void* k_out, void* v_out, int32_t* pos_out,
                        hipStream_t s) {
-  if (capacity == 0) return LAVA_OK;
-  const int row_bytes = d.head_dim * (d.dtype == LAVA_BF16 ? 2 : 4);
-  const int lpr = row_bytes / 16;
-  const int rows_per_block = kCompactThreads / lpr;
-  const dim3 grid((unsigned)((capacity + rows_per_block - 1) / rows_per_block)), block(kCompactThreads);
-  ProfScope ps(KID_COMPACT, s);
-#define LAVA_COMPACT(L)                                                                          \
-  hipLaunchKernelGGL(compact_kernel<L>, grid, block, 0, s, d.n_kv_heads, (long long)n, src_offsets, \
-                     static_cast<const uint4*>(k), static_cast<const uint4*>(v), pos_src, head_offsets, \
-                     kept_idx, (long long)capacity, static_cast<uint4*>(k_out),                  \
-                     static_cast<uint4*>(v_out), pos_out)
-  switch (lpr) {
-    case 8: LAVA_COMPACT(8); break;
-    case 16: LAVA_COMPACT(16); break;
-    case 32: LAVA_COMPACT(32); break;
-    default: return LAVA_ERR_SHAPE;
-  }
-#undef LAVA_COMPACT
-  return launch_status();
+  lava_compact_problem pr;
+  pr.src_rows = n;
+  pr.src_offsets = src_offsets;
+  pr.k_src = k;
+  pr.v_src = v;
+  pr.pos_src = pos_src;
+  pr.head_offsets = head_offsets;
+  pr.kept_idx = kept_idx;
+  pr.capacity = capacity;
+  pr.k_out = k_out;
+  pr.v_out = v_out;
+  pr.pos_out = pos_out;
+  return launch_compact_batch(d, 1, &pr, s);
 }
 
 }  // namespace lava

@@ -331,12 +331,12 @@ __device__ __forceinline__ void write_phase(const float (&val)[kSelPerThread], l
 // Grid-wide barrier of the fused kernel: all of its workgroups are resident (the host checks the
 // grid against the device's capacity), arrivals are counted monotonically, and the wait is
 // bounded: if it ever gives up, the error word is set and the kernel still runs to completion.
-__device__ __forceinline__ void grid_sync(SelectState* __restrict__ st, unsigned int round) {
+__device__ __forceinline__ void grid_sync(SelectState* __restrict__ st, unsigned int round, unsigned int n_blocks) {
   drain_vmem();
   __syncthreads();
   if (threadIdx.x == 0) {
     __hip_atomic_fetch_add(&st->barrier, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const unsigned int target = round * gridDim.x;
+    const unsigned int target = round * n_blocks;
     unsigned int spins = 0u;
     while (ld_dev(&st->barrier) < target) {
       __builtin_amdgcn_s_sleep(2);
@@ -349,11 +349,31 @@ __device__ __forceinline__ void grid_sync(SelectState* __restrict__ st, unsigned
   __syncthreads();
 }
 
-__global__ void __launch_bounds__(kSelThreads)
-sel_init_kernel(unsigned int* __restrict__ hist, SelectState* __restrict__ st,
-                int32_t* __restrict__ head_counts, int n_heads) {
+// One launch serves up to kMaxSelProblems independent selections (blockIdx.y picks the problem):
+// the table travels in the kernel arguments.  Every problem has its own histograms, barrier
+// counter and per-workgroup counts in its own region of the workspace, so problems never wait
+// for each other; workgroups beyond a problem's own count return at once.
+struct SelectBatch {
+  int n_heads;
+  int n_problems;
+  char* ws;                      // region of problem p at ws + p * ws_stride
+  size_t ws_stride, off_hist, off_state, off_blk;
+  int blk_stride;                // n_blocks the regions were laid out for
+  lava_select_problem p[kMaxSelProblems];
+};
+
+__device__ __forceinline__ int problem_blocks(const lava_select_problem& pr) {
+  const long long nb = (pr.total_entries + kSelChunk - 1) / kSelChunk;
+  return nb < 1 ? 1 : (int)nb;
+}
+
+__global__ void __launch_bounds__(kSelThreads) sel_init_kernel(const SelectBatch a) {
+  const lava_select_problem pr = a.p[blockIdx.x];
+  char* region = a.ws + blockIdx.x * a.ws_stride;
+  unsigned int* hist = reinterpret_cast<unsigned int*>(region + a.off_hist);
+  SelectState* st = reinterpret_cast<SelectState*>(region + a.off_state);
   for (int i = threadIdx.x; i < 3 * kBins; i += kSelThreads) hist[i] = 0u;
-  if (threadIdx.x < n_heads) head_counts[threadIdx.x] = 0;
+  if (threadIdx.x < a.n_heads) pr.head_counts[threadIdx.x] = 0;
   if (threadIdx.x == 0) {
     st->barrier = 0u;
     st->error = 0u;
@@ -372,61 +392,68 @@ __device__ __forceinline__ long long device_total(long long bound, const int64_t
 }
 
 // The whole selection in one launch.
-__global__ void __launch_bounds__(kSelThreads)
-sel_fused_kernel(const float* __restrict__ scores, long long total, int n_heads,
-                 const int64_t* __restrict__ seg_offsets, long long budget,
-                 const int64_t* __restrict__ budget_dev, unsigned int* __restrict__ hist,
-                 SelectState* __restrict__ st, unsigned int* __restrict__ blk,
-                 int32_t* __restrict__ head_counts, int64_t* __restrict__ head_offsets,
-                 int32_t* __restrict__ kept_idx, float* __restrict__ kept_scores) {
+__global__ void __launch_bounds__(kSelThreads) sel_fused_kernel(const SelectBatch a) {
+  const lava_select_problem pr = a.p[blockIdx.y];
+  const unsigned int nb = (unsigned int)problem_blocks(pr);
+  if (blockIdx.x >= nb) return;
+  char* region = a.ws + blockIdx.y * a.ws_stride;
+  unsigned int* hist = reinterpret_cast<unsigned int*>(region + a.off_hist);
+  SelectState* st = reinterpret_cast<SelectState*>(region + a.off_state);
+  unsigned int* blk = reinterpret_cast<unsigned int*>(region + a.off_blk);
+  const float* __restrict__ scores = pr.scores;
+  const int64_t* __restrict__ seg_offsets = pr.seg_offsets;
+  const int n_heads = a.n_heads;
+  const long long budget = pr.budget;
+
   __shared__ SelShared sh;
-  const unsigned int nb = gridDim.x;
-  total = device_total(total, seg_offsets, n_heads);
+  const long long total = device_total(pr.total_entries, seg_offsets, n_heads);
   float val[kSelPerThread];
   load_chunk(scores, total, sh, val);
   Pick pk;
   pk.prefix = 0u;
-  pk.need = effective_budget(budget, budget_dev, total);
+  pk.need = effective_budget(budget, pr.budget_dev, total);
   const long long kept_total = pk.need;
 
   hist_phase<0>(val, total, pk.prefix, sh, hist);
-  grid_sync(st, 1u);
+  grid_sync(st, 1u, nb);
   pk = pick_phase<0>(hist, pk, sh);
   hist_phase<1>(val, total, pk.prefix, sh, hist + kBins);
-  grid_sync(st, 2u);
+  grid_sync(st, 2u, nb);
   pk = pick_phase<1>(hist + kBins, pk, sh);
   hist_phase<2>(val, total, pk.prefix, sh, hist + 2 * kBins);
-  grid_sync(st, 3u);
+  grid_sync(st, 3u, nb);
   pk = pick_phase<2>(hist + 2 * kBins, pk, sh);
 
   unsigned int gt_mask, eq_mask;
-  count_phase(val, total, pk.prefix, sh, blk, (int)nb, gt_mask, eq_mask);
-  grid_sync(st, 4u);
+  count_phase(val, total, pk.prefix, sh, blk, a.blk_stride, gt_mask, eq_mask);
+  grid_sync(st, 4u, nb);
   long long gt_before, eq_before;
-  prefix_phase(blk, (int)nb, sh, gt_before, eq_before);
+  prefix_phase(blk, a.blk_stride, sh, gt_before, eq_before);
   write_phase(val, total, n_heads, seg_offsets, gt_mask, eq_mask, pk.need, budget, gt_before, eq_before,
-              kept_total, sh, head_counts, head_offsets, kept_idx, kept_scores);
+              kept_total, sh, pr.head_counts, pr.head_offsets, pr.kept_idx, pr.kept_scores);
 }
 
-// The same phases as separate launches (kernel boundaries take the place of the grid barriers).
-// STEP 0..2: histogram pass STEP; 3: counts; 4: write.
+// The same phases as separate launches (kernel boundaries take the place of the grid barriers),
+// for a problem too large to keep its whole grid resident.  STEP 0..2: histogram pass STEP; 3: counts; 4: write.
 template <int STEP>
-__global__ void __launch_bounds__(kSelThreads)
-sel_step_kernel(const float* __restrict__ scores, long long total, int n_heads,
-                const int64_t* __restrict__ seg_offsets, long long budget,
-                const int64_t* __restrict__ budget_dev, unsigned int* __restrict__ hist,
-                unsigned int* __restrict__ blk, int32_t* __restrict__ head_counts,
-                int64_t* __restrict__ head_offsets, int32_t* __restrict__ kept_idx,
-                float* __restrict__ kept_scores) {
+__global__ void __launch_bounds__(kSelThreads) sel_step_kernel(const SelectBatch a) {
+  const lava_select_problem pr = a.p[blockIdx.y];
+  const int nb = problem_blocks(pr);
+  if ((int)blockIdx.x >= nb) return;
+  char* region = a.ws + blockIdx.y * a.ws_stride;
+  unsigned int* hist = reinterpret_cast<unsigned int*>(region + a.off_hist);
+  unsigned int* blk = reinterpret_cast<unsigned int*>(region + a.off_blk);
+  const int64_t* __restrict__ seg_offsets = pr.seg_offsets;
+  const int n_heads = a.n_heads;
+  const long long budget = pr.budget;
   __shared__ SelShared sh;
   {
-    const int nb = (int)gridDim.x;
-    total = device_total(total, seg_offsets, n_heads);
+    const long long total = device_total(pr.total_entries, seg_offsets, n_heads);
     float val[kSelPerThread];
-    load_chunk(scores, total, sh, val);
+    load_chunk(pr.scores, total, sh, val);
     Pick pk;
     pk.prefix = 0u;
-    pk.need = effective_budget(budget, budget_dev, total);
+    pk.need = effective_budget(budget, pr.budget_dev, total);
     const long long kept_total = pk.need;
     if constexpr (STEP >= 1) pk = pick_phase<0>(hist, pk, sh);
     if constexpr (STEP >= 2) pk = pick_phase<1>(hist + kBins, pk, sh);
@@ -436,12 +463,12 @@ sel_step_kernel(const float* __restrict__ scores, long long total, int n_heads,
     } else {
       unsigned int gt_mask, eq_mask;
       // counts are recomputed in the write step (cheap) so that both steps share count_phase
-      count_phase(val, total, pk.prefix, sh, blk, nb, gt_mask, eq_mask);
+      count_phase(val, total, pk.prefix, sh, blk, a.blk_stride, gt_mask, eq_mask);
       if constexpr (STEP == 4) {
         long long gt_before, eq_before;
-        prefix_phase(blk, nb, sh, gt_before, eq_before);
+        prefix_phase(blk, a.blk_stride, sh, gt_before, eq_before);
         write_phase(val, total, n_heads, seg_offsets, gt_mask, eq_mask, pk.need, budget, gt_before, eq_before,
-                    kept_total, sh, head_counts, head_offsets, kept_idx, kept_scores);
+                    kept_total, sh, pr.head_counts, pr.head_offsets, pr.kept_idx, pr.kept_scores);
       }
     }
   }
@@ -464,50 +491,87 @@ static int fused_capacity() {
   return cached[dev];
 }
 
+// Selections of a batch: consecutive problems are packed into launches of the fused kernel as long
+// as their workgroups fit into half of the device together (they all have to be resident: each
+// problem meets at its own grid barriers); a problem that does not fit alone runs as step launches.
+int32_t launch_select_batch(int n_heads, int n_problems, const lava_select_problem* problems, int64_t max_total,
+                            void* ws, hipStream_t s) {
+  const SelectWorkspace w = make_select_workspace(max_total);
+  SelectBatch a;
+  a.n_heads = n_heads;
+  a.ws_stride = w.bytes;
+  a.off_hist = w.off_hist;
+  a.off_state = w.off_state;
+  a.off_blk = w.off_blk;
+  a.blk_stride = w.n_blocks;
+  const dim3 block(kSelThreads);
+  const int cap = fused_capacity() / 2;
+  int first = 0;
+  while (first < n_problems) {
+    int count = 0, blocks = 0, widest = 0;
+    while (first + count < n_problems && count < kMaxSelProblems) {
+      const int64_t t = problems[first + count].total_entries;
+      const int nb = (int)((t + kSelChunk - 1) / kSelChunk) < 1 ? 1 : (int)((t + kSelChunk - 1) / kSelChunk);
+      if (count > 0 && blocks + nb > cap) break;
+      blocks += nb;
+      if (nb > widest) widest = nb;
+      a.p[count] = problems[first + count];
+      ++count;
+    }
+    a.n_problems = count;
+    a.ws = static_cast<char*>(ws) + (size_t)first * w.bytes;
+    {
+      ProfScope ps(KID_SEL_INIT, s);
+      hipLaunchKernelGGL(sel_init_kernel, dim3(count), block, 0, s, a);
+    }
+    if (blocks <= cap) {
+      ProfScope ps(KID_SEL_FUSED, s);
+      hipLaunchKernelGGL(sel_fused_kernel, dim3(widest, count), block, 0, s, a);
+    } else {                                               // a single problem wider than the device allows
+      ProfScope ps(KID_SEL_STEPS, s);
+      const dim3 grid(widest, count);
+      hipLaunchKernelGGL(sel_step_kernel<0>, grid, block, 0, s, a);
+      hipLaunchKernelGGL(sel_step_kernel<1>, grid, block, 0, s, a);
+      hipLaunchKernelGGL(sel_step_kernel<2>, grid, block, 0, s, a);
+      hipLaunchKernelGGL(sel_step_kernel<3>, grid, block, 0, s, a);
+      hipLaunchKernelGGL(sel_step_kernel<4>, grid, block, 0, s, a);
+    }
+    const int32_t st = launch_status();
+    if (st != LAVA_OK) return st;
+    first += count;
+  }
+  return LAVA_OK;
+}
+
 int32_t launch_select(int n_heads, const float* scores, const int64_t* seg_offsets, int64_t total,
                       int64_t budget, const int64_t* budget_dev, int32_t* head_counts,
                       int64_t* head_offsets, int32_t* kept_idx, float* kept_scores, void* ws,
                       hipStream_t s) {
-  const SelectWorkspace w = make_select_workspace(total);
-  char* base = static_cast<char*>(ws);
-  unsigned int* hist = reinterpret_cast<unsigned int*>(base + w.off_hist);
-  SelectState* st = reinterpret_cast<SelectState*>(base + w.off_state);
-  unsigned int* blk = reinterpret_cast<unsigned int*>(base + w.off_blk);
-  const dim3 grid(w.n_blocks), block(kSelThreads);
-  {
-    ProfScope ps(KID_SEL_INIT, s);
-    hipLaunchKernelGGL(sel_init_kernel, dim3(1), block, 0, s, hist, st, head_counts, n_heads);
-  }
-  // The fused kernel needs its whole grid resident; half of the device's capacity leaves room
-  // for other work (and another selection) running beside it.
-  if (w.n_blocks <= fused_capacity() / 2) {
-    ProfScope ps(KID_SEL_FUSED, s);
-    hipLaunchKernelGGL(sel_fused_kernel, grid, block, 0, s, scores, (long long)total, n_heads, seg_offsets,
-                       (long long)budget, budget_dev, hist, st, blk, head_counts, head_offsets, kept_idx,
-                       kept_scores);
-    return launch_status();
-  }
-  ProfScope ps(KID_SEL_STEPS, s);
-#define LAVA_SEL_STEP(STEP, GRID)                                                                       \
-  hipLaunchKernelGGL(sel_step_kernel<STEP>, GRID, block, 0, s, scores, (long long)total, n_heads,       \
-                     seg_offsets, (long long)budget, budget_dev, hist, blk, head_counts, head_offsets,  \
-                     kept_idx, kept_scores)
-  LAVA_SEL_STEP(0, grid);
-  LAVA_SEL_STEP(1, grid);
-  LAVA_SEL_STEP(2, grid);
-  LAVA_SEL_STEP(3, grid);
-  LAVA_SEL_STEP(4, grid);
-#undef LAVA_SEL_STEP
-  return launch_status();
+  lava_select_problem pr;
+  pr.scores = scores;
+  pr.seg_offsets = seg_offsets;
+  pr.total_entries = total;
+  pr.budget = budget;
+  pr.budget_dev = budget_dev;
+  pr.head_counts = head_counts;
+  pr.head_offsets = head_offsets;
+  pr.kept_idx = kept_idx;
+  pr.kept_scores = kept_scores;
+  return launch_select_batch(n_heads, 1, &pr, total, ws, s);
 }
 
-int32_t select_error_flag(const void* ws, int64_t total, hipStream_t s, int* flag) {
-  const SelectWorkspace w = make_select_workspace(total);
-  const SelectState* st = reinterpret_cast<const SelectState*>(static_cast<const char*>(ws) + w.off_state);
-  unsigned int host = 0u;
-  if (hipMemcpyAsync(&host, &st->error, sizeof(host), hipMemcpyDeviceToHost, s) != hipSuccess) return LAVA_ERR_HIP;
-  if (hipStreamSynchronize(s) != hipSuccess) return LAVA_ERR_HIP;
-  *flag = (int)host;
+// Error words of the first n_problems regions laid out for max_total: flag = OR of them.
+int32_t select_error_flag(const void* ws, int64_t max_total, int n_problems, hipStream_t s, int* flag) {
+  const SelectWorkspace w = make_select_workspace(max_total);
+  *flag = 0;
+  for (int p = 0; p < n_problems; ++p) {
+    const SelectState* st = reinterpret_cast<const SelectState*>(static_cast<const char*>(ws) + (size_t)p * w.bytes +
+                                                                 w.off_state);
+    unsigned int host = 0u;
+    if (hipMemcpyAsync(&host, &st->error, sizeof(host), hipMemcpyDeviceToHost, s) != hipSuccess) return LAVA_ERR_HIP;
+    if (hipStreamSynchronize(s) != hipSuccess) return LAVA_ERR_HIP;
+    *flag |= (int)host;
+  }
   return LAVA_OK;
 }
 

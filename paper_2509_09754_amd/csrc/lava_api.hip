@@ -215,70 +215,112 @@ size_t lava_select_workspace_bytes(int64_t total_entries) {
   return make_select_workspace(total_entries).bytes;
 }
 
+size_t lava_select_batch_workspace_bytes(int32_t n_problems, int64_t max_total_entries) {
+  if (n_problems < 1 || max_total_entries < 1 || max_total_entries >= (int64_t)1 << 31) return 0;
+  return make_select_workspace(max_total_entries).bytes * (size_t)n_problems;
+}
+
+static int32_t check_select_problem(int32_t n_heads, const lava_select_problem& p) {
+  if (p.scores == nullptr || p.head_counts == nullptr || p.head_offsets == nullptr || p.kept_idx == nullptr ||
+      p.total_entries < 1)
+    return LAVA_ERR_INVALID_ARG;
+  if (p.total_entries >= (int64_t)1 << 31) return LAVA_ERR_SHAPE;
+  if (p.seg_offsets == nullptr && p.total_entries % n_heads != 0) return LAVA_ERR_SHAPE;
+  if (p.budget < 0 || p.budget > p.total_entries) return LAVA_ERR_BUDGET;
+  return LAVA_OK;
+}
+
+int32_t lava_select_topk_batch(int32_t n_heads, int32_t n_problems, const lava_select_problem* problems,
+                               int64_t max_total_entries, void* workspace, size_t workspace_bytes,
+                               void* hip_stream) {
+  if (n_heads < 1 || n_problems < 1 || problems == nullptr || max_total_entries < 1) return LAVA_ERR_INVALID_ARG;
+  if (n_heads > 64 || max_total_entries >= (int64_t)1 << 31) return LAVA_ERR_SHAPE;
+  for (int p = 0; p < n_problems; ++p) {
+    const int32_t st = check_select_problem(n_heads, problems[p]);
+    if (st != LAVA_OK) return st;
+    if (problems[p].total_entries > max_total_entries) return LAVA_ERR_SHAPE;
+  }
+  const size_t need = make_select_workspace(max_total_entries).bytes * (size_t)n_problems;
+  if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 || workspace_bytes < need)
+    return LAVA_ERR_WORKSPACE;
+  return launch_select_batch(n_heads, n_problems, problems, max_total_entries, workspace,
+                             static_cast<hipStream_t>(hip_stream));
+}
+
 int32_t lava_select_topk(int32_t n_heads, const float* scores, const int64_t* seg_offsets,
                          int64_t total_entries, int64_t budget, const int64_t* budget_dev,
                          int32_t* head_counts, int64_t* head_offsets, int32_t* kept_idx,
                          float* kept_scores, void* workspace, size_t workspace_bytes,
                          void* hip_stream) {
-  if (n_heads < 1 || scores == nullptr || head_counts == nullptr || head_offsets == nullptr ||
-      kept_idx == nullptr || total_entries < 1)
+  if (n_heads < 1) return LAVA_ERR_INVALID_ARG;
+  const lava_select_problem p = {scores,      seg_offsets,  total_entries, budget,     budget_dev,
+                                 head_counts, head_offsets, kept_idx,      kept_scores};
+  return lava_select_topk_batch(n_heads, 1, &p, total_entries, workspace, workspace_bytes, hip_stream);
+}
+
+int32_t lava_select_batch_status(const void* workspace, int32_t n_problems, int64_t max_total_entries,
+                                 void* hip_stream) {
+  if (workspace == nullptr || n_problems < 1 || max_total_entries < 1 || max_total_entries >= (int64_t)1 << 31)
     return LAVA_ERR_INVALID_ARG;
-  if (n_heads > 64 || total_entries >= (int64_t)1 << 31) return LAVA_ERR_SHAPE;
-  if (seg_offsets == nullptr && total_entries % n_heads != 0) return LAVA_ERR_SHAPE;
-  if (budget < 0 || budget > total_entries) return LAVA_ERR_BUDGET;
-  const size_t need = make_select_workspace(total_entries).bytes;
-  if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 ||
-      workspace_bytes < need)
-    return LAVA_ERR_WORKSPACE;
-  return launch_select(n_heads, scores, seg_offsets, total_entries, budget, budget_dev, head_counts,
-                       head_offsets, kept_idx, kept_scores, workspace,
-                       static_cast<hipStream_t>(hip_stream));
+  int flag = 0;
+  const int32_t st = select_error_flag(workspace, max_total_entries, n_problems,
+                                       static_cast<hipStream_t>(hip_stream), &flag);
+  if (st != LAVA_OK) return st;
+  return flag ? LAVA_ERR_HIP : LAVA_OK;
 }
 
 int32_t lava_select_status(const void* workspace, int64_t total_entries, void* hip_stream) {
-  if (workspace == nullptr || total_entries < 1 || total_entries >= (int64_t)1 << 31)
+  return lava_select_batch_status(workspace, 1, total_entries, hip_stream);
+}
+
+static int32_t check_compact_problem(const lava_layer_desc& d, const lava_compact_problem& p) {
+  if (p.k_src == nullptr || p.v_src == nullptr || p.head_offsets == nullptr || p.kept_idx == nullptr ||
+      p.k_out == nullptr || p.v_out == nullptr || p.src_rows < 1 || p.capacity < 0)
     return LAVA_ERR_INVALID_ARG;
-  int flag = 0;
-  const int32_t st = select_error_flag(workspace, total_entries, static_cast<hipStream_t>(hip_stream), &flag);
+  if (!aligned16(p.k_src) || !aligned16(p.v_src) || !aligned16(p.k_out) || !aligned16(p.v_out))
+    return LAVA_ERR_INVALID_ARG;
+  const int64_t rows = p.src_offsets ? p.src_rows : (int64_t)d.n_kv_heads * p.src_rows;
+  if (p.capacity > rows) return LAVA_ERR_BUDGET;
+  return LAVA_OK;
+}
+
+int32_t lava_compact_batch(const lava_layer_desc* desc, int32_t n_problems,
+                           const lava_compact_problem* problems, void* hip_stream) {
+  int32_t st = check_desc(desc);
   if (st != LAVA_OK) return st;
-  return flag ? LAVA_ERR_HIP : LAVA_OK;
+  if (n_problems < 1 || problems == nullptr) return LAVA_ERR_INVALID_ARG;
+  for (int p = 0; p < n_problems; ++p) {
+    st = check_compact_problem(*desc, problems[p]);
+    if (st != LAVA_OK) return st;
+  }
+  return launch_compact_batch(*desc, n_problems, problems, static_cast<hipStream_t>(hip_stream));
 }
 
 int32_t lava_compact_kv(const lava_layer_desc* desc, int64_t n, const void* k, const void* v,
                         const int64_t* head_offsets, const int32_t* kept_idx, int64_t capacity,
                         void* k_out, void* v_out, void* hip_stream) {
-  int32_t st = check_desc(desc);
-  if (st != LAVA_OK) return st;
-  if (k == nullptr || v == nullptr || head_offsets == nullptr || kept_idx == nullptr ||
-      k_out == nullptr || v_out == nullptr || n < 1 || capacity < 0)
-    return LAVA_ERR_INVALID_ARG;
-  if (!aligned16(k) || !aligned16(v) || !aligned16(k_out) || !aligned16(v_out))
-    return LAVA_ERR_INVALID_ARG;
-  if (capacity > (int64_t)desc->n_kv_heads * n) return LAVA_ERR_BUDGET;
-  return launch_compact(*desc, n, nullptr, k, v, nullptr, head_offsets, kept_idx, capacity, k_out, v_out,
-                        nullptr, static_cast<hipStream_t>(hip_stream));
+  const lava_compact_problem p = {n, nullptr, k, v, nullptr, head_offsets, kept_idx, capacity, k_out, v_out, nullptr};
+  return lava_compact_batch(desc, 1, &p, hip_stream);
 }
 
 int32_t lava_compact_packed(const lava_layer_desc* desc, const int64_t* src_offsets, int64_t src_rows,
                             const void* k_src, const void* v_src, const int32_t* pos_src,
                             const int64_t* head_offsets, const int32_t* kept_idx, int64_t capacity,
                             void* k_out, void* v_out, int32_t* pos_out, void* hip_stream) {
-  int32_t st = check_desc(desc);
+  const int32_t st = check_desc(desc);
   if (st != LAVA_OK) return st;
-  if (src_offsets == nullptr || k_src == nullptr || v_src == nullptr || head_offsets == nullptr ||
-      kept_idx == nullptr || k_out == nullptr || v_out == nullptr || src_rows < 1 || capacity < 0)
-    return LAVA_ERR_INVALID_ARG;
-  if (!aligned16(k_src) || !aligned16(v_src) || !aligned16(k_out) || !aligned16(v_out)) return LAVA_ERR_INVALID_ARG;
-  if (capacity > src_rows) return LAVA_ERR_BUDGET;
-  return launch_compact(*desc, src_rows, src_offsets, k_src, v_src, pos_src, head_offsets, kept_idx, capacity,
-                        k_out, v_out, pos_out, static_cast<hipStream_t>(hip_stream));
+  if (src_offsets == nullptr) return LAVA_ERR_INVALID_ARG;
+  const lava_compact_problem p = {src_rows, src_offsets, k_src, v_src, pos_src, head_offsets,
+                                  kept_idx, capacity,    k_out, v_out, pos_out};
+  return lava_compact_batch(desc, 1, &p, hip_stream);
 }
 
-size_t lava_cascade_workspace_bytes(const lava_layer_desc* desc, int64_t n) {
-  if (check_desc(desc) != LAVA_OK || n <= desc->window) return 0;
-  const int64_t total = (int64_t)desc->n_kv_heads * n;
-  if (total >= (int64_t)1 << 31) return 0;
-  return make_select_workspace(total).bytes;
+size_t lava_cascade_workspace_bytes(const lava_layer_desc* desc, int64_t n, int32_t n_layers, int64_t capacity) {
+  if (check_desc(desc) != LAVA_OK || n <= desc->window || n_layers < 1 || n_layers > 1024 || capacity < 1) return 0;
+  const int64_t dense = (int64_t)desc->n_kv_heads * n;
+  const int64_t widest = dense > capacity ? dense : capacity;
+  if (widest >= (int64_t)1 << 31) return 0;
+  return make_select_workspace(widest).bytes * (size_t)n_layers;
 }
 
 int32_t lava_cascade_step(const lava_layer_desc* desc, int32_t layer, int64_t n, const void* k_new,
@@ -297,6 +339,7 @@ int32_t lava_cascade_step(const lava_layer_desc* desc, int32_t layer, int64_t n,
   if (total_budget < lo * (layer + 1) || total_budget > dense * (layer + 1)) return LAVA_ERR_BUDGET;
   if (!aligned16(k_new) || !aligned16(v_new)) return LAVA_ERR_INVALID_ARG;
   const int64_t first_cap = total_budget < dense ? total_budget : dense;
+  int64_t widest = dense;
   for (int t = 0; t <= layer; ++t) {
     const lava_cascade_layer& L = layers[t];
     for (int i = 0; i < 2; ++i)
@@ -305,38 +348,42 @@ int32_t lava_cascade_step(const lava_layer_desc* desc, int32_t layer, int64_t n,
         return LAVA_ERR_INVALID_ARG;
     if (L.head_counts == nullptr || L.kept_idx == nullptr || (L.cur != 0 && L.cur != 1)) return LAVA_ERR_INVALID_ARG;
     if (L.capacity < first_cap || L.capacity >= (int64_t)1 << 31) return LAVA_ERR_BUDGET;
+    if (t < layer && L.capacity > widest) widest = L.capacity;
   }
   if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 ||
-      workspace_bytes < make_select_workspace(dense).bytes)
+      workspace_bytes < make_select_workspace(widest).bytes * (size_t)(layer + 1))
     return LAVA_ERR_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
 
   st = launch_budgets_uniform_bounds(layer + 1, e, total_budget, lo, dense, budgets, s);
   if (st != LAVA_OK) return st;
 
-  // the new layer: dense scores, equal segments; its state starts in pool 0
+  // One table of selections and one of compactions: the new layer first (dense scores, equal
+  // segments, its state starts in pool 0), then every earlier layer from what it still holds
+  // into its other pool, ranked by the scores it retained.
+  std::vector<lava_select_problem> sel(layer + 1);
+  std::vector<lava_compact_problem> cmp(layer + 1);
   {
     lava_cascade_layer& L = layers[layer];
-    st = launch_select(desc->n_kv_heads, scores_new, nullptr, dense, first_cap, budgets + layer, L.head_counts,
-                       L.head_offsets[0], L.kept_idx, L.scores[0], workspace, s);
-    if (st != LAVA_OK) return st;
-    st = launch_compact(*desc, n, nullptr, k_new, v_new, nullptr, L.head_offsets[0], L.kept_idx, first_cap,
-                        L.k[0], L.v[0], L.pos[0], s);
-    if (st != LAVA_OK) return st;
-    L.cur = 0;
+    sel[0] = {scores_new,   nullptr,           dense,      first_cap,  budgets + layer,
+              L.head_counts, L.head_offsets[0], L.kept_idx, L.scores[0]};
+    cmp[0] = {n,          nullptr,   k_new,  v_new,  nullptr, L.head_offsets[0],
+              L.kept_idx, first_cap, L.k[0], L.v[0], L.pos[0]};
   }
-  // every earlier layer again, from what it still holds (the workspace is reused: same stream)
   for (int t = 0; t < layer; ++t) {
     lava_cascade_layer& L = layers[t];
     const int a = L.cur, b = 1 - L.cur;
-    st = launch_select(desc->n_kv_heads, L.scores[a], L.head_offsets[a], L.capacity, L.capacity, budgets + t,
-                       L.head_counts, L.head_offsets[b], L.kept_idx, L.scores[b], workspace, s);
-    if (st != LAVA_OK) return st;
-    st = launch_compact(*desc, L.capacity, L.head_offsets[a], L.k[a], L.v[a], L.pos[a], L.head_offsets[b],
-                        L.kept_idx, L.capacity, L.k[b], L.v[b], L.pos[b], s);
-    if (st != LAVA_OK) return st;
-    L.cur = b;
+    sel[t + 1] = {L.scores[a],   L.head_offsets[a], L.capacity, L.capacity, budgets + t,
+                  L.head_counts, L.head_offsets[b], L.kept_idx, L.scores[b]};
+    cmp[t + 1] = {L.capacity, L.head_offsets[a], L.k[a], L.v[a], L.pos[a], L.head_offsets[b],
+                  L.kept_idx, L.capacity,        L.k[b], L.v[b], L.pos[b]};
   }
+  st = launch_select_batch(desc->n_kv_heads, layer + 1, sel.data(), widest, workspace, s);
+  if (st != LAVA_OK) return st;
+  st = launch_compact_batch(*desc, layer + 1, cmp.data(), s);
+  if (st != LAVA_OK) return st;
+  layers[layer].cur = 0;
+  for (int t = 0; t < layer; ++t) layers[t].cur = 1 - layers[t].cur;
   return LAVA_OK;
 }
 

@@ -23,7 +23,9 @@ LAVA_SCORE_LAVA, LAVA_SCORE_ATTENTION = 0, 1
 EXPORTS = [
     "lava_status_string", "lava_window_scores_workspace_bytes", "lava_window_scores",
     "lava_layer_budgets", "lava_select_workspace_bytes", "lava_select_topk", "lava_select_status",
-    "lava_compact_kv", "lava_compact_packed", "lava_cascade_workspace_bytes", "lava_cascade_step",
+    "lava_select_batch_workspace_bytes", "lava_select_topk_batch", "lava_select_batch_status",
+    "lava_compact_kv", "lava_compact_packed", "lava_compact_batch",
+    "lava_cascade_workspace_bytes", "lava_cascade_step",
     "lava_decode_workspace_bytes", "lava_decode_attention",
     "lava_prof_kernel_count", "lava_prof_kernel_name", "lava_prof_enable", "lava_prof_reset",
     "lava_prof_read", "lava_probe_stream",
@@ -82,7 +84,15 @@ def _load() -> ctypes.CDLL:
     lib.lava_compact_packed.restype = i32
     lib.lava_compact_packed.argtypes = [dp, vp, i64, vp, vp, vp, vp, vp, i64, vp, vp, vp, vp]
     lib.lava_cascade_workspace_bytes.restype = sz
-    lib.lava_cascade_workspace_bytes.argtypes = [dp, i64]
+    lib.lava_cascade_workspace_bytes.argtypes = [dp, i64, i32, i64]
+    lib.lava_select_batch_workspace_bytes.restype = sz
+    lib.lava_select_batch_workspace_bytes.argtypes = [i32, i64]
+    lib.lava_select_topk_batch.restype = i32
+    lib.lava_select_topk_batch.argtypes = [i32, i32, vp, i64, vp, sz, vp]
+    lib.lava_select_batch_status.restype = i32
+    lib.lava_select_batch_status.argtypes = [vp, i32, i64, vp]
+    lib.lava_compact_batch.restype = i32
+    lib.lava_compact_batch.argtypes = [dp, i32, vp, vp]
     lib.lava_cascade_step.restype = i32
     lib.lava_cascade_step.argtypes = [dp, i32, i64, vp, vp, vp, vp, i64, vp, vp, vp, sz, vp]
     lib.lava_decode_workspace_bytes.restype = sz
@@ -250,6 +260,89 @@ def lava_select_status(workspace: torch.Tensor, total_entries: int, stream=None)
     return int(lib.lava_select_status(_ptr(workspace), int(total_entries), _stream(stream)))
 
 
+class SelectProblem(ctypes.Structure):
+    """Mirror of lava_select_problem."""
+    _fields_ = [
+        ("scores", ctypes.c_void_p), ("seg_offsets", ctypes.c_void_p), ("total_entries", ctypes.c_int64),
+        ("budget", ctypes.c_int64), ("budget_dev", ctypes.c_void_p), ("head_counts", ctypes.c_void_p),
+        ("head_offsets", ctypes.c_void_p), ("kept_idx", ctypes.c_void_p), ("kept_scores", ctypes.c_void_p),
+    ]
+
+
+class CompactProblem(ctypes.Structure):
+    """Mirror of lava_compact_problem."""
+    _fields_ = [
+        ("src_rows", ctypes.c_int64), ("src_offsets", ctypes.c_void_p), ("k_src", ctypes.c_void_p),
+        ("v_src", ctypes.c_void_p), ("pos_src", ctypes.c_void_p), ("head_offsets", ctypes.c_void_p),
+        ("kept_idx", ctypes.c_void_p), ("capacity", ctypes.c_int64), ("k_out", ctypes.c_void_p),
+        ("v_out", ctypes.c_void_p), ("pos_out", ctypes.c_void_p),
+    ]
+
+
+def _addr(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+def select_problem(scores, budget, head_counts, head_offsets, kept_idx, kept_scores=None, seg_offsets=None,
+                   budget_dev=None, total_entries=None) -> SelectProblem:
+    """One row of the table of lava_select_topk_batch from device tensors (the caller keeps them alive)."""
+    _dev(scores, "scores", torch.float32), _dev(head_counts, "head_counts", torch.int32)
+    _dev(head_offsets, "head_offsets", torch.int64), _dev(kept_idx, "kept_idx", torch.int32)
+    for name, t, dt in (("kept_scores", kept_scores, torch.float32), ("seg_offsets", seg_offsets, torch.int64),
+                        ("budget_dev", budget_dev, torch.int64)):
+        if t is not None:
+            _dev(t, name, dt)
+    total = scores.numel() if total_entries is None else int(total_entries)
+    return SelectProblem(_addr(scores), _addr(seg_offsets), total, int(budget), _addr(budget_dev),
+                         _addr(head_counts), _addr(head_offsets), _addr(kept_idx), _addr(kept_scores))
+
+
+def compact_problem(desc: LayerDesc, src_rows, k_src, v_src, head_offsets, kept_idx, capacity, k_out, v_out,
+                    src_offsets=None, pos_src=None, pos_out=None) -> CompactProblem:
+    """One row of the table of lava_compact_batch (dense source when src_offsets is None)."""
+    for name, t in (("k_src", k_src), ("v_src", v_src), ("k_out", k_out), ("v_out", v_out)):
+        _dev(t, name, desc.torch_dtype)
+    _dev(head_offsets, "head_offsets", torch.int64), _dev(kept_idx, "kept_idx", torch.int32)
+    for name, t, dt in (("src_offsets", src_offsets, torch.int64), ("pos_src", pos_src, torch.int32),
+                        ("pos_out", pos_out, torch.int32)):
+        if t is not None:
+            _dev(t, name, dt)
+    return CompactProblem(int(src_rows), _addr(src_offsets), _addr(k_src), _addr(v_src), _addr(pos_src),
+                          _addr(head_offsets), _addr(kept_idx), int(capacity), _addr(k_out), _addr(v_out),
+                          _addr(pos_out))
+
+
+def lava_select_batch_workspace_bytes(n_problems: int, max_total_entries: int) -> int:
+    return int(lib.lava_select_batch_workspace_bytes(int(n_problems), int(max_total_entries)))
+
+
+def lava_select_topk_batch(n_heads: int, problems, max_total_entries=None, workspace=None, device="cuda",
+                           stream=None):
+    """problems: sequence of SelectProblem.  Returns the workspace (for lava_select_batch_status)."""
+    table = (SelectProblem * len(problems))(*problems)
+    widest = max((p.total_entries for p in problems), default=0) if max_total_entries is None else int(max_total_entries)
+    if workspace is None:
+        need = lava_select_batch_workspace_bytes(len(problems), widest)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=device)
+    st = lib.lava_select_topk_batch(int(n_heads), len(problems), ctypes.cast(table, ctypes.c_void_p), widest,
+                                    _ptr(workspace), workspace.numel(), _stream(stream))
+    _check(st, "lava_select_topk_batch")
+    return workspace
+
+
+def lava_select_batch_status(workspace: torch.Tensor, n_problems: int, max_total_entries: int, stream=None) -> int:
+    return int(lib.lava_select_batch_status(_ptr(workspace), int(n_problems), int(max_total_entries),
+                                            _stream(stream)))
+
+
+def lava_compact_batch(desc: LayerDesc, problems, stream=None) -> None:
+    """problems: sequence of CompactProblem."""
+    table = (CompactProblem * len(problems))(*problems)
+    st = lib.lava_compact_batch(ctypes.byref(desc), len(problems), ctypes.cast(table, ctypes.c_void_p),
+                                _stream(stream))
+    _check(st, "lava_compact_batch")
+
+
 def lava_compact_kv(desc: LayerDesc, n: int, k: torch.Tensor, v: torch.Tensor, head_offsets: torch.Tensor,
                     kept_idx: torch.Tensor, capacity: int, k_out=None, v_out=None, stream=None):
     _dev(k, "k", desc.torch_dtype), _dev(v, "v", desc.torch_dtype)
@@ -334,8 +427,8 @@ class CascadeState:
                     head_offsets=b[f"offs{c}"], head_counts=b["counts"])
 
 
-def lava_cascade_workspace_bytes(desc: LayerDesc, n: int) -> int:
-    return int(lib.lava_cascade_workspace_bytes(ctypes.byref(desc), int(n)))
+def lava_cascade_workspace_bytes(desc: LayerDesc, n: int, n_layers: int, capacity: int) -> int:
+    return int(lib.lava_cascade_workspace_bytes(ctypes.byref(desc), int(n), int(n_layers), int(capacity)))
 
 
 def lava_cascade_step(desc: LayerDesc, layer: int, n: int, k_new: torch.Tensor, v_new: torch.Tensor,
@@ -344,7 +437,8 @@ def lava_cascade_step(desc: LayerDesc, layer: int, n: int, k_new: torch.Tensor, 
     _dev(k_new, "k_new", desc.torch_dtype), _dev(v_new, "v_new", desc.torch_dtype)
     _dev(scores_new, "scores_new", torch.float32)
     if workspace is None:
-        workspace = torch.empty(max(lava_cascade_workspace_bytes(desc, n), 256), dtype=torch.uint8, device=k_new.device)
+        need = lava_cascade_workspace_bytes(desc, n, state.n_layers, state.capacity)
+        workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=k_new.device)
     st = lib.lava_cascade_step(ctypes.byref(desc), int(layer), int(n), _ptr(k_new), _ptr(v_new), _ptr(scores_new),
                                _ptr(state.e), int(total_budget), ctypes.cast(state.layers, ctypes.c_void_p),
                                _ptr(state.budgets), _ptr(workspace), workspace.numel(), _stream(stream))

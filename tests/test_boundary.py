@@ -204,5 +204,61 @@ def test_cascade_and_packed_compaction_argument_errors():
     broken = lava.CascadeLayer.from_buffer_copy(layer)
     broken.pos[1] = None
     assert step(lay=broken) == lava.LAVA_ERR_INVALID_ARG
-    assert lava.lava_cascade_workspace_bytes(d, n) == lava.lava_select_workspace_bytes(8 * n)
-    assert lava.lava_cascade_workspace_bytes(d, 16) == 0
+    assert lava.lava_cascade_workspace_bytes(d, n, 1, 8192) == lava.lava_select_workspace_bytes(8 * n)
+    assert lava.lava_cascade_workspace_bytes(d, n, 5, 8192) == 5 * lava.lava_select_workspace_bytes(8 * n)
+    assert lava.lava_cascade_workspace_bytes(d, n, 2, 16 * n) == 2 * lava.lava_select_workspace_bytes(16 * n)
+    assert lava.lava_cascade_workspace_bytes(d, 16, 1, 8192) == 0
+    assert lava.lava_cascade_workspace_bytes(d, n, 0, 8192) == 0
+    assert step(layer_idx=0, wsb=lava.lava_select_workspace_bytes(8 * n) - 1) == lava.LAVA_ERR_WORKSPACE
+
+
+def test_batch_select_and_compact_argument_errors():
+    L = lava.lib
+    big = 1 << 40
+    good = lava.SelectProblem(0x10000, None, 8 * 1024, 100, None, 0x10000, 0x10000, 0x10000, None)
+
+    def sel(problems, nh=8, widest=8 * 1024, ws=FAKE, wsb=big):
+        table = (lava.SelectProblem * max(len(problems), 1))(*problems)
+        return L.lava_select_topk_batch(nh, len(problems), ctypes.cast(table, ctypes.c_void_p), widest, ws, wsb, None)
+
+    def changed(**kw):
+        p = lava.SelectProblem.from_buffer_copy(good)
+        for k, v in kw.items():
+            setattr(p, k, v)
+        return p
+
+    assert sel([]) == lava.LAVA_ERR_INVALID_ARG
+    assert L.lava_select_topk_batch(8, 1, None, 1024, FAKE, big, None) == lava.LAVA_ERR_INVALID_ARG
+    assert sel([good, changed(budget=8 * 1024 + 1)]) == lava.LAVA_ERR_BUDGET       # any row of the table is checked
+    assert sel([good, changed(scores=None)]) == lava.LAVA_ERR_INVALID_ARG
+    assert sel([good, changed(total_entries=1001)]) == lava.LAVA_ERR_SHAPE         # equal segments
+    assert sel([good, changed(total_entries=16 * 1024)]) == lava.LAVA_ERR_SHAPE    # wider than the stated maximum
+    assert sel([good], nh=65) == lava.LAVA_ERR_SHAPE
+    assert sel([good, good], ws=None) == lava.LAVA_ERR_WORKSPACE
+    one = lava.lava_select_workspace_bytes(8 * 1024)
+    assert lava.lava_select_batch_workspace_bytes(3, 8 * 1024) == 3 * one
+    assert lava.lava_select_batch_workspace_bytes(0, 8 * 1024) == 0
+    assert sel([good, good, good], wsb=3 * one - 1) == lava.LAVA_ERR_WORKSPACE
+    assert L.lava_select_batch_status(None, 2, 1024, None) == lava.LAVA_ERR_INVALID_ARG
+    assert L.lava_select_batch_status(FAKE, 0, 1024, None) == lava.LAVA_ERR_INVALID_ARG
+
+    d = _desc()
+    okc = lava.CompactProblem(1024, None, 0x10000, 0x10000, None, 0x10000, 0x10000, 0, 0x10000, 0x10000, None)
+
+    def cmp(problems):
+        table = (lava.CompactProblem * max(len(problems), 1))(*problems)
+        return L.lava_compact_batch(ctypes.byref(d), len(problems), ctypes.cast(table, ctypes.c_void_p), None)
+
+    def cchanged(**kw):
+        p = lava.CompactProblem.from_buffer_copy(okc)
+        for k, v in kw.items():
+            setattr(p, k, v)
+        return p
+
+    assert cmp([]) == lava.LAVA_ERR_INVALID_ARG
+    assert cmp([okc, okc]) == lava.LAVA_OK                                          # capacities 0: nothing launched
+    assert cmp([okc, cchanged(capacity=8 * 1024 + 1)]) == lava.LAVA_ERR_BUDGET      # dense source: H_kv * n rows
+    assert cmp([okc, cchanged(src_offsets=0x10000, capacity=1025)]) == lava.LAVA_ERR_BUDGET   # packed source: pool rows
+    assert cmp([okc, cchanged(k_out=None)]) == lava.LAVA_ERR_INVALID_ARG
+    assert cmp([okc, cchanged(k_src=0x10008)]) == lava.LAVA_ERR_INVALID_ARG         # rows move as 16-byte words
+    assert cmp([okc, cchanged(src_rows=0)]) == lava.LAVA_ERR_INVALID_ARG

@@ -1,0 +1,158 @@
+"""Tables of selections / compactions (lava_select_topk_batch, lava_compact_batch) against the oracle.
+
+Every problem of a table is one Alg.-1 selection or compaction, so each must equal the oracle's
+result for that problem alone, bit for bit, whatever else shares the launch.
+"""
+import numpy as np
+import pytest
+import torch
+
+from oracle import lava_oracle as O
+from paper_2509_09754_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lava():
+    from paper_2509_09754_amd import lava as mod
+    assert torch.cuda.is_available()
+    return mod
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def run_select_table(lava, nh, cases, seed):
+    """cases: list of (entries per head, budget, explicit segments?, device budget?)."""
+    dev = "cuda"
+    keep, probs, refs = [], [], []
+    widest = 0
+    for i, (n, budget, ragged, dev_budget) in enumerate(cases):
+        s = synth.random_scores(nh, n, seed + i).ravel()
+        total = s.size
+        if ragged:
+            r = np.random.Generator(np.random.PCG64(seed + 100 + i))
+            cuts = np.sort(r.integers(0, total + 1, nh - 1))
+            offs = np.concatenate([[0], cuts, [total]]).astype(np.int64)
+        else:
+            offs = (np.arange(nh + 1) * n).astype(np.int64)
+        cap = budget
+        bd = None
+        if dev_budget:                       # the device value wins; the host value is the capacity of the outputs
+            cap = min(total, budget + 50)
+            bd = torch.tensor([budget], dtype=torch.int64, device=dev)
+        sc = torch.from_numpy(s).to(dev)
+        t = dict(scores=sc, counts=torch.full((nh,), -7, dtype=torch.int32, device=dev),
+                 offs=torch.full((nh + 1,), -7, dtype=torch.int64, device=dev),
+                 idx=torch.full((max(cap, 1),), -7, dtype=torch.int32, device=dev),
+                 ks=torch.full((max(cap, 1),), -7.0, dtype=torch.float32, device=dev),
+                 seg=torch.from_numpy(offs).to(dev) if ragged else None, bd=bd)
+        keep.append(t)
+        probs.append(lava.select_problem(sc, cap, t["counts"], t["offs"], t["idx"], t["ks"], seg_offsets=t["seg"],
+                                         budget_dev=bd))
+        refs.append((O.select_topk(s.astype(np.float64), offs, budget), s, budget))
+        widest = max(widest, total)
+    ws = lava.lava_select_topk_batch(nh, probs, widest)
+    torch.cuda.synchronize()
+    assert lava.lava_select_batch_status(ws, len(probs), widest) == lava.LAVA_OK
+    for i, (t, ((rc, ro, ri, rs), s, budget)) in enumerate(zip(keep, refs)):
+        assert np.array_equal(t["counts"].cpu().numpy(), rc), i
+        assert np.array_equal(t["offs"].cpu().numpy(), ro), i
+        assert np.array_equal(t["idx"].cpu().numpy()[:budget], ri), i
+        assert np.array_equal(t["ks"].cpu().numpy()[:budget].view(np.uint32),
+                              np.asarray(rs, dtype=np.float32).view(np.uint32)), i
+        if budget < t["idx"].numel():
+            assert torch.all(t["idx"][budget:] == -7), i        # nothing past the survivors
+    return keep
+
+
+def test_select_table_mixed_sizes(lava):
+    say("select batch: 7 problems of mixed size, segments and budget sources in one launch")
+    cases = [(1000, 300, False, False), (17, 17 * 4, False, False), (5000, 1, True, True), (40000, 12345, True, False),
+             (1, 0, False, False), (16384 * 2 + 3, 4000, False, True), (300, 1200, True, False)]
+    run_select_table(lava, 4, cases, 11)
+
+
+def test_select_table_more_problems_than_one_launch_holds(lava):
+    say("select batch: 40 problems (two tables), then problems wide enough to need several launches")
+    r = np.random.Generator(np.random.PCG64(3))
+    cases = [(int(r.integers(1, 3000)), 0, bool(i % 2), bool(i % 3 == 0)) for i in range(40)]
+    cases = [(n, int(r.integers(0, 8 * n + 1)), rg, db) for (n, _, rg, db) in cases]
+    run_select_table(lava, 8, cases, 50)
+    # 6 problems of 64 workgroups each and one of a single workgroup: more than one launch's share
+    wide = [(131072, 4096 + 100 * i, bool(i % 2), True) for i in range(6)] + [(100, 37, False, False)]
+    run_select_table(lava, 8, wide, 70)
+
+
+def test_select_table_equals_single_calls(lava):
+    say("select batch: results identical to one lava_select_topk call per problem, ties included")
+    nh = 8
+    dev = "cuda"
+    r = np.random.Generator(np.random.PCG64(9))
+    probs, outs, singles = [], [], []
+    for i in range(5):
+        n = 3000 + 700 * i
+        s = np.round(r.standard_normal(nh * n) * 4).astype(np.float32)          # heavy ties
+        sc = torch.from_numpy(s).to(dev)
+        budget = 500 + 333 * i
+        o = [torch.empty(nh, dtype=torch.int32, device=dev), torch.empty(nh + 1, dtype=torch.int64, device=dev),
+             torch.empty(budget, dtype=torch.int32, device=dev), torch.empty(budget, dtype=torch.float32, device=dev)]
+        probs.append(lava.select_problem(sc, budget, *o))
+        outs.append((sc, o))
+        singles.append(lava.lava_select_topk(nh, sc, budget))
+    lava.lava_select_topk_batch(nh, probs)
+    torch.cuda.synchronize()
+    for (sc, o), single in zip(outs, singles):
+        for a, b in zip(o, single):
+            assert torch.equal(a, b)
+
+
+def test_compact_table_matches_oracle(lava):
+    say("compact batch: dense and packed sources of different sizes in one launch")
+    dev = "cuda"
+    Hkv, d = 4, 128
+    desc = lava.LayerDesc.make(8, Hkv, d, 8, "bf16")
+    r = np.random.Generator(np.random.PCG64(21))
+    probs, checks, hold = [], [], []
+    for i, n in enumerate([700, 64, 5000, 1]):
+        dense = i % 2 == 0
+        if dense:
+            src_counts = np.full(Hkv, n)
+            src_offs = None
+        else:
+            src_counts = r.integers(0, n + 1, Hkv)
+            src_offs = np.concatenate([[0], np.cumsum(src_counts)]).astype(np.int64)
+        rows = int(src_counts.sum())
+        pool = max(rows, 1) + 3
+        k_src = synth.store(r.standard_normal((pool, d), dtype=np.float32), "bf16")
+        v_src = synth.store(r.standard_normal((pool, d), dtype=np.float32), "bf16")
+        pos_src = r.integers(0, 1 << 20, pool).astype(np.int32)
+        kept = [np.sort(r.choice(c, size=int(r.integers(0, c + 1)), replace=False)) if c else np.zeros(0, dtype=np.int64)
+                for c in src_counts]
+        new_offs = np.concatenate([[0], np.cumsum([len(x) for x in kept])]).astype(np.int64)
+        idx = np.concatenate(kept).astype(np.int32) if new_offs[-1] else np.zeros(1, dtype=np.int32)
+        cap = int(new_offs[-1])
+        starts = np.arange(Hkv) * n if dense else src_offs[:-1]
+        src_row = np.concatenate([starts[g] + kept[g] for g in range(Hkv)]).astype(np.int64)
+        t = dict(k=lava.to_device(k_src, "bf16", dev), v=lava.to_device(v_src, "bf16", dev),
+                 pos=torch.from_numpy(pos_src).to(dev), offs=torch.from_numpy(new_offs).to(dev),
+                 idx=torch.from_numpy(idx).to(dev),
+                 src=None if dense else torch.from_numpy(src_offs).to(dev),
+                 ko=torch.full((cap + 2, d), 5.0, dtype=torch.bfloat16, device=dev),
+                 vo=torch.full((cap + 2, d), 5.0, dtype=torch.bfloat16, device=dev),
+                 po=torch.full((cap + 2,), -3, dtype=torch.int32, device=dev))
+        hold.append(t)
+        probs.append(lava.compact_problem(desc, n if dense else pool, t["k"], t["v"], t["offs"], t["idx"], cap, t["ko"],
+                                          t["vo"], src_offsets=t["src"], pos_src=None if dense else t["pos"],
+                                          pos_out=t["po"]))
+        want_pos = np.concatenate(kept).astype(np.int32) if dense else pos_src[src_row]
+        checks.append((cap, k_src[src_row], v_src[src_row], want_pos))
+    lava.lava_compact_batch(desc, probs)
+    torch.cuda.synchronize()
+    for i, (t, (cap, wk, wv, wp)) in enumerate(zip(hold, checks)):
+        assert np.array_equal(lava.to_host_bits(t["ko"][:cap]), wk), i
+        assert np.array_equal(lava.to_host_bits(t["vo"][:cap]), wv), i
+        assert np.array_equal(t["po"][:cap].cpu().numpy(), wp), i
+        assert torch.all(t["ko"][cap:] == 5.0) and torch.all(t["po"][cap:] == -3), i
