@@ -220,15 +220,24 @@ def ragged_batch(lava, synth, torch, np, dev, args):
     ws_batch = torch.empty(lava.lava_select_batch_workspace_bytes(len(lens), Hkv * max(lens)), dtype=torch.uint8,
                            device=dev)
 
-    def tail_batched(q, k, v):
-        lava.lava_layer_budgets(stat.view(-1, 1), total_b, lo, hi, budgets=budgets)
-        sel, cmp = [], []
+    # the tables hold pointers only: built once per buffer set, as a serving loop would keep them
+    sel = []
+    for b, n in enumerate(lens):
+        a0, a1 = int(starts[b]) * Hkv, int(starts[b + 1]) * Hkv
+        sel.append(lava.select_problem(scores[a0:a1], B, counts[b], offs[b], idx[b], kept[b], budget_dev=budgets[b]))
+    sel_table = (lava.SelectProblem * len(lens))(*sel)
+    cmp_tables = []
+    for _, k, v in sets:
+        cmp = []
         for b, n in enumerate(lens):
             a0, a1 = int(starts[b]) * Hkv, int(starts[b + 1]) * Hkv
-            sel.append(lava.select_problem(scores[a0:a1], B, counts[b], offs[b], idx[b], kept[b], budget_dev=budgets[b]))
             cmp.append(lava.compact_problem(desc, n, k[a0:a1], v[a0:a1], offs[b], idx[b], B, k_hat[b], v_hat[b]))
-        lava.lava_select_topk_batch(Hkv, sel, Hkv * max(lens), workspace=ws_batch)
-        lava.lava_compact_batch(desc, cmp)
+        cmp_tables.append((lava.CompactProblem * len(lens))(*cmp))
+
+    def tail_batched(i):
+        lava.lava_layer_budgets(stat.view(-1, 1), total_b, lo, hi, budgets=budgets)
+        lava.lava_select_topk_batch(Hkv, sel_table, Hkv * max(lens), workspace=ws_batch)
+        lava.lava_compact_batch(desc, cmp_tables[i % n_sets])
 
     def tail(q, k, v):
         lava.lava_layer_budgets(stat.view(-1, 1), total_b, lo, hi, budgets=budgets)
@@ -241,7 +250,7 @@ def ragged_batch(lava, synth, torch, np, dev, args):
     def step_batched(i):
         q, k, v = sets[i % n_sets]
         lava.lava_window_scores(desc, lens, q, k, v, scores=scores, vbar=vbar, layer_stat=stat, workspace=ws)
-        tail_batched(q, k, v)
+        tail_batched(i)
 
     def step_one_by_one(i):
         q, k, v = sets[i % n_sets]

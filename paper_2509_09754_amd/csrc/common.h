@@ -56,8 +56,13 @@ struct SweepPlan {
   int vnorm_tiles_per_block;
   int blocks_x_bound, vnorm_blocks_bound;   // upper bounds of blocks_x / vnorm_blocks for any shorter sequence
   bool fused_pool;     // the scores kernel also pools, scales and forms the layer statistic
+  bool narrow;         // 4-wavefront workgroups, two per CU (launches of several rounds of workgroups)
 };
-SweepPlan make_sweep_plan(const lava_layer_desc& d, int64_t n);
+// batch_tokens: tokens of all sequences that share the launches (0 or n: the sequence is alone);
+// narrow: ask for the two-per-CU shape (ignored where the kernels have only one shape)
+SweepPlan make_sweep_plan(const lava_layer_desc& d, int64_t n, int64_t batch_tokens = 0, bool narrow = false);
+bool sweep_has_narrow_shape(const lava_layer_desc& d);
+int sweep_device_wgs();   // compute units of the current device
 
 // Workspace of lava_window_scores for one sequence (all offsets 256-byte aligned).
 struct ScoreWorkspace {

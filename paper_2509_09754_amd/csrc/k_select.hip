@@ -85,9 +85,9 @@ __device__ __forceinline__ long long effective_budget(long long budget, const in
 
 // Chunk -> registers: coalesced reads through shared memory, then 16 consecutive entries per lane
 // (flat order inside the workgroup = lane order, which the ordered write needs).
-__device__ __forceinline__ void load_chunk(const float* __restrict__ scores, long long total,
+__device__ __forceinline__ void load_chunk(int bx, const float* __restrict__ scores, long long total,
                                            SelShared& sh, float (&val)[kSelPerThread]) {
-  const long long base = (long long)blockIdx.x * kSelChunk;
+  const long long base = (long long)bx * kSelChunk;
   float tmp[kSelPerThread];
 #pragma unroll
   for (int j = 0; j < kSelPerThread; ++j) {        // all loads in flight before the first use
@@ -116,13 +116,13 @@ template <int PASS> struct Digit {
 // Histogram of digit PASS over this workgroup's keys that match the prefix; merged into the
 // global histogram with integer atomics.
 template <int PASS>
-__device__ __forceinline__ void hist_phase(const float (&val)[kSelPerThread], long long total,
+__device__ __forceinline__ void hist_phase(int bx, const float (&val)[kSelPerThread], long long total,
                                            unsigned int prefix, SelShared& sh,
                                            unsigned int* __restrict__ ghist) {
   using Dg = Digit<PASS>;
   for (int i = threadIdx.x; i < Dg::kNum; i += kSelThreads) sh.hist[i] = 0u;
   __syncthreads();
-  const long long p0 = (long long)blockIdx.x * kSelChunk + threadIdx.x * kSelPerThread;
+  const long long p0 = (long long)bx * kSelChunk + threadIdx.x * kSelPerThread;
   // neighbouring entries mostly share a digit (pooling makes plateaus, magnitudes vary slowly), so a
   // lane adds one count per run of equal digits instead of one per entry
   unsigned int run_digit = 0xffffffffu, run_len = 0u;
@@ -200,10 +200,10 @@ __device__ __forceinline__ Pick pick_phase(const unsigned int* __restrict__ ghis
 }
 
 // Keys above / equal to the threshold in this workgroup, published for the other workgroups.
-__device__ __forceinline__ void count_phase(const float (&val)[kSelPerThread], long long total,
+__device__ __forceinline__ void count_phase(int bx, const float (&val)[kSelPerThread], long long total,
                                             unsigned int T, SelShared& sh, unsigned int* __restrict__ blk,
                                             int n_blocks, unsigned int& gt_mask, unsigned int& eq_mask) {
-  const long long p0 = (long long)blockIdx.x * kSelChunk + threadIdx.x * kSelPerThread;
+  const long long p0 = (long long)bx * kSelChunk + threadIdx.x * kSelPerThread;
   gt_mask = 0u;
   eq_mask = 0u;
 #pragma unroll
@@ -222,17 +222,17 @@ __device__ __forceinline__ void count_phase(const float (&val)[kSelPerThread], l
   if (threadIdx.x == 0) {
     unsigned int tot = 0u;
     for (int i = 0; i < kSelThreads / 64; ++i) tot += sh.wave[i];
-    st_dev(&blk[blockIdx.x], tot >> 16);
-    st_dev(&blk[n_blocks + blockIdx.x], tot & 0xffffu);
+    st_dev(&blk[bx], tot >> 16);
+    st_dev(&blk[n_blocks + bx], tot & 0xffffu);
   }
   __syncthreads();
 }
 
 // Sums of (gt, eq) over the workgroups before this one.
-__device__ __forceinline__ void prefix_phase(const unsigned int* __restrict__ blk, int n_blocks,
+__device__ __forceinline__ void prefix_phase(int bx, const unsigned int* __restrict__ blk, int n_blocks,
                                              SelShared& sh, long long& gt_before, long long& eq_before) {
   unsigned long long acc = 0ull;   // gt in the high word, eq in the low word (each < 2^31)
-  for (int b = threadIdx.x; b < (int)blockIdx.x; b += kSelThreads)
+  for (int b = threadIdx.x; b < bx; b += kSelThreads)
     acc += ((unsigned long long)ld_dev(&blk[b]) << 32) | (unsigned long long)ld_dev(&blk[n_blocks + b]);
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
@@ -247,7 +247,7 @@ __device__ __forceinline__ void prefix_phase(const unsigned int* __restrict__ bl
 
 // Ordered write of this workgroup's survivors; survivors per head are added to head_counts and the
 // head offsets are written by the lanes that own the first entry of each head.
-__device__ __forceinline__ void write_phase(const float (&val)[kSelPerThread], long long total, int n_heads,
+__device__ __forceinline__ void write_phase(int bx, const float (&val)[kSelPerThread], long long total, int n_heads,
                                             const int64_t* __restrict__ seg_offsets, unsigned int gt_mask,
                                             unsigned int eq_mask, long long need, long long capacity,
                                             long long gt_blocks_before, long long eq_blocks_before,
@@ -277,10 +277,10 @@ __device__ __forceinline__ void write_phase(const float (&val)[kSelPerThread], l
   long long gt_before = gt_blocks_before + (long long)(excl >> 16);
   long long eq_before = eq_blocks_before + (long long)(excl & 0xffffu);
 
-  const long long first = (long long)blockIdx.x * kSelChunk + threadIdx.x * kSelPerThread;
+  const long long first = (long long)bx * kSelChunk + threadIdx.x * kSelPerThread;
   // head_offsets[h] = survivors before the first entry of head h: written by the lane that owns that
   // entry; segments starting at or beyond the end (empty trailing heads) and the two ends by lane 0
-  if (blockIdx.x == 0 && threadIdx.x == 0) {
+  if (bx == 0 && threadIdx.x == 0) {
     const long long kept = need_total;
     head_offsets[0] = 0;
     head_offsets[n_heads] = kept;
@@ -349,13 +349,14 @@ __device__ __forceinline__ void grid_sync(SelectState* __restrict__ st, unsigned
   __syncthreads();
 }
 
-// One launch serves up to kMaxSelProblems independent selections (blockIdx.y picks the problem):
-// the table travels in the kernel arguments.  Every problem has its own histograms, barrier
-// counter and per-workgroup counts in its own region of the workspace, so problems never wait
-// for each other; workgroups beyond a problem's own count return at once.
+// One launch serves up to kMaxSelProblems independent selections: the table travels in the kernel
+// arguments, and the workgroups of all problems are numbered through (first_block), so every
+// workgroup of the grid has work.  Every problem has its own histograms, barrier counter and
+// per-workgroup counts in its own region of the workspace, so problems never wait for each other.
 struct SelectBatch {
   int n_heads;
   int n_problems;
+  int first_block[kMaxSelProblems + 1];   // workgroups of problem p: first_block[p] .. first_block[p + 1] - 1
   char* ws;                      // region of problem p at ws + p * ws_stride
   size_t ws_stride, off_hist, off_state, off_blk;
   int blk_stride;                // n_blocks the regions were laid out for
@@ -365,6 +366,13 @@ struct SelectBatch {
 __device__ __forceinline__ int problem_blocks(const lava_select_problem& pr) {
   const long long nb = (pr.total_entries + kSelChunk - 1) / kSelChunk;
   return nb < 1 ? 1 : (int)nb;
+}
+
+// Problem of this workgroup (uniform over the workgroup).
+__device__ __forceinline__ int problem_of_block(const SelectBatch& a) {
+  int p = 0;
+  while (p + 1 < a.n_problems && (int)blockIdx.x >= a.first_block[p + 1]) ++p;
+  return p;
 }
 
 __global__ void __launch_bounds__(kSelThreads) sel_init_kernel(const SelectBatch a) {
@@ -393,10 +401,11 @@ __device__ __forceinline__ long long device_total(long long bound, const int64_t
 
 // The whole selection in one launch.
 __global__ void __launch_bounds__(kSelThreads) sel_fused_kernel(const SelectBatch a) {
-  const lava_select_problem pr = a.p[blockIdx.y];
+  const int prob = problem_of_block(a);
+  const lava_select_problem pr = a.p[prob];
   const unsigned int nb = (unsigned int)problem_blocks(pr);
-  if (blockIdx.x >= nb) return;
-  char* region = a.ws + blockIdx.y * a.ws_stride;
+  const int bx = (int)blockIdx.x - a.first_block[prob];
+  char* region = a.ws + prob * a.ws_stride;
   unsigned int* hist = reinterpret_cast<unsigned int*>(region + a.off_hist);
   SelectState* st = reinterpret_cast<SelectState*>(region + a.off_state);
   unsigned int* blk = reinterpret_cast<unsigned int*>(region + a.off_blk);
@@ -408,28 +417,28 @@ __global__ void __launch_bounds__(kSelThreads) sel_fused_kernel(const SelectBatc
   __shared__ SelShared sh;
   const long long total = device_total(pr.total_entries, seg_offsets, n_heads);
   float val[kSelPerThread];
-  load_chunk(scores, total, sh, val);
+  load_chunk(bx, scores, total, sh, val);
   Pick pk;
   pk.prefix = 0u;
   pk.need = effective_budget(budget, pr.budget_dev, total);
   const long long kept_total = pk.need;
 
-  hist_phase<0>(val, total, pk.prefix, sh, hist);
+  hist_phase<0>(bx, val, total, pk.prefix, sh, hist);
   grid_sync(st, 1u, nb);
   pk = pick_phase<0>(hist, pk, sh);
-  hist_phase<1>(val, total, pk.prefix, sh, hist + kBins);
+  hist_phase<1>(bx, val, total, pk.prefix, sh, hist + kBins);
   grid_sync(st, 2u, nb);
   pk = pick_phase<1>(hist + kBins, pk, sh);
-  hist_phase<2>(val, total, pk.prefix, sh, hist + 2 * kBins);
+  hist_phase<2>(bx, val, total, pk.prefix, sh, hist + 2 * kBins);
   grid_sync(st, 3u, nb);
   pk = pick_phase<2>(hist + 2 * kBins, pk, sh);
 
   unsigned int gt_mask, eq_mask;
-  count_phase(val, total, pk.prefix, sh, blk, a.blk_stride, gt_mask, eq_mask);
+  count_phase(bx, val, total, pk.prefix, sh, blk, a.blk_stride, gt_mask, eq_mask);
   grid_sync(st, 4u, nb);
   long long gt_before, eq_before;
-  prefix_phase(blk, a.blk_stride, sh, gt_before, eq_before);
-  write_phase(val, total, n_heads, seg_offsets, gt_mask, eq_mask, pk.need, budget, gt_before, eq_before,
+  prefix_phase(bx, blk, a.blk_stride, sh, gt_before, eq_before);
+  write_phase(bx, val, total, n_heads, seg_offsets, gt_mask, eq_mask, pk.need, budget, gt_before, eq_before,
               kept_total, sh, pr.head_counts, pr.head_offsets, pr.kept_idx, pr.kept_scores);
 }
 
@@ -437,10 +446,10 @@ __global__ void __launch_bounds__(kSelThreads) sel_fused_kernel(const SelectBatc
 // for a problem too large to keep its whole grid resident.  STEP 0..2: histogram pass STEP; 3: counts; 4: write.
 template <int STEP>
 __global__ void __launch_bounds__(kSelThreads) sel_step_kernel(const SelectBatch a) {
-  const lava_select_problem pr = a.p[blockIdx.y];
-  const int nb = problem_blocks(pr);
-  if ((int)blockIdx.x >= nb) return;
-  char* region = a.ws + blockIdx.y * a.ws_stride;
+  const int prob = problem_of_block(a);
+  const lava_select_problem pr = a.p[prob];
+  const int bx = (int)blockIdx.x - a.first_block[prob];
+  char* region = a.ws + prob * a.ws_stride;
   unsigned int* hist = reinterpret_cast<unsigned int*>(region + a.off_hist);
   unsigned int* blk = reinterpret_cast<unsigned int*>(region + a.off_blk);
   const int64_t* __restrict__ seg_offsets = pr.seg_offsets;
@@ -450,7 +459,7 @@ __global__ void __launch_bounds__(kSelThreads) sel_step_kernel(const SelectBatch
   {
     const long long total = device_total(pr.total_entries, seg_offsets, n_heads);
     float val[kSelPerThread];
-    load_chunk(pr.scores, total, sh, val);
+    load_chunk(bx, pr.scores, total, sh, val);
     Pick pk;
     pk.prefix = 0u;
     pk.need = effective_budget(budget, pr.budget_dev, total);
@@ -459,15 +468,15 @@ __global__ void __launch_bounds__(kSelThreads) sel_step_kernel(const SelectBatch
     if constexpr (STEP >= 2) pk = pick_phase<1>(hist + kBins, pk, sh);
     if constexpr (STEP >= 3) pk = pick_phase<2>(hist + 2 * kBins, pk, sh);
     if constexpr (STEP <= 2) {
-      hist_phase<STEP>(val, total, pk.prefix, sh, hist + STEP * kBins);
+      hist_phase<STEP>(bx, val, total, pk.prefix, sh, hist + STEP * kBins);
     } else {
       unsigned int gt_mask, eq_mask;
       // counts are recomputed in the write step (cheap) so that both steps share count_phase
-      count_phase(val, total, pk.prefix, sh, blk, a.blk_stride, gt_mask, eq_mask);
+      count_phase(bx, val, total, pk.prefix, sh, blk, a.blk_stride, gt_mask, eq_mask);
       if constexpr (STEP == 4) {
         long long gt_before, eq_before;
-        prefix_phase(blk, a.blk_stride, sh, gt_before, eq_before);
-        write_phase(val, total, n_heads, seg_offsets, gt_mask, eq_mask, pk.need, budget, gt_before, eq_before,
+        prefix_phase(bx, blk, a.blk_stride, sh, gt_before, eq_before);
+        write_phase(bx, val, total, n_heads, seg_offsets, gt_mask, eq_mask, pk.need, budget, gt_before, eq_before,
                     kept_total, sh, pr.head_counts, pr.head_offsets, pr.kept_idx, pr.kept_scores);
       }
     }
@@ -492,8 +501,10 @@ static int fused_capacity() {
 }
 
 // Selections of a batch: consecutive problems are packed into launches of the fused kernel as long
-// as their workgroups fit into half of the device together (they all have to be resident: each
-// problem meets at its own grid barriers); a problem that does not fit alone runs as step launches.
+// as their workgroups fit on the device together (they all have to be resident: each problem meets
+// at its own grid barriers; should another stream hold compute units for so long that a bounded
+// wait gives up, the status call reports it).  A single problem only takes the fused path up to half
+// of the device and runs as step launches beyond that.
 int32_t launch_select_batch(int n_heads, int n_problems, const lava_select_problem* problems, int64_t max_total,
                             void* ws, hipStream_t s) {
   const SelectWorkspace w = make_select_workspace(max_total);
@@ -505,31 +516,32 @@ int32_t launch_select_batch(int n_heads, int n_problems, const lava_select_probl
   a.off_blk = w.off_blk;
   a.blk_stride = w.n_blocks;
   const dim3 block(kSelThreads);
-  const int cap = fused_capacity() / 2;
+  const int cap = fused_capacity();
   int first = 0;
   while (first < n_problems) {
-    int count = 0, blocks = 0, widest = 0;
+    int count = 0, blocks = 0;
     while (first + count < n_problems && count < kMaxSelProblems) {
       const int64_t t = problems[first + count].total_entries;
       const int nb = (int)((t + kSelChunk - 1) / kSelChunk) < 1 ? 1 : (int)((t + kSelChunk - 1) / kSelChunk);
       if (count > 0 && blocks + nb > cap) break;
+      a.first_block[count] = blocks;
       blocks += nb;
-      if (nb > widest) widest = nb;
       a.p[count] = problems[first + count];
       ++count;
     }
     a.n_problems = count;
+    a.first_block[count] = blocks;
     a.ws = static_cast<char*>(ws) + (size_t)first * w.bytes;
     {
       ProfScope ps(KID_SEL_INIT, s);
       hipLaunchKernelGGL(sel_init_kernel, dim3(count), block, 0, s, a);
     }
-    if (blocks <= cap) {
+    if (count > 1 || blocks <= cap / 2) {
       ProfScope ps(KID_SEL_FUSED, s);
-      hipLaunchKernelGGL(sel_fused_kernel, dim3(widest, count), block, 0, s, a);
+      hipLaunchKernelGGL(sel_fused_kernel, dim3(blocks), block, 0, s, a);
     } else {                                               // a single problem wider than the device allows
       ProfScope ps(KID_SEL_STEPS, s);
-      const dim3 grid(widest, count);
+      const dim3 grid(blocks);
       hipLaunchKernelGGL(sel_step_kernel<0>, grid, block, 0, s, a);
       hipLaunchKernelGGL(sel_step_kernel<1>, grid, block, 0, s, a);
       hipLaunchKernelGGL(sel_step_kernel<2>, grid, block, 0, s, a);

@@ -30,16 +30,28 @@ namespace lava {
 // "last workgroup done" tickets in the workspace (zeroed by the first kernel of every call)
 constexpr int kCounterPool = 0;                         // poolstat: one two-level ticket
 
-// Wavefronts per workgroup and ring depth.  The ring takes 128 KiB of LDS in all.  Kernels whose
-// registers fit twice into a SIMD run 8 wavefronts (2 per SIMD: one wavefront's exponentials
-// overlap the other's MFMAs and waits) with a shallower ring; the f32 / d_h 128 kernels need more
-// than 256 registers and stay at 4 wavefronts.
-template <int DT, int D>
+// Wavefronts per workgroup and ring depth.  Kernels whose registers fit twice into a SIMD come in two
+// shapes.  Wide (W = 8): 8 wavefronts (2 per SIMD: one wavefront's exponentials overlap the
+// other's MFMAs and waits), a 128 KiB ring, so a CU holds one workgroup: the shape for a launch
+// whose workgroups all start together (one sequence).  Narrow (W = 4): 4 wavefronts and a 64 KiB
+// ring, two workgroups per CU with the same registers, wavefronts and bytes in flight per CU: in a
+// launch of several rounds of workgroups (a batch) the two run out of phase, and one's set-up and
+// tail hide behind the other's streaming.  The f32 / d_h 128 kernels need more than 256 registers:
+// 4 wavefronts and the whole ring in either case.
+constexpr int kFusedTilesWide = 128;
+constexpr int kFusedTilesNarrow = 64;
+template <int DT, int D, int W>
 struct Shape {
-  static constexpr int kWaves = (DT == LAVA_F32 && D == 128) ? 4 : 8;
+  static_assert(W == 4 || W == 8, "wavefronts per workgroup");
+  static constexpr bool kBig = DT == LAVA_F32 && D == 128;
+  static constexpr bool kNarrow = W == 4 && !kBig;
+  static constexpr int kWaves = kBig ? 4 : W;
   static constexpr int kThreads = kWaves * 64;
-  static constexpr int kStagesRaw = (128 * 1024) / (kWaves * Tile<DT, D>::kTileBytes);
+  static constexpr int kMinWaves = kNarrow ? 2 : 1;      // per SIMD, for the register allocator
+  static constexpr int kRingBytes = kNarrow ? 64 * 1024 : 128 * 1024;
+  static constexpr int kStagesRaw = kRingBytes / (kWaves * Tile<DT, D>::kTileBytes);
   static constexpr int kStages = kStagesRaw > 4 ? 4 : kStagesRaw;
+  static constexpr int kFusedTiles = kNarrow ? kFusedTilesNarrow : kFusedTilesWide;   // span of raw scores kept in LDS
   static_assert(kStages >= 2 && kStages <= kMaxRingStages, "ring depth");
 };
 
@@ -94,8 +106,8 @@ __device__ __forceinline__ void entropy_finish(double acc_s, double acc_t, doubl
 // Row r may see keys 0 .. n - w + r only (each window row is normalised over the keys up to
 // and including its own position).
 // ------------------------------------------------------------------------------------------
-template <int DT, int D, int GT>
-__global__ void __launch_bounds__((Shape<DT, D>::kThreads))
+template <int DT, int D, int GT, int W>
+__global__ void __launch_bounds__((Shape<DT, D, W>::kThreads), (Shape<DT, D, W>::kMinWaves))
 stats_kernel(const SweepArgs a) {
   using T = Tile<DT, D>;
   const SweepSeq sq = a.s[blockIdx.z];
@@ -107,8 +119,8 @@ stats_kernel(const SweepArgs a) {
       static_cast<const u32x4*>(a.q_win) + (long long)(a.first_seq + blockIdx.z) * a.H * w * T::kCpr;
   const u32x4* __restrict__ k = static_cast<const u32x4*>(a.k) + (long long)a.H_kv * sq.tok * T::kCpr;
   float2* __restrict__ stat_part = reinterpret_cast<float2*>(a.ws + sq.ws_off + a.off_stat_part);
-  constexpr int kWaves = Shape<DT, D>::kWaves;
-  constexpr int kStages = Shape<DT, D>::kStages;
+  constexpr int kWaves = Shape<DT, D, W>::kWaves;
+  constexpr int kStages = Shape<DT, D, W>::kStages;
   __shared__ u32x4 s_tile[kWaves][kStages][T::kTileChunks];
   __shared__ float2 s_red[kWaves][kMaxChunkHeads * 32];   // [wave][head*32+row]
 
@@ -235,12 +247,11 @@ stats_kernel(const SweepArgs a) {
 // caller-supplied log-sum-exp.
 // ------------------------------------------------------------------------------------------
 //
-// FUSED (all heads of the group in one workgroup, at most kFusedTiles tiles per workgroup): the
+// FUSED (all heads of the group in one workgroup, at most Shape::kFusedTiles tiles per workgroup): the
 // workgroup keeps the raw scores of its key span in LDS, recomputes one tile on either side of
 // the span (the pooling halo; 2 extra tiles per workgroup instead of a trip through HBM and
 // another launch), and finishes the scores itself: max-pool, value factor, +inf for the window
 // entries, and the layer statistic.  Otherwise the raw scores go to s_raw for poolstat_kernel.
-constexpr int kFusedTiles = 128;
 constexpr int kPoolMaxHalf = 7;   // pooling kernels up to 15
 
 struct PoolArgs {
@@ -254,8 +265,8 @@ struct PoolArgs {
   uint32_t* counters;
 };
 
-template <int DT, int D, int GT, bool FUSED>
-__global__ void __launch_bounds__((Shape<DT, D>::kThreads))
+template <int DT, int D, int GT, bool FUSED, int W>
+__global__ void __launch_bounds__((Shape<DT, D, W>::kThreads), (Shape<DT, D, W>::kMinWaves))
 scores_kernel(const SweepArgs a) {
   using T = Tile<DT, D>;
   const SweepSeq sq = a.s[blockIdx.z];
@@ -280,11 +291,11 @@ scores_kernel(const SweepArgs a) {
   pa.layer_stat = a.layer_stat + seq;
   pa.ent_part = reinterpret_cast<double2*>(region + a.off_ent_part);
   pa.counters = reinterpret_cast<uint32_t*>(region + a.off_counter);
-  constexpr int kWaves = Shape<DT, D>::kWaves;
-  constexpr int kStages = Shape<DT, D>::kStages;
+  constexpr int kWaves = Shape<DT, D, W>::kWaves;
+  constexpr int kStages = Shape<DT, D, W>::kStages;
   __shared__ u32x4 s_tile[kWaves][kStages][T::kTileChunks];
   __shared__ __attribute__((aligned(16))) float s_bias[GT * 32];
-  __shared__ __attribute__((aligned(16))) float s_span[FUSED ? (kFusedTiles + 2) * kTileKeys : 4];   // raw scores of the span + halo tiles
+  __shared__ __attribute__((aligned(16))) float s_span[FUSED ? (Shape<DT, D, W>::kFusedTiles + 2) * kTileKeys : 4];   // raw scores of the span + halo tiles
 
   const int lane = threadIdx.x & 63, wave = wave_index();
   const int g = blockIdx.y / n_chunks, chunk = blockIdx.y % n_chunks;
@@ -295,11 +306,11 @@ scores_kernel(const SweepArgs a) {
 
   float vb = 0.0f;   // this thread's share of the head's value-norm partials (reduced after the sweep)
   if constexpr (FUSED) {
-    for (int i = threadIdx.x; i < pa.vnorm_blocks; i += Shape<DT, D>::kThreads)
+    for (int i = threadIdx.x; i < pa.vnorm_blocks; i += Shape<DT, D, W>::kThreads)
       vb = fmaxf(vb, pa.vnorm_part[(long long)g * pa.vnorm_blocks + i]);
   }
 
-  constexpr int kThreads = Shape<DT, D>::kThreads;
+  constexpr int kThreads = Shape<DT, D, W>::kThreads;
   constexpr int kRows = GT * 32;
   constexpr int kSlices = kThreads / kRows;
   __shared__ float2 s_merge[kThreads];
@@ -492,7 +503,7 @@ scores_kernel(const SweepArgs a) {
     static_assert(kPoolMaxHalf <= kPer - 1, "taps must stay inside the 24 values read");
     const float* out_head = pa.scores + (long long)g * n;
     for (long long base = p_begin + (long long)threadIdx.x * kPer; base < p_end;
-         base += (long long)Shape<DT, D>::kThreads * kPer) {
+         base += (long long)Shape<DT, D, W>::kThreads * kPer) {
       float raw[3 * kPer];
       const float4* src = reinterpret_cast<const float4*>(&s_span[(int)(base - kPer - span0)]);
 #pragma unroll
@@ -536,7 +547,7 @@ scores_kernel(const SweepArgs a) {
     // the workgroup that owns the head's last prefix tile also writes the window entries
     if (t_begin < t_end && t_end == n_tiles && threadIdx.x < (unsigned)w)
       pa.scores[(long long)g * n + n_prefix + threadIdx.x] = INFINITY;
-    entropy_finish<Shape<DT, D>::kThreads>(acc_s, acc_t, pa.ent_part, pa.counters, sq.blocks_x * gridDim.y,
+    entropy_finish<Shape<DT, D, W>::kThreads>(acc_s, acc_t, pa.ent_part, pa.counters, sq.blocks_x * gridDim.y,
                                            blockIdx.y * sq.blocks_x + blockIdx.x,
                                            (double)gridDim.y * (double)n_prefix, pa.layer_stat, s_s, s_t,
                                            &s_last);
@@ -726,7 +737,11 @@ static int compute_units() {
   return cached;
 }
 
-SweepPlan make_sweep_plan(const lava_layer_desc& d, int64_t n) {
+int sweep_device_wgs() { return compute_units(); }
+
+bool sweep_has_narrow_shape(const lava_layer_desc& d) { return !(d.dtype == LAVA_F32 && d.head_dim == 128); }
+
+SweepPlan make_sweep_plan(const lava_layer_desc& d, int64_t n, int64_t batch_tokens, bool narrow) {
   SweepPlan p;
   const int G = d.n_q_heads / d.n_kv_heads;
   int gt = kMaxChunkHeads;
@@ -734,37 +749,51 @@ SweepPlan make_sweep_plan(const lava_layer_desc& d, int64_t n) {
   p.chunk_heads = G < gt ? G : gt;
   if (p.chunk_heads == 3) p.chunk_heads = 4;   // kernels are built for 1, 2 and 4 heads per chunk
   p.n_chunks = (G + p.chunk_heads - 1) / p.chunk_heads;
+  p.narrow = narrow && sweep_has_narrow_shape(d);
   const int64_t n_tiles = (n + kTileKeys - 1) / kTileKeys;
-  // One workgroup per compute unit: the sweeps keep the group's query rows in registers and a
-  // 128 KiB tile ring in LDS, so a CU holds exactly one workgroup, and per-workgroup set-up (query
-  // load, partial results) is amortised over as many tiles as possible.
-  int64_t target_wgs = compute_units();
+  // One resident workgroup per slot of the device (one per CU for the wide shape, two for the
+  // narrow one): the sweeps keep the group's query rows in registers and a tile ring in LDS, and
+  // per-workgroup set-up (query load, partial results) is amortised over as many tiles as possible.
+  const int64_t device_wgs = compute_units();
+  int64_t target_wgs = p.narrow ? 2 * device_wgs : device_wgs;
   if (const char* env = getenv("LAVA_SWEEP_WGS")) {      // tuning knob: workgroups per sweep launch
     const long v = atol(env);
     if (v >= 1 && v <= 65536) target_wgs = v;
   }
-  int64_t max_bx = target_wgs / ((int64_t)d.n_kv_heads * p.n_chunks);
+  // a sequence that shares its launches with others gets its share of the device, so that the
+  // batch as a whole is cut into the longest runs the kernels allow
+  const bool shared = batch_tokens > n;
+  const auto share = [&](int64_t wgs) { return shared ? (wgs * n + batch_tokens - 1) / batch_tokens : wgs; };
+  int64_t max_bx = share(target_wgs) / ((int64_t)d.n_kv_heads * p.n_chunks);
   if (max_bx < 1) max_bx = 1;
   int64_t tpb = (n_tiles + max_bx - 1) / max_bx;
   if (tpb < 16) tpb = 16;
   // all heads of a group in one workgroup -> the scores kernel can finish the scores itself, which
-  // needs the workgroup's span of raw scores in LDS: at most kFusedTiles tiles per workgroup
+  // needs the workgroup's span of raw scores in LDS: a bounded number of tiles per workgroup
   p.fused_pool = p.n_chunks == 1;
-  if (p.fused_pool && tpb > kFusedTiles) tpb = kFusedTiles;
+  const int64_t fused_cap = p.narrow ? kFusedTilesNarrow : kFusedTilesWide;
+  if (p.fused_pool && tpb > fused_cap) tpb = fused_cap;
   p.tiles_per_block = (int)tpb;
   p.blocks_x = (int)((n_tiles + tpb - 1) / tpb);
-  // bounds that never shrink when n grows: a workspace sized for the longest sequence of a batch
-  // must also hold the (slightly differently split) partials of every shorter one
-  const int64_t capped = (n_tiles + kFusedTiles - 1) / kFusedTiles;
-  p.blocks_x_bound = (int)(max_bx > capped ? max_bx : capped);
-  // value norms: one workgroup per CU as well, at least 8 tiles (one per wavefront) each
-  int64_t vb = target_wgs / d.n_kv_heads;
+  // bounds that hold for either shape, alone or in a batch, and never shrink when n grows: a
+  // workspace sized for the longest sequence of a batch must also hold the (differently split)
+  // partials of every shorter one
+  int64_t bx_alone = 2 * device_wgs / ((int64_t)d.n_kv_heads * p.n_chunks);
+  if (target_wgs / ((int64_t)d.n_kv_heads * p.n_chunks) > bx_alone) bx_alone = target_wgs / ((int64_t)d.n_kv_heads * p.n_chunks);
+  if (bx_alone < 1) bx_alone = 1;
+  const int64_t capped = (n_tiles + kFusedTilesNarrow - 1) / kFusedTilesNarrow;
+  p.blocks_x_bound = (int)(bx_alone > capped ? bx_alone : capped);
+  // value norms: one workgroup per CU for a sequence alone, at least 8 tiles (one per wavefront)
+  // each.  Sequences of a batch keep that cut (no share): the kernel's set-up is short, and many
+  // small workgroups even out the unequal lengths better than few long ones.
+  int64_t vb = (p.narrow ? device_wgs : target_wgs) / d.n_kv_heads;
   if (vb < 1) vb = 1;
   int64_t vtpb = (n_tiles + vb - 1) / vb;
   if (vtpb < 8) vtpb = 8;
   p.vnorm_tiles_per_block = (int)vtpb;
   p.vnorm_blocks = (int)((n_tiles + vtpb - 1) / vtpb);
-  p.vnorm_blocks_bound = (int)vb;
+  const int64_t vb_bound = (target_wgs > device_wgs ? target_wgs : device_wgs) / d.n_kv_heads;
+  p.vnorm_blocks_bound = (int)(vb_bound > 1 ? vb_bound : 1);
   return p;
 }
 
@@ -853,10 +882,16 @@ int32_t launch_stats(const lava_layer_desc& d, const SweepArgs& a, int max_block
                      hipStream_t s) {
   const dim3 grid(max_blocks_x, d.n_kv_heads * p.n_chunks, a.n_seq);
   ProfScope ps(KID_STATS, s);
-#define LAVA_STATS(DTV, DV, GTV) \
-  hipLaunchKernelGGL((stats_kernel<DTV, DV, GTV>), grid, dim3(Shape<DTV, DV>::kThreads), 0, s, a)
+#define LAVA_STATS_W(DTV, DV, GTV, WV) \
+  hipLaunchKernelGGL((stats_kernel<DTV, DV, GTV, WV>), grid, dim3(Shape<DTV, DV, WV>::kThreads), 0, s, a)
+#define LAVA_STATS(DTV, DV, GTV)                                               \
+  do {                                                                         \
+    if (Shape<DTV, DV, 4>::kNarrow && p.narrow) LAVA_STATS_W(DTV, DV, GTV, (Shape<DTV, DV, 4>::kNarrow ? 4 : 8)); \
+    else LAVA_STATS_W(DTV, DV, GTV, 8);                                        \
+  } while (0)
   LAVA_SWEEP_DISPATCH(LAVA_STATS);
 #undef LAVA_STATS
+#undef LAVA_STATS_W
   return launch_status();
 }
 
@@ -871,17 +906,23 @@ int32_t launch_scores(const lava_layer_desc& d, const SweepArgs& a, int max_bloc
     hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)((count + 1023) / 1024)), dim3(256), 0, s,
                        reinterpret_cast<float*>(a.ws + a.s[0].ws_off + a.off_sraw), count);
   }
-#define LAVA_SCORES(DTV, DV, GTV)                                                                       \
-  do {                                                                                                  \
-    if (p.fused_pool)                                                                                   \
-      hipLaunchKernelGGL((scores_kernel<DTV, DV, GTV, true>), grid, dim3(Shape<DTV, DV>::kThreads), 0,  \
-                         s, a);                                                                         \
-    else                                                                                                \
-      hipLaunchKernelGGL((scores_kernel<DTV, DV, GTV, false>), grid, dim3(Shape<DTV, DV>::kThreads), 0, \
-                         s, a);                                                                         \
+#define LAVA_SCORES_W(DTV, DV, GTV, WV)                                                                     \
+  do {                                                                                                      \
+    if (p.fused_pool)                                                                                       \
+      hipLaunchKernelGGL((scores_kernel<DTV, DV, GTV, true, WV>), grid, dim3(Shape<DTV, DV, WV>::kThreads), \
+                         0, s, a);                                                                          \
+    else                                                                                                    \
+      hipLaunchKernelGGL((scores_kernel<DTV, DV, GTV, false, WV>), grid, dim3(Shape<DTV, DV, WV>::kThreads), \
+                         0, s, a);                                                                          \
+  } while (0)
+#define LAVA_SCORES(DTV, DV, GTV)                                               \
+  do {                                                                          \
+    if (Shape<DTV, DV, 4>::kNarrow && p.narrow) LAVA_SCORES_W(DTV, DV, GTV, (Shape<DTV, DV, 4>::kNarrow ? 4 : 8)); \
+    else LAVA_SCORES_W(DTV, DV, GTV, 8);                                        \
   } while (0)
   LAVA_SWEEP_DISPATCH(LAVA_SCORES);
 #undef LAVA_SCORES
+#undef LAVA_SCORES_W
   return launch_status();
 }
 

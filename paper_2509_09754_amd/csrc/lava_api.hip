@@ -1,5 +1,6 @@
 // C ABI of the library: argument checks on the host, then kernel launches on the caller's
 // stream.  Nothing here allocates device memory.
+#include <stdlib.h>
 #include <string.h>
 
 #include <vector>
@@ -160,9 +161,27 @@ int32_t lava_window_scores(const lava_layer_desc* desc, int32_t batch, const int
     a.n_seq = batch - b0 < per_launch ? batch - b0 : per_launch;
     int max_bx = 0, max_vb = 0;
     SweepPlan plan = plan_max;
+    int64_t launch_tokens = 0;
+    for (int i = 0; i < a.n_seq; ++i) launch_tokens += seq_lens[b0 + i];
+    // Several sequences whose workgroups do not all fit on the device at once: the narrow shape
+    // (two workgroups per CU, out of phase) hides the per-workgroup set-up that a launch of
+    // several rounds of one-per-CU workgroups would pay once per round.
+    bool narrow = false;
+    if (a.n_seq > 1) {
+      int64_t wide_wgs = 0;
+      for (int i = 0; i < a.n_seq; ++i)
+        wide_wgs += (int64_t)make_sweep_plan(d, seq_lens[b0 + i], launch_tokens).blocks_x * d.n_kv_heads * plan_max.n_chunks;
+      narrow = wide_wgs > sweep_device_wgs();
+    }
+    if (const char* env = getenv("LAVA_SWEEP_SHAPE")) {      // tuning knob: force one shape
+      if (strcmp(env, "narrow") == 0) narrow = true;
+      else if (strcmp(env, "wide") == 0) narrow = false;
+    }
+    SweepPlan plan_launch = plan_max;
+    plan_launch.narrow = narrow && sweep_has_narrow_shape(d);
     for (int i = 0; i < a.n_seq; ++i) {
       const int64_t n = seq_lens[b0 + i];
-      plan = make_sweep_plan(d, n);
+      plan = make_sweep_plan(d, n, launch_tokens, narrow);
       SweepSeq& sq = a.s[i];
       sq.n = n;
       sq.tok = tok;
@@ -178,10 +197,10 @@ int32_t lava_window_scores(const lava_layer_desc* desc, int32_t batch, const int
     st = d.score_kind == LAVA_SCORE_ATTENTION ? launch_unit_vnorm(d, a, max_vb, s) : launch_vnorm(d, a, max_vb, s);
     if (st != LAVA_OK) return st;
     if (lse == nullptr) {
-      st = launch_stats(d, a, max_bx, plan_max, s);
+      st = launch_stats(d, a, max_bx, plan_launch, s);
       if (st != LAVA_OK) return st;
     }
-    st = launch_scores(d, a, max_bx, plan_max, s);
+    st = launch_scores(d, a, max_bx, plan_launch, s);
     if (st != LAVA_OK) return st;
     if (!together) {                                         // one sequence: `plan` is its plan
       const SweepSeq& sq = a.s[0];

@@ -318,8 +318,9 @@ def lava_select_batch_workspace_bytes(n_problems: int, max_total_entries: int) -
 
 def lava_select_topk_batch(n_heads: int, problems, max_total_entries=None, workspace=None, device="cuda",
                            stream=None):
-    """problems: sequence of SelectProblem.  Returns the workspace (for lava_select_batch_status)."""
-    table = (SelectProblem * len(problems))(*problems)
+    """problems: sequence of SelectProblem, or a ready (SelectProblem * n) array that a caller reuses from
+    step to step.  Returns the workspace (for lava_select_batch_status)."""
+    table = problems if isinstance(problems, ctypes.Array) else (SelectProblem * len(problems))(*problems)
     widest = max((p.total_entries for p in problems), default=0) if max_total_entries is None else int(max_total_entries)
     if workspace is None:
         need = lava_select_batch_workspace_bytes(len(problems), widest)
@@ -336,8 +337,8 @@ def lava_select_batch_status(workspace: torch.Tensor, n_problems: int, max_total
 
 
 def lava_compact_batch(desc: LayerDesc, problems, stream=None) -> None:
-    """problems: sequence of CompactProblem."""
-    table = (CompactProblem * len(problems))(*problems)
+    """problems: sequence of CompactProblem, or a ready (CompactProblem * n) array."""
+    table = problems if isinstance(problems, ctypes.Array) else (CompactProblem * len(problems))(*problems)
     st = lib.lava_compact_batch(ctypes.byref(desc), len(problems), ctypes.cast(table, ctypes.c_void_p),
                                 _stream(stream))
     _check(st, "lava_compact_batch")

@@ -222,6 +222,27 @@ def test_window_scores_vs_oracle(lava, name, sh):
         compare_scores(sh, got, ref_s, vbar, ref_vbar, stat, ref_e)
 
 
+NARROW_CASES = [c for c in SCORE_CASES if c[0] not in ("tiny-prefix", "w1")] + [
+    ("cfg2-9k", synth.config(2, n=9000 + 5, budget=8 * 64)),
+    ("f32-d64-G4", synth.LayerShape(8, 2, 64, 5000 + 9, 8, "f32", 300)),
+]
+
+
+@pytest.mark.parametrize("name,sh", NARROW_CASES, ids=[c[0] for c in NARROW_CASES])
+def test_window_scores_narrow_shape_vs_oracle(lava, name, sh, monkeypatch):
+    """The two-workgroups-per-CU shape of the sweeps (what a large batch runs), forced for one sequence."""
+    say(f"scores, narrow shape, {name}: {sh}")
+    monkeypatch.setenv("LAVA_SWEEP_SHAPE", "narrow")
+    inp = synth.gen_layer(sh, 2)
+    q, k, v = inp.f64()
+    ref_s, ref_vbar = O.lava_scores(q, k, v, sh.window, sh.pool_kernel)
+    _, _, got, vbar, stat = run_scores(lava, inp)
+    compare_scores(sh, got, ref_s, vbar, ref_vbar, stat, O.layer_entropy(ref_s))
+    lse = O.window_lse(q, k)
+    _, _, got, vbar, stat = run_scores(lava, inp, lse=lse)
+    compare_scores(sh, got, ref_s, vbar, ref_vbar, stat, O.layer_entropy(ref_s))
+
+
 def test_window_scores_pool_kernels_and_lse(lava):
     sh = synth.config(2, n=3000, budget=8 * 64)
     inp = synth.gen_layer(sh, 3)
