@@ -156,3 +156,75 @@ def test_compact_table_matches_oracle(lava):
         assert np.array_equal(lava.to_host_bits(t["vo"][:cap]), wv), i
         assert np.array_equal(t["po"][:cap].cpu().numpy(), wp), i
         assert torch.all(t["ko"][cap:] == 5.0) and torch.all(t["po"][cap:] == -3), i
+
+
+def test_ragged_batch_full_size_one_layer(lava):
+    """The batched serving configuration at full size (16 sequences of 4K-64K tokens, one layer), in the
+    launch configuration the benchmark times: one lava_window_scores call for the batch, device budgets,
+    one table of selections and one of compactions.  Scores and statistics against the oracle per
+    sequence; selection and compaction bit-exact on the scores the GPU produced."""
+    lens = [int(x) for x in synth.ragged_lengths(16, 0)]
+    say(f"ragged batch, full size: lengths {lens}")
+    base = synth.config(5)
+    H, Hkv, d, w = base.n_q_heads, base.n_kv_heads, base.head_dim, base.window
+    B = 4096
+    desc = lava.LayerDesc.make(H, Hkv, d, w, base.dtype)
+    dev = "cuda"
+    inps = [synth.gen_layer(synth.config(5, n=n, budget=B), 900 + b) for b, n in enumerate(lens)]
+    q = torch.cat([lava.to_device(i.q_win, "bf16").reshape(-1) for i in inps])
+    k = torch.cat([lava.to_device(i.k, "bf16").reshape(-1) for i in inps])
+    v = torch.cat([lava.to_device(i.v, "bf16").reshape(-1) for i in inps])
+    scores, vbar, stat = lava.lava_window_scores(desc, lens, q, k, v)
+    nb = len(lens)
+    total_b = torch.full((nb,), B, dtype=torch.int64, device=dev)
+    lo = torch.full((nb, 1), Hkv * w, dtype=torch.int64, device=dev)
+    hi = torch.tensor([[Hkv * n] for n in lens], dtype=torch.int64, device=dev)
+    budgets = lava.lava_layer_budgets(stat.view(-1, 1), total_b, lo, hi)
+    counts = torch.empty(nb, Hkv, dtype=torch.int32, device=dev)
+    offs = torch.empty(nb, Hkv + 1, dtype=torch.int64, device=dev)
+    idx = torch.empty(nb, B, dtype=torch.int32, device=dev)
+    k_hat = torch.empty(nb, B, d, dtype=torch.bfloat16, device=dev)
+    v_hat = torch.empty(nb, B, d, dtype=torch.bfloat16, device=dev)
+    starts = np.concatenate([[0], np.cumsum(lens)])
+    sel, cmp = [], []
+    for b, n in enumerate(lens):
+        a0, a1 = int(starts[b]) * Hkv, int(starts[b + 1]) * Hkv
+        sel.append(lava.select_problem(scores[a0:a1], B, counts[b], offs[b], idx[b], budget_dev=budgets[b]))
+        cmp.append(lava.compact_problem(desc, n, k.view(-1, d)[a0:a1], v.view(-1, d)[a0:a1], offs[b], idx[b], B,
+                                        k_hat[b], v_hat[b]))
+    ws = lava.lava_select_topk_batch(Hkv, sel, Hkv * max(lens))
+    lava.lava_compact_batch(desc, cmp)
+    torch.cuda.synchronize()
+    assert lava.lava_select_batch_status(ws, nb, Hkv * max(lens)) == lava.LAVA_OK
+    assert budgets.cpu().numpy().ravel().tolist() == [B] * nb          # one layer: the whole budget
+    s_host, vb_host, e_host = scores.cpu().numpy(), vbar.cpu().numpy(), stat.cpu().numpy()
+    worst, least = 0.0, 1.0
+    for b, (n, inp) in enumerate(zip(lens, inps)):
+        qq, kk, vv = inp.f64()
+        ref_s, ref_vbar = O.lava_scores(qq, kk, vv, w, 7)
+        got = s_host[Hkv * starts[b]: Hkv * starts[b + 1]].reshape(Hkv, n)
+        Np = n - w
+        assert np.all(np.isposinf(got[:, Np:]))
+        mask = ref_s > 1e-30 * ref_s.max()
+        rel = np.abs(got[:, :Np].astype(np.float64)[mask] - ref_s[mask]) / ref_s[mask]
+        worst = max(worst, float(rel.max()))
+        assert rel.max() < 1e-3, (b, rel.max())
+        np.testing.assert_allclose(vb_host[b], ref_vbar, rtol=1e-5)
+        ref_e = O.layer_entropy(ref_s)
+        assert abs(float(e_host[b]) - ref_e) <= 1e-4 * ref_e
+        # selection: exact on the GPU's own scores; kept set against the oracle's scores
+        uniform = (np.arange(Hkv + 1) * n).astype(np.int64)
+        rc, ro, ri, _ = O.select_topk(got.astype(np.float64).ravel(), uniform, B)
+        assert np.array_equal(counts[b].cpu().numpy(), rc) and np.array_equal(offs[b].cpu().numpy(), ro)
+        assert np.array_equal(idx[b].cpu().numpy(), ri)
+        flat_ref = O.flat_layer_scores(ref_s, n)
+        oc, oo, oi, _ = O.select_topk(flat_ref.ravel(), uniform, B)
+        mine = set(int(g * n + p) for g in range(Hkv) for p in ri[ro[g]:ro[g + 1]])
+        theirs = set(int(g * n + p) for g in range(Hkv) for p in oi[oo[g]:oo[g + 1]])
+        least = min(least, len(mine & theirs) / B)
+        assert np.all(rc >= w)
+        # compaction: bit copies of the selected rows
+        assert np.array_equal(lava.to_host_bits(k_hat[b]), O.compact(inp.k, ro, ri))
+        assert np.array_equal(lava.to_host_bits(v_hat[b]), O.compact(inp.v, ro, ri))
+    say(f"   worst score error {worst:.2e}, least kept-set overlap {least:.5f}")
+    assert least >= 0.999
