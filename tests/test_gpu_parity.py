@@ -375,6 +375,33 @@ def test_device_budgets_match_host_and_oracle(lava):
     assert bad.cpu().tolist() == [[-1, -1]]                     # infeasible bounds flagged on device
 
 
+@pytest.mark.parametrize("L", [1, 7, 64, 65, 200, 1024])
+def test_device_budgets_many_layers(lava, L):
+    """The device allocation spreads the layers over a wavefront: more layers than lanes, bounds that pin
+    layers at both ends in several rounds, equal weights (ties go to the lower layer), tiny totals."""
+    say(f"device budgets, {L} layers")
+    r = np.random.Generator(np.random.PCG64(1000 + L))
+    batch = 6
+    e = np.exp(r.standard_normal((batch, L)) * 2.0).astype(np.float32) * 1e-5
+    e[1, :] = 1e-5                                   # all equal
+    e[2, ::3] = 0.0
+    lo = np.full((batch, L), 64, dtype=np.int64)
+    hi = np.full((batch, L), 4096, dtype=np.int64)
+    lo[3] = r.integers(0, 100, L)
+    hi[3] = lo[3] + r.integers(0, 3000, L)
+    total = np.array([L * 1000, L * 64 + 5, L * 2000, int(lo[3].sum() + (hi[3] - lo[3]).sum() // 2), L * 4096 - 3, L * 64],
+                     dtype=np.int64)
+    host = lava.lava_layer_budgets(e, total, lo, hi)
+    dev = lava.lava_layer_budgets(torch.from_numpy(e).cuda(), torch.from_numpy(total).cuda(),
+                                  torch.from_numpy(lo).cuda(), torch.from_numpy(hi).cuda())
+    torch.cuda.synchronize()
+    assert np.array_equal(dev.cpu().numpy(), host)
+    for b in range(batch):
+        assert host[b].sum() == total[b] and np.all(host[b] >= lo[b]) and np.all(host[b] <= hi[b])
+        if L <= 200:
+            assert host[b].tolist() == O.layer_budgets(e[b].astype(np.float64), int(total[b]), lo[b], hi[b])
+
+
 def test_stack_dynamic_layer_budgets(lava):
     """A short stack of layers: statistics -> device budgets -> selection with the budget read on
     the device, against the oracle's final allocation (Alg. 2 collapses to one selection per layer
