@@ -95,6 +95,11 @@ def value_norm_max(v: np.ndarray) -> np.ndarray:
     return np.abs(v).sum(axis=2).max(axis=1)
 
 
+def value_norm_rows(v: np.ndarray) -> np.ndarray:
+    """L1 norm of every value row.  v [H_kv, N, d] -> [H_kv, N]."""
+    return np.abs(v).sum(axis=2)
+
+
 def head_scores(a: np.ndarray, vbar: np.ndarray, group: int) -> np.ndarray:
     """s_head[h, i] = Vbar[h // G] * a[h, i]."""
     H = a.shape[0]
@@ -136,6 +141,23 @@ def lava_scores(q_win, k, v, window: int, pool_kernel: int = 7, scale=None, use_
     s_head = head_scores(a, vbar if use_value_norm else np.ones_like(vbar), G)
     s = maxpool(group_max(s_head, G), pool_kernel)
     return s, vbar
+
+
+def token_norm_scores(q_win, k, v, window: int, pool_kernel: int = 7, scale=None):
+    """The comparison score of the paper's VATP ablation (appendix paragraph "VATP", Table 4 row
+    "recent attention scores + value vectors"): every token's own value norm times its attention
+    score, where LAVa uses one factor per head.  The attention score is the pooled, group-level
+    window mean (the rule is applied on top of the pooled SnapKV score in that ablation):
+        s[g, i] = ||V[g, i]||_1 * maxpool(max_{h in g} a[h, i]).
+    Returns (s, Vbar) like lava_scores."""
+    H, Hkv = q_win.shape[0], k.shape[0]
+    if q_win.shape[1] != window:
+        raise ValueError("q_win must hold exactly w rows")
+    G = H // Hkv
+    a = window_mean(window_attention(q_win, k, scale))
+    pooled = maxpool(group_max(a, G), pool_kernel)
+    norms = value_norm_rows(v)
+    return norms[:, : pooled.shape[1]] * pooled, norms.max(axis=1)
 
 
 # ------------------------------------------------------------------ layer statistic (Eq. 4-5)

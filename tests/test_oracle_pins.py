@@ -226,6 +226,47 @@ def test_special_case_reduces_to_window_mean_attention():
     np.testing.assert_allclose(s, ref / 4, rtol=1e-12)
 
 
+# ----------------------------------------------------------------- the per-token value-norm score (VATP ablation)
+@pytest.mark.parametrize("H,Hkv,w,d,N,pool", [(4, 2, 3, 4, 14, 7), (2, 2, 2, 3, 9, 3), (6, 3, 2, 4, 12, 1)])
+def test_token_norm_scores_brute_force(H, Hkv, w, d, N, pool):
+    r = rng(31 * H + N)
+    q, k, v = r.standard_normal((H, w, d)), r.standard_normal((Hkv, N, d)), r.standard_normal((Hkv, N, d))
+    s, vbar = O.token_norm_scores(q, k, v, w, pool)
+    A = brute_attention(q.tolist(), k.tolist(), 1.0 / math.sqrt(d))
+    G, Np, half = H // Hkv, N - w, pool // 2
+    for g in range(Hkv):
+        att = [max(sum(A[h][rr][i] for rr in range(w)) / w for h in range(g * G, (g + 1) * G)) for i in range(Np)]
+        for i in range(Np):
+            pooled = max(att[max(0, i - half): min(Np, i + half + 1)])
+            norm = sum(abs(x) for x in v[g, i].tolist())
+            assert math.isclose(s[g, i], norm * pooled, rel_tol=1e-12)
+        assert math.isclose(vbar[g], max(sum(abs(x) for x in row) for row in v[g].tolist()), rel_tol=1e-14)
+
+
+def test_token_norm_scores_reduce_to_lava_scores_for_equal_norms():
+    # rows of equal L1 norm inside a head (signed permutations of one vector): the token's own norm
+    # and the head's maximum coincide, so the two scores are the same array
+    r = rng(77)
+    H, Hkv, w, d, N = 4, 2, 3, 6, 40
+    q, k = r.standard_normal((H, w, d)), r.standard_normal((Hkv, N, d))
+    v = np.empty((Hkv, N, d))
+    for g in range(Hkv):
+        proto = r.standard_normal(d)
+        for i in range(N):
+            v[g, i] = r.permutation(proto) * r.choice([-1.0, 1.0], d)
+    a, va = O.token_norm_scores(q, k, v, w, 7)
+    b, vb = O.lava_scores(q, k, v, w, 7)
+    np.testing.assert_allclose(a, b, rtol=1e-13)
+    np.testing.assert_allclose(va, vb, rtol=1e-14)
+    # scaling one value row scales that entry's score alone, by the same factor
+    v2 = v.copy()
+    v2[1, 5] *= -3.0
+    c, _ = O.token_norm_scores(q, k, v2, w, 7)
+    assert math.isclose(c[1, 5], 3.0 * a[1, 5], rel_tol=1e-13)
+    c[1, 5] = a[1, 5]
+    assert np.array_equal(c, a)
+
+
 # ----------------------------------------------------------------- pooling
 @pytest.mark.parametrize("n,kernel", [(1, 7), (3, 7), (6, 7), (7, 7), (50, 7), (50, 3), (50, 1), (9, 9)])
 def test_maxpool_vs_library_and_loop(n, kernel):
