@@ -53,8 +53,11 @@ typedef enum { LAVA_F32 = 0, LAVA_BF16 = 1 } lava_dtype;
  *   LAVA_SCORE_ATTENTION  window-mean attention alone: the value factor is 1 and V is not read
  *                         (the recent-window attention score of the SnapKV / Ada-KV rows of
  *                         Table 4, and the paper's ablation without the value norm); vbar = 1
- * Group-max, pooling and the layer statistic are the same for both. */
-typedef enum { LAVA_SCORE_LAVA = 0, LAVA_SCORE_ATTENTION = 1 } lava_score_kind;
+ *   LAVA_SCORE_TOKEN_NORM the pooled window-mean attention times the token's own ||V[i]||_1
+ *                         (the VATP comparison of the appendix and of Table 4: a factor per
+ *                         token where LAVa has one per head); vbar is still max_k ||V[k]||_1
+ * Group-max, pooling and the layer statistic are the same for all. */
+typedef enum { LAVA_SCORE_LAVA = 0, LAVA_SCORE_ATTENTION = 1, LAVA_SCORE_TOKEN_NORM = 2 } lava_score_kind;
 
 /* One layer of one model.  Plain data, read during the call only. */
 typedef struct lava_layer_desc {

@@ -105,6 +105,7 @@ struct SweepArgs {
   char* ws;
   size_t off_stat_part, off_vnorm_part, off_sraw, off_ent_part, off_counter;   // inside a sequence's region
   int H, H_kv, w, G, n_chunks, pool_half;
+  int token_norm;            // value factor per token: vnorm leaves ||V[g, i]||_1 in scores[g][i], the pooling step multiplies by it
   float c2;
   int first_seq;             // index in the batch of s[0]
   int n_seq;

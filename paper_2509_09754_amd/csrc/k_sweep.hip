@@ -258,6 +258,7 @@ struct PoolArgs {
   const float* vnorm_part;   // [H_kv][vnorm_blocks] value-norm partials
   int vnorm_blocks;
   int pool_half;
+  int token_norm;            // scores[g][i] holds ||V[g, i]||_1 on entry: the value factor of entry i
   float* scores;             // [H_kv][n]
   float* vbar;               // [H_kv]
   float* layer_stat;         // [1]
@@ -288,6 +289,7 @@ scores_kernel(const SweepArgs a) {
   pa.pool_half = a.pool_half;
   pa.scores = a.scores + (long long)a.H_kv * sq.tok;
   pa.vbar = a.vbar + (long long)seq * a.H_kv;
+  pa.token_norm = a.token_norm;
   pa.layer_stat = a.layer_stat + seq;
   pa.ent_part = reinterpret_cast<double2*>(region + a.off_ent_part);
   pa.counters = reinterpret_cast<uint32_t*>(region + a.off_counter);
@@ -526,9 +528,17 @@ scores_kernel(const SweepArgs a) {
           for (int j = 0; j < kPer; ++j) sc[j] = fmaxf(sc[j], fmaxf(raw[kPer + j - dd], raw[kPer + j + dd]));
         }
       }
+      float fac[kPer];
+#pragma unroll
+      for (int j = 0; j < kPer; ++j) fac[j] = vb;
+      if (pa.token_norm) {                                     // uniform
+#pragma unroll
+        for (int j = 0; j < kPer; ++j)
+          if (base + j < p_end) fac[j] = out_head[base + j];
+      }
 #pragma unroll
       for (int j = 0; j < kPer; ++j) {
-        sc[j] *= vb;
+        sc[j] *= fac[j];
         if (base + j < p_end) {
           acc_s += (double)sc[j];
           if (sc[j] > 0.0f) acc_t += (double)sc[j] * (double)logf(sc[j]);
@@ -596,6 +606,7 @@ vnorm_kernel(const SweepArgs a) {
   const int tiles_per_block = sq.vnorm_tiles_per_block;
   const u32x4* __restrict__ v = static_cast<const u32x4*>(a.v) + (long long)a.H_kv * sq.tok * T::kCpr;
   float* __restrict__ vnorm_part = reinterpret_cast<float*>(a.ws + sq.ws_off + a.off_vnorm_part);
+  float* __restrict__ row_norm = a.scores + (long long)a.H_kv * sq.tok;
   uint32_t* __restrict__ counters = reinterpret_cast<uint32_t*>(a.ws + sq.ws_off + a.off_counter);
   constexpr int n_counter_words = kArriveWords;
   constexpr int kWaves = VShape<DT, D>::kWaves;
@@ -645,6 +656,10 @@ vnorm_kernel(const SweepArgs a) {
     for (int j = 0; j < T::kSteps; ++j) s = abs_sum16<DT>(f[j], s);
     s += __shfl_xor(s, 32);
     best = fmaxf(best, s);
+    if (a.token_norm) {                                        // uniform: the rows' own norms, for the pooling step
+      const long long row = (first + (long long)it * kWaves) * kTileKeys + (lane & 31);
+      if (lane < 32 && row < n) row_norm[(long long)g * n + row] = s;
+    }
   }
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) best = fmaxf(best, __shfl_xor(best, off));
@@ -668,7 +683,7 @@ constexpr int kPoolPerThread = 8;
 constexpr int kPoolChunk = kPoolThreads * kPoolPerThread;
 
 __global__ void __launch_bounds__(kPoolThreads)
-poolstat_kernel(const float* __restrict__ s_raw, long long n, int w, int pool_half,
+poolstat_kernel(const float* __restrict__ s_raw, long long n, int w, int pool_half, int token_norm,
                 const float* __restrict__ vnorm_part, int vnorm_blocks, float* __restrict__ scores,
                 float* __restrict__ vbar, float* __restrict__ layer_stat,
                 double2* __restrict__ ent_part, uint32_t* __restrict__ counters) {
@@ -704,7 +719,7 @@ poolstat_kernel(const float* __restrict__ s_raw, long long n, int w, int pool_ha
     if (p < n_prefix) {
       float m = s_in[i + pool_half];
       for (int d = 1; d <= pool_half; ++d) m = fmaxf(m, fmaxf(s_in[i + pool_half - d], s_in[i + pool_half + d]));
-      const float s = vb * m;
+      const float s = (token_norm ? scores[(long long)g * n + p] : vb) * m;   // the entry's own value norm, left there by vnorm
       scores[(long long)g * n + p] = s;
       acc_s += (double)s;
       if (s > 0.0f) acc_t += (double)s * (double)logf(s);
@@ -932,7 +947,7 @@ int32_t launch_poolstat(const lava_layer_desc& d, int64_t n, const float* s_raw,
   const dim3 grid(pool_blocks(d, n), d.n_kv_heads), block(kPoolThreads);
   ProfScope ps(KID_POOLSTAT, s);
   hipLaunchKernelGGL(poolstat_kernel, grid, block, 0, s, s_raw, (long long)n, d.window,
-                     d.pool_kernel / 2, vnorm_part, vnorm_blocks, scores, vbar, layer_stat, ent_part,
+                     d.pool_kernel / 2, d.score_kind == LAVA_SCORE_TOKEN_NORM ? 1 : 0, vnorm_part, vnorm_blocks, scores, vbar, layer_stat, ent_part,
                      counters);
   return launch_status();
 }

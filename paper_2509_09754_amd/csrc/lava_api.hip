@@ -64,7 +64,7 @@ static int32_t check_desc(const lava_layer_desc* d) {
   if (d->n_q_heads < 1 || d->n_kv_heads < 1 || d->window < 1 || d->pool_kernel < 1)
     return LAVA_ERR_INVALID_ARG;
   if (!(d->softmax_scale >= 0.0f) || d->softmax_scale > 1e30f) return LAVA_ERR_INVALID_ARG;
-  if (d->score_kind != LAVA_SCORE_LAVA && d->score_kind != LAVA_SCORE_ATTENTION) return LAVA_ERR_INVALID_ARG;
+  if (d->score_kind < LAVA_SCORE_LAVA || d->score_kind > LAVA_SCORE_TOKEN_NORM) return LAVA_ERR_INVALID_ARG;
   if (d->n_q_heads % d->n_kv_heads != 0) return LAVA_ERR_SHAPE;
   if (d->n_q_heads / d->n_kv_heads > 8 || d->n_kv_heads > 64) return LAVA_ERR_SHAPE;
   if (d->head_dim != 64 && d->head_dim != 128) return LAVA_ERR_SHAPE;
@@ -152,6 +152,7 @@ int32_t lava_window_scores(const lava_layer_desc* desc, int32_t batch, const int
   a.G = d.n_q_heads / d.n_kv_heads;
   a.n_chunks = plan_max.n_chunks;
   a.pool_half = d.pool_kernel / 2;
+  a.token_norm = d.score_kind == LAVA_SCORE_TOKEN_NORM ? 1 : 0;
   a.c2 = sweep_exp2_scale(d);
 
   const int per_launch = together ? kMaxSeqPerLaunch : 1;

@@ -18,7 +18,7 @@ LIB_PATH = os.path.join(_HERE, "liblava.so")
 
 LAVA_OK, LAVA_ERR_INVALID_ARG, LAVA_ERR_SHAPE, LAVA_ERR_BUDGET, LAVA_ERR_WORKSPACE, LAVA_ERR_HIP = range(6)
 LAVA_F32, LAVA_BF16 = 0, 1
-LAVA_SCORE_LAVA, LAVA_SCORE_ATTENTION = 0, 1
+LAVA_SCORE_LAVA, LAVA_SCORE_ATTENTION, LAVA_SCORE_TOKEN_NORM = 0, 1, 2
 
 EXPORTS = [
     "lava_status_string", "lava_window_scores_workspace_bytes", "lava_window_scores",

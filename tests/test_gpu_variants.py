@@ -45,6 +45,62 @@ def test_attention_only_score(lava, cfg, over):
     np.testing.assert_allclose(full, want * vb[:, None], rtol=1e-12)
 
 
+TOKEN_NORM_CASES = [
+    ("cfg1", synth.config(1), None),
+    ("cfg2-4k", synth.config(2, n=4096 + 77), None),
+    ("cfg2-9k-narrow", synth.config(2, n=9000 + 5), "narrow"),
+    ("bf16-G8-two-chunks", synth.LayerShape(16, 2, 128, 2100, 32, "bf16", 300), None),
+    ("f32-d128", synth.LayerShape(8, 2, 128, 1111, 32, "f32", 300), None),
+    ("bf16-d64-pool3", synth.LayerShape(8, 4, 64, 3000, 16, "bf16", 400, pool_kernel=3), None),
+]
+
+
+@pytest.mark.parametrize("name,sh,shape", TOKEN_NORM_CASES, ids=[c[0] for c in TOKEN_NORM_CASES])
+def test_token_norm_score(lava, name, sh, shape, monkeypatch):
+    say(f"variant: per-token value-norm score, {name}")
+    if shape:
+        monkeypatch.setenv("LAVA_SWEEP_SHAPE", shape)
+    inp = synth.gen_layer(sh, 6)
+    desc = lava.LayerDesc.make(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.window, sh.dtype,
+                               pool_kernel=sh.pool_kernel, score_kind=lava.LAVA_SCORE_TOKEN_NORM)
+    q, k, v = (lava.to_device(a, sh.dtype) for a in (inp.q_win, inp.k, inp.v))
+    scores, vbar, stat = lava.lava_window_scores(desc, [sh.n], q, k, v)
+    torch.cuda.synchronize()
+    qf, kf, vf = inp.f64()
+    want, want_vbar = O.token_norm_scores(qf, kf, vf, sh.window, sh.pool_kernel)
+    got = scores.cpu().numpy().reshape(sh.n_kv_heads, sh.n)
+    assert np.all(np.isposinf(got[:, sh.n_prefix:]))
+    np.testing.assert_allclose(vbar.cpu().numpy()[0], want_vbar, rtol=1e-5)
+    got = got[:, : sh.n_prefix].astype(np.float64)
+    mask = want > 1e-30 * want.max()
+    assert np.max(np.abs(got[mask] - want[mask]) / want[mask]) <= 1e-3
+    assert np.all(got[~mask] <= 1e-29 * want.max())
+    assert abs(float(stat[0]) - O.layer_entropy(want)) <= 1e-4 * O.layer_entropy(want)
+
+
+def test_token_norm_score_ragged_batch(lava):
+    say("variant: per-token value-norm score, ragged batch of three sequences")
+    shapes = [synth.config(2, n=n, budget=8 * 64) for n in (1500, 6000 + 3, 33 + 32)]
+    inps = [synth.gen_layer(s, 70 + i) for i, s in enumerate(shapes)]
+    sh0 = shapes[0]
+    desc = lava.LayerDesc.make(sh0.n_q_heads, sh0.n_kv_heads, sh0.head_dim, sh0.window, sh0.dtype,
+                               score_kind=lava.LAVA_SCORE_TOKEN_NORM)
+    q = torch.cat([lava.to_device(i.q_win, "bf16").reshape(-1) for i in inps])
+    k = torch.cat([lava.to_device(i.k, "bf16").reshape(-1) for i in inps])
+    v = torch.cat([lava.to_device(i.v, "bf16").reshape(-1) for i in inps])
+    scores, vbar, stat = lava.lava_window_scores(desc, [s.n for s in shapes], q, k, v)
+    torch.cuda.synchronize()
+    s_host, tok = scores.cpu().numpy(), 0
+    for b, (sh, inp) in enumerate(zip(shapes, inps)):
+        qf, kf, vf = inp.f64()
+        want, _ = O.token_norm_scores(qf, kf, vf, sh.window, 7)
+        got = s_host[8 * tok: 8 * (tok + sh.n)].reshape(8, sh.n)[:, : sh.n_prefix].astype(np.float64)
+        mask = want > 1e-30 * want.max()
+        assert np.max(np.abs(got[mask] - want[mask]) / want[mask]) <= 1e-3, b
+        assert abs(float(stat[b]) - O.layer_entropy(want)) <= 1e-4 * O.layer_entropy(want)
+        tok += sh.n
+
+
 def test_per_head_topk_with_one_selection_per_head(lava):
     say("variant: uniform head budgets = one top-k per head (n_heads = 1 on each head's segment)")
     nh, n, w, per_head = 8, 4096 + 13, 32, 300
