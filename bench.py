@@ -59,16 +59,14 @@ def cascade_leg(lava, torch, np, sh, desc, dev, sets, scores, args):
     n_layers = 8
     per_layer = sh.budget
     total = n_layers * per_layer
-    cap = min(total, sh.n_kv_heads * sh.n)
-    state = lava.CascadeState(desc, n_layers, cap, device=dev)
+    state = lava.CascadeState(desc, n_layers, total, device=dev)
     rng = np.random.Generator(np.random.PCG64(args.seed + 5))
     state.e.copy_(torch.from_numpy((1e-6 * (0.5 + rng.random(n_layers))).astype(np.float32)))
-    ws = torch.empty(lava.lava_cascade_workspace_bytes(desc, sh.n, n_layers, cap), dtype=torch.uint8, device=dev)
+    ws = torch.empty(lava.lava_cascade_workspace_bytes(desc, sh.n, n_layers, total), dtype=torch.uint8, device=dev)
     _, k, v = sets[0]
 
     def run():
-        for t in range(n_layers):
-            state.layers[t].cur = 0
+        state.reset()
         times = []
         for l in range(n_layers):
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -85,7 +83,8 @@ def cascade_leg(lava, torch, np, sh, desc, dev, sets, scores, args):
     budgets = state.budgets.cpu().numpy().tolist()
     return {"note": "Alg. 2 outer loop, one step per arriving layer: budgets + one (re-)eviction per layer so far",
             "layers": n_layers, "total_budget": total, "us_per_step": [round(x, 1) for x in best],
-            "us_all_steps": round(sum(best), 1), "final_budgets": budgets}
+            "us_all_steps": round(sum(best), 1), "final_budgets": budgets,
+            "state_bytes": state.bytes(), "dense_kv_bytes_of_the_layers": n_layers * 2 * k.numel() * k.element_size()}
 
 
 def decode_leg(lava, synth, torch, np, sh, desc, dev, sets, k_hat, v_hat, offs, B, args):

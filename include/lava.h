@@ -205,7 +205,10 @@ int32_t lava_compact_packed(const lava_layer_desc* desc, const int64_t* src_offs
  * an outer iteration of Alg. 2 evicts again, or the sequences of a ragged batch (Alg. 1 per
  * sequence).  Each problem is exactly one lava_select_topk / lava_compact_packed call (same
  * meaning, layout and limits of every field); results are identical to calling them one by one.
- * The tables are host arrays, read during the call.
+ * The tables are host arrays, read during the call.  The optional *_offset_dev fields let a
+ * problem's data start at a position inside its buffers that only the device knows (layers packed
+ * back to back in one pool whose split was decided on the device); the caller guarantees that the
+ * offsets, plus what the problem reads and writes, stay inside the buffers.
  */
 typedef struct lava_select_problem {
   const float* scores;
@@ -217,6 +220,9 @@ typedef struct lava_select_problem {
   int64_t* head_offsets;
   int32_t* kept_idx;
   float* kept_scores;           /* or NULL                                                     */
+  const int64_t* in_offset_dev; /* or NULL: device int64, entries added to `scores` (the problem's
+                                   scores start there)                                          */
+  const int64_t* out_offset_dev;/* or NULL: device int64, entries added to kept_idx / kept_scores */
 } lava_select_problem;
 
 typedef struct lava_compact_problem {
@@ -232,6 +238,11 @@ typedef struct lava_compact_problem {
   void* k_out;
   void* v_out;
   int32_t* pos_out;             /* or NULL                                                     */
+  const int64_t* src_offset_dev;/* or NULL: device int64, first row of a packed source inside
+                                   k_src / v_src / pos_src (src_rows counts from their base)   */
+  const int64_t* out_offset_dev;/* or NULL: device int64, first output row inside k_out / v_out /
+                                   pos_out and first entry inside kept_idx (capacity counts from
+                                   their base)                                                 */
 } lava_compact_problem;
 
 /* Workspace of a batch: n_problems regions, each sized for max_total_entries.  0 if invalid. */
@@ -255,51 +266,62 @@ int32_t lava_compact_batch(const lava_layer_desc* desc, int32_t n_problems,
                            const lava_compact_problem* problems, void* hip_stream);
 
 /*
- * Algorithm 2 as a driver: state of one layer between cascade steps.  Every pointer is device
- * memory owned by the caller; buffers come in pairs because a re-eviction is out of place, and
- * `cur` (host) says which of the pair holds the layer's current state.  capacity: rows of each
- * pool, at least min(total budget, H_kv * N).
+ * Algorithm 2 as a driver: the compressed caches of all layers between cascade steps.  Every
+ * pointer is device memory owned by the caller.  The layers sit back to back in one pool ("arena")
+ * of `capacity` rows: their sizes change at every step but always sum to at most the total budget,
+ * so the whole state needs capacity >= total budget rows, whatever the number of layers.  A step
+ * gathers every layer from the current arena into the other one (a re-eviction is out of place),
+ * hence two arenas; `cur` (host) says which one holds the state.
+ *   layer t occupies arena rows layer_start[cur][t] .. layer_start[cur][t + 1] - 1; inside them
+ *   head g owns rows head_offsets[cur][t][g] .. head_offsets[cur][t][g + 1] - 1 (relative to the
+ *   layer's first row), in ascending token position.
+ * lava_decode_attention reads a layer in place: k_hat / v_hat = the arena, head_offsets =
+ * head_offsets[cur] + t * (H_kv + 1), seq_base = layer_start[cur] + t, rows_capacity = capacity.
  */
-typedef struct lava_cascade_layer {
-  void* k[2];               /* [capacity][d_h] packed keys                                     */
-  void* v[2];               /* [capacity][d_h] packed values                                   */
-  int32_t* pos[2];          /* [capacity] token position of each retained row                  */
-  float* scores[2];         /* [capacity] retained LAVa scores (what the next re-eviction ranks)*/
-  int64_t* head_offsets[2]; /* [H_kv + 1]                                                      */
-  int32_t* head_counts;     /* [H_kv] dynamic head budgets after the latest step               */
-  int32_t* kept_idx;        /* [capacity] scratch                                              */
-  int64_t capacity;
-  int32_t cur;              /* updated by lava_cascade_step                                    */
-  int32_t reserved;
-} lava_cascade_layer;
+typedef struct lava_cascade_state {
+  void* k[2];               /* [capacity][d_h] packed keys                                      */
+  void* v[2];               /* [capacity][d_h] packed values                                    */
+  int32_t* pos[2];          /* [capacity] token position of each retained row                   */
+  float* scores[2];         /* [capacity] retained scores (what the next re-eviction ranks)     */
+  int64_t* head_offsets[2]; /* [max_layers][H_kv + 1]                                           */
+  int64_t* layer_start[2];  /* [max_layers + 1]                                                 */
+  int32_t* head_counts;     /* [max_layers][H_kv] dynamic head budgets after the latest step    */
+  int32_t* kept_idx;        /* [capacity] scratch                                               */
+  int64_t capacity;         /* rows per arena, >= total budget                                  */
+  int32_t max_layers;
+  int32_t cur;              /* 0 or 1; flipped by every lava_cascade_step                       */
+} lava_cascade_state;
 
 /*
  * Bytes of device workspace lava_cascade_step needs for up to n_layers layers of H_kv * n entries
- * whose pools hold `capacity` rows (all layers of a step are evicted by one batched selection, one
- * workspace region per layer).  Returns 0 for invalid arguments.
+ * and a total budget (all layers of a step are evicted by one batched selection, one workspace
+ * region per layer).  Returns 0 for invalid arguments.
  */
 size_t lava_cascade_workspace_bytes(const lava_layer_desc* desc, int64_t n, int32_t n_layers,
-                                    int64_t capacity);
+                                    int64_t total_budget);
 
 /*
  * One outer iteration of Algorithm 2, after layer `layer` (0-based) has been prefilled and scored:
  *   budgets  B_t = e_t / sum_{t' <= layer} e_t' * total_budget for t = 0..layer (device, bounds
- *            H_kv * w and H_kv * n, rounding as lava_layer_budgets)
+ *            H_kv * w and H_kv * n, rounding as lava_layer_budgets); the budget applied to a
+ *            layer is min(B_t, entries it still holds)
  *   layer    first eviction of the new layer from its dense cache k_new, v_new [H_kv][n][d_h] by
- *            its scores [H_kv][n] (as written by lava_window_scores) into layers[layer], pool 0
- *   t<layer  re-eviction of every earlier layer from its current pool into the other one with the
- *            scores it retained; the budget actually applied is min(B_t, entries still held)
+ *            its scores [H_kv][n] (as written by lava_window_scores)
+ *   t<layer  re-eviction of every earlier layer from what it holds, ranked by the scores it
+ *            retained
+ * All layers are written into the other arena, back to back in layer order; state->cur flips.
  *
  *   e        device float [>= layer + 1]: statistics of layers 0..layer (point layer_stat of
  *            lava_window_scores at e + layer)
- *   layers   host array [layer + 1]
  *   budgets  device int64 [>= layer + 1] out
- * Everything is enqueued on the stream; nothing is read back.  Selection is integer-exact, rows
- * are bit copies, so the state after every step equals the literal algorithm's.
+ * Three launches, whatever the number of layers; everything is enqueued on the stream, nothing
+ * is read back.  Selection is integer-exact, rows are bit copies, so the state after every step
+ * equals the literal algorithm's.  layer < state->max_layers; total_budget <= state->capacity and
+ * within [H_kv * w, H_kv * n] * (layer + 1).
  */
 int32_t lava_cascade_step(const lava_layer_desc* desc, int32_t layer, int64_t n, const void* k_new,
                           const void* v_new, const float* scores_new, const float* e,
-                          int64_t total_budget, lava_cascade_layer* layers, int64_t* budgets,
+                          int64_t total_budget, lava_cascade_state* state, int64_t* budgets,
                           void* workspace, size_t workspace_bytes, void* hip_stream);
 
 /* Bytes of device workspace lava_decode_attention needs.  Returns 0 for invalid arguments. */

@@ -171,14 +171,17 @@ int32_t launch_decode(const lava_layer_desc& d, int32_t batch, const void* q, co
                       hipStream_t s);
 
 // ---------------------------------------------------------------- layer budgets
-// Sequential allocation shared by the host path and the device kernel (one thread per
-// sequence) so both give bit-identical integers.  scratch: 3 * n_layers doubles.
+// The host path runs the sequential allocation, the device kernel the same arithmetic spread over
+// one wavefront per sequence: bit-identical integers.
 int32_t budgets_host(int32_t batch, int32_t n_layers, const float* e, const int64_t* total,
                      const int64_t* lo, const int64_t* hi, int64_t* out);
 int32_t launch_budgets(int32_t batch, int32_t n_layers, const float* e, const int64_t* total,
                        const int64_t* lo, const int64_t* hi, int64_t* out, hipStream_t s);
-// one sequence, the same bounds for every layer, all scalars passed by value
-int32_t launch_budgets_uniform_bounds(int32_t n_layers, const float* e, int64_t total, int64_t lo, int64_t hi,
-                                      int64_t* out, hipStream_t s);
+// A cascade step's plan for one sequence: budgets of layers 0..n_layers-1 (bounds lo / hi for every
+// layer), the rows each keeps = min(budget, bound, rows it holds: head_offsets_cur[t][n_heads]
+// for t < n_layers - 1, hi for the newest), and layer_start[0..n_layers] = their prefix sums.
+int32_t launch_cascade_plan(int32_t n_layers, int32_t n_heads, const float* e, int64_t total, int64_t lo, int64_t hi,
+                            int64_t bound, const int64_t* head_offsets_cur, int64_t* budgets, int64_t* layer_start,
+                            hipStream_t s);
 
 }  // namespace lava

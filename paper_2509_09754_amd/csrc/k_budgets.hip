@@ -268,9 +268,15 @@ __global__ void __launch_bounds__(64) budgets_kernel(int n_layers, const float* 
     for (int i = threadIdx.x; i < n_layers; i += 64) out_b[i] = -1;
 }
 
-__global__ void __launch_bounds__(64) budgets_uniform_kernel(int n_layers, const float* __restrict__ e,
-                                                             long long total, long long lo, long long hi,
-                                                             int64_t* __restrict__ out) {
+// A step of the cascade: budgets of the layers seen so far (same bounds for every layer), then the
+// rows each layer will keep = its budget, but no more than it holds (for the newest layer: its
+// dense size `hi`), and from those the first row of every layer in the pool the step writes.
+__global__ void __launch_bounds__(64) cascade_plan_kernel(int n_layers, int n_heads, const float* __restrict__ e,
+                                                          long long total, long long lo, long long hi,
+                                                          long long bound,
+                                                          const int64_t* __restrict__ head_offsets_cur,
+                                                          int64_t* __restrict__ out,
+                                                          int64_t* __restrict__ layer_start) {
   __shared__ BudgetScratch sc;
   for (int i = threadIdx.x; i < n_layers; i += 64) {
     sc.ed[i] = (double)e[i];
@@ -283,14 +289,36 @@ __global__ void __launch_bounds__(64) budgets_uniform_kernel(int n_layers, const
                                         sc.frac, sc.state);
   if (bad)
     for (int i = threadIdx.x; i < n_layers; i += 64) out_b[i] = -1;
+  __syncthreads();
+  for (int t = threadIdx.x; t < n_layers; t += 64) {
+    long long held = hi;
+    if (t + 1 < n_layers) {
+      held = (long long)head_offsets_cur[(long long)t * (n_heads + 1) + n_heads];
+      held = held < 0 ? 0 : held;
+    }
+    const long long cap = held < bound ? held : bound;
+    long long kept = out_b[t];
+    kept = kept < 0 ? 0 : (kept < cap ? kept : cap);
+    sc.base[t] = kept;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    long long start = 0;
+    for (int t = 0; t < n_layers; ++t) {
+      layer_start[t] = start;
+      start += sc.base[t];
+    }
+    layer_start[n_layers] = start;
+  }
 }
 
-int32_t launch_budgets_uniform_bounds(int32_t n_layers, const float* e, int64_t total, int64_t lo, int64_t hi,
-                                      int64_t* out, hipStream_t s) {
+int32_t launch_cascade_plan(int32_t n_layers, int32_t n_heads, const float* e, int64_t total, int64_t lo, int64_t hi,
+                            int64_t bound, const int64_t* head_offsets_cur, int64_t* budgets, int64_t* layer_start,
+                            hipStream_t s) {
   if (n_layers > kMaxLayers) return LAVA_ERR_SHAPE;
   ProfScope ps(KID_BUDGETS, s);
-  hipLaunchKernelGGL(budgets_uniform_kernel, dim3(1), dim3(64), 0, s, n_layers, e, (long long)total,
-                     (long long)lo, (long long)hi, out);
+  hipLaunchKernelGGL(cascade_plan_kernel, dim3(1), dim3(64), 0, s, n_layers, n_heads, e, (long long)total,
+                     (long long)lo, (long long)hi, (long long)bound, head_offsets_cur, budgets, layer_start);
   return launch_status();
 }
 

@@ -409,7 +409,9 @@ __global__ void __launch_bounds__(kSelThreads) sel_fused_kernel(const SelectBatc
   unsigned int* hist = reinterpret_cast<unsigned int*>(region + a.off_hist);
   SelectState* st = reinterpret_cast<SelectState*>(region + a.off_state);
   unsigned int* blk = reinterpret_cast<unsigned int*>(region + a.off_blk);
-  const float* __restrict__ scores = pr.scores;
+  const long long in_off = pr.in_offset_dev ? (long long)*pr.in_offset_dev : 0;
+  const long long out_off = pr.out_offset_dev ? (long long)*pr.out_offset_dev : 0;
+  const float* __restrict__ scores = pr.scores + in_off;
   const int64_t* __restrict__ seg_offsets = pr.seg_offsets;
   const int n_heads = a.n_heads;
   const long long budget = pr.budget;
@@ -439,7 +441,8 @@ __global__ void __launch_bounds__(kSelThreads) sel_fused_kernel(const SelectBatc
   long long gt_before, eq_before;
   prefix_phase(bx, blk, a.blk_stride, sh, gt_before, eq_before);
   write_phase(bx, val, total, n_heads, seg_offsets, gt_mask, eq_mask, pk.need, budget, gt_before, eq_before,
-              kept_total, sh, pr.head_counts, pr.head_offsets, pr.kept_idx, pr.kept_scores);
+              kept_total, sh, pr.head_counts, pr.head_offsets, pr.kept_idx + out_off,
+              pr.kept_scores ? pr.kept_scores + out_off : nullptr);
 }
 
 // The same phases as separate launches (kernel boundaries take the place of the grid barriers),
@@ -459,7 +462,9 @@ __global__ void __launch_bounds__(kSelThreads) sel_step_kernel(const SelectBatch
   {
     const long long total = device_total(pr.total_entries, seg_offsets, n_heads);
     float val[kSelPerThread];
-    load_chunk(bx, pr.scores, total, sh, val);
+    const long long in_off = pr.in_offset_dev ? (long long)*pr.in_offset_dev : 0;
+    const long long out_off = pr.out_offset_dev ? (long long)*pr.out_offset_dev : 0;
+    load_chunk(bx, pr.scores + in_off, total, sh, val);
     Pick pk;
     pk.prefix = 0u;
     pk.need = effective_budget(budget, pr.budget_dev, total);
@@ -477,7 +482,8 @@ __global__ void __launch_bounds__(kSelThreads) sel_step_kernel(const SelectBatch
         long long gt_before, eq_before;
         prefix_phase(bx, blk, a.blk_stride, sh, gt_before, eq_before);
         write_phase(bx, val, total, n_heads, seg_offsets, gt_mask, eq_mask, pk.need, budget, gt_before, eq_before,
-                    kept_total, sh, pr.head_counts, pr.head_offsets, pr.kept_idx, pr.kept_scores);
+                    kept_total, sh, pr.head_counts, pr.head_offsets, pr.kept_idx + out_off,
+                    pr.kept_scores ? pr.kept_scores + out_off : nullptr);
       }
     }
   }
@@ -569,6 +575,8 @@ int32_t launch_select(int n_heads, const float* scores, const int64_t* seg_offse
   pr.head_offsets = head_offsets;
   pr.kept_idx = kept_idx;
   pr.kept_scores = kept_scores;
+  pr.in_offset_dev = nullptr;
+  pr.out_offset_dev = nullptr;
   return launch_select_batch(n_heads, 1, &pr, total, ws, s);
 }
 

@@ -335,22 +335,27 @@ int32_t lava_compact_packed(const lava_layer_desc* desc, const int64_t* src_offs
   return lava_compact_batch(desc, 1, &p, hip_stream);
 }
 
-size_t lava_cascade_workspace_bytes(const lava_layer_desc* desc, int64_t n, int32_t n_layers, int64_t capacity) {
-  if (check_desc(desc) != LAVA_OK || n <= desc->window || n_layers < 1 || n_layers > 1024 || capacity < 1) return 0;
+// Entries a layer can hold when a step starts: the dense layer, or at most the whole budget.
+static int64_t cascade_layer_bound(int64_t dense, int64_t total_budget) {
+  return total_budget < dense ? total_budget : dense;
+}
+
+size_t lava_cascade_workspace_bytes(const lava_layer_desc* desc, int64_t n, int32_t n_layers, int64_t total_budget) {
+  if (check_desc(desc) != LAVA_OK || n <= desc->window || n_layers < 1 || n_layers > 1024 || total_budget < 1)
+    return 0;
   const int64_t dense = (int64_t)desc->n_kv_heads * n;
-  const int64_t widest = dense > capacity ? dense : capacity;
-  if (widest >= (int64_t)1 << 31) return 0;
-  return make_select_workspace(widest).bytes * (size_t)n_layers;
+  if (dense >= (int64_t)1 << 31) return 0;
+  return make_select_workspace(dense).bytes * (size_t)n_layers;
 }
 
 int32_t lava_cascade_step(const lava_layer_desc* desc, int32_t layer, int64_t n, const void* k_new,
                           const void* v_new, const float* scores_new, const float* e,
-                          int64_t total_budget, lava_cascade_layer* layers, int64_t* budgets,
+                          int64_t total_budget, lava_cascade_state* state, int64_t* budgets,
                           void* workspace, size_t workspace_bytes, void* hip_stream) {
   int32_t st = check_desc(desc);
   if (st != LAVA_OK) return st;
   if (layer < 0 || k_new == nullptr || v_new == nullptr || scores_new == nullptr || e == nullptr ||
-      layers == nullptr || budgets == nullptr)
+      state == nullptr || budgets == nullptr)
     return LAVA_ERR_INVALID_ARG;
   if (n <= desc->window || layer >= 1024) return LAVA_ERR_SHAPE;
   const int64_t dense = (int64_t)desc->n_kv_heads * n;
@@ -358,52 +363,55 @@ int32_t lava_cascade_step(const lava_layer_desc* desc, int32_t layer, int64_t n,
   const int64_t lo = (int64_t)desc->n_kv_heads * desc->window;
   if (total_budget < lo * (layer + 1) || total_budget > dense * (layer + 1)) return LAVA_ERR_BUDGET;
   if (!aligned16(k_new) || !aligned16(v_new)) return LAVA_ERR_INVALID_ARG;
-  const int64_t first_cap = total_budget < dense ? total_budget : dense;
-  int64_t widest = dense;
-  for (int t = 0; t <= layer; ++t) {
-    const lava_cascade_layer& L = layers[t];
-    for (int i = 0; i < 2; ++i)
-      if (L.k[i] == nullptr || L.v[i] == nullptr || L.pos[i] == nullptr || L.scores[i] == nullptr ||
-          L.head_offsets[i] == nullptr || !aligned16(L.k[i]) || !aligned16(L.v[i]))
-        return LAVA_ERR_INVALID_ARG;
-    if (L.head_counts == nullptr || L.kept_idx == nullptr || (L.cur != 0 && L.cur != 1)) return LAVA_ERR_INVALID_ARG;
-    if (L.capacity < first_cap || L.capacity >= (int64_t)1 << 31) return LAVA_ERR_BUDGET;
-    if (t < layer && L.capacity > widest) widest = L.capacity;
-  }
+  lava_cascade_state& S = *state;
+  for (int i = 0; i < 2; ++i)
+    if (S.k[i] == nullptr || S.v[i] == nullptr || S.pos[i] == nullptr || S.scores[i] == nullptr ||
+        S.head_offsets[i] == nullptr || S.layer_start[i] == nullptr || !aligned16(S.k[i]) || !aligned16(S.v[i]))
+      return LAVA_ERR_INVALID_ARG;
+  if (S.head_counts == nullptr || S.kept_idx == nullptr || (S.cur != 0 && S.cur != 1) || S.max_layers < 1)
+    return LAVA_ERR_INVALID_ARG;
+  if (layer >= S.max_layers) return LAVA_ERR_SHAPE;
+  if (S.capacity < total_budget || S.capacity >= (int64_t)1 << 31) return LAVA_ERR_BUDGET;
+  const int64_t bound = cascade_layer_bound(dense, total_budget);
   if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 ||
-      workspace_bytes < make_select_workspace(widest).bytes * (size_t)(layer + 1))
+      workspace_bytes < make_select_workspace(dense).bytes * (size_t)(layer + 1))
     return LAVA_ERR_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  const int H1 = desc->n_kv_heads + 1;
+  const int a = S.cur, b = 1 - S.cur;
 
-  st = launch_budgets_uniform_bounds(layer + 1, e, total_budget, lo, dense, budgets, s);
+  // budgets of the layers seen so far, and from them where every layer will start in the other arena
+  st = launch_cascade_plan(layer + 1, desc->n_kv_heads, e, total_budget, lo, dense, bound, S.head_offsets[a],
+                           budgets, S.layer_start[b], s);
   if (st != LAVA_OK) return st;
 
-  // One table of selections and one of compactions: the new layer first (dense scores, equal
-  // segments, its state starts in pool 0), then every earlier layer from what it still holds
-  // into its other pool, ranked by the scores it retained.
+  // One table of selections and one of compactions: every earlier layer from what it holds in the
+  // current arena, ranked by the scores it retained, then the new layer from its dense cache.
   std::vector<lava_select_problem> sel(layer + 1);
   std::vector<lava_compact_problem> cmp(layer + 1);
-  {
-    lava_cascade_layer& L = layers[layer];
-    sel[0] = {scores_new,   nullptr,           dense,      first_cap,  budgets + layer,
-              L.head_counts, L.head_offsets[0], L.kept_idx, L.scores[0]};
-    cmp[0] = {n,          nullptr,   k_new,  v_new,  nullptr, L.head_offsets[0],
-              L.kept_idx, first_cap, L.k[0], L.v[0], L.pos[0]};
+  for (int t = 0; t <= layer; ++t) {
+    int32_t* counts = S.head_counts + (size_t)t * desc->n_kv_heads;
+    int64_t* offs_new = S.head_offsets[b] + (size_t)t * H1;
+    const int64_t* start_new = S.layer_start[b] + t;
+    if (t < layer) {
+      const int64_t* offs_cur = S.head_offsets[a] + (size_t)t * H1;
+      const int64_t* start_cur = S.layer_start[a] + t;
+      sel[t] = {S.scores[a], offs_cur, bound,      bound,       budgets + t, counts,
+                offs_new,    S.kept_idx, S.scores[b], start_cur, start_new};
+      cmp[t] = {S.capacity, offs_cur, S.k[a], S.v[a], S.pos[a],  offs_new,  S.kept_idx,
+                S.capacity, S.k[b],   S.v[b], S.pos[b], start_cur, start_new};
+    } else {
+      sel[t] = {scores_new, nullptr,    dense,       bound,   budgets + t, counts,
+                offs_new,   S.kept_idx, S.scores[b], nullptr, start_new};
+      cmp[t] = {n,          nullptr, k_new,  v_new,    nullptr, offs_new, S.kept_idx,
+                S.capacity, S.k[b],  S.v[b], S.pos[b], nullptr, start_new};
+    }
   }
-  for (int t = 0; t < layer; ++t) {
-    lava_cascade_layer& L = layers[t];
-    const int a = L.cur, b = 1 - L.cur;
-    sel[t + 1] = {L.scores[a],   L.head_offsets[a], L.capacity, L.capacity, budgets + t,
-                  L.head_counts, L.head_offsets[b], L.kept_idx, L.scores[b]};
-    cmp[t + 1] = {L.capacity, L.head_offsets[a], L.k[a], L.v[a], L.pos[a], L.head_offsets[b],
-                  L.kept_idx, L.capacity,        L.k[b], L.v[b], L.pos[b]};
-  }
-  st = launch_select_batch(desc->n_kv_heads, layer + 1, sel.data(), widest, workspace, s);
+  st = launch_select_batch(desc->n_kv_heads, layer + 1, sel.data(), dense, workspace, s);
   if (st != LAVA_OK) return st;
   st = launch_compact_batch(*desc, layer + 1, cmp.data(), s);
   if (st != LAVA_OK) return st;
-  layers[layer].cur = 0;
-  for (int t = 0; t < layer; ++t) layers[t].cur = 1 - layers[t].cur;
+  S.cur = b;
   return LAVA_OK;
 }
 

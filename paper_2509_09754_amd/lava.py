@@ -266,6 +266,7 @@ class SelectProblem(ctypes.Structure):
         ("scores", ctypes.c_void_p), ("seg_offsets", ctypes.c_void_p), ("total_entries", ctypes.c_int64),
         ("budget", ctypes.c_int64), ("budget_dev", ctypes.c_void_p), ("head_counts", ctypes.c_void_p),
         ("head_offsets", ctypes.c_void_p), ("kept_idx", ctypes.c_void_p), ("kept_scores", ctypes.c_void_p),
+        ("in_offset_dev", ctypes.c_void_p), ("out_offset_dev", ctypes.c_void_p),
     ]
 
 
@@ -276,6 +277,7 @@ class CompactProblem(ctypes.Structure):
         ("v_src", ctypes.c_void_p), ("pos_src", ctypes.c_void_p), ("head_offsets", ctypes.c_void_p),
         ("kept_idx", ctypes.c_void_p), ("capacity", ctypes.c_int64), ("k_out", ctypes.c_void_p),
         ("v_out", ctypes.c_void_p), ("pos_out", ctypes.c_void_p),
+        ("src_offset_dev", ctypes.c_void_p), ("out_offset_dev", ctypes.c_void_p),
     ]
 
 
@@ -284,32 +286,36 @@ def _addr(t: Optional[torch.Tensor]):
 
 
 def select_problem(scores, budget, head_counts, head_offsets, kept_idx, kept_scores=None, seg_offsets=None,
-                   budget_dev=None, total_entries=None) -> SelectProblem:
+                   budget_dev=None, total_entries=None, in_offset_dev=None, out_offset_dev=None) -> SelectProblem:
     """One row of the table of lava_select_topk_batch from device tensors (the caller keeps them alive)."""
     _dev(scores, "scores", torch.float32), _dev(head_counts, "head_counts", torch.int32)
     _dev(head_offsets, "head_offsets", torch.int64), _dev(kept_idx, "kept_idx", torch.int32)
     for name, t, dt in (("kept_scores", kept_scores, torch.float32), ("seg_offsets", seg_offsets, torch.int64),
-                        ("budget_dev", budget_dev, torch.int64)):
+                        ("budget_dev", budget_dev, torch.int64), ("in_offset_dev", in_offset_dev, torch.int64),
+                        ("out_offset_dev", out_offset_dev, torch.int64)):
         if t is not None:
             _dev(t, name, dt)
     total = scores.numel() if total_entries is None else int(total_entries)
     return SelectProblem(_addr(scores), _addr(seg_offsets), total, int(budget), _addr(budget_dev),
-                         _addr(head_counts), _addr(head_offsets), _addr(kept_idx), _addr(kept_scores))
+                         _addr(head_counts), _addr(head_offsets), _addr(kept_idx), _addr(kept_scores),
+                         _addr(in_offset_dev), _addr(out_offset_dev))
 
 
 def compact_problem(desc: LayerDesc, src_rows, k_src, v_src, head_offsets, kept_idx, capacity, k_out, v_out,
-                    src_offsets=None, pos_src=None, pos_out=None) -> CompactProblem:
+                    src_offsets=None, pos_src=None, pos_out=None, src_offset_dev=None,
+                    out_offset_dev=None) -> CompactProblem:
     """One row of the table of lava_compact_batch (dense source when src_offsets is None)."""
     for name, t in (("k_src", k_src), ("v_src", v_src), ("k_out", k_out), ("v_out", v_out)):
         _dev(t, name, desc.torch_dtype)
     _dev(head_offsets, "head_offsets", torch.int64), _dev(kept_idx, "kept_idx", torch.int32)
     for name, t, dt in (("src_offsets", src_offsets, torch.int64), ("pos_src", pos_src, torch.int32),
-                        ("pos_out", pos_out, torch.int32)):
+                        ("pos_out", pos_out, torch.int32), ("src_offset_dev", src_offset_dev, torch.int64),
+                        ("out_offset_dev", out_offset_dev, torch.int64)):
         if t is not None:
             _dev(t, name, dt)
     return CompactProblem(int(src_rows), _addr(src_offsets), _addr(k_src), _addr(v_src), _addr(pos_src),
                           _addr(head_offsets), _addr(kept_idx), int(capacity), _addr(k_out), _addr(v_out),
-                          _addr(pos_out))
+                          _addr(pos_out), _addr(src_offset_dev), _addr(out_offset_dev))
 
 
 def lava_select_batch_workspace_bytes(n_problems: int, max_total_entries: int) -> int:
@@ -381,55 +387,71 @@ def lava_compact_packed(desc: LayerDesc, src_offsets: torch.Tensor, k_src: torch
     return k_out, v_out, pos_out
 
 
-class CascadeLayer(ctypes.Structure):
-    """Mirror of lava_cascade_layer."""
+class CascadeStateStruct(ctypes.Structure):
+    """Mirror of lava_cascade_state."""
     _fields_ = [
         ("k", ctypes.c_void_p * 2), ("v", ctypes.c_void_p * 2), ("pos", ctypes.c_void_p * 2),
-        ("scores", ctypes.c_void_p * 2), ("head_offsets", ctypes.c_void_p * 2),
+        ("scores", ctypes.c_void_p * 2), ("head_offsets", ctypes.c_void_p * 2), ("layer_start", ctypes.c_void_p * 2),
         ("head_counts", ctypes.c_void_p), ("kept_idx", ctypes.c_void_p),
-        ("capacity", ctypes.c_int64), ("cur", ctypes.c_int32), ("reserved", ctypes.c_int32),
+        ("capacity", ctypes.c_int64), ("max_layers", ctypes.c_int32), ("cur", ctypes.c_int32),
     ]
 
 
 class CascadeState:
-    """Device buffers of a stack of layers for lava_cascade_step (allocation and views only)."""
+    """Device buffers of a stack of layers for lava_cascade_step (allocation and views only): two arenas of
+    `capacity` rows in which the layers sit back to back, plus the per-layer offsets."""
 
-    def __init__(self, desc: LayerDesc, n_layers: int, capacity: int, device="cuda"):
-        self.desc, self.n_layers, self.capacity = desc, n_layers, int(capacity)
-        self.layers = (CascadeLayer * n_layers)()
-        self.tensors = []
-        for t in range(n_layers):
-            bufs = {}
-            for i in range(2):
-                bufs[f"k{i}"] = torch.empty(capacity, desc.head_dim, dtype=desc.torch_dtype, device=device)
-                bufs[f"v{i}"] = torch.empty(capacity, desc.head_dim, dtype=desc.torch_dtype, device=device)
-                bufs[f"pos{i}"] = torch.empty(capacity, dtype=torch.int32, device=device)
-                bufs[f"scores{i}"] = torch.empty(capacity, dtype=torch.float32, device=device)
-                bufs[f"offs{i}"] = torch.zeros(desc.n_kv_heads + 1, dtype=torch.int64, device=device)
-                self.layers[t].k[i] = bufs[f"k{i}"].data_ptr()
-                self.layers[t].v[i] = bufs[f"v{i}"].data_ptr()
-                self.layers[t].pos[i] = bufs[f"pos{i}"].data_ptr()
-                self.layers[t].scores[i] = bufs[f"scores{i}"].data_ptr()
-                self.layers[t].head_offsets[i] = bufs[f"offs{i}"].data_ptr()
-            bufs["counts"] = torch.zeros(desc.n_kv_heads, dtype=torch.int32, device=device)
-            bufs["idx"] = torch.empty(capacity, dtype=torch.int32, device=device)
-            self.layers[t].head_counts = bufs["counts"].data_ptr()
-            self.layers[t].kept_idx = bufs["idx"].data_ptr()
-            self.layers[t].capacity = capacity
-            self.layers[t].cur = 0
-            self.tensors.append(bufs)
-        self.e = torch.zeros(n_layers, dtype=torch.float32, device=device)
-        self.budgets = torch.zeros(n_layers, dtype=torch.int64, device=device)
+    def __init__(self, desc: LayerDesc, max_layers: int, capacity: int, device="cuda"):
+        self.desc, self.n_layers, self.capacity = desc, int(max_layers), int(capacity)
+        hk = desc.n_kv_heads
+        self.k = [torch.empty(capacity, desc.head_dim, dtype=desc.torch_dtype, device=device) for _ in range(2)]
+        self.v = [torch.empty(capacity, desc.head_dim, dtype=desc.torch_dtype, device=device) for _ in range(2)]
+        self.pos = [torch.empty(capacity, dtype=torch.int32, device=device) for _ in range(2)]
+        self.scores = [torch.empty(capacity, dtype=torch.float32, device=device) for _ in range(2)]
+        self.head_offsets = [torch.zeros(max_layers, hk + 1, dtype=torch.int64, device=device) for _ in range(2)]
+        self.layer_start = [torch.zeros(max_layers + 1, dtype=torch.int64, device=device) for _ in range(2)]
+        self.head_counts = torch.zeros(max_layers, hk, dtype=torch.int32, device=device)
+        self.kept_idx = torch.empty(capacity, dtype=torch.int32, device=device)
+        self.e = torch.zeros(max_layers, dtype=torch.float32, device=device)
+        self.budgets = torch.zeros(max_layers, dtype=torch.int64, device=device)
+        c = self.c = CascadeStateStruct()
+        for i in range(2):
+            c.k[i], c.v[i], c.pos[i] = self.k[i].data_ptr(), self.v[i].data_ptr(), self.pos[i].data_ptr()
+            c.scores[i] = self.scores[i].data_ptr()
+            c.head_offsets[i], c.layer_start[i] = self.head_offsets[i].data_ptr(), self.layer_start[i].data_ptr()
+        c.head_counts, c.kept_idx = self.head_counts.data_ptr(), self.kept_idx.data_ptr()
+        c.capacity, c.max_layers, c.cur = self.capacity, self.n_layers, 0
+
+    @property
+    def cur(self) -> int:
+        return int(self.c.cur)
+
+    def reset(self) -> None:
+        self.c.cur = 0
+
+    def bytes(self) -> int:
+        """Device bytes the state holds."""
+        ts = self.k + self.v + self.pos + self.scores + self.head_offsets + self.layer_start
+        ts += [self.head_counts, self.kept_idx, self.e, self.budgets]
+        return sum(t.numel() * t.element_size() for t in ts)
+
+    def decode_args(self, t: int) -> dict:
+        """What lava_decode_attention needs to read layer t in place (nothing is read back)."""
+        c = self.cur
+        return dict(k_hat=self.k[c], v_hat=self.v[c], head_offsets=self.head_offsets[c][t: t + 1],
+                    seq_base=self.layer_start[c][t: t + 1], rows_capacity=self.capacity)
 
     def current(self, t: int) -> dict:
-        """Views of layer t's current state."""
-        c, b = self.layers[t].cur, self.tensors[t]
-        return dict(k_hat=b[f"k{c}"], v_hat=b[f"v{c}"], pos=b[f"pos{c}"], scores=b[f"scores{c}"],
-                    head_offsets=b[f"offs{c}"], head_counts=b["counts"])
+        """Views of layer t's current state (reads the layer's extent back: synchronises)."""
+        c = self.cur
+        start, end = (int(x) for x in self.layer_start[c][t: t + 2].cpu())
+        return dict(k_hat=self.k[c][start:end], v_hat=self.v[c][start:end], pos=self.pos[c][start:end],
+                    scores=self.scores[c][start:end], head_offsets=self.head_offsets[c][t],
+                    head_counts=self.head_counts[t], start=start)
 
 
-def lava_cascade_workspace_bytes(desc: LayerDesc, n: int, n_layers: int, capacity: int) -> int:
-    return int(lib.lava_cascade_workspace_bytes(ctypes.byref(desc), int(n), int(n_layers), int(capacity)))
+def lava_cascade_workspace_bytes(desc: LayerDesc, n: int, n_layers: int, total_budget: int) -> int:
+    return int(lib.lava_cascade_workspace_bytes(ctypes.byref(desc), int(n), int(n_layers), int(total_budget)))
 
 
 def lava_cascade_step(desc: LayerDesc, layer: int, n: int, k_new: torch.Tensor, v_new: torch.Tensor,
@@ -438,10 +460,10 @@ def lava_cascade_step(desc: LayerDesc, layer: int, n: int, k_new: torch.Tensor, 
     _dev(k_new, "k_new", desc.torch_dtype), _dev(v_new, "v_new", desc.torch_dtype)
     _dev(scores_new, "scores_new", torch.float32)
     if workspace is None:
-        need = lava_cascade_workspace_bytes(desc, n, state.n_layers, state.capacity)
+        need = lava_cascade_workspace_bytes(desc, n, state.n_layers, total_budget)
         workspace = torch.empty(max(need, 256), dtype=torch.uint8, device=k_new.device)
     st = lib.lava_cascade_step(ctypes.byref(desc), int(layer), int(n), _ptr(k_new), _ptr(v_new), _ptr(scores_new),
-                               _ptr(state.e), int(total_budget), ctypes.cast(state.layers, ctypes.c_void_p),
+                               _ptr(state.e), int(total_budget), ctypes.byref(state.c),
                                _ptr(state.budgets), _ptr(workspace), workspace.numel(), _stream(stream))
     _check(st, "lava_cascade_step")
     return workspace

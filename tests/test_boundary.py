@@ -185,37 +185,40 @@ def test_cascade_and_packed_compaction_argument_errors():
     assert cp(cap=1001) == lava.LAVA_ERR_BUDGET
     assert cp(cap=0) == lava.LAVA_OK                              # nothing to move, nothing launched
 
-    layer = lava.CascadeLayer()
+    state = lava.CascadeStateStruct()
     for i in range(2):
-        layer.k[i] = layer.v[i] = layer.pos[i] = layer.scores[i] = layer.head_offsets[i] = 0x10000
-    layer.head_counts = layer.kept_idx = 0x10000
-    layer.capacity, layer.cur = 8192, 0
+        state.k[i] = state.v[i] = state.pos[i] = state.scores[i] = 0x10000
+        state.head_offsets[i] = state.layer_start[i] = 0x10000
+    state.head_counts = state.kept_idx = 0x10000
+    state.capacity, state.max_layers, state.cur = 8192, 4, 0
     n = 4096
-    step = lambda lay=layer, layer_idx=0, total=8192, ws=FAKE, wsb=1 << 40, nn=n: L.lava_cascade_step(
-        ctypes.byref(d), layer_idx, nn, FAKE, FAKE, FAKE, FAKE, total, ctypes.byref(lay), FAKE, ws, wsb, None)
+    step = lambda st=state, layer_idx=0, total=8192, ws=FAKE, wsb=1 << 40, nn=n: L.lava_cascade_step(
+        ctypes.byref(d), layer_idx, nn, FAKE, FAKE, FAKE, FAKE, total, ctypes.byref(st), FAKE, ws, wsb, None)
     assert step(total=8 * 32 - 1) == lava.LAVA_ERR_BUDGET         # below H_kv * w per layer
     assert step(total=8 * n + 1) == lava.LAVA_ERR_BUDGET          # more than the layers seen so far hold
     assert step(nn=32) == lava.LAVA_ERR_SHAPE
+    assert step(layer_idx=4, total=5 * 8192) == lava.LAVA_ERR_SHAPE        # beyond max_layers
     assert step(ws=None) == lava.LAVA_ERR_WORKSPACE
     assert step(wsb=16) == lava.LAVA_ERR_WORKSPACE
-    small = lava.CascadeLayer.from_buffer_copy(layer)
-    small.capacity = 100
-    assert step(lay=small) == lava.LAVA_ERR_BUDGET                # pools smaller than the first budget
-    broken = lava.CascadeLayer.from_buffer_copy(layer)
-    broken.pos[1] = None
-    assert step(lay=broken) == lava.LAVA_ERR_INVALID_ARG
-    assert lava.lava_cascade_workspace_bytes(d, n, 1, 8192) == lava.lava_select_workspace_bytes(8 * n)
-    assert lava.lava_cascade_workspace_bytes(d, n, 5, 8192) == 5 * lava.lava_select_workspace_bytes(8 * n)
-    assert lava.lava_cascade_workspace_bytes(d, n, 2, 16 * n) == 2 * lava.lava_select_workspace_bytes(16 * n)
+    assert step(layer_idx=1, total=8193) == lava.LAVA_ERR_BUDGET  # the arenas hold `capacity` rows in all
+    broken = lava.CascadeStateStruct.from_buffer_copy(state)
+    broken.layer_start[1] = None
+    assert step(st=broken) == lava.LAVA_ERR_INVALID_ARG
+    broken = lava.CascadeStateStruct.from_buffer_copy(state)
+    broken.cur = 2
+    assert step(st=broken) == lava.LAVA_ERR_INVALID_ARG
+    one = lava.lava_select_workspace_bytes(8 * n)
+    assert lava.lava_cascade_workspace_bytes(d, n, 1, 8192) == one
+    assert lava.lava_cascade_workspace_bytes(d, n, 5, 8192) == 5 * one
     assert lava.lava_cascade_workspace_bytes(d, 16, 1, 8192) == 0
     assert lava.lava_cascade_workspace_bytes(d, n, 0, 8192) == 0
-    assert step(layer_idx=0, wsb=lava.lava_select_workspace_bytes(8 * n) - 1) == lava.LAVA_ERR_WORKSPACE
+    assert step(layer_idx=0, wsb=one - 1) == lava.LAVA_ERR_WORKSPACE
 
 
 def test_batch_select_and_compact_argument_errors():
     L = lava.lib
     big = 1 << 40
-    good = lava.SelectProblem(0x10000, None, 8 * 1024, 100, None, 0x10000, 0x10000, 0x10000, None)
+    good = lava.SelectProblem(0x10000, None, 8 * 1024, 100, None, 0x10000, 0x10000, 0x10000, None, None, None)
 
     def sel(problems, nh=8, widest=8 * 1024, ws=FAKE, wsb=big):
         table = (lava.SelectProblem * max(len(problems), 1))(*problems)
@@ -243,7 +246,8 @@ def test_batch_select_and_compact_argument_errors():
     assert L.lava_select_batch_status(FAKE, 0, 1024, None) == lava.LAVA_ERR_INVALID_ARG
 
     d = _desc()
-    okc = lava.CompactProblem(1024, None, 0x10000, 0x10000, None, 0x10000, 0x10000, 0, 0x10000, 0x10000, None)
+    okc = lava.CompactProblem(1024, None, 0x10000, 0x10000, None, 0x10000, 0x10000, 0, 0x10000, 0x10000, None, None,
+                              None)
 
     def cmp(problems):
         table = (lava.CompactProblem * max(len(problems), 1))(*problems)

@@ -228,3 +228,62 @@ def test_ragged_batch_full_size_one_layer(lava):
         assert np.array_equal(lava.to_host_bits(v_hat[b]), O.compact(inp.v, ro, ri))
     say(f"   worst score error {worst:.2e}, least kept-set overlap {least:.5f}")
     assert least >= 0.999
+
+
+def test_tables_with_device_side_offsets(lava):
+    """Problems whose data sit back to back in shared buffers at offsets only the device knows (the layout
+    of the cascade's pools): selection reads / writes at the offsets, compaction gathers from and to them."""
+    say("select + compact batch: packed inputs and outputs addressed through device-side offsets")
+    dev = "cuda"
+    Hkv, d = 4, 64
+    desc = lava.LayerDesc.make(8, Hkv, d, 8, "bf16")
+    r = np.random.Generator(np.random.PCG64(33))
+    held = [900, 40, 3000]                                    # rows each source layer holds
+    budgets = [300, 40, 1111]
+    src_start = np.concatenate([[0], np.cumsum(held)]).astype(np.int64)
+    out_start = np.concatenate([[0], np.cumsum(budgets)]).astype(np.int64)
+    pool = int(src_start[-1]) + 7
+    k_src = synth.store(r.standard_normal((pool, d), dtype=np.float32), "bf16")
+    v_src = synth.store(r.standard_normal((pool, d), dtype=np.float32), "bf16")
+    pos_src = r.integers(0, 1 << 20, pool).astype(np.int32)
+    sc_src = synth.random_scores(1, pool, 5).ravel()
+    seg = []
+    for h in held:
+        cuts = np.sort(r.integers(0, h + 1, Hkv - 1))
+        seg.append(np.concatenate([[0], cuts, [h]]).astype(np.int64))
+    out_rows = int(out_start[-1])
+    t = dict(k=lava.to_device(k_src, "bf16", dev), v=lava.to_device(v_src, "bf16", dev),
+             pos=torch.from_numpy(pos_src).to(dev), sc=torch.from_numpy(sc_src).to(dev),
+             src_start=torch.from_numpy(src_start).to(dev), out_start=torch.from_numpy(out_start).to(dev),
+             seg=[torch.from_numpy(x).to(dev) for x in seg],
+             counts=torch.zeros(3, Hkv, dtype=torch.int32, device=dev),
+             offs=torch.zeros(3, Hkv + 1, dtype=torch.int64, device=dev),
+             idx=torch.full((out_rows + 3,), -7, dtype=torch.int32, device=dev),
+             ks=torch.full((out_rows + 3,), -7.0, dtype=torch.float32, device=dev),
+             ko=torch.full((out_rows + 3, d), 5.0, dtype=torch.bfloat16, device=dev),
+             vo=torch.full((out_rows + 3, d), 5.0, dtype=torch.bfloat16, device=dev),
+             po=torch.full((out_rows + 3,), -3, dtype=torch.int32, device=dev))
+    sel, cmp = [], []
+    for i in range(3):
+        sel.append(lava.select_problem(t["sc"], budgets[i], t["counts"][i], t["offs"][i], t["idx"], t["ks"],
+                                       seg_offsets=t["seg"][i], total_entries=held[i],
+                                       in_offset_dev=t["src_start"][i: i + 1], out_offset_dev=t["out_start"][i: i + 1]))
+        cmp.append(lava.compact_problem(desc, pool, t["k"], t["v"], t["offs"][i], t["idx"], out_rows, t["ko"], t["vo"],
+                                        src_offsets=t["seg"][i], pos_src=t["pos"], pos_out=t["po"],
+                                        src_offset_dev=t["src_start"][i: i + 1], out_offset_dev=t["out_start"][i: i + 1]))
+    lava.lava_select_topk_batch(Hkv, sel, max(held))
+    lava.lava_compact_batch(desc, cmp)
+    torch.cuda.synchronize()
+    idx, ks = t["idx"].cpu().numpy(), t["ks"].cpu().numpy()
+    for i in range(3):
+        a, b = int(src_start[i]), int(src_start[i + 1])
+        rc, ro, ri, rs = O.select_topk(sc_src[a:b].astype(np.float64), seg[i], budgets[i])
+        o0 = int(out_start[i])
+        assert np.array_equal(t["counts"][i].cpu().numpy(), rc) and np.array_equal(t["offs"][i].cpu().numpy(), ro), i
+        assert np.array_equal(idx[o0: o0 + budgets[i]], ri), i
+        assert np.array_equal(ks[o0: o0 + budgets[i]].view(np.uint32), np.asarray(rs, np.float32).view(np.uint32)), i
+        rows = np.concatenate([a + seg[i][g] + ri[ro[g]: ro[g + 1]] for g in range(Hkv)]).astype(np.int64)
+        assert np.array_equal(lava.to_host_bits(t["ko"][o0: o0 + budgets[i]]), k_src[rows]), i
+        assert np.array_equal(lava.to_host_bits(t["vo"][o0: o0 + budgets[i]]), v_src[rows]), i
+        assert np.array_equal(t["po"][o0: o0 + budgets[i]].cpu().numpy(), pos_src[rows]), i
+    assert np.all(idx[out_rows:] == -7) and torch.all(t["ko"][out_rows:] == 5.0) and torch.all(t["po"][out_rows:] == -3)

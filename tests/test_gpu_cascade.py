@@ -34,6 +34,7 @@ def check_state(lava, state, t, ref_state, k_store, v_store, dtype, tag):
     offs = cur["head_offsets"].cpu().numpy()
     assert np.array_equal(offs, offs_ref), (tag, offs, offs_ref)
     kept = int(offs[-1])
+    assert cur["pos"].shape[0] == kept, tag                      # the layer's extent in the arena is exactly what it holds
     assert np.array_equal(cur["pos"][:kept].cpu().numpy(), pos_ref), tag
     assert np.array_equal(cur["scores"][:kept].cpu().numpy().view(np.uint32),
                           sc_ref.astype(np.float32).view(np.uint32)), tag
@@ -50,8 +51,7 @@ def check_state(lava, state, t, ref_state, k_store, v_store, dtype, tag):
 def run_cascade(lava, shape, n_layers, total_budget, seeds, use_gpu_scores):
     H, Hkv, d, N, w = shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.n, shape.window
     desc = lava.LayerDesc.make(H, Hkv, d, w, shape.dtype, pool_kernel=shape.pool_kernel)
-    cap = min(total_budget, Hkv * N)
-    state = lava.CascadeState(desc, n_layers, cap)
+    state = lava.CascadeState(desc, n_layers, total_budget)      # two arenas of `total_budget` rows, whatever the depth
     layer_scores, ents, stores = [], [], []
     ws = None
     for l in range(n_layers):
@@ -78,6 +78,8 @@ def run_cascade(lava, shape, n_layers, total_budget, seeds, use_gpu_scores):
         # oracle: the literal algorithm on the layers seen so far, same scores, same statistics
         ref_state, history = O.cascade(layer_scores, N, total_budget, w, entropies=ents)
         assert state.budgets[: l + 1].cpu().numpy().tolist() == history[-1], (l, history[-1])
+        starts = state.layer_start[state.cur][: l + 2].cpu().numpy()
+        assert starts[0] == 0 and np.array_equal(np.diff(starts), [int(r[0][-1]) for r in ref_state])   # back to back
         for t in range(l + 1):
             check_state(lava, state, t, ref_state[t], stores[t][0], stores[t][1], shape.dtype, f"step {l} layer {t}")
     return state, history
@@ -110,6 +112,7 @@ def test_cascade_first_layer_takes_everything(lava):
     run_cascade(lava, shape, 3, total, dict(base=300, fracs=fr), use_gpu_scores=False)
     desc = lava.LayerDesc.make(shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.window, shape.dtype)
     state = lava.CascadeState(desc, 1, total + 1)
+    assert state.bytes() < 3 * (total + 1) * (2 * shape.head_dim * 4 + 12)        # two arenas + scratch, not per layer
     dummy = torch.zeros(shape.n_kv_heads * 600 * shape.head_dim, dtype=torch.float32, device="cuda")
     with pytest.raises(lava.LavaError) as ei:   # more than the layers seen so far can hold: infeasible, as in the oracle
         lava.lava_cascade_step(desc, 0, 600, dummy, dummy, dummy[: shape.n_kv_heads * 600], state, total + 1)
@@ -161,3 +164,27 @@ def test_select_reads_total_from_segment_offsets(lava):
     counts, o, idx, ks = lava.lava_select_topk(nh, sc, 4000, seg_offsets=torch.from_numpy(offs).cuda())
     torch.cuda.synchronize()
     assert counts.cpu().numpy().tolist() == [1000, 0, 1600, 500] and int(o[-1]) == 3100
+
+
+def test_decode_reads_a_cascade_layer_in_place(lava):
+    say("cascade: decode attention over layer 1 of a 3-layer state, straight from the arena")
+    shape = synth.config(2, n=2048 + 9, budget=512)
+    fr = synth.stack_heavy_fracs(3, 2)
+    state, _ = run_cascade(lava, shape, 3, 3 * 512, dict(base=400, fracs=fr), use_gpu_scores=True)
+    H, Hkv, d = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
+    desc = lava.LayerDesc.make(H, Hkv, d, shape.window, shape.dtype)
+    r = np.random.Generator(np.random.PCG64(8))
+    q_new = synth.store(r.standard_normal((1, H, d), dtype=np.float32), shape.dtype)
+    args = state.decode_args(1)
+    out, lse = lava.lava_decode_attention(desc, 1, lava.to_device(q_new, shape.dtype), args["k_hat"], args["v_hat"],
+                                          args["head_offsets"], args["rows_capacity"], seq_base=args["seq_base"])
+    torch.cuda.synchronize()
+    cur = state.current(1)
+    want, want_lse = O.decode_attention(synth.load_f64(q_new, shape.dtype)[0],
+                                        synth.load_f64(lava.to_host_bits(cur["k_hat"]), shape.dtype),
+                                        synth.load_f64(lava.to_host_bits(cur["v_hat"]), shape.dtype),
+                                        cur["head_offsets"].cpu().numpy())
+    got = out.cpu().numpy()[0]
+    for h in range(H):
+        assert np.abs(got[h] - want[h]).max() <= 2e-5 * np.abs(want[h]).max()
+    assert np.allclose(lse.cpu().numpy()[0], want_lse, rtol=1e-5, atol=1e-5)
