@@ -104,6 +104,15 @@ def test_cascade_bf16_gpu_scores(lava):
     say("  final budgets", history[-1])
 
 
+def test_cascade_many_layers_tight_budget(lava):
+    say("cascade: 14 layers, f32, N=300, total barely above the lower bounds -> many layers pinned at H_kv * w")
+    shape = synth.config(1, n=300)
+    fr = synth.stack_heavy_fracs(14, 11)
+    total = 14 * shape.n_kv_heads * shape.window + 90          # 16 per layer is the floor
+    state, history = run_cascade(lava, shape, 14, total, dict(base=500, fracs=fr), use_gpu_scores=False)
+    assert sum(history[-1]) == total and min(history[-1]) >= shape.n_kv_heads * shape.window
+
+
 def test_cascade_first_layer_takes_everything(lava):
     say("cascade: total budget = one layer's size -> the first layer is kept whole, then shrinks")
     shape = synth.config(1, n=600)
