@@ -1,0 +1,145 @@
+"""The 32-layer stack at full size (config 3: 32 layers of 32K tokens, one shared budget of 131072 entries,
+4 GiB of K + V resident): Algorithm 2 run two ways on the GPU and against the oracle.
+
+  cascade      one lava_cascade_step per arriving layer (budgets, re-eviction of every earlier layer)
+  single shot  budgets of all layers at once, one table of selections, one of compactions
+
+Both rank the same scores (computed once, for all layers in one batched call), so their final states
+must be identical entry for entry (survivor sets are nested), and both must equal the oracle's literal
+cascade on those scores.  The scores themselves are checked against the oracle layer by layer.
+"""
+import dataclasses
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import lava_oracle as O
+from paper_2509_09754_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def lava():
+    from paper_2509_09754_amd import lava as mod
+    assert torch.cuda.is_available()
+    return mod
+
+
+def say(*a):
+    print(*a, flush=True)
+
+
+def test_config3_full_stack_cascade_equals_single_shot_equals_oracle(lava):
+    L, total = 32, 131072
+    base = synth.config(3)
+    H, Hkv, d, N, w = base.n_q_heads, base.n_kv_heads, base.head_dim, base.n, base.window
+    dense = Hkv * N
+    say(f"stack: {L} layers of N={N}, total budget {total}")
+    desc = lava.LayerDesc.make(H, Hkv, d, w, base.dtype)
+    dev = "cuda"
+    fracs = synth.stack_heavy_fracs(L, 0)
+    k_host, v_host = [], []
+    q_dev = torch.empty(L, H, w, d, dtype=torch.bfloat16, device=dev)
+    k_dev = torch.empty(L, Hkv, N, d, dtype=torch.bfloat16, device=dev)
+    v_dev = torch.empty(L, Hkv, N, d, dtype=torch.bfloat16, device=dev)
+    ref_scores, ref_e = [], []
+    for l in range(L):
+        inp = synth.gen_layer(dataclasses.replace(base, heavy_frac=float(fracs[l])), 3000 + l)
+        k_host.append(inp.k)
+        v_host.append(inp.v)
+        q_dev[l] = lava.to_device(inp.q_win, "bf16", dev)
+        k_dev[l] = lava.to_device(inp.k, "bf16", dev)
+        v_dev[l] = lava.to_device(inp.v, "bf16", dev)
+        qf, kf, vf = inp.f64()
+        s, _ = O.lava_scores(qf, kf, vf, w, 7)
+        ref_scores.append(s)
+        ref_e.append(O.layer_entropy(s))
+        if l % 8 == 7:
+            say(f"   generated and scored (oracle) {l + 1} layers")
+
+    # the layers as a batch of 32 sequences: three sweep launches for the whole model
+    state = lava.CascadeState(desc, L, total)
+    scores, vbar, stat = lava.lava_window_scores(desc, [N] * L, q_dev, k_dev, v_dev, layer_stat=state.e)
+    torch.cuda.synchronize()
+    s_host = scores.cpu().numpy().reshape(L, Hkv, N)
+    e_host = stat.cpu().numpy()
+    worst = 0.0
+    for l in range(L):
+        got = s_host[l][:, : N - w].astype(np.float64)
+        mask = ref_scores[l] > 1e-30 * ref_scores[l].max()
+        worst = max(worst, float(np.max(np.abs(got[mask] - ref_scores[l][mask]) / ref_scores[l][mask])))
+        assert np.all(np.isposinf(s_host[l][:, N - w:]))
+        assert abs(float(e_host[l]) - ref_e[l]) <= 1e-4 * ref_e[l]
+    say(f"   scores of all layers: worst relative error {worst:.2e}")
+    assert worst < 1e-3
+
+    # ---- cascade: one step per arriving layer
+    ws = None
+    for l in range(L):
+        ws = lava.lava_cascade_step(desc, l, N, k_dev[l], v_dev[l], scores[l * dense: (l + 1) * dense], state, total,
+                                    workspace=ws)
+    torch.cuda.synchronize()
+    casc_budgets = state.budgets.cpu().numpy()
+    starts = state.layer_start[state.cur].cpu().numpy()
+    assert casc_budgets.sum() == total and starts[-1] == total
+
+    # ---- single shot: budgets of all layers, one selection table, one compaction table, one arena
+    lo = torch.full((1, L), Hkv * w, dtype=torch.int64, device=dev)
+    hi = torch.full((1, L), dense, dtype=torch.int64, device=dev)
+    budgets = lava.lava_layer_budgets(stat.view(1, L), torch.tensor([total], device=dev), lo, hi)
+    layer_start = torch.zeros(L + 1, dtype=torch.int64, device=dev)
+    layer_start[1:] = torch.cumsum(budgets[0], 0)
+    counts = torch.empty(L, Hkv, dtype=torch.int32, device=dev)
+    offs = torch.empty(L, Hkv + 1, dtype=torch.int64, device=dev)
+    idx = torch.empty(total, dtype=torch.int32, device=dev)
+    k_hat = torch.empty(total, d, dtype=torch.bfloat16, device=dev)
+    v_hat = torch.empty(total, d, dtype=torch.bfloat16, device=dev)
+    pos = torch.empty(total, dtype=torch.int32, device=dev)
+    cap = min(total, dense)
+    sel, cmp = [], []
+    for l in range(L):
+        sel.append(lava.select_problem(scores[l * dense: (l + 1) * dense], cap, counts[l], offs[l], idx,
+                                       budget_dev=budgets[0, l: l + 1], out_offset_dev=layer_start[l: l + 1]))
+        cmp.append(lava.compact_problem(desc, N, k_dev[l].view(-1, d), v_dev[l].view(-1, d), offs[l], idx, total,
+                                        k_hat, v_hat, pos_out=pos, out_offset_dev=layer_start[l: l + 1]))
+    wsel = lava.lava_select_topk_batch(Hkv, sel, dense)
+    lava.lava_compact_batch(desc, cmp)
+    torch.cuda.synchronize()
+    assert lava.lava_select_batch_status(wsel, L, dense) == lava.LAVA_OK
+    single_budgets = budgets.cpu().numpy()[0]
+    say(f"   budgets {single_budgets.tolist()}")
+    assert np.array_equal(single_budgets, casc_budgets)                       # the last cascade step sees all layers
+    assert single_budgets.tolist() == O.layer_budgets(e_host.astype(np.float64), total, [Hkv * w] * L, [dense] * L)
+
+    # ---- the two GPU routes agree entry for entry
+    c = state.cur
+    assert np.array_equal(starts, layer_start.cpu().numpy())
+    assert torch.equal(state.head_offsets[c], offs) and torch.equal(state.head_counts, counts)
+    assert torch.equal(state.pos[c][:total], pos)
+    assert torch.equal(state.k[c][:total].view(torch.int16), k_hat.view(torch.int16))
+    assert torch.equal(state.v[c][:total].view(torch.int16), v_hat.view(torch.int16))
+
+    # ---- and both equal the oracle's literal cascade on the same scores and statistics
+    layer_scores = [s_host[l].astype(np.float64) for l in range(L)]            # [H_kv, N], window entries +inf
+    ref_state, history = O.cascade(layer_scores, N, total, w, entropies=[float(x) for x in e_host])
+    assert history[-1] == single_budgets.tolist()
+    offs_host, pos_host = offs.cpu().numpy(), pos.cpu().numpy()
+    kh, vh = lava.to_host_bits(k_hat), lava.to_host_bits(v_hat)
+    st = layer_start.cpu().numpy()
+    for l in range(L):
+        r_offs, r_pos, _ = ref_state[l]
+        assert np.array_equal(offs_host[l], r_offs), l
+        a = int(st[l])
+        assert np.array_equal(pos_host[a: a + int(r_offs[-1])], r_pos), l
+        for g in (0, Hkv - 1):                                                # rows: bit copies (two heads per layer)
+            lo_g, hi_g = a + int(r_offs[g]), a + int(r_offs[g + 1])
+            assert np.array_equal(kh[lo_g:hi_g], k_host[l][g][r_pos[r_offs[g]: r_offs[g + 1]]]), (l, g)
+            assert np.array_equal(vh[lo_g:hi_g], v_host[l][g][r_pos[r_offs[g]: r_offs[g + 1]]]), (l, g)
+        # kept-set overlap with a selection on the oracle's own scores
+        rc, ro, ri, _ = O.select_topk(O.flat_layer_scores(ref_scores[l], N).ravel(),
+                                      (np.arange(Hkv + 1) * N).astype(np.int64), int(single_budgets[l]))
+        mine = set(int(g * N + p) for g in range(Hkv) for p in r_pos[r_offs[g]: r_offs[g + 1]])
+        theirs = set(int(g * N + p) for g in range(Hkv) for p in ri[ro[g]: ro[g + 1]])
+        assert len(mine & theirs) >= 0.999 * int(single_budgets[l]), l
