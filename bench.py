@@ -37,13 +37,13 @@ def parse():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="cfg4", choices=["cfg1", "cfg2", "cfg4", "cfg5"])
+    ap.add_argument("--workload", default="cfg4", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--sets", type=int, default=0, help="distinct K/V buffer sets (0 = enough for >= 1.5 GiB)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode-attention leg")
-    ap.add_argument("--no-cascade", action="store_true", help="skip the Algorithm-2 cascade leg")
+    ap.add_argument("--no-cascade", action="store_true", help="skip the Algorithm-2 cascade leg (cfg3: the layer-by-layer route)")
     ap.add_argument("--no-compare", action="store_true",
                     help="cfg5: skip the comparison leg (one call per sequence), for profiling the batched launches")
     ap.add_argument("--decode-only", action="store_true",
@@ -290,6 +290,95 @@ def ragged_batch(lava, synth, torch, np, dev, args):
     }
 
 
+def layer_stack(lava, synth, torch, np, dev, args):
+    """Config 3: a 32-layer model, 32K cached tokens per layer, one shared budget of 131072 entries; K + V of
+    all layers (4 GiB) resident.  Throughput only: K / V / Q are drawn on the device.  Two routes to the
+    same final state: `single_shot` once every layer is there (the layers as a batch: three sweep launches,
+    one budgets launch, one table of selections, one of compactions) and `cascade`, Algorithm 2 as layers
+    arrive (per layer: the sweeps of that layer, then one cascade step over all layers so far)."""
+    sh = synth.config(3)
+    H, Hkv, d, w, N = sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.window, sh.n
+    L, total = 32, 131072
+    dense = Hkv * N
+    desc = lava.LayerDesc.make(H, Hkv, d, w, sh.dtype)
+    gen = torch.Generator(device=dev).manual_seed(args.seed)
+    k = torch.empty(L, Hkv * N, d, dtype=torch.bfloat16, device=dev)
+    v = torch.empty(L, Hkv * N, d, dtype=torch.bfloat16, device=dev)
+    for l in range(L):
+        k[l] = torch.randn(Hkv * N, d, generator=gen, device=dev).to(torch.bfloat16)
+        v[l] = (torch.randn(Hkv * N, d, generator=gen, device=dev) *
+                torch.exp(0.5 * torch.randn(Hkv * N, 1, generator=gen, device=dev))).to(torch.bfloat16)
+    q = torch.randn(L, H, w, d, generator=gen, device=dev).to(torch.bfloat16)
+    state = lava.CascadeState(desc, L, total, device=dev)
+    scores = torch.empty(L * dense, dtype=torch.float32, device=dev)
+    vbar = torch.empty(L, Hkv, dtype=torch.float32, device=dev)
+    ws_batch = torch.empty(lava.lava_window_scores_workspace_bytes(desc, L, L * N), dtype=torch.uint8, device=dev)
+    ws_one = torch.empty(lava.lava_window_scores_workspace_bytes(desc, 1, N), dtype=torch.uint8, device=dev)
+    ws_casc = torch.empty(lava.lava_cascade_workspace_bytes(desc, N, L, total), dtype=torch.uint8, device=dev)
+    ws_sel = torch.empty(lava.lava_select_batch_workspace_bytes(L, dense), dtype=torch.uint8, device=dev)
+    lo = torch.full((1, L), Hkv * w, dtype=torch.int64, device=dev)
+    hi = torch.full((1, L), dense, dtype=torch.int64, device=dev)
+    total_t = torch.tensor([total], dtype=torch.int64, device=dev)
+    budgets = torch.empty(1, L, dtype=torch.int64, device=dev)
+    layer_start = torch.zeros(L + 1, dtype=torch.int64, device=dev)
+    counts = torch.empty(L, Hkv, dtype=torch.int32, device=dev)
+    offs = torch.empty(L, Hkv + 1, dtype=torch.int64, device=dev)
+    idx = torch.empty(total, dtype=torch.int32, device=dev)
+    k_hat = torch.empty(total, d, dtype=torch.bfloat16, device=dev)
+    v_hat = torch.empty(total, d, dtype=torch.bfloat16, device=dev)
+    cap = min(total, dense)
+    sel = [lava.select_problem(scores[l * dense: (l + 1) * dense], cap, counts[l], offs[l], idx,
+                               budget_dev=budgets[0, l: l + 1], out_offset_dev=layer_start[l: l + 1]) for l in range(L)]
+    cmp = [lava.compact_problem(desc, N, k[l], v[l], offs[l], idx, total, k_hat, v_hat,
+                                out_offset_dev=layer_start[l: l + 1]) for l in range(L)]
+    sel_table = (lava.SelectProblem * L)(*sel)
+    cmp_table = (lava.CompactProblem * L)(*cmp)
+
+    def single_shot():
+        lava.lava_window_scores(desc, [N] * L, q, k, v, scores=scores, vbar=vbar, layer_stat=state.e, workspace=ws_batch)
+        lava.lava_layer_budgets(state.e.view(1, L), total_t, lo, hi, budgets=budgets)
+        torch.cumsum(budgets[0], 0, out=layer_start[1:])
+        lava.lava_select_topk_batch(Hkv, sel_table, dense, workspace=ws_sel)
+        lava.lava_compact_batch(desc, cmp_table)
+
+    def cascade():
+        state.reset()
+        for l in range(L):
+            sc = scores[l * dense: (l + 1) * dense]
+            lava.lava_window_scores(desc, [N], q[l: l + 1], k[l], v[l], scores=sc, vbar=vbar[l: l + 1],
+                                    layer_stat=state.e[l: l + 1], workspace=ws_one)
+            lava.lava_cascade_step(desc, l, N, k[l], v[l], sc, state, total, workspace=ws_casc)
+
+    def timed(fn, reps):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / reps
+
+    reps = max(5, args.steps // 20)
+    t_single = timed(single_shot, reps)
+    t_casc = None if args.no_cascade else timed(cascade, reps)
+    tokens = L * N
+    kv_bytes = 2 * k.numel() * k.element_size()
+    path_bytes = kv_bytes + 2 * 4 * L * dense + 4 * total * d * 2
+    return {
+        "metric": "cached tokens evicted-and-compacted/sec per layer; achieved HBM GB/s vs peak",
+        "value": round(tokens / t_single, 1), "unit": "tokens/s/layer", "n_gpus": 1, "steps": reps, "warmup": 1,
+        "ms_per_step": round(1e3 * t_single, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16", "data": "synthetic (drawn on the device)",
+        "config": {"workload": f"cfg3: {L} layers, 32q/8kv heads, d_h 128, N={N} per layer, w=32, shared budget "
+                               f"{total}, bf16; one step = the whole stack", "kv_bytes_resident": kv_bytes},
+        "path": {"algorithmic_bytes": path_bytes, "achieved_GBs": round(path_bytes / t_single / 1e9, 1),
+                 "frac_of_hbm_peak": round(path_bytes / t_single / 1e9 / HBM_PEAK_GBS, 4)},
+        "cascade_as_layers_arrive": None if t_casc is None else {
+            "ms_per_stack": round(1e3 * t_casc, 4), "value": round(tokens / t_casc, 1),
+            "us_per_layer": round(1e6 * t_casc / L, 1), "state_bytes": state.bytes()},
+    }
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -308,6 +397,9 @@ def main():
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
 
+    if args.workload == "cfg3":
+        print(json.dumps(layer_stack(lava, synth, torch, np, dev, args)), flush=True)
+        return
     if args.workload == "cfg5":
         print(json.dumps(ragged_batch(lava, synth, torch, np, dev, args)), flush=True)
         return
