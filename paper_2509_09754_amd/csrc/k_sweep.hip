@@ -39,7 +39,7 @@ constexpr int kCounterPool = 0;                         // poolstat: one two-lev
 // tail hide behind the other's streaming.  The f32 / d_h 128 kernels need more than 256 registers:
 // 4 wavefronts and the whole ring in either case.
 constexpr int kFusedTilesWide = 128;
-constexpr int kFusedTilesNarrow = 64;
+constexpr int kFusedTilesNarrow = 96;
 template <int DT, int D, int W>
 struct Shape {
   static_assert(W == 4 || W == 8, "wavefronts per workgroup");
