@@ -13,6 +13,9 @@
  *                        of survivors per head is the dynamic head budget   (Alg. 1, Sec. 4.1)
  *   lava_compact_kv      packs the surviving K/V rows per head              (Alg. 1, last loop)
  * and, after the path, lava_decode_attention reads the packed cache (Sec. 2 decoding step).
+ * Around the path: lava_select_topk_batch / lava_compact_batch run tables of independent
+ * selections / compactions in one launch each (the sequences of a ragged batch, the layers of a
+ * stack), and lava_cascade_step is Algorithm 2 as a driver over a stack's compressed caches.
  *
  * Conventions common to all calls
  *   - "device" pointers are HIP device memory of the current device, "host" pointers are
