@@ -95,3 +95,61 @@ def test_layer_eviction_replays_from_a_graph(lava):
                 a, b = a[:kept], b[:kept]
             assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), (rep, name)
         assert lava.lava_select_status(bufs["ws_sel"], Hkv * N) == lava.LAVA_OK
+
+
+def test_cascade_of_three_layers_replays_from_a_graph(lava):
+    print("graph: capture three cascade steps (scores + step per layer), replay 3 times", flush=True)
+    sh = synth.config(2, n=4096 + 21, budget=0)
+    H, Hkv, d, N, w = sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.n, sh.window
+    L, total = 3, 3 * 700
+    desc = lava.LayerDesc.make(H, Hkv, d, w, sh.dtype)
+    dev = "cuda"
+    inps = [[synth.gen_layer(sh, 10 * r + l) for l in range(L)] for r in range(2)]
+    q = [lava.to_device(inps[0][l].q_win, sh.dtype, dev).clone() for l in range(L)]
+    k = [lava.to_device(inps[0][l].k, sh.dtype, dev).clone() for l in range(L)]
+    v = [lava.to_device(inps[0][l].v, sh.dtype, dev).clone() for l in range(L)]
+    state = lava.CascadeState(desc, L, total, device=dev)
+    scores = torch.empty(L, Hkv * N, dtype=torch.float32, device=dev)
+    vbar = torch.empty(L, Hkv, dtype=torch.float32, device=dev)
+    ws_s = torch.empty(lava.lava_window_scores_workspace_bytes(desc, 1, N), dtype=torch.uint8, device=dev)
+    ws_c = torch.empty(lava.lava_cascade_workspace_bytes(desc, N, L, total), dtype=torch.uint8, device=dev)
+
+    def run():
+        state.reset()
+        for l in range(L):
+            lava.lava_window_scores(desc, [N], q[l], k[l], v[l], scores=scores[l], vbar=vbar[l: l + 1],
+                                    layer_stat=state.e[l: l + 1], workspace=ws_s)
+            lava.lava_cascade_step(desc, l, N, k[l], v[l], scores[l], state, total, workspace=ws_c)
+
+    def snapshot():
+        torch.cuda.synchronize()
+        c = state.cur
+        return [t.clone() for t in (state.budgets, state.layer_start[c], state.head_offsets[c], state.head_counts,
+                                    state.pos[c][:total], state.scores[c][:total], state.k[c][:total], state.v[c][:total])]
+
+    run()
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        with torch.cuda.graph(graph, stream=side):
+            run()
+    torch.cuda.current_stream().wait_stream(side)
+    final_cur = state.cur                                   # an odd number of steps: the state ends in arena 1
+    for rep in range(3):
+        src = inps[rep % 2]
+        for l in range(L):
+            q[l].copy_(lava.to_device(src[l].q_win, sh.dtype, dev))
+            k[l].copy_(lava.to_device(src[l].k, sh.dtype, dev))
+            v[l].copy_(lava.to_device(src[l].v, sh.dtype, dev))
+        run()
+        want = snapshot()
+        assert state.cur == final_cur and int(want[1][-1]) == total
+        for i in range(2):                                   # scribble over both arenas: the replay must rewrite them
+            state.k[i].fill_(0), state.pos[i].fill_(-1), state.scores[i].fill_(0)
+        (torch.rand(1 << 20, device=dev) * 2).sum().item()
+        graph.replay()
+        got = snapshot()
+        for a, b in zip(want, got):
+            assert torch.equal(a.view(torch.uint8), b.view(torch.uint8)), rep
