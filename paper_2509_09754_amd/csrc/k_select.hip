@@ -26,6 +26,12 @@ constexpr int kBins = 2048;
 constexpr int kMaxHeads = 64;
 constexpr unsigned int kSpinLimit = 1u << 18;           // polls of a grid barrier before giving up
 
+// The fused kernel's last histogram pass also publishes, per workgroup, how many of its keys lie
+// above each possible last digit (kPubWords = 1024 digits + 1), so that the counts every
+// workgroup needs from those before it are two loads once the threshold is known.
+constexpr int kPubWords = 1025;
+constexpr int kFusedMaxBlocks = 1024;   // more workgroups than any device keeps resident
+
 struct SelectState {
   unsigned int barrier;      // arrivals at the grid barriers of the fused kernel (monotonic)
   unsigned int error;        // set when a barrier wait gave up (results are then invalid)
@@ -39,7 +45,12 @@ SelectWorkspace make_select_workspace(int64_t total) {
   size_t off = 0;
   w.off_hist = off;  off += align_up(sizeof(unsigned int) * 3 * kBins);
   w.off_state = off; off += align_up(sizeof(SelectState));
-  w.off_blk = off;   off += align_up(sizeof(unsigned int) * 2 * (size_t)w.n_blocks);
+  // per-workgroup counts: two words per workgroup for the step launches; the fused kernel publishes
+  // kPubWords per workgroup (it serves problems of up to kFusedMaxBlocks workgroups)
+  size_t words = 2 * (size_t)w.n_blocks;
+  const size_t fused = (size_t)(w.n_blocks < kFusedMaxBlocks ? w.n_blocks : kFusedMaxBlocks) * kPubWords;
+  if (fused > words) words = fused;
+  w.off_blk = off;   off += align_up(sizeof(unsigned int) * words);
   w.bytes = off;
   return w;
 }
@@ -328,6 +339,104 @@ __device__ __forceinline__ void write_phase(int bx, const float (&val)[kSelPerTh
   }
 }
 
+// Last histogram pass of the fused kernel.  Besides merging the workgroup's histogram of the last
+// digit (keys matching the 22 digits found so far) into the global one, it publishes
+//   pub[d] = #keys of this workgroup above every key that matches the prefix and has last digit < d
+//          = #keys whose first 22 bits exceed the prefix + #matching keys with last digit >= d,
+// d = 0 .. 1024, so that for a threshold with last digit t the workgroup holds pub[t + 1] keys above
+// it and pub[t] - pub[t + 1] equal to it.
+__device__ __forceinline__ void hist_publish_phase(int bx, const float (&val)[kSelPerThread], long long total,
+                                                   unsigned int prefix, SelShared& sh,
+                                                   unsigned int* __restrict__ ghist,
+                                                   unsigned int* __restrict__ pub) {
+  using Dg = Digit<2>;
+  static_assert(Dg::kNum == kSelThreads && Dg::kNum + 1 == kPubWords, "one last digit per thread");
+  sh.hist[threadIdx.x] = 0u;
+  __syncthreads();
+  const long long p0 = (long long)bx * kSelChunk + threadIdx.x * kSelPerThread;
+  unsigned int run_digit = 0xffffffffu, run_len = 0u, above = 0u;
+#pragma unroll
+  for (int j = 0; j < kSelPerThread; ++j) {
+    unsigned int digit = 0xffffffffu;
+    if (p0 + j < total) {
+      const unsigned int key = score_key(val[j]);
+      const unsigned int hi = key >> Dg::kHiShift;
+      above += hi > prefix ? 1u : 0u;
+      if (hi == prefix) digit = key & (Dg::kNum - 1);
+    }
+    if (digit != run_digit) {
+      if (run_len != 0u && run_digit != 0xffffffffu) atomicAdd(&sh.hist[run_digit], run_len);
+      run_digit = digit;
+      run_len = 0u;
+    }
+    ++run_len;
+  }
+  if (run_digit != 0xffffffffu) atomicAdd(&sh.hist[run_digit], run_len);
+  __syncthreads();
+  // thread t owns digit kNum - 1 - t: an inclusive scan over t is a suffix sum over the digits
+  const int d = Dg::kNum - 1 - (int)threadIdx.x;
+  const unsigned int c = sh.hist[d];
+  if (c) __hip_atomic_fetch_add(&ghist[d], c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  unsigned int incl = c;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+#pragma unroll
+  for (int off = 1; off < 64; off <<= 1) {
+    const unsigned int up = __shfl_up(incl, off);
+    if (lane >= off) incl += up;
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) above += __shfl_xor(above, off);
+  if (lane == 63) sh.wave[wave] = incl;
+  if (lane == 0) sh.wave64[wave] = above;
+  __syncthreads();
+  unsigned int base = 0u, above_all = 0u;
+  for (int i = 0; i < kSelThreads / 64; ++i) {
+    if (i < wave) base += sh.wave[i];
+    above_all += (unsigned int)sh.wave64[i];
+  }
+  st_dev(&pub[d], above_all + base + incl);
+  if (threadIdx.x == 0) st_dev(&pub[Dg::kNum], above_all);
+  __syncthreads();
+}
+
+// This lane's keys above / equal to the threshold.
+__device__ __forceinline__ void mask_phase(int bx, const float (&val)[kSelPerThread], long long total,
+                                           unsigned int T, unsigned int& gt_mask, unsigned int& eq_mask) {
+  const long long p0 = (long long)bx * kSelChunk + threadIdx.x * kSelPerThread;
+  gt_mask = 0u;
+  eq_mask = 0u;
+#pragma unroll
+  for (int j = 0; j < kSelPerThread; ++j) {
+    if (p0 + j < total) {
+      const unsigned int key = score_key(val[j]);
+      gt_mask |= (key > T ? 1u : 0u) << j;
+      eq_mask |= (key == T ? 1u : 0u) << j;
+    }
+  }
+}
+
+// Sums of (above, equal) over the workgroups before this one, from what they published.
+__device__ __forceinline__ void prefix_published_phase(int bx, const unsigned int* __restrict__ pub_all,
+                                                       unsigned int T, SelShared& sh, long long& gt_before,
+                                                       long long& eq_before) {
+  const unsigned int t = T & (unsigned int)(Digit<2>::kNum - 1);
+  unsigned long long acc = 0ull;   // above in the high word, equal in the low word (each < 2^31)
+  for (int b = threadIdx.x; b < bx; b += kSelThreads) {
+    const unsigned int ge = ld_dev(&pub_all[(size_t)b * kPubWords + t]);
+    const unsigned int gt = ld_dev(&pub_all[(size_t)b * kPubWords + t + 1]);
+    acc += ((unsigned long long)gt << 32) | (unsigned long long)(ge - gt);
+  }
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) acc += __shfl_xor(acc, off);
+  if ((threadIdx.x & 63) == 0) sh.wave64[threadIdx.x >> 6] = acc;
+  __syncthreads();
+  unsigned long long tot = 0ull;
+  for (int i = 0; i < kSelThreads / 64; ++i) tot += sh.wave64[i];
+  gt_before = (long long)(tot >> 32);
+  eq_before = (long long)(tot & 0xffffffffull);
+  __syncthreads();
+}
+
 // Grid-wide barrier of the fused kernel: all of its workgroups are resident (the host checks the
 // grid against the device's capacity), arrivals are counted monotonically, and the wait is
 // bounded: if it ever gives up, the error word is set and the kernel still runs to completion.
@@ -431,15 +540,16 @@ __global__ void __launch_bounds__(kSelThreads) sel_fused_kernel(const SelectBatc
   hist_phase<1>(bx, val, total, pk.prefix, sh, hist + kBins);
   grid_sync(st, 2u, nb);
   pk = pick_phase<1>(hist + kBins, pk, sh);
-  hist_phase<2>(bx, val, total, pk.prefix, sh, hist + 2 * kBins);
+  hist_publish_phase(bx, val, total, pk.prefix, sh, hist + 2 * kBins, blk + (size_t)bx * kPubWords);
   grid_sync(st, 3u, nb);
   pk = pick_phase<2>(hist + 2 * kBins, pk, sh);
 
+  // the counts of the workgroups before this one were published with the last histogram: no
+  // further pass over the keys and no fourth barrier
   unsigned int gt_mask, eq_mask;
-  count_phase(bx, val, total, pk.prefix, sh, blk, a.blk_stride, gt_mask, eq_mask);
-  grid_sync(st, 4u, nb);
+  mask_phase(bx, val, total, pk.prefix, gt_mask, eq_mask);
   long long gt_before, eq_before;
-  prefix_phase(bx, blk, a.blk_stride, sh, gt_before, eq_before);
+  prefix_published_phase(bx, blk, pk.prefix, sh, gt_before, eq_before);
   write_phase(bx, val, total, n_heads, seg_offsets, gt_mask, eq_mask, pk.need, budget, gt_before, eq_before,
               kept_total, sh, pr.head_counts, pr.head_offsets, pr.kept_idx + out_off,
               pr.kept_scores ? pr.kept_scores + out_off : nullptr);
@@ -522,7 +632,7 @@ int32_t launch_select_batch(int n_heads, int n_problems, const lava_select_probl
   a.off_blk = w.off_blk;
   a.blk_stride = w.n_blocks;
   const dim3 block(kSelThreads);
-  const int cap = fused_capacity();
+  const int cap = fused_capacity() < kFusedMaxBlocks ? fused_capacity() : kFusedMaxBlocks;
   int first = 0;
   while (first < n_problems) {
     int count = 0, blocks = 0;
