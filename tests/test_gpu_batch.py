@@ -211,7 +211,7 @@ def test_ragged_batch_full_size_one_layer(lava):
         assert rel.max() < 1e-3, (b, rel.max())
         np.testing.assert_allclose(vb_host[b], ref_vbar, rtol=1e-5)
         ref_e = O.layer_entropy(ref_s)
-        assert abs(float(e_host[b]) - ref_e) <= 1e-4 * ref_e
+        assert abs(float(e_host[b]) - ref_e) <= 1e-4 * ref_e + 2e-5 / ref_s.size
         # selection: exact on the GPU's own scores; kept set against the oracle's scores
         uniform = (np.arange(Hkv + 1) * n).astype(np.int64)
         rc, ro, ri, _ = O.select_topk(got.astype(np.float64).ravel(), uniform, B)

@@ -189,7 +189,7 @@ def compare_scores(sh, got, ref_s, vbar, ref_vbar, stat, ref_e):
     assert rel.max() < SCORE_RTOL
     assert np.all(g[~mask] <= 1e-29 * r.max())
     np.testing.assert_allclose(vbar, ref_vbar, rtol=1e-5)
-    assert abs(stat - ref_e) <= 1e-4 * ref_e
+    assert abs(stat - ref_e) <= 1e-4 * ref_e + 2e-5 / ref_s.size   # fp32 logs: an absolute part, seen only in tiny layers
 
 
 SCORE_CASES = [
@@ -241,6 +241,53 @@ def test_window_scores_narrow_shape_vs_oracle(lava, name, sh, monkeypatch):
     lse = O.window_lse(q, k)
     _, _, got, vbar, stat = run_scores(lava, inp, lse=lse)
     compare_scores(sh, got, ref_s, vbar, ref_vbar, stat, O.layer_entropy(ref_s))
+
+
+def random_shapes(count, seed):
+    """Seeded draw of layer shapes across everything the descriptor allows (small N: the oracle is quick)."""
+    r = np.random.Generator(np.random.PCG64(seed))
+    out = []
+    for i in range(count):
+        dtype = ["bf16", "f32"][int(r.integers(0, 2))]
+        d = [64, 128][int(r.integers(0, 2))]
+        G = int(r.integers(1, 9))
+        Hkv = int(r.integers(1, 5))
+        w = int(r.integers(1, 33))
+        n = w + int(r.choice([1, 2, 7, 31, 32, 33, 100, 500, 1500, 3300, 6200]))
+        pool = int(r.choice([1, 3, 5, 7, 9, 15]))
+        budget = min(Hkv * n, Hkv * w + int(r.integers(0, 200)))
+        out.append((f"r{i}-{dtype}-d{d}-G{G}-kv{Hkv}-w{w}-n{n}-p{pool}",
+                    synth.LayerShape(G * Hkv, Hkv, d, n, w, dtype, budget, heavy_count=min(8, n - w), pool_kernel=pool),
+                    ["wide", "narrow"][i % 2]))
+    return out
+
+
+RANDOM_CASES = random_shapes(24, 2024)
+
+
+@pytest.mark.parametrize("name,sh,shape", RANDOM_CASES, ids=[c[0] for c in RANDOM_CASES])
+def test_window_scores_random_shapes(lava, name, sh, shape, monkeypatch):
+    """Random draws over head counts, group sizes 1..8, windows 1..32, pooling kernels, lengths from one
+    prefix token to a few thousand, both dtypes and both sweep shapes; then the whole layer on the same input."""
+    say(f"scores, random shape {name} ({shape})")
+    monkeypatch.setenv("LAVA_SWEEP_SHAPE", shape)
+    inp = synth.gen_layer(sh, 5)
+    q, k, v = inp.f64()
+    ref_s, ref_vbar = O.lava_scores(q, k, v, sh.window, sh.pool_kernel)
+    _, _, got, vbar, stat = run_scores(lava, inp)
+    compare_scores(sh, got, ref_s, vbar, ref_vbar, stat, O.layer_entropy(ref_s))
+    # selection + compaction on the GPU's scores: exact against the oracle on the same values
+    desc = lava.LayerDesc.make(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.window, sh.dtype, pool_kernel=sh.pool_kernel)
+    sc = torch.from_numpy(got.astype(np.float32).ravel()).cuda()
+    counts, offs, idx, _ = lava.lava_select_topk(sh.n_kv_heads, sc, sh.budget)
+    kd, vd = lava.to_device(inp.k, sh.dtype), lava.to_device(inp.v, sh.dtype)
+    k_hat, v_hat = lava.lava_compact_kv(desc, sh.n, kd, vd, offs, idx, sh.budget)
+    torch.cuda.synchronize()
+    rc, ro, ri, _ = O.select_topk(got.astype(np.float64).ravel(), offsets_uniform(sh.n_kv_heads, sh.n), sh.budget)
+    assert np.array_equal(counts.cpu().numpy(), rc) and np.array_equal(idx.cpu().numpy()[: sh.budget], ri)
+    assert np.all(rc >= sh.window)
+    assert np.array_equal(lava.to_host_bits(k_hat)[: sh.budget], O.compact(inp.k, ro, ri))
+    assert np.array_equal(lava.to_host_bits(v_hat)[: sh.budget], O.compact(inp.v, ro, ri))
 
 
 def test_window_scores_pool_kernels_and_lse(lava):

@@ -39,7 +39,7 @@ def test_attention_only_score(lava, cfg, over):
     got = got[:, : sh.n_prefix].astype(np.float64)
     mask = want > 1e-30 * want.max()
     assert np.max(np.abs(got[mask] - want[mask]) / want[mask]) <= 1e-3
-    assert abs(float(stat[0]) - O.layer_entropy(want)) <= 1e-4 * O.layer_entropy(want)
+    assert abs(float(stat[0]) - O.layer_entropy(want)) <= 1e-4 * O.layer_entropy(want) + 2e-5 / want.size
     # the value factor is the only difference from the LAVa score: same array up to the per-head scale
     full, vb = O.lava_scores(qf, kf, vf, sh.window, sh.pool_kernel)
     np.testing.assert_allclose(full, want * vb[:, None], rtol=1e-12)
@@ -75,7 +75,7 @@ def test_token_norm_score(lava, name, sh, shape, monkeypatch):
     mask = want > 1e-30 * want.max()
     assert np.max(np.abs(got[mask] - want[mask]) / want[mask]) <= 1e-3
     assert np.all(got[~mask] <= 1e-29 * want.max())
-    assert abs(float(stat[0]) - O.layer_entropy(want)) <= 1e-4 * O.layer_entropy(want)
+    assert abs(float(stat[0]) - O.layer_entropy(want)) <= 1e-4 * O.layer_entropy(want) + 2e-5 / want.size
 
 
 def test_token_norm_score_ragged_batch(lava):
@@ -97,7 +97,7 @@ def test_token_norm_score_ragged_batch(lava):
         got = s_host[8 * tok: 8 * (tok + sh.n)].reshape(8, sh.n)[:, : sh.n_prefix].astype(np.float64)
         mask = want > 1e-30 * want.max()
         assert np.max(np.abs(got[mask] - want[mask]) / want[mask]) <= 1e-3, b
-        assert abs(float(stat[b]) - O.layer_entropy(want)) <= 1e-4 * O.layer_entropy(want)
+        assert abs(float(stat[b]) - O.layer_entropy(want)) <= 1e-4 * O.layer_entropy(want) + 2e-5 / want.size
         tok += sh.n
 
 
