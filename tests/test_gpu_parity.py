@@ -331,6 +331,29 @@ def test_window_scores_deterministic_and_batched(lava):
         tok += sh.n
 
 
+def test_window_scores_batch_larger_than_one_launch_table(lava):
+    say("scores: 37 short sequences in one call (the per-launch table holds 32)")
+    r = np.random.Generator(np.random.PCG64(12))
+    lens = [int(x) for x in r.integers(9, 700, 37)]
+    shapes = [synth.config(1, n=n, budget=2 * 8) for n in lens]
+    inps = [synth.gen_layer(s, 200 + i) for i, s in enumerate(shapes)]
+    sh0 = shapes[0]
+    desc = lava.LayerDesc.make(sh0.n_q_heads, sh0.n_kv_heads, sh0.head_dim, sh0.window, sh0.dtype)
+    q = torch.cat([lava.to_device(i.q_win, "f32").reshape(-1) for i in inps])
+    k = torch.cat([lava.to_device(i.k, "f32").reshape(-1) for i in inps])
+    v = torch.cat([lava.to_device(i.v, "f32").reshape(-1) for i in inps])
+    s1, vb1, e1 = lava.lava_window_scores(desc, lens, q, k, v)
+    torch.cuda.synchronize()
+    s1 = s1.cpu().numpy()
+    tok, Hkv = 0, sh0.n_kv_heads
+    for b, (sh, inp) in enumerate(zip(shapes, inps)):
+        qq, kk, vv = inp.f64()
+        ref_s, ref_vbar = O.lava_scores(qq, kk, vv, sh.window, 7)
+        got = s1[Hkv * tok: Hkv * (tok + sh.n)].reshape(Hkv, sh.n)
+        compare_scores(sh, got, ref_s, vb1[b].cpu().numpy(), ref_vbar, float(e1[b]), O.layer_entropy(ref_s))
+        tok += sh.n
+
+
 # ------------------------------------------------------------------------------ whole layer
 def kept_set(counts, offs, idx, n):
     return set(int(g * n + p) for g in range(len(counts)) for p in idx[offs[g]:offs[g + 1]])
