@@ -287,3 +287,33 @@ def test_tables_with_device_side_offsets(lava):
         assert np.array_equal(lava.to_host_bits(t["vo"][o0: o0 + budgets[i]]), v_src[rows]), i
         assert np.array_equal(t["po"][o0: o0 + budgets[i]].cpu().numpy(), pos_src[rows]), i
     assert np.all(idx[out_rows:] == -7) and torch.all(t["ko"][out_rows:] == 5.0) and torch.all(t["po"][out_rows:] == -3)
+
+
+def test_compact_table_larger_than_one_launch_table(lava):
+    say("compact batch: 35 small problems (the per-launch table holds 32)")
+    dev = "cuda"
+    Hkv, d = 2, 64
+    desc = lava.LayerDesc.make(4, Hkv, d, 4, "f32")
+    r = np.random.Generator(np.random.PCG64(55))
+    probs, hold, want = [], [], []
+    for i in range(35):
+        n = int(r.integers(1, 90))
+        k_src = r.standard_normal((Hkv, n, d)).astype(np.float32)
+        v_src = r.standard_normal((Hkv, n, d)).astype(np.float32)
+        kept = [np.sort(r.choice(n, size=int(r.integers(0, n + 1)), replace=False)) for _ in range(Hkv)]
+        offs = np.concatenate([[0], np.cumsum([len(x) for x in kept])]).astype(np.int64)
+        idx = np.concatenate(kept).astype(np.int32) if offs[-1] else np.zeros(1, dtype=np.int32)
+        cap = int(offs[-1])
+        t = dict(k=torch.from_numpy(k_src).to(dev), v=torch.from_numpy(v_src).to(dev),
+                 offs=torch.from_numpy(offs).to(dev), idx=torch.from_numpy(idx).to(dev),
+                 ko=torch.full((cap + 1, d), 9.0, dtype=torch.float32, device=dev),
+                 vo=torch.full((cap + 1, d), 9.0, dtype=torch.float32, device=dev))
+        hold.append(t)
+        probs.append(lava.compact_problem(desc, n, t["k"].view(-1, d), t["v"].view(-1, d), t["offs"], t["idx"], cap,
+                                          t["ko"], t["vo"]))
+        want.append((cap, O.compact(k_src, offs, idx), O.compact(v_src, offs, idx)))
+    lava.lava_compact_batch(desc, probs)
+    torch.cuda.synchronize()
+    for i, (t, (cap, wk, wv)) in enumerate(zip(hold, want)):
+        assert np.array_equal(t["ko"][:cap].cpu().numpy(), wk) and np.array_equal(t["vo"][:cap].cpu().numpy(), wv), i
+        assert torch.all(t["ko"][cap:] == 9.0), i
