@@ -171,6 +171,26 @@ int32_t lava_select_topk(int32_t n_heads, const float* scores, const int64_t* se
 int32_t lava_select_status(const void* workspace, int64_t total_entries, void* hip_stream);
 
 /*
+ * lava_select_topk without a workspace argument, for callers that cannot allocate device memory:
+ * code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, same results bit for bit, same kernels; the selection's scratch memory (histograms,
+ * barrier counter, per-workgroup counts) is a fixed array of about 1 MiB inside the library's
+ * device image, which every GPU the library runs on holds until the process ends.  The call
+ * allocates and frees nothing.
+ *   total_entries <= LAVA_SELECT_STATIC_MAX_ENTRIES, else LAVA_ERR_WORKSPACE (nothing launched).
+ * All calls on one GPU share that GPU's array (it is cleared by the call's own first kernel, so
+ * a call does not depend on what the previous one left): calls that overlap in time on one GPU,
+ * on different streams or from different threads, race and must be serialised by the caller.
+ * A failed bounded wait cannot be queried for this variant (there is no workspace to pass to
+ * lava_select_status); the outputs are marked as described for lava_select_topk.
+ */
+#define LAVA_SELECT_STATIC_MAX_ENTRIES ((int64_t)1 << 22)
+int32_t lava_select_topk_static(int32_t n_heads, const float* scores, const int64_t* seg_offsets,
+                                int64_t total_entries, int64_t budget, const int64_t* budget_dev,
+                                int32_t* head_counts, int64_t* head_offsets, int32_t* kept_idx,
+                                float* kept_scores, void* hip_stream);
+
+/*
  * Packed surviving rows (Alg. 1: K^ = K (.) I, V^ = V (.) I, stored without the evicted rows):
  *   k_out[head_offsets[g] + t][:] = k[g][kept_idx[head_offsets[g] + t]][:], same for v.
  *

@@ -41,7 +41,7 @@ inline int32_t hip_ok(hipError_t e) { return e == hipSuccess ? LAVA_OK : LAVA_ER
 inline int32_t launch_status() { return hip_ok(hipGetLastError()); }
 
 constexpr size_t kAlign = 256;
-inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
+constexpr size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
 
 // ---------------------------------------------------------------- sweep (K, V) kernels
 constexpr int kTileKeys = 32;        // keys per MFMA tile
@@ -147,6 +147,8 @@ int32_t launch_select_batch(int n_heads, int n_problems, const lava_select_probl
                             void* ws, hipStream_t s);
 
 int32_t select_error_flag(const void* ws, int64_t max_total, int n_problems, hipStream_t s, int* flag);
+// host-side argument checks of one selection (shared by every entry point that takes one)
+int32_t check_select_problem(int32_t n_heads, const lava_select_problem& p);
 
 // src_offsets null: dense source [H_kv][n]; otherwise a packed source inside a pool of n rows.
 int32_t launch_compact(const lava_layer_desc& d, int64_t n, const int64_t* src_offsets, const void* k,

@@ -38,8 +38,10 @@ struct SelectState {
   unsigned int reserved[6];
 };
 
-SelectWorkspace make_select_workspace(int64_t total) {
-  SelectWorkspace w;
+// Layout of a selection's workspace for `total` entries (also evaluated at compile time, for the
+// built-in scratch array of lava_select_topk_static).
+static constexpr SelectWorkspace select_layout(int64_t total) {
+  SelectWorkspace w{};
   w.n_blocks = (int)((total + kSelChunk - 1) / kSelChunk);
   if (w.n_blocks < 1) w.n_blocks = 1;
   size_t off = 0;
@@ -54,6 +56,8 @@ SelectWorkspace make_select_workspace(int64_t total) {
   w.bytes = off;
   return w;
 }
+
+SelectWorkspace make_select_workspace(int64_t total) { return select_layout(total); }
 
 // Order-preserving map float -> uint32 (larger score = larger key); -0 and +0 coincide.
 __device__ __forceinline__ unsigned int score_key(float f) {
@@ -706,3 +710,58 @@ int32_t select_error_flag(const void* ws, int64_t max_total, int n_problems, hip
 }
 
 }  // namespace lava
+
+// ------------------------------------------------------------------------------------------
+// lava_select_topk for callers that cannot allocate (code under HIP graph capture, serving loops
+// and harnesses that forbid hipMalloc): the selection's workspace is a fixed array in the
+// library's own device image instead of a caller buffer.  Every GPU holds its own copy of the
+// array at its own address; the address is looked up once per device and the kernels receive it
+// as an ordinary pointer argument, exactly as they receive a caller's workspace.
+// ------------------------------------------------------------------------------------------
+namespace {
+constexpr int64_t kStaticMaxEntries = LAVA_SELECT_STATIC_MAX_ENTRIES;
+constexpr size_t kStaticScratchBytes = lava::select_layout(kStaticMaxEntries).bytes;
+static_assert(kStaticScratchBytes <= ((size_t)2 << 20), "the built-in scratch array is meant to stay small");
+}  // namespace
+
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+namespace {
+constexpr int kMaxDevices = 64;
+void* g_scratch_ptr[kMaxDevices];       // device address of `scratch` on each GPU, once known
+bool g_scratch_known[kMaxDevices];
+
+// Device address of this GPU's copy of the array (the array's name is a host-side handle, never a
+// device address).
+int32_t scratch_of_current_device(void** out) {
+  int dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return LAVA_ERR_HIP;
+  if (!g_scratch_known[dev]) {
+    void* p = nullptr;
+    if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || p == nullptr) return LAVA_ERR_HIP;
+    g_scratch_ptr[dev] = p;
+    g_scratch_known[dev] = true;
+  }
+  *out = g_scratch_ptr[dev];
+  return LAVA_OK;
+}
+}  // namespace
+
+extern "C" int32_t lava_select_topk_static(int32_t n_heads, const float* scores, const int64_t* seg_offsets,
+                                           int64_t total_entries, int64_t budget, const int64_t* budget_dev,
+                                           int32_t* head_counts, int64_t* head_offsets, int32_t* kept_idx,
+                                           float* kept_scores, void* hip_stream) {
+  if (n_heads < 1) return LAVA_ERR_INVALID_ARG;
+  if (n_heads > lava::kMaxHeads) return LAVA_ERR_SHAPE;
+  const lava_select_problem p = {scores,      seg_offsets,  total_entries, budget,     budget_dev,
+                                 head_counts, head_offsets, kept_idx,      kept_scores, nullptr, nullptr};
+  const int32_t st = lava::check_select_problem(n_heads, p);
+  if (st != LAVA_OK) return st;
+  if (total_entries > kStaticMaxEntries) return LAVA_ERR_WORKSPACE;   // beyond what the built-in array holds
+  void* ws = nullptr;
+  const int32_t sw = scratch_of_current_device(&ws);
+  if (sw != LAVA_OK) return sw;
+  // histograms, barrier counter and error word are cleared by the selection's own first kernel
+  return lava::launch_select_batch(n_heads, 1, &p, total_entries, ws, static_cast<hipStream_t>(hip_stream));
+}
+

@@ -73,6 +73,16 @@ static int32_t check_desc(const lava_layer_desc* d) {
   return LAVA_OK;
 }
 
+int32_t check_select_problem(int32_t n_heads, const lava_select_problem& p) {
+  if (p.scores == nullptr || p.head_counts == nullptr || p.head_offsets == nullptr || p.kept_idx == nullptr ||
+      p.total_entries < 1)
+    return LAVA_ERR_INVALID_ARG;
+  if (p.total_entries >= (int64_t)1 << 31) return LAVA_ERR_SHAPE;
+  if (p.seg_offsets == nullptr && p.total_entries % n_heads != 0) return LAVA_ERR_SHAPE;
+  if (p.budget < 0 || p.budget > p.total_entries) return LAVA_ERR_BUDGET;
+  return LAVA_OK;
+}
+
 static bool aligned16(const void* p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 }  // namespace lava
@@ -238,16 +248,6 @@ size_t lava_select_workspace_bytes(int64_t total_entries) {
 size_t lava_select_batch_workspace_bytes(int32_t n_problems, int64_t max_total_entries) {
   if (n_problems < 1 || max_total_entries < 1 || max_total_entries >= (int64_t)1 << 31) return 0;
   return make_select_workspace(max_total_entries).bytes * (size_t)n_problems;
-}
-
-static int32_t check_select_problem(int32_t n_heads, const lava_select_problem& p) {
-  if (p.scores == nullptr || p.head_counts == nullptr || p.head_offsets == nullptr || p.kept_idx == nullptr ||
-      p.total_entries < 1)
-    return LAVA_ERR_INVALID_ARG;
-  if (p.total_entries >= (int64_t)1 << 31) return LAVA_ERR_SHAPE;
-  if (p.seg_offsets == nullptr && p.total_entries % n_heads != 0) return LAVA_ERR_SHAPE;
-  if (p.budget < 0 || p.budget > p.total_entries) return LAVA_ERR_BUDGET;
-  return LAVA_OK;
 }
 
 int32_t lava_select_topk_batch(int32_t n_heads, int32_t n_problems, const lava_select_problem* problems,

@@ -23,6 +23,7 @@ LAVA_SCORE_LAVA, LAVA_SCORE_ATTENTION, LAVA_SCORE_TOKEN_NORM = 0, 1, 2
 EXPORTS = [
     "lava_status_string", "lava_window_scores_workspace_bytes", "lava_window_scores",
     "lava_layer_budgets", "lava_select_workspace_bytes", "lava_select_topk", "lava_select_status",
+    "lava_select_topk_static",
     "lava_select_batch_workspace_bytes", "lava_select_topk_batch", "lava_select_batch_status",
     "lava_compact_kv", "lava_compact_packed", "lava_compact_batch",
     "lava_cascade_workspace_bytes", "lava_cascade_step",
@@ -77,6 +78,8 @@ def _load() -> ctypes.CDLL:
     lib.lava_select_workspace_bytes.argtypes = [i64]
     lib.lava_select_topk.restype = i32
     lib.lava_select_topk.argtypes = [i32, vp, vp, i64, i64, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.lava_select_topk_static.restype = i32
+    lib.lava_select_topk_static.argtypes = [i32, vp, vp, i64, i64, vp, vp, vp, vp, vp, vp]
     lib.lava_select_status.restype = i32
     lib.lava_select_status.argtypes = [vp, i64, vp]
     lib.lava_compact_kv.restype = i32
@@ -253,6 +256,28 @@ def lava_select_topk(n_heads: int, scores: torch.Tensor, budget: int, seg_offset
                               _ptr(workspace), workspace.numel(), _stream(stream))
     _check(st, "lava_select_topk")
     return head_counts, head_offsets, kept_idx, kept_scores
+
+
+SELECT_STATIC_MAX_ENTRIES = 1 << 22
+
+
+def lava_select_topk_static(n_heads: int, scores: torch.Tensor, budget: int, head_counts: torch.Tensor,
+                            head_offsets: torch.Tensor, kept_idx: torch.Tensor,
+                            kept_scores: Optional[torch.Tensor] = None, seg_offsets: Optional[torch.Tensor] = None,
+                            budget_dev: Optional[torch.Tensor] = None, total_entries: Optional[int] = None,
+                            stream=None) -> None:
+    """lava_select_topk on the library's built-in scratch array.  Allocates nothing: every buffer is the caller's."""
+    _dev(scores, "scores", torch.float32), _dev(head_counts, "head_counts", torch.int32)
+    _dev(head_offsets, "head_offsets", torch.int64), _dev(kept_idx, "kept_idx", torch.int32)
+    for name, t, dt in (("kept_scores", kept_scores, torch.float32), ("seg_offsets", seg_offsets, torch.int64),
+                        ("budget_dev", budget_dev, torch.int64)):
+        if t is not None:
+            _dev(t, name, dt)
+    total = scores.numel() if total_entries is None else int(total_entries)
+    st = lib.lava_select_topk_static(n_heads, _ptr(scores), _ptr(seg_offsets), total, int(budget), _ptr(budget_dev),
+                                     _ptr(head_counts), _ptr(head_offsets), _ptr(kept_idx), _ptr(kept_scores),
+                                     _stream(stream))
+    _check(st, "lava_select_topk_static")
 
 
 def lava_select_status(workspace: torch.Tensor, total_entries: int, stream=None) -> int:
