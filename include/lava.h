@@ -23,8 +23,11 @@
  *     caller owns everything, including the workspace.  Outputs must not alias inputs.
  *   - Work is enqueued on `hip_stream` (a hipStream_t passed as void*; NULL = default stream)
  *     and the call returns without synchronising, unless stated otherwise.
- *   - All argument checks happen on the host before anything is launched; a call that returns
- *     an error has launched nothing.  Errors are reported by return code only.
+ *   - All argument checks happen on the host before anything is launched: a call that returns
+ *     an argument error (INVALID_ARG, SHAPE, BUDGET, WORKSPACE) has launched nothing.
+ *     LAVA_ERR_HIP means a launch failed; kernels of the same call enqueued before it may still
+ *     run.  An error left behind by earlier, unrelated HIP calls of the thread is discarded, not
+ *     reported.  Errors are reported by return code only.
  *   - Layouts are row-major with the last index fastest.  K and V are head-major per layer as
  *     in the paper's layer-wise view (App. A): [H_kv][N][d_h].
  *   - Notation: H query heads, H_kv KV heads, G = H / H_kv (query head h reads KV head
@@ -75,6 +78,29 @@ typedef struct lava_layer_desc {
 } lava_layer_desc;
 
 const char* lava_status_string(int32_t status);
+
+/*
+ * Launch-shape tuning, for tests and benchmarks: how the sweeps of lava_window_scores and the
+ * units of lava_decode_attention are cut, and how long a grid-wide wait polls.  A zero field
+ * means "the library's own choice", which is what production callers want.  The setting is
+ * process-wide and read at every call: set it while no call is in progress, and ask the
+ * *_workspace_bytes functions again after changing it (decode_rows_per_unit and
+ * sweep_workgroups change workspace sizes).  lava_set_tuning(NULL) restores the defaults.
+ * Results never depend on the tuning (scores: up to floating-point summation order of the
+ * softmax statistics; everything else bit for bit).
+ */
+typedef struct lava_tuning {
+  int32_t sweep_shape;          /* 0 library's choice, 1 wide (one workgroup per compute unit),
+                                   2 narrow (two per compute unit), where the kernels have both */
+  int32_t sweep_workgroups;     /* workgroups a sweep launch aims for, 1..65536                */
+  int32_t sweep_schedule;       /* 0 library's choice, 1 separate statistics and score launches,
+                                   2 one persistent launch for both where the shape allows it   */
+  int32_t decode_rows_per_unit; /* rows of one head per decode work unit, 128..8192            */
+  int32_t barrier_spin_limit;   /* polls of a grid-wide wait before it gives up (default 2^18) */
+  int32_t reserved[3];          /* must be zero                                                */
+} lava_tuning;
+int32_t lava_set_tuning(const lava_tuning* tuning);
+int32_t lava_get_tuning(lava_tuning* tuning);
 
 /* Bytes of device workspace lava_window_scores needs for `batch` sequences holding
  * `total_tokens` cached tokens in all.  Returns 0 for an invalid descriptor. */
@@ -155,6 +181,13 @@ size_t lava_select_workspace_bytes(int64_t total_entries);
  *   kept_scores   device float [budget] or NULL   the survivors' scores, same order (what a
  *                                             later re-selection with a smaller budget needs)
  * Integer-exact and deterministic.  n_heads <= 64, total_entries < 2^31.
+ *
+ * Up to half of the device's resident-workgroup capacity the selection is one launch whose
+ * workgroups meet at grid-wide barriers with bounded waits.  If a wait ever gives up (the device
+ * could not keep the workgroups resident together, e.g. because another stream held its compute
+ * units), the call's results are replaced by an unmistakable mark before the kernel ends:
+ * head_counts[h] = -1 for every head and head_offsets[0..n_heads] = 0, so that a compaction or a
+ * decode step fed with them moves and reads nothing; lava_select_status reports it on the host.
  */
 int32_t lava_select_topk(int32_t n_heads, const float* scores, const int64_t* seg_offsets,
                          int64_t total_entries, int64_t budget, const int64_t* budget_dev,
@@ -181,8 +214,8 @@ int32_t lava_select_status(const void* workspace, int64_t total_entries, void* h
  * All calls on one GPU share that GPU's array (it is cleared by the call's own first kernel, so
  * a call does not depend on what the previous one left): calls that overlap in time on one GPU,
  * on different streams or from different threads, race and must be serialised by the caller.
- * A failed bounded wait cannot be queried for this variant (there is no workspace to pass to
- * lava_select_status); the outputs are marked as described for lava_select_topk.
+ * A failed bounded wait cannot be queried with lava_select_status for this variant (there is no
+ * workspace to pass); the outputs carry the mark described for lava_select_topk.
  */
 #define LAVA_SELECT_STATIC_MAX_ENTRIES ((int64_t)1 << 22)
 int32_t lava_select_topk_static(int32_t n_heads, const float* scores, const int64_t* seg_offsets,
@@ -246,6 +279,9 @@ typedef struct lava_select_problem {
   const int64_t* in_offset_dev; /* or NULL: device int64, entries added to `scores` (the problem's
                                    scores start there)                                          */
   const int64_t* out_offset_dev;/* or NULL: device int64, entries added to kept_idx / kept_scores */
+  int32_t* error_dev;           /* or NULL: device int32 set to 1 if this selection gave up at a
+                                   bounded wait (never cleared by the library, so one word can
+                                   collect the failures of many selections)                     */
 } lava_select_problem;
 
 typedef struct lava_compact_problem {
@@ -310,6 +346,10 @@ typedef struct lava_cascade_state {
   int64_t* layer_start[2];  /* [max_layers + 1]                                                 */
   int32_t* head_counts;     /* [max_layers][H_kv] dynamic head budgets after the latest step    */
   int32_t* kept_idx;        /* [capacity] scratch                                               */
+  int32_t* error;           /* [1] or NULL: set to 1 by any step one of whose selections gave up
+                               at a bounded wait (that layer is then marked empty: head_counts
+                               -1, no rows); never cleared by the library: the state is invalid
+                               from then on, zero the word when the state is reset              */
   int64_t capacity;         /* rows per arena, >= total budget                                  */
   int32_t max_layers;
   int32_t cur;              /* 0 or 1; flipped by every lava_cascade_step                       */
@@ -372,7 +412,7 @@ size_t lava_decode_workspace_bytes(const lava_layer_desc* desc, int32_t batch, i
  *
  * A head without any row gives zeros (lse = -inf).  If a sequence's offsets exceed rows_capacity
  * its outputs are NaN.  fp32 accumulation, deterministic (fixed merge order).  Uses n_q_heads,
- * n_kv_heads (G <= 8), head_dim, dtype and softmax_scale of the descriptor; window and
+ * n_kv_heads (<= 64, G <= 8), head_dim, dtype and softmax_scale of the descriptor; window and
  * pool_kernel are ignored.
  */
 int32_t lava_decode_attention(const lava_layer_desc* desc, int32_t batch, const void* q,

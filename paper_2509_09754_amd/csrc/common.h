@@ -40,6 +40,13 @@ struct ProfScope {
 inline int32_t hip_ok(hipError_t e) { return e == hipSuccess ? LAVA_OK : LAVA_ERR_HIP; }
 inline int32_t launch_status() { return hip_ok(hipGetLastError()); }
 
+// Discards an error left in the thread by earlier HIP calls that are none of this library's, so that
+// the launch checks below report this call's launches only.
+inline void discard_stale_error() { (void)hipGetLastError(); }
+
+// The process-wide launch-shape tuning (lava_set_tuning); all-zero = the library's own choices.
+const lava_tuning& tuning();
+
 constexpr size_t kAlign = 256;
 constexpr size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
 

@@ -21,7 +21,6 @@
 //
 // The step is bound by HBM: 2 * d_h * elem bytes per retained row against 4 * G * d_h flop.
 #include <math.h>
-#include <stdlib.h>
 
 #include "common.h"
 #include "tile_ring.h"
@@ -111,10 +110,14 @@ struct UnitMap {
 __device__ __forceinline__ UnitMap map_units(const long long* __restrict__ offs, int n_heads, long long capacity,
                                              int rows_per_unit, long long tail_len, int lane) {
   UnitMap m;
-  const long long o = lane <= n_heads ? offs[lane] : 0;
-  const long long o_next = __shfl_down(o, 1);
+  // lane g holds offs[g]; the end of the last head comes from a load of its own, because with 64
+  // heads no lane is left to hold offs[64]
   const bool head = lane < n_heads;
-  const bool bad = (head && o_next < o) || (lane == 0 && o < 0) || (lane == n_heads && o > capacity);
+  const long long o = head ? offs[lane] : 0;
+  const long long o_end = offs[n_heads];
+  const long long o_down = __shfl_down(o, 1);
+  const long long o_next = lane == n_heads - 1 ? o_end : o_down;
+  const bool bad = (head && o_next < o) || (lane == 0 && o < 0) || o_end > capacity;
   m.usable = __ballot(bad) == 0ull;
   m.off = o;
   m.len = head && m.usable ? o_next - o : 0;
@@ -453,10 +456,7 @@ DecodePlan make_decode_plan(const lava_layer_desc& d, int32_t batch, int64_t row
   int64_t c = (total / (4 * (int64_t)device_cus()) + step - 1) / step * step;
   if (c < step) c = step;
   if (c > 8 * step) c = 8 * step;
-  if (const char* env = getenv("LAVA_DECODE_ROWS")) {      // tuning knob: rows per unit
-    const long v = atol(env);
-    if (v >= step && v <= 64 * step) c = v / step * step;
-  }
+  if (tuning().decode_rows_per_unit >= step) c = tuning().decode_rows_per_unit / step * step;   // caller's tuning
   p.rows_per_unit = (int)c;
   p.group_pad = padded_group(d.n_q_heads / d.n_kv_heads);
   const int64_t tail_units = tail_len > 0 ? (tail_len + c - 1) / c : 0;

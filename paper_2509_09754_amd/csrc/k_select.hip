@@ -24,7 +24,7 @@ constexpr int kSelPerThread = 16;
 constexpr int kSelChunk = kSelThreads * kSelPerThread;  // entries per workgroup
 constexpr int kBins = 2048;
 constexpr int kMaxHeads = 64;
-constexpr unsigned int kSpinLimit = 1u << 18;           // polls of a grid barrier before giving up
+constexpr unsigned int kSpinLimit = 1u << 18;           // polls of a grid barrier before giving up (default)
 
 // The fused kernel's last histogram pass also publishes, per workgroup, how many of its keys lie
 // above each possible last digit (kPubWords = 1024 digits + 1), so that the counts every
@@ -35,7 +35,8 @@ constexpr int kFusedMaxBlocks = 1024;   // more workgroups than any device keeps
 struct SelectState {
   unsigned int barrier;      // arrivals at the grid barriers of the fused kernel (monotonic)
   unsigned int error;        // set when a barrier wait gave up (results are then invalid)
-  unsigned int reserved[6];
+  unsigned int done;         // workgroups of the fused kernel that have written their results
+  unsigned int reserved[5];
 };
 
 // Layout of a selection's workspace for `total` entries (also evaluated at compile time, for the
@@ -444,7 +445,8 @@ __device__ __forceinline__ void prefix_published_phase(int bx, const unsigned in
 // Grid-wide barrier of the fused kernel: all of its workgroups are resident (the host checks the
 // grid against the device's capacity), arrivals are counted monotonically, and the wait is
 // bounded: if it ever gives up, the error word is set and the kernel still runs to completion.
-__device__ __forceinline__ void grid_sync(SelectState* __restrict__ st, unsigned int round, unsigned int n_blocks) {
+__device__ __forceinline__ void grid_sync(SelectState* __restrict__ st, unsigned int round, unsigned int n_blocks,
+                                          unsigned int spin_limit) {
   drain_vmem();
   __syncthreads();
   if (threadIdx.x == 0) {
@@ -453,7 +455,7 @@ __device__ __forceinline__ void grid_sync(SelectState* __restrict__ st, unsigned
     unsigned int spins = 0u;
     while (ld_dev(&st->barrier) < target) {
       __builtin_amdgcn_s_sleep(2);
-      if (++spins > kSpinLimit) {
+      if (++spins > spin_limit) {
         st_dev(&st->error, 1u);
         break;
       }
@@ -473,6 +475,7 @@ struct SelectBatch {
   char* ws;                      // region of problem p at ws + p * ws_stride
   size_t ws_stride, off_hist, off_state, off_blk;
   int blk_stride;                // n_blocks the regions were laid out for
+  unsigned int spin_limit;       // polls of a grid barrier before it gives up
   lava_select_problem p[kMaxSelProblems];
 };
 
@@ -498,6 +501,7 @@ __global__ void __launch_bounds__(kSelThreads) sel_init_kernel(const SelectBatch
   if (threadIdx.x == 0) {
     st->barrier = 0u;
     st->error = 0u;
+    st->done = 0u;
   }
 }
 
@@ -539,13 +543,13 @@ __global__ void __launch_bounds__(kSelThreads) sel_fused_kernel(const SelectBatc
   const long long kept_total = pk.need;
 
   hist_phase<0>(bx, val, total, pk.prefix, sh, hist);
-  grid_sync(st, 1u, nb);
+  grid_sync(st, 1u, nb, a.spin_limit);
   pk = pick_phase<0>(hist, pk, sh);
   hist_phase<1>(bx, val, total, pk.prefix, sh, hist + kBins);
-  grid_sync(st, 2u, nb);
+  grid_sync(st, 2u, nb, a.spin_limit);
   pk = pick_phase<1>(hist + kBins, pk, sh);
   hist_publish_phase(bx, val, total, pk.prefix, sh, hist + 2 * kBins, blk + (size_t)bx * kPubWords);
-  grid_sync(st, 3u, nb);
+  grid_sync(st, 3u, nb, a.spin_limit);
   pk = pick_phase<2>(hist + 2 * kBins, pk, sh);
 
   // the counts of the workgroups before this one were published with the last histogram: no
@@ -557,6 +561,22 @@ __global__ void __launch_bounds__(kSelThreads) sel_fused_kernel(const SelectBatc
   write_phase(bx, val, total, n_heads, seg_offsets, gt_mask, eq_mask, pk.need, budget, gt_before, eq_before,
               kept_total, sh, pr.head_counts, pr.head_offsets, pr.kept_idx + out_off,
               pr.kept_scores ? pr.kept_scores + out_off : nullptr);
+
+  // A wait that gave up leaves results computed from incomplete histograms.  The workgroup that
+  // finishes last (every other one has completed its writes before taking its ticket) then replaces
+  // them by a mark no consumer can mistake for a selection: no survivors anywhere, counts -1.
+  drain_vmem();
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    const unsigned int t = __hip_atomic_fetch_add(&st->done, 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    sh.wave[0] = (t + 1u == nb && ld_dev(&st->error) != 0u) ? 1u : 0u;
+  }
+  __syncthreads();
+  if (sh.wave[0] != 0u) {
+    if (threadIdx.x < (unsigned)n_heads) pr.head_counts[threadIdx.x] = -1;
+    if (threadIdx.x <= (unsigned)n_heads) pr.head_offsets[threadIdx.x] = 0;
+    if (threadIdx.x == 0 && pr.error_dev != nullptr) *pr.error_dev = 1;
+  }
 }
 
 // The same phases as separate launches (kernel boundaries take the place of the grid barriers),
@@ -621,10 +641,10 @@ static int fused_capacity() {
 }
 
 // Selections of a batch: consecutive problems are packed into launches of the fused kernel as long
-// as their workgroups fit on the device together (they all have to be resident: each problem meets
-// at its own grid barriers; should another stream hold compute units for so long that a bounded
-// wait gives up, the status call reports it).  A single problem only takes the fused path up to half
-// of the device and runs as step launches beyond that.
+// as their workgroups fit into half of the device together (they all have to be resident: each
+// problem meets at its own grid barriers; should another stream hold compute units for so long that
+// a bounded wait gives up, the kernel marks the outputs and the status call reports it).  A single
+// problem wider than that runs as step launches.
 int32_t launch_select_batch(int n_heads, int n_problems, const lava_select_problem* problems, int64_t max_total,
                             void* ws, hipStream_t s) {
   const SelectWorkspace w = make_select_workspace(max_total);
@@ -636,7 +656,10 @@ int32_t launch_select_batch(int n_heads, int n_problems, const lava_select_probl
   a.off_blk = w.off_blk;
   a.blk_stride = w.n_blocks;
   const dim3 block(kSelThreads);
-  const int cap = fused_capacity() < kFusedMaxBlocks ? fused_capacity() : kFusedMaxBlocks;
+  // Half of what the device can keep resident: the grid barriers need every workgroup of a launch
+  // on the device at once, and the margin leaves room for whatever else is running there.
+  const int cap = (fused_capacity() < kFusedMaxBlocks ? fused_capacity() : kFusedMaxBlocks) / 2;
+  a.spin_limit = tuning().barrier_spin_limit > 0 ? (unsigned int)tuning().barrier_spin_limit : kSpinLimit;
   int first = 0;
   while (first < n_problems) {
     int count = 0, blocks = 0;
@@ -656,7 +679,7 @@ int32_t launch_select_batch(int n_heads, int n_problems, const lava_select_probl
       ProfScope ps(KID_SEL_INIT, s);
       hipLaunchKernelGGL(sel_init_kernel, dim3(count), block, 0, s, a);
     }
-    if (count > 1 || blocks <= cap / 2) {
+    if (blocks <= cap) {
       ProfScope ps(KID_SEL_FUSED, s);
       hipLaunchKernelGGL(sel_fused_kernel, dim3(blocks), block, 0, s, a);
     } else {                                               // a single problem wider than the device allows
@@ -691,6 +714,7 @@ int32_t launch_select(int n_heads, const float* scores, const int64_t* seg_offse
   pr.kept_scores = kept_scores;
   pr.in_offset_dev = nullptr;
   pr.out_offset_dev = nullptr;
+  pr.error_dev = nullptr;
   return launch_select_batch(n_heads, 1, &pr, total, ws, s);
 }
 
@@ -754,13 +778,14 @@ extern "C" int32_t lava_select_topk_static(int32_t n_heads, const float* scores,
   if (n_heads < 1) return LAVA_ERR_INVALID_ARG;
   if (n_heads > lava::kMaxHeads) return LAVA_ERR_SHAPE;
   const lava_select_problem p = {scores,      seg_offsets,  total_entries, budget,     budget_dev,
-                                 head_counts, head_offsets, kept_idx,      kept_scores, nullptr, nullptr};
+                                 head_counts, head_offsets, kept_idx,      kept_scores, nullptr, nullptr, nullptr};
   const int32_t st = lava::check_select_problem(n_heads, p);
   if (st != LAVA_OK) return st;
   if (total_entries > kStaticMaxEntries) return LAVA_ERR_WORKSPACE;   // beyond what the built-in array holds
   void* ws = nullptr;
   const int32_t sw = scratch_of_current_device(&ws);
   if (sw != LAVA_OK) return sw;
+  lava::discard_stale_error();
   // histograms, barrier counter and error word are cleared by the selection's own first kernel
   return lava::launch_select_batch(n_heads, 1, &p, total_entries, ws, static_cast<hipStream_t>(hip_stream));
 }

@@ -19,7 +19,6 @@
 //   stats  : D = K_tile * Q^T  -> a lane holds 16 keys of ONE query row: row reductions stay in-lane
 //   scores : D = Q * K_tile^T  -> a lane holds 16 query rows of ONE key: the window mean stays in-lane
 #include <math.h>
-#include <stdlib.h>
 
 #include "common.h"
 #include "tile_ring.h"
@@ -771,10 +770,7 @@ SweepPlan make_sweep_plan(const lava_layer_desc& d, int64_t n, int64_t batch_tok
   // per-workgroup set-up (query load, partial results) is amortised over as many tiles as possible.
   const int64_t device_wgs = compute_units();
   int64_t target_wgs = p.narrow ? 2 * device_wgs : device_wgs;
-  if (const char* env = getenv("LAVA_SWEEP_WGS")) {      // tuning knob: workgroups per sweep launch
-    const long v = atol(env);
-    if (v >= 1 && v <= 65536) target_wgs = v;
-  }
+  if (tuning().sweep_workgroups > 0) target_wgs = tuning().sweep_workgroups;   // forced by the caller's tuning
   // a sequence that shares its launches with others gets its share of the device, so that the
   // batch as a whole is cut into the longest runs the kernels allow
   const bool shared = batch_tokens > n;

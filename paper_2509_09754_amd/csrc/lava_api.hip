@@ -1,6 +1,5 @@
 // C ABI of the library: argument checks on the host, then kernel launches on the caller's
 // stream.  Nothing here allocates device memory.
-#include <stdlib.h>
 #include <string.h>
 
 #include <vector>
@@ -57,6 +56,12 @@ void prof_end(int kid, hipStream_t s) {
   if (g_prof.used[kid] >= 4096) prof_collect();   // bound the number of live events
 }
 
+// ------------------------------------------------------------------ launch-shape tuning
+namespace {
+lava_tuning g_tuning = {};
+}
+const lava_tuning& tuning() { return g_tuning; }
+
 // ------------------------------------------------------------------ descriptor checks
 static int32_t check_desc(const lava_layer_desc* d) {
   if (d == nullptr) return LAVA_ERR_INVALID_ARG;
@@ -103,6 +108,26 @@ const char* lava_status_string(int32_t status) {
   }
 }
 
+int32_t lava_set_tuning(const lava_tuning* t) {
+  if (t == nullptr) {
+    g_tuning = lava_tuning{};
+    return LAVA_OK;
+  }
+  if (t->sweep_shape < 0 || t->sweep_shape > 2 || t->sweep_schedule < 0 || t->sweep_schedule > 2 ||
+      t->sweep_workgroups < 0 || t->sweep_workgroups > 65536 || t->barrier_spin_limit < 0 ||
+      (t->decode_rows_per_unit != 0 && (t->decode_rows_per_unit < 128 || t->decode_rows_per_unit > 8192)) ||
+      t->reserved[0] != 0 || t->reserved[1] != 0 || t->reserved[2] != 0)
+    return LAVA_ERR_INVALID_ARG;
+  g_tuning = *t;
+  return LAVA_OK;
+}
+
+int32_t lava_get_tuning(lava_tuning* t) {
+  if (t == nullptr) return LAVA_ERR_INVALID_ARG;
+  *t = g_tuning;
+  return LAVA_OK;
+}
+
 size_t lava_window_scores_workspace_bytes(const lava_layer_desc* desc, int32_t batch,
                                           int64_t total_tokens) {
   if (check_desc(desc) != LAVA_OK || batch < 1 || total_tokens <= desc->window) return 0;
@@ -142,6 +167,7 @@ int32_t lava_window_scores(const lava_layer_desc* desc, int32_t batch, const int
     return LAVA_ERR_WORKSPACE;
 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  discard_stale_error();
   SweepArgs a;
   a.q_win = q_win;
   a.k = k;
@@ -184,10 +210,8 @@ int32_t lava_window_scores(const lava_layer_desc* desc, int32_t batch, const int
         wide_wgs += (int64_t)make_sweep_plan(d, seq_lens[b0 + i], launch_tokens).blocks_x * d.n_kv_heads * plan_max.n_chunks;
       narrow = wide_wgs > sweep_device_wgs();
     }
-    if (const char* env = getenv("LAVA_SWEEP_SHAPE")) {      // tuning knob: force one shape
-      if (strcmp(env, "narrow") == 0) narrow = true;
-      else if (strcmp(env, "wide") == 0) narrow = false;
-    }
+    if (tuning().sweep_shape == 1) narrow = false;           // forced by the caller's tuning
+    else if (tuning().sweep_shape == 2) narrow = true;
     SweepPlan plan_launch = plan_max;
     plan_launch.narrow = narrow && sweep_has_narrow_shape(d);
     for (int i = 0; i < a.n_seq; ++i) {
@@ -234,6 +258,7 @@ int32_t lava_layer_budgets(int32_t batch, int32_t n_layers, const float* e, cons
       hi == nullptr || budgets == nullptr)
     return LAVA_ERR_INVALID_ARG;
   if (n_layers > 1024) return LAVA_ERR_SHAPE;
+  if (on_device) discard_stale_error();
   if (on_device)
     return launch_budgets(batch, n_layers, e, total, lo, hi, budgets,
                           static_cast<hipStream_t>(hip_stream));
@@ -263,6 +288,7 @@ int32_t lava_select_topk_batch(int32_t n_heads, int32_t n_problems, const lava_s
   const size_t need = make_select_workspace(max_total_entries).bytes * (size_t)n_problems;
   if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 || workspace_bytes < need)
     return LAVA_ERR_WORKSPACE;
+  discard_stale_error();
   return launch_select_batch(n_heads, n_problems, problems, max_total_entries, workspace,
                              static_cast<hipStream_t>(hip_stream));
 }
@@ -274,7 +300,7 @@ int32_t lava_select_topk(int32_t n_heads, const float* scores, const int64_t* se
                          void* hip_stream) {
   if (n_heads < 1) return LAVA_ERR_INVALID_ARG;
   const lava_select_problem p = {scores,      seg_offsets,  total_entries, budget,     budget_dev,
-                                 head_counts, head_offsets, kept_idx,      kept_scores};
+                                 head_counts, head_offsets, kept_idx,      kept_scores, nullptr, nullptr, nullptr};
   return lava_select_topk_batch(n_heads, 1, &p, total_entries, workspace, workspace_bytes, hip_stream);
 }
 
@@ -313,6 +339,7 @@ int32_t lava_compact_batch(const lava_layer_desc* desc, int32_t n_problems,
     st = check_compact_problem(*desc, problems[p]);
     if (st != LAVA_OK) return st;
   }
+  discard_stale_error();
   return launch_compact_batch(*desc, n_problems, problems, static_cast<hipStream_t>(hip_stream));
 }
 
@@ -377,6 +404,7 @@ int32_t lava_cascade_step(const lava_layer_desc* desc, int32_t layer, int64_t n,
       workspace_bytes < make_select_workspace(dense).bytes * (size_t)(layer + 1))
     return LAVA_ERR_WORKSPACE;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
+  discard_stale_error();
   const int H1 = desc->n_kv_heads + 1;
   const int a = S.cur, b = 1 - S.cur;
 
@@ -397,12 +425,12 @@ int32_t lava_cascade_step(const lava_layer_desc* desc, int32_t layer, int64_t n,
       const int64_t* offs_cur = S.head_offsets[a] + (size_t)t * H1;
       const int64_t* start_cur = S.layer_start[a] + t;
       sel[t] = {S.scores[a], offs_cur, bound,      bound,       budgets + t, counts,
-                offs_new,    S.kept_idx, S.scores[b], start_cur, start_new};
+                offs_new,    S.kept_idx, S.scores[b], start_cur, start_new, S.error};
       cmp[t] = {S.capacity, offs_cur, S.k[a], S.v[a], S.pos[a],  offs_new,  S.kept_idx,
                 S.capacity, S.k[b],   S.v[b], S.pos[b], start_cur, start_new};
     } else {
       sel[t] = {scores_new, nullptr,    dense,       bound,   budgets + t, counts,
-                offs_new,   S.kept_idx, S.scores[b], nullptr, start_new};
+                offs_new,   S.kept_idx, S.scores[b], nullptr, start_new, S.error};
       cmp[t] = {n,          nullptr, k_new,  v_new,    nullptr, offs_new, S.kept_idx,
                 S.capacity, S.k[b],  S.v[b], S.pos[b], nullptr, start_new};
     }
@@ -454,6 +482,7 @@ int32_t lava_decode_attention(const lava_layer_desc* desc, int32_t batch, const 
   if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 ||
       workspace_bytes < p.bytes)
     return LAVA_ERR_WORKSPACE;
+  discard_stale_error();
   return launch_decode(d, batch, q, k_hat, v_hat, head_offsets, seq_base, rows_capacity, k_tail, v_tail,
                        tail_len, tail_capacity, out, lse, workspace, p, static_cast<hipStream_t>(hip_stream));
 }

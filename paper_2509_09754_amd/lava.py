@@ -21,7 +21,7 @@ LAVA_F32, LAVA_BF16 = 0, 1
 LAVA_SCORE_LAVA, LAVA_SCORE_ATTENTION, LAVA_SCORE_TOKEN_NORM = 0, 1, 2
 
 EXPORTS = [
-    "lava_status_string", "lava_window_scores_workspace_bytes", "lava_window_scores",
+    "lava_status_string", "lava_set_tuning", "lava_get_tuning", "lava_window_scores_workspace_bytes", "lava_window_scores",
     "lava_layer_budgets", "lava_select_workspace_bytes", "lava_select_topk", "lava_select_status",
     "lava_select_topk_static",
     "lava_select_batch_workspace_bytes", "lava_select_topk_batch", "lava_select_batch_status",
@@ -52,6 +52,19 @@ class LayerDesc(ctypes.Structure):
         return torch.bfloat16 if self.dtype == LAVA_BF16 else torch.float32
 
 
+class Tuning(ctypes.Structure):
+    """Mirror of lava_tuning (zero = the library's own choice)."""
+    _fields_ = [
+        ("sweep_shape", ctypes.c_int32), ("sweep_workgroups", ctypes.c_int32), ("sweep_schedule", ctypes.c_int32),
+        ("decode_rows_per_unit", ctypes.c_int32), ("barrier_spin_limit", ctypes.c_int32),
+        ("reserved", ctypes.c_int32 * 3),
+    ]
+
+
+SWEEP_SHAPES = {"auto": 0, "wide": 1, "narrow": 2}
+SWEEP_SCHEDULES = {"auto": 0, "separate": 1, "persistent": 2}
+
+
 class LavaError(RuntimeError):
     def __init__(self, status: int, where: str):
         self.status = status
@@ -68,6 +81,10 @@ def _load() -> ctypes.CDLL:
     dp = ctypes.POINTER(LayerDesc)
     lib.lava_status_string.restype = ctypes.c_char_p
     lib.lava_status_string.argtypes = [i32]
+    lib.lava_set_tuning.restype = i32
+    lib.lava_set_tuning.argtypes = [ctypes.POINTER(Tuning)]
+    lib.lava_get_tuning.restype = i32
+    lib.lava_get_tuning.argtypes = [ctypes.POINTER(Tuning)]
     lib.lava_window_scores_workspace_bytes.restype = sz
     lib.lava_window_scores_workspace_bytes.argtypes = [dp, i32, i64]
     lib.lava_window_scores.restype = i32
@@ -160,6 +177,20 @@ def to_host_bits(t: torch.Tensor) -> np.ndarray:
 
 
 # ------------------------------------------------------------------------------ entry points
+def set_tuning(sweep_shape="auto", sweep_workgroups=0, sweep_schedule="auto", decode_rows_per_unit=0,
+               barrier_spin_limit=0) -> None:
+    """lava_set_tuning; called without arguments it restores the library's own choices."""
+    t = Tuning(SWEEP_SHAPES[sweep_shape], int(sweep_workgroups), SWEEP_SCHEDULES[sweep_schedule],
+               int(decode_rows_per_unit), int(barrier_spin_limit))
+    _check(lib.lava_set_tuning(ctypes.byref(t)), "lava_set_tuning")
+
+
+def get_tuning() -> Tuning:
+    t = Tuning()
+    _check(lib.lava_get_tuning(ctypes.byref(t)), "lava_get_tuning")
+    return t
+
+
 def lava_window_scores_workspace_bytes(desc: LayerDesc, batch: int, total_tokens: int) -> int:
     return int(lib.lava_window_scores_workspace_bytes(ctypes.byref(desc), batch, total_tokens))
 
@@ -291,7 +322,7 @@ class SelectProblem(ctypes.Structure):
         ("scores", ctypes.c_void_p), ("seg_offsets", ctypes.c_void_p), ("total_entries", ctypes.c_int64),
         ("budget", ctypes.c_int64), ("budget_dev", ctypes.c_void_p), ("head_counts", ctypes.c_void_p),
         ("head_offsets", ctypes.c_void_p), ("kept_idx", ctypes.c_void_p), ("kept_scores", ctypes.c_void_p),
-        ("in_offset_dev", ctypes.c_void_p), ("out_offset_dev", ctypes.c_void_p),
+        ("in_offset_dev", ctypes.c_void_p), ("out_offset_dev", ctypes.c_void_p), ("error_dev", ctypes.c_void_p),
     ]
 
 
@@ -311,19 +342,20 @@ def _addr(t: Optional[torch.Tensor]):
 
 
 def select_problem(scores, budget, head_counts, head_offsets, kept_idx, kept_scores=None, seg_offsets=None,
-                   budget_dev=None, total_entries=None, in_offset_dev=None, out_offset_dev=None) -> SelectProblem:
+                   budget_dev=None, total_entries=None, in_offset_dev=None, out_offset_dev=None,
+                   error_dev=None) -> SelectProblem:
     """One row of the table of lava_select_topk_batch from device tensors (the caller keeps them alive)."""
     _dev(scores, "scores", torch.float32), _dev(head_counts, "head_counts", torch.int32)
     _dev(head_offsets, "head_offsets", torch.int64), _dev(kept_idx, "kept_idx", torch.int32)
     for name, t, dt in (("kept_scores", kept_scores, torch.float32), ("seg_offsets", seg_offsets, torch.int64),
                         ("budget_dev", budget_dev, torch.int64), ("in_offset_dev", in_offset_dev, torch.int64),
-                        ("out_offset_dev", out_offset_dev, torch.int64)):
+                        ("out_offset_dev", out_offset_dev, torch.int64), ("error_dev", error_dev, torch.int32)):
         if t is not None:
             _dev(t, name, dt)
     total = scores.numel() if total_entries is None else int(total_entries)
     return SelectProblem(_addr(scores), _addr(seg_offsets), total, int(budget), _addr(budget_dev),
                          _addr(head_counts), _addr(head_offsets), _addr(kept_idx), _addr(kept_scores),
-                         _addr(in_offset_dev), _addr(out_offset_dev))
+                         _addr(in_offset_dev), _addr(out_offset_dev), _addr(error_dev))
 
 
 def compact_problem(desc: LayerDesc, src_rows, k_src, v_src, head_offsets, kept_idx, capacity, k_out, v_out,
@@ -417,7 +449,7 @@ class CascadeStateStruct(ctypes.Structure):
     _fields_ = [
         ("k", ctypes.c_void_p * 2), ("v", ctypes.c_void_p * 2), ("pos", ctypes.c_void_p * 2),
         ("scores", ctypes.c_void_p * 2), ("head_offsets", ctypes.c_void_p * 2), ("layer_start", ctypes.c_void_p * 2),
-        ("head_counts", ctypes.c_void_p), ("kept_idx", ctypes.c_void_p),
+        ("head_counts", ctypes.c_void_p), ("kept_idx", ctypes.c_void_p), ("error", ctypes.c_void_p),
         ("capacity", ctypes.c_int64), ("max_layers", ctypes.c_int32), ("cur", ctypes.c_int32),
     ]
 
@@ -437,6 +469,7 @@ class CascadeState:
         self.layer_start = [torch.zeros(max_layers + 1, dtype=torch.int64, device=device) for _ in range(2)]
         self.head_counts = torch.zeros(max_layers, hk, dtype=torch.int32, device=device)
         self.kept_idx = torch.empty(capacity, dtype=torch.int32, device=device)
+        self.error = torch.zeros(1, dtype=torch.int32, device=device)
         self.e = torch.zeros(max_layers, dtype=torch.float32, device=device)
         self.budgets = torch.zeros(max_layers, dtype=torch.int64, device=device)
         c = self.c = CascadeStateStruct()
@@ -445,6 +478,7 @@ class CascadeState:
             c.scores[i] = self.scores[i].data_ptr()
             c.head_offsets[i], c.layer_start[i] = self.head_offsets[i].data_ptr(), self.layer_start[i].data_ptr()
         c.head_counts, c.kept_idx = self.head_counts.data_ptr(), self.kept_idx.data_ptr()
+        c.error = self.error.data_ptr()
         c.capacity, c.max_layers, c.cur = self.capacity, self.n_layers, 0
 
     @property
@@ -453,6 +487,7 @@ class CascadeState:
 
     def reset(self) -> None:
         self.c.cur = 0
+        self.error.zero_()
 
     def bytes(self) -> int:
         """Device bytes the state holds."""

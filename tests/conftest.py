@@ -20,3 +20,12 @@ def pytest_collection_modifyitems(config, items):
     for item in items:
         if "gpu" in item.keywords:
             item.add_marker(skip)
+
+
+@pytest.fixture
+def tuning():
+    """lava.set_tuning for the duration of one test (launch shapes chosen through the C ABI); the
+    library's own choices are restored afterwards."""
+    from paper_2509_09754_amd import lava
+    yield lava.set_tuning
+    lava.set_tuning()

@@ -36,6 +36,37 @@ def test_status_strings():
     assert lava.lib.lava_prof_kernel_name(0) == b"vnorm"
 
 
+def test_tuning_round_trip_and_validation():
+    try:
+        lava.set_tuning(sweep_shape="narrow", sweep_workgroups=300, decode_rows_per_unit=256, barrier_spin_limit=7)
+        t = lava.get_tuning()
+        assert (t.sweep_shape, t.sweep_workgroups, t.decode_rows_per_unit, t.barrier_spin_limit) == (2, 300, 256, 7)
+        bad = lava.Tuning(3, 0, 0, 0, 0)
+        assert lava.lib.lava_set_tuning(ctypes.byref(bad)) == lava.LAVA_ERR_INVALID_ARG
+        bad = lava.Tuning(0, 0, 0, 64, 0)                       # fewer rows than one round of the decode wavefronts
+        assert lava.lib.lava_set_tuning(ctypes.byref(bad)) == lava.LAVA_ERR_INVALID_ARG
+        bad = lava.Tuning(0, 0, 0, 0, 0)
+        bad.reserved[1] = 1
+        assert lava.lib.lava_set_tuning(ctypes.byref(bad)) == lava.LAVA_ERR_INVALID_ARG
+        assert lava.get_tuning().sweep_workgroups == 300        # a rejected setting changes nothing
+        assert lava.lib.lava_get_tuning(None) == lava.LAVA_ERR_INVALID_ARG
+        # the decode unit size is part of the workspace layout: the size query follows the tuning
+        d = _desc()
+        small_units = lava.lava_decode_workspace_bytes(d, 4, 65536, 0)
+        lava.set_tuning(decode_rows_per_unit=1024)
+        assert lava.lava_decode_workspace_bytes(d, 4, 65536, 0) < small_units
+    finally:
+        assert lava.lib.lava_set_tuning(None) == lava.LAVA_OK
+    t = lava.get_tuning()
+    assert (t.sweep_shape, t.sweep_workgroups, t.sweep_schedule, t.decode_rows_per_unit, t.barrier_spin_limit) == (0,) * 5
+
+
+def test_no_environment_variable_is_read_by_the_library():
+    src = os.path.join(ROOT, "paper_2509_09754_amd", "csrc")
+    for name in sorted(os.listdir(src)):
+        assert "getenv" not in open(os.path.join(src, name)).read(), name
+
+
 def _desc(**kw):
     base = dict(n_q_heads=32, n_kv_heads=8, head_dim=128, window=32, dtype="bf16")
     base.update(kw)

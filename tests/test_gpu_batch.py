@@ -230,6 +230,116 @@ def test_ragged_batch_full_size_one_layer(lava):
     assert least >= 0.999
 
 
+def test_ragged_batch_several_layers_dynamic_budgets(lava):
+    """The batched serving configuration as a stack: 16 ragged sequences (one of them only w + 1 tokens
+    long) x 4 layers, every sequence with its own total budget split over its layers by the layer
+    statistics (batched lava_layer_budgets on the device), then one table of selections and one of
+    compactions over all (sequence, layer) pairs.  The expected values come from the oracle alone, per
+    sequence, from the raw inputs: statistics -> budgets -> kept sets; the GPU's budgets may differ from
+    them by one unit per layer (fp32 statistics on a rounding boundary), selections are bit-exact on the
+    scores the GPU produced, kept sets overlap the oracle's >= 99.9 %, rows are bit copies."""
+    L = 4
+    base = synth.config(5)
+    H, Hkv, d, w = base.n_q_heads, base.n_kv_heads, base.head_dim, base.window
+    lens = [int(x) for x in synth.ragged_lengths(15, 3)]
+    lens.insert(6, w + 1)                                       # one prefix token per head
+    nb = len(lens)
+    per_layer = Hkv * 256
+    totals = [min(L * per_layer, L * Hkv * n - (L if n > w + 1 else 8)) for n in lens]
+    say(f"ragged stack: {L} layers, lengths {lens}, totals {totals}")
+    desc = lava.LayerDesc.make(H, Hkv, d, w, base.dtype)
+    dev = "cuda"
+    starts = np.concatenate([[0], np.cumsum(lens)])
+    tok = int(starts[-1])
+    stat = torch.zeros(nb, L, dtype=torch.float32, device=dev)
+    scores = torch.empty(L, Hkv * tok, dtype=torch.float32, device=dev)
+    k_dev = torch.empty(L, Hkv * tok, d, dtype=torch.bfloat16, device=dev)
+    v_dev = torch.empty(L, Hkv * tok, d, dtype=torch.bfloat16, device=dev)
+    ref_e = np.zeros((nb, L))
+    ref_scores = [[None] * L for _ in range(nb)]
+    host_rows = [[None] * L for _ in range(nb)]
+    ws = torch.empty(lava.lava_window_scores_workspace_bytes(desc, nb, tok), dtype=torch.uint8, device=dev)
+    for l in range(L):
+        inps = [synth.gen_layer(synth.config(5, n=n, budget=Hkv * w), 7000 + 100 * l + b) for b, n in enumerate(lens)]
+        q = torch.cat([lava.to_device(i.q_win, "bf16").reshape(-1) for i in inps])
+        k_dev[l] = torch.cat([lava.to_device(i.k, "bf16").reshape(-1, d) for i in inps])
+        v_dev[l] = torch.cat([lava.to_device(i.v, "bf16").reshape(-1, d) for i in inps])
+        e_l = torch.empty(nb, dtype=torch.float32, device=dev)
+        lava.lava_window_scores(desc, lens, q, k_dev[l], v_dev[l], scores=scores[l], layer_stat=e_l, workspace=ws)
+        stat[:, l] = e_l
+        for b, inp in enumerate(inps):
+            qq, kk, vv = inp.f64()
+            ref_scores[b][l], _ = O.lava_scores(qq, kk, vv, w, 7)
+            ref_e[b, l] = O.layer_entropy(ref_scores[b][l])
+            host_rows[b][l] = (inp.k, inp.v)
+        say(f"   layer {l}: generated, scored on the GPU and by the oracle")
+    torch.cuda.synchronize()
+    e_host = stat.cpu().numpy()
+    for b in range(nb):
+        for l in range(L):
+            assert abs(float(e_host[b, l]) - ref_e[b, l]) <= 1e-4 * ref_e[b, l] + 2e-5 / ref_scores[b][l].size, (b, l)
+
+    total_t = torch.tensor(totals, dtype=torch.int64, device=dev)
+    lo = torch.full((nb, L), Hkv * w, dtype=torch.int64, device=dev)
+    hi = torch.tensor([[Hkv * n] * L for n in lens], dtype=torch.int64, device=dev)
+    budgets = lava.lava_layer_budgets(stat, total_t, lo, hi)
+    cap = [min(totals[b], Hkv * lens[b]) for b in range(nb)]
+    counts = torch.empty(nb, L, Hkv, dtype=torch.int32, device=dev)
+    offs = torch.empty(nb, L, Hkv + 1, dtype=torch.int64, device=dev)
+    idx = [[torch.full((cap[b] + 4,), -7, dtype=torch.int32, device=dev) for _ in range(L)] for b in range(nb)]
+    k_hat = [[torch.full((cap[b] + 1, d), 3.0, dtype=torch.bfloat16, device=dev) for _ in range(L)] for b in range(nb)]
+    v_hat = [[torch.full((cap[b] + 1, d), 3.0, dtype=torch.bfloat16, device=dev) for _ in range(L)] for b in range(nb)]
+    err = torch.zeros(1, dtype=torch.int32, device=dev)
+    sel, cmp = [], []
+    for b, n in enumerate(lens):
+        a0, a1 = int(starts[b]) * Hkv, int(starts[b + 1]) * Hkv
+        for l in range(L):
+            sel.append(lava.select_problem(scores[l][a0:a1], cap[b], counts[b, l], offs[b, l], idx[b][l],
+                                           budget_dev=budgets[b, l: l + 1], error_dev=err))
+            cmp.append(lava.compact_problem(desc, n, k_dev[l][a0:a1], v_dev[l][a0:a1], offs[b, l], idx[b][l], cap[b],
+                                            k_hat[b][l], v_hat[b][l]))
+    lava.lava_select_topk_batch(Hkv, sel, Hkv * max(lens))
+    lava.lava_compact_batch(desc, cmp)
+    torch.cuda.synchronize()
+    assert int(err[0]) == 0
+    got_budgets = budgets.cpu().numpy()
+    s_host = scores.cpu().numpy()
+    counts_h, offs_h = counts.cpu().numpy(), offs.cpu().numpy()
+    least, worst_delta = 1.0, 0
+    for b, n in enumerate(lens):
+        want = O.layer_budgets(ref_e[b], totals[b], [Hkv * w] * L, [Hkv * n] * L)
+        assert int(got_budgets[b].sum()) == totals[b] == sum(want)
+        assert np.all(got_budgets[b] >= Hkv * w) and np.all(got_budgets[b] <= Hkv * n)
+        worst_delta = max(worst_delta, int(np.abs(got_budgets[b] - np.asarray(want)).max()))
+        # the same allocation rule on the statistics the GPU produced: exact
+        assert got_budgets[b].tolist() == O.layer_budgets(e_host[b].astype(np.float64), totals[b], [Hkv * w] * L,
+                                                          [Hkv * n] * L)
+        uniform = (np.arange(Hkv + 1) * n).astype(np.int64)
+        a0, a1 = int(starts[b]) * Hkv, int(starts[b + 1]) * Hkv
+        for l in range(L):
+            B_gpu, B_ref = int(got_budgets[b, l]), int(want[l])
+            got = s_host[l][a0:a1].reshape(Hkv, n)
+            assert np.all(np.isposinf(got[:, n - w:]))
+            mask = ref_scores[b][l] > 1e-30 * ref_scores[b][l].max()
+            rel = np.abs(got[:, : n - w].astype(np.float64)[mask] - ref_scores[b][l][mask]) / ref_scores[b][l][mask]
+            assert rel.max() < 1e-3, (b, l, rel.max())
+            rc, ro, ri, _ = O.select_topk(got.astype(np.float64).ravel(), uniform, B_gpu)
+            i_h = idx[b][l].cpu().numpy()
+            assert np.array_equal(counts_h[b, l], rc) and np.array_equal(offs_h[b, l], ro), (b, l)
+            assert np.array_equal(i_h[:B_gpu], ri) and np.all(i_h[cap[b]:] == -7), (b, l)
+            assert np.all(rc >= w) and rc.sum() == B_gpu                     # Eq. 1
+            oc, oo, oi, _ = O.select_topk(O.flat_layer_scores(ref_scores[b][l], n).ravel(), uniform, B_ref)
+            mine = set(int(g * n + p) for g in range(Hkv) for p in ri[ro[g]:ro[g + 1]])
+            theirs = set(int(g * n + p) for g in range(Hkv) for p in oi[oo[g]:oo[g + 1]])
+            least = min(least, len(mine & theirs) / min(B_gpu, B_ref))
+            kk, vv = host_rows[b][l]
+            assert np.array_equal(lava.to_host_bits(k_hat[b][l][:B_gpu]), O.compact(kk, ro, ri)), (b, l)
+            assert np.array_equal(lava.to_host_bits(v_hat[b][l][:B_gpu]), O.compact(vv, ro, ri)), (b, l)
+            assert bool((k_hat[b][l][B_gpu:] == 3.0).all()), (b, l)
+    say(f"   budgets vs the oracle's: max |difference| {worst_delta}; least kept-set overlap {least:.5f}")
+    assert worst_delta <= 1 and least >= 0.999
+
+
 def test_tables_with_device_side_offsets(lava):
     """Problems whose data sit back to back in shared buffers at offsets only the device knows (the layout
     of the cascade's pools): selection reads / writes at the offsets, compaction gathers from and to them."""

@@ -96,6 +96,8 @@ CASES = [
     (16, 2, 128, "bf16", [2100, 1], 33),        # G = 8
     (28, 4, 128, "bf16", [3000], 0),            # G = 7
     (2, 2, 128, "bf16", [1, 2, 0], 0),          # single rows; an empty sequence
+    (64, 64, 64, "bf16", [4000, 333], 2),       # 64 KV heads (MHA): the largest head count the step takes
+    (128, 64, 128, "bf16", [2500], 0),          # 64 KV heads, G = 2
 ]
 
 

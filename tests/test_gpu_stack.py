@@ -133,13 +133,28 @@ def test_config3_full_stack_cascade_equals_single_shot_equals_oracle(lava):
         assert np.array_equal(offs_host[l], r_offs), l
         a = int(st[l])
         assert np.array_equal(pos_host[a: a + int(r_offs[-1])], r_pos), l
-        for g in (0, Hkv - 1):                                                # rows: bit copies (two heads per layer)
+        for g in range(Hkv):                                                  # rows: bit copies, every head
             lo_g, hi_g = a + int(r_offs[g]), a + int(r_offs[g + 1])
             assert np.array_equal(kh[lo_g:hi_g], k_host[l][g][r_pos[r_offs[g]: r_offs[g + 1]]]), (l, g)
             assert np.array_equal(vh[lo_g:hi_g], v_host[l][g][r_pos[r_offs[g]: r_offs[g + 1]]]), (l, g)
-        # kept-set overlap with a selection on the oracle's own scores
-        rc, ro, ri, _ = O.select_topk(O.flat_layer_scores(ref_scores[l], N).ravel(),
-                                      (np.arange(Hkv + 1) * N).astype(np.int64), int(single_budgets[l]))
+    # ---- from scratch: the oracle's own statistics, its own budgets, its own selections.  Nothing the
+    # GPU computed enters the expected values below.  Budgets may differ by one unit per layer (the GPU's
+    # statistics carry fp32 rounding, and a quota can sit on a rounding boundary); the kept sets are
+    # compared at the oracle's budgets.
+    oracle_budgets = O.layer_budgets(ref_e, total, [Hkv * w] * L, [dense] * L)
+    assert sum(oracle_budgets) == total
+    delta = np.abs(np.asarray(oracle_budgets) - single_budgets)
+    say(f"   budgets from the oracle's statistics: max |difference| {int(delta.max())}")
+    assert delta.max() <= 1
+    uniform = (np.arange(Hkv + 1) * N).astype(np.int64)
+    least = 1.0
+    for l in range(L):
+        r_offs, r_pos, _ = ref_state[l]
+        rc, ro, ri, _ = O.select_topk(O.flat_layer_scores(ref_scores[l], N).ravel(), uniform, int(oracle_budgets[l]))
         mine = set(int(g * N + p) for g in range(Hkv) for p in r_pos[r_offs[g]: r_offs[g + 1]])
         theirs = set(int(g * N + p) for g in range(Hkv) for p in ri[ro[g]: ro[g + 1]])
-        assert len(mine & theirs) >= 0.999 * int(single_budgets[l]), l
+        b_min = min(int(oracle_budgets[l]), int(single_budgets[l]))
+        least = min(least, len(mine & theirs) / b_min)
+        assert len(mine & theirs) >= 0.999 * b_min, l
+        assert np.all(np.diff(r_offs) >= w)                                   # Eq. 1: the window is always kept
+    say(f"   least kept-set overlap with the oracle's own selection: {least:.5f}")

@@ -56,10 +56,10 @@ TOKEN_NORM_CASES = [
 
 
 @pytest.mark.parametrize("name,sh,shape", TOKEN_NORM_CASES, ids=[c[0] for c in TOKEN_NORM_CASES])
-def test_token_norm_score(lava, name, sh, shape, monkeypatch):
+def test_token_norm_score(lava, name, sh, shape, tuning):
     say(f"variant: per-token value-norm score, {name}")
     if shape:
-        monkeypatch.setenv("LAVA_SWEEP_SHAPE", shape)
+        tuning(sweep_shape=shape)
     inp = synth.gen_layer(sh, 6)
     desc = lava.LayerDesc.make(sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.window, sh.dtype,
                                pool_kernel=sh.pool_kernel, score_kind=lava.LAVA_SCORE_TOKEN_NORM)

@@ -450,6 +450,42 @@ def test_cascade_equals_single_shot():
         assert all(b2 <= b1 + 1 for b1, b2 in zip(seq, seq[1:]))
 
 
+def test_cascade_with_given_statistics():
+    """cascade(entropies=...) allocates from the statistics it is handed and is otherwise the same
+    algorithm: handed its own statistics it reproduces the plain run; handed constant weights it
+    reproduces the uniform split (every step: total / layers so far, up to rounding), and the final
+    state is again a single top-k per layer with the tightest budget of the layer's history; the
+    scores' own entropies play no role then (scaling a layer's scores changes nothing)."""
+    Hkv, n, w, L, total = 3, 50, 4, 4, 4 * 3 * 10
+    layers = []
+    for l in range(L):
+        s = synth.random_scores(Hkv, n - w, 70 + l, plateau=2).astype(np.float64)
+        layers.append(O.flat_layer_scores(s, n))
+    own = [O.layer_entropy(x[:, : n - w]) for x in layers]
+    plain_state, plain_hist = O.cascade(layers, n, total, w)
+    given_state, given_hist = O.cascade(layers, n, total, w, entropies=own)
+    assert plain_hist == given_hist
+    for a, b in zip(plain_state, given_state):
+        assert all(np.array_equal(x, y) for x, y in zip(a, b))
+    const_state, const_hist = O.cascade(layers, n, total, w, entropies=[0.25] * L)
+    for l, h in enumerate(const_hist):
+        assert sum(h) == total and max(h) - min(h) <= 1 and len(h) == l + 1
+        assert h == sorted(h, reverse=True)                   # leftover units go to the lower layers first
+    scaled = [x * (3.0 ** l) for l, x in enumerate(layers)]
+    scaled_state, scaled_hist = O.cascade(scaled, n, total, w, entropies=[0.25] * L)
+    assert scaled_hist == const_hist
+    for l in range(L):
+        tightest = min(h[l] for h in const_hist[l:])
+        _, offs, idx, kept = O.select_topk(layers[l].ravel(), _offsets(Hkv, n), tightest)
+        assert np.array_equal(const_state[l][0], offs) and np.array_equal(const_state[l][1], idx)
+        assert np.array_equal(const_state[l][2], kept)
+        assert np.array_equal(scaled_state[l][1], idx)        # same positions: a positive factor keeps the order
+    # a skewed hand-made statistic: budgets follow it in proportion (exact here: 120 * 1/8, 1/8, 2/8, 4/8)
+    skew_state, skew_hist = O.cascade(layers, n, total, w, entropies=[1.0, 1.0, 2.0, 4.0])
+    assert skew_hist[-1] == [15, 15, 30, 60]
+    assert [int(st[0][-1]) for st in skew_state] == [15, 15, 30, 60]
+
+
 # ----------------------------------------------------------------- numbers the paper prints (App. D)
 def test_paper_cost_model_numbers():
     vals = {}
