@@ -14,7 +14,9 @@ import numpy as np
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "liblava.so")
+# LAVA_LIBRARY names another build of the same library (the host-sanitizer build of build.py --sanitize);
+# it is read by this binding only, never by the library itself
+LIB_PATH = os.environ.get("LAVA_LIBRARY") or os.path.join(_HERE, "liblava.so")
 
 LAVA_OK, LAVA_ERR_INVALID_ARG, LAVA_ERR_SHAPE, LAVA_ERR_BUDGET, LAVA_ERR_WORKSPACE, LAVA_ERR_HIP = range(6)
 LAVA_F32, LAVA_BF16 = 0, 1
