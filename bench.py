@@ -40,6 +40,8 @@ def parse():
     ap.add_argument("--workload", default="cfg4", choices=["cfg1", "cfg2", "cfg3", "cfg4", "cfg5"])
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--sets", type=int, default=0, help="distinct K/V buffer sets (0 = enough for >= 1.5 GiB)")
+    ap.add_argument("--sweep-schedule", default="auto", choices=["auto", "separate", "persistent"],
+                    help="lava_tuning.sweep_schedule for the whole run (A/B of the two key-sweep schedules)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode-attention leg")
@@ -396,6 +398,7 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
+    lava.set_tuning(sweep_schedule=args.sweep_schedule)
 
     if args.workload == "cfg3":
         print(json.dumps(layer_stack(lava, synth, torch, np, dev, args)), flush=True)

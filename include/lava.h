@@ -93,11 +93,15 @@ typedef struct lava_tuning {
   int32_t sweep_shape;          /* 0 library's choice, 1 wide (one workgroup per compute unit),
                                    2 narrow (two per compute unit), where the kernels have both */
   int32_t sweep_workgroups;     /* workgroups a sweep launch aims for, 1..65536                */
-  int32_t sweep_schedule;       /* 0 library's choice, 1 separate statistics and score launches,
-                                   2 one persistent launch for both where the shape allows it   */
+  int32_t sweep_schedule;       /* 0 library's choice (today: 1), 1 separate statistics and score
+                                   launches, 2 one persistent launch for both where the shape
+                                   allows it (bit-identical results)                            */
   int32_t decode_rows_per_unit; /* rows of one head per decode work unit, 128..8192            */
   int32_t barrier_spin_limit;   /* polls of a grid-wide wait before it gives up (default 2^18) */
-  int32_t reserved[3];          /* must be zero                                                */
+  int32_t sweep_orphan_units;   /* testing aid for the persistent sweep: the owners leave every n-th
+                                   statistics unit unclaimed, as if their workgroup were not resident,
+                                   so that a workgroup waiting for that head has to run it; 0 = none */
+  int32_t reserved[2];          /* must be zero                                                */
 } lava_tuning;
 int32_t lava_set_tuning(const lava_tuning* tuning);
 int32_t lava_get_tuning(lava_tuning* tuning);

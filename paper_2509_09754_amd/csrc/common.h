@@ -15,6 +15,7 @@ enum KernelId : int {
   KID_VNORM = 0,      // value-row L1 norms, per-block maxima
   KID_STATS,          // window softmax statistics (row max, row sum) per block
   KID_SCORES,         // window scores: group-max of window-mean attention
+  KID_SWEEP,          // statistics and scores of a layer in one persistent launch
   KID_POOLSTAT,       // max-pool, value factor, +inf window entries, entropy statistic
   KID_SEL_INIT,       // selection: clear histograms and counters
   KID_SEL_FUSED,      // selection: radix select + ordered write in one launch
@@ -99,6 +100,7 @@ struct SweepSeq {
   int tiles_per_block;
   int vnorm_blocks;          // value-norm partials per KV head the scores kernel finds
   int vnorm_tiles_per_block;
+  int unit_base;             // persistent launch: work units of the sequences before this one (H_kv * blocks_x each)
 };
 
 struct SweepArgs {
@@ -116,6 +118,10 @@ struct SweepArgs {
   float c2;
   int first_seq;             // index in the batch of s[0]
   int n_seq;
+  int n_units;               // persistent launch: H_kv * sum of blocks_x over the table
+  unsigned int spin_limit;   // persistent launch: polls of a wait for other workgroups before it gives up
+  unsigned int help_after;   // persistent launch: polls after which a waiting workgroup looks for unclaimed units (>= 1)
+  int orphan_mod;            // persistent launch, testing aid: owners leave every orphan_mod-th statistics unit unclaimed (0: none)
   SweepSeq s[kMaxSeqPerLaunch];
 };
 
@@ -125,6 +131,8 @@ int32_t launch_vnorm(const lava_layer_desc& d, const SweepArgs& a, int max_vnorm
 int32_t launch_unit_vnorm(const lava_layer_desc& d, const SweepArgs& a, int max_vnorm_blocks, hipStream_t s);
 int32_t launch_stats(const lava_layer_desc& d, const SweepArgs& a, int max_blocks_x, const SweepPlan& p,
                      hipStream_t s);
+// statistics and scores in one persistent launch (all heads of a group in one workgroup, no caller LSE)
+int32_t launch_sweep(const lava_layer_desc& d, const SweepArgs& a, const SweepPlan& p, hipStream_t s);
 // not fused (a group split into chunks): one sequence per launch, raw scores to the region's s_raw
 int32_t launch_scores(const lava_layer_desc& d, const SweepArgs& a, int max_blocks_x, const SweepPlan& p,
                       hipStream_t s);

@@ -28,6 +28,10 @@ namespace lava {
 
 // "last workgroup done" tickets in the workspace (zeroed by the first kernel of every call)
 constexpr int kCounterPool = 0;                         // poolstat: one two-level ticket
+// control words of the persistent sweep, behind the ticket (a sequence's counter region)
+constexpr int kCtlError = kArriveWords;                 // a wait for other workgroups gave up (first sequence's region)
+constexpr int kCtlDoneA = kArriveWords + 1;             // [64] statistics units completed, per KV head of the sequence
+constexpr int kCtlUnitA = kCtlDoneA + 64;               // [H_kv * blocks_x] claim word of every statistics unit of the sequence
 
 // Wavefronts per workgroup and ring depth.  Kernels whose registers fit twice into a SIMD come in two
 // shapes.  Wide (W = 8): 8 wavefronts (2 per SIMD: one wavefront's exponentials overlap the
@@ -62,7 +66,7 @@ __device__ __forceinline__ void entropy_finish(double acc_s, double acc_t, doubl
                                                uint32_t* __restrict__ counters, unsigned int n_blocks,
                                                unsigned int block_id, double n_entries,
                                                float* __restrict__ layer_stat, double* s_s, double* s_t,
-                                               unsigned int* s_last) {
+                                               unsigned int* s_last, const uint32_t* error_word = nullptr) {
   constexpr int kW = THREADS / 64;
   for (int off = 32; off > 0; off >>= 1) {
     acc_s += __shfl_xor(acc_s, off);
@@ -96,80 +100,36 @@ __device__ __forceinline__ void entropy_finish(double acc_s, double acc_t, doubl
   for (int i = 0; i < kW; ++i) { S += s_s[i]; Tt += s_t[i]; }
   double e = 0.0;
   if (S > 0.0) e = (log(S) - Tt / S) / n_entries;
+  if (error_word != nullptr && ld_dev(error_word) != 0u) e = (double)NAN;   // scores of this call are not to be used
   layer_stat[0] = (float)e;
 }
 
-// ------------------------------------------------------------------------------------------
-// stats: per workgroup and per (head of the chunk, window row) the running maximum of the raw
-// dot products and sum of exp2((dot - max) * c2) over the workgroup's keys, c2 = scale * log2 e.
-// Row r may see keys 0 .. n - w + r only (each window row is normalised over the keys up to
-// and including its own position).
-// ------------------------------------------------------------------------------------------
-template <int DT, int D, int GT, int W>
-__global__ void __launch_bounds__((Shape<DT, D, W>::kThreads), (Shape<DT, D, W>::kMinWaves))
-stats_kernel(const SweepArgs a) {
+// The statistics sweep of one wavefront: tiles first, first + WAVES, ... (cnt of them) of the head
+// at kg, whose first STAGES - 1 tiles have already been requested into `ring`.  Returns, per head of
+// the chunk, this lane's running maximum of the raw dot products of its query row (lane % 32) and
+// the sum of exp2((dot - max) * c2) over the keys this lane saw (the two lane halves see different
+// keys of the same rows).  The assignment of tiles to wavefronts is static: the sums depend on the
+// order, and results must not depend on timing.
+template <int DT, int D, int GT, int WAVES, int STAGES>
+__device__ __forceinline__ void stats_tiles(const TileDma<DT, D>& dma, const FragReader<DT, D>& frags,
+                                            const char* __restrict__ kg, long long n, int w, float c2,
+                                            long long first, int cnt, u32x4* ring,
+                                            const u32x4 (&qf)[GT][Tile<DT, D>::kSteps], int lane,
+                                            float (&m_run)[GT], float (&z_run)[GT]) {
   using T = Tile<DT, D>;
-  const SweepSeq sq = a.s[blockIdx.z];
-  if (blockIdx.x >= (unsigned int)sq.blocks_x) return;
-  const long long n = sq.n;
-  const int w = a.w, G = a.G, n_chunks = a.n_chunks, tiles_per_block = sq.tiles_per_block;
-  const float c2 = a.c2;
-  const u32x4* __restrict__ q_win =
-      static_cast<const u32x4*>(a.q_win) + (long long)(a.first_seq + blockIdx.z) * a.H * w * T::kCpr;
-  const u32x4* __restrict__ k = static_cast<const u32x4*>(a.k) + (long long)a.H_kv * sq.tok * T::kCpr;
-  float2* __restrict__ stat_part = reinterpret_cast<float2*>(a.ws + sq.ws_off + a.off_stat_part);
-  constexpr int kWaves = Shape<DT, D, W>::kWaves;
-  constexpr int kStages = Shape<DT, D, W>::kStages;
-  __shared__ u32x4 s_tile[kWaves][kStages][T::kTileChunks];
-  __shared__ float2 s_red[kWaves][kMaxChunkHeads * 32];   // [wave][head*32+row]
-
-  const int lane = threadIdx.x & 63, wave = wave_index();
-  const int g = blockIdx.y / n_chunks, chunk = blockIdx.y % n_chunks;
-  const int h0 = g * G + chunk * GT;
-  const int nh = (G - chunk * GT) < GT ? (G - chunk * GT) : GT;
-  const char* kg = reinterpret_cast<const char*>(k) + (long long)g * n * T::kRowBytes;
-
-  TileDma<DT, D> dma;
-  dma.init(lane);
-  FragReader<DT, D> frags;
-  frags.init(lane);
-
-  const long long n_tiles = (n + kTileKeys - 1) / kTileKeys;
-  const long long t_begin = (long long)blockIdx.x * tiles_per_block;
-  long long t_end = t_begin + tiles_per_block;
-  if (t_end > n_tiles) t_end = n_tiles;
-
-  float m_run[GT], z_run[GT];
 #pragma unroll
   for (int t = 0; t < GT; ++t) { m_run[t] = -INFINITY; z_run[t] = 0.0f; }
-
   const int r = lane & 31, half = lane >> 5;
-
-  // this wavefront's tiles: t_begin + wave, + kWaves, ...; ring of kStages buffers, kStages-1 tiles ahead
-  const long long first = t_begin + wave;
-  const int cnt = first < t_end ? (int)((t_end - first + kWaves - 1) / kWaves) : 0;
-  u32x4* ring = s_tile[wave][0];
   const unsigned int ring_addr = lds_addr(ring);
-#pragma unroll
-  for (int p = 0; p < kStages - 1; ++p)
-    if (p < cnt) dma.issue(kg, first + (long long)p * kWaves, n, lane, ring + p * T::kTileChunks);
-  // Every wavefront fetches its own copy of the query rows, after its first tiles so that the two
-  // latencies overlap.  (Staging them once per workgroup through LDS, as the scores kernel does, was
-  // measured slower here: the wavefronts then leave the barrier in step and the sweep loses more
-  // than the set-up gains.)  Both are in before the loop: otherwise the compiler, which cannot count
-  // the ring's loads across iterations, waits for everything in flight before each tile's products.
-  u32x4 qf[GT][T::kSteps];
-  load_q<DT, D, GT>(q_win, h0, nh, w, lane, qf);
-  wait_vmcnt<0>();
   for (int it = 0; it < cnt; ++it) {
-    const long long tile = first + (long long)it * kWaves;
-    const int ahead = it + kStages - 1;
+    const long long tile = first + (long long)it * WAVES;
+    const int ahead = it + STAGES - 1;
     if (ahead < cnt)
-      dma.issue(kg, first + (long long)ahead * kWaves, n, lane, ring + (ahead % kStages) * T::kTileChunks);
-    const int younger = cnt - 1 - it < kStages - 1 ? cnt - 1 - it : kStages - 1;
+      dma.issue(kg, first + (long long)ahead * WAVES, n, lane, ring + (ahead % STAGES) * T::kTileChunks);
+    const int younger = cnt - 1 - it < STAGES - 1 ? cnt - 1 - it : STAGES - 1;
     wait_tile<DT, D>(younger);
     u32x4 kf[T::kSteps];
-    frags.read(ring_addr + (it % kStages) * T::kTileBytes, kf);
+    frags.read(ring_addr + (it % STAGES) * T::kTileBytes, kf);
 
     const long long key0 = tile * kTileKeys;
     if (key0 + kTileKeys - 1 <= n - w) {
@@ -218,8 +178,15 @@ stats_kernel(const SweepArgs a) {
       }
     }
   }
+}
 
-  // merge the two lane halves (same row, different keys), then the wavefronts
+// Merge of the two lane halves (same row, different keys), then of the wavefronts in wavefront order.
+// Thread (head * 32 + row) of the workgroup returns true and the merged (max, sum) of its row.
+// Contains a workgroup barrier.
+template <int GT, int WAVES>
+__device__ __forceinline__ bool stats_merge_waves(float (&m_run)[GT], float (&z_run)[GT], float c2, int lane, int wave,
+                                                  float2 (*s_red)[kMaxChunkHeads * 32], float2& out) {
+  const int r = lane & 31, half = lane >> 5;
 #pragma unroll
   for (int t = 0; t < GT; ++t) {
     const float m2 = __shfl_xor(m_run[t], 32);
@@ -228,15 +195,77 @@ stats_kernel(const SweepArgs a) {
     if (half == 0) s_red[wave][t * 32 + r] = make_float2(m_run[t], z_run[t]);
   }
   __syncthreads();
-  if (threadIdx.x < GT * 32) {
-    float m = -INFINITY, z = 0.0f;
+  if (threadIdx.x >= GT * 32) return false;
+  float m = -INFINITY, z = 0.0f;
 #pragma unroll
-    for (int wv = 0; wv < kWaves; ++wv) {
-      const float2 p = s_red[wv][threadIdx.x];
-      merge_stat(m, z, p.x, p.y, c2);
-    }
-    stat_part[((long long)blockIdx.y * sq.blocks_x + blockIdx.x) * (GT * 32) + threadIdx.x] = make_float2(m, z);
+  for (int wv = 0; wv < WAVES; ++wv) {
+    const float2 p = s_red[wv][threadIdx.x];
+    merge_stat(m, z, p.x, p.y, c2);
   }
+  out = make_float2(m, z);
+  return true;
+}
+
+// ------------------------------------------------------------------------------------------
+// stats: per workgroup and per (head of the chunk, window row) the running maximum of the raw
+// dot products and sum of exp2((dot - max) * c2) over the workgroup's keys, c2 = scale * log2 e.
+// Row r may see keys 0 .. n - w + r only (each window row is normalised over the keys up to
+// and including its own position).
+// ------------------------------------------------------------------------------------------
+template <int DT, int D, int GT, int W>
+__global__ void __launch_bounds__((Shape<DT, D, W>::kThreads), (Shape<DT, D, W>::kMinWaves))
+stats_kernel(const SweepArgs a) {
+  using T = Tile<DT, D>;
+  const SweepSeq sq = a.s[blockIdx.z];
+  if (blockIdx.x >= (unsigned int)sq.blocks_x) return;
+  const long long n = sq.n;
+  const int w = a.w, G = a.G, n_chunks = a.n_chunks, tiles_per_block = sq.tiles_per_block;
+  const float c2 = a.c2;
+  const u32x4* __restrict__ q_win =
+      static_cast<const u32x4*>(a.q_win) + (long long)(a.first_seq + blockIdx.z) * a.H * w * T::kCpr;
+  const u32x4* __restrict__ k = static_cast<const u32x4*>(a.k) + (long long)a.H_kv * sq.tok * T::kCpr;
+  float2* __restrict__ stat_part = reinterpret_cast<float2*>(a.ws + sq.ws_off + a.off_stat_part);
+  constexpr int kWaves = Shape<DT, D, W>::kWaves;
+  constexpr int kStages = Shape<DT, D, W>::kStages;
+  __shared__ u32x4 s_tile[kWaves][kStages][T::kTileChunks];
+  __shared__ float2 s_red[kWaves][kMaxChunkHeads * 32];   // [wave][head*32+row]
+
+  const int lane = threadIdx.x & 63, wave = wave_index();
+  const int g = blockIdx.y / n_chunks, chunk = blockIdx.y % n_chunks;
+  const int h0 = g * G + chunk * GT;
+  const int nh = (G - chunk * GT) < GT ? (G - chunk * GT) : GT;
+  const char* kg = reinterpret_cast<const char*>(k) + (long long)g * n * T::kRowBytes;
+
+  TileDma<DT, D> dma;
+  dma.init(lane);
+  FragReader<DT, D> frags;
+  frags.init(lane);
+
+  const long long n_tiles = (n + kTileKeys - 1) / kTileKeys;
+  const long long t_begin = (long long)blockIdx.x * tiles_per_block;
+  long long t_end = t_begin + tiles_per_block;
+  if (t_end > n_tiles) t_end = n_tiles;
+
+  // this wavefront's tiles: t_begin + wave, + kWaves, ...; ring of kStages buffers, kStages-1 tiles ahead
+  const long long first = t_begin + wave;
+  const int cnt = first < t_end ? (int)((t_end - first + kWaves - 1) / kWaves) : 0;
+  u32x4* ring = s_tile[wave][0];
+#pragma unroll
+  for (int p = 0; p < kStages - 1; ++p)
+    if (p < cnt) dma.issue(kg, first + (long long)p * kWaves, n, lane, ring + p * T::kTileChunks);
+  // Every wavefront fetches its own copy of the query rows, after its first tiles so that the two
+  // latencies overlap.  (Staging them once per workgroup through LDS, as the scores kernel does, was
+  // measured slower here: the wavefronts then leave the barrier in step and the sweep loses more
+  // than the set-up gains.)  Both are in before the loop: otherwise the compiler, which cannot count
+  // the ring's loads across iterations, waits for everything in flight before each tile's products.
+  u32x4 qf[GT][T::kSteps];
+  load_q<DT, D, GT>(q_win, h0, nh, w, lane, qf);
+  wait_vmcnt<0>();
+  float m_run[GT], z_run[GT];
+  stats_tiles<DT, D, GT, kWaves, kStages>(dma, frags, kg, n, w, c2, first, cnt, ring, qf, lane, m_run, z_run);
+  float2 mine;
+  if (stats_merge_waves<GT, kWaves>(m_run, z_run, c2, lane, wave, s_red, mine))
+    stat_part[((long long)blockIdx.y * sq.blocks_x + blockIdx.x) * (GT * 32) + threadIdx.x] = mine;
 }
 
 // ------------------------------------------------------------------------------------------
@@ -263,7 +292,258 @@ struct PoolArgs {
   float* layer_stat;         // [1]
   double2* ent_part;         // [workgroups]
   uint32_t* counters;
+  const uint32_t* error_word; // persistent launch: non-zero once a wait for other workgroups gave up (statistic -> NaN); else null
 };
+
+// Exponent bias of every (head, row) of a scores workgroup, step 1: thread (row, slice) merges its slice
+// of the head's statistics partials in workgroup order into s_merge[slice][row] (always the same fixed
+// order, independent loads: deterministic, no tickets).  DEVICE_SCOPE: the partials were written by
+// other workgroups of the SAME launch (device-scope stores), so they are read with device-scope loads.
+// `part` points at partial 0 of the head's (chunk's) rows.  The caller synchronises afterwards.
+template <int GT, int THREADS, bool DEVICE_SCOPE>
+__device__ __forceinline__ void merge_partials(const float2* __restrict__ part, int stat_blocks, bool have_lse,
+                                               float c2, float2* s_merge) {
+  constexpr int kRows = GT * 32;
+  constexpr int kSlices = THREADS / kRows;
+  const int row = threadIdx.x % kRows, slice = threadIdx.x / kRows;
+  float m = -INFINITY, z = 0.0f;
+  if (!have_lse) {
+    const int per = (stat_blocks + kSlices - 1) / kSlices;
+    const int b_begin = slice * per, b_end = (b_begin + per < stat_blocks) ? b_begin + per : stat_blocks;
+    const float2* p = part + row;
+    for (int b0 = b_begin; b0 < b_end; b0 += 16) {
+      float2 x[16];
+#pragma unroll
+      for (int u = 0; u < 16; ++u) {
+        if (b0 + u < b_end)
+          x[u] = DEVICE_SCOPE ? ld_dev_f2(&p[(long long)(b0 + u) * kRows]) : p[(long long)(b0 + u) * kRows];
+        else
+          x[u] = make_float2(-INFINITY, 0.0f);
+      }
+#pragma unroll
+      for (int u = 0; u < 16; ++u) merge_stat(m, z, x[u].x, x[u].y, c2);
+    }
+  }
+  s_merge[slice * kRows + row] = make_float2(m, z);
+}
+
+// Step 2: the slices are merged in slice order; bias = log2(row normaliser * w) in the exp2 domain,
+// +inf for padding rows (their exponentials vanish).
+template <int GT, int THREADS>
+__device__ __forceinline__ void write_bias(const float2* s_merge, const float* __restrict__ lse, int h0, int nh, int w,
+                                           float c2, float* s_bias) {
+  constexpr int kRows = GT * 32;
+  constexpr int kSlices = THREADS / kRows;
+  if (threadIdx.x < kRows) {
+    const int t = threadIdx.x >> 5, rr = threadIdx.x & 31;
+    float bias = INFINITY;
+    if (t < nh && rr < w) {
+      if (lse != nullptr) {
+        bias = lse[(long long)(h0 + t) * w + rr] * kLog2e;
+      } else {
+        float m = -INFINITY, z = 0.0f;
+#pragma unroll
+        for (int sl = 0; sl < kSlices; ++sl) {
+          const float2 x = s_merge[sl * kRows + threadIdx.x];
+          merge_stat(m, z, x.x, x.y, c2);
+        }
+        bias = m * c2 + log2f(z);
+      }
+      bias += log2f((float)w);
+    }
+    s_bias[threadIdx.x] = bias;
+  }
+}
+
+// The score sweep of one wavefront over the jobs of its workgroup: the workgroup's own tiles
+// t_begin .. t_end - 1, then (FUSED) the pooling halo, i.e. the tile before and the tile after the
+// span.  fifo[] holds the jobs this wavefront has already requested into its ring (the first
+// STAGES - 1 are fixed); the rest are taken from the shared counter *next_job as wavefronts become
+// free, because the wavefronts of a workgroup do not run at the same speed.  Which wavefront
+// computes a tile does not change its result, so the scores stay deterministic.
+// FUSED: raw scores go to s_span (position p of the prefix at s_span[p - (t_begin - 1) * 32]);
+// otherwise to raw_head[position] (atomic maximum when the group is split over workgroups).
+template <int DT, int D, int GT, int WAVES, int STAGES, bool FUSED>
+__device__ __forceinline__ void scores_tiles(const TileDma<DT, D>& dma, const FragReader<DT, D>& frags,
+                                             const char* __restrict__ kg, long long n, long long n_prefix, float c2,
+                                             long long t_begin, long long t_end, int n_own, bool halo_left,
+                                             bool halo_right, int n_jobs, int (&fifo)[STAGES], u32x4* ring,
+                                             unsigned int* next_job, const float* s_bias, float* s_span,
+                                             const u32x4 (&qf)[GT][Tile<DT, D>::kSteps], int lane,
+                                             float* __restrict__ raw_head, int n_chunks) {
+  using T = Tile<DT, D>;
+  auto job_tile = [&](int j) -> long long {
+    if (j < n_own) return t_begin + j;
+    return (j == n_own && halo_left) ? t_begin - 1 : t_end;
+  };
+  (void)halo_right;
+  const int half = lane >> 5;
+  const unsigned int ring_addr = lds_addr(ring);
+  const unsigned int next_job_addr = lds_addr(next_job);
+  // rows held by this lane in result register v: 8 * (v / 4) + 4 * half + v % 4 -> four float4 per head
+  const unsigned int bias_addr = lds_addr(s_bias) + half * 16;
+  const unsigned int span_base = lds_addr(s_span);
+
+  // The result of a tile is stored one iteration later, right after the next tile's arrival wait:
+  // the store then has a whole iteration to complete before a wait counts it among the older
+  // operations, instead of stalling every iteration on its acknowledgement.
+  float pend = 0.0f;
+  int pend_key = -1;                 // n < 2^31
+  auto store_result = [&](int key, float value) {
+    if (half == 0 && key >= 0 && key < n_prefix) {
+      float* dst = raw_head + key;
+      if (n_chunks == 1) {
+        *dst = value;
+      } else {   // heads of the group are split over workgroups: non-negative floats order as integers
+        atomicMax(reinterpret_cast<unsigned int*>(dst), __float_as_uint(value));
+      }
+    }
+  };
+  bool more = true;                                             // the counter has not run out yet
+  for (int it = 0; fifo[0] >= 0; ++it) {
+    const long long tile = job_tile(fifo[0]);
+    if (more) {
+      unsigned int j = 0;
+      if (lane == 0) j = lds_fetch_inc(next_job_addr);
+      j = __builtin_amdgcn_readfirstlane(j);
+      more = j < (unsigned int)n_jobs;
+      if (more) {
+        fifo[STAGES - 1] = (int)j;
+        dma.issue(kg, job_tile((int)j), n, lane, ring + ((it + STAGES - 1) % STAGES) * T::kTileChunks);
+      }
+    }
+    int younger = 0;
+#pragma unroll
+    for (int p = 1; p < STAGES; ++p) younger += fifo[p] >= 0 ? 1 : 0;
+    wait_tile<DT, D>(younger);
+#pragma unroll
+    for (int p = 0; p + 1 < STAGES; ++p) fifo[p] = fifo[p + 1];
+    fifo[STAGES - 1] = -1;
+    if constexpr (!FUSED) store_result(pend_key, pend);
+    u32x4 kf[T::kSteps];
+    frags.read(ring_addr + (it % STAGES) * T::kTileBytes, kf);
+
+    float best = 0.0f;
+    f32x16 acc = dot_tile<DT, D, false>(kf, qf[0]);
+#pragma unroll
+    for (int t = 0; t < GT; ++t) {
+      f32x16 nxt = acc;
+      if (t + 1 < GT) nxt = dot_tile<DT, D, false>(kf, qf[t + 1]);
+      float ps = 0.0f;
+      u32x4 bb[4];                       // biases of rows 8*jj + 4*half + 0..3 of head t
+      lds_read128x4_strided<32>(bias_addr + t * 128, bb[0], bb[1], bb[2], bb[3]);
+#pragma unroll
+      for (int jj = 0; jj < 4; ++jj) {
+        ps += fast_exp2(fmaf(acc[4 * jj + 0], c2, -__uint_as_float(bb[jj].x)));
+        ps += fast_exp2(fmaf(acc[4 * jj + 1], c2, -__uint_as_float(bb[jj].y)));
+        ps += fast_exp2(fmaf(acc[4 * jj + 2], c2, -__uint_as_float(bb[jj].z)));
+        ps += fast_exp2(fmaf(acc[4 * jj + 3], c2, -__uint_as_float(bb[jj].w)));
+      }
+      ps += __shfl_xor(ps, 32);
+      best = fmaxf(best, ps);
+      acc = nxt;
+    }
+    if constexpr (FUSED) {
+      // the lane's slot in the span is formed here from the lane counter instead of living in a register
+      // across the loop, which has none to spare
+      unsigned int l;
+      asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
+      if (l < 32u) lds_write32(span_base + (unsigned int)(tile - t_begin + 1) * (kTileKeys * 4) + l * 4u, best);
+    } else {
+      pend = best;
+      pend_key = (int)(tile * kTileKeys) + (lane & 31);
+    }
+  }
+  if constexpr (!FUSED) store_result(pend_key, pend);
+}
+
+// Finishes the scores of a workgroup's span from the raw scores in s_span (FUSED): Vbar of the head
+// (vb: this thread's share of the head's value-norm partials), max-pool over the prefix, the value
+// factor, +inf for the window entries, and the workgroup's share of the layer statistic; the last
+// workgroup of the sequence to arrive (block_id of n_blocks) forms e.  Contains workgroup barriers.
+template <int THREADS>
+__device__ __forceinline__ void scores_finish(const PoolArgs& pa, float vb, int g, long long n, long long n_prefix, int w,
+                                              long long t_begin, long long t_end, long long n_tiles,
+                                              const float* s_span, float* s_vb, double* s_s, double* s_t,
+                                              unsigned int* s_last, unsigned int n_blocks, unsigned int block_id,
+                                              int n_heads, bool writes_vbar, int wave) {
+  constexpr int kWaves = THREADS / 64;
+#pragma unroll
+  for (int off = 32; off > 0; off >>= 1) vb = fmaxf(vb, __shfl_xor(vb, off));
+  if ((threadIdx.x & 63) == 0) s_vb[wave] = vb;
+  lds_reads_done();                      // this wavefront's span entries are written
+  __syncthreads();                       // s_span complete, s_vb visible
+  vb = s_vb[0];
+#pragma unroll
+  for (int i = 1; i < kWaves; ++i) vb = fmaxf(vb, s_vb[i]);
+  if (writes_vbar && threadIdx.x == 0) pa.vbar[g] = vb;
+
+  const long long p_begin = t_begin * kTileKeys;
+  long long p_end = t_end * kTileKeys;
+  if (p_end > n_prefix) p_end = n_prefix;
+  const long long span0 = (t_begin - 1) * kTileKeys;      // position held by s_span[0]
+  // Eight consecutive positions per thread: 24 raw scores (positions base-8 .. base+15, six
+  // 128-bit reads) cover every tap of a pooling window of up to 15; positions outside the prefix
+  // do not take part in the maximum (the window is clipped, not padded).
+  double acc_s = 0.0, acc_t = 0.0;
+  constexpr int kPer = 8;
+  static_assert(kPoolMaxHalf <= kPer - 1, "taps must stay inside the 24 values read");
+  const float* out_head = pa.scores + (long long)g * n;
+  for (long long base = p_begin + (long long)threadIdx.x * kPer; base < p_end; base += (long long)THREADS * kPer) {
+    float raw[3 * kPer];
+    const float4* src = reinterpret_cast<const float4*>(&s_span[(int)(base - kPer - span0)]);
+#pragma unroll
+    for (int i = 0; i < 3 * kPer / 4; ++i) {
+      const float4 x = src[i];
+      raw[4 * i + 0] = x.x; raw[4 * i + 1] = x.y; raw[4 * i + 2] = x.z; raw[4 * i + 3] = x.w;
+    }
+#pragma unroll
+    for (int i = 0; i < 3 * kPer; ++i) {
+      const long long pos = base - kPer + i;
+      if (pos < 0 || pos >= n_prefix) raw[i] = -INFINITY;
+    }
+    float sc[kPer];
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) sc[j] = raw[kPer + j];
+#pragma unroll
+    for (int dd = 1; dd <= kPoolMaxHalf; ++dd) {
+      if (dd <= pa.pool_half) {                              // uniform
+#pragma unroll
+        for (int j = 0; j < kPer; ++j) sc[j] = fmaxf(sc[j], fmaxf(raw[kPer + j - dd], raw[kPer + j + dd]));
+      }
+    }
+    float fac[kPer];
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) fac[j] = vb;
+    if (pa.token_norm) {                                     // uniform
+#pragma unroll
+      for (int j = 0; j < kPer; ++j)
+        if (base + j < p_end) fac[j] = out_head[base + j];
+    }
+#pragma unroll
+    for (int j = 0; j < kPer; ++j) {
+      sc[j] *= fac[j];
+      if (base + j < p_end) {
+        acc_s += (double)sc[j];
+        if (sc[j] > 0.0f) acc_t += (double)sc[j] * (double)logf(sc[j]);
+      }
+    }
+    if (base + kPer <= p_end && (reinterpret_cast<uintptr_t>(out_head + base) & 15) == 0) {
+      float4* dst = reinterpret_cast<float4*>(const_cast<float*>(out_head) + base);
+      dst[0] = make_float4(sc[0], sc[1], sc[2], sc[3]);
+      dst[1] = make_float4(sc[4], sc[5], sc[6], sc[7]);
+    } else {
+#pragma unroll
+      for (int j = 0; j < kPer; ++j)
+        if (base + j < p_end) pa.scores[(long long)g * n + base + j] = sc[j];
+    }
+  }
+  // the workgroup that owns the head's last prefix tile also writes the window entries
+  if (t_begin < t_end && t_end == n_tiles && threadIdx.x < (unsigned)w)
+    pa.scores[(long long)g * n + n_prefix + threadIdx.x] = INFINITY;
+  entropy_finish<THREADS>(acc_s, acc_t, pa.ent_part, pa.counters, n_blocks, block_id,
+                          (double)n_heads * (double)n_prefix, pa.layer_stat, s_s, s_t, s_last, pa.error_word);
+}
 
 template <int DT, int D, int GT, bool FUSED, int W>
 __global__ void __launch_bounds__((Shape<DT, D, W>::kThreads), (Shape<DT, D, W>::kMinWaves))
@@ -292,6 +572,7 @@ scores_kernel(const SweepArgs a) {
   pa.layer_stat = a.layer_stat + seq;
   pa.ent_part = reinterpret_cast<double2*>(region + a.off_ent_part);
   pa.counters = reinterpret_cast<uint32_t*>(region + a.off_counter);
+  pa.error_word = nullptr;
   constexpr int kWaves = Shape<DT, D, W>::kWaves;
   constexpr int kStages = Shape<DT, D, W>::kStages;
   __shared__ u32x4 s_tile[kWaves][kStages][T::kTileChunks];
@@ -313,7 +594,6 @@ scores_kernel(const SweepArgs a) {
 
   constexpr int kThreads = Shape<DT, D, W>::kThreads;
   constexpr int kRows = GT * 32;
-  constexpr int kSlices = kThreads / kRows;
   __shared__ float2 s_merge[kThreads];
 
   // start the ring first: these loads only need the key pointer
@@ -340,7 +620,6 @@ scores_kernel(const SweepArgs a) {
   };
   __shared__ unsigned int s_next_job;
   if (threadIdx.x == 0) s_next_job = kWaves * (kStages - 1);   // published by the barriers below
-  const unsigned int next_job_addr = lds_addr(&s_next_job);
   int fifo[kStages];                                            // jobs requested and not yet computed; -1: none
 #pragma unroll
   for (int p = 0; p < kStages; ++p) {
@@ -348,7 +627,6 @@ scores_kernel(const SweepArgs a) {
     fifo[p] = (p < kStages - 1 && j < n_jobs) ? j : -1;
   }
   u32x4* ring = s_tile[wave][0];
-  const unsigned int ring_addr = lds_addr(ring);
 #pragma unroll
   for (int p = 0; p < kStages - 1; ++p)
     if (fifo[p] >= 0) dma.issue(kg, job_tile(fifo[p]), n, lane, ring + p * T::kTileChunks);
@@ -358,208 +636,288 @@ scores_kernel(const SweepArgs a) {
   static_assert(kWaves >= GT, "one staging buffer per head");
   stage_q<DT, D, GT, kThreads>(q_win, h0, nh, w, [&](int t) { return &s_tile[t][kStages - 1][0]; });
 
-  // exponent bias of every (head, row): log2 of (row normaliser * w), +inf for padding rows.
-  // Thread (row, slice) merges its slice of the workgroup partials in workgroup order, then the
-  // slices are merged in slice order.
-  {
-    const int row = threadIdx.x % kRows, slice = threadIdx.x / kRows;
-    float m = -INFINITY, z = 0.0f;
-    if (lse == nullptr) {
-      const int per = (stat_blocks + kSlices - 1) / kSlices;
-      const int b_begin = slice * per, b_end = (b_begin + per < stat_blocks) ? b_begin + per : stat_blocks;
-      const float2* part = stat_part + (long long)blockIdx.y * stat_blocks * kRows + row;
-      for (int b0 = b_begin; b0 < b_end; b0 += 16) {
-        float2 x[16];
-#pragma unroll
-        for (int u = 0; u < 16; ++u)
-          x[u] = (b0 + u < b_end) ? part[(long long)(b0 + u) * kRows] : make_float2(-INFINITY, 0.0f);
-#pragma unroll
-        for (int u = 0; u < 16; ++u) merge_stat(m, z, x[u].x, x[u].y, c2);
-      }
-    }
-    s_merge[slice * kRows + row] = make_float2(m, z);
-  }
+  // exponent bias of every (head, row), from the statistics partials or the caller's log-sum-exp
+  merge_partials<GT, kThreads, false>(stat_part + (long long)blockIdx.y * stat_blocks * kRows, stat_blocks,
+                                      lse != nullptr, c2, s_merge);
   __syncthreads();
-  if (threadIdx.x < kRows) {
-    const int t = threadIdx.x >> 5, rr = threadIdx.x & 31;
-    float bias = INFINITY;
-    if (t < nh && rr < w) {
-      if (lse != nullptr) {
-        bias = lse[(long long)(h0 + t) * w + rr] * kLog2e;
-      } else {
-        float m = -INFINITY, z = 0.0f;
-#pragma unroll
-        for (int sl = 0; sl < kSlices; ++sl) {
-          const float2 x = s_merge[sl * kRows + threadIdx.x];
-          merge_stat(m, z, x.x, x.y, c2);
-        }
-        bias = m * c2 + log2f(z);
-      }
-      bias += log2f((float)w);
-    }
-    s_bias[threadIdx.x] = bias;
-  }
+  write_bias<GT, kThreads>(s_merge, lse, h0, nh, w, c2, s_bias);
   u32x4 qf[GT][T::kSteps];
 #pragma unroll
   for (int t = 0; t < GT; ++t) frags.read(lds_addr(&s_tile[t][kStages - 1][0]), qf[t]);
   __syncthreads();
 
-  const int half = lane >> 5;
-  // rows held by this lane in result register v: 8 * (v / 4) + 4 * half + v % 4 -> four float4 per head
-  const unsigned int bias_addr = lds_addr(s_bias) + half * 16;
-  const unsigned int span_addr = lds_addr(s_span) + lane * 4;
-
-  // The result of a tile is stored one iteration later, right after the next tile's arrival wait:
-  // the store then has a whole iteration to complete before a wait counts it among the older
-  // operations, instead of stalling every iteration on its acknowledgement.
-  float pend = 0.0f;
-  int pend_key = -1;                 // n < 2^31
-  auto store_result = [&](int key, float value) {
-    if (half == 0 && key >= 0 && key < n_prefix) {
-      float* dst = s_raw + (long long)g * n_prefix + key;
-      if (n_chunks == 1) {
-        *dst = value;
-      } else {   // heads of the group are split over workgroups: non-negative floats order as integers
-        atomicMax(reinterpret_cast<unsigned int*>(dst), __float_as_uint(value));
-      }
-    }
-  };
-  bool more = true;                                             // the counter has not run out yet
-  for (int it = 0; fifo[0] >= 0; ++it) {
-    const long long tile = job_tile(fifo[0]);
-    if (more) {
-      unsigned int j = 0;
-      if (lane == 0) j = lds_fetch_inc(next_job_addr);
-      j = __builtin_amdgcn_readfirstlane(j);
-      more = j < (unsigned int)n_jobs;
-      if (more) {
-        fifo[kStages - 1] = (int)j;
-        dma.issue(kg, job_tile((int)j), n, lane, ring + ((it + kStages - 1) % kStages) * T::kTileChunks);
-      }
-    }
-    int younger = 0;
-#pragma unroll
-    for (int p = 1; p < kStages; ++p) younger += fifo[p] >= 0 ? 1 : 0;
-    wait_tile<DT, D>(younger);
-#pragma unroll
-    for (int p = 0; p + 1 < kStages; ++p) fifo[p] = fifo[p + 1];
-    fifo[kStages - 1] = -1;
-    if constexpr (!FUSED) store_result(pend_key, pend);
-    u32x4 kf[T::kSteps];
-    frags.read(ring_addr + (it % kStages) * T::kTileBytes, kf);
-
-    float best = 0.0f;
-    f32x16 acc = dot_tile<DT, D, false>(kf, qf[0]);
-#pragma unroll
-    for (int t = 0; t < GT; ++t) {
-      f32x16 nxt = acc;
-      if (t + 1 < GT) nxt = dot_tile<DT, D, false>(kf, qf[t + 1]);
-      float ps = 0.0f;
-      u32x4 bb[4];                       // biases of rows 8*jj + 4*half + 0..3 of head t
-      lds_read128x4_strided<32>(bias_addr + t * 128, bb[0], bb[1], bb[2], bb[3]);
-#pragma unroll
-      for (int jj = 0; jj < 4; ++jj) {
-        ps += fast_exp2(fmaf(acc[4 * jj + 0], c2, -__uint_as_float(bb[jj].x)));
-        ps += fast_exp2(fmaf(acc[4 * jj + 1], c2, -__uint_as_float(bb[jj].y)));
-        ps += fast_exp2(fmaf(acc[4 * jj + 2], c2, -__uint_as_float(bb[jj].z)));
-        ps += fast_exp2(fmaf(acc[4 * jj + 3], c2, -__uint_as_float(bb[jj].w)));
-      }
-      ps += __shfl_xor(ps, 32);
-      best = fmaxf(best, ps);
-      acc = nxt;
-    }
-    if constexpr (FUSED) {
-      if (half == 0) lds_write32(span_addr + (unsigned int)(tile - t_begin + 1) * (kTileKeys * 4), best);
-    } else {
-      pend = best;
-      pend_key = (int)(tile * kTileKeys) + (lane & 31);
-    }
-  }
-  if constexpr (!FUSED) {
-    store_result(pend_key, pend);
-  } else {
-    // ---- finish the scores of this span: Vbar, max-pool, +inf window entries, layer statistic
+  scores_tiles<DT, D, GT, kWaves, kStages, FUSED>(dma, frags, kg, n, n_prefix, c2, t_begin, t_end, n_own, halo_left,
+                                                  halo_right, n_jobs, fifo, ring, &s_next_job, s_bias, s_span,
+                                                  qf, lane, s_raw + (long long)g * n_prefix, n_chunks);
+  if constexpr (FUSED) {
     __shared__ float s_vb[kWaves];
     __shared__ double s_s[kWaves], s_t[kWaves];
     __shared__ unsigned int s_last;
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) vb = fmaxf(vb, __shfl_xor(vb, off));
-    if ((threadIdx.x & 63) == 0) s_vb[wave] = vb;
-    lds_reads_done();                      // this wavefront's span entries are written
-    __syncthreads();                       // s_span complete, s_vb visible
-    vb = s_vb[0];
-#pragma unroll
-    for (int i = 1; i < kWaves; ++i) vb = fmaxf(vb, s_vb[i]);
-    if (blockIdx.x == 0 && threadIdx.x == 0) pa.vbar[g] = vb;
+    scores_finish<kThreads>(pa, vb, g, n, n_prefix, w, t_begin, t_end, n_tiles, s_span, s_vb, s_s, s_t, &s_last,
+                            sq.blocks_x * gridDim.y, blockIdx.y * sq.blocks_x + blockIdx.x, (int)gridDim.y,
+                            blockIdx.x == 0, wave);
+  }
+}
 
-    const long long p_begin = t_begin * kTileKeys;
-    long long p_end = t_end * kTileKeys;
-    if (p_end > n_prefix) p_end = n_prefix;
-    const long long span0 = (t_begin - 1) * kTileKeys;      // position held by s_span[0]
-    // Eight consecutive positions per thread: 24 raw scores (positions base-8 .. base+15, six
-    // 128-bit reads) cover every tap of a pooling window of up to 15; positions outside the prefix
-    // do not take part in the maximum (the window is clipped, not padded).
-    double acc_s = 0.0, acc_t = 0.0;
-    constexpr int kPer = 8;
-    static_assert(kPoolMaxHalf <= kPer - 1, "taps must stay inside the 24 values read");
-    const float* out_head = pa.scores + (long long)g * n;
-    for (long long base = p_begin + (long long)threadIdx.x * kPer; base < p_end;
-         base += (long long)Shape<DT, D, W>::kThreads * kPer) {
-      float raw[3 * kPer];
-      const float4* src = reinterpret_cast<const float4*>(&s_span[(int)(base - kPer - span0)]);
-#pragma unroll
-      for (int i = 0; i < 3 * kPer / 4; ++i) {
-        const float4 x = src[i];
-        raw[4 * i + 0] = x.x; raw[4 * i + 1] = x.y; raw[4 * i + 2] = x.z; raw[4 * i + 3] = x.w;
-      }
-#pragma unroll
-      for (int i = 0; i < 3 * kPer; ++i) {
-        const long long pos = base - kPer + i;
-        if (pos < 0 || pos >= n_prefix) raw[i] = -INFINITY;
-      }
-      float sc[kPer];
-#pragma unroll
-      for (int j = 0; j < kPer; ++j) sc[j] = raw[kPer + j];
-#pragma unroll
-      for (int dd = 1; dd <= kPoolMaxHalf; ++dd) {
-        if (dd <= pa.pool_half) {                              // uniform
-#pragma unroll
-          for (int j = 0; j < kPer; ++j) sc[j] = fmaxf(sc[j], fmaxf(raw[kPer + j - dd], raw[kPer + j + dd]));
-        }
-      }
-      float fac[kPer];
-#pragma unroll
-      for (int j = 0; j < kPer; ++j) fac[j] = vb;
-      if (pa.token_norm) {                                     // uniform
-#pragma unroll
-        for (int j = 0; j < kPer; ++j)
-          if (base + j < p_end) fac[j] = out_head[base + j];
-      }
-#pragma unroll
-      for (int j = 0; j < kPer; ++j) {
-        sc[j] *= fac[j];
-        if (base + j < p_end) {
-          acc_s += (double)sc[j];
-          if (sc[j] > 0.0f) acc_t += (double)sc[j] * (double)logf(sc[j]);
-        }
-      }
-      if (base + kPer <= p_end && (reinterpret_cast<uintptr_t>(out_head + base) & 15) == 0) {
-        float4* dst = reinterpret_cast<float4*>(const_cast<float*>(out_head) + base);
-        dst[0] = make_float4(sc[0], sc[1], sc[2], sc[3]);
-        dst[1] = make_float4(sc[4], sc[5], sc[6], sc[7]);
-      } else {
-#pragma unroll
-        for (int j = 0; j < kPer; ++j)
-          if (base + j < p_end) pa.scores[(long long)g * n + base + j] = sc[j];
-      }
+// ------------------------------------------------------------------------------------------
+// sweep: statistics and scores of a launch's sequences in ONE persistent launch.
+//
+// Work units are (sequence, KV head, span of keys): the same spans the two separate kernels give
+// their workgroups.  Workgroup b of a grid of `grid` workgroups owns units b, b + grid, ... : it
+// first runs their statistics passes, then their score passes.  A score unit needs the statistics
+// of all spans of its head: it waits for the head's completion count.  So that this wait cannot
+// depend on the whole grid being resident, every statistics unit carries a claim word: its owner
+// claims it (a compare-and-swap on a word nobody else touches, in flight while the unit's first
+// tiles are requested), and a workgroup whose wait lasts long looks for unclaimed statistics units
+// of the head it waits for and runs them itself (it already holds that head's query rows).  A
+// claimed unit is being run by a resident workgroup that waits for nothing, so every wait ends.
+// (The waits are bounded all the same; one that gives up sets an error word and the layer
+// statistic becomes NaN.)
+// What the single launch saves over two: the query rows are fetched once, the second pass of a
+// head starts as soon as that head's statistics are complete instead of after the slowest
+// workgroup of the whole device, its first tiles are requested before the statistics are even
+// published, and there is no second launch.  Results are bit-identical to the separate kernels:
+// the same tiles are combined in the same order.
+// ------------------------------------------------------------------------------------------
+template <int DT, int D, int GT, int W>
+struct SweepSmem {
+  using T = Tile<DT, D>;
+  using S = Shape<DT, D, W>;
+  u32x4 tile[S::kWaves][S::kStages][T::kTileChunks];
+  __attribute__((aligned(16))) float bias[GT * 32];
+  union {
+    float2 red[S::kWaves][kMaxChunkHeads * 32];            // statistics units: per-wavefront results
+    struct {
+      float2 merge[S::kThreads];                           // score units: slices of the partial merge
+      __attribute__((aligned(16))) float span[(S::kFusedTiles + 2) * kTileKeys];   // raw scores of the span + halo
+    } sc;
+  };
+  float vb[S::kWaves];
+  double ss[S::kWaves], st[S::kWaves];
+  unsigned int last, next_job;
+  int claim[4];                                             // words handed from thread 0 to the workgroup
+};
+
+__device__ __forceinline__ void lds_write128(unsigned int a, const u32x4& x) {
+  asm volatile("ds_write_b128 %0, %1" : : "v"(a), "v"(x) : "memory");
+}
+
+template <int DT, int D, int GT, int W>
+__global__ void __launch_bounds__((Shape<DT, D, W>::kThreads), (Shape<DT, D, W>::kMinWaves))
+sweep_kernel(const SweepArgs a) {
+  using T = Tile<DT, D>;
+  using S = Shape<DT, D, W>;
+  constexpr int kWaves = S::kWaves, kStages = S::kStages, kThreads = S::kThreads, kRows = GT * 32;
+  static_assert(kWaves >= GT, "one staging buffer per head");
+  __shared__ SweepSmem<DT, D, GT, W> sm;
+  const int lane = threadIdx.x & 63, wave = wave_index();
+  const int w = a.w, G = a.G, H_kv = a.H_kv;
+  const float c2 = a.c2;
+  uint32_t* __restrict__ ctl0 = reinterpret_cast<uint32_t*>(a.ws + a.s[0].ws_off + a.off_counter);
+  TileDma<DT, D> dma;
+  dma.init(lane);
+  FragReader<DT, D> frags;
+  frags.init(lane);
+  u32x4* ring = sm.tile[wave][0];
+
+  // Query rows of (sequence si, head g), once per workgroup and unit.  The w rows of a head are one
+  // contiguous run of q_win, i.e. a key tile of w rows: wavefront t requests head t's rows straight into
+  // its idle last ring stage with the same direct-to-LDS loads (rows beyond the window repeat row w - 1,
+  // heads beyond the group repeat its last head: their results are never used), AHEAD of the unit's first
+  // key tiles, so that q_commit only waits for the older loads and the tiles stay in flight.
+  // (Keeping the rows in registers from one unit to the next costs more registers than the two
+  // passes leave.)  The workgroup is past a barrier since it last used those stages.
+  auto q_request = [&](int si, int g) {
+    if (wave < GT) {
+      const int nh = G < GT ? G : GT;
+      const int h = g * G + (wave < nh ? wave : nh - 1);
+      const char* rows = static_cast<const char*>(a.q_win) +
+                         ((long long)(a.first_seq + si) * a.H + h) * w * (long long)T::kRowBytes;
+      dma.issue_clamped(rows, 0, w, lane, ring + (kStages - 1) * T::kTileChunks);
     }
-    // the workgroup that owns the head's last prefix tile also writes the window entries
-    if (t_begin < t_end && t_end == n_tiles && threadIdx.x < (unsigned)w)
-      pa.scores[(long long)g * n + n_prefix + threadIdx.x] = INFINITY;
-    entropy_finish<Shape<DT, D, W>::kThreads>(acc_s, acc_t, pa.ent_part, pa.counters, sq.blocks_x * gridDim.y,
-                                           blockIdx.y * sq.blocks_x + blockIdx.x,
-                                           (double)gridDim.y * (double)n_prefix, pa.layer_stat, s_s, s_t,
-                                           &s_last);
+  };
+  // `younger`: key tiles this wavefront has requested since q_request
+  auto q_commit = [&](u32x4 (&qf)[GT][T::kSteps], int younger) {
+    if (wave < GT) wait_tile<DT, D>(younger);
+    __syncthreads();
+#pragma unroll
+    for (int t = 0; t < GT; ++t) frags.read(lds_addr(&sm.tile[t][kStages - 1][0]), qf[t]);
+    __syncthreads();
+  };
+  auto seq_of_unit = [&](int u) {
+    int si = 0;
+    while (si + 1 < a.n_seq && u >= a.s[si + 1].unit_base) ++si;
+    return si;
+  };
+
+  // The workgroup's own units: u_a walks its statistics units, then u_b its score units.  A score unit
+  // whose wait for its head's statistics lasts may hand a statistics unit of that head to the top of
+  // the loop (help_bx >= 0) and is set up again afterwards; there is one copy of each pass's code.
+  int u_a = (int)blockIdx.x, u_b = (int)blockIdx.x;
+  int help_si = 0, help_g = 0, help_bx = -1;
+  for (;;) {
+    // ------------------------------------------------------------ a statistics unit, if there is one to run
+    int si = 0, g = 0, bx = -1;
+    if (help_bx >= 0) {
+      si = help_si; g = help_g; bx = help_bx;
+      help_bx = -1;
+    } else if (u_a < a.n_units) {
+      const int u = u_a;
+      u_a += (int)gridDim.x;
+      // testing aid: every orphan_mod-th unit is left alone by its owner, as if the owner were not resident;
+      // somebody waiting for the unit's head has to run it (the helping path below)
+      if (a.orphan_mod != 0 && (u % a.orphan_mod) == 0) continue;
+      si = seq_of_unit(u);
+      const int rel = u - a.s[si].unit_base;
+      g = rel / a.s[si].blocks_x;
+      bx = rel % a.s[si].blocks_x;
+    }
+    if (bx >= 0) {
+      const SweepSeq sq = a.s[si];
+      const long long n = sq.n;
+      const char* kg = static_cast<const char*>(a.k) + ((long long)H_kv * sq.tok + (long long)g * n) * T::kRowBytes;
+      char* region = a.ws + sq.ws_off;
+      float2* __restrict__ stat_part = reinterpret_cast<float2*>(region + a.off_stat_part);
+      uint32_t* __restrict__ ctl = reinterpret_cast<uint32_t*>(region + a.off_counter);
+      const long long n_tiles = (n + kTileKeys - 1) / kTileKeys;
+      const long long t_begin = (long long)bx * sq.tiles_per_block;
+      long long t_end = t_begin + sq.tiles_per_block;
+      if (t_end > n_tiles) t_end = n_tiles;
+      const long long first = t_begin + wave;
+      const int cnt = first < t_end ? (int)((t_end - first + kWaves - 1) / kWaves) : 0;
+      // Exactly the statistics kernel's pass: every wavefront fetches its own copy of the query rows after
+      // its first tiles and enters the loop when both are in, without a workgroup barrier in front of
+      // the loop (one there costs the pass a fifth of its speed, measured).
+#pragma unroll
+      for (int p = 0; p < kStages - 1; ++p)
+        if (p < cnt) dma.issue(kg, first + (long long)p * kWaves, n, lane, ring + p * T::kTileChunks);
+      u32x4 qf[GT][T::kSteps];
+      load_q<DT, D, GT>(static_cast<const u32x4*>(a.q_win) + (long long)(a.first_seq + si) * a.H * w * T::kCpr, g * G,
+                        G < GT ? G : GT, w, lane, qf);
+      wait_vmcnt<0>();
+      float m_run[GT], z_run[GT];
+      stats_tiles<DT, D, GT, kWaves, kStages>(dma, frags, kg, n, w, c2, first, cnt, ring, qf, lane, m_run, z_run);
+      float2 mine;
+      if (stats_merge_waves<GT, kWaves>(m_run, z_run, c2, lane, wave, sm.red, mine))
+        st_dev_f2(&stat_part[((long long)g * sq.blocks_x + bx) * kRows + threadIdx.x], mine.x, mine.y);
+      // published: the partials are device-visible before the head's completion count moves.  The unit's
+      // word goes to "done" (2); should a helper and the owner both have run the unit (their partials are
+      // bit-identical), only the first to finish counts it.
+      drain_vmem();
+      __syncthreads();
+      if (threadIdx.x == 0) {
+        uint32_t* word = &ctl[kCtlUnitA + g * sq.blocks_x + bx];
+        if (__hip_atomic_exchange(word, 2u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 2u)
+          __hip_atomic_fetch_add(&ctl[kCtlDoneA + g], 1u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      continue;
+    }
+
+    // ------------------------------------------------------------ a score unit
+    if (u_b >= a.n_units) break;
+    si = seq_of_unit(u_b);
+    const SweepSeq sq = a.s[si];
+    const int rel = u_b - sq.unit_base;
+    g = rel / sq.blocks_x;
+    bx = rel % sq.blocks_x;
+    const int seq = a.first_seq + si;
+    const long long n = sq.n, n_prefix = n - w;
+    const char* kg = static_cast<const char*>(a.k) + ((long long)H_kv * sq.tok + (long long)g * n) * T::kRowBytes;
+    char* region = a.ws + sq.ws_off;
+    const float2* __restrict__ stat_part = reinterpret_cast<const float2*>(region + a.off_stat_part);
+    uint32_t* __restrict__ ctl = reinterpret_cast<uint32_t*>(region + a.off_counter);
+
+    const long long n_tiles = (n_prefix + kTileKeys - 1) / kTileKeys;
+    const long long t_begin = (long long)bx * sq.tiles_per_block;
+    long long t_end = t_begin + sq.tiles_per_block;
+    if (t_end > n_tiles) t_end = n_tiles;
+    const int n_own = t_begin < t_end ? (int)(t_end - t_begin) : 0;
+    const bool halo_left = n_own > 0 && t_begin > 0;
+    const bool halo_right = n_own > 0 && t_end < n_tiles;
+    const int n_jobs = n_own + (halo_left ? 1 : 0) + (halo_right ? 1 : 0);
+    auto job_tile = [&](int j) -> long long {
+      if (j < n_own) return t_begin + j;
+      return (j == n_own && halo_left) ? t_begin - 1 : t_end;
+    };
+    __syncthreads();                                   // every wavefront is done with the previous unit's LDS
+    // The unit's first tiles are requested before anything else, so that they travel while the head's
+    // statistics are awaited and merged.
+    q_request(si, g);
+    if (threadIdx.x == 0) sm.next_job = kWaves * (kStages - 1);   // published by the barriers below
+    int fifo[kStages];
+#pragma unroll
+    for (int p = 0; p < kStages; ++p) {
+      const int j = wave + p * kWaves;
+      fifo[p] = (p < kStages - 1 && j < n_jobs) ? j : -1;
+    }
+    int primed = 0;
+#pragma unroll
+    for (int p = 0; p < kStages - 1; ++p)
+      if (fifo[p] >= 0) {
+        dma.issue(kg, job_tile(fifo[p]), n, lane, ring + p * T::kTileChunks);
+        ++primed;
+      }
+    u32x4 qf[GT][T::kSteps];
+    q_commit(qf, primed);
+
+    // The head's statistics.  A wait that lasts looks for statistics units of this head nobody has
+    // claimed (their owners are not resident yet); one is then run above and this unit set up again.
+    if (threadIdx.x == 0) {
+      unsigned int spins = 0u;
+      int verdict = -1;                                // -1: complete (or gave up), else: span of the unit to run
+      while (ld_dev(&ctl[kCtlDoneA + g]) < (unsigned int)sq.blocks_x) {
+        __builtin_amdgcn_s_sleep(4);
+        ++spins;
+        if (spins > a.spin_limit) {
+          st_dev(&ctl0[kCtlError], 1u);
+          break;
+        }
+        if ((spins % a.help_after) == 0u) {
+          for (int x = 0; x < sq.blocks_x && verdict < 0; ++x) {
+            uint32_t* word = &ctl[kCtlUnitA + g * sq.blocks_x + x];
+            if (ld_dev(word) == 0u && atomicCAS(word, 0u, 1u) == 0u) verdict = x;
+          }
+          if (verdict >= 0) break;
+        }
+      }
+      sm.claim[0] = verdict;
+    }
+    __syncthreads();
+    help_bx = sm.claim[0];
+    __syncthreads();
+    if (help_bx >= 0) {
+      help_si = si;
+      help_g = g;
+      wait_vmcnt<0>();                                 // the tiles requested for this unit have landed; they are asked for again
+      __syncthreads();
+      continue;
+    }
+    PoolArgs pa;
+    pa.vnorm_part = reinterpret_cast<const float*>(region + a.off_vnorm_part);
+    pa.vnorm_blocks = sq.vnorm_blocks;
+    pa.pool_half = a.pool_half;
+    pa.scores = a.scores + (long long)H_kv * sq.tok;
+    pa.vbar = a.vbar + (long long)seq * H_kv;
+    pa.token_norm = a.token_norm;
+    pa.layer_stat = a.layer_stat + seq;
+    pa.ent_part = reinterpret_cast<double2*>(region + a.off_ent_part);
+    pa.counters = ctl;
+    pa.error_word = &ctl0[kCtlError];
+    float vb = 0.0f;   // this thread's share of the head's value-norm partials (an earlier launch wrote them)
+    for (int i = threadIdx.x; i < pa.vnorm_blocks; i += kThreads)
+      vb = fmaxf(vb, pa.vnorm_part[(long long)g * pa.vnorm_blocks + i]);
+    merge_partials<GT, kThreads, true>(stat_part + (long long)g * sq.blocks_x * kRows, sq.blocks_x, false, c2,
+                                       sm.sc.merge);
+    __syncthreads();
+    write_bias<GT, kThreads>(sm.sc.merge, nullptr, g * G, G < GT ? G : GT, w, c2, sm.bias);
+    __syncthreads();
+    scores_tiles<DT, D, GT, kWaves, kStages, true>(dma, frags, kg, n, n_prefix, c2, t_begin, t_end, n_own, halo_left,
+                                                   halo_right, n_jobs, fifo, ring, &sm.next_job, sm.bias, sm.sc.span,
+                                                   qf, lane, nullptr, 1);
+    scores_finish<kThreads>(pa, vb, g, n, n_prefix, w, t_begin, t_end, n_tiles, sm.sc.span, sm.vb, sm.ss, sm.st,
+                            &sm.last, (unsigned int)(sq.blocks_x * H_kv), (unsigned int)(g * sq.blocks_x + bx), H_kv,
+                            bx == 0, wave);
+    u_b += (int)gridDim.x;
   }
 }
 
@@ -607,7 +965,7 @@ vnorm_kernel(const SweepArgs a) {
   float* __restrict__ vnorm_part = reinterpret_cast<float*>(a.ws + sq.ws_off + a.off_vnorm_part);
   float* __restrict__ row_norm = a.scores + (long long)a.H_kv * sq.tok;
   uint32_t* __restrict__ counters = reinterpret_cast<uint32_t*>(a.ws + sq.ws_off + a.off_counter);
-  constexpr int n_counter_words = kArriveWords;
+  const int n_counter_words = kCtlUnitA + a.H_kv * sq.blocks_x;
   constexpr int kWaves = VShape<DT, D>::kWaves;
   constexpr int kStages = VShape<DT, D>::kStages < 2 ? 2 : VShape<DT, D>::kStages;
   __shared__ u32x4 s_tile[kWaves][kStages][T::kTileChunks];
@@ -828,7 +1186,7 @@ ScoreWorkspace make_score_workspace(const lava_layer_desc& d, int64_t n) {
                                 ? (size_t)pool_blocks(d, n) : (size_t)p.blocks_x_bound * p.n_chunks;
   off += align_up(sizeof(double2) * (size_t)d.n_kv_heads * ent_blocks);
   w.off_counter = off;
-  off += align_up(sizeof(uint32_t) * kArriveWords);
+  off += align_up(sizeof(uint32_t) * ((size_t)kCtlUnitA + (size_t)d.n_kv_heads * p.blocks_x_bound));
   w.bytes = off;
   return w;
 }
@@ -853,12 +1211,12 @@ __global__ void __launch_bounds__(256) unit_vnorm_kernel(const SweepArgs a) {
   uint32_t* counters = reinterpret_cast<uint32_t*>(a.ws + sq.ws_off + a.off_counter);
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i < a.H_kv * sq.vnorm_blocks) vnorm_part[i] = 1.0f;
-  if (i < kArriveWords) counters[i] = 0u;
+  for (int j = i; j < kCtlUnitA + a.H_kv * sq.blocks_x; j += (int)gridDim.x * 256) counters[j] = 0u;
 }
 
 int32_t launch_unit_vnorm(const lava_layer_desc& d, const SweepArgs& a, int max_vnorm_blocks, hipStream_t s) {
   const int n_part = d.n_kv_heads * max_vnorm_blocks;
-  const int n = n_part > kArriveWords ? n_part : kArriveWords;
+  const int n = n_part > kCtlUnitA ? n_part : kCtlUnitA;
   ProfScope ps(KID_VNORM, s);
   hipLaunchKernelGGL(unit_vnorm_kernel, dim3((n + 255) / 256, 1, a.n_seq), dim3(256), 0, s, a);
   return launch_status();
@@ -903,6 +1261,25 @@ int32_t launch_stats(const lava_layer_desc& d, const SweepArgs& a, int max_block
   LAVA_SWEEP_DISPATCH(LAVA_STATS);
 #undef LAVA_STATS
 #undef LAVA_STATS_W
+  return launch_status();
+}
+
+int32_t launch_sweep(const lava_layer_desc& d, const SweepArgs& a, const SweepPlan& p, hipStream_t s) {
+  if (!p.fused_pool || a.lse != nullptr) return LAVA_ERR_INVALID_ARG;
+  // persistent workgroups: as many as the device keeps resident for this shape, at most one per unit
+  const int slots = compute_units() * ((p.narrow && sweep_has_narrow_shape(d)) ? 2 : 1);
+  const dim3 grid(a.n_units < slots ? a.n_units : slots);
+  ProfScope ps(KID_SWEEP, s);
+#define LAVA_SWEEP_W(DTV, DV, GTV, WV) \
+  hipLaunchKernelGGL((sweep_kernel<DTV, DV, GTV, WV>), grid, dim3(Shape<DTV, DV, WV>::kThreads), 0, s, a)
+#define LAVA_SWEEP(DTV, DV, GTV)                                               \
+  do {                                                                         \
+    if (Shape<DTV, DV, 4>::kNarrow && p.narrow) LAVA_SWEEP_W(DTV, DV, GTV, (Shape<DTV, DV, 4>::kNarrow ? 4 : 8)); \
+    else LAVA_SWEEP_W(DTV, DV, GTV, 8);                                        \
+  } while (0)
+  LAVA_SWEEP_DISPATCH(LAVA_SWEEP);
+#undef LAVA_SWEEP
+#undef LAVA_SWEEP_W
   return launch_status();
 }
 

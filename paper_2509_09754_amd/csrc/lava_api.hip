@@ -19,7 +19,7 @@ struct ProfState {
 } g_prof;
 
 const char* const kKernelNames[KID_COUNT] = {
-    "vnorm", "stats", "scores", "poolstat", "sel_init", "sel_fused", "sel_steps", "compact", "budgets",
+    "vnorm", "stats", "scores", "sweep", "poolstat", "sel_init", "sel_fused", "sel_steps", "compact", "budgets",
     "decode", "decode_merge"};
 
 void prof_collect() {
@@ -116,7 +116,7 @@ int32_t lava_set_tuning(const lava_tuning* t) {
   if (t->sweep_shape < 0 || t->sweep_shape > 2 || t->sweep_schedule < 0 || t->sweep_schedule > 2 ||
       t->sweep_workgroups < 0 || t->sweep_workgroups > 65536 || t->barrier_spin_limit < 0 ||
       (t->decode_rows_per_unit != 0 && (t->decode_rows_per_unit < 128 || t->decode_rows_per_unit > 8192)) ||
-      t->reserved[0] != 0 || t->reserved[1] != 0 || t->reserved[2] != 0)
+      t->sweep_orphan_units < 0 || t->reserved[0] != 0 || t->reserved[1] != 0)
     return LAVA_ERR_INVALID_ARG;
   g_tuning = *t;
   return LAVA_OK;
@@ -231,6 +231,24 @@ int32_t lava_window_scores(const lava_layer_desc* desc, int32_t batch, const int
     }
     st = d.score_kind == LAVA_SCORE_ATTENTION ? launch_unit_vnorm(d, a, max_vb, s) : launch_vnorm(d, a, max_vb, s);
     if (st != LAVA_OK) return st;
+    // Statistics and scores: two launches, or (when the caller's tuning asks for it, all heads of a group
+    // fit one workgroup and the statistics pass is needed) one persistent launch that runs both passes.
+    // The persistent launch measured a few per cent slower on this device, so it is not the default.
+    const bool persistent = together && lse == nullptr && tuning().sweep_schedule == 2;
+    if (persistent) {
+      int units = 0;
+      for (int i = 0; i < a.n_seq; ++i) {
+        a.s[i].unit_base = units;
+        units += d.n_kv_heads * a.s[i].blocks_x;
+      }
+      a.n_units = units;
+      a.spin_limit = tuning().barrier_spin_limit > 0 ? (unsigned int)tuning().barrier_spin_limit : 1u << 18;
+      a.help_after = a.spin_limit / 4 < 64u ? (a.spin_limit / 4 > 0u ? a.spin_limit / 4 : 1u) : 64u;
+      a.orphan_mod = tuning().sweep_orphan_units;
+      st = launch_sweep(d, a, plan_launch, s);
+      if (st != LAVA_OK) return st;
+      continue;
+    }
     if (lse == nullptr) {
       st = launch_stats(d, a, max_bx, plan_launch, s);
       if (st != LAVA_OK) return st;

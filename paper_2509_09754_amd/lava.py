@@ -59,7 +59,7 @@ class Tuning(ctypes.Structure):
     _fields_ = [
         ("sweep_shape", ctypes.c_int32), ("sweep_workgroups", ctypes.c_int32), ("sweep_schedule", ctypes.c_int32),
         ("decode_rows_per_unit", ctypes.c_int32), ("barrier_spin_limit", ctypes.c_int32),
-        ("reserved", ctypes.c_int32 * 3),
+        ("sweep_orphan_units", ctypes.c_int32), ("reserved", ctypes.c_int32 * 2),
     ]
 
 
@@ -180,10 +180,10 @@ def to_host_bits(t: torch.Tensor) -> np.ndarray:
 
 # ------------------------------------------------------------------------------ entry points
 def set_tuning(sweep_shape="auto", sweep_workgroups=0, sweep_schedule="auto", decode_rows_per_unit=0,
-               barrier_spin_limit=0) -> None:
+               barrier_spin_limit=0, sweep_orphan_units=0) -> None:
     """lava_set_tuning; called without arguments it restores the library's own choices."""
     t = Tuning(SWEEP_SHAPES[sweep_shape], int(sweep_workgroups), SWEEP_SCHEDULES[sweep_schedule],
-               int(decode_rows_per_unit), int(barrier_spin_limit))
+               int(decode_rows_per_unit), int(barrier_spin_limit), int(sweep_orphan_units))
     _check(lib.lava_set_tuning(ctypes.byref(t)), "lava_set_tuning")
 
 

@@ -270,15 +270,45 @@ SCORE_CASES = [
 
 
 @pytest.mark.parametrize("name,sh", SCORE_CASES, ids=[c[0] for c in SCORE_CASES])
-def test_window_scores_vs_oracle(lava, name, sh):
+def test_window_scores_vs_oracle(lava, name, sh, tuning):
+    """Every case under both schedules of the key sweeps (one persistent launch for statistics and scores,
+    or one launch each): each against the oracle, and the two against each other bit for bit (the same
+    tiles are combined in the same order)."""
     say(f"scores {name}: {sh}")
     for seed in (0, 1):
         inp = synth.gen_layer(sh, seed)
         q, k, v = inp.f64()
         ref_s, ref_vbar = O.lava_scores(q, k, v, sh.window, sh.pool_kernel)
         ref_e = O.layer_entropy(ref_s)
+        outs = {}
+        for schedule in ("persistent", "separate"):
+            tuning(sweep_schedule=schedule)
+            _, _, got, vbar, stat = run_scores(lava, inp)
+            compare_scores(sh, got, ref_s, vbar, ref_vbar, stat, ref_e)
+            outs[schedule] = (got, vbar, stat)
+        a, b = outs["persistent"], outs["separate"]
+        assert np.array_equal(a[0].view(np.uint32), b[0].view(np.uint32)) and np.array_equal(a[1], b[1])
+        assert np.float32(a[2]).view(np.uint32) == np.float32(b[2]).view(np.uint32)
+
+
+def test_persistent_sweep_runs_units_their_owners_left(lava, tuning):
+    """The persistent schedule's waits must not depend on every workgroup being resident: a workgroup that
+    waits long for a head's statistics runs the statistics units nobody has finished.  Forced from the
+    host: the owners skip every third unit and the waits turn to helping after a few polls.  Every kernel
+    exits normally, and the result equals the separate launches bit for bit."""
+    say("scores: persistent schedule with orphaned statistics units")
+    sh = synth.config(2, n=20000 + 13, budget=8 * 64)
+    inp = synth.gen_layer(sh, 8)
+    for shape in ("wide", "narrow"):                          # (the two shapes cut the spans differently)
+        tuning(sweep_schedule="separate", sweep_shape=shape)
+        _, _, want, want_vbar, want_stat = run_scores(lava, inp)
+        tuning(sweep_schedule="persistent", sweep_shape=shape, sweep_orphan_units=3, barrier_spin_limit=4096)
         _, _, got, vbar, stat = run_scores(lava, inp)
-        compare_scores(sh, got, ref_s, vbar, ref_vbar, stat, ref_e)
+        assert np.array_equal(got.view(np.uint32), want.view(np.uint32)), shape
+        assert np.array_equal(vbar, want_vbar) and np.float32(stat).view(np.uint32) == np.float32(want_stat).view(np.uint32)
+    q, k, v = inp.f64()
+    ref_s, ref_vbar = O.lava_scores(q, k, v, sh.window, sh.pool_kernel)
+    compare_scores(sh, got, ref_s, vbar, ref_vbar, stat, O.layer_entropy(ref_s))
 
 
 NARROW_CASES = [c for c in SCORE_CASES if c[0] not in ("tiny-prefix", "w1")] + [
@@ -365,7 +395,7 @@ def test_window_scores_pool_kernels_and_lse(lava):
     compare_scores(sh, got, ref_s, vbar, ref_vbar, stat, O.layer_entropy(ref_s))
 
 
-def test_window_scores_deterministic_and_batched(lava):
+def test_window_scores_deterministic_and_batched(lava, tuning):
     say("scores determinism + ragged batch")
     # 16416 and 16384 tokens split into a different number of workgroups (513 vs 512 tiles)
     shapes = [synth.config(2, n=n, budget=8 * 64) for n in (1500, 16416, 33 + 32, 16384, 2777)]
@@ -381,6 +411,14 @@ def test_window_scores_deterministic_and_batched(lava):
         s2, vb2, e2 = lava.lava_window_scores(desc, lens, q, k, v)
         torch.cuda.synchronize()
         assert torch.equal(s1, s2) and torch.equal(vb1, vb2) and torch.equal(e1, e2), rerun
+    for shape in ("wide", "narrow"):                          # the two schedules on the same ragged batch, per shape
+        tuning(sweep_schedule="separate", sweep_shape=shape)
+        s3, vb3, e3 = lava.lava_window_scores(desc, lens, q, k, v)
+        tuning(sweep_schedule="persistent", sweep_shape=shape)
+        s2, vb2, e2 = lava.lava_window_scores(desc, lens, q, k, v)
+        torch.cuda.synchronize()
+        assert torch.equal(s3, s2) and torch.equal(vb3, vb2) and torch.equal(e3, e2), shape
+    tuning()
     s1 = s1.cpu().numpy()
     tok = 0
     for b, (sh, inp) in enumerate(zip(shapes, inps)):
