@@ -21,15 +21,100 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E, published peak
 
-# HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (two runs), each scaled by
-# what the same counter reads for the 1 GiB probe kernels below (FETCH_SIZE KiB x 2.000, WRITE_SIZE
-# KiB x 1.000); source tables: profiles/<workload>_hbm_counters.md.  (read_bytes, write_bytes)
-MEASURED_TRAFFIC = {
-    ("cfg4", "vnorm"): (268_501_402, 8_499), ("cfg4", "stats"): (270_686_003, 262_144),
-    ("cfg4", "scores"): (276_162_355, 4_219_494),
-    ("cfg2", "vnorm"): (67_175_014, 8_499), ("cfg2", "stats"): (69_361_459, 262_144),
-    ("cfg2", "scores"): (74_833_101, 1_073_766),
-}
+def measured_traffic(workload):
+    """{kernel: (read bytes, write bytes)} per launch from profiles/<workload>_hbm_counters.md, the summary that
+    `bench.py --summarize-profiles` writes from two rocprofv3 --pmc runs (FETCH_SIZE, WRITE_SIZE; scaled by
+    what the same counters read for the 1 GiB probe kernels).  Empty if the summary is not there."""
+    path = os.path.join(ROOT, "profiles", f"{workload}_hbm_counters.md")
+    out = {}
+    if not os.path.exists(path):
+        return out
+    for line in open(path):
+        cells = [c.strip() for c in line.strip().strip("|").split("|")]
+        if len(cells) < 5 or not cells[0] or cells[0] in ("kernel", "---"):
+            continue
+        try:
+            read_mib, write_mib = float(cells[3]), float(cells[4])
+        except ValueError:
+            continue
+        for kid in ("vnorm", "stats", "scores", "sweep", "sel_fused", "compact", "decode_merge", "decode"):
+            if cells[0].startswith(kid + "_kernel") and kid not in out:
+                out[kid] = (int(read_mib * 2**20), int(write_mib * 2**20))
+    return out
+
+
+def summarize_profiles(workload):
+    """Writes profiles/<workload>_kernel_trace.md and profiles/<workload>_hbm_counters.md from the rocprofv3 CSV
+    output under gpurun_out/ (directories prof_<wl>, pmc_fetch_<wl>, pmc_write_<wl>, pmc_util_<wl>, as the
+    commands quoted in the summaries leave them).  Reads files only; runs nothing."""
+    import collections
+    import csv
+    wl = workload
+    flags = {"decode": "--steps 40 --decode-only"}.get(
+        wl, "--steps 20 --warmup 3 --no-cpu-baseline --no-check --no-decode --no-cascade" + ("" if wl == "cfg4" else f" --workload {wl}"))
+    cmd = f"python3 bench.py {flags}"
+
+    def short(n):
+        return n.replace("(anonymous namespace)::", "").split("(")[0].replace("void lava::", "").replace("lava::", "")
+
+    def ours(n):
+        return not (n.startswith("void at::") or "rocclr" in n or n.startswith("Cijk") or n.strip() == "void")
+
+    rows = list(csv.DictReader(open(os.path.join(ROOT, f"gpurun_out/prof_{wl}/{wl}_kernel_stats.csv"))))
+    out = [f"# rocprofv3 kernel trace - {wl}\n",
+           "Command (from the repository root on the MI355X box, after `cd /tmp && export TMPDIR=/tmp`):\n",
+           f"    rocprofv3 --kernel-trace --stats --output-format csv -d gpurun_out/prof_{wl} -o {wl} -- {cmd}\n",
+           "Per-kernel durations from `*_kernel_stats.csv` (the command runs warm-up, timed, per-kernel-event and "
+           "caller-LSE loops; `calls` counts all of them); summary written by `python bench.py --summarize-profiles "
+           f"{wl}`.  Kernels PyTorch launches while the inputs are generated are left out.\n",
+           "| kernel | calls | avg us | min us | max us | % of GPU time |", "|---|---|---|---|---|---|"]
+    for r in rows:
+        n = short(r["Name"])
+        if ours(n):
+            out.append(f"| {n} | {r['Calls']} | {float(r['AverageNs']) / 1e3:.2f} | {float(r['MinNs']) / 1e3:.2f} | "
+                       f"{float(r['MaxNs']) / 1e3:.2f} | {r['Percentage']} |")
+    open(os.path.join(ROOT, "profiles", f"{wl}_kernel_trace.md"), "w").write("\n".join(out) + "\n")
+
+    def pmc(kind):
+        path = os.path.join(ROOT, f"gpurun_out/pmc_{kind}_{wl}/p_counter_collection.csv")
+        if not os.path.exists(path):
+            return None
+        agg = collections.defaultdict(lambda: collections.defaultdict(list))
+        for r in csv.DictReader(open(path)):
+            agg[short(r["Kernel_Name"])][r["Counter_Name"]].append(float(r["Counter_Value"]))
+        return {k: {c: sum(x) / len(x) for c, x in v.items()} for k, v in agg.items()}
+
+    f, w, u = pmc("fetch"), pmc("write"), pmc("util")
+    if f is None or w is None:
+        print(f"wrote profiles/{wl}_kernel_trace.md (no counter runs found)")
+        return
+    kib = 1048576.0
+    if "probe_read_kernel" in f and "probe_copy_kernel" in w:
+        ff, wf = kib / f["probe_read_kernel"]["FETCH_SIZE"], kib / w["probe_copy_kernel"]["WRITE_SIZE"]
+        calib = ("Calibration: the same command runs `lava_probe_stream` on 1 GiB (= 1048576 KiB): `probe_read_kernel` "
+                 f"FETCH_SIZE = {f['probe_read_kernel']['FETCH_SIZE']:.1f} -> bytes = counter KiB x {ff:.3f}; "
+                 f"`probe_copy_kernel` WRITE_SIZE = {w['probe_copy_kernel']['WRITE_SIZE']:.1f} -> bytes = counter KiB x {wf:.3f}.\n")
+    else:
+        ff, wf = 2.0, 1.0
+        calib = "Calibration: the factors of `cfg4_hbm_counters.md` (same counters): FETCH_SIZE KiB x 2.000, WRITE_SIZE KiB x 1.000.\n"
+    out = [f"# rocprofv3 HBM byte counters and utilisation - {wl}\n",
+           "Commands (each its own run, after `cd /tmp && export TMPDIR=/tmp`):\n",
+           f"    rocprofv3 --pmc FETCH_SIZE --output-format csv -d gpurun_out/pmc_fetch_{wl} -o p -- {cmd}",
+           f"    rocprofv3 --pmc WRITE_SIZE --output-format csv -d gpurun_out/pmc_write_{wl} -o p -- {cmd}",
+           f"    rocprofv3 --pmc MfmaUtil MemUnitStalled LDSBankConflict --output-format csv -d gpurun_out/pmc_util_{wl} -o p -- {cmd}\n",
+           calib, f"Summary written by `python bench.py --summarize-profiles {wl}`; `bench.py` reads columns 4 and 5 of "
+           "this table for `traffic`.\n",
+           "| kernel | FETCH_SIZE (KiB/dispatch) | WRITE_SIZE (KiB/dispatch) | HBM read MiB (scaled) | HBM write MiB (scaled) | "
+           "MfmaUtil % | MemUnitStalled % | LDSBankConflict % |", "|---|---|---|---|---|---|---|---|"]
+    for k in f:
+        if not ours(k) or k not in w:
+            continue
+        uu = (u or {}).get(k, {})
+        out.append(f"| {k} | {f[k]['FETCH_SIZE']:.1f} | {w[k]['WRITE_SIZE']:.1f} | {f[k]['FETCH_SIZE'] * ff / 1024:.2f} | "
+                   f"{w[k]['WRITE_SIZE'] * wf / 1024:.2f} | {uu.get('MfmaUtil', float('nan')):.1f} | "
+                   f"{uu.get('MemUnitStalled', float('nan')):.1f} | {uu.get('LDSBankConflict', float('nan')):.1f} |")
+    open(os.path.join(ROOT, "profiles", f"{wl}_hbm_counters.md"), "w").write("\n".join(out) + "\n")
+    print(f"wrote profiles/{wl}_kernel_trace.md and profiles/{wl}_hbm_counters.md")
 
 
 def parse():
@@ -42,6 +127,11 @@ def parse():
     ap.add_argument("--sets", type=int, default=0, help="distinct K/V buffer sets (0 = enough for >= 1.5 GiB)")
     ap.add_argument("--sweep-schedule", default="auto", choices=["auto", "separate", "persistent"],
                     help="lava_tuning.sweep_schedule for the whole run (A/B of the two key-sweep schedules)")
+    ap.add_argument("--summarize-profiles", metavar="WORKLOAD", default=None,
+                    help="write profiles/<workload>_*.md from rocprofv3 CSV output under gpurun_out/ and exit (no GPU)")
+    ap.add_argument("--no-primed", action="store_true",
+                    help="plain lava_window_scores + lava_select_topk instead of the pair in which the score kernels "
+                         "prepare the selection's first histogram")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-check", action="store_true")
     ap.add_argument("--no-decode", action="store_true", help="skip the decode-attention leg")
@@ -383,6 +473,9 @@ def layer_stack(lava, synth, torch, np, dev, args):
 
 def main():
     args = parse()
+    if args.summarize_profiles:
+        summarize_profiles(args.summarize_profiles)
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
               f"--gpus {args.gpus} is not supported. Re-run with --gpus 1.", file=sys.stderr)
@@ -463,36 +556,54 @@ def main():
     del probe_src, probe_dst
 
     lse_dev = [None]
+    primed = not args.no_primed
 
     def step(i):
         q, k, v = sets[i % n_sets]
         lava.lava_window_scores(desc, lens, q, k, v, lse=lse_dev[0], scores=scores, vbar=vbar, layer_stat=stat,
-                                workspace=ws_scores)
+                                workspace=ws_scores, select_workspace=ws_sel if primed else None)
         lava.lava_layer_budgets(stat.view(1, 1), total_b, lo, hi, budgets=budgets)
         lava.lava_select_topk(sh.n_kv_heads, scores, B, budget_dev=budgets.view(-1), head_counts=counts,
-                              head_offsets=offs, kept_idx=idx, kept_scores=kept_s, workspace=ws_sel)
+                              head_offsets=offs, kept_idx=idx, kept_scores=kept_s, workspace=ws_sel, primed=primed)
         lava.lava_compact_kv(desc, sh.n, k, v, offs, idx, B, k_out=k_hat, v_out=v_hat)
 
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    elapsed = time.perf_counter() - t0
+    def timed_loop():
+        for i in range(args.warmup):
+            step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(args.steps):
+            step(i)
+        torch.cuda.synchronize()
+        return time.perf_counter() - t0
+
+    def per_step_times():
+        """Duration of every step of an identical loop, from events between the steps (median / min)."""
+        marks = [torch.cuda.Event(enable_timing=True) for _ in range(args.steps + 1)]
+        marks[0].record()
+        for i in range(args.steps):
+            step(i)
+            marks[i + 1].record()
+        torch.cuda.synchronize()
+        t = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(args.steps))
+        return {"median_ms": round(t[len(t) // 2], 5), "min_ms": round(t[0], 5), "max_ms": round(t[-1], 5)}
+
+    def per_kernel_times():
+        """Average duration of every kernel over an identical loop, HIP events on the launch stream."""
+        lava.prof_enable(True)
+        lava.prof_reset()
+        for i in range(args.steps):
+            step(i)
+        torch.cuda.synchronize()
+        prof = lava.prof_read()
+        lava.prof_enable(False)
+        return {name: 1e3 * ms / max(cnt, 1) for name, (ms, cnt) in prof.items() if cnt}
+
+    elapsed = timed_loop()
     ms_per_step = 1e3 * elapsed / args.steps
     tokens_per_s = sh.n / (elapsed / args.steps)
-
-    # ---- per-kernel durations over an identical loop, HIP events on the launch stream
-    lava.prof_enable(True)
-    lava.prof_reset()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    prof = lava.prof_read()
-    lava.prof_enable(False)
-    per_kernel_us = {name: 1e3 * ms / max(cnt, 1) for name, (ms, cnt) in prof.items() if cnt}
+    step_spread = per_step_times()
+    per_kernel_us = per_kernel_times()
 
     # ---- variant: the prefill attention hands over the window rows' log-sum-exp, so the statistics
     # pass is skipped (the LSE itself is prepared here with torch, outside any timed region)
@@ -506,34 +617,56 @@ def main():
         logits = logits.masked_fill(pos > last, float("-inf"))
         lse_dev[0] = torch.logsumexp(logits, dim=2).contiguous()
         del logits, qf
-    for i in range(args.warmup):
-        step(i)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    for i in range(args.steps):
-        step(i)
-    torch.cuda.synchronize()
-    lse_elapsed = time.perf_counter() - t0
+    lse_elapsed = timed_loop()
+    lse_kernel_us = per_kernel_times()
     lse_dev[0] = None
 
-    # algorithmic bytes of each sweep kernel per launch (bytes it must move given its inputs/outputs)
+    # ---- algorithmic bytes of each sweep kernel per launch (what it must move given its inputs / outputs)
     q_bytes = sh.n_q_heads * sh.window * sh.head_dim * esize
     score_bytes = 4 * total_entries
     alg_bytes = {
         "vnorm": kv_bytes,
         "stats": kv_bytes + q_bytes,
         "scores": kv_bytes + q_bytes + score_bytes,
+        "sweep": 2 * (kv_bytes + q_bytes) + score_bytes,
         "sel_fused": score_bytes,
         "compact": 4 * B * sh.head_dim * esize,
     }
-    dominant = max(per_kernel_us, key=per_kernel_us.get)
-    dom_bytes = alg_bytes.get(dominant, 0)
-    achieved = dom_bytes / (per_kernel_us[dominant] * 1e-6) / 1e9 if dom_bytes else 0.0
-    roofline = {"bound": "hbm", "kernel": dominant, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                "traffic": sum(MEASURED_TRAFFIC[(args.workload, dominant)])
-                if (args.workload, dominant) in MEASURED_TRAFFIC else None,
-                "kernel_us": round(per_kernel_us[dominant], 2), "algorithmic_bytes": dom_bytes}
+    traffic = measured_traffic(args.workload)
+
+    def kernel_line(name, us):
+        gbs = alg_bytes[name] / (us * 1e-6) / 1e9
+        return {"us": round(us, 2), "algorithmic_bytes": alg_bytes[name], "GBs": round(gbs, 1),
+                "frac_of_hbm_peak": round(gbs / HBM_PEAK_GBS, 4),
+                "traffic": sum(traffic[name]) if name in traffic else None}
+
+    sweep_names = [n for n in ("vnorm", "stats", "scores", "sweep") if n in per_kernel_us]
+    sweep_kernels = {n: kernel_line(n, per_kernel_us[n]) for n in sweep_names}
+    # the dominant kernel: the slowest of the sweeps (stats and scores are within a few per cent of each
+    # other, so the name may differ from run to run; sweep_kernels lists them all)
+    dominant = max(sweep_names, key=lambda n: per_kernel_us[n])
+    dom = sweep_kernels[dominant]
+    roofline = {"bound": "hbm", "kernel": dominant, "achieved": dom["GBs"], "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": dom["frac_of_hbm_peak"], "traffic": dom["traffic"],
+                "traffic_source": f"profiles/{args.workload}_hbm_counters.md" if dom["traffic"] is not None else None,
+                "kernel_us": dom["us"], "algorithmic_bytes": dom["algorithmic_bytes"]}
+    # the K/V sweep as a whole, both accountings: K once + V once (a second pass over K is overhead) and
+    # the bytes the kernels actually have to stream (K twice + V once); and with the caller's LSE (K once)
+    sweep_us = sum(per_kernel_us[n] for n in sweep_names)
+    once = 2 * kv_bytes + q_bytes + score_bytes
+    moved = sum(alg_bytes[n] for n in sweep_names)
+    lse_names = [n for n in ("vnorm", "scores") if n in lse_kernel_us]
+    lse_us = sum(lse_kernel_us[n] for n in lse_names)
+    kv_sweep = {
+        "kernels": sweep_names, "us": round(sweep_us, 2),
+        "k_once_v_once": {"bytes": once, "GBs": round(once / sweep_us / 1e3, 1),
+                          "frac_of_hbm_peak": round(once / sweep_us / 1e3 / HBM_PEAK_GBS, 4)},
+        "bytes_streamed": {"bytes": moved, "GBs": round(moved / sweep_us / 1e3, 1),
+                           "frac_of_hbm_peak": round(moved / sweep_us / 1e3 / HBM_PEAK_GBS, 4)},
+        "with_lse": {"kernels": lse_names, "us": round(lse_us, 2), "bytes": once,
+                     "GBs": round(once / lse_us / 1e3, 1),
+                     "frac_of_hbm_peak": round(once / lse_us / 1e3 / HBM_PEAK_GBS, 4)},
+    }
     # whole-path view: K once + V once + scores + kept rows, over the whole step
     path_bytes = 2 * kv_bytes + q_bytes + 2 * score_bytes + 4 * B * sh.head_dim * esize
     path_gbs = path_bytes / (elapsed / args.steps) / 1e9
@@ -545,8 +678,12 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": sh.dtype, "data": "synthetic",
         "config": {"workload": f"{args.workload}: one layer, {sh.n_q_heads}q/{sh.n_kv_heads}kv heads, d_h {sh.head_dim}, "
                                f"N={sh.n}, w={sh.window}, B_l={B}, {sh.dtype}, batch 1",
-                   "kv_buffer_sets": n_sets},
+                   "kv_buffer_sets": n_sets, "sweep_schedule": args.sweep_schedule,
+                   "scores_prepare_selection": primed},
         "roofline": roofline,
+        "step_spread": step_spread,
+        "sweep_kernels": sweep_kernels,
+        "kv_sweep": kv_sweep,
         "path": {"algorithmic_bytes": path_bytes, "achieved_GBs": round(path_gbs, 1),
                  "frac_of_hbm_peak": round(path_gbs / HBM_PEAK_GBS, 4)},
         "kernels_us": {k: round(v, 2) for k, v in per_kernel_us.items()},
@@ -554,7 +691,8 @@ def main():
         "with_lse": {"note": "window-row log-sum-exp supplied by the caller: statistics pass skipped",
                      "ms_per_step": round(1e3 * lse_elapsed / args.steps, 5),
                      "value": round(sh.n / (lse_elapsed / args.steps), 1),
-                     "path_frac_of_hbm_peak": round(path_bytes / (lse_elapsed / args.steps) / 1e9 / HBM_PEAK_GBS, 4)},
+                     "path_frac_of_hbm_peak": round(path_bytes / (lse_elapsed / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
+                     "kernels_us": {k: round(v, 2) for k, v in lse_kernel_us.items()}},
     }
 
     if not args.no_decode:

@@ -139,6 +139,28 @@ int32_t lava_window_scores(const lava_layer_desc* desc, int32_t batch, const int
                            size_t workspace_bytes, void* hip_stream);
 
 /*
+ * lava_window_scores that also prepares the workspace of the selection which will rank the scores it
+ * writes (Alg. 1 runs the two back to back): while the final scores are still in registers the score
+ * kernels count the selection's first radix digit, so that the selection needs neither its clearing
+ * launch nor its first pass over the scores nor the grid-wide wait behind that pass.  Results of both
+ * calls are unchanged bit for bit.
+ *
+ *   select_workspace  device, 256-byte aligned, laid out as for lava_select_topk_batch with `batch`
+ *                     problems and max_total_entries = H_kv * max_b N_b (for batch = 1 that is the
+ *                     workspace of lava_select_topk for H_kv * N entries): region b belongs to
+ *                     sequence b.  Too small -> LAVA_ERR_WORKSPACE.
+ * Afterwards rank sequence b's scores ([H_kv][N_b], equal segments, all H_kv * N_b entries) ONCE with
+ * lava_select_topk_primed, or with lava_select_topk_batch where problem b has primed = 1 and
+ * max_total_entries is the same H_kv * max_b N_b.  A prepared region is used up by that selection; a
+ * selection with primed = 0 ignores what was prepared and clears the region itself.
+ */
+int32_t lava_window_scores_primed(const lava_layer_desc* desc, int32_t batch, const int64_t* seq_lens,
+                                  const void* q_win, const void* k, const void* v, const float* lse,
+                                  float* scores, float* vbar, float* layer_stat, void* workspace,
+                                  size_t workspace_bytes, void* select_workspace,
+                                  size_t select_workspace_bytes, void* hip_stream);
+
+/*
  * Layer budgets B_l = e_l / sum_l e_l * total (Alg. 2, inner loop) as integers.
  *
  *   e          [batch][n_layers] float   statistics of the layers prefilled so far
@@ -198,6 +220,13 @@ int32_t lava_select_topk(int32_t n_heads, const float* scores, const int64_t* se
                          int32_t* head_counts, int64_t* head_offsets, int32_t* kept_idx,
                          float* kept_scores, void* workspace, size_t workspace_bytes,
                          void* hip_stream);
+
+/* lava_select_topk over a score array whose workspace lava_window_scores_primed prepared (equal
+ * segments of total_entries / n_heads; total_entries = H_kv * N of that sequence). */
+int32_t lava_select_topk_primed(int32_t n_heads, const float* scores, int64_t total_entries, int64_t budget,
+                                const int64_t* budget_dev, int32_t* head_counts, int64_t* head_offsets,
+                                int32_t* kept_idx, float* kept_scores, void* workspace,
+                                size_t workspace_bytes, void* hip_stream);
 
 /*
  * Synchronises the stream and reports whether the last lava_select_topk that used `workspace`
@@ -286,6 +315,9 @@ typedef struct lava_select_problem {
   int32_t* error_dev;           /* or NULL: device int32 set to 1 if this selection gave up at a
                                    bounded wait (never cleared by the library, so one word can
                                    collect the failures of many selections)                     */
+  int32_t primed;               /* non-zero: this problem's workspace region was prepared by
+                                   lava_window_scores_primed for exactly these scores (seg_offsets
+                                   and in_offset_dev must be NULL)                              */
 } lava_select_problem;
 
 typedef struct lava_compact_problem {

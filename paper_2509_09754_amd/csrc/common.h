@@ -48,6 +48,16 @@ inline void discard_stale_error() { (void)hipGetLastError(); }
 // The process-wide launch-shape tuning (lava_set_tuning); all-zero = the library's own choices.
 const lava_tuning& tuning();
 
+// Order-preserving map float -> uint32 used by the selection (larger score = larger key); -0 and +0
+// coincide.  The selection's first digit is the key's top kSelDigit0Bits bits.
+__device__ __forceinline__ unsigned int score_key(float f) {
+  unsigned int b = __float_as_uint(f);
+  if ((b << 1) == 0u) b = 0u;
+  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
+}
+constexpr int kSelBins = 2048;
+constexpr int kSelDigit0Shift = 21;
+
 constexpr size_t kAlign = 256;
 constexpr size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
 
@@ -118,6 +128,10 @@ struct SweepArgs {
   float c2;
   int first_seq;             // index in the batch of s[0]
   int n_seq;
+  // lava_window_scores_primed: the selection workspace whose region (first_seq + z) the launch prepares
+  // (null: none): region stride and the offsets of the histograms / the state inside a region
+  char* sel_ws;
+  size_t sel_stride, sel_off_hist, sel_off_state;
   int n_units;               // persistent launch: H_kv * sum of blocks_x over the table
   unsigned int spin_limit;   // persistent launch: polls of a wait for other workgroups before it gives up
   unsigned int help_after;   // persistent launch: polls after which a waiting workgroup looks for unclaimed units (>= 1)
@@ -139,7 +153,10 @@ int32_t launch_scores(const lava_layer_desc& d, const SweepArgs& a, int max_bloc
 float sweep_exp2_scale(const lava_layer_desc& d);
 int32_t launch_poolstat(const lava_layer_desc& d, int64_t n, const float* s_raw,
                         const float* vnorm_part, int vnorm_blocks, float* scores, float* vbar,
-                        float* layer_stat, double2* ent_part, uint32_t* counters, hipStream_t s);
+                        float* layer_stat, double2* ent_part, uint32_t* counters, unsigned int* sel_hist0,
+                        hipStream_t s);
+// words of a selection's state block (cleared together with its histograms)
+constexpr int kSelStateWords = 8;
 
 // ---------------------------------------------------------------- selection / compaction
 struct SelectWorkspace {

@@ -22,7 +22,7 @@ namespace lava {
 constexpr int kSelThreads = 1024;   // few, large workgroups: grid-wide barriers and histogram merges cost per workgroup
 constexpr int kSelPerThread = 16;
 constexpr int kSelChunk = kSelThreads * kSelPerThread;  // entries per workgroup
-constexpr int kBins = 2048;
+constexpr int kBins = kSelBins;
 constexpr int kMaxHeads = 64;
 constexpr unsigned int kSpinLimit = 1u << 18;           // polls of a grid barrier before giving up (default)
 
@@ -38,6 +38,7 @@ struct SelectState {
   unsigned int done;         // workgroups of the fused kernel that have written their results
   unsigned int reserved[5];
 };
+static_assert(sizeof(SelectState) == kSelStateWords * sizeof(unsigned int), "cleared word by word by the score kernels");
 
 // Layout of a selection's workspace for `total` entries (also evaluated at compile time, for the
 // built-in scratch array of lava_select_topk_static).
@@ -59,13 +60,6 @@ static constexpr SelectWorkspace select_layout(int64_t total) {
 }
 
 SelectWorkspace make_select_workspace(int64_t total) { return select_layout(total); }
-
-// Order-preserving map float -> uint32 (larger score = larger key); -0 and +0 coincide.
-__device__ __forceinline__ unsigned int score_key(float f) {
-  unsigned int b = __float_as_uint(f);
-  if ((b << 1) == 0u) b = 0u;
-  return (b & 0x80000000u) ? ~b : (b | 0x80000000u);
-}
 
 struct SelShared {
   union {
@@ -310,8 +304,12 @@ __device__ __forceinline__ void write_phase(int bx, const float (&val)[kSelPerTh
   long long next_start = g + 1 < n_heads ? sh.off[g + 1] : kNever;
   long long head_start = sh.off[g];
   unsigned int local_cnt = 0u;
+  // most lanes hold no survivor and no segment start (a fraction of a per cent of the entries survive):
+  // they have nothing to write
+  const bool idle = gt_mask == 0u && (eq_mask == 0u || eq_before >= need) && next_start >= first + kSelPerThread;
 #pragma unroll
   for (int j = 0; j < kSelPerThread; ++j) {
+    if (idle) break;
     const long long p = first + j;
     while (p >= next_start) {
       if (local_cnt) atomicAdd(&sh.cnt[g], local_cnt);
@@ -476,6 +474,8 @@ struct SelectBatch {
   size_t ws_stride, off_hist, off_state, off_blk;
   int blk_stride;                // n_blocks the regions were laid out for
   unsigned int spin_limit;       // polls of a grid barrier before it gives up
+  unsigned int primed_mask;      // bit p: problem p's region was prepared by the score kernels (first histogram
+                                 // complete, the rest cleared)
   lava_select_problem p[kMaxSelProblems];
 };
 
@@ -496,8 +496,9 @@ __global__ void __launch_bounds__(kSelThreads) sel_init_kernel(const SelectBatch
   char* region = a.ws + blockIdx.x * a.ws_stride;
   unsigned int* hist = reinterpret_cast<unsigned int*>(region + a.off_hist);
   SelectState* st = reinterpret_cast<SelectState*>(region + a.off_state);
-  for (int i = threadIdx.x; i < 3 * kBins; i += kSelThreads) hist[i] = 0u;
   if (threadIdx.x < a.n_heads) pr.head_counts[threadIdx.x] = 0;
+  if ((a.primed_mask >> blockIdx.x) & 1u) return;           // histograms and state are as the score kernels left them
+  for (int i = threadIdx.x; i < 3 * kBins; i += kSelThreads) hist[i] = 0u;
   if (threadIdx.x == 0) {
     st->barrier = 0u;
     st->error = 0u;
@@ -542,14 +543,24 @@ __global__ void __launch_bounds__(kSelThreads) sel_fused_kernel(const SelectBatc
   pk.need = effective_budget(budget, pr.budget_dev, total);
   const long long kept_total = pk.need;
 
-  hist_phase<0>(bx, val, total, pk.prefix, sh, hist);
-  grid_sync(st, 1u, nb, a.spin_limit);
+  // A primed problem arrives with its first histogram complete (the score kernels built it from the
+  // scores they wrote) and everything else cleared: no init launch, no first pass, one barrier fewer.
+  // Its survivor counts are cleared here, by a workgroup that passes two barriers before anybody adds to them.
+  const bool primed = (a.primed_mask >> prob) & 1u;
+  unsigned int round = 0u;
+  if (primed) {
+    if (bx == 0 && threadIdx.x < (unsigned)n_heads)        // device-scope store: the counts are added to with device-scope atomics
+      st_dev(reinterpret_cast<unsigned int*>(&pr.head_counts[threadIdx.x]), 0u);
+  } else {
+    hist_phase<0>(bx, val, total, pk.prefix, sh, hist);
+    grid_sync(st, ++round, nb, a.spin_limit);
+  }
   pk = pick_phase<0>(hist, pk, sh);
   hist_phase<1>(bx, val, total, pk.prefix, sh, hist + kBins);
-  grid_sync(st, 2u, nb, a.spin_limit);
+  grid_sync(st, ++round, nb, a.spin_limit);
   pk = pick_phase<1>(hist + kBins, pk, sh);
   hist_publish_phase(bx, val, total, pk.prefix, sh, hist + 2 * kBins, blk + (size_t)bx * kPubWords);
-  grid_sync(st, 3u, nb, a.spin_limit);
+  grid_sync(st, ++round, nb, a.spin_limit);
   pk = pick_phase<2>(hist + 2 * kBins, pk, sh);
 
   // the counts of the workgroups before this one were published with the last histogram: no
@@ -675,17 +686,22 @@ int32_t launch_select_batch(int n_heads, int n_problems, const lava_select_probl
     a.n_problems = count;
     a.first_block[count] = blocks;
     a.ws = static_cast<char*>(ws) + (size_t)first * w.bytes;
-    {
+    a.primed_mask = 0u;
+    for (int i = 0; i < count; ++i)
+      if (a.p[i].primed) a.primed_mask |= 1u << i;
+    const bool all_primed = a.primed_mask == (count == 32 ? 0xffffffffu : (1u << count) - 1u);
+    const bool fused = blocks <= cap;
+    if (!(fused && all_primed)) {                          // the one-launch selection clears a primed problem's counts itself
       ProfScope ps(KID_SEL_INIT, s);
       hipLaunchKernelGGL(sel_init_kernel, dim3(count), block, 0, s, a);
     }
-    if (blocks <= cap) {
+    if (fused) {
       ProfScope ps(KID_SEL_FUSED, s);
       hipLaunchKernelGGL(sel_fused_kernel, dim3(blocks), block, 0, s, a);
     } else {                                               // a single problem wider than the device allows
       ProfScope ps(KID_SEL_STEPS, s);
       const dim3 grid(blocks);
-      hipLaunchKernelGGL(sel_step_kernel<0>, grid, block, 0, s, a);
+      if (!all_primed) hipLaunchKernelGGL(sel_step_kernel<0>, grid, block, 0, s, a);
       hipLaunchKernelGGL(sel_step_kernel<1>, grid, block, 0, s, a);
       hipLaunchKernelGGL(sel_step_kernel<2>, grid, block, 0, s, a);
       hipLaunchKernelGGL(sel_step_kernel<3>, grid, block, 0, s, a);
@@ -715,6 +731,7 @@ int32_t launch_select(int n_heads, const float* scores, const int64_t* seg_offse
   pr.in_offset_dev = nullptr;
   pr.out_offset_dev = nullptr;
   pr.error_dev = nullptr;
+  pr.primed = 0;
   return launch_select_batch(n_heads, 1, &pr, total, ws, s);
 }
 
@@ -778,7 +795,7 @@ extern "C" int32_t lava_select_topk_static(int32_t n_heads, const float* scores,
   if (n_heads < 1) return LAVA_ERR_INVALID_ARG;
   if (n_heads > lava::kMaxHeads) return LAVA_ERR_SHAPE;
   const lava_select_problem p = {scores,      seg_offsets,  total_entries, budget,     budget_dev,
-                                 head_counts, head_offsets, kept_idx,      kept_scores, nullptr, nullptr, nullptr};
+                                 head_counts, head_offsets, kept_idx,      kept_scores, nullptr, nullptr, nullptr, 0};
   const int32_t st = lava::check_select_problem(n_heads, p);
   if (st != LAVA_OK) return st;
   if (total_entries > kStaticMaxEntries) return LAVA_ERR_WORKSPACE;   // beyond what the built-in array holds

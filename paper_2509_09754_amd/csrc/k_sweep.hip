@@ -293,7 +293,33 @@ struct PoolArgs {
   double2* ent_part;         // [workgroups]
   uint32_t* counters;
   const uint32_t* error_word; // persistent launch: non-zero once a wait for other workgroups gave up (statistic -> NaN); else null
+  unsigned int* sel_hist0;    // first-digit histogram of the selection that will rank these scores, or null
 };
+
+// Histogram of the selection's first digit over the scores a workgroup has just written, for a selection
+// workspace prepared alongside (lava_window_scores_primed): per-workgroup counts in `bins` (kSelBins words
+// of LDS, zeroed and published by a barrier before the first call), then one device-scope add per
+// non-empty bin.  Runs of equal digits (pooling makes plateaus) are counted once per run by the caller.
+__device__ __forceinline__ void digit0_count(unsigned int* bins, float score, unsigned int& run_digit,
+                                             unsigned int& run_len) {
+  const unsigned int digit = score_key(score) >> kSelDigit0Shift;
+  if (digit != run_digit) {
+    if (run_len != 0u) atomicAdd(&bins[run_digit], run_len);
+    run_digit = digit;
+    run_len = 0u;
+  }
+  ++run_len;
+}
+template <int THREADS>
+__device__ __forceinline__ void digit0_flush(unsigned int* bins, unsigned int run_digit, unsigned int run_len,
+                                             unsigned int* __restrict__ global_hist) {
+  if (run_len != 0u) atomicAdd(&bins[run_digit], run_len);
+  __syncthreads();
+  for (int i = threadIdx.x; i < kSelBins; i += THREADS) {
+    const unsigned int c = bins[i];
+    if (c) __hip_atomic_fetch_add(&global_hist[i], c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+  }
+}
 
 // Exponent bias of every (head, row) of a scores workgroup, step 1: thread (row, slice) merges its slice
 // of the head's statistics partials in workgroup order into s_merge[slice][row] (always the same fixed
@@ -466,8 +492,14 @@ __device__ __forceinline__ void scores_finish(const PoolArgs& pa, float vb, int 
                                               long long t_begin, long long t_end, long long n_tiles,
                                               const float* s_span, float* s_vb, double* s_s, double* s_t,
                                               unsigned int* s_last, unsigned int n_blocks, unsigned int block_id,
-                                              int n_heads, bool writes_vbar, int wave) {
+                                              int n_heads, bool writes_vbar, int wave, unsigned int* bins) {
   constexpr int kWaves = THREADS / 64;
+  // `bins`: kSelBins words of LDS that only wavefront 0 has used since the workgroup's last barrier (the
+  // start of its own tile ring, which it is done with)
+  const bool count_digits = pa.sel_hist0 != nullptr;
+  if (count_digits && wave == 0)
+    for (int i = threadIdx.x; i < kSelBins; i += 64) bins[i] = 0u;
+  unsigned int run_digit = 0u, run_len = 0u;
 #pragma unroll
   for (int off = 32; off > 0; off >>= 1) vb = fmaxf(vb, __shfl_xor(vb, off));
   if ((threadIdx.x & 63) == 0) s_vb[wave] = vb;
@@ -526,6 +558,7 @@ __device__ __forceinline__ void scores_finish(const PoolArgs& pa, float vb, int 
       if (base + j < p_end) {
         acc_s += (double)sc[j];
         if (sc[j] > 0.0f) acc_t += (double)sc[j] * (double)logf(sc[j]);
+        if (count_digits) digit0_count(bins, sc[j], run_digit, run_len);
       }
     }
     if (base + kPer <= p_end && (reinterpret_cast<uintptr_t>(out_head + base) & 15) == 0) {
@@ -539,8 +572,11 @@ __device__ __forceinline__ void scores_finish(const PoolArgs& pa, float vb, int 
     }
   }
   // the workgroup that owns the head's last prefix tile also writes the window entries
-  if (t_begin < t_end && t_end == n_tiles && threadIdx.x < (unsigned)w)
+  if (t_begin < t_end && t_end == n_tiles && threadIdx.x < (unsigned)w) {
     pa.scores[(long long)g * n + n_prefix + threadIdx.x] = INFINITY;
+    if (count_digits) digit0_count(bins, INFINITY, run_digit, run_len);
+  }
+  if (count_digits) digit0_flush<THREADS>(bins, run_digit, run_len, pa.sel_hist0);
   entropy_finish<THREADS>(acc_s, acc_t, pa.ent_part, pa.counters, n_blocks, block_id,
                           (double)n_heads * (double)n_prefix, pa.layer_stat, s_s, s_t, s_last, pa.error_word);
 }
@@ -573,6 +609,7 @@ scores_kernel(const SweepArgs a) {
   pa.ent_part = reinterpret_cast<double2*>(region + a.off_ent_part);
   pa.counters = reinterpret_cast<uint32_t*>(region + a.off_counter);
   pa.error_word = nullptr;
+  pa.sel_hist0 = a.sel_ws ? reinterpret_cast<unsigned int*>(a.sel_ws + (size_t)seq * a.sel_stride + a.sel_off_hist) : nullptr;
   constexpr int kWaves = Shape<DT, D, W>::kWaves;
   constexpr int kStages = Shape<DT, D, W>::kStages;
   __shared__ u32x4 s_tile[kWaves][kStages][T::kTileChunks];
@@ -655,7 +692,7 @@ scores_kernel(const SweepArgs a) {
     __shared__ unsigned int s_last;
     scores_finish<kThreads>(pa, vb, g, n, n_prefix, w, t_begin, t_end, n_tiles, s_span, s_vb, s_s, s_t, &s_last,
                             sq.blocks_x * gridDim.y, blockIdx.y * sq.blocks_x + blockIdx.x, (int)gridDim.y,
-                            blockIdx.x == 0, wave);
+                            blockIdx.x == 0, wave, reinterpret_cast<unsigned int*>(&s_tile[0][0][0]));
   }
 }
 
@@ -903,6 +940,7 @@ sweep_kernel(const SweepArgs a) {
     pa.ent_part = reinterpret_cast<double2*>(region + a.off_ent_part);
     pa.counters = ctl;
     pa.error_word = &ctl0[kCtlError];
+    pa.sel_hist0 = a.sel_ws ? reinterpret_cast<unsigned int*>(a.sel_ws + (size_t)seq * a.sel_stride + a.sel_off_hist) : nullptr;
     float vb = 0.0f;   // this thread's share of the head's value-norm partials (an earlier launch wrote them)
     for (int i = threadIdx.x; i < pa.vnorm_blocks; i += kThreads)
       vb = fmaxf(vb, pa.vnorm_part[(long long)g * pa.vnorm_blocks + i]);
@@ -916,7 +954,7 @@ sweep_kernel(const SweepArgs a) {
                                                    qf, lane, nullptr, 1);
     scores_finish<kThreads>(pa, vb, g, n, n_prefix, w, t_begin, t_end, n_tiles, sm.sc.span, sm.vb, sm.ss, sm.st,
                             &sm.last, (unsigned int)(sq.blocks_x * H_kv), (unsigned int)(g * sq.blocks_x + bx), H_kv,
-                            bx == 0, wave);
+                            bx == 0, wave, reinterpret_cast<unsigned int*>(&sm.tile[0][0][0]));
     u_b += (int)gridDim.x;
   }
 }
@@ -942,6 +980,17 @@ __device__ __forceinline__ float abs_sum16(const u32x4& x, float s) {
     for (int i = 0; i < 4; ++i) s += fabsf(__uint_as_float(u[i]));
   }
   return s;
+}
+
+// The selection region a primed call prepares for sequence z of the launch: histograms and state to zero
+// (the score kernels of the same call then fill the first histogram).  Called by one workgroup.
+__device__ __forceinline__ void clear_selection_region(const SweepArgs& a, int z, int threads) {
+  if (a.sel_ws == nullptr) return;
+  char* region = a.sel_ws + (size_t)(a.first_seq + z) * a.sel_stride;
+  unsigned int* hist = reinterpret_cast<unsigned int*>(region + a.sel_off_hist);
+  unsigned int* state = reinterpret_cast<unsigned int*>(region + a.sel_off_state);
+  for (int i = threadIdx.x; i < 3 * kSelBins; i += threads) hist[i] = 0u;
+  if (threadIdx.x < kSelStateWords) state[threadIdx.x] = 0u;
 }
 
 template <int DT, int D>
@@ -970,8 +1019,10 @@ vnorm_kernel(const SweepArgs a) {
   constexpr int kStages = VShape<DT, D>::kStages < 2 ? 2 : VShape<DT, D>::kStages;
   __shared__ u32x4 s_tile[kWaves][kStages][T::kTileChunks];
   __shared__ float s_max[kWaves];
-  if (blockIdx.x == 0 && blockIdx.y == 0)
+  if (blockIdx.x == 0 && blockIdx.y == 0) {
     for (int i = threadIdx.x; i < n_counter_words; i += VShape<DT, D>::kThreads) counters[i] = 0u;
+    clear_selection_region(a, (int)blockIdx.z, VShape<DT, D>::kThreads);
+  }
 
   const int lane = threadIdx.x & 63, wave = wave_index();
   const int g = blockIdx.y;
@@ -1043,8 +1094,12 @@ __global__ void __launch_bounds__(kPoolThreads)
 poolstat_kernel(const float* __restrict__ s_raw, long long n, int w, int pool_half, int token_norm,
                 const float* __restrict__ vnorm_part, int vnorm_blocks, float* __restrict__ scores,
                 float* __restrict__ vbar, float* __restrict__ layer_stat,
-                double2* __restrict__ ent_part, uint32_t* __restrict__ counters) {
+                double2* __restrict__ ent_part, uint32_t* __restrict__ counters, unsigned int* __restrict__ sel_hist0) {
   __shared__ float s_in[kPoolChunk + 2 * kPoolMaxHalf];
+  __shared__ unsigned int s_bins[kSelBins];
+  if (sel_hist0 != nullptr)
+    for (int i = threadIdx.x; i < kSelBins; i += kPoolThreads) s_bins[i] = 0u;      // published by the barrier below
+  unsigned int run_digit = 0u, run_len = 0u;
   __shared__ float s_vmax[kPoolThreads / 64];
   __shared__ double s_s[kPoolThreads / 64], s_t[kPoolThreads / 64];
   __shared__ unsigned int s_last;
@@ -1080,10 +1135,13 @@ poolstat_kernel(const float* __restrict__ s_raw, long long n, int w, int pool_ha
       scores[(long long)g * n + p] = s;
       acc_s += (double)s;
       if (s > 0.0f) acc_t += (double)s * (double)logf(s);
+      if (sel_hist0 != nullptr) digit0_count(s_bins, s, run_digit, run_len);
     } else if (p < n) {
       scores[(long long)g * n + p] = INFINITY;
+      if (sel_hist0 != nullptr) digit0_count(s_bins, INFINITY, run_digit, run_len);
     }
   }
+  if (sel_hist0 != nullptr) digit0_flush<kPoolThreads>(s_bins, run_digit, run_len, sel_hist0);
   entropy_finish<kPoolThreads>(acc_s, acc_t, ent_part, counters, gridDim.x * gridDim.y,
                                blockIdx.y * gridDim.x + blockIdx.x, (double)gridDim.y * (double)n_prefix,
                                layer_stat, s_s, s_t, &s_last);
@@ -1212,6 +1270,7 @@ __global__ void __launch_bounds__(256) unit_vnorm_kernel(const SweepArgs a) {
   const int i = blockIdx.x * 256 + threadIdx.x;
   if (i < a.H_kv * sq.vnorm_blocks) vnorm_part[i] = 1.0f;
   for (int j = i; j < kCtlUnitA + a.H_kv * sq.blocks_x; j += (int)gridDim.x * 256) counters[j] = 0u;
+  if (blockIdx.x == 0) clear_selection_region(a, (int)blockIdx.z, 256);
 }
 
 int32_t launch_unit_vnorm(const lava_layer_desc& d, const SweepArgs& a, int max_vnorm_blocks, hipStream_t s) {
@@ -1316,12 +1375,13 @@ int32_t launch_scores(const lava_layer_desc& d, const SweepArgs& a, int max_bloc
 
 int32_t launch_poolstat(const lava_layer_desc& d, int64_t n, const float* s_raw,
                         const float* vnorm_part, int vnorm_blocks, float* scores, float* vbar,
-                        float* layer_stat, double2* ent_part, uint32_t* counters, hipStream_t s) {
+                        float* layer_stat, double2* ent_part, uint32_t* counters, unsigned int* sel_hist0,
+                        hipStream_t s) {
   const dim3 grid(pool_blocks(d, n), d.n_kv_heads), block(kPoolThreads);
   ProfScope ps(KID_POOLSTAT, s);
   hipLaunchKernelGGL(poolstat_kernel, grid, block, 0, s, s_raw, (long long)n, d.window,
                      d.pool_kernel / 2, d.score_kind == LAVA_SCORE_TOKEN_NORM ? 1 : 0, vnorm_part, vnorm_blocks, scores, vbar, layer_stat, ent_part,
-                     counters);
+                     counters, sel_hist0);
   return launch_status();
 }
 

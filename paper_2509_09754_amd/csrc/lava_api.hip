@@ -85,6 +85,8 @@ int32_t check_select_problem(int32_t n_heads, const lava_select_problem& p) {
   if (p.total_entries >= (int64_t)1 << 31) return LAVA_ERR_SHAPE;
   if (p.seg_offsets == nullptr && p.total_entries % n_heads != 0) return LAVA_ERR_SHAPE;
   if (p.budget < 0 || p.budget > p.total_entries) return LAVA_ERR_BUDGET;
+  // a prepared workspace holds the histogram of a whole score array as lava_window_scores_primed wrote it
+  if (p.primed != 0 && (p.seg_offsets != nullptr || p.in_offset_dev != nullptr)) return LAVA_ERR_INVALID_ARG;
   return LAVA_OK;
 }
 
@@ -141,10 +143,13 @@ size_t lava_window_scores_workspace_bytes(const lava_layer_desc* desc, int32_t b
   return make_sweep_plan(*desc, max_n).fused_pool ? region * (size_t)batch : region;
 }
 
-int32_t lava_window_scores(const lava_layer_desc* desc, int32_t batch, const int64_t* seq_lens,
-                           const void* q_win, const void* k, const void* v, const float* lse,
-                           float* scores, float* vbar, float* layer_stat, void* workspace,
-                           size_t workspace_bytes, void* hip_stream) {
+// lava_window_scores, optionally preparing a selection workspace (select_ws != null) for the selections
+// that will rank the scores it writes.
+static int32_t window_scores(const lava_layer_desc* desc, int32_t batch, const int64_t* seq_lens,
+                             const void* q_win, const void* k, const void* v, const float* lse,
+                             float* scores, float* vbar, float* layer_stat, void* workspace,
+                             size_t workspace_bytes, void* select_ws, size_t select_ws_bytes, bool primed,
+                             void* hip_stream) {
   int32_t st = check_desc(desc);
   if (st != LAVA_OK) return st;
   if (batch < 1 || seq_lens == nullptr || q_win == nullptr || k == nullptr || v == nullptr ||
@@ -165,10 +170,22 @@ int32_t lava_window_scores(const lava_layer_desc* desc, int32_t batch, const int
   if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 ||
       workspace_bytes < need)
     return LAVA_ERR_WORKSPACE;
+  SelectWorkspace sel_layout = {};
+  if (primed) {
+    if ((int64_t)desc->n_kv_heads * max_n >= (int64_t)1 << 31) return LAVA_ERR_SHAPE;
+    sel_layout = make_select_workspace((int64_t)desc->n_kv_heads * max_n);
+    if (select_ws == nullptr || (reinterpret_cast<uintptr_t>(select_ws) % kAlign) != 0 ||
+        select_ws_bytes < sel_layout.bytes * (size_t)batch)
+      return LAVA_ERR_WORKSPACE;
+  }
 
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   discard_stale_error();
   SweepArgs a;
+  a.sel_ws = primed ? static_cast<char*>(select_ws) : nullptr;
+  a.sel_stride = sel_layout.bytes;
+  a.sel_off_hist = sel_layout.off_hist;
+  a.sel_off_state = sel_layout.off_state;
   a.q_win = q_win;
   a.k = k;
   a.v = v;
@@ -262,11 +279,31 @@ int32_t lava_window_scores(const lava_layer_desc* desc, int32_t batch, const int
                            reinterpret_cast<const float*>(reg + a.off_vnorm_part), sq.vnorm_blocks,
                            scores + (size_t)d.n_kv_heads * sq.tok, vbar + (size_t)b0 * d.n_kv_heads,
                            layer_stat + b0, reinterpret_cast<double2*>(reg + a.off_ent_part),
-                           reinterpret_cast<uint32_t*>(reg + a.off_counter), s);
+                           reinterpret_cast<uint32_t*>(reg + a.off_counter),
+                           a.sel_ws ? reinterpret_cast<unsigned int*>(a.sel_ws + (size_t)b0 * a.sel_stride + a.sel_off_hist)
+                                    : nullptr,
+                           s);
       if (st != LAVA_OK) return st;
     }
   }
   return LAVA_OK;
+}
+
+int32_t lava_window_scores(const lava_layer_desc* desc, int32_t batch, const int64_t* seq_lens,
+                           const void* q_win, const void* k, const void* v, const float* lse,
+                           float* scores, float* vbar, float* layer_stat, void* workspace,
+                           size_t workspace_bytes, void* hip_stream) {
+  return window_scores(desc, batch, seq_lens, q_win, k, v, lse, scores, vbar, layer_stat, workspace, workspace_bytes,
+                       nullptr, 0, false, hip_stream);
+}
+
+int32_t lava_window_scores_primed(const lava_layer_desc* desc, int32_t batch, const int64_t* seq_lens,
+                                  const void* q_win, const void* k, const void* v, const float* lse,
+                                  float* scores, float* vbar, float* layer_stat, void* workspace,
+                                  size_t workspace_bytes, void* select_workspace, size_t select_workspace_bytes,
+                                  void* hip_stream) {
+  return window_scores(desc, batch, seq_lens, q_win, k, v, lse, scores, vbar, layer_stat, workspace, workspace_bytes,
+                       select_workspace, select_workspace_bytes, true, hip_stream);
 }
 
 int32_t lava_layer_budgets(int32_t batch, int32_t n_layers, const float* e, const int64_t* total,
@@ -318,7 +355,17 @@ int32_t lava_select_topk(int32_t n_heads, const float* scores, const int64_t* se
                          void* hip_stream) {
   if (n_heads < 1) return LAVA_ERR_INVALID_ARG;
   const lava_select_problem p = {scores,      seg_offsets,  total_entries, budget,     budget_dev,
-                                 head_counts, head_offsets, kept_idx,      kept_scores, nullptr, nullptr, nullptr};
+                                 head_counts, head_offsets, kept_idx,      kept_scores, nullptr, nullptr, nullptr, 0};
+  return lava_select_topk_batch(n_heads, 1, &p, total_entries, workspace, workspace_bytes, hip_stream);
+}
+
+int32_t lava_select_topk_primed(int32_t n_heads, const float* scores, int64_t total_entries, int64_t budget,
+                                const int64_t* budget_dev, int32_t* head_counts, int64_t* head_offsets,
+                                int32_t* kept_idx, float* kept_scores, void* workspace, size_t workspace_bytes,
+                                void* hip_stream) {
+  if (n_heads < 1) return LAVA_ERR_INVALID_ARG;
+  const lava_select_problem p = {scores,      nullptr,      total_entries, budget,      budget_dev,
+                                 head_counts, head_offsets, kept_idx,      kept_scores, nullptr, nullptr, nullptr, 1};
   return lava_select_topk_batch(n_heads, 1, &p, total_entries, workspace, workspace_bytes, hip_stream);
 }
 
@@ -443,12 +490,12 @@ int32_t lava_cascade_step(const lava_layer_desc* desc, int32_t layer, int64_t n,
       const int64_t* offs_cur = S.head_offsets[a] + (size_t)t * H1;
       const int64_t* start_cur = S.layer_start[a] + t;
       sel[t] = {S.scores[a], offs_cur, bound,      bound,       budgets + t, counts,
-                offs_new,    S.kept_idx, S.scores[b], start_cur, start_new, S.error};
+                offs_new,    S.kept_idx, S.scores[b], start_cur, start_new, S.error, 0};
       cmp[t] = {S.capacity, offs_cur, S.k[a], S.v[a], S.pos[a],  offs_new,  S.kept_idx,
                 S.capacity, S.k[b],   S.v[b], S.pos[b], start_cur, start_new};
     } else {
       sel[t] = {scores_new, nullptr,    dense,       bound,   budgets + t, counts,
-                offs_new,   S.kept_idx, S.scores[b], nullptr, start_new, S.error};
+                offs_new,   S.kept_idx, S.scores[b], nullptr, start_new, S.error, 0};
       cmp[t] = {n,          nullptr, k_new,  v_new,    nullptr, offs_new, S.kept_idx,
                 S.capacity, S.k[b],  S.v[b], S.pos[b], nullptr, start_new};
     }

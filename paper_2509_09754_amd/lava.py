@@ -24,6 +24,7 @@ LAVA_SCORE_LAVA, LAVA_SCORE_ATTENTION, LAVA_SCORE_TOKEN_NORM = 0, 1, 2
 
 EXPORTS = [
     "lava_status_string", "lava_set_tuning", "lava_get_tuning", "lava_window_scores_workspace_bytes", "lava_window_scores",
+    "lava_window_scores_primed", "lava_select_topk_primed",
     "lava_layer_budgets", "lava_select_workspace_bytes", "lava_select_topk", "lava_select_status",
     "lava_select_topk_static",
     "lava_select_batch_workspace_bytes", "lava_select_topk_batch", "lava_select_batch_status",
@@ -91,6 +92,10 @@ def _load() -> ctypes.CDLL:
     lib.lava_window_scores_workspace_bytes.argtypes = [dp, i32, i64]
     lib.lava_window_scores.restype = i32
     lib.lava_window_scores.argtypes = [dp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+    lib.lava_window_scores_primed.restype = i32
+    lib.lava_window_scores_primed.argtypes = [dp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, sz, vp]
+    lib.lava_select_topk_primed.restype = i32
+    lib.lava_select_topk_primed.argtypes = [i32, vp, i64, i64, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lava_layer_budgets.restype = i32
     lib.lava_layer_budgets.argtypes = [i32, i32, vp, vp, vp, vp, vp, i32, vp]
     lib.lava_select_workspace_bytes.restype = sz
@@ -199,8 +204,9 @@ def lava_window_scores_workspace_bytes(desc: LayerDesc, batch: int, total_tokens
 
 def lava_window_scores(desc: LayerDesc, seq_lens: Sequence[int], q_win: torch.Tensor, k: torch.Tensor,
                        v: torch.Tensor, lse: Optional[torch.Tensor] = None, scores=None, vbar=None,
-                       layer_stat=None, workspace=None, stream=None):
-    """Scores [sum_b H_kv * N_b] (per sequence [H_kv][N_b]), vbar [batch, H_kv], layer_stat [batch]."""
+                       layer_stat=None, workspace=None, stream=None, select_workspace=None):
+    """Scores [sum_b H_kv * N_b] (per sequence [H_kv][N_b]), vbar [batch, H_kv], layer_stat [batch].
+    With select_workspace the call is lava_window_scores_primed."""
     lens = np.ascontiguousarray(np.asarray(seq_lens, dtype=np.int64))
     batch, total = int(lens.shape[0]), int(lens.sum())
     dev = k.device
@@ -223,6 +229,13 @@ def lava_window_scores(desc: LayerDesc, seq_lens: Sequence[int], q_win: torch.Te
     if workspace is None:
         nbytes = lava_window_scores_workspace_bytes(desc, batch, total)
         workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
+    if select_workspace is not None:
+        st = lib.lava_window_scores_primed(ctypes.byref(desc), batch, lens.ctypes.data_as(ctypes.c_void_p), _ptr(q_win),
+                                           _ptr(k), _ptr(v), _ptr(lse), _ptr(scores), _ptr(vbar), _ptr(layer_stat),
+                                           _ptr(workspace), workspace.numel(), _ptr(select_workspace),
+                                           select_workspace.numel(), _stream(stream))
+        _check(st, "lava_window_scores_primed")
+        return scores, vbar, layer_stat
     st = lib.lava_window_scores(ctypes.byref(desc), batch, lens.ctypes.data_as(ctypes.c_void_p), _ptr(q_win),
                                 _ptr(k), _ptr(v), _ptr(lse), _ptr(scores), _ptr(vbar), _ptr(layer_stat),
                                 _ptr(workspace), workspace.numel(), _stream(stream))
@@ -266,7 +279,8 @@ def lava_select_workspace_bytes(total_entries: int) -> int:
 def lava_select_topk(n_heads: int, scores: torch.Tensor, budget: int, seg_offsets: Optional[torch.Tensor] = None,
                      budget_dev: Optional[torch.Tensor] = None, total_entries: Optional[int] = None,
                      head_counts=None, head_offsets=None, kept_idx=None, kept_scores=None,
-                     want_scores: bool = True, workspace=None, stream=None):
+                     want_scores: bool = True, workspace=None, stream=None, primed: bool = False):
+    """primed: `workspace` was prepared by lava_window_scores(select_workspace=workspace) for these scores."""
     _dev(scores, "scores", torch.float32)
     total = scores.numel() if total_entries is None else int(total_entries)
     dev = scores.device
@@ -284,6 +298,14 @@ def lava_select_topk(n_heads: int, scores: torch.Tensor, budget: int, seg_offset
         kept_scores = torch.empty(max(int(budget), 1), dtype=torch.float32, device=dev)
     if workspace is None:
         workspace = torch.empty(max(lava_select_workspace_bytes(total), 256), dtype=torch.uint8, device=dev)
+    if primed:
+        if seg_offsets is not None:
+            raise ValueError("a prepared workspace serves equal segments only")
+        st = lib.lava_select_topk_primed(n_heads, _ptr(scores), total, int(budget), _ptr(budget_dev),
+                                         _ptr(head_counts), _ptr(head_offsets), _ptr(kept_idx), _ptr(kept_scores),
+                                         _ptr(workspace), workspace.numel(), _stream(stream))
+        _check(st, "lava_select_topk_primed")
+        return head_counts, head_offsets, kept_idx, kept_scores
     st = lib.lava_select_topk(n_heads, _ptr(scores), _ptr(seg_offsets), total, int(budget), _ptr(budget_dev),
                               _ptr(head_counts), _ptr(head_offsets), _ptr(kept_idx), _ptr(kept_scores),
                               _ptr(workspace), workspace.numel(), _stream(stream))
@@ -325,6 +347,7 @@ class SelectProblem(ctypes.Structure):
         ("budget", ctypes.c_int64), ("budget_dev", ctypes.c_void_p), ("head_counts", ctypes.c_void_p),
         ("head_offsets", ctypes.c_void_p), ("kept_idx", ctypes.c_void_p), ("kept_scores", ctypes.c_void_p),
         ("in_offset_dev", ctypes.c_void_p), ("out_offset_dev", ctypes.c_void_p), ("error_dev", ctypes.c_void_p),
+        ("primed", ctypes.c_int32),
     ]
 
 
@@ -345,7 +368,7 @@ def _addr(t: Optional[torch.Tensor]):
 
 def select_problem(scores, budget, head_counts, head_offsets, kept_idx, kept_scores=None, seg_offsets=None,
                    budget_dev=None, total_entries=None, in_offset_dev=None, out_offset_dev=None,
-                   error_dev=None) -> SelectProblem:
+                   error_dev=None, primed=False) -> SelectProblem:
     """One row of the table of lava_select_topk_batch from device tensors (the caller keeps them alive)."""
     _dev(scores, "scores", torch.float32), _dev(head_counts, "head_counts", torch.int32)
     _dev(head_offsets, "head_offsets", torch.int64), _dev(kept_idx, "kept_idx", torch.int32)
@@ -357,7 +380,7 @@ def select_problem(scores, budget, head_counts, head_offsets, kept_idx, kept_sco
     total = scores.numel() if total_entries is None else int(total_entries)
     return SelectProblem(_addr(scores), _addr(seg_offsets), total, int(budget), _addr(budget_dev),
                          _addr(head_counts), _addr(head_offsets), _addr(kept_idx), _addr(kept_scores),
-                         _addr(in_offset_dev), _addr(out_offset_dev), _addr(error_dev))
+                         _addr(in_offset_dev), _addr(out_offset_dev), _addr(error_dev), 1 if primed else 0)
 
 
 def compact_problem(desc: LayerDesc, src_rows, k_src, v_src, head_offsets, kept_idx, capacity, k_out, v_out,

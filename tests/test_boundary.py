@@ -101,6 +101,14 @@ def test_window_scores_argument_errors():
     assert _ws(good, [4096], ws=None) == lava.LAVA_ERR_WORKSPACE
     assert _ws(good, [4096], ws_bytes=16) == lava.LAVA_ERR_WORKSPACE
     assert _ws(good, [4096], ws=ctypes.c_void_p(0x10010)) == lava.LAVA_ERR_WORKSPACE
+    lens = np.asarray([4096, 9000], dtype=np.int64)
+    prm = lambda sws, swsb: lava.lib.lava_window_scores_primed(
+        ctypes.byref(good), 2, lens.ctypes.data_as(ctypes.c_void_p), FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, FAKE,
+        1 << 40, sws, swsb, None)
+    need = lava.lava_select_batch_workspace_bytes(2, 8 * 9000)  # one region per sequence, sized for the longest
+    assert prm(None, need) == lava.LAVA_ERR_WORKSPACE
+    assert prm(FAKE, need - 1) == lava.LAVA_ERR_WORKSPACE
+    assert prm(ctypes.c_void_p(0x10010), need) == lava.LAVA_ERR_WORKSPACE
     assert lava.lava_window_scores_workspace_bytes(good, 1, 4096) > 8 * 4064 * 4
     assert lava.lava_window_scores_workspace_bytes(_desc(head_dim=100), 1, 4096) == 0
 
@@ -129,6 +137,11 @@ def test_select_and_compact_argument_errors():
     assert call(8, 1024, 10, sc=None) == lava.LAVA_ERR_INVALID_ARG
     assert call(8, 1024, 10, ws=None) == lava.LAVA_ERR_WORKSPACE
     assert call(8, 1024, 10, wsb=8) == lava.LAVA_ERR_WORKSPACE
+    primed = lambda nh, total, budget, ws=FAKE, wsb=big: L.lava_select_topk_primed(
+        nh, FAKE, total, budget, None, FAKE, FAKE, FAKE, None, ws, wsb, None)
+    assert primed(8, 1001, 10) == lava.LAVA_ERR_SHAPE           # a prepared workspace serves equal segments
+    assert primed(8, 1024, 2000) == lava.LAVA_ERR_BUDGET
+    assert primed(8, 1024, 10, wsb=8) == lava.LAVA_ERR_WORKSPACE
     assert lava.lava_select_workspace_bytes(1 << 20) >= 3 * 2048 * 4
     assert lava.lava_select_workspace_bytes(0) == 0
     assert L.lava_select_status(None, 1024, None) == lava.LAVA_ERR_INVALID_ARG
@@ -250,6 +263,8 @@ def test_batch_select_and_compact_argument_errors():
     L = lava.lib
     big = 1 << 40
     good = lava.SelectProblem(0x10000, None, 8 * 1024, 100, None, 0x10000, 0x10000, 0x10000, None, None, None)
+    seg_primed = lava.SelectProblem(0x10000, 0x10000, 8 * 1024, 100, None, 0x10000, 0x10000, 0x10000, None, None, None,
+                                    None, 1)
 
     def sel(problems, nh=8, widest=8 * 1024, ws=FAKE, wsb=big):
         table = (lava.SelectProblem * max(len(problems), 1))(*problems)
@@ -268,6 +283,7 @@ def test_batch_select_and_compact_argument_errors():
     assert sel([good, changed(total_entries=1001)]) == lava.LAVA_ERR_SHAPE         # equal segments
     assert sel([good, changed(total_entries=16 * 1024)]) == lava.LAVA_ERR_SHAPE    # wider than the stated maximum
     assert sel([good], nh=65) == lava.LAVA_ERR_SHAPE
+    assert sel([good, seg_primed]) == lava.LAVA_ERR_INVALID_ARG                    # prepared + explicit segments
     assert sel([good, good], ws=None) == lava.LAVA_ERR_WORKSPACE
     one = lava.lava_select_workspace_bytes(8 * 1024)
     assert lava.lava_select_batch_workspace_bytes(3, 8 * 1024) == 3 * one

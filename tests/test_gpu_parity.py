@@ -610,3 +610,81 @@ def test_stack_dynamic_layer_budgets(lava):
         a = kept_set(counts.cpu().numpy(), offs.cpu().numpy(), idx.cpu().numpy(), n)
         b = kept_set(rc, ro, ri, n)
         assert len(a & b) / max(1, int(got_b[l])) >= 0.999
+
+
+# ------------------------------------------------------------------------------ scores that prepare their selection
+PRIMED_CASES = [
+    ("cfg1", synth.config(1), "auto", "auto"),
+    ("cfg2-9k-wide", synth.config(2, n=9000 + 5, budget=8 * 64), "wide", "separate"),
+    ("cfg2-9k-narrow", synth.config(2, n=9000 + 5, budget=8 * 64), "narrow", "separate"),
+    ("cfg2-20k-persistent", synth.config(2, n=20000 + 13, budget=8 * 300), "auto", "persistent"),
+    ("bf16-G8-two-chunks", synth.LayerShape(16, 2, 128, 2100, 32, "bf16", 300), "auto", "auto"),
+    ("f32-d128-G4", synth.LayerShape(8, 2, 128, 1111, 32, "f32", 300), "auto", "auto"),
+    ("tiny-prefix", synth.LayerShape(8, 2, 64, 8 + 3, 8, "f32", 2 * 8 + 2, heavy_count=0), "auto", "auto"),
+]
+
+
+@pytest.mark.parametrize("name,sh,shape,schedule", PRIMED_CASES, ids=[c[0] for c in PRIMED_CASES])
+def test_scores_that_prepare_their_selection(lava, name, sh, shape, schedule, tuning):
+    """lava_window_scores_primed + lava_select_topk_primed against the plain pair: the scores, the statistic and
+    every output of the selection are identical bit for bit (the prepared histogram is the one the selection
+    would have built), for several budgets, with the LAVa score and the per-token value-norm score; and
+    the selection equals the oracle's on those scores."""
+    say(f"primed scores + selection, {name}")
+    tuning(sweep_shape=shape, sweep_schedule=schedule)
+    inp = synth.gen_layer(sh, 9)
+    Hkv, n = sh.n_kv_heads, sh.n
+    for kind in (lava.LAVA_SCORE_LAVA, lava.LAVA_SCORE_TOKEN_NORM):
+        desc = lava.LayerDesc.make(sh.n_q_heads, Hkv, sh.head_dim, sh.window, sh.dtype, pool_kernel=sh.pool_kernel,
+                                   score_kind=kind)
+        q, k, v = (lava.to_device(a, sh.dtype) for a in (inp.q_win, inp.k, inp.v))
+        s0, vb0, e0 = lava.lava_window_scores(desc, [n], q, k, v)
+        ws = torch.full((max(lava.lava_select_workspace_bytes(Hkv * n), 256),), 0xAB, dtype=torch.uint8, device="cuda")
+        for budget in (Hkv * sh.window, sh.budget, Hkv * n - 1):
+            want = lava.lava_select_topk(Hkv, s0, budget)
+            s1, vb1, e1 = lava.lava_window_scores(desc, [n], q, k, v, select_workspace=ws)
+            got = lava.lava_select_topk(Hkv, s1, budget, workspace=ws, primed=True)
+            torch.cuda.synchronize()
+            assert torch.equal(s0.view(torch.int32), s1.view(torch.int32)) and torch.equal(vb0, vb1) and torch.equal(e0, e1)
+            for a, b in zip(got, want):
+                assert torch.equal(a.view(torch.int32) if a.dtype == torch.float32 else a,
+                                   b.view(torch.int32) if b.dtype == torch.float32 else b), (kind, budget)
+            assert lava.lava_select_status(ws, Hkv * n) == lava.LAVA_OK
+        rc, ro, ri, _ = O.select_topk(s0.cpu().numpy().astype(np.float64), offsets_uniform(Hkv, n), budget)
+        assert np.array_equal(got[0].cpu().numpy(), rc) and np.array_equal(got[2].cpu().numpy()[:budget], ri)
+
+
+def test_primed_ragged_batch_and_mixed_table(lava):
+    """A ragged batch whose score call prepares one region per sequence; the table of selections mixes
+    prepared problems with an unprepared one (another array, own region): same results as the plain calls."""
+    say("primed scores + selection table, ragged batch")
+    shapes = [synth.config(2, n=n, budget=8 * 64) for n in (1500, 16416, 33 + 32, 2777)]
+    inps = [synth.gen_layer(s, 60 + i) for i, s in enumerate(shapes)]
+    sh0 = shapes[0]
+    Hkv = sh0.n_kv_heads
+    desc = lava.LayerDesc.make(sh0.n_q_heads, Hkv, sh0.head_dim, sh0.window, sh0.dtype)
+    q = torch.cat([lava.to_device(i.q_win, "bf16").reshape(-1) for i in inps])
+    k = torch.cat([lava.to_device(i.k, "bf16").reshape(-1) for i in inps])
+    v = torch.cat([lava.to_device(i.v, "bf16").reshape(-1) for i in inps])
+    lens = [s.n for s in shapes]
+    widest = Hkv * max(lens)
+    nb = len(lens)
+    extra = torch.from_numpy(synth.random_scores(Hkv, 3000, 5).ravel()).cuda()
+    ws = torch.full((lava.lava_select_batch_workspace_bytes(nb + 1, widest),), 0xCD, dtype=torch.uint8, device="cuda")
+    scores, _, _ = lava.lava_window_scores(desc, lens, q, k, v, select_workspace=ws)
+    starts = np.concatenate([[0], np.cumsum(lens)]) * Hkv
+    B = [Hkv * 40, Hkv * 200, Hkv * 33, Hkv * 100, 777]
+    arrays = [scores[int(starts[b]): int(starts[b + 1])] for b in range(nb)] + [extra]
+    outs = [(torch.empty(Hkv, dtype=torch.int32, device="cuda"), torch.empty(Hkv + 1, dtype=torch.int64, device="cuda"),
+             torch.empty(B[i], dtype=torch.int32, device="cuda"), torch.empty(B[i], dtype=torch.float32, device="cuda"))
+            for i in range(nb + 1)]
+    probs = [lava.select_problem(arrays[i], B[i], *outs[i], primed=i < nb) for i in range(nb + 1)]
+    lava.lava_select_topk_batch(Hkv, probs, widest, workspace=ws)
+    torch.cuda.synchronize()
+    assert lava.lava_select_batch_status(ws, nb + 1, widest) == lava.LAVA_OK
+    for i in range(nb + 1):
+        want = lava.lava_select_topk(Hkv, arrays[i], B[i])
+        torch.cuda.synchronize()
+        for a, b in zip(outs[i], want):
+            assert torch.equal(a.view(torch.int32) if a.dtype == torch.float32 else a,
+                               b.view(torch.int32) if b.dtype == torch.float32 else b), i
