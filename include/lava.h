@@ -68,9 +68,9 @@ typedef enum { LAVA_SCORE_LAVA = 0, LAVA_SCORE_ATTENTION = 1, LAVA_SCORE_TOKEN_N
 /* One layer of one model.  Plain data, read during the call only. */
 typedef struct lava_layer_desc {
   int32_t n_q_heads;    /* H                                                                  */
-  int32_t n_kv_heads;   /* H_kv; H % H_kv == 0 and G = H / H_kv <= 8                          */
+  int32_t n_kv_heads;   /* H_kv <= 64; H % H_kv == 0 and G = H / H_kv <= 16 (decode step: <= 8)   */
   int32_t head_dim;     /* d_h: 64 or 128                                                     */
-  int32_t window;       /* w, 1 <= w <= 32: number of observation-window query rows           */
+  int32_t window;       /* w, 1 <= w <= 64: number of observation-window query rows           */
   int32_t pool_kernel;  /* odd, 1..15; the paper uses 7 (Sec. 5.1); 1 disables pooling        */
   int32_t dtype;        /* lava_dtype of q_win, k, v, k_out, v_out                            */
   float softmax_scale;  /* logits are scale * <q, k>; 0 selects 1 / sqrt(d_h) (Sec. 2)        */

@@ -66,8 +66,8 @@ constexpr int kTileKeys = 32;        // keys per MFMA tile
 constexpr int kMaxChunkHeads = 4;    // query heads a wavefront keeps in registers
 
 struct SweepPlan {
-  int chunk_heads;     // GT: heads per chunk (<= kMaxChunkHeads; <= 2 for f32 with d_h 128)
-  int n_chunks;        // ceil(G / GT)
+  int chunk_heads;     // GT: row blocks (32 window rows of one head) per chunk (<= kMaxChunkHeads; <= 2 for f32 with d_h 128)
+  int n_chunks;        // ceil(G * blocks per head / GT)
   int blocks_x;        // workgroups along the key axis per (KV head, chunk)
   int tiles_per_block; // key tiles per workgroup
   int vnorm_blocks;    // workgroups per KV head of the value-norm kernel
@@ -81,6 +81,7 @@ struct SweepPlan {
 SweepPlan make_sweep_plan(const lava_layer_desc& d, int64_t n, int64_t batch_tokens = 0, bool narrow = false);
 bool sweep_has_narrow_shape(const lava_layer_desc& d);
 int sweep_device_wgs();   // compute units of the current device
+int sweep_blocks_per_head(const lava_layer_desc& d);   // 32-row blocks a head's window rows take: 1 or 2
 
 // Workspace of lava_window_scores for one sequence (all offsets 256-byte aligned).
 struct ScoreWorkspace {
@@ -123,7 +124,8 @@ struct SweepArgs {
   float* layer_stat;         // [batch]
   char* ws;
   size_t off_stat_part, off_vnorm_part, off_sraw, off_ent_part, off_counter;   // inside a sequence's region
-  int H, H_kv, w, G, n_chunks, pool_half;
+  int H, H_kv, w, G, n_chunks, pool_half;   // G: row blocks of 32 window rows per KV group = (H / H_kv) * bph
+  int bph;                   // row blocks per query head: 1 (w <= 32) or 2
   int token_norm;            // value factor per token: vnorm leaves ||V[g, i]||_1 in scores[g][i], the pooling step multiplies by it
   float c2;
   int first_seq;             // index in the batch of s[0]

@@ -112,7 +112,7 @@ __device__ __forceinline__ void entropy_finish(double acc_s, double acc_t, doubl
 // order, and results must not depend on timing.
 template <int DT, int D, int GT, int WAVES, int STAGES>
 __device__ __forceinline__ void stats_tiles(const TileDma<DT, D>& dma, const FragReader<DT, D>& frags,
-                                            const char* __restrict__ kg, long long n, int w, float c2,
+                                            const char* __restrict__ kg, long long n, int w, int bph, float c2,
                                             long long first, int cnt, u32x4* ring,
                                             const u32x4 (&qf)[GT][Tile<DT, D>::kSteps], int lane,
                                             float (&m_run)[GT], float (&z_run)[GT]) {
@@ -155,9 +155,12 @@ __device__ __forceinline__ void stats_tiles(const TileDma<DT, D>& dma, const Fra
     } else {
       // tile touches the window or the end of the sequence: mask what a row may not see
       const int rel0 = (int)(key0 - (n - w));                // position of the tile's first key relative to N - w
-      const int row_limit = r < w - 1 ? r : w - 1;            // row r sees relative positions <= min(r, w - 1)
 #pragma unroll
       for (int t = 0; t < GT; ++t) {
+        // window row of this lane in block t (a chunk starts at an even block when heads have two blocks);
+        // row rr sees relative positions <= min(rr, w - 1)
+        const int rr = r + ((bph == 2 && (t & 1)) ? 32 : 0);
+        const int row_limit = rr < w - 1 ? rr : w - 1;
         f32x16 acc = dot_tile<DT, D, true>(kf, qf[t]);
 #pragma unroll
         for (int v = 0; v < 16; ++v)
@@ -259,10 +262,10 @@ stats_kernel(const SweepArgs a) {
   // than the set-up gains.)  Both are in before the loop: otherwise the compiler, which cannot count
   // the ring's loads across iterations, waits for everything in flight before each tile's products.
   u32x4 qf[GT][T::kSteps];
-  load_q<DT, D, GT>(q_win, h0, nh, w, lane, qf);
+  load_q<DT, D, GT>(q_win, h0, nh, w, a.bph, lane, qf);
   wait_vmcnt<0>();
   float m_run[GT], z_run[GT];
-  stats_tiles<DT, D, GT, kWaves, kStages>(dma, frags, kg, n, w, c2, first, cnt, ring, qf, lane, m_run, z_run);
+  stats_tiles<DT, D, GT, kWaves, kStages>(dma, frags, kg, n, w, a.bph, c2, first, cnt, ring, qf, lane, m_run, z_run);
   float2 mine;
   if (stats_merge_waves<GT, kWaves>(m_run, z_run, c2, lane, wave, s_red, mine))
     stat_part[((long long)blockIdx.y * sq.blocks_x + blockIdx.x) * (GT * 32) + threadIdx.x] = mine;
@@ -357,15 +360,16 @@ __device__ __forceinline__ void merge_partials(const float2* __restrict__ part, 
 // +inf for padding rows (their exponentials vanish).
 template <int GT, int THREADS>
 __device__ __forceinline__ void write_bias(const float2* s_merge, const float* __restrict__ lse, int h0, int nh, int w,
-                                           float c2, float* s_bias) {
+                                           int bph, float c2, float* s_bias) {
   constexpr int kRows = GT * 32;
   constexpr int kSlices = THREADS / kRows;
   if (threadIdx.x < kRows) {
-    const int t = threadIdx.x >> 5, rr = threadIdx.x & 31;
+    const int t = threadIdx.x >> 5;
+    const int head = (h0 + t) / bph, rr = ((h0 + t) % bph) * 32 + (int)(threadIdx.x & 31);   // head and window row of this block row
     float bias = INFINITY;
     if (t < nh && rr < w) {
       if (lse != nullptr) {
-        bias = lse[(long long)(h0 + t) * w + rr] * kLog2e;
+        bias = lse[(long long)head * w + rr] * kLog2e;
       } else {
         float m = -INFINITY, z = 0.0f;
 #pragma unroll
@@ -396,7 +400,7 @@ __device__ __forceinline__ void scores_tiles(const TileDma<DT, D>& dma, const Fr
                                              bool halo_right, int n_jobs, int (&fifo)[STAGES], u32x4* ring,
                                              unsigned int* next_job, const float* s_bias, float* s_span,
                                              const u32x4 (&qf)[GT][Tile<DT, D>::kSteps], int lane,
-                                             float* __restrict__ raw_head, int n_chunks) {
+                                             float* __restrict__ raw_head, int n_chunks, int bph) {
   using T = Tile<DT, D>;
   auto job_tile = [&](int j) -> long long {
     if (j < n_own) return t_begin + j;
@@ -449,7 +453,7 @@ __device__ __forceinline__ void scores_tiles(const TileDma<DT, D>& dma, const Fr
     u32x4 kf[T::kSteps];
     frags.read(ring_addr + (it % STAGES) * T::kTileBytes, kf);
 
-    float best = 0.0f;
+    float best = 0.0f, pair = 0.0f;
     f32x16 acc = dot_tile<DT, D, false>(kf, qf[0]);
 #pragma unroll
     for (int t = 0; t < GT; ++t) {
@@ -466,7 +470,12 @@ __device__ __forceinline__ void scores_tiles(const TileDma<DT, D>& dma, const Fr
         ps += fast_exp2(fmaf(acc[4 * jj + 3], c2, -__uint_as_float(bb[jj].w)));
       }
       ps += __shfl_xor(ps, 32);
-      best = fmaxf(best, ps);
+      if (bph == 2) {                    // uniform: a head's window mean is the sum over its two row blocks
+        if (t & 1) best = fmaxf(best, pair + ps);
+        else pair = ps;
+      } else {
+        best = fmaxf(best, ps);
+      }
       acc = nxt;
     }
     if constexpr (FUSED) {
@@ -671,13 +680,13 @@ scores_kernel(const SweepArgs a) {
   // the query rows go through the last stage of the first GT wavefronts' rings (idle until the loop
   // starts); their loads are in flight together with the normaliser partials below
   static_assert(kWaves >= GT, "one staging buffer per head");
-  stage_q<DT, D, GT, kThreads>(q_win, h0, nh, w, [&](int t) { return &s_tile[t][kStages - 1][0]; });
+  stage_q<DT, D, GT, kThreads>(q_win, h0, nh, w, a.bph, [&](int t) { return &s_tile[t][kStages - 1][0]; });
 
   // exponent bias of every (head, row), from the statistics partials or the caller's log-sum-exp
   merge_partials<GT, kThreads, false>(stat_part + (long long)blockIdx.y * stat_blocks * kRows, stat_blocks,
                                       lse != nullptr, c2, s_merge);
   __syncthreads();
-  write_bias<GT, kThreads>(s_merge, lse, h0, nh, w, c2, s_bias);
+  write_bias<GT, kThreads>(s_merge, lse, h0, nh, w, a.bph, c2, s_bias);
   u32x4 qf[GT][T::kSteps];
 #pragma unroll
   for (int t = 0; t < GT; ++t) frags.read(lds_addr(&s_tile[t][kStages - 1][0]), qf[t]);
@@ -685,7 +694,7 @@ scores_kernel(const SweepArgs a) {
 
   scores_tiles<DT, D, GT, kWaves, kStages, FUSED>(dma, frags, kg, n, n_prefix, c2, t_begin, t_end, n_own, halo_left,
                                                   halo_right, n_jobs, fifo, ring, &s_next_job, s_bias, s_span,
-                                                  qf, lane, s_raw + (long long)g * n_prefix, n_chunks);
+                                                  qf, lane, s_raw + (long long)g * n_prefix, n_chunks, a.bph);
   if constexpr (FUSED) {
     __shared__ float s_vb[kWaves];
     __shared__ double s_s[kWaves], s_t[kWaves];
@@ -830,10 +839,10 @@ sweep_kernel(const SweepArgs a) {
         if (p < cnt) dma.issue(kg, first + (long long)p * kWaves, n, lane, ring + p * T::kTileChunks);
       u32x4 qf[GT][T::kSteps];
       load_q<DT, D, GT>(static_cast<const u32x4*>(a.q_win) + (long long)(a.first_seq + si) * a.H * w * T::kCpr, g * G,
-                        G < GT ? G : GT, w, lane, qf);
+                        G < GT ? G : GT, w, a.bph, lane, qf);
       wait_vmcnt<0>();
       float m_run[GT], z_run[GT];
-      stats_tiles<DT, D, GT, kWaves, kStages>(dma, frags, kg, n, w, c2, first, cnt, ring, qf, lane, m_run, z_run);
+      stats_tiles<DT, D, GT, kWaves, kStages>(dma, frags, kg, n, w, a.bph, c2, first, cnt, ring, qf, lane, m_run, z_run);
       float2 mine;
       if (stats_merge_waves<GT, kWaves>(m_run, z_run, c2, lane, wave, sm.red, mine))
         st_dev_f2(&stat_part[((long long)g * sq.blocks_x + bx) * kRows + threadIdx.x], mine.x, mine.y);
@@ -947,11 +956,11 @@ sweep_kernel(const SweepArgs a) {
     merge_partials<GT, kThreads, true>(stat_part + (long long)g * sq.blocks_x * kRows, sq.blocks_x, false, c2,
                                        sm.sc.merge);
     __syncthreads();
-    write_bias<GT, kThreads>(sm.sc.merge, nullptr, g * G, G < GT ? G : GT, w, c2, sm.bias);
+    write_bias<GT, kThreads>(sm.sc.merge, nullptr, g * G, G < GT ? G : GT, w, a.bph, c2, sm.bias);
     __syncthreads();
     scores_tiles<DT, D, GT, kWaves, kStages, true>(dma, frags, kg, n, n_prefix, c2, t_begin, t_end, n_own, halo_left,
                                                    halo_right, n_jobs, fifo, ring, &sm.next_job, sm.bias, sm.sc.span,
-                                                   qf, lane, nullptr, 1);
+                                                   qf, lane, nullptr, 1, 1);
     scores_finish<kThreads>(pa, vb, g, n, n_prefix, w, t_begin, t_end, n_tiles, sm.sc.span, sm.vb, sm.ss, sm.st,
                             &sm.last, (unsigned int)(sq.blocks_x * H_kv), (unsigned int)(g * sq.blocks_x + bx), H_kv,
                             bx == 0, wave, reinterpret_cast<unsigned int*>(&sm.tile[0][0][0]));
@@ -1169,14 +1178,16 @@ static int compute_units() {
 
 int sweep_device_wgs() { return compute_units(); }
 
+int sweep_blocks_per_head(const lava_layer_desc& d) { return d.window > 32 ? 2 : 1; }
+
 bool sweep_has_narrow_shape(const lava_layer_desc& d) { return !(d.dtype == LAVA_F32 && d.head_dim == 128); }
 
 SweepPlan make_sweep_plan(const lava_layer_desc& d, int64_t n, int64_t batch_tokens, bool narrow) {
   SweepPlan p;
-  const int G = d.n_q_heads / d.n_kv_heads;
+  const int G = (d.n_q_heads / d.n_kv_heads) * sweep_blocks_per_head(d);   // row blocks of 32 window rows per group
   int gt = kMaxChunkHeads;
   if (d.dtype == LAVA_F32 && d.head_dim == 128) gt = 2;
-  p.chunk_heads = G < gt ? G : gt;
+  p.chunk_heads = G < gt ? G : gt;     // even whenever heads have two blocks: a head's blocks stay in one chunk
   if (p.chunk_heads == 3) p.chunk_heads = 4;   // kernels are built for 1, 2 and 4 heads per chunk
   p.n_chunks = (G + p.chunk_heads - 1) / p.chunk_heads;
   p.narrow = narrow && sweep_has_narrow_shape(d);
@@ -1324,7 +1335,7 @@ int32_t launch_stats(const lava_layer_desc& d, const SweepArgs& a, int max_block
 }
 
 int32_t launch_sweep(const lava_layer_desc& d, const SweepArgs& a, const SweepPlan& p, hipStream_t s) {
-  if (!p.fused_pool || a.lse != nullptr) return LAVA_ERR_INVALID_ARG;
+  if (!p.fused_pool || a.lse != nullptr || a.bph != 1) return LAVA_ERR_INVALID_ARG;
   // persistent workgroups: as many as the device keeps resident for this shape, at most one per unit
   const int slots = compute_units() * ((p.narrow && sweep_has_narrow_shape(d)) ? 2 : 1);
   const dim3 grid(a.n_units < slots ? a.n_units : slots);

@@ -71,9 +71,9 @@ static int32_t check_desc(const lava_layer_desc* d) {
   if (!(d->softmax_scale >= 0.0f) || d->softmax_scale > 1e30f) return LAVA_ERR_INVALID_ARG;
   if (d->score_kind < LAVA_SCORE_LAVA || d->score_kind > LAVA_SCORE_TOKEN_NORM) return LAVA_ERR_INVALID_ARG;
   if (d->n_q_heads % d->n_kv_heads != 0) return LAVA_ERR_SHAPE;
-  if (d->n_q_heads / d->n_kv_heads > 8 || d->n_kv_heads > 64) return LAVA_ERR_SHAPE;
+  if (d->n_q_heads / d->n_kv_heads > 16 || d->n_kv_heads > 64) return LAVA_ERR_SHAPE;
   if (d->head_dim != 64 && d->head_dim != 128) return LAVA_ERR_SHAPE;
-  if (d->window > 32) return LAVA_ERR_SHAPE;
+  if (d->window > 64) return LAVA_ERR_SHAPE;
   if (d->pool_kernel % 2 == 0 || d->pool_kernel > 15) return LAVA_ERR_SHAPE;
   return LAVA_OK;
 }
@@ -202,7 +202,8 @@ static int32_t window_scores(const lava_layer_desc* desc, int32_t batch, const i
   a.H = d.n_q_heads;
   a.H_kv = d.n_kv_heads;
   a.w = d.window;
-  a.G = d.n_q_heads / d.n_kv_heads;
+  a.bph = sweep_blocks_per_head(d);
+  a.G = (d.n_q_heads / d.n_kv_heads) * a.bph;
   a.n_chunks = plan_max.n_chunks;
   a.pool_half = d.pool_kernel / 2;
   a.token_norm = d.score_kind == LAVA_SCORE_TOKEN_NORM ? 1 : 0;
@@ -251,7 +252,7 @@ static int32_t window_scores(const lava_layer_desc* desc, int32_t batch, const i
     // Statistics and scores: two launches, or (when the caller's tuning asks for it, all heads of a group
     // fit one workgroup and the statistics pass is needed) one persistent launch that runs both passes.
     // The persistent launch measured a few per cent slower on this device, so it is not the default.
-    const bool persistent = together && lse == nullptr && tuning().sweep_schedule == 2;
+    const bool persistent = together && lse == nullptr && a.bph == 1 && tuning().sweep_schedule == 2;
     if (persistent) {
       int units = 0;
       for (int i = 0; i < a.n_seq; ++i) {
@@ -514,7 +515,9 @@ static int32_t check_desc_decode(const lava_layer_desc* desc, lava_layer_desc* o
   *out = *desc;
   out->window = 1;
   out->pool_kernel = 1;
-  return check_desc(out);
+  const int32_t st = check_desc(out);
+  if (st != LAVA_OK) return st;
+  return out->n_q_heads / out->n_kv_heads > 8 ? LAVA_ERR_SHAPE : LAVA_OK;   // the step's operand holds 8 heads of a group
 }
 
 size_t lava_decode_workspace_bytes(const lava_layer_desc* desc, int32_t batch, int64_t rows_capacity,

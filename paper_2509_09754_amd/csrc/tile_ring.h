@@ -299,32 +299,37 @@ struct FragReader {
   }
 };
 
-// Query fragments of the chunk's heads, one copy per wavefront straight from global memory:
-// row r = lane % 32 (zero beyond the window or the chunk).
+// The matrix cores take 32 query rows at a time, so a head whose window has more than 32 rows is
+// handled as `bph` (1 or 2) row blocks of 32: block index hb = head * bph + block, rows block * 32 ..
+// Everything up to the point where a head's window rows are summed treats a row block as a head.
+//
+// Query fragments of the chunk's row blocks hb0 .. hb0 + nh - 1, one copy per wavefront straight from
+// global memory: row r = lane % 32 of the block (zero beyond the window or the chunk).
 template <int DT, int D, int GT>
-__device__ __forceinline__ void load_q(const u32x4* __restrict__ qg, int h0, int nh, int w, int lane,
+__device__ __forceinline__ void load_q(const u32x4* __restrict__ qg, int hb0, int nh, int w, int bph, int lane,
                                        u32x4 (&qf)[GT][Tile<DT, D>::kSteps]) {
   using T = Tile<DT, D>;
   const int r = lane & 31, half = lane >> 5;
 #pragma unroll
   for (int t = 0; t < GT; ++t) {
+    const int head = (hb0 + t) / bph, row = ((hb0 + t) % bph) * 32 + r;
 #pragma unroll
     for (int j = 0; j < T::kSteps; ++j) {
       u32x4 x = u32x4{0u, 0u, 0u, 0u};
-      if (t < nh && r < w) x = qg[((long long)(h0 + t) * w + r) * T::kCpr + 2 * j + half];
+      if (t < nh && row < w) x = qg[((long long)head * w + row) * T::kCpr + 2 * j + half];
       qf[t][j] = x;
     }
   }
 }
 
-// Query rows of the chunk's heads, copied once per workgroup into tile-shaped LDS buffers (one per
-// head: row r of head t at row r, 16-byte chunks swizzled like a key tile, zero beyond the window
+// Query rows of the chunk's row blocks, copied once per workgroup into tile-shaped LDS buffers (one per
+// block: row r of block t at row r, 16-byte chunks swizzled like a key tile, zero beyond the window
 // or the chunk), from where every wavefront reads them as fragments with FragReader.  Letting each
 // wavefront fetch its own copy from global memory costs kWaves times the traffic on a handful of
 // cache lines that every workgroup of the grid wants at the same moment.
 // bufs(t) returns the buffer of head t.  The caller synchronises the workgroup afterwards.
 template <int DT, int D, int GT, int THREADS, class BUFS>
-__device__ __forceinline__ void stage_q(const u32x4* __restrict__ qg, int h0, int nh, int w, BUFS&& bufs) {
+__device__ __forceinline__ void stage_q(const u32x4* __restrict__ qg, int hb0, int nh, int w, int bph, BUFS&& bufs) {
   using T = Tile<DT, D>;
   constexpr int kPerHead = kTileKeys * T::kCpr;
   constexpr int kTotal = GT * kPerHead;
@@ -334,7 +339,8 @@ __device__ __forceinline__ void stage_q(const u32x4* __restrict__ qg, int h0, in
     if (kTotal % THREADS != 0 && c >= kTotal) break;
     const int t = c / kPerHead, rr = (c / T::kCpr) % kTileKeys, ch = c % T::kCpr;
     u32x4 x = u32x4{0u, 0u, 0u, 0u};
-    if (t < nh && rr < w) x = qg[((long long)(h0 + t) * w + rr) * T::kCpr + ch];
+    const int head = (hb0 + t) / bph, row = ((hb0 + t) % bph) * 32 + rr;
+    if (t < nh && row < w) x = qg[((long long)head * w + row) * T::kCpr + ch];
     bufs(t)[rr * T::kCpr + (ch ^ (rr & 7))] = x;
   }
 }

@@ -89,7 +89,9 @@ def test_window_scores_argument_errors():
     good = _desc()
     assert _ws(_desc(n_q_heads=30), [4096]) == lava.LAVA_ERR_SHAPE            # H % H_kv != 0
     assert _ws(_desc(head_dim=96), [4096]) == lava.LAVA_ERR_SHAPE
-    assert _ws(_desc(window=33), [4096]) == lava.LAVA_ERR_SHAPE
+    assert _ws(_desc(window=65), [4096]) == lava.LAVA_ERR_SHAPE
+    assert _ws(_desc(n_q_heads=8 * 17), [4096]) == lava.LAVA_ERR_SHAPE         # G = 17
+    assert lava.lava_window_scores_workspace_bytes(_desc(window=64, n_q_heads=8 * 16), 1, 4096) > 0
     assert _ws(_desc(pool_kernel=4), [4096]) == lava.LAVA_ERR_SHAPE
     assert _ws(_desc(window=0), [4096]) == lava.LAVA_ERR_INVALID_ARG
     assert _ws(_desc(dtype=lava.LAVA_BF16), [32]) == lava.LAVA_ERR_SHAPE      # N must exceed w

@@ -266,6 +266,15 @@ SCORE_CASES = [
     ("f32-d128-mha", synth.LayerShape(2, 2, 128, 700, 5, "f32", 100)),
     ("tiny-prefix", synth.LayerShape(8, 2, 64, 8 + 3, 8, "f32", 2 * 8 + 2, heavy_count=0)),
     ("w1", synth.LayerShape(4, 2, 64, 300, 1, "f32", 50)),
+    # windows of more than 32 rows (two row blocks per head) and groups of up to 16 query heads
+    ("bf16-w64-G4", synth.LayerShape(32, 8, 128, 3000 + 7, 64, "bf16", 8 * 100)),
+    ("bf16-w48-G2-fused", synth.LayerShape(4, 2, 128, 5000 + 3, 48, "bf16", 400)),
+    ("bf16-w33-mha-d64", synth.LayerShape(3, 3, 64, 2222, 33, "bf16", 300)),
+    ("f32-w64-G3-d64", synth.LayerShape(6, 2, 64, 1500, 64, "f32", 300)),
+    ("f32-w40-d128-G2", synth.LayerShape(4, 2, 128, 900, 40, "f32", 200)),
+    ("bf16-G16", synth.LayerShape(32, 2, 128, 2100, 32, "bf16", 300)),
+    ("bf16-G12-w64-d64", synth.LayerShape(24, 2, 64, 1300, 64, "bf16", 300)),
+    ("w64-prefix-of-one", synth.LayerShape(8, 2, 64, 64 + 1, 64, "f32", 2 * 64 + 1, heavy_count=0)),
 ]
 
 
@@ -311,7 +320,7 @@ def test_persistent_sweep_runs_units_their_owners_left(lava, tuning):
     compare_scores(sh, got, ref_s, vbar, ref_vbar, stat, O.layer_entropy(ref_s))
 
 
-NARROW_CASES = [c for c in SCORE_CASES if c[0] not in ("tiny-prefix", "w1")] + [
+NARROW_CASES = [c for c in SCORE_CASES if c[0] not in ("tiny-prefix", "w1", "w64-prefix-of-one")] + [
     ("cfg2-9k", synth.config(2, n=9000 + 5, budget=8 * 64)),
     ("f32-d64-G4", synth.LayerShape(8, 2, 64, 5000 + 9, 8, "f32", 300)),
 ]
@@ -339,9 +348,9 @@ def random_shapes(count, seed):
     for i in range(count):
         dtype = ["bf16", "f32"][int(r.integers(0, 2))]
         d = [64, 128][int(r.integers(0, 2))]
-        G = int(r.integers(1, 9))
+        G = int(r.integers(1, 9)) if i % 4 else int(r.integers(9, 17))
         Hkv = int(r.integers(1, 5))
-        w = int(r.integers(1, 33))
+        w = int(r.integers(1, 33)) if i % 3 else int(r.integers(33, 65))
         n = w + int(r.choice([1, 2, 7, 31, 32, 33, 100, 500, 1500, 3300, 6200]))
         pool = int(r.choice([1, 3, 5, 7, 9, 15]))
         budget = min(Hkv * n, Hkv * w + int(r.integers(0, 200)))
@@ -356,7 +365,7 @@ RANDOM_CASES = random_shapes(24, 2024)
 
 @pytest.mark.parametrize("name,sh,shape", RANDOM_CASES, ids=[c[0] for c in RANDOM_CASES])
 def test_window_scores_random_shapes(lava, name, sh, shape, tuning):
-    """Random draws over head counts, group sizes 1..8, windows 1..32, pooling kernels, lengths from one
+    """Random draws over head counts, group sizes 1..16, windows 1..64, pooling kernels, lengths from one
     prefix token to a few thousand, both dtypes and both sweep shapes; then the whole layer on the same input."""
     say(f"scores, random shape {name} ({shape})")
     tuning(sweep_shape=shape)
