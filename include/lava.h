@@ -93,9 +93,11 @@ typedef struct lava_tuning {
   int32_t sweep_shape;          /* 0 library's choice, 1 wide (one workgroup per compute unit),
                                    2 narrow (two per compute unit), where the kernels have both */
   int32_t sweep_workgroups;     /* workgroups a sweep launch aims for, 1..65536                */
-  int32_t sweep_schedule;       /* 0 library's choice (today: 1), 1 separate statistics and score
-                                   launches, 2 one persistent launch for both where the shape
-                                   allows it (bit-identical results)                            */
+  int32_t sweep_schedule;       /* 0 library's choice (today: 3 for a launch of one sequence, else
+                                   1), 1 three launches (value norms, statistics, scores), 2 value
+                                   norms, then one persistent launch for statistics and scores
+                                   where the shape allows it, 3 value norms inside the statistics
+                                   launch, then scores.  All give bit-identical results          */
   int32_t decode_rows_per_unit; /* rows of one head per decode work unit, 128..8192            */
   int32_t barrier_spin_limit;   /* polls of a grid-wide wait before it gives up (default 2^18) */
   int32_t sweep_orphan_units;   /* testing aid for the persistent sweep: the owners leave every n-th

@@ -16,6 +16,7 @@ enum KernelId : int {
   KID_STATS,          // window softmax statistics (row max, row sum) per block
   KID_SCORES,         // window scores: group-max of window-mean attention
   KID_SWEEP,          // statistics and scores of a layer in one persistent launch
+  KID_PREPASS,        // value-row norms and window softmax statistics in one launch
   KID_POOLSTAT,       // max-pool, value factor, +inf window entries, entropy statistic
   KID_SEL_INIT,       // selection: clear histograms and counters
   KID_SEL_FUSED,      // selection: radix select + ordered write in one launch
@@ -145,8 +146,9 @@ struct SweepArgs {
 int32_t launch_vnorm(const lava_layer_desc& d, const SweepArgs& a, int max_vnorm_blocks, hipStream_t s);
 // value factor 1 for every head (scores without the value norm): fills the partials, clears the tickets
 int32_t launch_unit_vnorm(const lava_layer_desc& d, const SweepArgs& a, int max_vnorm_blocks, hipStream_t s);
+// with_vnorm: the launch also sweeps the value rows (SweepSeq::vnorm_blocks == blocks_x, no launch_vnorm)
 int32_t launch_stats(const lava_layer_desc& d, const SweepArgs& a, int max_blocks_x, const SweepPlan& p,
-                     hipStream_t s);
+                     bool with_vnorm, hipStream_t s);
 // statistics and scores in one persistent launch (all heads of a group in one workgroup, no caller LSE)
 int32_t launch_sweep(const lava_layer_desc& d, const SweepArgs& a, const SweepPlan& p, hipStream_t s);
 // not fused (a group split into chunks): one sequence per launch, raw scores to the region's s_raw

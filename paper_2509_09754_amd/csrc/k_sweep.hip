@@ -109,14 +109,16 @@ __device__ __forceinline__ void entropy_finish(double acc_s, double acc_t, doubl
 // the chunk, this lane's running maximum of the raw dot products of its query row (lane % 32) and
 // the sum of exp2((dot - max) * c2) over the keys this lane saw (the two lane halves see different
 // keys of the same rows).  The assignment of tiles to wavefronts is static: the sums depend on the
-// order, and results must not depend on timing.
+// order, and results must not depend on timing.  Tile `it` sits in ring slot (it + slot0) % STAGES
+// (slot0 != 0 when another sweep of the same wavefront used the ring just before and requested these tiles).
 template <int DT, int D, int GT, int WAVES, int STAGES>
 __device__ __forceinline__ void stats_tiles(const TileDma<DT, D>& dma, const FragReader<DT, D>& frags,
                                             const char* __restrict__ kg, long long n, int w, int bph, float c2,
                                             long long first, int cnt, u32x4* ring,
                                             const u32x4 (&qf)[GT][Tile<DT, D>::kSteps], int lane,
-                                            float (&m_run)[GT], float (&z_run)[GT]) {
+                                            float (&m_run)[GT], float (&z_run)[GT], int slot0 = 0) {
   using T = Tile<DT, D>;
+  static_assert((STAGES & (STAGES - 1)) == 0, "ring slots are taken modulo a power of two");
 #pragma unroll
   for (int t = 0; t < GT; ++t) { m_run[t] = -INFINITY; z_run[t] = 0.0f; }
   const int r = lane & 31, half = lane >> 5;
@@ -125,11 +127,11 @@ __device__ __forceinline__ void stats_tiles(const TileDma<DT, D>& dma, const Fra
     const long long tile = first + (long long)it * WAVES;
     const int ahead = it + STAGES - 1;
     if (ahead < cnt)
-      dma.issue(kg, first + (long long)ahead * WAVES, n, lane, ring + (ahead % STAGES) * T::kTileChunks);
+      dma.issue(kg, first + (long long)ahead * WAVES, n, lane, ring + ((ahead + slot0) % STAGES) * T::kTileChunks);
     const int younger = cnt - 1 - it < STAGES - 1 ? cnt - 1 - it : STAGES - 1;
     wait_tile<DT, D>(younger);
     u32x4 kf[T::kSteps];
-    frags.read(ring_addr + (it % STAGES) * T::kTileBytes, kf);
+    frags.read(ring_addr + ((it + slot0) % STAGES) * T::kTileBytes, kf);
 
     const long long key0 = tile * kTileKeys;
     if (key0 + kTileKeys - 1 <= n - w) {
@@ -209,13 +211,87 @@ __device__ __forceinline__ bool stats_merge_waves(float (&m_run)[GT], float (&z_
   return true;
 }
 
+// sum of |x| over 16 bytes, added to s
+template <int DT>
+__device__ __forceinline__ float abs_sum16(const u32x4& x, float s) {
+  const unsigned int u[4] = {x.x, x.y, x.z, x.w};
+  if constexpr (DT == LAVA_BF16) {
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+#pragma unroll
+    for (int i = 0; i < 4; ++i)   // clear both sign bits, then a.x * 1 + a.y * 1 + s in one instruction
+      s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, u[i] & 0x7fff7fffu), ones, s, false);
+  } else {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) s += fabsf(__uint_as_float(u[i]));
+  }
+  return s;
+}
+
+// The selection region a primed call prepares for sequence z of the launch: histograms and state to zero
+// (the score kernels of the same call then fill the first histogram).  Called by one workgroup.
+__device__ __forceinline__ void clear_selection_region(const SweepArgs& a, int z, int threads) {
+  if (a.sel_ws == nullptr) return;
+  char* region = a.sel_ws + (size_t)(a.first_seq + z) * a.sel_stride;
+  unsigned int* hist = reinterpret_cast<unsigned int*>(region + a.sel_off_hist);
+  unsigned int* state = reinterpret_cast<unsigned int*>(region + a.sel_off_state);
+  for (int i = threadIdx.x; i < 3 * kSelBins; i += threads) hist[i] = 0u;
+  if (threadIdx.x < kSelStateWords) state[threadIdx.x] = 0u;
+}
+
+// The value-norm sweep of one wavefront: tiles first, first + WAVES, ... (cnt of them) of the head at
+// vg, whose first STAGES - 1 tiles have already been requested into `ring`.  Returns this lane's maximum
+// over its rows (row lane % 32 of every tile) of sum_c |V[row, c]|; with token_norm the rows' own norms
+// also go to row_norm (indexed by position).  CHAIN: as the ring drains, the first STAGES - 1 tiles
+// of the same numbers at `next` (the head's keys) are requested into the slots that follow, so that the
+// statistics sweep continues without a gap: its tile `it` is in slot (cnt + it) % STAGES.
+template <int DT, int D, int WAVES, int STAGES, bool CHAIN>
+__device__ __forceinline__ float vnorm_tiles(const TileDma<DT, D>& dma, const FragReader<DT, D>& frags,
+                                             const char* __restrict__ vg, const char* __restrict__ next, long long n,
+                                             long long first, int cnt, u32x4* ring, int lane, bool token_norm,
+                                             float* __restrict__ row_norm) {
+  using T = Tile<DT, D>;
+  static_assert((STAGES & (STAGES - 1)) == 0, "ring slots are taken modulo a power of two");
+  const unsigned int ring_addr = lds_addr(ring);
+  const int total = CHAIN ? 2 * cnt : cnt;                   // tiles this wavefront requests through the ring
+  float best = 0.0f;
+  for (int it = 0; it < cnt; ++it) {
+    const int ahead = it + STAGES - 1;
+    if (ahead < cnt)
+      dma.issue(vg, first + (long long)ahead * WAVES, n, lane, ring + (ahead % STAGES) * T::kTileChunks);
+    else if (CHAIN && ahead < total)
+      dma.issue(next, first + (long long)(ahead - cnt) * WAVES, n, lane, ring + (ahead % STAGES) * T::kTileChunks);
+    const int younger = total - 1 - it < STAGES - 1 ? total - 1 - it : STAGES - 1;
+    wait_tile<DT, D>(younger);
+    // each lane sums the half row it holds (row lane % 32; rows past n repeat row n - 1), the two
+    // halves are added across lanes
+    u32x4 f[T::kSteps];
+    frags.read(ring_addr + (it % STAGES) * T::kTileBytes, f);
+    float s = 0.0f;
+#pragma unroll
+    for (int j = 0; j < T::kSteps; ++j) s = abs_sum16<DT>(f[j], s);
+    s += __shfl_xor(s, 32);
+    best = fmaxf(best, s);
+    if (token_norm) {                                          // uniform: the rows' own norms, for the pooling step
+      const long long row = (first + (long long)it * WAVES) * kTileKeys + (lane & 31);
+      if (lane < 32 && row < n) row_norm[row] = s;
+    }
+  }
+  return best;
+}
+
 // ------------------------------------------------------------------------------------------
 // stats: per workgroup and per (head of the chunk, window row) the running maximum of the raw
 // dot products and sum of exp2((dot - max) * c2) over the workgroup's keys, c2 = scale * log2 e.
 // Row r may see keys 0 .. n - w + r only (each window row is normalised over the keys up to
 // and including its own position).
 // ------------------------------------------------------------------------------------------
-template <int DT, int D, int GT, int W>
+//
+// VN: the workgroup of a head's first chunk first sweeps the same span of the head's VALUE rows for their
+// L1 norms (what vnorm_kernel does in a launch of its own, cut here like the statistics: vnorm_blocks ==
+// blocks_x), through the same ring, and runs on into the keys without draining it.  One launch instead of
+// two: one start-up and one tail for both streams.  Workgroup (0, 0) also clears what vnorm_kernel clears.
+template <int DT, int D, int GT, int W, bool VN>
 __global__ void __launch_bounds__((Shape<DT, D, W>::kThreads), (Shape<DT, D, W>::kMinWaves))
 stats_kernel(const SweepArgs a) {
   using T = Tile<DT, D>;
@@ -253,9 +329,27 @@ stats_kernel(const SweepArgs a) {
   const long long first = t_begin + wave;
   const int cnt = first < t_end ? (int)((t_end - first + kWaves - 1) / kWaves) : 0;
   u32x4* ring = s_tile[wave][0];
+  const bool with_v = VN && chunk == 0;                        // uniform
+  const char* first_stream = kg;
+  if constexpr (VN) {
+    if (with_v) {
+      const u32x4* __restrict__ v = static_cast<const u32x4*>(a.v) + (long long)a.H_kv * sq.tok * T::kCpr;
+      first_stream = reinterpret_cast<const char*>(v) + (long long)g * n * T::kRowBytes;
+    }
+    if (blockIdx.x == 0 && blockIdx.y == 0) {
+      uint32_t* __restrict__ counters = reinterpret_cast<uint32_t*>(a.ws + sq.ws_off + a.off_counter);
+      const int n_counter_words = kCtlUnitA + a.H_kv * sq.blocks_x;
+      for (int i = threadIdx.x; i < n_counter_words; i += Shape<DT, D, W>::kThreads) counters[i] = 0u;
+      clear_selection_region(a, (int)blockIdx.z, Shape<DT, D, W>::kThreads);
+    }
+  }
+  // with the value rows first, the ring holds both streams in turn: the wavefront's cnt value tiles, then
+  // its cnt key tiles (a wavefront with few tiles already requests keys here)
 #pragma unroll
-  for (int p = 0; p < kStages - 1; ++p)
-    if (p < cnt) dma.issue(kg, first + (long long)p * kWaves, n, lane, ring + p * T::kTileChunks);
+  for (int p = 0; p < kStages - 1; ++p) {
+    if (p < cnt) dma.issue(first_stream, first + (long long)p * kWaves, n, lane, ring + p * T::kTileChunks);
+    else if (with_v && p < 2 * cnt) dma.issue(kg, first + (long long)(p - cnt) * kWaves, n, lane, ring + p * T::kTileChunks);
+  }
   // Every wavefront fetches its own copy of the query rows, after its first tiles so that the two
   // latencies overlap.  (Staging them once per workgroup through LDS, as the scores kernel does, was
   // measured slower here: the wavefronts then leave the barrier in step and the sweep loses more
@@ -264,11 +358,39 @@ stats_kernel(const SweepArgs a) {
   u32x4 qf[GT][T::kSteps];
   load_q<DT, D, GT>(q_win, h0, nh, w, a.bph, lane, qf);
   wait_vmcnt<0>();
+  float v_best = 0.0f;
+  int slot0 = 0;
+  if constexpr (VN) {
+    if (with_v) {
+      v_best = vnorm_tiles<DT, D, kWaves, kStages, true>(dma, frags, first_stream, kg, n, first, cnt, ring, lane,
+                                                         a.token_norm != 0,
+                                                         a.scores + (long long)a.H_kv * sq.tok + (long long)g * n);
+      slot0 = cnt % kStages;
+    }
+  }
   float m_run[GT], z_run[GT];
-  stats_tiles<DT, D, GT, kWaves, kStages>(dma, frags, kg, n, w, a.bph, c2, first, cnt, ring, qf, lane, m_run, z_run);
-  float2 mine;
-  if (stats_merge_waves<GT, kWaves>(m_run, z_run, c2, lane, wave, s_red, mine))
-    stat_part[((long long)blockIdx.y * sq.blocks_x + blockIdx.x) * (GT * 32) + threadIdx.x] = mine;
+  stats_tiles<DT, D, GT, kWaves, kStages>(dma, frags, kg, n, w, a.bph, c2, first, cnt, ring, qf, lane, m_run, z_run,
+                                          slot0);
+  if constexpr (VN) {
+    __shared__ float s_vmax[kWaves];
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) v_best = fmaxf(v_best, __shfl_xor(v_best, off));
+    if (lane == 0) s_vmax[wave] = v_best;                      // read after the barrier of the merge below
+    float2 mine;
+    const bool owner = stats_merge_waves<GT, kWaves>(m_run, z_run, c2, lane, wave, s_red, mine);
+    if (owner) stat_part[((long long)blockIdx.y * sq.blocks_x + blockIdx.x) * (GT * 32) + threadIdx.x] = mine;
+    if (with_v && threadIdx.x == 0) {
+      float m = s_vmax[0];
+#pragma unroll
+      for (int i = 1; i < kWaves; ++i) m = fmaxf(m, s_vmax[i]);
+      float* __restrict__ vnorm_part = reinterpret_cast<float*>(a.ws + sq.ws_off + a.off_vnorm_part);
+      vnorm_part[(long long)g * sq.vnorm_blocks + blockIdx.x] = m;
+    }
+  } else {
+    float2 mine;
+    if (stats_merge_waves<GT, kWaves>(m_run, z_run, c2, lane, wave, s_red, mine))
+      stat_part[((long long)blockIdx.y * sq.blocks_x + blockIdx.x) * (GT * 32) + threadIdx.x] = mine;
+  }
 }
 
 // ------------------------------------------------------------------------------------------
@@ -974,34 +1096,6 @@ sweep_kernel(const SweepArgs a) {
 // registers), 32-row tiles, no matrix work.
 // ------------------------------------------------------------------------------------------
 
-// sum of |x| over 16 bytes, added to s
-template <int DT>
-__device__ __forceinline__ float abs_sum16(const u32x4& x, float s) {
-  const unsigned int u[4] = {x.x, x.y, x.z, x.w};
-  if constexpr (DT == LAVA_BF16) {
-    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-#pragma unroll
-    for (int i = 0; i < 4; ++i)   // clear both sign bits, then a.x * 1 + a.y * 1 + s in one instruction
-      s = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, u[i] & 0x7fff7fffu), ones, s, false);
-  } else {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) s += fabsf(__uint_as_float(u[i]));
-  }
-  return s;
-}
-
-// The selection region a primed call prepares for sequence z of the launch: histograms and state to zero
-// (the score kernels of the same call then fill the first histogram).  Called by one workgroup.
-__device__ __forceinline__ void clear_selection_region(const SweepArgs& a, int z, int threads) {
-  if (a.sel_ws == nullptr) return;
-  char* region = a.sel_ws + (size_t)(a.first_seq + z) * a.sel_stride;
-  unsigned int* hist = reinterpret_cast<unsigned int*>(region + a.sel_off_hist);
-  unsigned int* state = reinterpret_cast<unsigned int*>(region + a.sel_off_state);
-  for (int i = threadIdx.x; i < 3 * kSelBins; i += threads) hist[i] = 0u;
-  if (threadIdx.x < kSelStateWords) state[threadIdx.x] = 0u;
-}
-
 template <int DT, int D>
 struct VShape {
   static constexpr int kWaves = Tile<DT, D>::kTileBytes > 8192 ? 4 : 8;
@@ -1048,39 +1142,15 @@ vnorm_kernel(const SweepArgs a) {
   const long long first = t_begin + wave;
   const int cnt = first < t_end ? (int)((t_end - first + kWaves - 1) / kWaves) : 0;
   u32x4* ring = s_tile[wave][0];
-  const unsigned int ring_addr = lds_addr(ring);
 #pragma unroll
   for (int p = 0; p < kStages - 1; ++p)
     if (p < cnt) dma.issue(vg, first + (long long)p * kWaves, n, lane, ring + p * T::kTileChunks);
-  float best = 0.0f;
-  for (int it = 0; it < cnt; ++it) {
-    const int ahead = it + kStages - 1;
-    if (ahead < cnt)
-      dma.issue(vg, first + (long long)ahead * kWaves, n, lane, ring + (ahead % kStages) * T::kTileChunks);
-    const int younger = cnt - 1 - it < kStages - 1 ? cnt - 1 - it : kStages - 1;
-    switch (younger) {
-      case 0: wait_vmcnt<0>(); break;
-      case 1: wait_vmcnt<T::kLoads>(); break;
-      case 2: wait_vmcnt<2 * T::kLoads>(); break;
-      default: wait_vmcnt<3 * T::kLoads>(); break;
-    }
-    // each lane sums the half row it holds (row lane % 32; rows past n repeat row n - 1), the two
-    // halves are added across lanes
-    u32x4 f[T::kSteps];
-    frags.read(ring_addr + (it % kStages) * T::kTileBytes, f);
-    float s = 0.0f;
+  const float best = vnorm_tiles<DT, D, kWaves, kStages, false>(dma, frags, vg, nullptr, n, first, cnt, ring, lane,
+                                                                 a.token_norm != 0, row_norm + (long long)g * n);
+  float wave_best = best;
 #pragma unroll
-    for (int j = 0; j < T::kSteps; ++j) s = abs_sum16<DT>(f[j], s);
-    s += __shfl_xor(s, 32);
-    best = fmaxf(best, s);
-    if (a.token_norm) {                                        // uniform: the rows' own norms, for the pooling step
-      const long long row = (first + (long long)it * kWaves) * kTileKeys + (lane & 31);
-      if (lane < 32 && row < n) row_norm[(long long)g * n + row] = s;
-    }
-  }
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) best = fmaxf(best, __shfl_xor(best, off));
-  if ((threadIdx.x & 63) == 0) s_max[wave] = best;
+  for (int off = 32; off > 0; off >>= 1) wave_best = fmaxf(wave_best, __shfl_xor(wave_best, off));
+  if ((threadIdx.x & 63) == 0) s_max[wave] = wave_best;
   __syncthreads();
   if (threadIdx.x == 0) {
     float m = s_max[0];
@@ -1232,6 +1302,7 @@ SweepPlan make_sweep_plan(const lava_layer_desc& d, int64_t n, int64_t batch_tok
   p.vnorm_blocks = (int)((n_tiles + vtpb - 1) / vtpb);
   const int64_t vb_bound = (target_wgs > device_wgs ? target_wgs : device_wgs) / d.n_kv_heads;
   p.vnorm_blocks_bound = (int)(vb_bound > 1 ? vb_bound : 1);
+  if (p.vnorm_blocks_bound < p.blocks_x_bound) p.vnorm_blocks_bound = p.blocks_x_bound;   // value norms cut like the statistics
   return p;
 }
 
@@ -1318,11 +1389,16 @@ float sweep_exp2_scale(const lava_layer_desc& d) {
   } while (0)
 
 int32_t launch_stats(const lava_layer_desc& d, const SweepArgs& a, int max_blocks_x, const SweepPlan& p,
-                     hipStream_t s) {
+                     bool with_vnorm, hipStream_t s) {
   const dim3 grid(max_blocks_x, d.n_kv_heads * p.n_chunks, a.n_seq);
-  ProfScope ps(KID_STATS, s);
-#define LAVA_STATS_W(DTV, DV, GTV, WV) \
-  hipLaunchKernelGGL((stats_kernel<DTV, DV, GTV, WV>), grid, dim3(Shape<DTV, DV, WV>::kThreads), 0, s, a)
+  ProfScope ps(with_vnorm ? KID_PREPASS : KID_STATS, s);
+#define LAVA_STATS_W(DTV, DV, GTV, WV)                                                                             \
+  do {                                                                                                             \
+    if (with_vnorm)                                                                                                \
+      hipLaunchKernelGGL((stats_kernel<DTV, DV, GTV, WV, true>), grid, dim3(Shape<DTV, DV, WV>::kThreads), 0, s, a); \
+    else                                                                                                           \
+      hipLaunchKernelGGL((stats_kernel<DTV, DV, GTV, WV, false>), grid, dim3(Shape<DTV, DV, WV>::kThreads), 0, s, a); \
+  } while (0)
 #define LAVA_STATS(DTV, DV, GTV)                                               \
   do {                                                                         \
     if (Shape<DTV, DV, 4>::kNarrow && p.narrow) LAVA_STATS_W(DTV, DV, GTV, (Shape<DTV, DV, 4>::kNarrow ? 4 : 8)); \

@@ -19,7 +19,7 @@ struct ProfState {
 } g_prof;
 
 const char* const kKernelNames[KID_COUNT] = {
-    "vnorm", "stats", "scores", "sweep", "poolstat", "sel_init", "sel_fused", "sel_steps", "compact", "budgets",
+    "vnorm", "stats", "scores", "sweep", "prepass", "poolstat", "sel_init", "sel_fused", "sel_steps", "compact", "budgets",
     "decode", "decode_merge"};
 
 void prof_collect() {
@@ -115,7 +115,7 @@ int32_t lava_set_tuning(const lava_tuning* t) {
     g_tuning = lava_tuning{};
     return LAVA_OK;
   }
-  if (t->sweep_shape < 0 || t->sweep_shape > 2 || t->sweep_schedule < 0 || t->sweep_schedule > 2 ||
+  if (t->sweep_shape < 0 || t->sweep_shape > 2 || t->sweep_schedule < 0 || t->sweep_schedule > 3 ||
       t->sweep_workgroups < 0 || t->sweep_workgroups > 65536 || t->barrier_spin_limit < 0 ||
       (t->decode_rows_per_unit != 0 && (t->decode_rows_per_unit < 128 || t->decode_rows_per_unit > 8192)) ||
       t->sweep_orphan_units < 0 || t->reserved[0] != 0 || t->reserved[1] != 0)
@@ -247,12 +247,25 @@ static int32_t window_scores(const lava_layer_desc* desc, int32_t batch, const i
       if (plan.vnorm_blocks > max_vb) max_vb = plan.vnorm_blocks;
       tok += n;
     }
-    st = d.score_kind == LAVA_SCORE_ATTENTION ? launch_unit_vnorm(d, a, max_vb, s) : launch_vnorm(d, a, max_vb, s);
-    if (st != LAVA_OK) return st;
     // Statistics and scores: two launches, or (when the caller's tuning asks for it, all heads of a group
     // fit one workgroup and the statistics pass is needed) one persistent launch that runs both passes.
     // The persistent launch measured a few per cent slower on this device, so it is not the default.
     const bool persistent = together && lse == nullptr && a.bph == 1 && tuning().sweep_schedule == 2;
+    // Value norms: a launch of their own, or, where a statistics launch follows anyway, inside it (its
+    // workgroups sweep the value rows of their span before the keys: one launch fewer).  Measured: a gain
+    // for one sequence per launch (4 % of the whole path at 32K tokens, none at 128K), a loss of about 3 %
+    // for a launch of many sequences, whose value norms do better with their own, finer cut.
+    const bool prepass = lse == nullptr && !persistent && d.score_kind != LAVA_SCORE_ATTENTION &&
+                         (tuning().sweep_schedule == 3 || (tuning().sweep_schedule == 0 && a.n_seq == 1));
+    if (prepass) {
+      for (int i = 0; i < a.n_seq; ++i) {
+        a.s[i].vnorm_blocks = a.s[i].blocks_x;
+        a.s[i].vnorm_tiles_per_block = a.s[i].tiles_per_block;
+      }
+    } else {
+      st = d.score_kind == LAVA_SCORE_ATTENTION ? launch_unit_vnorm(d, a, max_vb, s) : launch_vnorm(d, a, max_vb, s);
+      if (st != LAVA_OK) return st;
+    }
     if (persistent) {
       int units = 0;
       for (int i = 0; i < a.n_seq; ++i) {
@@ -268,7 +281,7 @@ static int32_t window_scores(const lava_layer_desc* desc, int32_t batch, const i
       continue;
     }
     if (lse == nullptr) {
-      st = launch_stats(d, a, max_bx, plan_launch, s);
+      st = launch_stats(d, a, max_bx, plan_launch, prepass, s);
       if (st != LAVA_OK) return st;
     }
     st = launch_scores(d, a, max_bx, plan_launch, s);

@@ -65,7 +65,7 @@ class Tuning(ctypes.Structure):
 
 
 SWEEP_SHAPES = {"auto": 0, "wide": 1, "narrow": 2}
-SWEEP_SCHEDULES = {"auto": 0, "separate": 1, "persistent": 2}
+SWEEP_SCHEDULES = {"auto": 0, "separate": 1, "persistent": 2, "prepass": 3}
 
 
 class LavaError(RuntimeError):

@@ -43,6 +43,8 @@ def test_tuning_round_trip_and_validation():
         assert (t.sweep_shape, t.sweep_workgroups, t.decode_rows_per_unit, t.barrier_spin_limit) == (2, 300, 256, 7)
         bad = lava.Tuning(3, 0, 0, 0, 0)
         assert lava.lib.lava_set_tuning(ctypes.byref(bad)) == lava.LAVA_ERR_INVALID_ARG
+        bad = lava.Tuning(0, 0, 4, 0, 0)                        # schedules are 0..3
+        assert lava.lib.lava_set_tuning(ctypes.byref(bad)) == lava.LAVA_ERR_INVALID_ARG
         bad = lava.Tuning(0, 0, 0, 64, 0)                       # fewer rows than one round of the decode wavefronts
         assert lava.lib.lava_set_tuning(ctypes.byref(bad)) == lava.LAVA_ERR_INVALID_ARG
         bad = lava.Tuning(0, 0, 0, 0, 0)

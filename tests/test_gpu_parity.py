@@ -280,9 +280,9 @@ SCORE_CASES = [
 
 @pytest.mark.parametrize("name,sh", SCORE_CASES, ids=[c[0] for c in SCORE_CASES])
 def test_window_scores_vs_oracle(lava, name, sh, tuning):
-    """Every case under both schedules of the key sweeps (one persistent launch for statistics and scores,
-    or one launch each): each against the oracle, and the two against each other bit for bit (the same
-    tiles are combined in the same order)."""
+    """Every case under the three schedules of the sweeps (one launch per pass; value norms, then one
+    persistent launch for statistics and scores; value norms inside the statistics launch): each against the
+    oracle, and all against each other bit for bit (the same tiles are combined in the same order)."""
     say(f"scores {name}: {sh}")
     for seed in (0, 1):
         inp = synth.gen_layer(sh, seed)
@@ -290,14 +290,16 @@ def test_window_scores_vs_oracle(lava, name, sh, tuning):
         ref_s, ref_vbar = O.lava_scores(q, k, v, sh.window, sh.pool_kernel)
         ref_e = O.layer_entropy(ref_s)
         outs = {}
-        for schedule in ("persistent", "separate"):
+        for schedule in ("persistent", "prepass", "separate"):
             tuning(sweep_schedule=schedule)
             _, _, got, vbar, stat = run_scores(lava, inp)
             compare_scores(sh, got, ref_s, vbar, ref_vbar, stat, ref_e)
             outs[schedule] = (got, vbar, stat)
-        a, b = outs["persistent"], outs["separate"]
-        assert np.array_equal(a[0].view(np.uint32), b[0].view(np.uint32)) and np.array_equal(a[1], b[1])
-        assert np.float32(a[2]).view(np.uint32) == np.float32(b[2]).view(np.uint32)
+        b = outs["separate"]
+        for schedule in ("persistent", "prepass"):
+            a = outs[schedule]
+            assert np.array_equal(a[0].view(np.uint32), b[0].view(np.uint32)) and np.array_equal(a[1], b[1]), schedule
+            assert np.float32(a[2]).view(np.uint32) == np.float32(b[2]).view(np.uint32), schedule
 
 
 def test_persistent_sweep_runs_units_their_owners_left(lava, tuning):
@@ -423,10 +425,11 @@ def test_window_scores_deterministic_and_batched(lava, tuning):
     for shape in ("wide", "narrow"):                          # the two schedules on the same ragged batch, per shape
         tuning(sweep_schedule="separate", sweep_shape=shape)
         s3, vb3, e3 = lava.lava_window_scores(desc, lens, q, k, v)
-        tuning(sweep_schedule="persistent", sweep_shape=shape)
-        s2, vb2, e2 = lava.lava_window_scores(desc, lens, q, k, v)
-        torch.cuda.synchronize()
-        assert torch.equal(s3, s2) and torch.equal(vb3, vb2) and torch.equal(e3, e2), shape
+        for schedule in ("persistent", "prepass"):
+            tuning(sweep_schedule=schedule, sweep_shape=shape)
+            s2, vb2, e2 = lava.lava_window_scores(desc, lens, q, k, v)
+            torch.cuda.synchronize()
+            assert torch.equal(s3, s2) and torch.equal(vb3, vb2) and torch.equal(e3, e2), (shape, schedule)
     tuning()
     s1 = s1.cpu().numpy()
     tok = 0
@@ -626,6 +629,7 @@ PRIMED_CASES = [
     ("cfg1", synth.config(1), "auto", "auto"),
     ("cfg2-9k-wide", synth.config(2, n=9000 + 5, budget=8 * 64), "wide", "separate"),
     ("cfg2-9k-narrow", synth.config(2, n=9000 + 5, budget=8 * 64), "narrow", "separate"),
+    ("cfg2-9k-narrow-prepass", synth.config(2, n=9000 + 5, budget=8 * 64), "narrow", "prepass"),
     ("cfg2-20k-persistent", synth.config(2, n=20000 + 13, budget=8 * 300), "auto", "persistent"),
     ("bf16-G8-two-chunks", synth.LayerShape(16, 2, 128, 2100, 32, "bf16", 300), "auto", "auto"),
     ("f32-d128-G4", synth.LayerShape(8, 2, 128, 1111, 32, "f32", 300), "auto", "auto"),
