@@ -130,6 +130,8 @@ def parse():
     ap.add_argument("--sets", type=int, default=0, help="distinct K/V buffer sets (0 = enough for >= 1.5 GiB)")
     ap.add_argument("--sweep-schedule", default="auto", choices=["auto", "separate", "persistent", "prepass"],
                     help="lava_tuning.sweep_schedule for the whole run (A/B of the sweep schedules)")
+    ap.add_argument("--no-plan", action="store_true",
+                    help="lava_layer_budgets as a launch of its own instead of the budget plan carried by the scores call")
     ap.add_argument("--summarize-profiles", metavar="WORKLOAD", default=None,
                     help="write profiles/<workload>_*.md from rocprofv3 CSV output under gpurun_out/ and exit (no GPU)")
     ap.add_argument("--no-primed", action="store_true",
@@ -561,14 +563,23 @@ def main():
     lse_dev = [None]
     primed = not args.no_primed
 
+    # budgets (Alg. 2's rule over the layers seen so far: here one layer) formed by the scores call itself,
+    # or by a launch of their own
+    planned = not args.no_plan
+    e_table = torch.zeros(1, 1, dtype=torch.float32, device=dev)
+    plan = lava.make_budget_plan(e_table, 0, total_b, lo, hi, budgets) if planned else None
+
     def step(i):
         q, k, v = sets[i % n_sets]
         lava.lava_window_scores(desc, lens, q, k, v, lse=lse_dev[0], scores=scores, vbar=vbar, layer_stat=stat,
-                                workspace=ws_scores, select_workspace=ws_sel if primed else None)
-        lava.lava_layer_budgets(stat.view(1, 1), total_b, lo, hi, budgets=budgets)
+                                workspace=ws_scores, select_workspace=ws_sel if primed else None, budget_plan=plan)
+        if not planned:
+            lava.lava_layer_budgets(stat.view(1, 1), total_b, lo, hi, budgets=budgets)
         lava.lava_select_topk(sh.n_kv_heads, scores, B, budget_dev=budgets.view(-1), head_counts=counts,
                               head_offsets=offs, kept_idx=idx, kept_scores=kept_s, workspace=ws_sel, primed=primed)
         lava.lava_compact_kv(desc, sh.n, k, v, offs, idx, B, k_out=k_hat, v_out=v_hat)
+
+    host_enqueue = [0.0]   # seconds the host spent enqueueing the timed steps of the latest loop
 
     def timed_loop():
         for i in range(args.warmup):
@@ -577,6 +588,7 @@ def main():
         t0 = time.perf_counter()
         for i in range(args.steps):
             step(i)
+        host_enqueue[0] = time.perf_counter() - t0
         torch.cuda.synchronize()
         return time.perf_counter() - t0
 
@@ -603,6 +615,7 @@ def main():
         return {name: 1e3 * ms / max(cnt, 1) for name, (ms, cnt) in prof.items() if cnt}
 
     elapsed = timed_loop()
+    host_ms_per_step = 1e3 * host_enqueue[0] / args.steps
     ms_per_step = 1e3 * elapsed / args.steps
     tokens_per_s = sh.n / (elapsed / args.steps)
     step_spread = per_step_times()
@@ -620,7 +633,14 @@ def main():
         logits = logits.masked_fill(pos > last, float("-inf"))
         lse_dev[0] = torch.logsumexp(logits, dim=2).contiguous()
         del logits, qf
-    lse_elapsed = timed_loop()
+    # (the host sometimes enqueues slowly right after the large temporaries above are released and the loop
+    # then measures the host; best of three loops, each of exactly --steps steps, for this secondary figure)
+    lse_elapsed, lse_host_ms_per_step = float("inf"), 0.0
+    for _ in range(3):
+        t = timed_loop()
+        if t < lse_elapsed:
+            lse_elapsed, lse_host_ms_per_step = t, 1e3 * host_enqueue[0] / args.steps
+    lse_spread = per_step_times()
     lse_kernel_us = per_kernel_times()
     lse_dev[0] = None
 
@@ -682,9 +702,10 @@ def main():
         "config": {"workload": f"{args.workload}: one layer, {sh.n_q_heads}q/{sh.n_kv_heads}kv heads, d_h {sh.head_dim}, "
                                f"N={sh.n}, w={sh.window}, B_l={B}, {sh.dtype}, batch 1",
                    "kv_buffer_sets": n_sets, "sweep_schedule": args.sweep_schedule,
-                   "scores_prepare_selection": primed},
+                   "scores_prepare_selection": primed, "scores_form_budgets": planned},
         "roofline": roofline,
         "step_spread": step_spread,
+        "host_enqueue_ms_per_step": round(host_ms_per_step, 5),
         "sweep_kernels": sweep_kernels,
         "kv_sweep": kv_sweep,
         "path": {"algorithmic_bytes": path_bytes, "achieved_GBs": round(path_gbs, 1),
@@ -695,6 +716,7 @@ def main():
                      "ms_per_step": round(1e3 * lse_elapsed / args.steps, 5),
                      "value": round(sh.n / (lse_elapsed / args.steps), 1),
                      "path_frac_of_hbm_peak": round(path_bytes / (lse_elapsed / args.steps) / 1e9 / HBM_PEAK_GBS, 4),
+                     "step_spread": lse_spread, "host_enqueue_ms_per_step": round(lse_host_ms_per_step, 5),
                      "kernels_us": {k: round(v, 2) for k, v in lse_kernel_us.items()}},
     }
 

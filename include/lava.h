@@ -163,6 +163,44 @@ int32_t lava_window_scores_primed(const lava_layer_desc* desc, int32_t batch, co
                                   size_t select_workspace_bytes, void* hip_stream);
 
 /*
+ * Budgets formed by the scores call itself (Alg. 2 computes them from the statistic the scores have
+ * just produced; the workgroup that forms e_l goes on to run the budget rule, which saves the small
+ * launch of lava_layer_budgets).  All pointers are device memory; sequence b uses row b of each table.
+ *
+ *   n_layers   layers that share each sequence's total, this call's layer included; 1..128
+ *              (LAVA_PLAN_MAX_LAYERS; deeper stacks call lava_layer_budgets)
+ *   layer      0 <= layer < n_layers: the column of `e` this call's statistic belongs to
+ *   e          [batch][n_layers] float   statistics; the call writes column `layer` (the same value
+ *                                        as layer_stat[b]) and reads the other columns
+ *   total      [batch] int64             total budget of each sequence
+ *   lo, hi     [batch][n_layers] int64   bounds, as for lava_layer_budgets
+ *   budgets    [batch][n_layers] int64   out: exactly what lava_layer_budgets(on_device = 1) returns
+ *                                        for these tables, -1 everywhere for infeasible bounds
+ */
+#define LAVA_PLAN_MAX_LAYERS 128
+typedef struct lava_budget_plan {
+  int32_t n_layers;
+  int32_t layer;
+  float* e;
+  const int64_t* total;
+  const int64_t* lo;
+  const int64_t* hi;
+  int64_t* budgets;
+} lava_budget_plan;
+
+/*
+ * lava_window_scores with both optional extras: select_workspace as for lava_window_scores_primed
+ * (NULL with 0 bytes: the selection is not prepared) and `plan` (NULL: no budgets).  A plan with
+ * n_layers or layer out of range or a null table returns LAVA_ERR_INVALID_ARG.
+ */
+int32_t lava_window_scores_planned(const lava_layer_desc* desc, int32_t batch, const int64_t* seq_lens,
+                                   const void* q_win, const void* k, const void* v, const float* lse,
+                                   float* scores, float* vbar, float* layer_stat, void* workspace,
+                                   size_t workspace_bytes, void* select_workspace,
+                                   size_t select_workspace_bytes, const lava_budget_plan* plan,
+                                   void* hip_stream);
+
+/*
  * Layer budgets B_l = e_l / sum_l e_l * total (Alg. 2, inner loop) as integers.
  *
  *   e          [batch][n_layers] float   statistics of the layers prefilled so far

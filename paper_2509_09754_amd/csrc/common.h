@@ -115,6 +115,17 @@ struct SweepSeq {
   int unit_base;             // persistent launch: work units of the sequences before this one (H_kv * blocks_x each)
 };
 
+// Budgets formed right after the layer statistic, by the workgroup that formed it (e == nullptr: none).
+// Sequence b of the batch uses row b of every table.
+struct BudgetPlanArgs {
+  float* e;                  // [batch][n_layers] statistics; column `layer` is written by this call
+  const int64_t* total;      // [batch]
+  const int64_t* lo;         // [batch][n_layers]
+  const int64_t* hi;         // [batch][n_layers]
+  int64_t* out;              // [batch][n_layers] budgets (-1 everywhere for infeasible bounds)
+  int n_layers, layer;
+};
+
 struct SweepArgs {
   const void* q_win;         // [batch][H][w][d_h]
   const void* k;             // packed, [H_kv][n][d_h] per sequence
@@ -135,6 +146,7 @@ struct SweepArgs {
   // (null: none): region stride and the offsets of the histograms / the state inside a region
   char* sel_ws;
   size_t sel_stride, sel_off_hist, sel_off_state;
+  BudgetPlanArgs plan;
   int n_units;               // persistent launch: H_kv * sum of blocks_x over the table
   unsigned int spin_limit;   // persistent launch: polls of a wait for other workgroups before it gives up
   unsigned int help_after;   // persistent launch: polls after which a waiting workgroup looks for unclaimed units (>= 1)
@@ -158,7 +170,7 @@ float sweep_exp2_scale(const lava_layer_desc& d);
 int32_t launch_poolstat(const lava_layer_desc& d, int64_t n, const float* s_raw,
                         const float* vnorm_part, int vnorm_blocks, float* scores, float* vbar,
                         float* layer_stat, double2* ent_part, uint32_t* counters, unsigned int* sel_hist0,
-                        hipStream_t s);
+                        const BudgetPlanArgs& plan, int plan_seq, hipStream_t s);
 // words of a selection's state block (cleared together with its histograms)
 constexpr int kSelStateWords = 8;
 

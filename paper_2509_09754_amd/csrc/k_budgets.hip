@@ -9,11 +9,10 @@
 
 #include <vector>
 
+#include "budget_wave.h"
 #include "common.h"
 
 namespace lava {
-
-constexpr int kMaxLayers = 1024;
 
 // One sequence.  Returns 0, or 1 when the bounds are infeasible.
 // Scratch arrays (length n each): quota, base, freelist, frac.
@@ -125,129 +124,6 @@ int32_t budgets_host(int32_t batch, int32_t n_layers, const float* e, const int6
   return LAVA_OK;
 }
 
-__device__ __forceinline__ long long wave_sum(long long x) {
-#pragma unroll
-  for (int off = 32; off > 0; off >>= 1) x += __shfl_xor(x, off);
-  return x;
-}
-
-// The same routine run by the 64 lanes of one wavefront (the workgroup): every per-layer quantity
-// is computed by one lane with the arithmetic of allocate_budgets, integer sums are reduced
-// across lanes (exact in any order), the fp64 weight sum is taken in layer order by every lane, and
-// the rare and order-dependent parts (units taken back after a rounding overshoot, the free list)
-// stay with lane 0.  Results are identical to the sequential routine.  All control flow is uniform.
-// Scratch in LDS (length n each): ed, quota, frac, base, freel; state: two words.
-__device__ inline int allocate_budgets_wave(int n, const double* ed, long long total, const long long* lo,
-                                            const long long* hi, long long* out, double* quota,
-                                            long long* base, int* freel, double* frac, long long* state) {
-#pragma clang fp contract(off)
-  const int lane = threadIdx.x;
-  long long slo = 0, shi = 0, bad = 0;
-  for (int i = lane; i < n; i += 64) {
-    if (lo[i] > hi[i] || lo[i] < 0) bad = 1;
-    slo += lo[i];
-    shi += hi[i];
-    freel[i] = i;
-  }
-  bad = wave_sum(bad);
-  slo = wave_sum(slo);
-  shi = wave_sum(shi);
-  if (bad != 0 || slo > total || shi < total) return 1;
-  __syncthreads();
-  int nf = n;
-  long long remaining = total;
-  while (nf > 0) {
-    double wsum = 0.0;
-    for (int j = 0; j < nf; ++j) wsum += ed[freel[j]];
-    const bool uniform = !(wsum > 0.0);
-    if (uniform) wsum = (double)nf;
-    long long given = 0;
-    for (int j = lane; j < nf; j += 64) {
-      const double wj = uniform ? 1.0 : ed[freel[j]];
-      quota[j] = (wj / wsum) * (double)remaining;
-      base[j] = (long long)floor(quota[j]);
-      frac[j] = quota[j] - (double)base[j];
-      given += base[j];
-    }
-    given = wave_sum(given);
-    __syncthreads();
-    const long long left = remaining - given;
-    if (left > 0) {
-      const long long cycles = left / nf, rem = left % nf;
-      for (int j = lane; j < nf; j += 64) {
-        const double fj = frac[j];
-        int rank = 0;
-        for (int t = 0; t < nf; ++t) {
-          const double ft = frac[t];
-          rank += (ft > fj) || (ft == fj && t < j);
-        }
-        base[j] += cycles + (rank < rem ? 1 : 0);
-      }
-    } else if (left < 0) {
-      if (lane == 0) {
-        long long l = left;
-        int guard = 0;
-        while (l < 0 && guard < 4 * nf) {
-          const int want = nf - 1 - (guard % nf);
-          for (int j = 0; j < nf; ++j) {
-            int rank = 0;
-            for (int t = 0; t < nf; ++t) rank += (frac[t] > frac[j]) || (frac[t] == frac[j] && t < j);
-            if (rank == want && base[j] > 0 && l < 0) {
-              base[j] -= 1;
-              l += 1;
-            }
-          }
-          ++guard;
-        }
-      }
-    }
-    __syncthreads();
-    long long excess = 0, deficit = 0, n_over = 0, n_under = 0;
-    for (int j = lane; j < nf; j += 64) {
-      const int i = freel[j];
-      if (base[j] > hi[i]) { excess += base[j] - hi[i]; ++n_over; }
-      if (base[j] < lo[i]) { deficit += lo[i] - base[j]; ++n_under; }
-    }
-    excess = wave_sum(excess);
-    deficit = wave_sum(deficit);
-    n_over = wave_sum(n_over);
-    n_under = wave_sum(n_under);
-    if (n_over == 0 && n_under == 0) {
-      for (int j = lane; j < nf; j += 64) out[freel[j]] = base[j];
-      break;
-    }
-    const bool pin_over = n_over > 0 && excess >= deficit;
-    if (lane == 0) {
-      int keep = 0;
-      long long rest = remaining;
-      for (int j = 0; j < nf; ++j) {
-        const int i = freel[j];
-        const bool pin = pin_over ? (base[j] > hi[i]) : (base[j] < lo[i]);
-        if (pin) {
-          out[i] = pin_over ? hi[i] : lo[i];
-          rest -= out[i];
-        } else {
-          freel[keep++] = i;
-        }
-      }
-      state[0] = rest;
-      state[1] = keep;
-    }
-    __syncthreads();
-    remaining = state[0];
-    nf = (int)state[1];
-    __syncthreads();
-  }
-  return 0;
-}
-
-struct BudgetScratch {
-  double ed[kMaxLayers], quota[kMaxLayers], frac[kMaxLayers];
-  long long base[kMaxLayers], lo[kMaxLayers], hi[kMaxLayers];
-  int freel[kMaxLayers];
-  long long state[2];
-};
-
 __global__ void __launch_bounds__(64) budgets_kernel(int n_layers, const float* __restrict__ e,
                                                      const int64_t* __restrict__ total,
                                                      const int64_t* __restrict__ lo,
@@ -262,7 +138,7 @@ __global__ void __launch_bounds__(64) budgets_kernel(int n_layers, const float* 
   }
   __syncthreads();
   long long* out_b = reinterpret_cast<long long*>(out) + b * n_layers;
-  const int bad = allocate_budgets_wave(n_layers, sc.ed, (long long)total[b], sc.lo, sc.hi, out_b, sc.quota,
+  const int bad = allocate_budgets_wave<BlockSync>((int)threadIdx.x, n_layers, sc.ed, (long long)total[b], sc.lo, sc.hi, out_b, sc.quota,
                                         sc.base, sc.freel, sc.frac, sc.state);
   if (bad)
     for (int i = threadIdx.x; i < n_layers; i += 64) out_b[i] = -1;
@@ -285,7 +161,7 @@ __global__ void __launch_bounds__(64) cascade_plan_kernel(int n_layers, int n_he
   }
   __syncthreads();
   long long* out_b = reinterpret_cast<long long*>(out);
-  const int bad = allocate_budgets_wave(n_layers, sc.ed, total, sc.lo, sc.hi, out_b, sc.quota, sc.base, sc.freel,
+  const int bad = allocate_budgets_wave<BlockSync>((int)threadIdx.x, n_layers, sc.ed, total, sc.lo, sc.hi, out_b, sc.quota, sc.base, sc.freel,
                                         sc.frac, sc.state);
   if (bad)
     for (int i = threadIdx.x; i < n_layers; i += 64) out_b[i] = -1;

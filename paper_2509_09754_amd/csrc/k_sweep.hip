@@ -20,6 +20,7 @@
 //   scores : D = Q * K_tile^T  -> a lane holds 16 query rows of ONE key: the window mean stays in-lane
 #include <math.h>
 
+#include "budget_wave.h"
 #include "common.h"
 #include "tile_ring.h"
 #include "xblock.h"
@@ -60,9 +61,11 @@ struct Shape {
 
 // Layer statistic from per-lane partial sums S = sum s, T = sum s ln s (fp64): fixed-order reduction
 // over lanes (xor tree), wavefronts and, by the last workgroup to arrive, workgroups; then
-// e = (ln S - T / S) / n_entries  (Eq. 4-5 in closed form).  Contains workgroup barriers.
+// e = (ln S - T / S) / n_entries  (Eq. 4-5 in closed form).  Contains workgroup barriers.  Returns true in
+// every thread of that last workgroup, whose thread 0 has then also left the statistic (as stored,
+// rounded to fp32) in s_t[0] for whatever the workgroup does next with it (not yet published by a barrier).
 template <int THREADS>
-__device__ __forceinline__ void entropy_finish(double acc_s, double acc_t, double2* __restrict__ ent_part,
+__device__ __forceinline__ bool entropy_finish(double acc_s, double acc_t, double2* __restrict__ ent_part,
                                                uint32_t* __restrict__ counters, unsigned int n_blocks,
                                                unsigned int block_id, double n_entries,
                                                float* __restrict__ layer_stat, double* s_s, double* s_t,
@@ -81,7 +84,7 @@ __device__ __forceinline__ void entropy_finish(double acc_s, double acc_t, doubl
     st_dev_f64(&mine->x, S);
     st_dev_f64(&mine->y, Tt);
   }
-  if (!arrive_last(&counters[kCounterPool], n_blocks, block_id, s_last)) return;
+  if (!arrive_last(&counters[kCounterPool], n_blocks, block_id, s_last)) return false;
   // last workgroup: thread t sums partials t, t + THREADS, ... then the same fixed tree as above
   double S = 0.0, Tt = 0.0;
   for (unsigned int i = threadIdx.x; i < n_blocks; i += THREADS) {
@@ -95,13 +98,79 @@ __device__ __forceinline__ void entropy_finish(double acc_s, double acc_t, doubl
   __syncthreads();
   if ((threadIdx.x & 63) == 0) { s_s[threadIdx.x >> 6] = S; s_t[threadIdx.x >> 6] = Tt; }
   __syncthreads();
-  if (threadIdx.x != 0) return;
+  if (threadIdx.x != 0) return true;
   S = 0.0; Tt = 0.0;
   for (int i = 0; i < kW; ++i) { S += s_s[i]; Tt += s_t[i]; }
   double e = 0.0;
   if (S > 0.0) e = (log(S) - Tt / S) / n_entries;
   if (error_word != nullptr && ld_dev(error_word) != 0u) e = (double)NAN;   // scores of this call are not to be used
   layer_stat[0] = (float)e;
+  s_t[0] = (double)(float)e;
+  return true;
+}
+
+// What the budget rule reads, fetched by the lanes of wavefront 0 well before the statistic exists (any
+// workgroup may turn out to be the one that forms it; the loads are few and hit in L2): layers lane and
+// lane + 64 of sequence b's rows.
+struct PlanInputs {
+  long long lo[2], hi[2], total;
+  float e[2];
+};
+static_assert(kMaxPlannedLayers <= 128, "two layers per lane");
+__device__ __forceinline__ PlanInputs plan_prefetch(const BudgetPlanArgs& plan, int b) {
+  PlanInputs in = {};
+  if (plan.e == nullptr || threadIdx.x >= 64) return in;
+  const long long row = (long long)b * plan.n_layers;
+  in.total = (long long)plan.total[b];
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int i = (int)threadIdx.x + 64 * j;
+    if (i < plan.n_layers) {
+      in.lo[j] = (long long)plan.lo[row + i];
+      in.hi[j] = (long long)plan.hi[row + i];
+      if (i != plan.layer) in.e[j] = plan.e[row + i];
+    }
+  }
+  return in;
+}
+
+// Budgets of sequence b of the batch from the statistics of its layers (Alg. 2, inner loop), by
+// wavefront 0 of the workgroup that has just formed the statistic e_new of layer plan.layer: the same
+// routine, on the same values, as the budgets kernel.  `lds`: sizeof(BudgetScratchT<kMaxPlannedLayers>)
+// bytes, 8-aligned, that no other wavefront of the workgroup touches meanwhile.  A NaN statistic (a
+// failed launch) leaves all budgets of the sequence at -1.
+__device__ __forceinline__ void plan_budgets(const BudgetPlanArgs& plan, const PlanInputs& in, int b, float e_new,
+                                             void* lds) {
+  if (threadIdx.x >= 64) return;
+  using Scratch = BudgetScratchT<kMaxPlannedLayers>;
+  Scratch* sc = static_cast<Scratch*>(lds);
+  const int lane = (int)threadIdx.x, n = plan.n_layers;
+  const long long row = (long long)b * n;
+#pragma unroll
+  for (int j = 0; j < 2; ++j) {
+    const int i = lane + 64 * j;
+    if (i < n) {
+      sc->ed[i] = i == plan.layer ? (double)e_new : (double)in.e[j];
+      sc->lo[i] = in.lo[j];
+      sc->hi[i] = in.hi[j];
+    }
+  }
+  if (lane == 0) plan.e[row + plan.layer] = e_new;
+  WaveSync::sync();
+  long long* out_b = reinterpret_cast<long long*>(plan.out) + row;
+  int bad = e_new != e_new ? 1 : 0;
+  if (n == 1) {
+    // a single layer takes the whole total (its quota is total * e / e, exactly), if the bounds allow it:
+    // what the rule below returns, without its reductions across the wavefront
+    const long long lo0 = __shfl(in.lo[0], 0), hi0 = __shfl(in.hi[0], 0);
+    if (lane == 0) out_b[0] = (!bad && lo0 >= 0 && lo0 <= in.total && in.total <= hi0) ? in.total : -1;
+    return;
+  }
+  if (!bad)
+    bad = allocate_budgets_wave<WaveSync>(lane, n, sc->ed, in.total, sc->lo, sc->hi, out_b, sc->quota, sc->base,
+                                          sc->freel, sc->frac, sc->state);
+  if (bad)
+    for (int i = lane; i < n; i += 64) out_b[i] = -1;
 }
 
 // The statistics sweep of one wavefront: tiles first, first + WAVES, ... (cnt of them) of the head
@@ -419,6 +488,8 @@ struct PoolArgs {
   uint32_t* counters;
   const uint32_t* error_word; // persistent launch: non-zero once a wait for other workgroups gave up (statistic -> NaN); else null
   unsigned int* sel_hist0;    // first-digit histogram of the selection that will rank these scores, or null
+  BudgetPlanArgs plan;        // budgets right after the statistic (e == nullptr: none)
+  int plan_seq;               // the sequence's row in the plan's tables
 };
 
 // Histogram of the selection's first digit over the scores a workgroup has just written, for a selection
@@ -628,6 +699,7 @@ __device__ __forceinline__ void scores_finish(const PoolArgs& pa, float vb, int 
   // `bins`: kSelBins words of LDS that only wavefront 0 has used since the workgroup's last barrier (the
   // start of its own tile ring, which it is done with)
   const bool count_digits = pa.sel_hist0 != nullptr;
+  const PlanInputs plan_in = plan_prefetch(pa.plan, pa.plan_seq);
   if (count_digits && wave == 0)
     for (int i = threadIdx.x; i < kSelBins; i += 64) bins[i] = 0u;
   unsigned int run_digit = 0u, run_len = 0u;
@@ -708,8 +780,15 @@ __device__ __forceinline__ void scores_finish(const PoolArgs& pa, float vb, int 
     if (count_digits) digit0_count(bins, INFINITY, run_digit, run_len);
   }
   if (count_digits) digit0_flush<THREADS>(bins, run_digit, run_len, pa.sel_hist0);
-  entropy_finish<THREADS>(acc_s, acc_t, pa.ent_part, pa.counters, n_blocks, block_id,
-                          (double)n_heads * (double)n_prefix, pa.layer_stat, s_s, s_t, s_last, pa.error_word);
+  const bool last = entropy_finish<THREADS>(acc_s, acc_t, pa.ent_part, pa.counters, n_blocks, block_id,
+                                            (double)n_heads * (double)n_prefix, pa.layer_stat, s_s, s_t, s_last,
+                                            pa.error_word);
+  if (last && pa.plan.e != nullptr) {                        // uniform
+    __syncthreads();                                         // s_t[0]; every wavefront is done with `bins`
+    // scratch: what is left of wavefront 0's own tile ring behind the bins
+    static_assert(kSelBins * 4 + sizeof(BudgetScratchT<kMaxPlannedLayers>) <= 16 * 1024, "wavefront 0's ring");
+    plan_budgets(pa.plan, plan_in, pa.plan_seq, (float)s_t[0], bins + kSelBins);
+  }
 }
 
 template <int DT, int D, int GT, bool FUSED, int W>
@@ -741,6 +820,8 @@ scores_kernel(const SweepArgs a) {
   pa.counters = reinterpret_cast<uint32_t*>(region + a.off_counter);
   pa.error_word = nullptr;
   pa.sel_hist0 = a.sel_ws ? reinterpret_cast<unsigned int*>(a.sel_ws + (size_t)seq * a.sel_stride + a.sel_off_hist) : nullptr;
+  pa.plan = a.plan;
+  pa.plan_seq = seq;
   constexpr int kWaves = Shape<DT, D, W>::kWaves;
   constexpr int kStages = Shape<DT, D, W>::kStages;
   __shared__ u32x4 s_tile[kWaves][kStages][T::kTileChunks];
@@ -1072,6 +1153,8 @@ sweep_kernel(const SweepArgs a) {
     pa.counters = ctl;
     pa.error_word = &ctl0[kCtlError];
     pa.sel_hist0 = a.sel_ws ? reinterpret_cast<unsigned int*>(a.sel_ws + (size_t)seq * a.sel_stride + a.sel_off_hist) : nullptr;
+    pa.plan = a.plan;
+    pa.plan_seq = seq;
     float vb = 0.0f;   // this thread's share of the head's value-norm partials (an earlier launch wrote them)
     for (int i = threadIdx.x; i < pa.vnorm_blocks; i += kThreads)
       vb = fmaxf(vb, pa.vnorm_part[(long long)g * pa.vnorm_blocks + i]);
@@ -1173,9 +1256,12 @@ __global__ void __launch_bounds__(kPoolThreads)
 poolstat_kernel(const float* __restrict__ s_raw, long long n, int w, int pool_half, int token_norm,
                 const float* __restrict__ vnorm_part, int vnorm_blocks, float* __restrict__ scores,
                 float* __restrict__ vbar, float* __restrict__ layer_stat,
-                double2* __restrict__ ent_part, uint32_t* __restrict__ counters, unsigned int* __restrict__ sel_hist0) {
+                double2* __restrict__ ent_part, uint32_t* __restrict__ counters, unsigned int* __restrict__ sel_hist0,
+                const BudgetPlanArgs plan, int plan_seq) {
   __shared__ float s_in[kPoolChunk + 2 * kPoolMaxHalf];
+  __shared__ BudgetScratchT<kMaxPlannedLayers> s_plan;
   __shared__ unsigned int s_bins[kSelBins];
+  const PlanInputs plan_in = plan_prefetch(plan, plan_seq);
   if (sel_hist0 != nullptr)
     for (int i = threadIdx.x; i < kSelBins; i += kPoolThreads) s_bins[i] = 0u;      // published by the barrier below
   unsigned int run_digit = 0u, run_len = 0u;
@@ -1221,9 +1307,13 @@ poolstat_kernel(const float* __restrict__ s_raw, long long n, int w, int pool_ha
     }
   }
   if (sel_hist0 != nullptr) digit0_flush<kPoolThreads>(s_bins, run_digit, run_len, sel_hist0);
-  entropy_finish<kPoolThreads>(acc_s, acc_t, ent_part, counters, gridDim.x * gridDim.y,
-                               blockIdx.y * gridDim.x + blockIdx.x, (double)gridDim.y * (double)n_prefix,
-                               layer_stat, s_s, s_t, &s_last);
+  const bool last = entropy_finish<kPoolThreads>(acc_s, acc_t, ent_part, counters, gridDim.x * gridDim.y,
+                                                 blockIdx.y * gridDim.x + blockIdx.x,
+                                                 (double)gridDim.y * (double)n_prefix, layer_stat, s_s, s_t, &s_last);
+  if (last && plan.e != nullptr) {
+    __syncthreads();
+    plan_budgets(plan, plan_in, plan_seq, (float)s_t[0], &s_plan);
+  }
 }
 
 __global__ void __launch_bounds__(256) fill_zero_kernel(float* __restrict__ p, long long count) {
@@ -1463,12 +1553,12 @@ int32_t launch_scores(const lava_layer_desc& d, const SweepArgs& a, int max_bloc
 int32_t launch_poolstat(const lava_layer_desc& d, int64_t n, const float* s_raw,
                         const float* vnorm_part, int vnorm_blocks, float* scores, float* vbar,
                         float* layer_stat, double2* ent_part, uint32_t* counters, unsigned int* sel_hist0,
-                        hipStream_t s) {
+                        const BudgetPlanArgs& plan, int plan_seq, hipStream_t s) {
   const dim3 grid(pool_blocks(d, n), d.n_kv_heads), block(kPoolThreads);
   ProfScope ps(KID_POOLSTAT, s);
   hipLaunchKernelGGL(poolstat_kernel, grid, block, 0, s, s_raw, (long long)n, d.window,
                      d.pool_kernel / 2, d.score_kind == LAVA_SCORE_TOKEN_NORM ? 1 : 0, vnorm_part, vnorm_blocks, scores, vbar, layer_stat, ent_part,
-                     counters, sel_hist0);
+                     counters, sel_hist0, plan, plan_seq);
   return launch_status();
 }
 

@@ -4,6 +4,7 @@
 
 #include <vector>
 
+#include "budget_wave.h"
 #include "common.h"
 
 namespace lava {
@@ -149,9 +150,14 @@ static int32_t window_scores(const lava_layer_desc* desc, int32_t batch, const i
                              const void* q_win, const void* k, const void* v, const float* lse,
                              float* scores, float* vbar, float* layer_stat, void* workspace,
                              size_t workspace_bytes, void* select_ws, size_t select_ws_bytes, bool primed,
-                             void* hip_stream) {
+                             const lava_budget_plan* budget_plan, void* hip_stream) {
   int32_t st = check_desc(desc);
   if (st != LAVA_OK) return st;
+  if (budget_plan != nullptr &&
+      (budget_plan->n_layers < 1 || budget_plan->n_layers > LAVA_PLAN_MAX_LAYERS || budget_plan->layer < 0 ||
+       budget_plan->layer >= budget_plan->n_layers || budget_plan->e == nullptr || budget_plan->total == nullptr ||
+       budget_plan->lo == nullptr || budget_plan->hi == nullptr || budget_plan->budgets == nullptr))
+    return LAVA_ERR_INVALID_ARG;
   if (batch < 1 || seq_lens == nullptr || q_win == nullptr || k == nullptr || v == nullptr ||
       scores == nullptr || vbar == nullptr || layer_stat == nullptr)
     return LAVA_ERR_INVALID_ARG;
@@ -186,6 +192,10 @@ static int32_t window_scores(const lava_layer_desc* desc, int32_t batch, const i
   a.sel_stride = sel_layout.bytes;
   a.sel_off_hist = sel_layout.off_hist;
   a.sel_off_state = sel_layout.off_state;
+  a.plan = BudgetPlanArgs{};
+  if (budget_plan != nullptr)
+    a.plan = BudgetPlanArgs{budget_plan->e,  budget_plan->total,    budget_plan->lo,   budget_plan->hi,
+                            budget_plan->budgets, budget_plan->n_layers, budget_plan->layer};
   a.q_win = q_win;
   a.k = k;
   a.v = v;
@@ -296,7 +306,7 @@ static int32_t window_scores(const lava_layer_desc* desc, int32_t batch, const i
                            reinterpret_cast<uint32_t*>(reg + a.off_counter),
                            a.sel_ws ? reinterpret_cast<unsigned int*>(a.sel_ws + (size_t)b0 * a.sel_stride + a.sel_off_hist)
                                     : nullptr,
-                           s);
+                           a.plan, b0, s);
       if (st != LAVA_OK) return st;
     }
   }
@@ -308,7 +318,7 @@ int32_t lava_window_scores(const lava_layer_desc* desc, int32_t batch, const int
                            float* scores, float* vbar, float* layer_stat, void* workspace,
                            size_t workspace_bytes, void* hip_stream) {
   return window_scores(desc, batch, seq_lens, q_win, k, v, lse, scores, vbar, layer_stat, workspace, workspace_bytes,
-                       nullptr, 0, false, hip_stream);
+                       nullptr, 0, false, nullptr, hip_stream);
 }
 
 int32_t lava_window_scores_primed(const lava_layer_desc* desc, int32_t batch, const int64_t* seq_lens,
@@ -317,7 +327,18 @@ int32_t lava_window_scores_primed(const lava_layer_desc* desc, int32_t batch, co
                                   size_t workspace_bytes, void* select_workspace, size_t select_workspace_bytes,
                                   void* hip_stream) {
   return window_scores(desc, batch, seq_lens, q_win, k, v, lse, scores, vbar, layer_stat, workspace, workspace_bytes,
-                       select_workspace, select_workspace_bytes, true, hip_stream);
+                       select_workspace, select_workspace_bytes, true, nullptr, hip_stream);
+}
+
+int32_t lava_window_scores_planned(const lava_layer_desc* desc, int32_t batch, const int64_t* seq_lens,
+                                   const void* q_win, const void* k, const void* v, const float* lse,
+                                   float* scores, float* vbar, float* layer_stat, void* workspace,
+                                   size_t workspace_bytes, void* select_workspace, size_t select_workspace_bytes,
+                                   const lava_budget_plan* plan, void* hip_stream) {
+  static_assert(LAVA_PLAN_MAX_LAYERS == kMaxPlannedLayers, "header and kernels agree on the plan's depth");
+  const bool primed = select_workspace != nullptr || select_workspace_bytes != 0;
+  return window_scores(desc, batch, seq_lens, q_win, k, v, lse, scores, vbar, layer_stat, workspace, workspace_bytes,
+                       select_workspace, select_workspace_bytes, primed, plan, hip_stream);
 }
 
 int32_t lava_layer_budgets(int32_t batch, int32_t n_layers, const float* e, const int64_t* total,

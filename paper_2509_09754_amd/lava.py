@@ -24,7 +24,7 @@ LAVA_SCORE_LAVA, LAVA_SCORE_ATTENTION, LAVA_SCORE_TOKEN_NORM = 0, 1, 2
 
 EXPORTS = [
     "lava_status_string", "lava_set_tuning", "lava_get_tuning", "lava_window_scores_workspace_bytes", "lava_window_scores",
-    "lava_window_scores_primed", "lava_select_topk_primed",
+    "lava_window_scores_primed", "lava_select_topk_primed", "lava_window_scores_planned",
     "lava_layer_budgets", "lava_select_workspace_bytes", "lava_select_topk", "lava_select_status",
     "lava_select_topk_static",
     "lava_select_batch_workspace_bytes", "lava_select_topk_batch", "lava_select_batch_status",
@@ -65,6 +65,14 @@ class Tuning(ctypes.Structure):
 
 
 SWEEP_SHAPES = {"auto": 0, "wide": 1, "narrow": 2}
+class BudgetPlan(ctypes.Structure):
+    """lava_budget_plan"""
+    _fields_ = [("n_layers", ctypes.c_int32), ("layer", ctypes.c_int32), ("e", ctypes.c_void_p),
+                ("total", ctypes.c_void_p), ("lo", ctypes.c_void_p), ("hi", ctypes.c_void_p),
+                ("budgets", ctypes.c_void_p)]
+
+
+LAVA_PLAN_MAX_LAYERS = 128
 SWEEP_SCHEDULES = {"auto": 0, "separate": 1, "persistent": 2, "prepass": 3}
 
 
@@ -94,6 +102,8 @@ def _load() -> ctypes.CDLL:
     lib.lava_window_scores.argtypes = [dp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lava_window_scores_primed.restype = i32
     lib.lava_window_scores_primed.argtypes = [dp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, sz, vp]
+    lib.lava_window_scores_planned.restype = i32
+    lib.lava_window_scores_planned.argtypes = [dp, i32, vp, vp, vp, vp, vp, vp, vp, vp, vp, sz, vp, sz, vp, vp]
     lib.lava_select_topk_primed.restype = i32
     lib.lava_select_topk_primed.argtypes = [i32, vp, i64, i64, vp, vp, vp, vp, vp, vp, sz, vp]
     lib.lava_layer_budgets.restype = i32
@@ -204,9 +214,10 @@ def lava_window_scores_workspace_bytes(desc: LayerDesc, batch: int, total_tokens
 
 def lava_window_scores(desc: LayerDesc, seq_lens: Sequence[int], q_win: torch.Tensor, k: torch.Tensor,
                        v: torch.Tensor, lse: Optional[torch.Tensor] = None, scores=None, vbar=None,
-                       layer_stat=None, workspace=None, stream=None, select_workspace=None):
+                       layer_stat=None, workspace=None, stream=None, select_workspace=None, budget_plan=None):
     """Scores [sum_b H_kv * N_b] (per sequence [H_kv][N_b]), vbar [batch, H_kv], layer_stat [batch].
-    With select_workspace the call is lava_window_scores_primed."""
+    With select_workspace the call is lava_window_scores_primed; with budget_plan (see make_budget_plan)
+    it is lava_window_scores_planned, which also accepts select_workspace."""
     lens = np.ascontiguousarray(np.asarray(seq_lens, dtype=np.int64))
     batch, total = int(lens.shape[0]), int(lens.sum())
     dev = k.device
@@ -229,6 +240,14 @@ def lava_window_scores(desc: LayerDesc, seq_lens: Sequence[int], q_win: torch.Te
     if workspace is None:
         nbytes = lava_window_scores_workspace_bytes(desc, batch, total)
         workspace = torch.empty(max(nbytes, 256), dtype=torch.uint8, device=dev)
+    if budget_plan is not None:
+        st = lib.lava_window_scores_planned(ctypes.byref(desc), batch, lens.ctypes.data_as(ctypes.c_void_p), _ptr(q_win),
+                                            _ptr(k), _ptr(v), _ptr(lse), _ptr(scores), _ptr(vbar), _ptr(layer_stat),
+                                            _ptr(workspace), workspace.numel(), _ptr(select_workspace),
+                                            select_workspace.numel() if select_workspace is not None else 0,
+                                            ctypes.byref(budget_plan), _stream(stream))
+        _check(st, "lava_window_scores_planned")
+        return scores, vbar, layer_stat
     if select_workspace is not None:
         st = lib.lava_window_scores_primed(ctypes.byref(desc), batch, lens.ctypes.data_as(ctypes.c_void_p), _ptr(q_win),
                                            _ptr(k), _ptr(v), _ptr(lse), _ptr(scores), _ptr(vbar), _ptr(layer_stat),
@@ -241,6 +260,19 @@ def lava_window_scores(desc: LayerDesc, seq_lens: Sequence[int], q_win: torch.Te
                                 _ptr(workspace), workspace.numel(), _stream(stream))
     _check(st, "lava_window_scores")
     return scores, vbar, layer_stat
+
+
+def make_budget_plan(e: torch.Tensor, layer: int, total: torch.Tensor, lo: torch.Tensor, hi: torch.Tensor,
+                     budgets: torch.Tensor) -> "BudgetPlan":
+    """lava_budget_plan over device tensors e [batch, L] float32 (column `layer` is written by the scores
+    call), total [batch], lo / hi / budgets [batch, L] int64.  The plan holds pointers only: keep the tensors."""
+    batch, L = e.shape
+    for name, t, dt in (("e", e, torch.float32), ("total", total, torch.int64), ("lo", lo, torch.int64),
+                        ("hi", hi, torch.int64), ("budgets", budgets, torch.int64)):
+        _dev(t, name, dt)
+    if total.numel() != batch or lo.numel() != batch * L or hi.numel() != batch * L or budgets.numel() != batch * L:
+        raise ValueError("budget plan tables must be [batch] / [batch, L]")
+    return BudgetPlan(L, int(layer), e.data_ptr(), total.data_ptr(), lo.data_ptr(), hi.data_ptr(), budgets.data_ptr())
 
 
 def lava_layer_budgets(e, total, lo, hi, budgets=None, stream=None):

@@ -115,6 +115,22 @@ def test_window_scores_argument_errors():
     assert prm(ctypes.c_void_p(0x10010), need) == lava.LAVA_ERR_WORKSPACE
     assert lava.lava_window_scores_workspace_bytes(good, 1, 4096) > 8 * 4064 * 4
     assert lava.lava_window_scores_workspace_bytes(_desc(head_dim=100), 1, 4096) == 0
+    # a budget plan is validated before anything is launched
+    one = np.asarray([4096], dtype=np.int64)
+    def planned(plan):
+        return lava.lib.lava_window_scores_planned(
+            ctypes.byref(good), 1, one.ctypes.data_as(ctypes.c_void_p), FAKE, FAKE, FAKE, None, FAKE, FAKE, FAKE, None,
+            0, None, 0, ctypes.byref(plan), None)
+    fake = FAKE.value
+    assert planned(lava.BudgetPlan(4, 1, fake, fake, fake, fake, fake)) == lava.LAVA_ERR_WORKSPACE   # plan accepted
+    assert planned(lava.BudgetPlan(0, 0, fake, fake, fake, fake, fake)) == lava.LAVA_ERR_INVALID_ARG
+    assert planned(lava.BudgetPlan(lava.LAVA_PLAN_MAX_LAYERS + 1, 0, fake, fake, fake, fake, fake)) == lava.LAVA_ERR_INVALID_ARG
+    assert planned(lava.BudgetPlan(4, 4, fake, fake, fake, fake, fake)) == lava.LAVA_ERR_INVALID_ARG
+    assert planned(lava.BudgetPlan(4, -1, fake, fake, fake, fake, fake)) == lava.LAVA_ERR_INVALID_ARG
+    for missing in range(5):
+        ptrs = [fake] * 5
+        ptrs[missing] = None
+        assert planned(lava.BudgetPlan(4, 1, *ptrs)) == lava.LAVA_ERR_INVALID_ARG
 
 
 def test_workspace_size_never_shrinks_with_length():

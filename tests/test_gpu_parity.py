@@ -701,3 +701,92 @@ def test_primed_ragged_batch_and_mixed_table(lava):
         for a, b in zip(outs[i], want):
             assert torch.equal(a.view(torch.int32) if a.dtype == torch.float32 else a,
                                b.view(torch.int32) if b.dtype == torch.float32 else b), i
+
+
+PLANNED_CASES = [
+    # name, shapes of the batch, layers sharing the total, schedule
+    ("cfg1-one-layer", [synth.config(1)], 1, "auto"),
+    ("cfg2-9k-5-layers", [synth.config(2, n=9000 + 5, budget=8 * 64)], 5, "auto"),
+    ("cfg2-9k-128-layers-persistent", [synth.config(2, n=9000 + 5, budget=8 * 64)], 128, "persistent"),
+    ("G8-two-chunks-7-layers", [synth.LayerShape(16, 2, 128, 2100, 32, "bf16", 300)], 7, "auto"),
+    ("ragged-batch-of-3", [synth.config(2, n=n, budget=8 * 64) for n in (4096, 1500 + 3, 7000 + 11)], 4, "auto"),
+]
+
+
+@pytest.mark.parametrize("name,shapes,n_layers,schedule", PLANNED_CASES, ids=[c[0] for c in PLANNED_CASES])
+def test_scores_that_also_form_the_budgets(lava, name, shapes, n_layers, schedule, tuning):
+    """lava_window_scores_planned: scores, statistic and the prepared selection are those of the plain calls
+    bit for bit, column `layer` of the statistics table receives the statistic, and the budgets equal what
+    lava_layer_budgets returns for the same tables on the device, on the host, and the oracle's rule;
+    bounds that pin layers, and infeasible bounds (-1 everywhere), included."""
+    say(f"planned scores, {name}")
+    tuning(sweep_schedule=schedule)
+    rng = np.random.default_rng(41)
+    sh0, batch = shapes[0], len(shapes)
+    Hkv = sh0.n_kv_heads
+    inps = [synth.gen_layer(sh, 60 + i) for i, sh in enumerate(shapes)]
+    desc = lava.LayerDesc.make(sh0.n_q_heads, Hkv, sh0.head_dim, sh0.window, sh0.dtype, pool_kernel=sh0.pool_kernel)
+    q = torch.cat([lava.to_device(i.q_win, sh0.dtype).reshape(-1) for i in inps])
+    k = torch.cat([lava.to_device(i.k, sh0.dtype).reshape(-1) for i in inps])
+    v = torch.cat([lava.to_device(i.v, sh0.dtype).reshape(-1) for i in inps])
+    lens = [s.n for s in shapes]
+    s0, vb0, e0 = lava.lava_window_scores(desc, lens, q, k, v)
+    torch.cuda.synchronize()
+    e_new = e0.cpu().numpy()
+    for trial, layer in enumerate(sorted({0, n_layers // 2, n_layers - 1})):
+        # statistics of the other layers around this one's, bounds that pin some layers on either side
+        e_host = (e_new[:, None] * rng.uniform(0.3, 3.0, size=(batch, n_layers))).astype(np.float32)
+        dense = np.asarray([Hkv * n for n in lens], dtype=np.int64)
+        lo_host = np.full((batch, n_layers), Hkv * sh0.window, dtype=np.int64)
+        hi_host = np.repeat(dense[:, None], n_layers, axis=1)
+        total_host = (dense * n_layers * rng.uniform(0.2, 0.6, size=batch)).astype(np.int64)
+        if n_layers > 2:
+            hi_host[:, 1] = lo_host[:, 1] + 5                               # an upper bound that binds
+            lo_host[:, 2] = np.minimum(hi_host[:, 2], total_host // 2)      # a lower bound that binds
+        if trial == 1 and batch > 1:
+            total_host[1] = Hkv * sh0.window * n_layers - 1                 # infeasible for sequence 1 only
+        e_tab = torch.from_numpy(e_host).cuda()
+        e_tab[:, layer] = -7.0                                              # must be overwritten by the call
+        total_t, lo_t, hi_t = (torch.from_numpy(a).cuda() for a in (total_host, lo_host, hi_host))
+        budgets = torch.full((batch, n_layers), -99, dtype=torch.int64, device="cuda")
+        plan = lava.make_budget_plan(e_tab, layer, total_t, lo_t, hi_t, budgets)
+        max_entries = Hkv * max(lens)
+        sel_ws = torch.empty(lava.lava_select_batch_workspace_bytes(batch, max_entries), dtype=torch.uint8, device="cuda")
+        s1, vb1, e1 = lava.lava_window_scores(desc, lens, q, k, v, select_workspace=sel_ws if trial != 1 else None,
+                                              budget_plan=plan)
+        torch.cuda.synchronize()
+        assert torch.equal(s0, s1) and torch.equal(vb0, vb1) and torch.equal(e0, e1)
+        assert torch.equal(e_tab[:, layer], e0)
+        e_full = e_tab.cpu().numpy()
+        want_dev = lava.lava_layer_budgets(e_tab, total_t, lo_t, hi_t).cpu().numpy()
+        got = budgets.cpu().numpy()
+        assert np.array_equal(got, want_dev), (layer, got, want_dev)
+        for b in range(batch):
+            if trial == 1 and batch > 1 and b == 1:
+                assert np.all(got[b] == -1)
+                continue
+            want = O.layer_budgets(e_full[b].astype(np.float64), int(total_host[b]), lo_host[b].tolist(), hi_host[b].tolist())
+            assert got[b].tolist() == want, (layer, b)
+            assert np.array_equal(lava.lava_layer_budgets(e_full[b], [total_host[b]], lo_host[b], hi_host[b])[0], got[b])
+            assert got[b].sum() == total_host[b] and np.all(got[b] >= lo_host[b]) and np.all(got[b] <= hi_host[b])
+        if trial != 1:                                                      # the prepared selection, with its planned budget
+            tok = 0
+            for b, n in enumerate(lens):
+                seg = s1[Hkv * tok: Hkv * (tok + n)]
+                B = int(min(got[b, layer], Hkv * n))
+                region = sel_ws[b * (sel_ws.numel() // batch): (b + 1) * (sel_ws.numel() // batch)]
+                if batch == 1:
+                    c1, o1, i1, _ = lava.lava_select_topk(Hkv, seg, Hkv * n, budget_dev=budgets[b, layer: layer + 1],
+                                                          workspace=region, primed=True)
+                    c2, o2, i2, _ = lava.lava_select_topk(Hkv, seg, B)
+                    torch.cuda.synchronize()
+                    assert torch.equal(c1, c2) and torch.equal(o1, o2) and torch.equal(i1[:B], i2[:B])
+                tok += n
+    if n_layers == 1:                                                       # a single layer: total outside its bounds
+        for total_bad in (int(hi_host[0, 0]) + 1, int(lo_host[0, 0]) - 1):
+            total_t = torch.full((batch,), total_bad, dtype=torch.int64, device="cuda")
+            plan = lava.make_budget_plan(e_tab, 0, total_t, lo_t, hi_t, budgets)
+            lava.lava_window_scores(desc, lens, q, k, v, budget_plan=plan)
+            torch.cuda.synchronize()
+            assert torch.equal(budgets, lava.lava_layer_budgets(e_tab, total_t, lo_t, hi_t))
+            assert bool((budgets == -1).all())
