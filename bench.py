@@ -322,7 +322,8 @@ def ragged_batch(lava, synth, torch, np, dev, args):
     sel = []
     for b, n in enumerate(lens):
         a0, a1 = int(starts[b]) * Hkv, int(starts[b + 1]) * Hkv
-        sel.append(lava.select_problem(scores[a0:a1], B, counts[b], offs[b], idx[b], kept[b], budget_dev=budgets[b]))
+        sel.append(lava.select_problem(scores[a0:a1], B, counts[b], offs[b], idx[b], kept[b], budget_dev=budgets[b],
+                                       primed=not args.no_primed))
     sel_table = (lava.SelectProblem * len(lens))(*sel)
     cmp_tables = []
     for _, k, v in sets:
@@ -332,8 +333,14 @@ def ragged_batch(lava, synth, torch, np, dev, args):
             cmp.append(lava.compact_problem(desc, n, k[a0:a1], v[a0:a1], offs[b], idx[b], B, k_hat[b], v_hat[b]))
         cmp_tables.append((lava.CompactProblem * len(lens))(*cmp))
 
+    # budgets of every sequence (one layer each here) formed by the scores call, or by a launch of their own
+    planned = not args.no_plan
+    e_table = torch.zeros(len(lens), 1, dtype=torch.float32, device=dev)
+    plan = lava.make_budget_plan(e_table, 0, total_b, lo, hi, budgets) if planned else None
+
     def tail_batched(i):
-        lava.lava_layer_budgets(stat.view(-1, 1), total_b, lo, hi, budgets=budgets)
+        if not planned:
+            lava.lava_layer_budgets(stat.view(-1, 1), total_b, lo, hi, budgets=budgets)
         lava.lava_select_topk_batch(Hkv, sel_table, Hkv * max(lens), workspace=ws_batch)
         lava.lava_compact_batch(desc, cmp_tables[i % n_sets])
 
@@ -347,7 +354,8 @@ def ragged_batch(lava, synth, torch, np, dev, args):
 
     def step_batched(i):
         q, k, v = sets[i % n_sets]
-        lava.lava_window_scores(desc, lens, q, k, v, scores=scores, vbar=vbar, layer_stat=stat, workspace=ws)
+        lava.lava_window_scores(desc, lens, q, k, v, scores=scores, vbar=vbar, layer_stat=stat, workspace=ws,
+                                select_workspace=None if args.no_primed else ws_batch, budget_plan=plan)
         tail_batched(i)
 
     def step_one_by_one(i):
