@@ -6,6 +6,26 @@
 // atomic stores (write-through), the writer waits until its own stores have completed
 // (vmcnt == 0) before it takes a ticket, and readers use device-scope atomic loads, which do not
 // hit in caches that are not coherent across XCDs.  Nothing else is exchanged this way.
+//
+// What this rests on, and the rules that keep it valid:
+//  * Hardware, not the language's memory model: on gfx942 / gfx950 a device-scope atomic store goes
+//    through to memory that every XCD sees, its completion is what vmcnt counts, and a device-scope
+//    atomic load is served from there and not from a per-XCD cache line filled earlier.  Relaxed
+//    atomics carry no ordering of their own; the order "data, then ticket" comes from drain_vmem()
+//    (the writer's stores have completed before the ticket is taken) and from the reader's data
+//    dependence on the ticket it has seen.
+//  * Every word of a published buffer is written ONLY with st_dev* and read by other workgroups ONLY
+//    with ld_dev* (or device-scope atomic adds on both sides, as for histograms).  A plain store to
+//    such a buffer may sit in the writer's L2 past the ticket; a plain load may hit a stale line.
+//    Published buffers in this library: the statistic partials (ent_part), the statistics partials
+//    of the persistent sweep and its unit / completion words, the selection's histograms, published
+//    counts, state words and head_counts of a prepared selection.
+//  * Counters and tickets must be zero before the launch that uses them: they are cleared by an
+//    EARLIER kernel of the same call on the same stream (the value-norm / statistics launch, the
+//    selection's init kernel) or by the same kernel before a grid-wide wait that every workgroup passes;
+//    never by a memset node (a caller may capture the calls in a graph).
+//  * Stress test: tests/test_gpu_parity.py runs launches of over a thousand workgroups thirty times and
+//    requires the bits of the first run every time.
 #pragma once
 
 #include <hip/hip_runtime.h>

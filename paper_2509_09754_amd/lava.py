@@ -64,15 +64,15 @@ class Tuning(ctypes.Structure):
     ]
 
 
-SWEEP_SHAPES = {"auto": 0, "wide": 1, "narrow": 2}
 class BudgetPlan(ctypes.Structure):
-    """lava_budget_plan"""
+    """Mirror of lava_budget_plan (device pointers; see make_budget_plan)."""
     _fields_ = [("n_layers", ctypes.c_int32), ("layer", ctypes.c_int32), ("e", ctypes.c_void_p),
                 ("total", ctypes.c_void_p), ("lo", ctypes.c_void_p), ("hi", ctypes.c_void_p),
                 ("budgets", ctypes.c_void_p)]
 
 
 LAVA_PLAN_MAX_LAYERS = 128
+SWEEP_SHAPES = {"auto": 0, "wide": 1, "narrow": 2}
 SWEEP_SCHEDULES = {"auto": 0, "separate": 1, "persistent": 2, "prepass": 3}
 
 
@@ -640,10 +640,16 @@ def probe_stream(src: torch.Tensor, dst: torch.Tensor, nbytes: int, mode: int, b
            "lava_probe_stream")
 
 
-def evict_layer(desc: LayerDesc, n: int, q_win, k, v, budget: int, lse=None, stream=None):
-    """The four calls in order for one sequence of one layer (fixed budget)."""
-    scores, vbar, stat = lava_window_scores(desc, [n], q_win, k, v, lse=lse, stream=stream)
-    counts, offs, idx, kept_s = lava_select_topk(desc.n_kv_heads, scores, budget, stream=stream)
+def evict_layer(desc: LayerDesc, n: int, q_win, k, v, budget: int, lse=None, stream=None, primed: bool = True):
+    """The calls of one layer in order for one sequence (fixed budget): scores, selection, compaction.
+    primed: the scores call prepares the selection's workspace (lava_window_scores_primed +
+    lava_select_topk_primed) instead of the plain pair; the results are the same."""
+    ws = None
+    if primed:
+        ws = torch.empty(max(lava_select_workspace_bytes(desc.n_kv_heads * n), 256), dtype=torch.uint8, device=k.device)
+    scores, vbar, stat = lava_window_scores(desc, [n], q_win, k, v, lse=lse, stream=stream, select_workspace=ws)
+    counts, offs, idx, kept_s = lava_select_topk(desc.n_kv_heads, scores, budget, stream=stream, workspace=ws,
+                                                 primed=primed)
     k_hat, v_hat = lava_compact_kv(desc, n, k, v, offs, idx, budget, stream=stream)
     return dict(scores=scores, vbar=vbar, layer_stat=stat, head_counts=counts, head_offsets=offs,
                 kept_idx=idx, kept_scores=kept_s, k_hat=k_hat, v_hat=v_hat)

@@ -18,8 +18,13 @@ def lava():
     return mod
 
 
-def test_layer_eviction_replays_from_a_graph(lava):
-    print("graph: capture one layer's eviction + decode, replay 4 times on changing inputs", flush=True)
+@pytest.mark.parametrize("composed", [False, True], ids=["plain-calls", "prepared-selection-and-planned-budget"])
+def test_layer_eviction_replays_from_a_graph(lava, composed):
+    """composed: the scores call prepares the selection's workspace and forms the budget itself (four
+    launches for the eviction instead of seven); the clearing those calls rely on is done by kernels, so
+    the sequence is as capturable as the plain one."""
+    print(f"graph: capture one layer's eviction + decode (composed={composed}), replay 4 times on changing inputs",
+          flush=True)
     sh = synth.config(2, n=8192 + 40, budget=2048)
     H, Hkv, d, N, w, B = sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.n, sh.window, sh.budget
     desc = lava.LayerDesc.make(H, Hkv, d, w, sh.dtype)
@@ -49,14 +54,19 @@ def test_layer_eviction_replays_from_a_graph(lava):
         lse=torch.empty(1, H, dtype=torch.float32, device=dev),
     )
 
+    e_table = torch.zeros(1, 1, dtype=torch.float32, device=dev)
+    plan = lava.make_budget_plan(e_table, 0, bufs["total"], bufs["lo"], bufs["hi"], bufs["budgets"]) if composed else None
+
     def step():
         b = bufs
         lava.lava_window_scores(desc, [N], q, k, v, scores=b["scores"], vbar=b["vbar"], layer_stat=b["stat"],
-                                workspace=b["ws_scores"])
-        lava.lava_layer_budgets(b["stat"].view(1, 1), b["total"], b["lo"], b["hi"], budgets=b["budgets"])
+                                workspace=b["ws_scores"], select_workspace=b["ws_sel"] if composed else None,
+                                budget_plan=plan)
+        if not composed:
+            lava.lava_layer_budgets(b["stat"].view(1, 1), b["total"], b["lo"], b["hi"], budgets=b["budgets"])
         lava.lava_select_topk(Hkv, b["scores"], B, budget_dev=b["budgets"].view(-1), head_counts=b["counts"],
                               head_offsets=b["offs"].view(-1), kept_idx=b["idx"], kept_scores=b["kept"],
-                              workspace=b["ws_sel"])
+                              workspace=b["ws_sel"], primed=composed)
         lava.lava_compact_kv(desc, N, k, v, b["offs"].view(-1), b["idx"], B, k_out=b["k_hat"], v_out=b["v_hat"])
         lava.lava_decode_attention(desc, 1, q_new, b["k_hat"], b["v_hat"], b["offs"], B, out=b["out"], lse=b["lse"],
                                    workspace=b["ws_dec"])
@@ -84,6 +94,7 @@ def test_layer_eviction_replays_from_a_graph(lava):
         want = snapshot()
         for name in ("scores", "idx", "kept", "k_hat", "out"):   # scribble over outputs: the replay must rewrite them
             bufs[name].fill_(0)
+        bufs["budgets"].fill_(-5)
         (torch.rand(1 << 20, device=dev) * 2).sum().item()      # unrelated eager work and a synchronisation in between
         graph.replay()
         got = snapshot()

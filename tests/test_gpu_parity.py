@@ -790,3 +790,37 @@ def test_scores_that_also_form_the_budgets(lava, name, shapes, n_layers, schedul
             torch.cuda.synchronize()
             assert torch.equal(budgets, lava.lava_layer_budgets(e_tab, total_t, lo_t, hi_t))
             assert bool((budgets == -1).all())
+
+
+def test_exchange_between_many_workgroups_is_stable(lava, tuning):
+    """The statistic, the partial merges and the prepared histogram travel between workgroups through
+    device-scope stores and loads without fences.  A launch cut into far more workgroups than the device
+    holds at once (several rounds, every exchange many times over) must give, on every one of 30 runs,
+    the bits of the first run, and that run must match the oracle; the selection prepared by each run
+    must equal the plain selection.  Stops at the first difference."""
+    say("exchange stress: 4096 workgroups per sweep, 30 runs")
+    sh = synth.config(2, n=65536 + 333, budget=8 * 700)
+    inp = synth.gen_layer(sh, 5)
+    Hkv, n = sh.n_kv_heads, sh.n
+    desc = lava.LayerDesc.make(sh.n_q_heads, Hkv, sh.head_dim, sh.window, sh.dtype, pool_kernel=sh.pool_kernel)
+    q, k, v = (lava.to_device(a, sh.dtype) for a in (inp.q_win, inp.k, inp.v))
+    qq, kk, vv = inp.f64()
+    ref_s, ref_vbar = O.lava_scores(qq, kk, vv, sh.window, sh.pool_kernel)
+    ws = torch.empty(lava.lava_select_workspace_bytes(Hkv * n), dtype=torch.uint8, device="cuda")
+    for shape in ("narrow", "wide"):
+        tuning(sweep_workgroups=4096, sweep_shape=shape)
+        first = None
+        for run in range(30):
+            s1, vb1, e1 = lava.lava_window_scores(desc, [n], q, k, v, select_workspace=ws)
+            c1, o1, i1, _ = lava.lava_select_topk(Hkv, s1, sh.budget, workspace=ws, primed=True)
+            torch.cuda.synchronize()
+            if first is None:
+                first = (s1.clone(), vb1.clone(), e1.clone(), c1.clone(), o1.clone(), i1.clone())
+                compare_scores(sh, s1.cpu().numpy().reshape(Hkv, n), ref_s, vb1.cpu().numpy()[0], ref_vbar,
+                               float(e1[0]), O.layer_entropy(ref_s))
+                c0, o0, i0, _ = lava.lava_select_topk(Hkv, s1, sh.budget)
+                torch.cuda.synchronize()
+                assert torch.equal(c0, c1) and torch.equal(o0, o1) and torch.equal(i0, i1)
+            else:
+                for a, b in zip(first, (s1, vb1, e1, c1, o1, i1)):
+                    assert torch.equal(a, b), (shape, run)
