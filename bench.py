@@ -132,6 +132,8 @@ def parse():
                     help="lava_tuning.sweep_schedule for the whole run (A/B of the sweep schedules)")
     ap.add_argument("--no-plan", action="store_true",
                     help="lava_layer_budgets as a launch of its own instead of the budget plan carried by the scores call")
+    ap.add_argument("--sweep-shape", default="auto", choices=["auto", "wide", "narrow"],
+                    help="lava_tuning.sweep_shape for the whole run (A/B of the two workgroup shapes of the key sweeps)")
     ap.add_argument("--summarize-profiles", metavar="WORKLOAD", default=None,
                     help="write profiles/<workload>_*.md from rocprofv3 CSV output under gpurun_out/ and exit (no GPU)")
     ap.add_argument("--no-primed", action="store_true",
@@ -504,7 +506,7 @@ def main():
         sys.exit(2)
     torch.cuda.set_device(0)
     dev = torch.device("cuda:0")
-    lava.set_tuning(sweep_schedule=args.sweep_schedule)
+    lava.set_tuning(sweep_schedule=args.sweep_schedule, sweep_shape=args.sweep_shape)
 
     if args.workload == "cfg3":
         print(json.dumps(layer_stack(lava, synth, torch, np, dev, args)), flush=True)
@@ -709,7 +711,7 @@ def main():
         "scaling": "weak", "vs_baseline": None, "dtype": sh.dtype, "data": "synthetic",
         "config": {"workload": f"{args.workload}: one layer, {sh.n_q_heads}q/{sh.n_kv_heads}kv heads, d_h {sh.head_dim}, "
                                f"N={sh.n}, w={sh.window}, B_l={B}, {sh.dtype}, batch 1",
-                   "kv_buffer_sets": n_sets, "sweep_schedule": args.sweep_schedule,
+                   "kv_buffer_sets": n_sets, "sweep_schedule": args.sweep_schedule, "sweep_shape": args.sweep_shape,
                    "scores_prepare_selection": primed, "scores_form_budgets": planned},
         "roofline": roofline,
         "step_spread": step_spread,
