@@ -782,6 +782,16 @@ def test_scores_that_also_form_the_budgets(lava, name, shapes, n_layers, schedul
                     torch.cuda.synchronize()
                     assert torch.equal(c1, c2) and torch.equal(o1, o2) and torch.equal(i1[:B], i2[:B])
                 tok += n
+    if batch == 1:                                                          # with the caller's log-sum-exp (no statistics launch)
+        qq, kk, _ = inps[0].f64()
+        lse = torch.from_numpy(O.window_lse(qq, kk).astype(np.float32)).cuda()
+        s2, vb2, e2 = lava.lava_window_scores(desc, lens, q, k, v, lse=lse)
+        budgets.fill_(-99)
+        e_tab[:, layer] = -7.0
+        s3, vb3, e3 = lava.lava_window_scores(desc, lens, q, k, v, lse=lse, budget_plan=plan)
+        torch.cuda.synchronize()
+        assert torch.equal(s2, s3) and torch.equal(vb2, vb3) and torch.equal(e2, e3) and torch.equal(e_tab[:, layer], e2)
+        assert torch.equal(budgets, lava.lava_layer_budgets(e_tab, total_t, lo_t, hi_t))
     if n_layers == 1:                                                       # a single layer: total outside its bounds
         for total_bad in (int(hi_host[0, 0]) + 1, int(lo_host[0, 0]) - 1):
             total_t = torch.full((batch,), total_bad, dtype=torch.int64, device="cuda")
