@@ -710,6 +710,8 @@ PLANNED_CASES = [
     ("cfg2-9k-128-layers-persistent", [synth.config(2, n=9000 + 5, budget=8 * 64)], 128, "persistent"),
     ("G8-two-chunks-7-layers", [synth.LayerShape(16, 2, 128, 2100, 32, "bf16", 300)], 7, "auto"),
     ("ragged-batch-of-3", [synth.config(2, n=n, budget=8 * 64) for n in (4096, 1500 + 3, 7000 + 11)], 4, "auto"),
+    # more sequences than one sweep launch takes: the second launch's sequences use their own rows of the plan
+    ("batch-of-40-short", [synth.config(2, n=300 + 23 * i, budget=8 * 40) for i in range(40)], 3, "auto"),
 ]
 
 
