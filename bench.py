@@ -158,32 +158,41 @@ def cascade_leg(lava, torch, np, sh, desc, dev, sets, scores, args):
     n_layers = 8
     per_layer = sh.budget
     total = n_layers * per_layer
-    state = lava.CascadeState(desc, n_layers, total, device=dev)
     rng = np.random.Generator(np.random.PCG64(args.seed + 5))
-    state.e.copy_(torch.from_numpy((1e-6 * (0.5 + rng.random(n_layers))).astype(np.float32)))
+    stats = torch.from_numpy((1e-6 * (0.5 + rng.random(n_layers))).astype(np.float32))
     ws = torch.empty(lava.lava_cascade_workspace_bytes(desc, sh.n, n_layers, total), dtype=torch.uint8, device=dev)
     _, k, v = sets[0]
 
-    def run():
-        state.reset()
-        times = []
-        for l in range(n_layers):
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record()
-            lava.lava_cascade_step(desc, l, sh.n, k, v, scores, state, total, workspace=ws)
-            b.record()
-            times.append((a, b))
-        torch.cuda.synchronize()
-        return [1e3 * a.elapsed_time(b) for a, b in times]
+    def measure(in_place):
+        state = lava.CascadeState(desc, n_layers, total, device=dev, in_place=in_place)
+        state.e.copy_(stats)
 
-    run()
-    reps = [run() for _ in range(5)]
-    best = [min(r[l] for r in reps) for l in range(n_layers)]
-    budgets = state.budgets.cpu().numpy().tolist()
+        def run():
+            state.reset()
+            times = []
+            for l in range(n_layers):
+                a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                a.record()
+                lava.lava_cascade_step(desc, l, sh.n, k, v, scores, state, total, workspace=ws)
+                b.record()
+                times.append((a, b))
+            torch.cuda.synchronize()
+            return [1e3 * a.elapsed_time(b) for a, b in times]
+
+        run()
+        reps = [run() for _ in range(5)]
+        best = [min(r[l] for r in reps) for l in range(n_layers)]
+        return best, state.budgets.cpu().numpy().tolist(), state.bytes()
+
+    best, budgets, state_bytes = measure(False)
+    best_ip, budgets_ip, state_bytes_ip = measure(True)
+    assert budgets == budgets_ip
     return {"note": "Alg. 2 outer loop, one step per arriving layer: budgets + one (re-)eviction per layer so far",
             "layers": n_layers, "total_budget": total, "us_per_step": [round(x, 1) for x in best],
             "us_all_steps": round(sum(best), 1), "final_budgets": budgets,
-            "state_bytes": state.bytes(), "dense_kv_bytes_of_the_layers": n_layers * 2 * k.numel() * k.element_size()}
+            "state_bytes": state_bytes, "dense_kv_bytes_of_the_layers": n_layers * 2 * k.numel() * k.element_size(),
+            "one_arena_in_place": {"us_per_step": [round(x, 1) for x in best_ip], "us_all_steps": round(sum(best_ip), 1),
+                                   "state_bytes": state_bytes_ip}}
 
 
 def decode_leg(lava, synth, torch, np, sh, desc, dev, sets, k_hat, v_hat, offs, B, args):

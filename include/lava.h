@@ -406,7 +406,11 @@ int32_t lava_compact_batch(const lava_layer_desc* desc, int32_t n_problems,
  * of `capacity` rows: their sizes change at every step but always sum to at most the total budget,
  * so the whole state needs capacity >= total budget rows, whatever the number of layers.  A step
  * gathers every layer from the current arena into the other one (a re-eviction is out of place),
- * hence two arenas; `cur` (host) says which one holds the state.
+ * hence two arenas; `cur` (host) says which one holds the state.  K and V, which are nearly all of
+ * the state's bytes, may instead share ONE arena: pass k[1] == k[0] and v[1] == v[0] and the step
+ * moves the earlier layers' rows inside that arena (every surviving row moves towards the front or
+ * stays, which makes that possible) at the price of one more launch per step; pos, scores,
+ * head_offsets and layer_start stay double-buffered either way.
  *   layer t occupies arena rows layer_start[cur][t] .. layer_start[cur][t + 1] - 1; inside them
  *   head g owns rows head_offsets[cur][t][g] .. head_offsets[cur][t][g + 1] - 1 (relative to the
  *   layer's first row), in ascending token position.
@@ -453,7 +457,7 @@ size_t lava_cascade_workspace_bytes(const lava_layer_desc* desc, int64_t n, int3
  *   e        device float [>= layer + 1]: statistics of layers 0..layer (point layer_stat of
  *            lava_window_scores at e + layer)
  *   budgets  device int64 [>= layer + 1] out
- * Three launches, whatever the number of layers; everything is enqueued on the stream, nothing
+ * Three launches (four with a shared K/V arena), whatever the number of layers; everything is enqueued on the stream, nothing
  * is read back.  Selection is integer-exact, rows are bit copies, so the state after every step
  * equals the literal algorithm's.  layer < state->max_layers; total_budget <= state->capacity and
  * within [H_kv * w, H_kv * n] * (layer + 1).

@@ -205,6 +205,14 @@ int32_t launch_compact(const lava_layer_desc& d, int64_t n, const int64_t* src_o
                        hipStream_t s);
 int32_t launch_compact_batch(const lava_layer_desc& d, int n_problems, const lava_compact_problem* problems,
                              hipStream_t s);
+// Re-compaction of layers 0..n_layers-1 of a cascade arena IN PLACE (K and V rows move inside k / v; token
+// positions go from pos_src to pos_dst): row r of the new layout (layer_start_new, offs_new [layer][H_kv+1],
+// kept_idx[r] = index in the head's old segment) comes from the old layout (layer_start_cur, offs_cur).
+// Every row moves towards the front or stays, which is what makes it possible.  `sync`: 128 zeroed words.
+int32_t launch_compact_inplace(const lava_layer_desc& d, int n_layers, const int64_t* layer_start_cur,
+                               const int64_t* layer_start_new, const int64_t* offs_cur, const int64_t* offs_new,
+                               const int32_t* kept_idx, void* k, void* v, const int32_t* pos_src, int32_t* pos_dst,
+                               int64_t capacity, unsigned int* sync, int32_t* error, hipStream_t s);
 
 // ---------------------------------------------------------------- decode attention
 struct DecodePlan {
@@ -230,8 +238,9 @@ int32_t launch_budgets(int32_t batch, int32_t n_layers, const float* e, const in
 // A cascade step's plan for one sequence: budgets of layers 0..n_layers-1 (bounds lo / hi for every
 // layer), the rows each keeps = min(budget, bound, rows it holds: head_offsets_cur[t][n_heads]
 // for t < n_layers - 1, hi for the newest), and layer_start[0..n_layers] = their prefix sums.
+// gather_sync: 128 words the kernel sets to zero for launch_compact_inplace later in the step, or null.
 int32_t launch_cascade_plan(int32_t n_layers, int32_t n_heads, const float* e, int64_t total, int64_t lo, int64_t hi,
                             int64_t bound, const int64_t* head_offsets_cur, int64_t* budgets, int64_t* layer_start,
-                            hipStream_t s);
+                            unsigned int* gather_sync, hipStream_t s);
 
 }  // namespace lava

@@ -152,8 +152,14 @@ __global__ void __launch_bounds__(64) cascade_plan_kernel(int n_layers, int n_he
                                                           long long bound,
                                                           const int64_t* __restrict__ head_offsets_cur,
                                                           int64_t* __restrict__ out,
-                                                          int64_t* __restrict__ layer_start) {
+                                                          int64_t* __restrict__ layer_start,
+                                                          unsigned int* __restrict__ gather_sync) {
   __shared__ BudgetScratch sc;
+  // the in-place gather later in the same step meets at a grid-wide barrier: its counter starts at zero
+  if (gather_sync != nullptr) {
+    gather_sync[threadIdx.x] = 0u;
+    gather_sync[64 + threadIdx.x] = 0u;
+  }
   for (int i = threadIdx.x; i < n_layers; i += 64) {
     sc.ed[i] = (double)e[i];
     sc.lo[i] = lo;
@@ -190,11 +196,12 @@ __global__ void __launch_bounds__(64) cascade_plan_kernel(int n_layers, int n_he
 
 int32_t launch_cascade_plan(int32_t n_layers, int32_t n_heads, const float* e, int64_t total, int64_t lo, int64_t hi,
                             int64_t bound, const int64_t* head_offsets_cur, int64_t* budgets, int64_t* layer_start,
-                            hipStream_t s) {
+                            unsigned int* gather_sync, hipStream_t s) {
   if (n_layers > kMaxLayers) return LAVA_ERR_SHAPE;
   ProfScope ps(KID_BUDGETS, s);
   hipLaunchKernelGGL(cascade_plan_kernel, dim3(1), dim3(64), 0, s, n_layers, n_heads, e, (long long)total,
-                     (long long)lo, (long long)hi, (long long)bound, head_offsets_cur, budgets, layer_start);
+                     (long long)lo, (long long)hi, (long long)bound, head_offsets_cur, budgets, layer_start,
+                     gather_sync);
   return launch_status();
 }
 

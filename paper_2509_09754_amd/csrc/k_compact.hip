@@ -2,6 +2,7 @@
 // K^ = K (.) I, V^ = V (.) I, stored without the evicted rows).  A pure gather: every row is
 // moved with 128-bit loads and stores, one row per group of (row bytes / 16) lanes.
 #include "common.h"
+#include "xblock.h"
 
 namespace lava {
 
@@ -71,6 +72,184 @@ __global__ void __launch_bounds__(kCompactThreads) compact_kernel(const CompactB
     v_out[out] = vv;
     if (pos_out != nullptr && c == 0) pos_out[out_off + t] = pos_src ? pos_src[row] : (int32_t)src;
   }
+}
+
+// ------------------------------------------------------------------------------------------
+// In-place re-compaction of the earlier layers of a cascade arena (Alg. 2, inner loop, without a
+// second arena for K and V).
+//
+// After a step's selections every surviving row's new place is at or before its old one: layers
+// only shrink (a layer keeps min(budget, rows it holds)), so every layer starts at or before
+// where it started; inside a layer every head keeps a subset of its rows, so every head starts at
+// or before where it started; and inside a head the survivors keep their order.  A gather that
+// overwrites its own source is then safe if rows are taken in passes of increasing NEW position
+// and, within a pass, every row is read before any row is written: what a pass overwrites lies
+// before everything later passes still have to read, and what it reads has not been overwritten
+// by earlier passes.  A pass therefore loads its rows into registers, the whole grid meets at a
+// barrier, and the pass stores them.  The grid is sized to stay resident (the barrier's wait is
+// bounded like the selection's: if it gives up the state's error word is set).
+// ------------------------------------------------------------------------------------------
+constexpr int kInplaceThreads = 1024;   // few, large workgroups: the grid barrier costs per workgroup
+constexpr int kInplaceRows = 8;          // rows a lane group holds in registers per pass
+constexpr int kInplaceMaxLayers = 1024;
+constexpr int kInplaceStaged = 2304;     // head offsets (layers x (heads + 1)) kept in LDS: 256 layers of 8 heads, 35 of 64
+
+struct InplaceArgs {
+  int n_layers, n_heads;
+  const int64_t* start_cur;   // [>= n_layers]
+  const int64_t* start_new;   // [>= n_layers + 1]
+  const int64_t* offs_cur;    // [n_layers][n_heads + 1]
+  const int64_t* offs_new;
+  const int32_t* kept_idx;    // by new arena row
+  uint4* k;
+  uint4* v;
+  const int32_t* pos_src;
+  int32_t* pos_dst;
+  long long capacity;
+  unsigned int* sync;         // kArriveWords zeroed words: arrivals (monotonic)
+  int32_t* error;             // set to 1 if a wait gave up, or null
+  unsigned int spin_limit;
+};
+
+template <int LPR>
+__global__ void __launch_bounds__(kInplaceThreads) compact_inplace_kernel(const InplaceArgs a) {
+  __shared__ long long s_new[kInplaceMaxLayers + 1], s_cur[kInplaceMaxLayers];
+  __shared__ long long s_on[kInplaceStaged], s_oc[kInplaceStaged];
+  for (int i = threadIdx.x; i <= a.n_layers; i += kInplaceThreads) {
+    s_new[i] = (long long)a.start_new[i];
+    if (i < a.n_layers) s_cur[i] = (long long)a.start_cur[i];
+  }
+  // the head offsets of every layer, old and new: a row's head is found by a search that would otherwise
+  // be a chain of dependent loads from memory per row (stacks too deep for the table read them from memory)
+  const int n_offs = a.n_layers * (a.n_heads + 1);
+  const bool staged = n_offs <= kInplaceStaged;               // uniform
+  if (staged)
+    for (int i = threadIdx.x; i < n_offs; i += kInplaceThreads) {
+      s_on[i] = (long long)a.offs_new[i];
+      s_oc[i] = (long long)a.offs_cur[i];
+    }
+  __syncthreads();
+  long long rows = s_new[a.n_layers];                         // rows the earlier layers keep
+  if (rows > a.capacity) rows = a.capacity;
+  constexpr int kGroups = kInplaceThreads / LPR;
+  const int c = threadIdx.x % LPR, grp = threadIdx.x / LPR;
+  const long long per_pass = (long long)gridDim.x * kGroups * kInplaceRows;
+  const int H = a.n_heads;
+  unsigned int round = 0u;
+  for (long long base = 0; base < rows; base += per_pass) {
+    uint4 kv[kInplaceRows], vv[kInplaceRows];
+    unsigned int moves = 0u;                                  // bit u: row u of this pass is moved by this lane group
+#pragma unroll
+    for (int u = 0; u < kInplaceRows; ++u) {
+      const long long r = base + ((long long)u * gridDim.x + blockIdx.x) * kGroups + grp;
+      long long src = 0;                                      // a row that is not moved reads row 0 and stores nothing
+      if (r < rows) {
+        int lo = 0, hi = a.n_layers - 1;                      // the layer: largest t with s_new[t] <= r
+        while (lo < hi) {
+          const int mid = (lo + hi + 1) >> 1;
+          if (s_new[mid] <= r) lo = mid; else hi = mid - 1;
+        }
+        const int t = lo;
+        const long long j = r - s_new[t];
+        const long long idx = (long long)a.kept_idx[r];
+        long long kept_t, oc0, oc1;                           // rows layer t keeps; the head's old segment
+        if (staged) {
+          const long long* on = s_on + t * (H + 1);
+          int g = 0;
+          while (g + 1 < H && j >= on[g + 1]) ++g;
+          kept_t = on[H];
+          oc0 = s_oc[t * (H + 1) + g];
+          oc1 = s_oc[t * (H + 1) + g + 1];
+        } else {
+          const int64_t* on = a.offs_new + (long long)t * (H + 1);
+          int g = 0;
+          while (g + 1 < H && j >= (long long)on[g + 1]) ++g;
+          kept_t = (long long)on[H];
+          oc0 = (long long)a.offs_cur[(long long)t * (H + 1) + g];
+          oc1 = (long long)a.offs_cur[(long long)t * (H + 1) + g + 1];
+        }
+        const long long from = s_cur[t] + oc0 + idx;
+        // never follow an index outside the head's old segment, never move a row backwards
+        if (j < kept_t && idx >= 0 && idx < oc1 - oc0 && from >= r && from < a.capacity) {
+          src = from;
+          moves |= 1u << u;
+          if (c == 0) a.pos_dst[r] = a.pos_src[from];
+        }
+      }
+      kv[u] = a.k[src * LPR + c];
+      vv[u] = a.v[src * LPR + c];
+    }
+    // every row of the pass is in registers before any is written
+    drain_vmem();
+    __syncthreads();
+    if (threadIdx.x == 0) {
+      // arrivals in two levels (hundreds of atomics on one address would serialise), then a bounded wait
+      // for the top counter: one increment per completed group and round
+      ++round;
+      arrive_two_level(a.sync, gridDim.x, blockIdx.x, round);
+      const unsigned int target = round * arrive_groups(gridDim.x);
+      unsigned int spins = 0u;
+      while (ld_dev(&a.sync[0]) < target) {
+        __builtin_amdgcn_s_sleep(16);                          // polls are device-scope loads of one address: keep them rare
+        if (++spins > a.spin_limit) {
+          if (a.error != nullptr) *a.error = 1;
+          break;
+        }
+      }
+    }
+    __syncthreads();
+#pragma unroll
+    for (int u = 0; u < kInplaceRows; ++u) {
+      if (moves & (1u << u)) {
+        const long long r = base + ((long long)u * gridDim.x + blockIdx.x) * kGroups + grp;
+        a.k[r * LPR + c] = kv[u];
+        a.v[r * LPR + c] = vv[u];
+      }
+    }
+  }
+}
+
+int32_t launch_compact_inplace(const lava_layer_desc& d, int n_layers, const int64_t* layer_start_cur,
+                               const int64_t* layer_start_new, const int64_t* offs_cur, const int64_t* offs_new,
+                               const int32_t* kept_idx, void* k, void* v, const int32_t* pos_src, int32_t* pos_dst,
+                               int64_t capacity, unsigned int* sync, int32_t* error, hipStream_t s) {
+  if (n_layers < 1) return LAVA_OK;
+  if (n_layers > kInplaceMaxLayers) return LAVA_ERR_SHAPE;
+  const int lpr = d.head_dim * (d.dtype == LAVA_BF16 ? 2 : 4) / 16;
+  InplaceArgs a;
+  a.n_layers = n_layers;
+  a.n_heads = d.n_kv_heads;
+  a.start_cur = layer_start_cur;
+  a.start_new = layer_start_new;
+  a.offs_cur = offs_cur;
+  a.offs_new = offs_new;
+  a.kept_idx = kept_idx;
+  a.k = static_cast<uint4*>(k);
+  a.v = static_cast<uint4*>(v);
+  a.pos_src = pos_src;
+  a.pos_dst = pos_dst;
+  a.capacity = capacity;
+  a.sync = sync;
+  a.error = error;
+  a.spin_limit = tuning().barrier_spin_limit > 0 ? (unsigned int)tuning().barrier_spin_limit : 1u << 18;
+  // all workgroups have to be resident at once: one per compute unit at most, fewer for a small arena
+  int cus = 0, dev = 0;
+  if (hipGetDevice(&dev) != hipSuccess ||
+      hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+    cus = 256;
+  const int64_t rows_per_wg = (int64_t)(kInplaceThreads / lpr) * kInplaceRows;
+  int64_t wgs = (capacity + rows_per_wg - 1) / rows_per_wg;
+  if (wgs > (int64_t)cus) wgs = (int64_t)cus;
+  if (wgs < 1) wgs = 1;
+  const dim3 grid((unsigned)wgs), block(kInplaceThreads);
+  ProfScope ps(KID_COMPACT, s);
+  switch (lpr) {
+    case 8: hipLaunchKernelGGL(compact_inplace_kernel<8>, grid, block, 0, s, a); break;
+    case 16: hipLaunchKernelGGL(compact_inplace_kernel<16>, grid, block, 0, s, a); break;
+    case 32: hipLaunchKernelGGL(compact_inplace_kernel<32>, grid, block, 0, s, a); break;
+    default: return LAVA_ERR_SHAPE;
+  }
+  return launch_status();
 }
 
 int32_t launch_compact_batch(const lava_layer_desc& d, int n_problems, const lava_compact_problem* problems,

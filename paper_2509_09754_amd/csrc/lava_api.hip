@@ -472,7 +472,7 @@ size_t lava_cascade_workspace_bytes(const lava_layer_desc* desc, int64_t n, int3
     return 0;
   const int64_t dense = (int64_t)desc->n_kv_heads * n;
   if (dense >= (int64_t)1 << 31) return 0;
-  return make_select_workspace(dense).bytes * (size_t)n_layers;
+  return make_select_workspace(dense).bytes * (size_t)n_layers + 2 * kAlign;   // + the in-place gather's barrier words
 }
 
 int32_t lava_cascade_step(const lava_layer_desc* desc, int32_t layer, int64_t n, const void* k_new,
@@ -499,10 +499,15 @@ int32_t lava_cascade_step(const lava_layer_desc* desc, int32_t layer, int64_t n,
     return LAVA_ERR_INVALID_ARG;
   if (layer >= S.max_layers) return LAVA_ERR_SHAPE;
   if (S.capacity < total_budget || S.capacity >= (int64_t)1 << 31) return LAVA_ERR_BUDGET;
+  // one arena for K and V (both pairs of pointers equal): the earlier layers are re-compacted in place
+  const bool in_place = S.k[0] == S.k[1];
+  if ((S.v[0] == S.v[1]) != in_place) return LAVA_ERR_INVALID_ARG;
   const int64_t bound = cascade_layer_bound(dense, total_budget);
+  const size_t select_bytes = make_select_workspace(dense).bytes * (size_t)(layer + 1);
   if (workspace == nullptr || (reinterpret_cast<uintptr_t>(workspace) % kAlign) != 0 ||
-      workspace_bytes < make_select_workspace(dense).bytes * (size_t)(layer + 1))
+      workspace_bytes < select_bytes + (in_place ? 2 * kAlign : 0))
     return LAVA_ERR_WORKSPACE;
+  unsigned int* gather_sync = in_place ? reinterpret_cast<unsigned int*>(static_cast<char*>(workspace) + select_bytes) : nullptr;
   hipStream_t s = static_cast<hipStream_t>(hip_stream);
   discard_stale_error();
   const int H1 = desc->n_kv_heads + 1;
@@ -510,7 +515,7 @@ int32_t lava_cascade_step(const lava_layer_desc* desc, int32_t layer, int64_t n,
 
   // budgets of the layers seen so far, and from them where every layer will start in the other arena
   st = launch_cascade_plan(layer + 1, desc->n_kv_heads, e, total_budget, lo, dense, bound, S.head_offsets[a],
-                           budgets, S.layer_start[b], s);
+                           budgets, S.layer_start[b], gather_sync, s);
   if (st != LAVA_OK) return st;
 
   // One table of selections and one of compactions: every earlier layer from what it holds in the
@@ -537,7 +542,16 @@ int32_t lava_cascade_step(const lava_layer_desc* desc, int32_t layer, int64_t n,
   }
   st = launch_select_batch(desc->n_kv_heads, layer + 1, sel.data(), dense, workspace, s);
   if (st != LAVA_OK) return st;
-  st = launch_compact_batch(*desc, layer + 1, cmp.data(), s);
+  if (in_place) {
+    // the earlier layers move inside the arena first; the new layer's rows land behind them afterwards
+    // (its place may still hold rows of the old layout until then)
+    st = launch_compact_inplace(*desc, layer, S.layer_start[a], S.layer_start[b], S.head_offsets[a], S.head_offsets[b],
+                                S.kept_idx, S.k[a], S.v[a], S.pos[a], S.pos[b], S.capacity, gather_sync, S.error, s);
+    if (st != LAVA_OK) return st;
+    st = launch_compact_batch(*desc, 1, &cmp[layer], s);
+  } else {
+    st = launch_compact_batch(*desc, layer + 1, cmp.data(), s);
+  }
   if (st != LAVA_OK) return st;
   S.cur = b;
   return LAVA_OK;

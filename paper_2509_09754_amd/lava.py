@@ -513,13 +513,17 @@ class CascadeStateStruct(ctypes.Structure):
 
 class CascadeState:
     """Device buffers of a stack of layers for lava_cascade_step (allocation and views only): two arenas of
-    `capacity` rows in which the layers sit back to back, plus the per-layer offsets."""
+    `capacity` rows in which the layers sit back to back, plus the per-layer offsets.  in_place: K and V
+    share ONE arena (the step re-compacts the earlier layers inside it), which halves the state."""
 
-    def __init__(self, desc: LayerDesc, max_layers: int, capacity: int, device="cuda"):
+    def __init__(self, desc: LayerDesc, max_layers: int, capacity: int, device="cuda", in_place: bool = False):
         self.desc, self.n_layers, self.capacity = desc, int(max_layers), int(capacity)
+        self.in_place = bool(in_place)
         hk = desc.n_kv_heads
-        self.k = [torch.empty(capacity, desc.head_dim, dtype=desc.torch_dtype, device=device) for _ in range(2)]
-        self.v = [torch.empty(capacity, desc.head_dim, dtype=desc.torch_dtype, device=device) for _ in range(2)]
+        self.k = [torch.empty(capacity, desc.head_dim, dtype=desc.torch_dtype, device=device)]
+        self.v = [torch.empty(capacity, desc.head_dim, dtype=desc.torch_dtype, device=device)]
+        self.k.append(self.k[0] if in_place else torch.empty_like(self.k[0]))
+        self.v.append(self.v[0] if in_place else torch.empty_like(self.v[0]))
         self.pos = [torch.empty(capacity, dtype=torch.int32, device=device) for _ in range(2)]
         self.scores = [torch.empty(capacity, dtype=torch.float32, device=device) for _ in range(2)]
         self.head_offsets = [torch.zeros(max_layers, hk + 1, dtype=torch.int64, device=device) for _ in range(2)]
@@ -548,7 +552,8 @@ class CascadeState:
 
     def bytes(self) -> int:
         """Device bytes the state holds."""
-        ts = self.k + self.v + self.pos + self.scores + self.head_offsets + self.layer_start
+        ts = (self.k[:1] + self.v[:1] if self.in_place else self.k + self.v)
+        ts = ts + self.pos + self.scores + self.head_offsets + self.layer_start
         ts += [self.head_counts, self.kept_idx, self.e, self.budgets]
         return sum(t.numel() * t.element_size() for t in ts)
 

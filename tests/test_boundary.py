@@ -272,11 +272,20 @@ def test_cascade_and_packed_compaction_argument_errors():
     broken.cur = 2
     assert step(st=broken) == lava.LAVA_ERR_INVALID_ARG
     one = lava.lava_select_workspace_bytes(8 * n)
-    assert lava.lava_cascade_workspace_bytes(d, n, 1, 8192) == one
-    assert lava.lava_cascade_workspace_bytes(d, n, 5, 8192) == 5 * one
+    assert lava.lava_cascade_workspace_bytes(d, n, 1, 8192) == one + 512      # + the in-place gather's barrier words
+    assert lava.lava_cascade_workspace_bytes(d, n, 5, 8192) == 5 * one + 512
     assert lava.lava_cascade_workspace_bytes(d, 16, 1, 8192) == 0
     assert lava.lava_cascade_workspace_bytes(d, n, 0, 8192) == 0
     assert step(layer_idx=0, wsb=one - 1) == lava.LAVA_ERR_WORKSPACE
+    # K and V share one arena (the state above: every pointer equal) -> the barrier words are needed too
+    assert step(layer_idx=0, wsb=one) == lava.LAVA_ERR_WORKSPACE
+    # ... and both of them share it, or neither
+    mixed = lava.CascadeStateStruct.from_buffer_copy(state)
+    mixed.v[1] = 0x20000
+    assert step(st=mixed) == lava.LAVA_ERR_INVALID_ARG
+    two = lava.CascadeStateStruct.from_buffer_copy(state)
+    two.k[1] = two.v[1] = 0x20000
+    assert step(st=two, layer_idx=0, wsb=one - 1) == lava.LAVA_ERR_WORKSPACE
 
 
 def test_batch_select_and_compact_argument_errors():

@@ -48,10 +48,15 @@ def check_state(lava, state, t, ref_state, k_store, v_store, dtype, tag):
         assert np.array_equal(vh[a:b], v_store[g][pos_ref[a:b]]), (tag, g)
 
 
-def run_cascade(lava, shape, n_layers, total_budget, seeds, use_gpu_scores):
+# every cascade runs twice: K and V in two arenas (out-of-place gathers), and in one arena that the step
+# re-compacts in place
+ARENAS = pytest.mark.parametrize("in_place", [False, True], ids=["two-arenas", "one-arena-in-place"])
+
+
+def run_cascade(lava, shape, n_layers, total_budget, seeds, use_gpu_scores, in_place=False):
     H, Hkv, d, N, w = shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.n, shape.window
     desc = lava.LayerDesc.make(H, Hkv, d, w, shape.dtype, pool_kernel=shape.pool_kernel)
-    state = lava.CascadeState(desc, n_layers, total_budget)      # two arenas of `total_budget` rows, whatever the depth
+    state = lava.CascadeState(desc, n_layers, total_budget, in_place=in_place)   # arenas of `total_budget` rows, whatever the depth
     layer_scores, ents, stores = [], [], []
     ws = None
     for l in range(n_layers):
@@ -85,43 +90,51 @@ def run_cascade(lava, shape, n_layers, total_budget, seeds, use_gpu_scores):
     return state, history
 
 
-def test_cascade_small_f32_matches_oracle(lava):
+@ARENAS
+def test_cascade_small_f32_matches_oracle(lava, in_place):
     say("cascade: 5 layers, f32, N=1024 (config 1 shape), oracle scores")
     shape = synth.config(1)
     fr = synth.stack_heavy_fracs(5, 3)
-    state, history = run_cascade(lava, shape, 5, 5 * 256, dict(base=100, fracs=fr), use_gpu_scores=False)
+    state, history = run_cascade(lava, shape, 5, 5 * 256, dict(base=100, fracs=fr), use_gpu_scores=False,
+                                 in_place=in_place)
     assert sum(history[-1]) == 5 * 256
     # budgets shrink as layers arrive (the memory is shared with more layers)
     say("  final budgets", history[-1])
 
 
-def test_cascade_bf16_gpu_scores(lava):
+@ARENAS
+def test_cascade_bf16_gpu_scores(lava, in_place):
     say("cascade: 4 layers, bf16 32q/8kv d128, N=4096+5, scores and statistics from the GPU")
     shape = synth.config(2, n=4096 + 5, budget=1024)
     fr = synth.stack_heavy_fracs(4, 5)
-    state, history = run_cascade(lava, shape, 4, 4 * 1024, dict(base=200, fracs=fr), use_gpu_scores=True)
+    state, history = run_cascade(lava, shape, 4, 4 * 1024, dict(base=200, fracs=fr), use_gpu_scores=True,
+                                 in_place=in_place)
     assert sum(history[-1]) == 4 * 1024
     say("  final budgets", history[-1])
 
 
-def test_cascade_many_layers_tight_budget(lava):
+@ARENAS
+def test_cascade_many_layers_tight_budget(lava, in_place):
     say("cascade: 14 layers, f32, N=300, total barely above the lower bounds -> many layers pinned at H_kv * w")
     shape = synth.config(1, n=300)
     fr = synth.stack_heavy_fracs(14, 11)
     total = 14 * shape.n_kv_heads * shape.window + 90          # 16 per layer is the floor
-    state, history = run_cascade(lava, shape, 14, total, dict(base=500, fracs=fr), use_gpu_scores=False)
+    state, history = run_cascade(lava, shape, 14, total, dict(base=500, fracs=fr), use_gpu_scores=False,
+                                 in_place=in_place)
     assert sum(history[-1]) == total and min(history[-1]) >= shape.n_kv_heads * shape.window
 
 
-def test_cascade_first_layer_takes_everything(lava):
+@ARENAS
+def test_cascade_first_layer_takes_everything(lava, in_place):
     say("cascade: total budget = one layer's size -> the first layer is kept whole, then shrinks")
     shape = synth.config(1, n=600)
     fr = synth.stack_heavy_fracs(3, 9)
     total = shape.n_kv_heads * 600             # the first step evicts nothing
-    run_cascade(lava, shape, 3, total, dict(base=300, fracs=fr), use_gpu_scores=False)
+    run_cascade(lava, shape, 3, total, dict(base=300, fracs=fr), use_gpu_scores=False, in_place=in_place)
     desc = lava.LayerDesc.make(shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.window, shape.dtype)
-    state = lava.CascadeState(desc, 1, total + 1)
-    assert state.bytes() < 3 * (total + 1) * (2 * shape.head_dim * 4 + 12)        # two arenas + scratch, not per layer
+    state = lava.CascadeState(desc, 1, total + 1, in_place=in_place)
+    arenas = 1 if in_place else 2
+    assert state.bytes() < (arenas + 0.5) * (total + 1) * (2 * shape.head_dim * 4 + 12)   # arenas + scratch, not per layer
     dummy = torch.zeros(shape.n_kv_heads * 600 * shape.head_dim, dtype=torch.float32, device="cuda")
     with pytest.raises(lava.LavaError) as ei:   # more than the layers seen so far can hold: infeasible, as in the oracle
         lava.lava_cascade_step(desc, 0, 600, dummy, dummy, dummy[: shape.n_kv_heads * 600], state, total + 1)
@@ -175,11 +188,12 @@ def test_select_reads_total_from_segment_offsets(lava):
     assert counts.cpu().numpy().tolist() == [1000, 0, 1600, 500] and int(o[-1]) == 3100
 
 
-def test_decode_reads_a_cascade_layer_in_place(lava):
+@ARENAS
+def test_decode_reads_a_cascade_layer_in_place(lava, in_place):
     say("cascade: decode attention over layer 1 of a 3-layer state, straight from the arena")
     shape = synth.config(2, n=2048 + 9, budget=512)
     fr = synth.stack_heavy_fracs(3, 2)
-    state, _ = run_cascade(lava, shape, 3, 3 * 512, dict(base=400, fracs=fr), use_gpu_scores=True)
+    state, _ = run_cascade(lava, shape, 3, 3 * 512, dict(base=400, fracs=fr), use_gpu_scores=True, in_place=in_place)
     H, Hkv, d = shape.n_q_heads, shape.n_kv_heads, shape.head_dim
     desc = lava.LayerDesc.make(H, Hkv, d, shape.window, shape.dtype)
     r = np.random.Generator(np.random.PCG64(8))

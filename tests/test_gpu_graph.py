@@ -108,8 +108,9 @@ def test_layer_eviction_replays_from_a_graph(lava, composed):
         assert lava.lava_select_status(bufs["ws_sel"], Hkv * N) == lava.LAVA_OK
 
 
-def test_cascade_of_three_layers_replays_from_a_graph(lava):
-    print("graph: capture three cascade steps (scores + step per layer), replay 3 times", flush=True)
+@pytest.mark.parametrize("in_place", [False, True], ids=["two-arenas", "one-arena-in-place"])
+def test_cascade_of_three_layers_replays_from_a_graph(lava, in_place):
+    print(f"graph: capture three cascade steps (scores + step per layer, in_place={in_place}), replay 3 times", flush=True)
     sh = synth.config(2, n=4096 + 21, budget=0)
     H, Hkv, d, N, w = sh.n_q_heads, sh.n_kv_heads, sh.head_dim, sh.n, sh.window
     L, total = 3, 3 * 700
@@ -119,7 +120,7 @@ def test_cascade_of_three_layers_replays_from_a_graph(lava):
     q = [lava.to_device(inps[0][l].q_win, sh.dtype, dev).clone() for l in range(L)]
     k = [lava.to_device(inps[0][l].k, sh.dtype, dev).clone() for l in range(L)]
     v = [lava.to_device(inps[0][l].v, sh.dtype, dev).clone() for l in range(L)]
-    state = lava.CascadeState(desc, L, total, device=dev)
+    state = lava.CascadeState(desc, L, total, device=dev, in_place=in_place)
     scores = torch.empty(L, Hkv * N, dtype=torch.float32, device=dev)
     vbar = torch.empty(L, Hkv, dtype=torch.float32, device=dev)
     ws_s = torch.empty(lava.lava_window_scores_workspace_bytes(desc, 1, N), dtype=torch.uint8, device=dev)

@@ -31,7 +31,10 @@ def say(*a):
     print(*a, flush=True)
 
 
-def test_config3_full_stack_cascade_equals_single_shot_equals_oracle(lava):
+@pytest.mark.parametrize("in_place", [False, True], ids=["two-arenas", "one-arena-in-place"])
+def test_config3_full_stack_cascade_equals_single_shot_equals_oracle(lava, in_place):
+    """in_place: K and V of the cascade live in ONE arena of 131072 rows (two passes of the in-place
+    gather per step); the final state must be the same, entry for entry."""
     L, total = 32, 131072
     base = synth.config(3)
     H, Hkv, d, N, w = base.n_q_heads, base.n_kv_heads, base.head_dim, base.n, base.window
@@ -60,7 +63,7 @@ def test_config3_full_stack_cascade_equals_single_shot_equals_oracle(lava):
             say(f"   generated and scored (oracle) {l + 1} layers")
 
     # the layers as a batch of 32 sequences: three sweep launches for the whole model
-    state = lava.CascadeState(desc, L, total)
+    state = lava.CascadeState(desc, L, total, in_place=in_place)
     scores, vbar, stat = lava.lava_window_scores(desc, [N] * L, q_dev, k_dev, v_dev, layer_stat=state.e)
     torch.cuda.synchronize()
     s_host = scores.cpu().numpy().reshape(L, Hkv, N)
