@@ -211,3 +211,30 @@ def test_decode_reads_a_cascade_layer_in_place(lava, in_place):
     for h in range(H):
         assert np.abs(got[h] - want[h]).max() <= 2e-5 * np.abs(want[h]).max()
     assert np.allclose(lse.cpu().numpy()[0], want_lse, rtol=1e-5, atol=1e-5)
+
+
+def test_in_place_step_with_a_wait_that_gives_up_marks_the_state(lava, tuning):
+    """The waits of a step are bounded (the selections' and the in-place gather's grid barriers).  With the
+    bound at a single poll, set from the host, every kernel still runs to its end and the state's error word
+    is set; the same steps with the default bound leave it clear."""
+    say("cascade in place: forced give-up of the bounded waits")
+    shape = synth.config(2, n=16384 + 3, budget=0)
+    H, Hkv, d, N, w = shape.n_q_heads, shape.n_kv_heads, shape.head_dim, shape.n, shape.window
+    desc = lava.LayerDesc.make(H, Hkv, d, w, shape.dtype)
+    total = 3 * 24000
+    for spin, expect in ((0, 0), (1, 1)):
+        state = lava.CascadeState(desc, 3, total, in_place=True)
+        ws = None
+        for l in range(3):
+            inp = synth.gen_layer(shape, 700 + l)
+            q_dev, k_dev, v_dev = (lava.to_device(a, shape.dtype) for a in (inp.q_win, inp.k, inp.v))
+            sc_dev, _, _ = lava.lava_window_scores(desc, [N], q_dev, k_dev, v_dev, layer_stat=state.e[l: l + 1])
+            if l == 2:
+                tuning(barrier_spin_limit=spin)
+            ws = lava.lava_cascade_step(desc, l, N, k_dev, v_dev, sc_dev, state, total, workspace=ws)
+            torch.cuda.synchronize()
+            tuning()
+        assert int(state.error[0]) == expect, spin
+        if not expect:
+            starts = state.layer_start[state.cur].cpu().numpy()
+            assert starts[0] == 0 and starts[3] == total
