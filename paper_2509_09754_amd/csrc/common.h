@@ -191,8 +191,10 @@ int32_t launch_select(int n_heads, const float* scores, const int64_t* seg_offse
 // independent selections in as few launches as the device's capacity allows; problem p uses the
 // p-th region of the workspace, regions laid out for max_total entries
 constexpr int kMaxSelProblems = 32;
+// cleared: an earlier kernel on the stream has zeroed every problem's region and survivor counts (what the
+// selection's own init kernel does), so launches that fit the one-kernel path skip that kernel
 int32_t launch_select_batch(int n_heads, int n_problems, const lava_select_problem* problems, int64_t max_total,
-                            void* ws, hipStream_t s);
+                            void* ws, hipStream_t s, bool cleared = false);
 
 int32_t select_error_flag(const void* ws, int64_t max_total, int n_problems, hipStream_t s, int* flag);
 // host-side argument checks of one selection (shared by every entry point that takes one)
@@ -239,8 +241,15 @@ int32_t launch_budgets(int32_t batch, int32_t n_layers, const float* e, const in
 // layer), the rows each keeps = min(budget, bound, rows it holds: head_offsets_cur[t][n_heads]
 // for t < n_layers - 1, hi for the newest), and layer_start[0..n_layers] = their prefix sums.
 // gather_sync: 128 words the kernel sets to zero for launch_compact_inplace later in the step, or null.
+// regions (ws != null): the workspace regions of the step's n_layers selections and their survivor counts
+// [n_layers][n_heads], cleared by extra workgroups of the same launch (launch_select_batch(cleared = true)).
+struct SelectRegions {
+  char* ws;
+  size_t stride, off_hist, off_state;
+  int32_t* head_counts;
+};
 int32_t launch_cascade_plan(int32_t n_layers, int32_t n_heads, const float* e, int64_t total, int64_t lo, int64_t hi,
                             int64_t bound, const int64_t* head_offsets_cur, int64_t* budgets, int64_t* layer_start,
-                            unsigned int* gather_sync, hipStream_t s);
+                            unsigned int* gather_sync, const SelectRegions& regions, hipStream_t s);
 
 }  // namespace lava

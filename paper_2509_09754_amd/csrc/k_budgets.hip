@@ -153,7 +153,20 @@ __global__ void __launch_bounds__(64) cascade_plan_kernel(int n_layers, int n_he
                                                           const int64_t* __restrict__ head_offsets_cur,
                                                           int64_t* __restrict__ out,
                                                           int64_t* __restrict__ layer_start,
-                                                          unsigned int* __restrict__ gather_sync) {
+                                                          unsigned int* __restrict__ gather_sync,
+                                                          const SelectRegions regions) {
+  // workgroups 1 .. n_layers: each clears the workspace region and the survivor counts of one of the
+  // step's selections, which then need no clearing launch of their own; workgroup 0: the plan
+  if (blockIdx.x > 0) {
+    const int t = (int)blockIdx.x - 1;
+    char* region = regions.ws + (size_t)t * regions.stride;
+    unsigned int* hist = reinterpret_cast<unsigned int*>(region + regions.off_hist);
+    unsigned int* state = reinterpret_cast<unsigned int*>(region + regions.off_state);
+    for (int i = threadIdx.x; i < 3 * kSelBins; i += 64) hist[i] = 0u;
+    if (threadIdx.x < kSelStateWords) state[threadIdx.x] = 0u;
+    for (int i = threadIdx.x; i < n_heads; i += 64) regions.head_counts[(size_t)t * n_heads + i] = 0;
+    return;
+  }
   __shared__ BudgetScratch sc;
   // the in-place gather later in the same step meets at a grid-wide barrier: its counter starts at zero
   if (gather_sync != nullptr) {
@@ -196,12 +209,12 @@ __global__ void __launch_bounds__(64) cascade_plan_kernel(int n_layers, int n_he
 
 int32_t launch_cascade_plan(int32_t n_layers, int32_t n_heads, const float* e, int64_t total, int64_t lo, int64_t hi,
                             int64_t bound, const int64_t* head_offsets_cur, int64_t* budgets, int64_t* layer_start,
-                            unsigned int* gather_sync, hipStream_t s) {
+                            unsigned int* gather_sync, const SelectRegions& regions, hipStream_t s) {
   if (n_layers > kMaxLayers) return LAVA_ERR_SHAPE;
   ProfScope ps(KID_BUDGETS, s);
-  hipLaunchKernelGGL(cascade_plan_kernel, dim3(1), dim3(64), 0, s, n_layers, n_heads, e, (long long)total,
-                     (long long)lo, (long long)hi, (long long)bound, head_offsets_cur, budgets, layer_start,
-                     gather_sync);
+  hipLaunchKernelGGL(cascade_plan_kernel, dim3(1 + (regions.ws != nullptr ? n_layers : 0)), dim3(64), 0, s, n_layers,
+                     n_heads, e, (long long)total, (long long)lo, (long long)hi, (long long)bound, head_offsets_cur,
+                     budgets, layer_start, gather_sync, regions);
   return launch_status();
 }
 

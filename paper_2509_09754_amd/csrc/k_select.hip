@@ -657,7 +657,7 @@ static int fused_capacity() {
 // a bounded wait gives up, the kernel marks the outputs and the status call reports it).  A single
 // problem wider than that runs as step launches.
 int32_t launch_select_batch(int n_heads, int n_problems, const lava_select_problem* problems, int64_t max_total,
-                            void* ws, hipStream_t s) {
+                            void* ws, hipStream_t s, bool cleared) {
   const SelectWorkspace w = make_select_workspace(max_total);
   SelectBatch a;
   a.n_heads = n_heads;
@@ -691,7 +691,7 @@ int32_t launch_select_batch(int n_heads, int n_problems, const lava_select_probl
       if (a.p[i].primed) a.primed_mask |= 1u << i;
     const bool all_primed = a.primed_mask == (count == 32 ? 0xffffffffu : (1u << count) - 1u);
     const bool fused = blocks <= cap;
-    if (!(fused && all_primed)) {                          // the one-launch selection clears a primed problem's counts itself
+    if (!(fused && (all_primed || cleared))) {             // the one-launch selection clears a primed problem's counts itself
       ProfScope ps(KID_SEL_INIT, s);
       hipLaunchKernelGGL(sel_init_kernel, dim3(count), block, 0, s, a);
     }

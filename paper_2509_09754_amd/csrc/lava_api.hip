@@ -514,8 +514,12 @@ int32_t lava_cascade_step(const lava_layer_desc* desc, int32_t layer, int64_t n,
   const int a = S.cur, b = 1 - S.cur;
 
   // budgets of the layers seen so far, and from them where every layer will start in the other arena
+  // (its extra workgroups clear the regions of the step's selections and their survivor counts)
+  const SelectWorkspace sel_layout = make_select_workspace(dense);
+  const SelectRegions regions = {static_cast<char*>(workspace), sel_layout.bytes, sel_layout.off_hist,
+                                 sel_layout.off_state, S.head_counts};
   st = launch_cascade_plan(layer + 1, desc->n_kv_heads, e, total_budget, lo, dense, bound, S.head_offsets[a],
-                           budgets, S.layer_start[b], gather_sync, s);
+                           budgets, S.layer_start[b], gather_sync, regions, s);
   if (st != LAVA_OK) return st;
 
   // One table of selections and one of compactions: every earlier layer from what it holds in the
@@ -540,7 +544,7 @@ int32_t lava_cascade_step(const lava_layer_desc* desc, int32_t layer, int64_t n,
                 S.capacity, S.k[b],  S.v[b], S.pos[b], nullptr, start_new};
     }
   }
-  st = launch_select_batch(desc->n_kv_heads, layer + 1, sel.data(), dense, workspace, s);
+  st = launch_select_batch(desc->n_kv_heads, layer + 1, sel.data(), dense, workspace, s, /*cleared=*/true);
   if (st != LAVA_OK) return st;
   if (in_place) {
     // the earlier layers move inside the arena first; the new layer's rows land behind them afterwards
